@@ -1,0 +1,320 @@
+"""CPU oracle for one NOMAD Projection epoch -- TEST INFRASTRUCTURE, NOT PRODUCT.
+
+Plain, slow, literal Python/numpy in float64.  It exists so that the HIP library
+can be checked against something written independently from the paper.  Only
+tests, the smoke check and the benchmark's CPU-baseline leg may import it; it
+imports nothing from the HIP package and shares no code with it.
+
+What it computes, in the paper's order and notation (arxiv 2505.15511):
+
+  * Cauchy kernel q(a,b) = 1/(1+|a-b|^2)                               -- Eq. 1
+  * NOMAD loss: for a head i and each of its graph edges ij,
+      l_ij = -log( q(ij) / (q(ij) + Mtilde_i + Mcal_ij) )              -- Eq. 4
+      Mtilde_i = |M| * sum_{r in Rtilde_i} p(m in r) q(theta_i, mu_r)  -- Eq. 5
+      Mcal_ij  = the noise-sample sum over the cells that are not
+                 approximated, estimated from s sampled negatives       -- Eq. 6
+    averaged over heads with p(j|i) as edge weights (uniform head marginal,
+    Section 3.3).  With no approximated cell this is the InfoNC-t-SNE loss (Eq. 2).
+  * mu_r = mean embedding of cell r, p(m in r) = n_r/n under the uniform noise
+    distribution over tails (Section 3.3).
+  * the gradient of that sampled loss w.r.t. every embedding row it touches
+    (head, tail, sampled negatives), with the sample indices and mu held fixed.
+  * SGD with a learning rate annealed linearly to zero (Section 3.4).
+
+Readings where the paper is silent (each one is listed in the design notes):
+  - p(j|i) is the row-normalised edge weight (unit weights -> 1/deg_i);
+  - one epoch = one full-batch step over all heads, each directed edge drawing s fresh
+    negatives; the step uses n * grad(L) so lr0 is in per-point units;
+  - negatives: Philox4x32-10, counter (lo32(e), hi32(e), t, slot>>2), key (lo32(seed),
+    hi32(seed)), word slot&3, index = high word of x * n_loc(i); no rejection;
+  - the cells approximated for head i are those whose group differs from the group of
+    i's own cluster; negatives are drawn from the points of i's own group (ascending
+    index order) and weighted by omega_i = |M| * (n_loc(i)/n) / s;
+  - mu is a constant of the epoch (no gradient through it);
+  - eta_t = lr0 * (1 - t/T).
+
+parity status: every function here is pinned by tests/test_oracle_*.py (closed forms,
+finite differences, brute force, invariants, Philox known answers).  Absolute embedding
+quality against the paper's figures is *parity unpinned*: the paper prints no value for
+any workload that can be rebuilt offline.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Optional
+
+import numpy as np
+
+# Philox4x32 constants of the published algorithm (Salmon et al., SC'11).
+_PHILOX_M0 = 0xD2511F53
+_PHILOX_M1 = 0xCD9E8D57
+_PHILOX_W0 = 0x9E3779B9
+_PHILOX_W1 = 0xBB67AE85
+_MASK32 = 0xFFFFFFFF
+
+
+def philox4x32_10(counter, key):
+    """Philox4x32 with 10 rounds on Python integers.  counter: 4 words, key: 2 words."""
+    c0, c1, c2, c3 = (int(x) & _MASK32 for x in counter)
+    k0, k1 = (int(x) & _MASK32 for x in key)
+    for _ in range(10):
+        p0 = _PHILOX_M0 * c0
+        p1 = _PHILOX_M1 * c2
+        hi0, lo0 = p0 >> 32, p0 & _MASK32
+        hi1, lo1 = p1 >> 32, p1 & _MASK32
+        c0, c1, c2, c3 = (hi1 ^ c1 ^ k0) & _MASK32, lo1, (hi0 ^ c3 ^ k1) & _MASK32, lo0
+        k0 = (k0 + _PHILOX_W0) & _MASK32
+        k1 = (k1 + _PHILOX_W1) & _MASK32
+    return (c0, c1, c2, c3)
+
+
+def philox4x32_10_array(c0, c1, c2, c3, k0, k1):
+    """Same generator on numpy arrays of counters (uint64 arithmetic, one shared key)."""
+    c0 = np.asarray(c0, dtype=np.uint64); c1 = np.asarray(c1, dtype=np.uint64)
+    c2 = np.asarray(c2, dtype=np.uint64); c3 = np.asarray(c3, dtype=np.uint64)
+    c0, c1, c2, c3 = np.broadcast_arrays(c0, c1, c2, c3)
+    k0 = int(k0) & _MASK32
+    k1 = int(k1) & _MASK32
+    m32 = np.uint64(_MASK32)
+    s32 = np.uint64(32)
+    for _ in range(10):
+        p0 = np.uint64(_PHILOX_M0) * c0
+        p1 = np.uint64(_PHILOX_M1) * c2
+        hi0, lo0 = p0 >> s32, p0 & m32
+        hi1, lo1 = p1 >> s32, p1 & m32
+        c0, c1, c2, c3 = (hi1 ^ c1 ^ np.uint64(k0)), lo1, (hi0 ^ c3 ^ np.uint64(k1)), lo0
+        k0 = (k0 + _PHILOX_W0) & _MASK32
+        k1 = (k1 + _PHILOX_W1) & _MASK32
+    return c0, c1, c2, c3
+
+
+@dataclasses.dataclass
+class Problem:
+    """Inputs of the epoch path: a kNN digraph in CSR, a partition into clusters (cells),
+    an optional grouping of cells, and the sampling / schedule parameters."""
+
+    n: int
+    row_ptr: np.ndarray                       # int [n+1]
+    col_idx: np.ndarray                       # int [E]
+    cluster_of: np.ndarray                    # int [n]
+    n_clusters: int
+    n_neg: int                                # s
+    noise_count: float                        # |M|   (<= 0 means "= s")
+    seed: int = 0
+    n_epochs: int = 1                         # T
+    lr0: float = 1.0
+    weights: Optional[np.ndarray] = None      # [E] or None = unit
+    cluster_group: Optional[np.ndarray] = None  # [n_clusters] or None = one group
+
+    def __post_init__(self):
+        self.row_ptr = np.asarray(self.row_ptr, dtype=np.int64)
+        self.col_idx = np.asarray(self.col_idx, dtype=np.int64)
+        self.cluster_of = np.asarray(self.cluster_of, dtype=np.int64)
+        if self.weights is not None:
+            self.weights = np.asarray(self.weights, dtype=np.float32)
+        if self.cluster_group is not None:
+            self.cluster_group = np.asarray(self.cluster_group, dtype=np.int64)
+        if self.noise_count <= 0:
+            self.noise_count = float(self.n_neg)
+
+    @property
+    def n_edges(self) -> int:
+        return int(self.row_ptr[-1])
+
+    @classmethod
+    def from_workload(cls, w: dict, **over):
+        d = dict(n=w["n"], row_ptr=w["row_ptr"], col_idx=w["col_idx"], cluster_of=w["cluster_of"],
+                 n_clusters=w["n_clusters"], n_neg=w["n_neg"], noise_count=w["noise_count"], seed=w["seed"],
+                 n_epochs=w["n_epochs"], lr0=w["lr0"], weights=w.get("weights"),
+                 cluster_group=w.get("cluster_group"))
+        d.update(over)
+        return cls(**d)
+
+
+def cauchy(a, b) -> float:
+    """q(a,b) = 1/(1+|a-b|^2)  (Eq. 1)."""
+    dx = float(a[0]) - float(b[0])
+    dy = float(a[1]) - float(b[1])
+    return 1.0 / (1.0 + dx * dx + dy * dy)
+
+
+def edge_probabilities(P: Problem) -> np.ndarray:
+    """p(j|i) for every CSR edge: the row-normalised weight (unit weights -> 1/deg_i)."""
+    E = P.n_edges
+    p = np.zeros(E, dtype=np.float64)
+    for i in range(P.n):
+        a, b = int(P.row_ptr[i]), int(P.row_ptr[i + 1])
+        if b == a:
+            continue
+        if P.weights is None:
+            p[a:b] = 1.0 / (b - a)
+        else:
+            w = P.weights[a:b].astype(np.float64)
+            p[a:b] = w / w.sum()
+    return p
+
+
+def cluster_stats(P: Problem, theta: np.ndarray):
+    """Cell sizes n_r, cell masses p(m in r) = n_r/n, and cell means mu_r of theta."""
+    R = P.n_clusters
+    counts = np.zeros(R, dtype=np.int64)
+    sums = np.zeros((R, 2), dtype=np.float64)
+    th = np.asarray(theta, dtype=np.float64)
+    for i in range(P.n):
+        r = int(P.cluster_of[i])
+        counts[r] += 1
+        sums[r] += th[i]
+    mu = np.zeros((R, 2), dtype=np.float64)
+    nz = counts > 0
+    mu[nz] = sums[nz] / counts[nz, None]
+    return counts, counts / float(P.n), mu
+
+
+def local_sets(P: Problem):
+    """group_of_point [n] and, per group, the ascending array of its points (the sampling
+    population N_i of every head in that group)."""
+    if P.cluster_group is None:
+        gop = np.zeros(P.n, dtype=np.int64)
+    else:
+        gop = P.cluster_group[P.cluster_of]
+    members = {}
+    for g in np.unique(gop):
+        members[int(g)] = np.nonzero(gop == g)[0].astype(np.int64)
+    return gop, members
+
+
+def mean_field(P: Problem, theta: np.ndarray, p_r: np.ndarray, mu: np.ndarray):
+    """A_i = sum_{r in Rtilde_i} p_r q(theta_i, mu_r) (so that Mtilde_i = |M| A_i, Eq. 5) and
+    B_i = sum_{r in Rtilde_i} p_r q(theta_i, mu_r)^2 (theta_i - mu_r), its derivative factor."""
+    n = P.n
+    A = np.zeros(n, dtype=np.float64)
+    B = np.zeros((n, 2), dtype=np.float64)
+    if P.cluster_group is None:
+        return A, B
+    th = np.asarray(theta, dtype=np.float64)
+    grp = P.cluster_group
+    for i in range(n):
+        gi = grp[P.cluster_of[i]]
+        for r in range(P.n_clusters):
+            if grp[r] == gi or p_r[r] == 0.0:
+                continue
+            q = cauchy(th[i], mu[r])
+            A[i] += p_r[r] * q
+            B[i] += p_r[r] * q * q * (th[i] - mu[r])
+    return A, B
+
+
+def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None) -> np.ndarray:
+    """Sampled negative indices m[e, slot] for the CSR edges e_begin..e_end-1 of epoch t."""
+    if e_end is None:
+        e_end = P.n_edges
+    s = P.n_neg
+    out = np.zeros((e_end - e_begin, s), dtype=np.int64)
+    if s == 0 or e_end == e_begin:
+        return out
+    gop, members = local_sets(P)
+    head = np.searchsorted(P.row_ptr, np.arange(e_begin, e_end), side="right") - 1
+    e = np.arange(e_begin, e_end, dtype=np.uint64)
+    k0, k1 = P.seed & _MASK32, (P.seed >> 32) & _MASK32
+    for blk in range((s + 3) // 4):
+        words = philox4x32_10_array(e & np.uint64(_MASK32), e >> np.uint64(32), np.uint64(t), np.uint64(blk), k0, k1)
+        for lane in range(4):
+            slot = 4 * blk + lane
+            if slot >= s:
+                break
+            x = words[lane]
+            for idx in range(e_end - e_begin):
+                pop = members[int(gop[head[idx]])]
+                u = (int(x[idx]) * len(pop)) >> 32
+                out[idx, slot] = pop[u]
+    return out
+
+
+def omega(P: Problem) -> np.ndarray:
+    """Weight of one sampled negative of head i: |M| * (n_loc(i)/n) / s, which makes the
+    sample sum an unbiased estimate of the exact-cell noise term (Eq. 6)."""
+    gop, members = local_sets(P)
+    w = np.zeros(P.n, dtype=np.float64)
+    if P.n_neg == 0:
+        return w
+    for g, pop in members.items():
+        w[gop == g] = P.noise_count * (len(pop) / float(P.n)) / P.n_neg
+    return w
+
+
+def _as_positions(theta) -> np.ndarray:
+    """The product's embeddings are fp32; a float64 array is taken as it is so that the
+    finite-difference checks can perturb below fp32 resolution."""
+    theta = np.asarray(theta)
+    if theta.dtype == np.float64:
+        return theta
+    return theta.astype(np.float32).astype(np.float64)
+
+
+def loss_and_grad(P: Problem, theta: np.ndarray, t: int, want_grad: bool = True, mu_fixed=None):
+    """Sampled NOMAD loss L_t(theta) (Eq. 4, uniform head marginal) and g = grad_theta(n * L_t)
+    with the negatives of epoch index t.  Returns (L, g [n,2]).  ``mu_fixed`` replaces the cell
+    means (the gradient holds them constant; a finite-difference check must do the same)."""
+    th = _as_positions(theta)
+    n, s, Mn = P.n, P.n_neg, float(P.noise_count)
+    pe = edge_probabilities(P)
+    _, p_r, mu = cluster_stats(P, th)
+    if mu_fixed is not None:
+        mu = np.asarray(mu_fixed, dtype=np.float64)
+    A, B = mean_field(P, th, p_r, mu)
+    neg = negatives(P, t)
+    om = omega(P)
+    g = np.zeros((n, 2), dtype=np.float64)
+    total = 0.0
+    for i in range(n):
+        for e in range(int(P.row_ptr[i]), int(P.row_ptr[i + 1])):
+            j = int(P.col_idx[e])
+            d_ij = th[i] - th[j]
+            q_ij = 1.0 / (1.0 + d_ij @ d_ij)
+            q_im = np.zeros(s)
+            for kap in range(s):
+                q_im[kap] = cauchy(th[i], th[neg[e, kap]])
+            S = q_ij + Mn * A[i] + om[i] * q_im.sum()
+            total += pe[e] * (-math.log(q_ij) + math.log(S))
+            if not want_grad:
+                continue
+            a_e = 2.0 * pe[e] * q_ij * (1.0 - q_ij / S)
+            g[i] += a_e * d_ij
+            g[j] -= a_e * d_ij
+            for kap in range(s):
+                m = int(neg[e, kap])
+                d_im = th[i] - th[m]
+                b = 2.0 * pe[e] * om[i] * q_im[kap] ** 2 / S
+                g[i] -= b * d_im
+                g[m] += b * d_im
+            g[i] -= 2.0 * pe[e] * Mn * B[i] / S
+    return total / n, g
+
+
+def learning_rate(P: Problem, t: int) -> float:
+    """eta_t = lr0 * (1 - t/T): linear decay towards zero (Section 3.4)."""
+    return P.lr0 * (1.0 - t / float(P.n_epochs))
+
+
+def epoch(P: Problem, theta: np.ndarray, t: int):
+    """One full-batch step.  Returns (theta_next fp32, g fp64, L at theta)."""
+    L, g = loss_and_grad(P, theta, t)
+    th = _as_positions(theta)
+    return (th - learning_rate(P, t) * g).astype(np.float32), g, L
+
+
+def inverse_rank_weights(k: int) -> np.ndarray:
+    """Inverse-rank edge model (Eq. 7) read with 1-based ranks rho = 1..k and a k-term
+    normaliser so that it is a distribution: p(rho) = exp(1/rho) / sum_{rho'=1..k} exp(1/rho')."""
+    w = np.exp(1.0 / np.arange(1, k + 1, dtype=np.float64))
+    return w / w.sum()
+
+
+def neighbourhood_preservation(nbrs_a: np.ndarray, nbrs_b: np.ndarray) -> float:
+    """Mean overlap of two k-neighbour lists per point (Section 4): (1/n) sum_i |A_i & B_i| / k."""
+    k = nbrs_a.shape[1]
+    tot = 0
+    for a, b in zip(nbrs_a, nbrs_b):
+        tot += len(set(a.tolist()) & set(b.tolist()))
+    return tot / (k * len(nbrs_a))
