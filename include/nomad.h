@@ -1,0 +1,161 @@
+/*
+ * libnomad -- the per-epoch optimisation of a 2-D embedding under the NOMAD Projection loss
+ * (arxiv 2505.15511), on one AMD MI355X (gfx950).  C ABI, plain pointers and sizes.
+ *
+ * One epoch (nomad_epoch) is one full-batch SGD step on the sampled NOMAD loss:
+ *   1. cluster (cell) means mu_r of the embedding                        -- Section 3.3, mu_r below Eq. 6
+ *   2. mean-field sums over the cells approximated for each head         -- Eq. 5
+ *   3. per directed kNN edge ij: Cauchy-kernel attraction (Eq. 1, numerator of Eq. 4),
+ *      s sampled negatives m (uniform noise over tails, Section 3.3) and their repulsion
+ *      (denominator of Eq. 2 / Eq. 4, sampled part Eq. 6)
+ *   4. gradient scatter to heads, tails and negatives
+ *   5. theta <- theta - eta_t g, eta_t = lr0 (1 - t/T)                   -- Section 3.4
+ *
+ * Conventions
+ *   - Every function returns NOMAD_OK (0) or a negative NOMAD_E_* code; nothing throws or aborts
+ *     across this boundary.  nomad_last_error() returns text for the last failure of a context.
+ *   - `mem` says where a caller buffer lives: NOMAD_HOST (pageable or pinned host memory) or
+ *     NOMAD_DEVICE (memory of the context's HIP device).
+ *   - Ownership: the caller owns every buffer it passes.  set_* calls copy their inputs (the
+ *     caller may free them afterwards); get_* calls copy into caller memory.  The library owns
+ *     all of its device state.
+ *   - All point indices and edge positions, in arguments and in results, are the caller's:
+ *     points 0..n-1 and CSR positions 0..E-1 as passed to nomad_set_graph.
+ *   - One context = one device + one stream.  A context is not thread-safe; different contexts
+ *     are independent.  nomad_epoch only enqueues work on the stream; get_* and nomad_loss wait
+ *     for it.
+ */
+#ifndef NOMAD_H
+#define NOMAD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NOMAD_HOST 0
+#define NOMAD_DEVICE 1
+
+#define NOMAD_OK 0
+#define NOMAD_E_INVALID_ARG (-1) /* null pointer, value out of range, struct_size mismatch          */
+#define NOMAD_E_BAD_GRAPH (-2)   /* CSR / weights / cluster ids violate a stated requirement        */
+#define NOMAD_E_ORDER (-3)       /* call made before the state it needs exists                      */
+#define NOMAD_E_TOO_LARGE (-4)   /* n or E does not fit 31-bit indices                              */
+#define NOMAD_E_OOM (-5)         /* device or host allocation failed                                */
+#define NOMAD_E_HIP (-6)         /* a HIP runtime call failed; see nomad_last_error                 */
+
+#define NOMAD_SCATTER_DETERMINISTIC 0
+#define NOMAD_SCATTER_ATOMIC 1
+
+#define NOMAD_MAX_NEG 16
+
+typedef struct nomad_ctx nomad_ctx; /* opaque, library-owned */
+
+typedef struct {
+    uint32_t struct_size;      /* = sizeof(nomad_config); checked by nomad_create                     */
+    int64_t n_points;          /* n >= 1                                                              */
+    int32_t n_clusters;        /* |R| >= 1: number of cells of the partition                          */
+    int32_t n_neg;             /* s: sampled negatives per directed edge, 0..NOMAD_MAX_NEG            */
+    float noise_count;         /* |M| of Eq. 2 / Eq. 4-6; <= 0 means "= n_neg"                        */
+    int32_t n_epochs;          /* T >= 1 of the linear schedule                                       */
+    float lr0;                 /* eta_0, applied to g = grad(n * L): per-point units                  */
+    uint64_t seed;             /* key of the counter-based negative sampler                           */
+    int32_t scatter_mode;      /* NOMAD_SCATTER_DETERMINISTIC or NOMAD_SCATTER_ATOMIC                 */
+    int32_t batches_per_epoch; /* reserved, must be 1                                                 */
+    int32_t device;            /* HIP device ordinal                                                  */
+    void* stream;              /* hipStream_t borrowed from the caller; NULL = the null stream        */
+} nomad_config;
+
+/* Create a context.  Allocates nothing on the device yet.  *out is set only on success. */
+int nomad_create(const nomad_config* cfg, nomad_ctx** out);
+
+/* Free the context and everything it owns.  NULL is allowed. */
+void nomad_destroy(nomad_ctx* ctx);
+
+/*
+ * The input kNN digraph (Section 3.1: a distribution P over directed edges ij, head i, tail j),
+ * the partition R into cells (Section 3.3) and, optionally, which cells each head approximates.
+ *
+ *   row_ptr  [n+1] int32  CSR offsets, row_ptr[0] = 0, non-decreasing, E = row_ptr[n] < 2^31
+ *   col_idx  [E]   int32  tails, 0 <= col < n, no self loops
+ *   weights  [E]   fp32   edge weights >= 0 with a positive sum on every non-empty row, or NULL
+ *                         for unit weights.  p(j|i) of Eq. 4 is the row-normalised weight.
+ *   cluster_of    [n]   int32  cell of each point, 0 <= id < |R|
+ *   cluster_group [|R|] int32  group label of each cell, 0 <= label < |R|, or NULL for a single
+ *                         group.  For a head i the cells of *other* groups are replaced by their
+ *                         means (they form R-tilde of Eq. 5); negatives are sampled from the points
+ *                         of i's own group and weighted |M| (n_group/n) / s (Eq. 6).  NULL means
+ *                         nothing is approximated and Eq. 4 is the InfoNC-t-SNE loss, Eq. 2.
+ *
+ * In deterministic mode the graph must also be structurally symmetric without parallel edges
+ * (the tail sums are pulled through the reverse edge).  Violations give NOMAD_E_BAD_GRAPH and
+ * leave the context without a graph.  Replaces any earlier graph and embedding.
+ */
+int nomad_set_graph(nomad_ctx* ctx, const int32_t* row_ptr, const int32_t* col_idx, const float* weights,
+                    const int32_t* cluster_of, const int32_t* cluster_group, int mem);
+
+/* theta [n*2] fp32 row-major (Section 3.1: the matrix of low-dimensional positions). */
+int nomad_set_embedding(nomad_ctx* ctx, const float* theta, int mem);
+
+/*
+ * One epoch with epoch index t, 0 <= t < T: fresh negatives keyed on (seed, t, edge, slot), the
+ * gradient of the sampled loss (Eq. 4 with Eq. 5-6) and the SGD step with eta_t = lr0 (1 - t/T)
+ * (Section 3.4).  Enqueued on the context's stream; returns without waiting.
+ */
+int nomad_epoch(nomad_ctx* ctx, int32_t t);
+
+/*
+ * The sampled loss of Eq. 4 at the current embedding, with the negatives of epoch index
+ * t_sample >= 0 and cell means of the current embedding.  Waits for the stream.  *out_host is a
+ * host double.  Does not change the embedding or the stored gradient.
+ */
+int nomad_loss(nomad_ctx* ctx, int32_t t_sample, double* out_host);
+
+/* Current embedding, [n*2] fp32.  Waits for the stream. */
+int nomad_get_embedding(nomad_ctx* ctx, float* out, int mem);
+
+/* ---- test hooks (same conventions; all wait for the stream) ---- */
+
+/* g = grad(n * L_t) of the most recent nomad_epoch, as it was applied.  [n*2] fp32. */
+int nomad_get_gradient(nomad_ctx* ctx, float* out, int mem);
+
+/* Negative indices of CSR edges e_begin..e_end-1 for epoch index t: [(e_end-e_begin)*s] int32. */
+int nomad_get_negatives(nomad_ctx* ctx, int32_t t, int64_t e_begin, int64_t e_end, int32_t* out, int mem);
+
+/* Cell means of the current embedding, mu [|R|*2] fp32, and cell sizes, counts [|R|] int64. */
+int nomad_get_means(nomad_ctx* ctx, float* mu, int64_t* counts, int mem);
+
+/* Mean-field sums of the current embedding: A [n] = sum_{r in R-tilde_i} p_r q(theta_i, mu_r) and
+ * B [n*2] = sum p_r q^2 (theta_i - mu_r) (Eq. 5 without |M|, and the factor of its derivative).
+ * All zero when no cell is approximated. */
+int nomad_get_mean_field(nomad_ctx* ctx, float* A, float* B, int mem);
+
+/* Number of directed edges E of the current graph (0 before nomad_set_graph). */
+int64_t nomad_num_edges(const nomad_ctx* ctx);
+
+/* ---- kernel timing (HIP events on the context's stream, around each launch) ---- */
+
+#define NOMAD_K_MEANS 0      /* cell means                         */
+#define NOMAD_K_MEANFIELD 1  /* mean-field sums                    */
+#define NOMAD_K_EDGES 2      /* attraction + sampling + repulsion  */
+#define NOMAD_K_SCATTER 3    /* deterministic tail pull + combine  */
+#define NOMAD_K_UPDATE 4     /* SGD step                           */
+#define NOMAD_K_LOSS 5       /* loss terms + reduction             */
+#define NOMAD_K_ZERO 6       /* clearing of accumulators           */
+#define NOMAD_K_COUNT 7
+
+/* Switch per-launch timing on (1) or off (0); switching on clears earlier samples. */
+int nomad_profile(nomad_ctx* ctx, int enable);
+
+/* Waits for the stream; total milliseconds and number of launches of one kernel kind since
+ * timing was switched on. */
+int nomad_profile_read(nomad_ctx* ctx, int kind, double* total_ms, int64_t* launches);
+
+/* Text of the last error of this context ("" if none).  Valid until the next call on it. */
+const char* nomad_last_error(const nomad_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NOMAD_H */

@@ -1,0 +1,6 @@
+"""NOMAD Projection epoch path for AMD MI355X: a C-ABI HIP library (libnomad.so) and its binding.
+
+Importing the package loads nothing; ``binding.load_library()`` opens the shared library and
+raises if it has not been built."""
+from .binding import (Nomad, NomadError, NomadConfig, load_library, SCATTER_ATOMIC, SCATTER_DETERMINISTIC,
+                      NOMAD_DEVICE, NOMAD_HOST)  # noqa: F401

@@ -1,0 +1,219 @@
+"""Thin ctypes binding of libnomad's C ABI (include/nomad.h).
+
+Argument marshalling only: every step of the epoch runs in the library's HIP kernels.  Buffers
+may be torch tensors (CPU or on the context's GPU) or numpy arrays; torch is used here for
+device memory and stream handles, nothing else.  There is no CPU fallback: if the shared library
+has not been built, loading fails with an error."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import _build
+
+NOMAD_HOST, NOMAD_DEVICE = 0, 1
+SCATTER_DETERMINISTIC, SCATTER_ATOMIC = 0, 1
+K_MEANS, K_MEANFIELD, K_EDGES, K_SCATTER, K_UPDATE, K_LOSS, K_ZERO = range(7)
+KERNEL_NAMES = ["means", "mean_field", "edges", "scatter", "update", "loss", "zero"]
+ERRORS = {-1: "NOMAD_E_INVALID_ARG", -2: "NOMAD_E_BAD_GRAPH", -3: "NOMAD_E_ORDER", -4: "NOMAD_E_TOO_LARGE",
+          -5: "NOMAD_E_OOM", -6: "NOMAD_E_HIP"}
+
+EXPORTS = ["nomad_create", "nomad_destroy", "nomad_set_graph", "nomad_set_embedding", "nomad_epoch", "nomad_loss",
+           "nomad_get_embedding", "nomad_get_gradient", "nomad_get_negatives", "nomad_get_means",
+           "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error"]
+
+
+class NomadConfig(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_points", C.c_int64), ("n_clusters", C.c_int32), ("n_neg", C.c_int32),
+                ("noise_count", C.c_float), ("n_epochs", C.c_int32), ("lr0", C.c_float), ("seed", C.c_uint64),
+                ("scatter_mode", C.c_int32), ("batches_per_epoch", C.c_int32), ("device", C.c_int32),
+                ("stream", C.c_void_p)]
+
+
+class NomadError(RuntimeError):
+    def __init__(self, code, text=""):
+        self.code = code
+        super().__init__(f"{ERRORS.get(code, code)}: {text}")
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen libnomad.so.  Raises if it has not been built (run __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        raise RuntimeError(f"{_build.LIB_PATH} is missing: build the HIP library first "
+                           "(python -c 'import __graft_entry__ as g; g.build()'); there is no fallback path")
+    lib = C.CDLL(_build.LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.nomad_create.argtypes = [C.POINTER(NomadConfig), C.POINTER(vp)]
+    lib.nomad_destroy.argtypes = [vp]
+    lib.nomad_destroy.restype = None
+    lib.nomad_set_graph.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int]
+    lib.nomad_set_embedding.argtypes = [vp, vp, C.c_int]
+    lib.nomad_epoch.argtypes = [vp, i32]
+    lib.nomad_loss.argtypes = [vp, i32, C.POINTER(C.c_double)]
+    lib.nomad_get_embedding.argtypes = [vp, vp, C.c_int]
+    lib.nomad_get_gradient.argtypes = [vp, vp, C.c_int]
+    lib.nomad_get_negatives.argtypes = [vp, i32, i64, i64, vp, C.c_int]
+    lib.nomad_get_means.argtypes = [vp, vp, vp, C.c_int]
+    lib.nomad_get_mean_field.argtypes = [vp, vp, vp, C.c_int]
+    lib.nomad_num_edges.argtypes = [vp]
+    lib.nomad_num_edges.restype = i64
+    lib.nomad_profile.argtypes = [vp, C.c_int]
+    lib.nomad_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.nomad_last_error.argtypes = [vp]
+    lib.nomad_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _is_torch(x):
+    return x is not None and type(x).__module__.startswith("torch")
+
+
+def _marshal(x, np_dtype, count=None):
+    """-> (pointer, mem, keepalive).  Accepts None, torch tensor (cpu/cuda) or array-like."""
+    if x is None:
+        return None, None, None
+    if _is_torch(x):
+        import torch
+        want = {np.int32: torch.int32, np.float32: torch.float32, np.int64: torch.int64}[np_dtype]
+        t = x if (x.dtype == want and x.is_contiguous()) else x.to(want).contiguous()
+        if count is not None and t.numel() != count:
+            raise ValueError(f"expected {count} elements, got {t.numel()}")
+        return C.c_void_p(t.data_ptr()), (NOMAD_DEVICE if t.is_cuda else NOMAD_HOST), t
+    a = np.ascontiguousarray(x, dtype=np_dtype)
+    if count is not None and a.size != count:
+        raise ValueError(f"expected {count} elements, got {a.size}")
+    return a.ctypes.data_as(C.c_void_p), NOMAD_HOST, a
+
+
+class Nomad:
+    """One libnomad context.  Method names are the C entry points without the prefix."""
+
+    def __init__(self, n_points, n_clusters, n_neg, noise_count=0.0, n_epochs=1, lr0=1.0, seed=0,
+                 scatter_mode=SCATTER_DETERMINISTIC, device=0, stream=None):
+        self.lib = load_library()
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream(device).cuda_stream
+        self.cfg = NomadConfig(C.sizeof(NomadConfig), int(n_points), int(n_clusters), int(n_neg), float(noise_count),
+                               int(n_epochs), float(lr0), int(seed), int(scatter_mode), 1, int(device),
+                               C.c_void_p(int(stream) if stream else None))
+        self.n, self.R, self.s = int(n_points), int(n_clusters), int(n_neg)
+        self.device = int(device)
+        self.ctx = C.c_void_p()
+        rc = self.lib.nomad_create(C.byref(self.cfg), C.byref(self.ctx))
+        if rc:
+            self.ctx = C.c_void_p()
+            raise NomadError(rc, "nomad_create")
+
+    @classmethod
+    def from_workload(cls, w, scatter_mode=SCATTER_DETERMINISTIC, device=0, **over):
+        kw = dict(n_points=w.n, n_clusters=w.n_clusters, n_neg=w.n_neg, noise_count=w.noise_count,
+                  n_epochs=w.n_epochs, lr0=w.lr0, seed=w.seed, scatter_mode=scatter_mode, device=device)
+        kw.update(over)
+        nm = cls(**kw)
+        nm.set_graph(w.row_ptr, w.col_idx, w.weights, w.cluster_of, w.cluster_group)
+        nm.set_embedding(w.theta0)
+        return nm
+
+    def _check(self, rc):
+        if rc:
+            raise NomadError(rc, self.lib.nomad_last_error(self.ctx).decode())
+
+    def close(self):
+        if getattr(self, "ctx", None) and self.ctx.value:
+            self.lib.nomad_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    __del__ = close
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    # ---- inputs
+    def set_graph(self, row_ptr, col_idx, weights, cluster_of, cluster_group=None):
+        rp, m0, k0 = _marshal(row_ptr, np.int32, self.n + 1)
+        ci, m1, k1 = _marshal(col_idx, np.int32)
+        w, m2, k2 = _marshal(weights, np.float32)
+        co, m3, k3 = _marshal(cluster_of, np.int32, self.n)
+        cg, m4, k4 = _marshal(cluster_group, np.int32, self.R if cluster_group is not None else None)
+        mems = {m for m in (m0, m1, m2, m3, m4) if m is not None}
+        if len(mems) > 1:
+            raise ValueError("all graph buffers must live in the same memory space")
+        self._check(self.lib.nomad_set_graph(self.ctx, rp, ci, w, co, cg, mems.pop()))
+
+    def set_embedding(self, theta):
+        p, mem, keep = _marshal(theta, np.float32, 2 * self.n)
+        self._check(self.lib.nomad_set_embedding(self.ctx, p, mem))
+
+    # ---- the path
+    def epoch(self, t):
+        self._check(self.lib.nomad_epoch(self.ctx, int(t)))
+
+    def loss(self, t_sample):
+        out = C.c_double(0.0)
+        self._check(self.lib.nomad_loss(self.ctx, int(t_sample), C.byref(out)))
+        return out.value
+
+    # ---- outputs (numpy on the host, or a torch tensor on the device when device=True)
+    def _out(self, fn, shape, np_dtype, device_out, *pre):
+        if device_out:
+            import torch
+            tdt = {np.float32: torch.float32, np.int32: torch.int32}[np_dtype]
+            t = torch.empty(shape, dtype=tdt, device=f"cuda:{self.device}")
+            self._check(fn(self.ctx, *pre, C.c_void_p(t.data_ptr()), NOMAD_DEVICE))
+            return t
+        a = np.empty(shape, dtype=np_dtype)
+        self._check(fn(self.ctx, *pre, a.ctypes.data_as(C.c_void_p), NOMAD_HOST))
+        return a
+
+    def get_embedding(self, device=False):
+        return self._out(self.lib.nomad_get_embedding, (self.n, 2), np.float32, device)
+
+    def get_gradient(self, device=False):
+        return self._out(self.lib.nomad_get_gradient, (self.n, 2), np.float32, device)
+
+    def get_negatives(self, t, e_begin=0, e_end=None, device=False):
+        e_end = self.num_edges() if e_end is None else e_end
+        return self._out(self.lib.nomad_get_negatives, (e_end - e_begin, self.s), np.int32, device, int(t),
+                         int(e_begin), int(e_end))
+
+    def get_means(self):
+        mu = np.empty((self.R, 2), dtype=np.float32)
+        counts = np.empty(self.R, dtype=np.int64)
+        self._check(self.lib.nomad_get_means(self.ctx, mu.ctypes.data_as(C.c_void_p), counts.ctypes.data_as(C.c_void_p),
+                                             NOMAD_HOST))
+        return mu, counts
+
+    def get_mean_field(self):
+        A = np.empty(self.n, dtype=np.float32)
+        B = np.empty((self.n, 2), dtype=np.float32)
+        self._check(self.lib.nomad_get_mean_field(self.ctx, A.ctypes.data_as(C.c_void_p), B.ctypes.data_as(C.c_void_p),
+                                                  NOMAD_HOST))
+        return A, B
+
+    def num_edges(self):
+        return int(self.lib.nomad_num_edges(self.ctx))
+
+    def profile(self, enable=True):
+        self._check(self.lib.nomad_profile(self.ctx, 1 if enable else 0))
+
+    def profile_read(self):
+        """-> {kernel name: (total ms, launches)}"""
+        out = {}
+        for kind, name in enumerate(KERNEL_NAMES):
+            ms, cnt = C.c_double(0.0), C.c_int64(0)
+            self._check(self.lib.nomad_profile_read(self.ctx, kind, C.byref(ms), C.byref(cnt)))
+            out[name] = (ms.value, cnt.value)
+        return out

@@ -1,0 +1,602 @@
+// libnomad: C ABI over the gfx950 kernels in nomad_kernels.h.  Host code only sequences kernel
+// launches on the context's stream and moves buffers; every step of the epoch runs on the GPU.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "nomad.h"
+#include "nomad_kernels.h"
+
+using namespace nomad;
+
+struct KernelTimer {
+    std::vector<hipEvent_t> begin, end;
+};
+
+struct nomad_ctx {
+    nomad_config cfg{};
+    hipStream_t stream = nullptr;
+    float noise_count = 0.f;
+    std::string err;
+    bool has_graph = false, has_theta = false, has_grad = false;
+    int64_t n = 0, E = 0;
+    int32_t R = 0;
+    bool grouped = false;
+    int lpr = 16;
+    // graph
+    int32_t *row_ptr = nullptr, *col = nullptr, *cluster_of = nullptr, *group_of_cluster = nullptr, *rev = nullptr;
+    float* pe = nullptr;
+    // partition tables
+    uint32_t *counts = nullptr, *gbase = nullptr, *gcount = nullptr, *chunk_start = nullptr;
+    float* gomega = nullptr;
+    int32_t *gmembers = nullptr, *cmembers = nullptr;
+    MeanChunk* chunks = nullptr;
+    uint32_t n_chunks = 0;
+    double2* mean_partial = nullptr;
+    float omega0 = 0.f;
+    // state
+    float2 *theta = nullptr, *g = nullptr, *ghead = nullptr, *mu = nullptr, *B = nullptr;
+    float4* cinfo = nullptr;
+    float *A = nullptr, *coef = nullptr;
+    unsigned long long* gfix = nullptr;
+    double *loss_partial = nullptr, *loss_out = nullptr;
+    uint32_t edge_grid = 0;
+    int* flags = nullptr;
+    // timing
+    bool profiling = false;
+    KernelTimer timers[NOMAD_K_COUNT];
+};
+
+namespace {
+
+int fail(nomad_ctx* c, int code, const char* fmt, ...) {
+    if (c) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof(buf), fmt, ap);
+        va_end(ap);
+        c->err = buf;
+    }
+    return code;
+}
+
+#define HIP_TRY(c, call)                                                                                   \
+    do {                                                                                                   \
+        hipError_t e_ = (call);                                                                            \
+        if (e_ != hipSuccess)                                                                              \
+            return fail((c), e_ == hipErrorOutOfMemory ? NOMAD_E_OOM : NOMAD_E_HIP, "%s: %s", #call,       \
+                        hipGetErrorString(e_));                                                            \
+    } while (0)
+
+template <typename T>
+int dev_alloc(nomad_ctx* c, T** p, size_t count) {
+    *p = nullptr;
+    HIP_TRY(c, hipMalloc((void**)p, std::max<size_t>(count, 1) * sizeof(T)));
+    return NOMAD_OK;
+}
+
+template <typename T>
+void dev_free(T*& p) {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+}
+
+void free_graph(nomad_ctx* c) {
+    dev_free(c->row_ptr); dev_free(c->col); dev_free(c->cluster_of); dev_free(c->group_of_cluster); dev_free(c->rev);
+    dev_free(c->pe); dev_free(c->counts); dev_free(c->gbase); dev_free(c->gcount); dev_free(c->chunk_start);
+    dev_free(c->gomega); dev_free(c->gmembers); dev_free(c->cmembers); dev_free(c->chunks); dev_free(c->mean_partial);
+    dev_free(c->theta); dev_free(c->g); dev_free(c->ghead); dev_free(c->mu); dev_free(c->B); dev_free(c->cinfo);
+    dev_free(c->A); dev_free(c->coef); dev_free(c->gfix); dev_free(c->loss_partial); dev_free(c->loss_out);
+    dev_free(c->flags);
+    c->has_graph = c->has_theta = c->has_grad = false;
+    c->E = 0;
+}
+
+hipMemcpyKind in_kind(int mem) { return mem == NOMAD_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice; }
+hipMemcpyKind out_kind(int mem) { return mem == NOMAD_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost; }
+
+inline uint32_t blocks_for(int64_t items, int per_block = kBlock) { return (uint32_t)((items + per_block - 1) / per_block); }
+
+struct Timed {  // records a begin/end event pair around one launch when timing is on
+    nomad_ctx* c; int kind; hipEvent_t e1 = nullptr;
+    Timed(nomad_ctx* ctx, int k) : c(ctx), kind(k) {
+        if (!c->profiling) return;
+        hipEvent_t e0 = nullptr;
+        if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { e1 = nullptr; return; }
+        (void)hipEventRecord(e0, c->stream);
+        c->timers[kind].begin.push_back(e0);
+    }
+    ~Timed() {
+        if (!e1) return;
+        (void)hipEventRecord(e1, c->stream);
+        c->timers[kind].end.push_back(e1);
+    }
+};
+
+void clear_timers(nomad_ctx* c) {
+    for (auto& t : c->timers) {
+        for (auto e : t.begin) (void)hipEventDestroy(e);
+        for (auto e : t.end) (void)hipEventDestroy(e);
+        t.begin.clear();
+        t.end.clear();
+    }
+}
+
+EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
+    EdgeArgs a{};
+    a.row_ptr = c->row_ptr; a.col = c->col; a.pe = c->pe; a.theta = c->theta;
+    a.cluster_of = c->cluster_of; a.group_of_cluster = c->grouped ? c->group_of_cluster : nullptr;
+    a.gbase = c->gbase; a.gcount = c->gcount; a.gomega = c->gomega; a.gmembers = c->gmembers;
+    a.A = c->A; a.B = c->B;
+    a.noise_count = c->noise_count; a.omega0 = c->omega0;
+    a.key0 = (uint32_t)c->cfg.seed; a.key1 = (uint32_t)(c->cfg.seed >> 32); a.epoch = t;
+    a.s = c->cfg.n_neg; a.n = c->n;
+    a.g = c->g; a.ghead = c->ghead; a.coef = c->coef; a.gfix = c->gfix; a.loss_partial = c->loss_partial;
+    return a;
+}
+
+template <int MODE, int LPR>
+void launch_edges_s(nomad_ctx* c, const EdgeArgs& a) {
+    const dim3 grid(c->edge_grid), block(kBlock);
+    switch (c->cfg.n_neg) {
+#define NOMAD_CASE(S) case S: hipLaunchKernelGGL((k_edges<S, MODE, LPR>), grid, block, 0, c->stream, a); break;
+        NOMAD_CASE(1) NOMAD_CASE(2) NOMAD_CASE(3) NOMAD_CASE(4) NOMAD_CASE(5) NOMAD_CASE(6) NOMAD_CASE(7) NOMAD_CASE(8)
+#undef NOMAD_CASE
+        default: hipLaunchKernelGGL((k_edges<0, MODE, LPR>), grid, block, 0, c->stream, a); break;
+    }
+}
+
+template <int MODE>
+void launch_edges(nomad_ctx* c, const EdgeArgs& a) {
+    launch_edges_s<MODE, 16>(c, a);
+}
+
+// cell means of the current embedding -> mu, cinfo
+int run_means(nomad_ctx* c) {
+    Timed tm(c, NOMAD_K_MEANS);
+    if (c->n_chunks)
+        hipLaunchKernelGGL(k_mean_chunks, dim3(c->n_chunks), dim3(kBlock), 0, c->stream, c->theta, c->cmembers, c->chunks,
+                           c->mean_partial);
+    hipLaunchKernelGGL(k_mean_finish, dim3(blocks_for((int64_t)c->R * 64)), dim3(kBlock), 0, c->stream, c->mean_partial,
+                       c->chunk_start, c->counts, c->grouped ? c->group_of_cluster : nullptr, c->R, 1.0 / (double)c->n, c->mu,
+                       c->cinfo);
+    return NOMAD_OK;
+}
+
+int run_mean_field(nomad_ctx* c) {
+    if (!c->grouped) return NOMAD_OK;
+    Timed tm(c, NOMAD_K_MEANFIELD);
+    hipLaunchKernelGGL(k_mean_field, dim3(blocks_for(c->n)), dim3(kBlock), 0, c->stream, c->theta, c->cluster_of,
+                       c->group_of_cluster, c->cinfo, c->R, c->n, c->A, c->B);
+    return NOMAD_OK;
+}
+
+int check_ready(nomad_ctx* c, bool need_theta) {
+    if (!c) return NOMAD_E_INVALID_ARG;
+    if (!c->has_graph) return fail(c, NOMAD_E_ORDER, "no graph: call nomad_set_graph first");
+    if (need_theta && !c->has_theta) return fail(c, NOMAD_E_ORDER, "no embedding: call nomad_set_embedding first");
+    return NOMAD_OK;
+}
+
+int copy_out(nomad_ctx* c, void* dst, const void* src, size_t bytes, int mem) {
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(dst, src, bytes, out_kind(mem)));
+    return NOMAD_OK;
+}
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+int nomad_create(const nomad_config* cfg, nomad_ctx** out) {
+    if (!cfg || !out) return NOMAD_E_INVALID_ARG;
+    if (cfg->struct_size != sizeof(nomad_config)) return NOMAD_E_INVALID_ARG;
+    if (cfg->n_points < 1 || cfg->n_clusters < 1 || cfg->n_neg < 0 || cfg->n_neg > NOMAD_MAX_NEG || cfg->n_epochs < 1 ||
+        cfg->batches_per_epoch != 1 || !(cfg->lr0 >= 0.f) || !std::isfinite(cfg->lr0) || !std::isfinite(cfg->noise_count) ||
+        (cfg->scatter_mode != NOMAD_SCATTER_DETERMINISTIC && cfg->scatter_mode != NOMAD_SCATTER_ATOMIC) || cfg->device < 0)
+        return NOMAD_E_INVALID_ARG;
+    if (cfg->n_points >= ((int64_t)1 << 31) || cfg->n_clusters > cfg->n_points) return cfg->n_points >= ((int64_t)1 << 31) ? NOMAD_E_TOO_LARGE : NOMAD_E_INVALID_ARG;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device >= ndev) return NOMAD_E_HIP;
+    nomad_ctx* c = new (std::nothrow) nomad_ctx();
+    if (!c) return NOMAD_E_OOM;
+    c->cfg = *cfg;
+    c->stream = (hipStream_t)cfg->stream;
+    c->n = cfg->n_points;
+    c->R = cfg->n_clusters;
+    c->noise_count = cfg->noise_count > 0.f ? cfg->noise_count : (float)cfg->n_neg;
+    *out = c;
+    return NOMAD_OK;
+}
+
+void nomad_destroy(nomad_ctx* c) {
+    if (!c) return;
+    (void)hipSetDevice(c->cfg.device);
+    (void)hipStreamSynchronize(c->stream);
+    clear_timers(c);
+    free_graph(c);
+    delete c;
+}
+
+const char* nomad_last_error(const nomad_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+int64_t nomad_num_edges(const nomad_ctx* c) { return c ? c->E : 0; }
+
+int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx, const float* weights,
+                    const int32_t* cluster_of, const int32_t* cluster_group, int mem) {
+    if (!c) return NOMAD_E_INVALID_ARG;
+    if (!row_ptr || !cluster_of || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return fail(c, NOMAD_E_INVALID_ARG, "null pointer or bad mem");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    free_graph(c);
+    const int64_t n = c->n;
+    const int32_t R = c->R;
+    hipStream_t st = c->stream;
+    int rc;
+#define TRY(x) do { rc = (x); if (rc != NOMAD_OK) { free_graph(c); return rc; } } while (0)
+#define HTRY(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { free_graph(c); return fail(c, e_ == hipErrorOutOfMemory ? NOMAD_E_OOM : NOMAD_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); } } while (0)
+
+    // ---- copy the CSR offsets, learn E
+    TRY(dev_alloc(c, &c->row_ptr, (size_t)n + 1));
+    HTRY(hipMemcpy(c->row_ptr, row_ptr, sizeof(int32_t) * ((size_t)n + 1), in_kind(mem)));
+    int32_t E32 = 0;
+    HTRY(hipMemcpy(&E32, c->row_ptr + n, sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (E32 < 0) { free_graph(c); return fail(c, NOMAD_E_BAD_GRAPH, "row_ptr[n] is negative"); }
+    const int64_t E = E32;
+    if (E > 0 && !col_idx) { free_graph(c); return fail(c, NOMAD_E_INVALID_ARG, "col_idx is null"); }
+    c->E = E;
+    TRY(dev_alloc(c, &c->col, (size_t)E));
+    if (E) HTRY(hipMemcpy(c->col, col_idx, sizeof(int32_t) * (size_t)E, in_kind(mem)));
+    TRY(dev_alloc(c, &c->cluster_of, (size_t)n));
+    HTRY(hipMemcpy(c->cluster_of, cluster_of, sizeof(int32_t) * (size_t)n, in_kind(mem)));
+    float* wdev = nullptr;
+    if (weights) {
+        TRY(dev_alloc(c, &c->pe, (size_t)E));
+        TRY(dev_alloc(c, &wdev, (size_t)E));
+        hipError_t e_ = E ? hipMemcpy(wdev, weights, sizeof(float) * (size_t)E, in_kind(mem)) : hipSuccess;
+        if (e_ != hipSuccess) { dev_free(wdev); free_graph(c); return fail(c, NOMAD_E_HIP, "copy of weights: %s", hipGetErrorString(e_)); }
+    }
+    std::vector<int32_t> hgroup;
+    c->grouped = false;
+    if (cluster_group) {
+        hgroup.resize(R);
+        hipError_t e_ = hipMemcpy(hgroup.data(), cluster_group, sizeof(int32_t) * (size_t)R,
+                                  mem == NOMAD_DEVICE ? hipMemcpyDeviceToHost : hipMemcpyHostToHost);
+        if (e_ != hipSuccess) { dev_free(wdev); free_graph(c); return fail(c, NOMAD_E_HIP, "copy of cluster_group: %s", hipGetErrorString(e_)); }
+        for (int32_t r = 0; r < R; ++r)
+            if (hgroup[r] < 0 || hgroup[r] >= R) { dev_free(wdev); free_graph(c); return fail(c, NOMAD_E_BAD_GRAPH, "cluster_group[%d] = %d is outside 0..|R|-1", r, hgroup[r]); }
+        for (int32_t r = 1; r < R; ++r)
+            if (hgroup[r] != hgroup[0]) c->grouped = true;   // one label everywhere == nothing approximated
+        if (c->grouped) {
+            rc = dev_alloc(c, &c->group_of_cluster, (size_t)R);
+            if (rc == NOMAD_OK && hipMemcpy(c->group_of_cluster, hgroup.data(), sizeof(int32_t) * (size_t)R, hipMemcpyHostToDevice) != hipSuccess) rc = fail(c, NOMAD_E_HIP, "upload of cluster_group failed");
+            if (rc != NOMAD_OK) { dev_free(wdev); free_graph(c); return rc; }
+        }
+    }
+
+    // ---- validate on the device
+    rc = dev_alloc(c, &c->flags, kFlagCount);
+    uint32_t *first = nullptr, *gfirst = nullptr;
+    unsigned long long* boundaries = nullptr;
+    if (rc == NOMAD_OK) rc = dev_alloc(c, &c->counts, (size_t)R);
+    if (rc == NOMAD_OK) rc = dev_alloc(c, &first, (size_t)R);
+    if (rc == NOMAD_OK) rc = dev_alloc(c, &gfirst, (size_t)R);
+    if (rc == NOMAD_OK) rc = dev_alloc(c, &boundaries, 2);
+    auto cleanup_tmp = [&]() { dev_free(wdev); dev_free(first); dev_free(gfirst); dev_free(boundaries); };
+    if (rc != NOMAD_OK) { cleanup_tmp(); free_graph(c); return rc; }
+#define HTRY2(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { cleanup_tmp(); free_graph(c); return fail(c, e_ == hipErrorOutOfMemory ? NOMAD_E_OOM : NOMAD_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); } } while (0)
+    HTRY2(hipMemsetAsync(c->flags, 0, sizeof(int) * kFlagCount, st));
+    HTRY2(hipMemsetAsync(c->counts, 0, sizeof(uint32_t) * (size_t)R, st));
+    HTRY2(hipMemsetAsync(first, 0xFF, sizeof(uint32_t) * (size_t)R, st));
+    HTRY2(hipMemsetAsync(gfirst, 0xFF, sizeof(uint32_t) * (size_t)R, st));
+    HTRY2(hipMemsetAsync(boundaries, 0, sizeof(unsigned long long) * 2, st));
+    hipLaunchKernelGGL(k_check_row_ptr, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->row_ptr, n, c->flags);
+    int hflags[kFlagCount];
+    HTRY2(hipMemcpyAsync(hflags, c->flags, sizeof(hflags), hipMemcpyDeviceToHost, st));
+    HTRY2(hipStreamSynchronize(st));
+    if (hflags[kFlagRowPtr]) { cleanup_tmp(); free_graph(c); return fail(c, NOMAD_E_BAD_GRAPH, "row_ptr must start at 0 and be non-decreasing"); }
+    hipLaunchKernelGGL(k_check_rows, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->row_ptr, c->col, wdev, c->pe, n, c->flags);
+    hipLaunchKernelGGL(k_cluster_census, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->cluster_of,
+                       c->grouped ? c->group_of_cluster : nullptr, n, R, c->counts, first, gfirst, boundaries, c->flags);
+    HTRY2(hipMemcpyAsync(hflags, c->flags, sizeof(hflags), hipMemcpyDeviceToHost, st));
+    HTRY2(hipStreamSynchronize(st));
+    const char* what = hflags[kFlagCol] ? "col_idx entry outside 0..n-1" : hflags[kFlagSelfLoop] ? "self loop in the graph"
+                     : hflags[kFlagWeight] ? "weights must be finite, >= 0, with a positive sum on every non-empty row"
+                     : hflags[kFlagCluster] ? "cluster_of entry outside 0..|R|-1" : nullptr;
+    if (what) { cleanup_tmp(); free_graph(c); return fail(c, NOMAD_E_BAD_GRAPH, "%s", what); }
+    dev_free(wdev);
+
+    // ---- partition tables (host arithmetic on |R|-sized arrays only)
+    std::vector<uint32_t> hcounts(R), hfirst(R), hgfirst(R);
+    unsigned long long hb[2];
+    HTRY2(hipMemcpy(hcounts.data(), c->counts, sizeof(uint32_t) * (size_t)R, hipMemcpyDeviceToHost));
+    HTRY2(hipMemcpy(hfirst.data(), first, sizeof(uint32_t) * (size_t)R, hipMemcpyDeviceToHost));
+    HTRY2(hipMemcpy(hgfirst.data(), gfirst, sizeof(uint32_t) * (size_t)R, hipMemcpyDeviceToHost));
+    HTRY2(hipMemcpy(hb, boundaries, sizeof(hb), hipMemcpyDeviceToHost));
+    cleanup_tmp();
+    int64_t nonempty = 0;
+    for (int32_t r = 0; r < R; ++r) nonempty += hcounts[r] > 0;
+    const bool clusters_contiguous = (int64_t)hb[0] == nonempty - 1;
+    std::vector<int32_t> hcluster;   // host copy of cluster_of, fetched only if a member list is needed
+    auto fetch_clusters = [&]() -> int {
+        if (!hcluster.empty()) return NOMAD_OK;
+        hcluster.resize((size_t)n);
+        hipError_t e_ = hipMemcpy(hcluster.data(), c->cluster_of, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost);
+        return e_ == hipSuccess ? NOMAD_OK : fail(c, NOMAD_E_HIP, "download of cluster_of: %s", hipGetErrorString(e_));
+    };
+    // member order of the cells for the mean reduction
+    std::vector<uint32_t> cstart(R + 1, 0);
+    if (clusters_contiguous) {
+        for (int32_t r = 0; r < R; ++r) cstart[r] = hcounts[r] ? hfirst[r] : 0;   // start in index space
+    } else {
+        TRY(fetch_clusters());
+        for (int32_t r = 0; r < R; ++r) cstart[r + 1] = cstart[r] + hcounts[r];
+        std::vector<uint32_t> cur(cstart.begin(), cstart.end() - 1);
+        std::vector<int32_t> mem_list((size_t)n);
+        for (int64_t i = 0; i < n; ++i) mem_list[cur[hcluster[i]]++] = (int32_t)i;
+        TRY(dev_alloc(c, &c->cmembers, (size_t)n));
+        HTRY(hipMemcpy(c->cmembers, mem_list.data(), sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+    }
+    {
+        constexpr uint32_t kChunk = 2048;
+        std::vector<MeanChunk> chunks;
+        std::vector<uint32_t> chunk_start(R + 1, 0);
+        for (int32_t r = 0; r < R; ++r) {
+            chunk_start[r] = (uint32_t)chunks.size();
+            for (uint32_t o = 0; o < hcounts[r]; o += kChunk)
+                chunks.push_back(MeanChunk{r, cstart[r] + o, cstart[r] + std::min(hcounts[r], o + kChunk)});
+        }
+        chunk_start[R] = (uint32_t)chunks.size();
+        c->n_chunks = (uint32_t)chunks.size();
+        TRY(dev_alloc(c, &c->chunks, chunks.size()));
+        TRY(dev_alloc(c, &c->chunk_start, (size_t)R + 1));
+        TRY(dev_alloc(c, &c->mean_partial, chunks.size()));
+        HTRY(hipMemcpy(c->chunks, chunks.data(), sizeof(MeanChunk) * chunks.size(), hipMemcpyHostToDevice));
+        HTRY(hipMemcpy(c->chunk_start, chunk_start.data(), sizeof(uint32_t) * ((size_t)R + 1), hipMemcpyHostToDevice));
+    }
+    // sampling populations
+    const double Mn = (double)c->noise_count;
+    const int s = c->cfg.n_neg;
+    c->omega0 = s > 0 ? (float)(Mn / (double)s) : 0.f;
+    if (c->grouped) {
+        std::vector<uint32_t> gcount(R, 0), gbase(R, 0);
+        std::vector<float> gomega(R, 0.f);
+        for (int32_t r = 0; r < R; ++r) gcount[hgroup[r]] += hcounts[r];
+        int64_t ngroups = 0;
+        for (int32_t g = 0; g < R; ++g) ngroups += gcount[g] > 0;
+        const bool groups_contiguous = (int64_t)hb[1] == ngroups - 1;
+        if (groups_contiguous) {
+            for (int32_t g = 0; g < R; ++g) gbase[g] = gcount[g] ? hgfirst[g] : 0;
+        } else {
+            TRY(fetch_clusters());
+            uint32_t run = 0;
+            for (int32_t g = 0; g < R; ++g) { gbase[g] = run; run += gcount[g]; }
+            std::vector<uint32_t> cur(gbase);
+            std::vector<int32_t> mem_list((size_t)n);
+            for (int64_t i = 0; i < n; ++i) mem_list[cur[hgroup[hcluster[i]]]++] = (int32_t)i;   // ascending inside each group
+            TRY(dev_alloc(c, &c->gmembers, (size_t)n));
+            HTRY(hipMemcpy(c->gmembers, mem_list.data(), sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+        }
+        for (int32_t g = 0; g < R; ++g) gomega[g] = s > 0 ? (float)(Mn * ((double)gcount[g] / (double)n) / (double)s) : 0.f;
+        TRY(dev_alloc(c, &c->gbase, (size_t)R));
+        TRY(dev_alloc(c, &c->gcount, (size_t)R));
+        TRY(dev_alloc(c, &c->gomega, (size_t)R));
+        HTRY(hipMemcpy(c->gbase, gbase.data(), sizeof(uint32_t) * (size_t)R, hipMemcpyHostToDevice));
+        HTRY(hipMemcpy(c->gcount, gcount.data(), sizeof(uint32_t) * (size_t)R, hipMemcpyHostToDevice));
+        HTRY(hipMemcpy(c->gomega, gomega.data(), sizeof(float) * (size_t)R, hipMemcpyHostToDevice));
+        TRY(dev_alloc(c, &c->A, (size_t)n));
+        TRY(dev_alloc(c, &c->B, (size_t)n));
+    }
+
+    // ---- state buffers
+    c->edge_grid = (blocks_for(n, kBlock / c->lpr) + 7u) & ~7u;
+    TRY(dev_alloc(c, &c->theta, (size_t)n));
+    TRY(dev_alloc(c, &c->g, (size_t)n));
+    TRY(dev_alloc(c, &c->mu, (size_t)R));
+    TRY(dev_alloc(c, &c->cinfo, (size_t)R));
+    TRY(dev_alloc(c, &c->loss_partial, (size_t)c->edge_grid));
+    TRY(dev_alloc(c, &c->loss_out, 1));
+    if (c->cfg.scatter_mode == NOMAD_SCATTER_DETERMINISTIC) {
+        TRY(dev_alloc(c, &c->rev, (size_t)E));
+        TRY(dev_alloc(c, &c->coef, (size_t)E));
+        TRY(dev_alloc(c, &c->ghead, (size_t)n));
+        TRY(dev_alloc(c, &c->gfix, (size_t)n * 2));
+        hipLaunchKernelGGL(k_build_rev, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->row_ptr, c->col, n, c->rev, c->flags);
+        hipLaunchKernelGGL(k_zero_u64, dim3(blocks_for(n * 2)), dim3(kBlock), 0, st, c->gfix, n * 2);
+        HTRY(hipMemcpyAsync(hflags, c->flags, sizeof(hflags), hipMemcpyDeviceToHost, st));
+        HTRY(hipStreamSynchronize(st));
+        if (hflags[kFlagAsymmetric]) {
+            free_graph(c);
+            return fail(c, NOMAD_E_BAD_GRAPH, "deterministic mode needs a symmetric graph without parallel edges");
+        }
+    }
+    HTRY(hipStreamSynchronize(st));
+    HTRY(hipGetLastError());
+#undef TRY
+#undef HTRY
+#undef HTRY2
+    c->has_graph = true;
+    c->err.clear();
+    return NOMAD_OK;
+}
+
+int nomad_set_embedding(nomad_ctx* c, const float* theta, int mem) {
+    int rc = check_ready(c, false);
+    if (rc) return rc;
+    if (!theta || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return fail(c, NOMAD_E_INVALID_ARG, "null pointer or bad mem");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(c->theta, theta, sizeof(float2) * (size_t)c->n, in_kind(mem)));
+    c->has_theta = true;
+    c->has_grad = false;
+    return NOMAD_OK;
+}
+
+int nomad_epoch(nomad_ctx* c, int32_t t) {
+    int rc = check_ready(c, true);
+    if (rc) return rc;
+    if (t < 0 || t >= c->cfg.n_epochs) return fail(c, NOMAD_E_INVALID_ARG, "epoch index %d outside 0..T-1", t);
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    const int64_t n = c->n;
+    run_means(c);
+    run_mean_field(c);
+    const EdgeArgs a = edge_args(c, (uint32_t)t);
+    if (c->cfg.scatter_mode == NOMAD_SCATTER_ATOMIC) {
+        { Timed tm(c, NOMAD_K_ZERO);
+          hipLaunchKernelGGL(k_zero_f2, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->g, n); }
+        { Timed tm(c, NOMAD_K_EDGES);
+          launch_edges<kModeAtomic>(c, a); }
+    } else {
+        { Timed tm(c, NOMAD_K_EDGES);
+          launch_edges<kModeDet>(c, a); }
+        { Timed tm(c, NOMAD_K_SCATTER);
+          hipLaunchKernelGGL((k_tail_pull<16>), dim3(c->edge_grid), dim3(kBlock), 0, c->stream, c->row_ptr, c->col, c->rev,
+                             c->coef, c->theta, c->ghead, c->gfix, c->g, n); }
+    }
+    const float eta = (float)((double)c->cfg.lr0 * (1.0 - (double)t / (double)c->cfg.n_epochs));
+    { Timed tm(c, NOMAD_K_UPDATE);
+      hipLaunchKernelGGL(k_update, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->theta, c->g, eta, n); }
+    HIP_TRY(c, hipGetLastError());
+    c->has_grad = true;
+    return NOMAD_OK;
+}
+
+int nomad_loss(nomad_ctx* c, int32_t t_sample, double* out_host) {
+    int rc = check_ready(c, true);
+    if (rc) return rc;
+    if (!out_host || t_sample < 0) return fail(c, NOMAD_E_INVALID_ARG, "null output or negative epoch index");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    run_means(c);
+    run_mean_field(c);
+    const EdgeArgs a = edge_args(c, (uint32_t)t_sample);
+    { Timed tm(c, NOMAD_K_LOSS);
+      launch_edges<kModeLoss>(c, a);
+      hipLaunchKernelGGL(k_loss_finish, dim3(1), dim3(kBlock), 0, c->stream, c->loss_partial, c->edge_grid, 1.0 / (double)c->n,
+                         c->loss_out); }
+    HIP_TRY(c, hipGetLastError());
+    return copy_out(c, out_host, c->loss_out, sizeof(double), NOMAD_HOST);
+}
+
+int nomad_get_embedding(nomad_ctx* c, float* out, int mem) {
+    int rc = check_ready(c, true);
+    if (rc) return rc;
+    if (!out || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return fail(c, NOMAD_E_INVALID_ARG, "null pointer or bad mem");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    return copy_out(c, out, c->theta, sizeof(float2) * (size_t)c->n, mem);
+}
+
+int nomad_get_gradient(nomad_ctx* c, float* out, int mem) {
+    int rc = check_ready(c, true);
+    if (rc) return rc;
+    if (!c->has_grad) return fail(c, NOMAD_E_ORDER, "no gradient yet: call nomad_epoch first");
+    if (!out || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return fail(c, NOMAD_E_INVALID_ARG, "null pointer or bad mem");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    return copy_out(c, out, c->g, sizeof(float2) * (size_t)c->n, mem);
+}
+
+int nomad_get_negatives(nomad_ctx* c, int32_t t, int64_t e_begin, int64_t e_end, int32_t* out, int mem) {
+    int rc = check_ready(c, false);
+    if (rc) return rc;
+    if (t < 0 || e_begin < 0 || e_end < e_begin || e_end > c->E || (mem != NOMAD_HOST && mem != NOMAD_DEVICE))
+        return fail(c, NOMAD_E_INVALID_ARG, "bad edge range or epoch index");
+    const int64_t cnt = e_end - e_begin;
+    const int s = c->cfg.n_neg;
+    if (cnt == 0 || s == 0) return NOMAD_OK;
+    if (!out) return fail(c, NOMAD_E_INVALID_ARG, "null output");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    int32_t* dst = out;
+    int32_t* tmp = nullptr;
+    if (mem == NOMAD_HOST) {
+        rc = dev_alloc(c, &tmp, (size_t)cnt * s);
+        if (rc) return rc;
+        dst = tmp;
+    }
+    const EdgeArgs a = edge_args(c, (uint32_t)t);
+    hipLaunchKernelGGL(k_negatives, dim3(blocks_for(cnt)), dim3(kBlock), 0, c->stream, a, e_begin, e_end, dst);
+    hipError_t e_ = hipStreamSynchronize(c->stream);
+    if (e_ == hipSuccess && tmp) e_ = hipMemcpy(out, tmp, sizeof(int32_t) * (size_t)cnt * s, hipMemcpyDeviceToHost);
+    dev_free(tmp);
+    if (e_ != hipSuccess) return fail(c, NOMAD_E_HIP, "negatives: %s", hipGetErrorString(e_));
+    return NOMAD_OK;
+}
+
+int nomad_get_means(nomad_ctx* c, float* mu, int64_t* counts, int mem) {
+    int rc = check_ready(c, true);
+    if (rc) return rc;
+    if ((!mu && !counts) || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return fail(c, NOMAD_E_INVALID_ARG, "null pointer or bad mem");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    run_means(c);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (mu) HIP_TRY(c, hipMemcpy(mu, c->mu, sizeof(float2) * (size_t)c->R, out_kind(mem)));
+    if (counts) {
+        std::vector<uint32_t> h32(c->R);
+        std::vector<int64_t> h64(c->R);
+        HIP_TRY(c, hipMemcpy(h32.data(), c->counts, sizeof(uint32_t) * (size_t)c->R, hipMemcpyDeviceToHost));
+        for (int32_t r = 0; r < c->R; ++r) h64[r] = (int64_t)h32[r];
+        HIP_TRY(c, hipMemcpy(counts, h64.data(), sizeof(int64_t) * (size_t)c->R,
+                             mem == NOMAD_DEVICE ? hipMemcpyHostToDevice : hipMemcpyHostToHost));
+    }
+    return NOMAD_OK;
+}
+
+int nomad_get_mean_field(nomad_ctx* c, float* A, float* B, int mem) {
+    int rc = check_ready(c, true);
+    if (rc) return rc;
+    if (!A || !B || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return fail(c, NOMAD_E_INVALID_ARG, "null pointer or bad mem");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    if (!c->grouped) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        if (mem == NOMAD_DEVICE) {
+            HIP_TRY(c, hipMemset(A, 0, sizeof(float) * (size_t)c->n));
+            HIP_TRY(c, hipMemset(B, 0, sizeof(float2) * (size_t)c->n));
+        } else {
+            memset(A, 0, sizeof(float) * (size_t)c->n);
+            memset(B, 0, sizeof(float2) * (size_t)c->n);
+        }
+        return NOMAD_OK;
+    }
+    run_means(c);
+    run_mean_field(c);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(A, c->A, sizeof(float) * (size_t)c->n, out_kind(mem)));
+    HIP_TRY(c, hipMemcpy(B, c->B, sizeof(float2) * (size_t)c->n, out_kind(mem)));
+    return NOMAD_OK;
+}
+
+int nomad_profile(nomad_ctx* c, int enable) {
+    if (!c) return NOMAD_E_INVALID_ARG;
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    clear_timers(c);
+    c->profiling = enable != 0;
+    return NOMAD_OK;
+}
+
+int nomad_profile_read(nomad_ctx* c, int kind, double* total_ms, int64_t* launches) {
+    if (!c || kind < 0 || kind >= NOMAD_K_COUNT || !total_ms || !launches) return NOMAD_E_INVALID_ARG;
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const KernelTimer& t = c->timers[kind];
+    double tot = 0.0;
+    const size_t cnt = std::min(t.begin.size(), t.end.size());
+    for (size_t k = 0; k < cnt; ++k) {
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, t.begin[k], t.end[k]));
+        tot += (double)ms;
+    }
+    *total_ms = tot;
+    *launches = (int64_t)cnt;
+    return NOMAD_OK;
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

@@ -1,0 +1,76 @@
+"""The C-ABI library loads and exports every symbol the header declares (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2505_15511_amd import _build, binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if _build.is_stale():
+        _build.build_library()
+    return binding.load_library()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "nomad.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nomad_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_entry_point_is_exported(lib):
+    names = _declared()
+    assert {"nomad_create", "nomad_set_graph", "nomad_epoch", "nomad_loss", "nomad_get_embedding"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_only_the_abi_is_exported():
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", _build.LIB_PATH], capture_output=True, text=True).stdout
+    syms = [l.split()[-1] for l in out.splitlines() if " T " in l]
+    assert syms and all(s.startswith("nomad_") for s in syms), syms
+
+
+def test_config_struct_layout_matches_header():
+    # uint32 | int64 | int32 int32 | float int32 | float (pad) | uint64 | int32 int32 | int32 (pad) | void*
+    assert C.sizeof(binding.NomadConfig) == 72
+    assert binding.NomadConfig.seed.offset == 40 and binding.NomadConfig.stream.offset == 64
+
+
+def test_argument_errors_before_any_device_work(lib):
+    ctx = C.c_void_p()
+    assert lib.nomad_create(None, C.byref(ctx)) == -1
+    cfg = binding.NomadConfig(C.sizeof(binding.NomadConfig), 10, 2, 5, 0.0, 10, 1.0, 1, 0, 1, 0, None)
+    assert lib.nomad_create(C.byref(cfg), None) == -1
+    cfg.struct_size = 8
+    assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1
+    cfg.struct_size = C.sizeof(binding.NomadConfig)
+    for field, bad in (("n_points", 0), ("n_clusters", 0), ("n_neg", 17), ("n_neg", -1), ("n_epochs", 0),
+                       ("scatter_mode", 2), ("batches_per_epoch", 2), ("lr0", float("nan")), ("n_clusters", 11)):
+        good = getattr(cfg, field)
+        setattr(cfg, field, bad)
+        assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1, field
+        setattr(cfg, field, good)
+    cfg.n_points = 2 ** 31
+    assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -4
+    assert not ctx.value
+    # null context is rejected everywhere, destroy(NULL) is a no-op
+    lib.nomad_destroy(None)
+    assert lib.nomad_epoch(None, 0) == -1
+    assert lib.nomad_set_graph(None, None, None, None, None, None, 0) == -1
+    assert lib.nomad_num_edges(None) == 0
+    assert lib.nomad_last_error(None) == b"null context"
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(_build, "LIB_PATH", "/nonexistent/libnomad.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.load_library()

@@ -1,0 +1,332 @@
+"""HIP path vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import ctypes as C
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import c_oracle
+from paper_2505_15511_amd import Nomad, NomadError, SCATTER_ATOMIC, SCATTER_DETERMINISTIC, workloads
+
+pytestmark = pytest.mark.gpu
+
+MODES = [pytest.param(SCATTER_DETERMINISTIC, id="det"), pytest.param(SCATTER_ATOMIC, id="atomic")]
+GRAD_TOL = 1e-5   # max_i |g_i - g^_i|_inf / max_i |g^_i|_inf, the bar named for the deterministic path
+LOSS_TOL = 1e-5   # relative
+
+
+def grad_err(g, ref):
+    return np.abs(np.asarray(g, dtype=np.float64) - ref).max() / np.abs(ref).max()
+
+
+def note(msg):
+    print(msg, flush=True)
+
+
+_cache = {}
+
+
+def workload(cfg, scale=1.0, **kw):
+    key = (cfg, scale, tuple(sorted(kw.items())))
+    if key not in _cache:
+        _cache[key] = workloads.make_config(cfg, scale=scale, **kw)
+    return _cache[key]
+
+
+def small_random(seed, n=3000, R=12, groups=True, weights=True, contiguous=False, s=3, M=4.0, T=20):
+    """Random symmetric graph with interleaved (non-contiguous) clusters, weights and groups."""
+    rng = np.random.default_rng(seed)
+    g = workloads.planted_knn_graph(n, R, 6, 0.05, seed)
+    cluster_of = g["cluster_of"].numpy().copy()
+    row_ptr, col = g["row_ptr"].numpy(), g["col_idx"].numpy()
+    if not contiguous:
+        cluster_of = rng.permutation(cluster_of)
+    w = rng.uniform(0.2, 2.0, len(col)).astype(np.float32) if weights else None
+    grp = None
+    if groups:
+        grp = rng.integers(0, 4, R).astype(np.int32)
+        grp[:4] = [0, 1, 2, 3]
+    theta0 = (rng.normal(size=(n, 2)) * 0.5).astype(np.float32)
+    return dict(n=n, row_ptr=row_ptr, col_idx=col, weights=w, cluster_of=cluster_of.astype(np.int32), n_clusters=R,
+                cluster_group=grp, theta0=theta0, n_neg=s, noise_count=M, n_epochs=T, lr0=0.5, seed=seed * 31 + 7)
+
+
+def make_nomad(d, mode):
+    nm = Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode)
+    nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
+    nm.set_embedding(d["theta0"])
+    return nm
+
+
+# ------------------------------------------------------------------ negatives: bit exact
+@pytest.mark.parametrize("case", ["config1", "config3@0.05", "config5@1e-3", "random-groups"])
+def test_negatives_bit_exact(case):
+    note(f"negatives {case}")
+    if case == "random-groups":
+        d = small_random(3)
+    else:
+        cfg, _, sc = case.partition("@")
+        d = workload(int(cfg[-1]), float(sc) if sc else 1.0).numpy()
+    O = c_oracle.COracle(**d)
+    with make_nomad(d, SCATTER_ATOMIC) as nm:
+        assert nm.num_edges() == O.n_edges
+        for t in (0, 7):
+            assert np.array_equal(nm.get_negatives(t), O.negatives(t))
+        E = O.n_edges
+        assert np.array_equal(nm.get_negatives(3, E // 3, E // 3 + 1000), O.negatives(3, E // 3, E // 3 + 1000))
+        assert nm.get_negatives(3, 5, 5).shape == (0, d["n_neg"])
+
+
+# ------------------------------------------------------------------ cluster statistics
+@pytest.mark.parametrize("case", ["config1", "config3@0.05", "random-groups"])
+def test_cluster_counts_exact_and_means_close(case):
+    note(f"means {case}")
+    d = small_random(4) if case == "random-groups" else workload(int(case[6]), float(case.partition("@")[2] or 1)).numpy()
+    rng = np.random.default_rng(1)
+    theta = (rng.normal(size=(d["n"], 2)) * 3 + [10.0, -4.0]).astype(np.float32)
+    O = c_oracle.COracle(**d)
+    counts, _, mu = O.cluster_stats(theta)
+    with make_nomad(d, SCATTER_ATOMIC) as nm:
+        nm.set_embedding(theta)
+        gmu, gcounts = nm.get_means()
+        assert np.array_equal(gcounts, counts)
+        assert np.abs(gmu - mu).max() < 1e-6 * max(1.0, np.abs(mu).max())
+        # set/get round trip is the identity
+        assert np.array_equal(nm.get_embedding(), theta)
+
+
+def test_mean_field_sums():
+    for d in (small_random(5), workload(5, 1e-3).numpy()):
+        note(f"mean field n={d['n']}")
+        O = c_oracle.COracle(**d)
+        rng = np.random.default_rng(2)
+        theta = (rng.normal(size=(d["n"], 2)) * 2).astype(np.float32)
+        _, _, A, B = O.loss_and_grad(theta, 0, mean_field=True)
+        with make_nomad(d, SCATTER_DETERMINISTIC) as nm:
+            nm.set_embedding(theta)
+            gA, gB = nm.get_mean_field()
+        assert np.abs(gA - A).max() < 2e-6 * np.abs(A).max()
+        assert np.abs(gB - B).max() < 2e-6 * np.abs(B).max()
+
+
+# ------------------------------------------------------------------ gradient and loss
+CASES = ["config1", "config2@0.1", "config3@0.05", "config5@1e-3", "random-groups", "random-plain", "random-contig"]
+
+
+def _case(case):
+    if case == "random-groups":
+        return small_random(6)
+    if case == "random-plain":
+        return small_random(7, groups=False, weights=False, s=5, M=5.0)
+    if case == "random-contig":
+        return small_random(8, contiguous=True)
+    cfg, _, sc = case.partition("@")
+    return workload(int(cfg[-1]), float(sc) if sc else 1.0).numpy()
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("case", CASES)
+def test_gradient_and_loss_after_one_epoch(case, mode):
+    note(f"gradient {case} mode={mode}")
+    d = _case(case)
+    O = c_oracle.COracle(**d)
+    th1, g_ref, _ = O.epoch(d["theta0"], 0)
+    L_ref, _ = O.loss_and_grad(th1, 1, want_grad=False)
+    with make_nomad(d, mode) as nm:
+        nm.epoch(0)
+        g = nm.get_gradient()
+        err = grad_err(g, g_ref)
+        L = nm.loss(1)
+        th = nm.get_embedding()
+    note(f"  grad err {err:.2e}  loss {L:.8f} vs {L_ref:.8f}")
+    assert err < GRAD_TOL
+    assert abs(L - L_ref) < LOSS_TOL * abs(L_ref)
+    assert np.abs(th - th1).max() < 1e-5 * max(1.0, np.abs(th1).max())
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("case", ["config1", "config3@0.05", "random-groups"])
+def test_mid_run_gradient_restarted_from_the_gpu_embedding(case, mode):
+    """Run some epochs on the GPU, then hand its embedding to the oracle and compare the next gradient."""
+    note(f"mid-run {case} mode={mode}")
+    d = _case(case)
+    O = c_oracle.COracle(**d)
+    t_mid = min(10, d["n_epochs"] - 2)
+    with make_nomad(d, mode) as nm:
+        for t in range(t_mid):
+            nm.epoch(t)
+        theta = nm.get_embedding()
+        nm.epoch(t_mid)
+        g = nm.get_gradient()
+    _, g_ref = O.loss_and_grad(theta, t_mid)
+    err = grad_err(g, g_ref)
+    note(f"  grad err {err:.2e}")
+    assert err < GRAD_TOL
+    assert np.abs(theta).max() > 0.05      # the embedding has actually moved away from the init
+
+
+# ------------------------------------------------------------------ the two scatter paths
+def test_deterministic_path_is_bit_reproducible_and_atomic_path_agrees():
+    d = workload(3, 0.05).numpy()
+    runs = []
+    for mode in (SCATTER_DETERMINISTIC, SCATTER_DETERMINISTIC, SCATTER_ATOMIC):
+        with make_nomad(d, mode) as nm:
+            for t in range(5):
+                nm.epoch(t)
+            runs.append((nm.get_gradient(), nm.get_embedding()))
+    assert np.array_equal(runs[0][0], runs[1][0]) and np.array_equal(runs[0][1], runs[1][1])
+    scale = np.abs(runs[0][0]).max()
+    assert np.abs(runs[0][0] - runs[2][0]).max() < 2e-5 * scale      # different summation order only
+    assert np.abs(runs[0][1] - runs[2][1]).max() < 1e-4
+
+
+def test_resume_from_embedding_and_epoch_index_is_bit_exact():
+    d = workload(1).numpy()
+    with make_nomad(d, SCATTER_DETERMINISTIC) as nm:
+        for t in range(10):
+            nm.epoch(t)
+        straight = nm.get_embedding()
+    with make_nomad(d, SCATTER_DETERMINISTIC) as nm:
+        for t in range(5):
+            nm.epoch(t)
+        half = nm.get_embedding()
+    with make_nomad(d, SCATTER_DETERMINISTIC) as nm:
+        nm.set_embedding(half)
+        for t in range(5, 10):
+            nm.epoch(t)
+        assert np.array_equal(nm.get_embedding(), straight)
+
+
+# ------------------------------------------------------------------ degenerate and edge cases
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("s", [0, 1, 4, 8, 9, 16])
+def test_negative_counts_through_both_kernel_variants(s, mode):
+    d = small_random(10 + s, n=1500, s=s, M=float(max(s, 2)))
+    O = c_oracle.COracle(**d)
+    _, g_ref, _ = O.epoch(d["theta0"], 0)
+    with make_nomad(d, mode) as nm:
+        if s:
+            assert np.array_equal(nm.get_negatives(0), O.negatives(0))
+        nm.epoch(0)
+        assert grad_err(nm.get_gradient(), g_ref) < GRAD_TOL
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_empty_rows_empty_cluster_and_tiny_graphs(mode):
+    # 6 points; points 4, 5 isolated; cluster 2 empty
+    row_ptr = np.array([0, 2, 4, 6, 8, 8, 8], dtype=np.int32)
+    col = np.array([1, 3, 0, 2, 1, 3, 0, 2], dtype=np.int32)
+    d = dict(n=6, row_ptr=row_ptr, col_idx=col, weights=None, cluster_of=np.array([0, 0, 1, 1, 3, 3], dtype=np.int32),
+             n_clusters=4, cluster_group=np.array([0, 0, 1, 1], dtype=np.int32), n_neg=5, noise_count=5.0, n_epochs=3,
+             lr0=0.3, seed=5, theta0=np.array([[0, 0], [1, 0], [1, 1], [0, 1], [3, 3], [-2, 1]], dtype=np.float32))
+    O = c_oracle.COracle(**d)
+    th1, g_ref, _ = O.epoch(d["theta0"], 0)
+    with make_nomad(d, mode) as nm:
+        assert np.array_equal(nm.get_negatives(0), O.negatives(0))
+        mu, counts = nm.get_means()
+        assert counts.tolist() == [2, 2, 0, 2] and np.all(mu[2] == 0)
+        nm.epoch(0)
+        assert grad_err(nm.get_gradient(), g_ref) < GRAD_TOL
+        assert abs(nm.loss(1) - O.loss_and_grad(th1, 1, want_grad=False)[0]) < 1e-5
+    # a single point with no edge: the loss of an empty graph is 0 and nothing moves
+    with Nomad(1, 1, 5, 5.0, 2, 1.0, 1, mode) as nm:
+        nm.set_graph(np.zeros(2, np.int32), np.zeros(0, np.int32), None, np.zeros(1, np.int32))
+        nm.set_embedding(np.array([[0.5, -1.0]], np.float32))
+        nm.epoch(0)
+        assert nm.loss(0) == 0.0 and np.array_equal(nm.get_embedding(), [[0.5, -1.0]])
+        assert np.all(nm.get_gradient() == 0)
+
+
+def test_coincident_points_closed_form():
+    """All rows equal: every q is 1, the loss is log(1+|M|) and no force acts (closed form, no oracle)."""
+    d = small_random(30, groups=False, weights=False, s=5, M=5.0)
+    d["theta0"] = np.full((d["n"], 2), 0.25, dtype=np.float32)
+    with make_nomad(d, SCATTER_DETERMINISTIC) as nm:
+        assert abs(nm.loss(0) - math.log(6.0)) < 1e-6
+        nm.epoch(0)
+        assert np.abs(nm.get_gradient()).max() < 1e-7
+
+
+def test_forces_cancel_without_approximated_cells():
+    d = workload(3, 0.05).numpy()
+    with make_nomad(d, SCATTER_DETERMINISTIC) as nm:
+        for t in range(3):
+            nm.epoch(t)
+        g = nm.get_gradient().astype(np.float64)
+    assert np.abs(g.sum(0)).max() < 1e-4 * np.abs(g).sum(0).max()
+
+
+def test_device_buffers_in_and_out():
+    w = workload(3, 0.05)
+    dev = torch.device("cuda:0")
+    with Nomad(w.n, w.n_clusters, w.n_neg, w.noise_count, w.n_epochs, w.lr0, w.seed, SCATTER_DETERMINISTIC) as nm:
+        nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None, w.cluster_of.to(dev), None)
+        nm.set_embedding(w.theta0.to(dev))
+        nm.epoch(0)
+        g_dev = nm.get_gradient(device=True)
+        th_dev = nm.get_embedding(device=True)
+        neg_dev = nm.get_negatives(0, 10, 500, device=True)
+        assert g_dev.is_cuda and th_dev.is_cuda
+        assert np.array_equal(g_dev.cpu().numpy(), nm.get_gradient())
+        assert np.array_equal(th_dev.cpu().numpy(), nm.get_embedding())
+        assert np.array_equal(neg_dev.cpu().numpy(), nm.get_negatives(0, 10, 500))
+
+
+# ------------------------------------------------------------------ error paths (forced from the host)
+def test_errors_are_codes_not_crashes():
+    d = small_random(40, n=500)
+    nm = Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], 1, SCATTER_DETERMINISTIC)
+    with pytest.raises(NomadError, match="ORDER"):
+        nm.epoch(0)
+    with pytest.raises(NomadError, match="ORDER"):
+        nm.set_embedding(d["theta0"])
+
+    def bad(**over):
+        a = dict(row_ptr=d["row_ptr"], col_idx=d["col_idx"], weights=d["weights"], cluster_of=d["cluster_of"],
+                 cluster_group=d["cluster_group"])
+        a.update(over)
+        with pytest.raises(NomadError, match="BAD_GRAPH"):
+            nm.set_graph(a["row_ptr"], a["col_idx"], a["weights"], a["cluster_of"], a["cluster_group"])
+
+    rp = d["row_ptr"].copy(); rp[5], rp[6] = rp[6], rp[5] - 1
+    bad(row_ptr=rp)
+    rp = d["row_ptr"].copy(); rp[0] = 1
+    bad(row_ptr=rp)
+    col = d["col_idx"].copy(); col[3] = d["n"]
+    bad(col_idx=col)
+    col = d["col_idx"].copy(); col[0] = 0          # row 0 -> self loop
+    bad(col_idx=col)
+    w = d["weights"].copy(); w[10] = -1.0
+    bad(weights=w)
+    w = d["weights"].copy(); w[d["row_ptr"][3]:d["row_ptr"][4]] = 0.0
+    bad(weights=w)
+    cl = d["cluster_of"].copy(); cl[7] = d["n_clusters"]
+    bad(cluster_of=cl)
+    grp = d["cluster_group"].copy(); grp[1] = -2
+    bad(cluster_group=grp)
+    # asymmetric graph: fine for the atomic path, refused by the deterministic one
+    col = d["col_idx"].copy()
+    a0 = d["row_ptr"][0]
+    others = np.setdiff1d(np.arange(1, d["n"]), col[a0:d["row_ptr"][1]])
+    col[a0] = others[-1]
+    bad(col_idx=col)
+    with Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], 1, SCATTER_ATOMIC) as nm2:
+        nm2.set_graph(d["row_ptr"], col, d["weights"], d["cluster_of"], d["cluster_group"])
+    # after a failed set_graph the context has no graph
+    with pytest.raises(NomadError, match="ORDER"):
+        nm.epoch(0)
+    nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
+    with pytest.raises(NomadError, match="ORDER"):
+        nm.epoch(0)                                 # still no embedding
+    nm.set_embedding(d["theta0"])
+    with pytest.raises(NomadError, match="ORDER"):
+        nm.get_gradient()
+    with pytest.raises(NomadError, match="INVALID_ARG"):
+        nm.epoch(d["n_epochs"])
+    with pytest.raises(NomadError, match="INVALID_ARG"):
+        nm.epoch(-1)
+    with pytest.raises(NomadError, match="INVALID_ARG"):
+        nm.get_negatives(0, 5, nm.num_edges() + 1)
+    nm.epoch(0)
+    nm.close()
