@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the NOMAD epoch path on one MI355X.
+
+A step is one nomad_epoch (cell means, [mean-field sums], edge pass, gradient scatter, SGD step)
+over a synthetic kNN graph that is already resident in HBM.  Default workload: benchmark
+configuration 4 (n = 10 M points, ~299 M directed edges, 5 negatives per edge).
+
+Prints ONE JSON line:  metric = positive+negative edge updates per second, E * (1 + s) / t_epoch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+FP32_VALU_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector rate
+
+
+def algorithmic_bytes(kernel, n, E, s, R, grouped, weighted, deterministic):
+    """Bytes the method has to move per launch of each kernel, every gather / scatter counted at
+    its useful size (8 B per embedding row, 4 B per index), an accumulation counted once."""
+    w = 4 if weighted else 0
+    mf = 12 if grouped else 0                    # A_i, B_i
+    if kernel == "edges":
+        per_edge = 4 + w + 8 + 8 * s             # col_idx, [p_e], theta_j, theta_m
+        per_edge += 8 * s                        # negatives' gradient contributions
+        per_edge += 4 if deterministic else 8    # a_e written / tail gradient accumulated
+        return per_edge * E + (4 + 8 + 8 + mf) * n   # row_ptr, theta_i, head gradient, [A,B]
+    if kernel == "scatter":                      # deterministic tail pull + combine
+        return (4 + 4 + 4 + 8) * E + (4 + 8 + 8 + 8 + 8) * n
+    if kernel == "update":
+        return 24 * n
+    if kernel == "means":
+        return 8 * n
+    if kernel == "zero":
+        return 8 * n
+    if kernel == "mean_field":
+        return (8 + 4 + 12) * n
+    if kernel == "loss":
+        return (4 + w + 8 + 8 * s) * E + (4 + 8 + mf) * n
+    raise KeyError(kernel)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1-5")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the configuration (testing only)")
+    ap.add_argument("--mode", choices=["det", "atomic"], default="det")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--groups", type=int, default=None, help="deal the clusters into this many groups")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build covers one GPU's share of the path; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2505_15511_amd import Nomad, SCATTER_ATOMIC, SCATTER_DETERMINISTIC, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda"
+    t0 = time.time()
+    w = workloads.make_config(args.config, scale=args.scale, device=dev if args.config >= 3 else "cpu",
+                              n_groups=args.groups)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    n, E, s, R = w.n, w.n_edges, w.n_neg, w.n_clusters
+    steps, warmup = args.steps, args.warmup
+    if warmup + steps > w.n_epochs:
+        steps = max(1, w.n_epochs - warmup)
+    mode = SCATTER_DETERMINISTIC if args.mode == "det" else SCATTER_ATOMIC
+    nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode)
+    t0 = time.time()
+    nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None, w.cluster_of.to(dev),
+                 None if w.cluster_group is None else w.cluster_group.to(dev))
+    nm.set_embedding(w.theta0.to(dev))
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    for t in range(warmup):
+        nm.epoch(t)
+    torch.cuda.synchronize()
+    nm.profile(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(warmup, warmup + steps):
+        nm.epoch(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = nm.profile_read()
+    nm.profile(False)
+    loss = nm.loss(warmup + steps)
+    ms_per_step = 1e3 * elapsed / steps
+    grouped = w.cluster_group is not None
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        if cnt:
+            ab = algorithmic_bytes(name, n, E, s, R, grouped, False, mode == SCATTER_DETERMINISTIC)
+            kernels[name] = dict(ms=ms / cnt, launches=cnt, algorithmic_gb=ab / 1e9, gbs=ab / (ms / cnt) / 1e6)
+    dom = max(kernels, key=lambda k: kernels[k]["ms"])
+    if dom == "mean_field":
+        # n * |R~| kernel evaluations of ~12 flops each: plain-ALU bound, not HBM bound
+        evals = float(n) * float(R)
+        flops = 12.0 * evals
+        roofline = dict(bound="alu", kernel=dom, achieved=flops / (kernels[dom]["ms"] * 1e-3) / 1e12,
+                        peak=FP32_VALU_PEAK_TFLOPS, unit="TFLOP/s", traffic=None)
+    else:
+        roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s", traffic=None)
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, False, mode == SCATTER_DETERMINISTIC) for k in kernels
+                      if k != "mean_field")
+    out = {
+        "metric": "positive+negative edge updates/sec per epoch at 1 GPU",
+        "value": E * (1 + s) / (elapsed / steps),
+        "unit": "updates/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: n={n}, E={E} directed edges, |R|={R} clusters, s={s} negatives/edge, "
+                               f"|M|={w.noise_count:g}, {'grouped (mean-field)' if grouped else 'no approximated cells'}",
+                   "scatter_mode": args.mode},
+        "edges_per_sec": E / (elapsed / steps),
+        "epoch_model_gb": epoch_bytes / 1e9,
+        "epoch_hbm_frac_model": epoch_bytes / (elapsed / steps) / 1e9 / HBM_PEAK_GBS,
+        "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
+        "loss_after": loss,
+        "setup_s": round(setup_s, 3), "generate_s": round(gen_s, 3),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import c_oracle
+        d = w.numpy()
+        O = c_oracle.COracle(**d)
+        if grouped and float(n) * R > 2e10:
+            # the full mean-field sum is out of reach on the host: time a sample of heads' gradients
+            rng = np.random.default_rng(0)
+            pts = rng.choice(n, size=max(1, n // 4096), replace=False)
+            t0 = time.perf_counter()
+            O.grad_at(d["theta0"], 0, pts)
+            dt = time.perf_counter() - t0
+            cpu = dict(value=None, unit="updates/s", cores=O.threads, kind="oracle",
+                       sample=f"gradient rows of {len(pts)} sampled points (full sampler sweep + their edges): {dt:.1f} s; "
+                              "not extrapolated")
+        else:
+            t0 = time.perf_counter()
+            O.loss_and_grad(d["theta0"], 0)
+            dt = time.perf_counter() - t0
+            cpu = dict(value=E * (1 + s) / dt, unit="updates/s", cores=O.threads, kind="oracle",
+                       sample=f"one full epoch's loss+gradient of {w.name} ({E} edges) in {dt:.2f} s")
+        out["cpu_baseline"] = cpu
+    nm.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
