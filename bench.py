@@ -28,9 +28,13 @@ def algorithmic_bytes(kernel, n, E, s, R, grouped, weighted, deterministic):
     mf = 12 if grouped else 0                    # A_i, B_i
     if kernel == "edges":
         per_edge = 4 + w + 8 + 8 * s             # col_idx, [p_e], theta_j, theta_m
-        per_edge += 8 * s                        # negatives' gradient contributions
+        per_edge += 8 * s                        # negatives' gradient contributions (handed on as records in binned mode)
         per_edge += 4 if deterministic else 8    # a_e written / tail gradient accumulated
         return per_edge * E + (4 + 8 + 8 + mf) * n   # row_ptr, theta_i, head gradient, [A,B]
+    if kernel == "tiles":                        # accumulation of the binned negatives: implementation traffic,
+        return 8 * n                             # algorithmically only the per-point result
+    if kernel == "bins":
+        return 0
     if kernel == "scatter":                      # deterministic tail pull + combine
         return (4 + 4 + 4 + 8) * E + (4 + 8 + 8 + 8 + 8) * n
     if kernel == "update":

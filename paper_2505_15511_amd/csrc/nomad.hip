@@ -46,6 +46,15 @@ struct nomad_ctx {
     float4* cinfo = nullptr;
     float *A = nullptr, *coef = nullptr;
     unsigned long long* gfix = nullptr;
+    // binned deterministic scatter
+    bool binned = false;
+    int n_wg = 0;
+    uint32_t n_bins = 0, max_chunks = 0;
+    uint32_t *pool = nullptr, *chunk_bin = nullptr, *chunk_fill = nullptr, *pool_next = nullptr, *bin_count = nullptr,
+             *bin_start = nullptr, *bin_cursor = nullptr, *bin_chunks = nullptr;
+    int32_t* wg_row_begin = nullptr;
+    float2* gneg = nullptr;
+    int* overflow = nullptr;
     double *loss_partial = nullptr, *loss_out = nullptr;
     uint32_t edge_grid = 0;
     int* flags = nullptr;
@@ -96,6 +105,10 @@ void free_graph(nomad_ctx* c) {
     dev_free(c->theta); dev_free(c->g); dev_free(c->ghead); dev_free(c->mu); dev_free(c->B); dev_free(c->cinfo);
     dev_free(c->A); dev_free(c->coef); dev_free(c->gfix); dev_free(c->loss_partial); dev_free(c->loss_out);
     dev_free(c->flags);
+    dev_free(c->pool); dev_free(c->chunk_bin); dev_free(c->chunk_fill); dev_free(c->pool_next); dev_free(c->bin_count);
+    dev_free(c->bin_start); dev_free(c->bin_cursor); dev_free(c->bin_chunks); dev_free(c->wg_row_begin); dev_free(c->gneg);
+    dev_free(c->overflow);
+    c->binned = false;
     c->has_graph = c->has_theta = c->has_grad = false;
     c->E = 0;
 }
@@ -159,6 +172,46 @@ void launch_edges(nomad_ctx* c, const EdgeArgs& a) {
     launch_edges_s<MODE, 16>(c, a);
 }
 
+BinArgs bin_args(nomad_ctx* c) {
+    BinArgs q{};
+    q.pool = c->pool; q.chunk_bin = c->chunk_bin; q.chunk_fill = c->chunk_fill; q.pool_next = c->pool_next;
+    q.max_chunks = c->max_chunks; q.n_bins = c->n_bins; q.wg_row_begin = c->wg_row_begin; q.overflow = c->overflow;
+    return q;
+}
+
+size_t binned_lds_bytes(uint32_t n_bins) { return (size_t)n_bins * 4 * sizeof(uint32_t); }
+
+template <int S>
+int prepare_binned_kernel(nomad_ctx* c) {
+    HIP_TRY(c, hipFuncSetAttribute((const void*)k_edges_binned<S>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)binned_lds_bytes(c->n_bins)));
+    return NOMAD_OK;
+}
+
+int prepare_binned(nomad_ctx* c) {
+    HIP_TRY(c, hipFuncSetAttribute((const void*)k_tile_accumulate, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)(sizeof(unsigned long long) * 2 * kTile)));
+    switch (c->cfg.n_neg) {
+        case 1: return prepare_binned_kernel<1>(c); case 2: return prepare_binned_kernel<2>(c);
+        case 3: return prepare_binned_kernel<3>(c); case 4: return prepare_binned_kernel<4>(c);
+        case 5: return prepare_binned_kernel<5>(c); case 6: return prepare_binned_kernel<6>(c);
+        case 7: return prepare_binned_kernel<7>(c); case 8: return prepare_binned_kernel<8>(c);
+    }
+    return NOMAD_E_INVALID_ARG;
+}
+
+void launch_edges_binned(nomad_ctx* c, const EdgeArgs& a) {
+    const BinArgs q = bin_args(c);
+    const dim3 grid(c->n_wg), block(kBinBlock);
+    const size_t lds = binned_lds_bytes(c->n_bins);
+    switch (c->cfg.n_neg) {
+#define NOMAD_CASE(S) case S: hipLaunchKernelGGL((k_edges_binned<S>), grid, block, lds, c->stream, a, q); break;
+        NOMAD_CASE(1) NOMAD_CASE(2) NOMAD_CASE(3) NOMAD_CASE(4) NOMAD_CASE(5) NOMAD_CASE(6) NOMAD_CASE(7) NOMAD_CASE(8)
+#undef NOMAD_CASE
+        default: break;
+    }
+}
+
 // cell means of the current embedding -> mu, cinfo
 int run_means(nomad_ctx* c) {
     Timed tm(c, NOMAD_K_MEANS);
@@ -188,6 +241,11 @@ int check_ready(nomad_ctx* c, bool need_theta) {
 
 int copy_out(nomad_ctx* c, void* dst, const void* src, size_t bytes, int mem) {
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->overflow) {
+        int ov = 0;
+        HIP_TRY(c, hipMemcpy(&ov, c->overflow, sizeof(int), hipMemcpyDeviceToHost));
+        if (ov) return fail(c, NOMAD_E_HIP, "internal error: record pool bound exceeded");
+    }
     HIP_TRY(c, hipMemcpy(dst, src, bytes, out_kind(mem)));
     return NOMAD_OK;
 }
@@ -410,6 +468,39 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         TRY(dev_alloc(c, &c->coef, (size_t)E));
         TRY(dev_alloc(c, &c->ghead, (size_t)n));
         TRY(dev_alloc(c, &c->gfix, (size_t)n * 2));
+        // Binned scatter of the negatives: needs a compile-time s and a tile table that fits LDS; if
+        // its record pool cannot be allocated the fixed-point global atomics remain as the fallback.
+        const uint32_t n_bins = (uint32_t)((n + kTile - 1) / kTile);
+        if (s >= 1 && s <= 8 && E > 0 && binned_lds_bytes(n_bins) <= 144 * 1024) {
+            hipDeviceProp_t prop;
+            HTRY(hipGetDeviceProperties(&prop, c->cfg.device));
+            const int per_cu = binned_lds_bytes(n_bins) <= 72 * 1024 ? 2 : 1;
+            c->n_wg = std::max(1, prop.multiProcessorCount) * per_cu;
+            c->n_bins = n_bins;
+            const uint64_t want = (uint64_t)E * (uint64_t)s / kChunk + (uint64_t)c->n_wg * n_bins + 1;
+            if (want < (1ull << 31)) {
+                c->max_chunks = (uint32_t)want;
+                bool ok = dev_alloc(c, &c->pool, (size_t)c->max_chunks * kChunk * 3) == NOMAD_OK &&
+                          dev_alloc(c, &c->chunk_bin, c->max_chunks) == NOMAD_OK && dev_alloc(c, &c->chunk_fill, c->max_chunks) == NOMAD_OK &&
+                          dev_alloc(c, &c->bin_chunks, c->max_chunks) == NOMAD_OK && dev_alloc(c, &c->pool_next, 1) == NOMAD_OK &&
+                          dev_alloc(c, &c->bin_count, n_bins) == NOMAD_OK && dev_alloc(c, &c->bin_start, (size_t)n_bins + 1) == NOMAD_OK &&
+                          dev_alloc(c, &c->bin_cursor, n_bins) == NOMAD_OK && dev_alloc(c, &c->wg_row_begin, (size_t)c->n_wg + 1) == NOMAD_OK &&
+                          dev_alloc(c, &c->gneg, (size_t)n) == NOMAD_OK && dev_alloc(c, &c->overflow, 1) == NOMAD_OK;
+                if (ok) ok = prepare_binned(c) == NOMAD_OK;
+                if (ok) {
+                    HTRY(hipMemsetAsync(c->overflow, 0, sizeof(int), st));
+                    hipLaunchKernelGGL(k_wg_rows, dim3(blocks_for(c->n_wg + 1)), dim3(kBlock), 0, st, c->row_ptr, n, E, c->n_wg,
+                                       c->wg_row_begin);
+                    c->binned = true;
+                } else {
+                    (void)hipGetLastError();
+                    dev_free(c->pool); dev_free(c->chunk_bin); dev_free(c->chunk_fill); dev_free(c->bin_chunks); dev_free(c->pool_next);
+                    dev_free(c->bin_count); dev_free(c->bin_start); dev_free(c->bin_cursor); dev_free(c->wg_row_begin); dev_free(c->gneg);
+                    dev_free(c->overflow);
+                    c->err.clear();
+                }
+            }
+        }
         hipLaunchKernelGGL(k_build_rev, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->row_ptr, c->col, n, c->rev, c->flags);
         hipLaunchKernelGGL(k_zero_u64, dim3(blocks_for(n * 2)), dim3(kBlock), 0, st, c->gfix, n * 2);
         HTRY(hipMemcpyAsync(hflags, c->flags, sizeof(hflags), hipMemcpyDeviceToHost, st));
@@ -455,12 +546,28 @@ int nomad_epoch(nomad_ctx* c, int32_t t) {
           hipLaunchKernelGGL(k_zero_f2, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->g, n); }
         { Timed tm(c, NOMAD_K_EDGES);
           launch_edges<kModeAtomic>(c, a); }
+    } else if (c->binned) {
+        { Timed tm(c, NOMAD_K_EDGES);
+          hipLaunchKernelGGL(k_bin_reset, dim3(blocks_for(c->n_bins)), dim3(kBlock), 0, c->stream, c->bin_count, c->n_bins, c->pool_next);
+          launch_edges_binned(c, a); }
+        { Timed tm(c, NOMAD_K_BINS);
+          const dim3 cg(blocks_for(c->max_chunks));
+          hipLaunchKernelGGL(k_chunk_census, cg, dim3(kBlock), 0, c->stream, c->chunk_bin, c->pool_next, c->max_chunks, c->bin_count);
+          hipLaunchKernelGGL(k_bin_scan, dim3(1), dim3(kBinBlock), 0, c->stream, c->bin_count, c->n_bins, c->bin_start, c->bin_cursor);
+          hipLaunchKernelGGL(k_chunk_lists, cg, dim3(kBlock), 0, c->stream, c->chunk_bin, c->pool_next, c->max_chunks, c->bin_cursor,
+                             c->bin_chunks); }
+        { Timed tm(c, NOMAD_K_TILES);
+          hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 * kTile, c->stream,
+                             c->pool, c->chunk_fill, c->bin_start, c->bin_chunks, c->gneg, n); }
+        { Timed tm(c, NOMAD_K_SCATTER);
+          hipLaunchKernelGGL((k_tail_pull<16>), dim3(c->edge_grid), dim3(kBlock), 0, c->stream, c->row_ptr, c->col, c->rev,
+                             c->coef, c->theta, c->ghead, c->gfix, c->gneg, c->g, n); }
     } else {
         { Timed tm(c, NOMAD_K_EDGES);
           launch_edges<kModeDet>(c, a); }
         { Timed tm(c, NOMAD_K_SCATTER);
           hipLaunchKernelGGL((k_tail_pull<16>), dim3(c->edge_grid), dim3(kBlock), 0, c->stream, c->row_ptr, c->col, c->rev,
-                             c->coef, c->theta, c->ghead, c->gfix, c->g, n); }
+                             c->coef, c->theta, c->ghead, c->gfix, (const float2*)nullptr, c->g, n); }
     }
     const float eta = (float)((double)c->cfg.lr0 * (1.0 - (double)t / (double)c->cfg.n_epochs));
     { Timed tm(c, NOMAD_K_UPDATE);

@@ -265,6 +265,98 @@ struct EdgeArgs {
 
 enum EdgeMode { kModeAtomic = 0, kModeDet = 1, kModeLoss = 2 };
 
+// Per-head constants of the edge pass.
+struct HeadCtx {
+    float2 ti;
+    float inv_deg;
+    float omega;          // weight of one sampled negative (Eq. 6 estimate)
+    float MA, MBx, MBy;   // |M| A_i and |M| B_i (Eq. 5 and its derivative factor)
+    Population pop;
+};
+
+__device__ __forceinline__ HeadCtx load_head(const EdgeArgs& P, int64_t i, int32_t ea, int32_t eb) {
+    HeadCtx h;
+    h.ti = P.theta[i];
+    h.inv_deg = eb > ea ? 1.0f / (float)(eb - ea) : 0.f;
+    h.MA = h.MBx = h.MBy = 0.f;
+    if (P.group_of_cluster) {
+        const int32_t gi = P.group_of_cluster[P.cluster_of[i]];
+        h.pop.base = P.gbase[gi];
+        h.pop.count = P.gcount[gi];
+        h.pop.members = P.gmembers;
+        h.omega = P.gomega[gi];
+        h.MA = P.noise_count * P.A[i];
+        const float2 b = P.B[i];
+        h.MBx = P.noise_count * b.x;
+        h.MBy = P.noise_count * b.y;
+    } else {
+        h.pop.base = 0;
+        h.pop.count = (uint32_t)P.n;
+        h.pop.members = nullptr;
+        h.omega = P.omega0;
+    }
+    return h;
+}
+
+// Everything one directed edge e = (i -> j) contributes, for a compile-time number S of negatives:
+//   a        attraction coefficient 2 p q_ij (1 - q_ij / S_e)         (gradient of Eq. 4's numerator and q_ij in S_e)
+//   m[k], (rx,ry)[k]  the sampled negatives and the force each receives, b_k (theta_i - theta_m)
+//   (hx,hy)  total force on the head: a d_ij - sum_k r_k - 2 p |M| B_i / S_e
+template <int S>
+struct EdgeOut {
+    float a, dx, dy, hx, hy, log_term;
+    int32_t m[S];
+    float rx[S], ry[S];
+};
+
+template <int S, bool LOSS>
+__device__ __forceinline__ void edge_terms(const EdgeArgs& P, const HeadCtx& h, int32_t e, EdgeOut<S>& o) {
+    const int32_t j = P.col[e];
+    const float2 tj = P.theta[j];
+    const float pe = P.pe ? P.pe[e] : h.inv_deg;
+    o.dx = h.ti.x - tj.x;
+    o.dy = h.ti.y - tj.y;
+    const float qij = cauchy(o.dx, o.dy);
+#pragma unroll
+    for (int b = 0; b < (S + 3) / 4; ++b) {
+        uint32_t w[4];
+        philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
+#pragma unroll
+        for (int l = 0; l < 4; ++l)
+            if (4 * b + l < S) o.m[4 * b + l] = draw_index(w[l], h.pop);
+    }
+    float qm[S];
+    float qsum = 0.f;
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+        const float2 tm = P.theta[o.m[k]];
+        o.rx[k] = h.ti.x - tm.x;
+        o.ry[k] = h.ti.y - tm.y;
+        qm[k] = cauchy(o.rx[k], o.ry[k]);
+        qsum += qm[k];
+    }
+    const float Se = qij + h.MA + h.omega * qsum;
+    if (LOSS) {
+        o.log_term = pe * logf(Se / qij);   // -log q + log S = log(S (1 + d^2))
+        return;
+    }
+    const float inv_S = 1.0f / Se;
+    o.a = 2.0f * pe * qij * (1.0f - qij * inv_S);
+    float fx = o.a * o.dx, fy = o.a * o.dy;
+    const float bscale = 2.0f * pe * h.omega * inv_S;
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+        const float b = bscale * qm[k] * qm[k];
+        o.rx[k] *= b;
+        o.ry[k] *= b;
+        fx -= o.rx[k];
+        fy -= o.ry[k];
+    }
+    const float c = 2.0f * pe * inv_S;
+    o.hx = fx - c * h.MBx;
+    o.hy = fy - c * h.MBy;
+}
+
 // Blocks are handed to the 8 XCDs round-robin; giving XCD x the x-th contiguous eighth of the
 // rows keeps each L2 on its own slice of theta and of the index stream.
 __device__ __forceinline__ uint32_t xcd_contiguous_block(uint32_t b, uint32_t nblocks) {
@@ -272,6 +364,60 @@ __device__ __forceinline__ uint32_t xcd_contiguous_block(uint32_t b, uint32_t nb
     return (b & 7u) * per + (b >> 3);
 }
 
+// Dynamic-s variant of the per-edge arithmetic (s = 0 or s > 8): the negatives are drawn twice,
+// once for S_e and once for the forces, so nothing has to be kept per slot.  `emit(m, rx, ry)`
+// receives the force on each negative.
+template <bool LOSS, typename Emit>
+__device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const HeadCtx& h, int32_t e, int32_t s, float& a,
+                                                   float& dx, float& dy, float& hx, float& hy, float& log_term, Emit emit) {
+    const int32_t j = P.col[e];
+    const float2 tj = P.theta[j];
+    const float pe = P.pe ? P.pe[e] : h.inv_deg;
+    dx = h.ti.x - tj.x;
+    dy = h.ti.y - tj.y;
+    const float qij = cauchy(dx, dy);
+    float qsum = 0.f;
+    for (int b = 0; 4 * b < s; ++b) {
+        uint32_t w[4];
+        philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
+        for (int l = 0; l < 4 && 4 * b + l < s; ++l) {
+            const float2 tm = P.theta[draw_index(w[l], h.pop)];
+            qsum += cauchy(h.ti.x - tm.x, h.ti.y - tm.y);
+        }
+    }
+    const float Se = qij + h.MA + h.omega * qsum;
+    if (LOSS) { log_term = pe * logf(Se / qij); return; }
+    const float inv_S = 1.0f / Se;
+    a = 2.0f * pe * qij * (1.0f - qij * inv_S);
+    float fx = a * dx, fy = a * dy;
+    const float bscale = 2.0f * pe * h.omega * inv_S;
+    for (int b = 0; 4 * b < s; ++b) {
+        uint32_t w[4];
+        philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
+        for (int l = 0; l < 4 && 4 * b + l < s; ++l) {
+            const int32_t mk = draw_index(w[l], h.pop);
+            const float2 tm = P.theta[mk];
+            const float gx = h.ti.x - tm.x, gy = h.ti.y - tm.y;
+            const float q = cauchy(gx, gy);
+            const float bb = bscale * q * q;
+            fx -= bb * gx;
+            fy -= bb * gy;
+            emit(mk, bb * gx, bb * gy);
+        }
+    }
+    const float c = 2.0f * pe * inv_S;
+    hx = fx - c * h.MBx;
+    hy = fy - c * h.MBy;
+}
+
+__device__ __forceinline__ void add_fixed(unsigned long long* gfix, int64_t m, float rx, float ry) {
+    atomicAdd(&gfix[2 * m], (unsigned long long)__float2ll_rn(rx * kFixScale));
+    atomicAdd(&gfix[2 * m + 1], (unsigned long long)__float2ll_rn(ry * kFixScale));
+}
+
+// The edge pass with forces scattered straight from the kernel: global fp32 atomics (kModeAtomic),
+// or a_e stored for the tail pull and negatives added in 64-bit fixed point (kModeDet); kModeLoss
+// only sums the loss terms.  S > 0: compile-time number of negatives; S = 0: run-time s.
 template <int S, int MODE, int LPR>
 __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
     constexpr int ROWS = kBlock / LPR;
@@ -283,120 +429,43 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
     double lsum = 0.0;
     if (i < P.n) {
         const int32_t ea = P.row_ptr[i], eb = P.row_ptr[i + 1];
-        const float2 ti = P.theta[i];
-        const float inv_deg = eb > ea ? 1.0f / (float)(eb - ea) : 0.f;
-        Population pop;
-        float omega, MA = 0.f, MBx = 0.f, MBy = 0.f;
-        if (P.group_of_cluster) {
-            const int32_t gi = P.group_of_cluster[P.cluster_of[i]];
-            pop.base = P.gbase[gi];
-            pop.count = P.gcount[gi];
-            pop.members = P.gmembers;
-            omega = P.gomega[gi];
-            MA = P.noise_count * P.A[i];
-            const float2 b = P.B[i];
-            MBx = P.noise_count * b.x;
-            MBy = P.noise_count * b.y;
-        } else {
-            pop.base = 0;
-            pop.count = (uint32_t)P.n;
-            pop.members = nullptr;
-            omega = P.omega0;
-        }
-        const int32_t s = S > 0 ? S : P.s;
+        const HeadCtx h = load_head(P, i, ea, eb);
         for (int32_t e = ea + lane; e < eb; e += LPR) {
-            const int32_t j = P.col[e];
-            const float2 tj = P.theta[j];
-            const float pe = P.pe ? P.pe[e] : inv_deg;
-            const float dx = ti.x - tj.x, dy = ti.y - tj.y;
-            const float qij = cauchy(dx, dy);
-            int32_t m[SS];
-            float ex[SS], ey[SS], qm[SS];
-            float qsum = 0.f;
+            float a = 0.f, dx = 0.f, dy = 0.f, ehx = 0.f, ehy = 0.f, lt = 0.f;
             if (S > 0) {
+                EdgeOut<SS> o;
+                edge_terms<SS, MODE == kModeLoss>(P, h, e, o);
+                if (MODE == kModeLoss) { lsum += (double)o.log_term; continue; }
+                a = o.a; dx = o.dx; dy = o.dy; ehx = o.hx; ehy = o.hy;
 #pragma unroll
-                for (int b = 0; b < (S + 3) / 4; ++b) {
-                    uint32_t w[4];
-                    philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
-#pragma unroll
-                    for (int l = 0; l < 4; ++l)
-                        if (4 * b + l < S) m[4 * b + l] = draw_index(w[l], pop);
-                }
-#pragma unroll
-                for (int k = 0; k < S; ++k) {
-                    const float2 tm = P.theta[m[k]];
-                    ex[k] = ti.x - tm.x;
-                    ey[k] = ti.y - tm.y;
-                    qm[k] = cauchy(ex[k], ey[k]);
-                    qsum += qm[k];
-                }
-            } else {
-                for (int b = 0; 4 * b < s; ++b) {
-                    uint32_t w[4];
-                    philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
-                    for (int l = 0; l < 4 && 4 * b + l < s; ++l) {
-                        const float2 tm = P.theta[draw_index(w[l], pop)];
-                        qsum += cauchy(ti.x - tm.x, ti.y - tm.y);
+                for (int k = 0; k < SS; ++k) {
+                    if (MODE == kModeAtomic) {
+                        unsafeAtomicAdd(&P.g[o.m[k]].x, o.rx[k]);
+                        unsafeAtomicAdd(&P.g[o.m[k]].y, o.ry[k]);
+                    } else {
+                        add_fixed(P.gfix, o.m[k], o.rx[k], o.ry[k]);
                     }
                 }
+            } else {
+                edge_terms_dynamic<MODE == kModeLoss>(P, h, e, P.s, a, dx, dy, ehx, ehy, lt, [&](int32_t mk, float rx, float ry) {
+                    if (MODE == kModeAtomic) {
+                        unsafeAtomicAdd(&P.g[mk].x, rx);
+                        unsafeAtomicAdd(&P.g[mk].y, ry);
+                    } else {
+                        add_fixed(P.gfix, mk, rx, ry);
+                    }
+                });
+                if (MODE == kModeLoss) { lsum += (double)lt; continue; }
             }
-            const float Se = qij + MA + omega * qsum;
-            if (MODE == kModeLoss) {
-                // -log q + log S = log(S (1 + d^2))
-                lsum += (double)(pe * logf(Se / qij));
-                continue;
-            }
-            const float inv_S = 1.0f / Se;
-            const float a = 2.0f * pe * qij * (1.0f - qij * inv_S);
-            float fx = a * dx, fy = a * dy;           // attraction on the head; the tail gets the opposite
-            if (MODE == kModeAtomic) {
-                unsafeAtomicAdd(&P.g[j].x, -fx);
-                unsafeAtomicAdd(&P.g[j].y, -fy);
+            if (MODE == kModeAtomic) {   // the tail takes the opposite of the attraction
+                const int32_t j = P.col[e];
+                unsafeAtomicAdd(&P.g[j].x, -a * dx);
+                unsafeAtomicAdd(&P.g[j].y, -a * dy);
             } else {
                 P.coef[e] = a;
             }
-            const float bscale = 2.0f * pe * omega * inv_S;
-            if (S > 0) {
-#pragma unroll
-                for (int k = 0; k < S; ++k) {
-                    const float b = bscale * qm[k] * qm[k];
-                    const float rx = b * ex[k], ry = b * ey[k];
-                    fx -= rx;
-                    fy -= ry;
-                    if (MODE == kModeAtomic) {
-                        unsafeAtomicAdd(&P.g[m[k]].x, rx);
-                        unsafeAtomicAdd(&P.g[m[k]].y, ry);
-                    } else {
-                        atomicAdd(&P.gfix[2 * (int64_t)m[k]], (unsigned long long)__float2ll_rn(rx * kFixScale));
-                        atomicAdd(&P.gfix[2 * (int64_t)m[k] + 1], (unsigned long long)__float2ll_rn(ry * kFixScale));
-                    }
-                }
-            } else {
-                for (int b = 0; 4 * b < s; ++b) {
-                    uint32_t w[4];
-                    philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
-                    for (int l = 0; l < 4 && 4 * b + l < s; ++l) {
-                        const int32_t mk = draw_index(w[l], pop);
-                        const float2 tm = P.theta[mk];
-                        const float gx = ti.x - tm.x, gy = ti.y - tm.y;
-                        const float q = cauchy(gx, gy);
-                        const float bb = bscale * q * q;
-                        const float rx = bb * gx, ry = bb * gy;
-                        fx -= rx;
-                        fy -= ry;
-                        if (MODE == kModeAtomic) {
-                            unsafeAtomicAdd(&P.g[mk].x, rx);
-                            unsafeAtomicAdd(&P.g[mk].y, ry);
-                        } else {
-                            atomicAdd(&P.gfix[2 * (int64_t)mk], (unsigned long long)__float2ll_rn(rx * kFixScale));
-                            atomicAdd(&P.gfix[2 * (int64_t)mk + 1], (unsigned long long)__float2ll_rn(ry * kFixScale));
-                        }
-                    }
-                }
-            }
-            const float c = 2.0f * pe * inv_S;        // mean-field term: -2 p |M| B_i / S
-            hx += fx - c * MBx;
-            hy += fy - c * MBy;
+            hx += ehx;
+            hy += ehy;
         }
     }
     if (MODE == kModeLoss) {
@@ -421,6 +490,241 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
             P.ghead[i] = make_float2(hx, hy);
         }
     }
+}
+
+// ------------------------------------------------------------------ K3 + K4, binned: the fast deterministic path
+// Global atomics run at a fixed ~21 G/s on this GPU whatever the locality, far too slow for the
+// E*s negative forces of an epoch.  Instead the edge pass *bins* every negative's force by the
+// destination's tile of kTile points and a second kernel accumulates each tile in LDS:
+//
+//   k_edges_binned   persistent workgroups, each owning a contiguous, edge-balanced range of rows.
+//                    Every (workgroup, tile) pair appends 12-byte records (local index, force x, y)
+//                    to its own chain of kChunk-record chunks taken from one global pool; the chain
+//                    state lives in LDS, a global atomic is spent only per new chunk.  Work is done
+//                    in rounds of one edge per lane with workgroup barriers, so that appends never
+//                    wait on one another (no spin loops).
+//   k_chunk_*        bucket the chunks by tile (tiny).
+//   k_tile_accumulate one workgroup per tile adds its records into 2 x 64-bit fixed-point
+//                    accumulators per point in LDS.  Integer addition is associative, so the result
+//                    does not depend on the order records were appended or read in.
+constexpr int kTileBits = 13;
+constexpr int kTile = 1 << kTileBits;   // 8192 points: 128 KB of accumulators
+constexpr int kChunk = 256;             // records per chunk
+constexpr int kBinBlock = 1024;
+constexpr uint32_t kNoChunk = 0xFFFFFFFFu;
+
+struct BinArgs {
+    uint32_t* pool;               // [max_chunks][kChunk][3]
+    uint32_t* chunk_bin;          // [max_chunks] tile of each chunk
+    uint32_t* chunk_fill;         // [max_chunks] records in each chunk
+    uint32_t* pool_next;          // chunks handed out so far
+    uint32_t max_chunks;
+    uint32_t n_bins;
+    const int32_t* wg_row_begin;  // [gridDim.x + 1]
+    int* overflow;                // set if the pool bound were ever exceeded (it cannot be)
+};
+
+template <int S>
+__global__ void __launch_bounds__(kBinBlock, 8) k_edges_binned(const EdgeArgs P, const BinArgs Q) {
+    constexpr int LPR = 16;
+    extern __shared__ uint32_t lds_bins[];
+    const uint32_t B = Q.n_bins;
+    uint32_t* fill = lds_bins;        // records already in the open chunk (kChunk: none / full)
+    uint32_t* chunk = lds_bins + B;   // open chunk of this (workgroup, tile)
+    uint32_t* cnt = lds_bins + 2 * B; // records this round
+    uint32_t* base = lds_bins + 3 * B;// first chunk allocated this round
+    __shared__ int next_row;
+    __shared__ int any_active[2];
+    const int tid = threadIdx.x, lane = tid % LPR;
+    const int32_t r1 = Q.wg_row_begin[blockIdx.x + 1];
+    for (uint32_t b = tid; b < B; b += kBinBlock) { fill[b] = kChunk; chunk[b] = kNoChunk; cnt[b] = 0; base[b] = 0; }
+    if (tid == 0) { next_row = Q.wg_row_begin[blockIdx.x]; any_active[0] = 0; any_active[1] = 0; }
+    __syncthreads();
+
+    int32_t row = -1, e_next = 0, e_end = 0;
+    bool out_of_rows = false;
+    float hx = 0.f, hy = 0.f;
+    HeadCtx h{};
+    for (int round = 0;; ++round) {
+        // a row group that has used up its row stores the head sum and takes the next row
+        while (!out_of_rows && e_next >= e_end) {
+            if (row >= 0) {
+                const float sx = rowgroup_sum<LPR>(hx), sy = rowgroup_sum<LPR>(hy);
+                if (lane == 0) P.ghead[row] = make_float2(sx, sy);
+                hx = 0.f; hy = 0.f;
+            }
+            int32_t r = 0;
+            if (lane == 0) r = atomicAdd(&next_row, 1);
+            r = __shfl(r, 0, LPR);
+            if (r >= r1) { out_of_rows = true; row = -1; break; }
+            row = r;
+            e_next = P.row_ptr[r];
+            e_end = P.row_ptr[r + 1];
+            h = load_head(P, r, e_next, e_end);
+        }
+        const int32_t e = e_next + lane;
+        const bool has = !out_of_rows && e < e_end;
+        if (!out_of_rows) e_next += LPR;
+        EdgeOut<S> o;
+        uint32_t rank[S];
+        if (has) {
+            edge_terms<S, false>(P, h, e, o);
+            P.coef[e] = o.a;
+            hx += o.hx;
+            hy += o.hy;
+#pragma unroll
+            for (int k = 0; k < S; ++k) rank[k] = atomicAdd(&cnt[(uint32_t)o.m[k] >> kTileBits], 1u);
+            any_active[round & 1] = 1;
+        }
+        __syncthreads();
+        if (!any_active[round & 1]) break;
+        // tiles whose open chunk cannot take this round's records get new chunks
+        for (uint32_t b = tid; b < B; b += kBinBlock) {
+            const uint32_t c = cnt[b];
+            if (c == 0) continue;
+            const uint32_t f = fill[b];
+            if (f + c > (uint32_t)kChunk) {
+                const uint32_t k = (f + c - 1) / kChunk;
+                const uint32_t nb = atomicAdd(Q.pool_next, k);
+                base[b] = nb;
+                if (nb + k > Q.max_chunks) *Q.overflow = 1;
+                if (chunk[b] < Q.max_chunks) Q.chunk_fill[chunk[b]] = kChunk;   // kNoChunk is above any valid id
+                for (uint32_t x = 0; x < k && nb + x < Q.max_chunks; ++x) {
+                    Q.chunk_bin[nb + x] = b;
+                    Q.chunk_fill[nb + x] = kChunk;   // the last one is corrected when it is closed
+                }
+            }
+        }
+        if (tid == 0) any_active[(round + 1) & 1] = 0;
+        __syncthreads();
+        if (has) {
+#pragma unroll
+            for (int k = 0; k < S; ++k) {
+                const uint32_t b = (uint32_t)o.m[k] >> kTileBits;
+                const uint32_t pos = fill[b] + rank[k];
+                uint32_t ch, off;
+                if (pos < (uint32_t)kChunk) { ch = chunk[b]; off = pos; }
+                else { ch = base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
+                if (ch < Q.max_chunks) {
+                    uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
+                    dst[0] = (uint32_t)o.m[k] & (kTile - 1);
+                    dst[1] = __float_as_uint(o.rx[k]);
+                    dst[2] = __float_as_uint(o.ry[k]);
+                }
+            }
+        }
+        __syncthreads();
+        for (uint32_t b = tid; b < B; b += kBinBlock) {
+            const uint32_t c = cnt[b];
+            if (c == 0) continue;
+            const uint32_t f = fill[b];
+            if (f + c > (uint32_t)kChunk) {
+                const uint32_t k = (f + c - 1) / kChunk;
+                chunk[b] = base[b] + k - 1;
+                fill[b] = f + c - k * kChunk;
+            } else {
+                fill[b] = f + c;
+            }
+            cnt[b] = 0;
+        }
+        __syncthreads();
+    }
+    // close the open chunks
+    for (uint32_t b = tid; b < B; b += kBinBlock)
+        if (chunk[b] < Q.max_chunks) Q.chunk_fill[chunk[b]] = fill[b];   // kNoChunk is above any valid id
+}
+
+// first row of each persistent workgroup: rows split so that every workgroup gets ~E/W edges
+__global__ void k_wg_rows(const int32_t* __restrict__ row_ptr, int64_t n, int64_t E, int W, int32_t* __restrict__ wg_row_begin) {
+    const int w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w > W) return;
+    if (w == W) { wg_row_begin[w] = (int32_t)n; return; }
+    const int64_t target = E * (int64_t)w / W;
+    int64_t lo = 0, hi = n;   // first row with row_ptr[row] >= target
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)row_ptr[mid] < target) lo = mid + 1; else hi = mid;
+    }
+    wg_row_begin[w] = (int32_t)lo;
+}
+
+__global__ void k_bin_reset(uint32_t* __restrict__ bin_count, uint32_t B, uint32_t* pool_next) {
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) bin_count[b] = 0;
+    if (b == 0) *pool_next = 0;
+}
+
+__global__ void k_chunk_census(const uint32_t* __restrict__ chunk_bin, const uint32_t* __restrict__ pool_next, uint32_t max_chunks,
+                               uint32_t* __restrict__ bin_count) {
+    const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < min(*pool_next, max_chunks)) atomicAdd(&bin_count[chunk_bin[c]], 1u);
+}
+
+// exclusive scan of the per-tile chunk counts (one block; B is a few thousand)
+__global__ void __launch_bounds__(kBinBlock) k_bin_scan(const uint32_t* __restrict__ bin_count, uint32_t B, uint32_t* __restrict__ bin_start,
+                                                       uint32_t* __restrict__ bin_cursor) {
+    __shared__ uint32_t part[kBinBlock];
+    const uint32_t per = (B + kBinBlock - 1) / kBinBlock;
+    const uint32_t b0 = threadIdx.x * per, b1 = min(B, b0 + per);
+    uint32_t sum = 0;
+    for (uint32_t b = b0; b < b1; ++b) sum += bin_count[b];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int t = 0; t < kBinBlock; ++t) { const uint32_t v = part[t]; part[t] = run; run += v; }
+        bin_start[B] = run;
+    }
+    __syncthreads();
+    uint32_t run = part[threadIdx.x];
+    for (uint32_t b = b0; b < b1; ++b) { bin_start[b] = run; bin_cursor[b] = run; run += bin_count[b]; }
+}
+
+__global__ void k_chunk_lists(const uint32_t* __restrict__ chunk_bin, const uint32_t* __restrict__ pool_next, uint32_t max_chunks,
+                              uint32_t* __restrict__ bin_cursor, uint32_t* __restrict__ bin_chunks) {
+    const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < min(*pool_next, max_chunks)) bin_chunks[atomicAdd(&bin_cursor[chunk_bin[c]], 1u)] = c;
+}
+
+__global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const uint32_t* __restrict__ pool, const uint32_t* __restrict__ chunk_fill,
+                                                              const uint32_t* __restrict__ bin_start,
+                                                              const uint32_t* __restrict__ bin_chunks, float2* __restrict__ gneg, int64_t n) {
+    extern __shared__ unsigned long long acc[];   // [kTile][2]
+    constexpr int kPerIter = kBinBlock / kChunk;   // chunks one sweep of the block covers
+    constexpr int kUnroll = 4;
+    const uint32_t b = blockIdx.x;
+    for (int l = threadIdx.x; l < 2 * kTile; l += kBinBlock) acc[l] = 0ull;
+    __syncthreads();
+    const uint32_t c_end = bin_start[b + 1];
+    const uint32_t off = threadIdx.x % kChunk;
+    for (uint32_t c0 = bin_start[b] + threadIdx.x / kChunk; c0 < c_end; c0 += kPerIter * kUnroll) {
+        uint32_t rec[kUnroll][3];
+        bool ok[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint32_t ci = c0 + u * kPerIter;
+            ok[u] = false;
+            if (ci < c_end) {
+                const uint32_t ch = bin_chunks[ci];
+                if (off < chunk_fill[ch]) {
+                    const uint32_t* src = pool + ((size_t)ch * kChunk + off) * 3;
+                    rec[u][0] = src[0]; rec[u][1] = src[1]; rec[u][2] = src[2];
+                    ok[u] = true;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            if (ok[u]) {
+                const uint32_t ml = rec[u][0] & (kTile - 1);
+                atomicAdd(&acc[2 * ml], (unsigned long long)__float2ll_rn(__uint_as_float(rec[u][1]) * kFixScale));
+                atomicAdd(&acc[2 * ml + 1], (unsigned long long)__float2ll_rn(__uint_as_float(rec[u][2]) * kFixScale));
+            }
+    }
+    __syncthreads();
+    const int64_t p0 = (int64_t)b * kTile;
+    for (int l = threadIdx.x; l < kTile && p0 + l < n; l += kBinBlock)
+        gneg[p0 + l] = make_float2((float)((double)(long long)acc[2 * l] * kFixInv), (float)((double)(long long)acc[2 * l + 1] * kFixInv));
 }
 
 // fixed-order sum of the per-block loss partials (one block)
@@ -449,7 +753,8 @@ template <int LPR>
 __global__ void __launch_bounds__(kBlock) k_tail_pull(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
                                                       const int32_t* __restrict__ rev, const float* __restrict__ coef,
                                                       const float2* __restrict__ theta, const float2* __restrict__ ghead,
-                                                      unsigned long long* __restrict__ gfix, float2* __restrict__ g, int64_t n) {
+                                                      unsigned long long* __restrict__ gfix, const float2* __restrict__ gneg,
+                                                      float2* __restrict__ g, int64_t n) {
     constexpr int ROWS = kBlock / LPR;
     const uint32_t lb = xcd_contiguous_block(blockIdx.x, gridDim.x);
     const int64_t j = (int64_t)lb * ROWS + (threadIdx.x / LPR);
@@ -468,10 +773,17 @@ __global__ void __launch_bounds__(kBlock) k_tail_pull(const int32_t* __restrict_
     ay = rowgroup_sum<LPR>(ay);
     if (lane == 0 && j < n) {
         const float2 h = ghead[j];
-        const double nx = (double)(long long)gfix[2 * j] * kFixInv;
-        const double ny = (double)(long long)gfix[2 * j + 1] * kFixInv;
-        gfix[2 * j] = 0ull;
-        gfix[2 * j + 1] = 0ull;
+        double nx, ny;
+        if (gneg) {
+            const float2 v = gneg[j];
+            nx = (double)v.x;
+            ny = (double)v.y;
+        } else {
+            nx = (double)(long long)gfix[2 * j] * kFixInv;
+            ny = (double)(long long)gfix[2 * j + 1] * kFixInv;
+            gfix[2 * j] = 0ull;
+            gfix[2 * j + 1] = 0ull;
+        }
         g[j] = make_float2((float)((double)h.x + (double)ax + nx), (float)((double)h.y + (double)ay + ny));
     }
 }
