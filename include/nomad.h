@@ -88,9 +88,8 @@ void nomad_destroy(nomad_ctx* ctx);
  *                         of i's own group and weighted |M| (n_group/n) / s (Eq. 6).  NULL means
  *                         nothing is approximated and Eq. 4 is the InfoNC-t-SNE loss, Eq. 2.
  *
- * In deterministic mode the graph must also be structurally symmetric without parallel edges
- * (the tail sums are pulled through the reverse edge).  Violations give NOMAD_E_BAD_GRAPH and
- * leave the context without a graph.  Replaces any earlier graph and embedding.
+ * The graph need not be symmetric.  Violations of the requirements above give NOMAD_E_BAD_GRAPH
+ * and leave the context without a graph.  Replaces any earlier graph and embedding.
  */
 int nomad_set_graph(nomad_ctx* ctx, const int32_t* row_ptr, const int32_t* col_idx, const float* weights,
                     const int32_t* cluster_of, const int32_t* cluster_group, int mem);
@@ -139,7 +138,7 @@ int64_t nomad_num_edges(const nomad_ctx* ctx);
 #define NOMAD_K_MEANS 0      /* cell means                         */
 #define NOMAD_K_MEANFIELD 1  /* mean-field sums                    */
 #define NOMAD_K_EDGES 2      /* attraction + sampling + repulsion  */
-#define NOMAD_K_SCATTER 3    /* deterministic tail pull + combine  */
+#define NOMAD_K_SCATTER 3    /* fallback: combine of fixed-point sums */
 #define NOMAD_K_UPDATE 4     /* SGD step                           */
 #define NOMAD_K_LOSS 5       /* loss terms + reduction             */
 #define NOMAD_K_ZERO 6       /* clearing of accumulators           */

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -31,7 +32,7 @@ struct nomad_ctx {
     bool grouped = false;
     int lpr = 16;
     // graph
-    int32_t *row_ptr = nullptr, *col = nullptr, *cluster_of = nullptr, *group_of_cluster = nullptr, *rev = nullptr;
+    int32_t *row_ptr = nullptr, *col = nullptr, *cluster_of = nullptr, *group_of_cluster = nullptr;
     float* pe = nullptr;
     // partition tables
     uint32_t *counts = nullptr, *gbase = nullptr, *gcount = nullptr, *chunk_start = nullptr;
@@ -44,7 +45,7 @@ struct nomad_ctx {
     // state
     float2 *theta = nullptr, *g = nullptr, *ghead = nullptr, *mu = nullptr, *B = nullptr;
     float4* cinfo = nullptr;
-    float *A = nullptr, *coef = nullptr;
+    float* A = nullptr;
     unsigned long long* gfix = nullptr;
     // binned deterministic scatter
     bool binned = false;
@@ -53,7 +54,6 @@ struct nomad_ctx {
     uint32_t *pool = nullptr, *chunk_bin = nullptr, *chunk_fill = nullptr, *pool_next = nullptr, *bin_count = nullptr,
              *bin_start = nullptr, *bin_cursor = nullptr, *bin_chunks = nullptr;
     int32_t* wg_row_begin = nullptr;
-    float2* gneg = nullptr;
     int* overflow = nullptr;
     double *loss_partial = nullptr, *loss_out = nullptr;
     uint32_t edge_grid = 0;
@@ -99,14 +99,14 @@ void dev_free(T*& p) {
 }
 
 void free_graph(nomad_ctx* c) {
-    dev_free(c->row_ptr); dev_free(c->col); dev_free(c->cluster_of); dev_free(c->group_of_cluster); dev_free(c->rev);
+    dev_free(c->row_ptr); dev_free(c->col); dev_free(c->cluster_of); dev_free(c->group_of_cluster);
     dev_free(c->pe); dev_free(c->counts); dev_free(c->gbase); dev_free(c->gcount); dev_free(c->chunk_start);
     dev_free(c->gomega); dev_free(c->gmembers); dev_free(c->cmembers); dev_free(c->chunks); dev_free(c->mean_partial);
     dev_free(c->theta); dev_free(c->g); dev_free(c->ghead); dev_free(c->mu); dev_free(c->B); dev_free(c->cinfo);
-    dev_free(c->A); dev_free(c->coef); dev_free(c->gfix); dev_free(c->loss_partial); dev_free(c->loss_out);
+    dev_free(c->A); dev_free(c->gfix); dev_free(c->loss_partial); dev_free(c->loss_out);
     dev_free(c->flags);
     dev_free(c->pool); dev_free(c->chunk_bin); dev_free(c->chunk_fill); dev_free(c->pool_next); dev_free(c->bin_count);
-    dev_free(c->bin_start); dev_free(c->bin_cursor); dev_free(c->bin_chunks); dev_free(c->wg_row_begin); dev_free(c->gneg);
+    dev_free(c->bin_start); dev_free(c->bin_cursor); dev_free(c->bin_chunks); dev_free(c->wg_row_begin);
     dev_free(c->overflow);
     c->binned = false;
     c->has_graph = c->has_theta = c->has_grad = false;
@@ -152,7 +152,7 @@ EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
     a.noise_count = c->noise_count; a.omega0 = c->omega0;
     a.key0 = (uint32_t)c->cfg.seed; a.key1 = (uint32_t)(c->cfg.seed >> 32); a.epoch = t;
     a.s = c->cfg.n_neg; a.n = c->n;
-    a.g = c->g; a.ghead = c->ghead; a.coef = c->coef; a.gfix = c->gfix; a.loss_partial = c->loss_partial;
+    a.g = c->g; a.ghead = c->ghead; a.gfix = c->gfix; a.loss_partial = c->loss_partial;
     return a;
 }
 
@@ -192,6 +192,7 @@ int prepare_binned(nomad_ctx* c) {
     HIP_TRY(c, hipFuncSetAttribute((const void*)k_tile_accumulate, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)(sizeof(unsigned long long) * 2 * kTile)));
     switch (c->cfg.n_neg) {
+        case 0: return prepare_binned_kernel<0>(c);
         case 1: return prepare_binned_kernel<1>(c); case 2: return prepare_binned_kernel<2>(c);
         case 3: return prepare_binned_kernel<3>(c); case 4: return prepare_binned_kernel<4>(c);
         case 5: return prepare_binned_kernel<5>(c); case 6: return prepare_binned_kernel<6>(c);
@@ -206,7 +207,7 @@ void launch_edges_binned(nomad_ctx* c, const EdgeArgs& a) {
     const size_t lds = binned_lds_bytes(c->n_bins);
     switch (c->cfg.n_neg) {
 #define NOMAD_CASE(S) case S: hipLaunchKernelGGL((k_edges_binned<S>), grid, block, lds, c->stream, a, q); break;
-        NOMAD_CASE(1) NOMAD_CASE(2) NOMAD_CASE(3) NOMAD_CASE(4) NOMAD_CASE(5) NOMAD_CASE(6) NOMAD_CASE(7) NOMAD_CASE(8)
+        NOMAD_CASE(0) NOMAD_CASE(1) NOMAD_CASE(2) NOMAD_CASE(3) NOMAD_CASE(4) NOMAD_CASE(5) NOMAD_CASE(6) NOMAD_CASE(7) NOMAD_CASE(8)
 #undef NOMAD_CASE
         default: break;
     }
@@ -464,20 +465,20 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
     TRY(dev_alloc(c, &c->loss_partial, (size_t)c->edge_grid));
     TRY(dev_alloc(c, &c->loss_out, 1));
     if (c->cfg.scatter_mode == NOMAD_SCATTER_DETERMINISTIC) {
-        TRY(dev_alloc(c, &c->rev, (size_t)E));
-        TRY(dev_alloc(c, &c->coef, (size_t)E));
         TRY(dev_alloc(c, &c->ghead, (size_t)n));
-        TRY(dev_alloc(c, &c->gfix, (size_t)n * 2));
-        // Binned scatter of the negatives: needs a compile-time s and a tile table that fits LDS; if
-        // its record pool cannot be allocated the fixed-point global atomics remain as the fallback.
+        // Binned scatter of the tail and negative forces: needs a compile-time s and a tile table
+        // that fits LDS; if its record pool cannot be allocated, fixed-point global atomics remain
+        // as the fallback.
         const uint32_t n_bins = (uint32_t)((n + kTile - 1) / kTile);
-        if (s >= 1 && s <= 8 && E > 0 && binned_lds_bytes(n_bins) <= 144 * 1024) {
+        if (s <= 8 && E > 0 && binned_lds_bytes(n_bins) <= 144 * 1024) {
             hipDeviceProp_t prop;
             HTRY(hipGetDeviceProperties(&prop, c->cfg.device));
-            const int per_cu = binned_lds_bytes(n_bins) <= 72 * 1024 ? 2 : 1;
+            int per_cu = binned_lds_bytes(n_bins) <= 72 * 1024 ? 2 : 1;
+            if (const char* knob = getenv("NOMAD_WG_PER_CU"))   // tuning knob: persistent workgroups per compute unit
+                per_cu = std::max(1, std::min(per_cu, atoi(knob)));
             c->n_wg = std::max(1, prop.multiProcessorCount) * per_cu;
             c->n_bins = n_bins;
-            const uint64_t want = (uint64_t)E * (uint64_t)s / kChunk + (uint64_t)c->n_wg * n_bins + 1;
+            const uint64_t want = (uint64_t)E * (uint64_t)(s + 1) / kChunk + (uint64_t)c->n_wg * n_bins + 1;
             if (want < (1ull << 31)) {
                 c->max_chunks = (uint32_t)want;
                 bool ok = dev_alloc(c, &c->pool, (size_t)c->max_chunks * kChunk * 3) == NOMAD_OK &&
@@ -485,7 +486,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                           dev_alloc(c, &c->bin_chunks, c->max_chunks) == NOMAD_OK && dev_alloc(c, &c->pool_next, 1) == NOMAD_OK &&
                           dev_alloc(c, &c->bin_count, n_bins) == NOMAD_OK && dev_alloc(c, &c->bin_start, (size_t)n_bins + 1) == NOMAD_OK &&
                           dev_alloc(c, &c->bin_cursor, n_bins) == NOMAD_OK && dev_alloc(c, &c->wg_row_begin, (size_t)c->n_wg + 1) == NOMAD_OK &&
-                          dev_alloc(c, &c->gneg, (size_t)n) == NOMAD_OK && dev_alloc(c, &c->overflow, 1) == NOMAD_OK;
+                          dev_alloc(c, &c->overflow, 1) == NOMAD_OK;
                 if (ok) ok = prepare_binned(c) == NOMAD_OK;
                 if (ok) {
                     HTRY(hipMemsetAsync(c->overflow, 0, sizeof(int), st));
@@ -495,19 +496,15 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 } else {
                     (void)hipGetLastError();
                     dev_free(c->pool); dev_free(c->chunk_bin); dev_free(c->chunk_fill); dev_free(c->bin_chunks); dev_free(c->pool_next);
-                    dev_free(c->bin_count); dev_free(c->bin_start); dev_free(c->bin_cursor); dev_free(c->wg_row_begin); dev_free(c->gneg);
+                    dev_free(c->bin_count); dev_free(c->bin_start); dev_free(c->bin_cursor); dev_free(c->wg_row_begin);
                     dev_free(c->overflow);
                     c->err.clear();
                 }
             }
         }
-        hipLaunchKernelGGL(k_build_rev, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->row_ptr, c->col, n, c->rev, c->flags);
-        hipLaunchKernelGGL(k_zero_u64, dim3(blocks_for(n * 2)), dim3(kBlock), 0, st, c->gfix, n * 2);
-        HTRY(hipMemcpyAsync(hflags, c->flags, sizeof(hflags), hipMemcpyDeviceToHost, st));
-        HTRY(hipStreamSynchronize(st));
-        if (hflags[kFlagAsymmetric]) {
-            free_graph(c);
-            return fail(c, NOMAD_E_BAD_GRAPH, "deterministic mode needs a symmetric graph without parallel edges");
+        if (!c->binned) {
+            TRY(dev_alloc(c, &c->gfix, (size_t)n * 2));
+            hipLaunchKernelGGL(k_zero_u64, dim3(blocks_for(n * 2)), dim3(kBlock), 0, st, c->gfix, n * 2);
         }
     }
     HTRY(hipStreamSynchronize(st));
@@ -558,16 +555,12 @@ int nomad_epoch(nomad_ctx* c, int32_t t) {
                              c->bin_chunks); }
         { Timed tm(c, NOMAD_K_TILES);
           hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 * kTile, c->stream,
-                             c->pool, c->chunk_fill, c->bin_start, c->bin_chunks, c->gneg, n); }
-        { Timed tm(c, NOMAD_K_SCATTER);
-          hipLaunchKernelGGL((k_tail_pull<16>), dim3(c->edge_grid), dim3(kBlock), 0, c->stream, c->row_ptr, c->col, c->rev,
-                             c->coef, c->theta, c->ghead, c->gfix, c->gneg, c->g, n); }
+                             c->pool, c->chunk_fill, c->bin_start, c->bin_chunks, c->ghead, c->g, n); }
     } else {
         { Timed tm(c, NOMAD_K_EDGES);
           launch_edges<kModeDet>(c, a); }
         { Timed tm(c, NOMAD_K_SCATTER);
-          hipLaunchKernelGGL((k_tail_pull<16>), dim3(c->edge_grid), dim3(kBlock), 0, c->stream, c->row_ptr, c->col, c->rev,
-                             c->coef, c->theta, c->ghead, c->gfix, (const float2*)nullptr, c->g, n); }
+          hipLaunchKernelGGL(k_combine_fixed, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->ghead, c->gfix, c->g, n); }
     }
     const float eta = (float)((double)c->cfg.lr0 * (1.0 - (double)t / (double)c->cfg.n_epochs));
     { Timed tm(c, NOMAD_K_UPDATE);

@@ -74,7 +74,6 @@ enum Flag {
     kFlagWeight = 3,     // negative / non-finite weight or non-positive row sum
     kFlagCluster = 4,    // cluster id out of range
     kFlagGroup = 5,      // group label out of range
-    kFlagAsymmetric = 6, // reverse edge missing or parallel edges
     kFlagCount = 8
 };
 
@@ -125,21 +124,6 @@ __global__ void k_cluster_census(const int32_t* __restrict__ cluster_of, const i
             if (p != c) atomicAdd(&boundaries[0], 1ull);
             if (group_of_cluster && group_of_cluster[p] != group_of_cluster[c]) atomicAdd(&boundaries[1], 1ull);
         }
-    }
-}
-
-// reverse-edge index: rev[e] = position of (j -> i) for e = (i -> j)
-__global__ void k_build_rev(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col, int64_t n,
-                            int32_t* __restrict__ rev, int* flags) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    for (int32_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
-        const int32_t j = col[e];
-        int32_t found = -1, hits = 0;
-        for (int32_t f = row_ptr[j]; f < row_ptr[j + 1]; ++f)
-            if (col[f] == i) { if (found < 0) found = f; ++hits; }
-        if (hits != 1) flags[kFlagAsymmetric] = 1;
-        rev[e] = found < 0 ? e : found;
     }
 }
 
@@ -258,8 +242,7 @@ struct EdgeArgs {
     // outputs
     float2* g;                     // atomic mode: accumulators of every force
     float2* ghead;                 // deterministic mode: head-side sums
-    float* coef;                   // deterministic mode: a_e per edge
-    unsigned long long* gfix;      // deterministic mode: fixed-point negative sums [n*2]
+    unsigned long long* gfix;      // deterministic fallback: fixed-point sums of tail and negative forces [n*2]
     double* loss_partial;          // loss mode: one partial per block
 };
 
@@ -305,13 +288,15 @@ __device__ __forceinline__ HeadCtx load_head(const EdgeArgs& P, int64_t i, int32
 template <int S>
 struct EdgeOut {
     float a, dx, dy, hx, hy, log_term;
+    int32_t j;
     int32_t m[S];
     float rx[S], ry[S];
 };
 
 template <int S, bool LOSS>
-__device__ __forceinline__ void edge_terms(const EdgeArgs& P, const HeadCtx& h, int32_t e, EdgeOut<S>& o) {
+__device__ __forceinline__ void edge_terms(const EdgeArgs& P, const HeadCtx& h, int32_t e, EdgeOut<(S > 0 ? S : 1)>& o) {
     const int32_t j = P.col[e];
+    o.j = j;
     const float2 tj = P.theta[j];
     const float pe = P.pe ? P.pe[e] : h.inv_deg;
     o.dx = h.ti.x - tj.x;
@@ -325,7 +310,7 @@ __device__ __forceinline__ void edge_terms(const EdgeArgs& P, const HeadCtx& h, 
         for (int l = 0; l < 4; ++l)
             if (4 * b + l < S) o.m[4 * b + l] = draw_index(w[l], h.pop);
     }
-    float qm[S];
+    float qm[S > 0 ? S : 1];
     float qsum = 0.f;
 #pragma unroll
     for (int k = 0; k < S; ++k) {
@@ -416,8 +401,8 @@ __device__ __forceinline__ void add_fixed(unsigned long long* gfix, int64_t m, f
 }
 
 // The edge pass with forces scattered straight from the kernel: global fp32 atomics (kModeAtomic),
-// or a_e stored for the tail pull and negatives added in 64-bit fixed point (kModeDet); kModeLoss
-// only sums the loss terms.  S > 0: compile-time number of negatives; S = 0: run-time s.
+// or global 64-bit fixed-point atomics (kModeDet: order-independent, the fallback of the binned
+// path below); kModeLoss only sums the loss terms.  S > 0: compile-time number of negatives; S = 0: run-time s.
 template <int S, int MODE, int LPR>
 __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
     constexpr int ROWS = kBlock / LPR;
@@ -457,12 +442,12 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
                 });
                 if (MODE == kModeLoss) { lsum += (double)lt; continue; }
             }
-            if (MODE == kModeAtomic) {   // the tail takes the opposite of the attraction
-                const int32_t j = P.col[e];
+            const int32_t j = P.col[e];   // the tail takes the opposite of the attraction
+            if (MODE == kModeAtomic) {
                 unsafeAtomicAdd(&P.g[j].x, -a * dx);
                 unsafeAtomicAdd(&P.g[j].y, -a * dy);
             } else {
-                P.coef[e] = a;
+                add_fixed(P.gfix, j, -a * dx, -a * dy);
             }
             hx += ehx;
             hy += ehy;
@@ -495,7 +480,8 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
 // ------------------------------------------------------------------ K3 + K4, binned: the fast deterministic path
 // Global atomics run at a fixed ~21 G/s on this GPU whatever the locality, far too slow for the
 // E*s negative forces of an epoch.  Instead the edge pass *bins* every negative's force by the
-// destination's tile of kTile points and a second kernel accumulates each tile in LDS:
+// destination's tile of kTile points and a second kernel accumulates each tile in LDS
+// (a segmented sum over destination tiles):
 //
 //   k_edges_binned   persistent workgroups, each owning a contiguous, edge-balanced range of rows.
 //                    Every (workgroup, tile) pair appends 12-byte records (local index, force x, y)
@@ -506,7 +492,9 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
 //   k_chunk_*        bucket the chunks by tile (tiny).
 //   k_tile_accumulate one workgroup per tile adds its records into 2 x 64-bit fixed-point
 //                    accumulators per point in LDS.  Integer addition is associative, so the result
-//                    does not depend on the order records were appended or read in.
+//                    does not depend on the order records were appended or read in.  It then adds
+//                    the head sums and writes g.
+// The force on a tail is a record like the forces on negatives (slot 0 of every edge).
 constexpr int kTileBits = 13;
 constexpr int kTile = 1 << kTileBits;   // 8192 points: 128 KB of accumulators
 constexpr int kChunk = 256;             // records per chunk
@@ -565,15 +553,20 @@ __global__ void __launch_bounds__(kBinBlock, 8) k_edges_binned(const EdgeArgs P,
         const int32_t e = e_next + lane;
         const bool has = !out_of_rows && e < e_end;
         if (!out_of_rows) e_next += LPR;
-        EdgeOut<S> o;
-        uint32_t rank[S];
+        // records of this lane's edge: slot 0 is the tail (force -a d_ij), slots 1..S the negatives
+        uint32_t dst_pt[S + 1];
+        float fx[S + 1], fy[S + 1];
+        uint32_t rank[S + 1];
         if (has) {
+            EdgeOut<(S > 0 ? S : 1)> o;
             edge_terms<S, false>(P, h, e, o);
-            P.coef[e] = o.a;
             hx += o.hx;
             hy += o.hy;
+            dst_pt[0] = (uint32_t)o.j; fx[0] = -o.a * o.dx; fy[0] = -o.a * o.dy;
 #pragma unroll
-            for (int k = 0; k < S; ++k) rank[k] = atomicAdd(&cnt[(uint32_t)o.m[k] >> kTileBits], 1u);
+            for (int k = 0; k < S; ++k) { dst_pt[k + 1] = (uint32_t)o.m[k]; fx[k + 1] = o.rx[k]; fy[k + 1] = o.ry[k]; }
+#pragma unroll
+            for (int k = 0; k <= S; ++k) rank[k] = atomicAdd(&cnt[dst_pt[k] >> kTileBits], 1u);
             any_active[round & 1] = 1;
         }
         __syncthreads();
@@ -599,17 +592,17 @@ __global__ void __launch_bounds__(kBinBlock, 8) k_edges_binned(const EdgeArgs P,
         __syncthreads();
         if (has) {
 #pragma unroll
-            for (int k = 0; k < S; ++k) {
-                const uint32_t b = (uint32_t)o.m[k] >> kTileBits;
+            for (int k = 0; k <= S; ++k) {
+                const uint32_t b = dst_pt[k] >> kTileBits;
                 const uint32_t pos = fill[b] + rank[k];
                 uint32_t ch, off;
                 if (pos < (uint32_t)kChunk) { ch = chunk[b]; off = pos; }
                 else { ch = base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
                 if (ch < Q.max_chunks) {
                     uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
-                    dst[0] = (uint32_t)o.m[k] & (kTile - 1);
-                    dst[1] = __float_as_uint(o.rx[k]);
-                    dst[2] = __float_as_uint(o.ry[k]);
+                    dst[0] = dst_pt[k] & (kTile - 1);
+                    dst[1] = __float_as_uint(fx[k]);
+                    dst[2] = __float_as_uint(fy[k]);
                 }
             }
         }
@@ -688,7 +681,8 @@ __global__ void k_chunk_lists(const uint32_t* __restrict__ chunk_bin, const uint
 
 __global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const uint32_t* __restrict__ pool, const uint32_t* __restrict__ chunk_fill,
                                                               const uint32_t* __restrict__ bin_start,
-                                                              const uint32_t* __restrict__ bin_chunks, float2* __restrict__ gneg, int64_t n) {
+                                                              const uint32_t* __restrict__ bin_chunks, const float2* __restrict__ ghead,
+                                                              float2* __restrict__ g, int64_t n) {
     extern __shared__ unsigned long long acc[];   // [kTile][2]
     constexpr int kPerIter = kBinBlock / kChunk;   // chunks one sweep of the block covers
     constexpr int kUnroll = 4;
@@ -723,8 +717,11 @@ __global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const uint32_t* _
     }
     __syncthreads();
     const int64_t p0 = (int64_t)b * kTile;
-    for (int l = threadIdx.x; l < kTile && p0 + l < n; l += kBinBlock)
-        gneg[p0 + l] = make_float2((float)((double)(long long)acc[2 * l] * kFixInv), (float)((double)(long long)acc[2 * l + 1] * kFixInv));
+    for (int l = threadIdx.x; l < kTile && p0 + l < n; l += kBinBlock) {
+        const float2 hd = ghead[p0 + l];
+        g[p0 + l] = make_float2((float)((double)hd.x + (double)(long long)acc[2 * l] * kFixInv),
+                                (float)((double)hd.y + (double)(long long)acc[2 * l + 1] * kFixInv));
+    }
 }
 
 // fixed-order sum of the per-block loss partials (one block)
@@ -743,49 +740,18 @@ __global__ void __launch_bounds__(kBlock) k_loss_finish(const double* __restrict
     }
 }
 
-// ------------------------------------------------------------------ K4: deterministic scatter
-// g_j = head sum + sum over the row of j of a_{rev(e')} (theta_j - theta_{col(e')}) + negatives.
-// The tail forces are *pulled*: the force edge (i -> j) puts on its tail j is read by row j through
-// the reverse edge (j -> i), in CSR order, so the sum has one fixed order.  The negatives' sums
-// arrive in 64-bit fixed point (integer addition is associative) and are cleared here for the
+// ------------------------------------------------------------------ K4 (fallback): combine
+// g = head sum + fixed-point sum of tail and negative forces; clears the accumulators for the
 // next epoch.
-template <int LPR>
-__global__ void __launch_bounds__(kBlock) k_tail_pull(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
-                                                      const int32_t* __restrict__ rev, const float* __restrict__ coef,
-                                                      const float2* __restrict__ theta, const float2* __restrict__ ghead,
-                                                      unsigned long long* __restrict__ gfix, const float2* __restrict__ gneg,
-                                                      float2* __restrict__ g, int64_t n) {
-    constexpr int ROWS = kBlock / LPR;
-    const uint32_t lb = xcd_contiguous_block(blockIdx.x, gridDim.x);
-    const int64_t j = (int64_t)lb * ROWS + (threadIdx.x / LPR);
-    const int lane = threadIdx.x % LPR;
-    float ax = 0.f, ay = 0.f;
-    if (j < n) {
-        const float2 tj = theta[j];
-        for (int32_t e = row_ptr[j] + lane; e < row_ptr[j + 1]; e += LPR) {
-            const float2 ti = theta[col[e]];
-            const float a = coef[rev[e]];
-            ax = fmaf(a, tj.x - ti.x, ax);
-            ay = fmaf(a, tj.y - ti.y, ay);
-        }
-    }
-    ax = rowgroup_sum<LPR>(ax);
-    ay = rowgroup_sum<LPR>(ay);
-    if (lane == 0 && j < n) {
-        const float2 h = ghead[j];
-        double nx, ny;
-        if (gneg) {
-            const float2 v = gneg[j];
-            nx = (double)v.x;
-            ny = (double)v.y;
-        } else {
-            nx = (double)(long long)gfix[2 * j] * kFixInv;
-            ny = (double)(long long)gfix[2 * j + 1] * kFixInv;
-            gfix[2 * j] = 0ull;
-            gfix[2 * j + 1] = 0ull;
-        }
-        g[j] = make_float2((float)((double)h.x + (double)ax + nx), (float)((double)h.y + (double)ay + ny));
-    }
+__global__ void __launch_bounds__(kBlock) k_combine_fixed(const float2* __restrict__ ghead, unsigned long long* __restrict__ gfix,
+                                                          float2* __restrict__ g, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float2 h = ghead[i];
+    const double sx = (double)(long long)gfix[2 * i] * kFixInv, sy = (double)(long long)gfix[2 * i + 1] * kFixInv;
+    gfix[2 * i] = 0ull;
+    gfix[2 * i + 1] = 0ull;
+    g[i] = make_float2((float)((double)h.x + sx), (float)((double)h.y + sy));
 }
 
 // ------------------------------------------------------------------ K5: SGD step (Section 3.4)

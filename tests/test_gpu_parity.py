@@ -238,6 +238,21 @@ def test_empty_rows_empty_cluster_and_tiny_graphs(mode):
         assert np.all(nm.get_gradient() == 0)
 
 
+@pytest.mark.parametrize("mode", MODES)
+def test_directed_graph_without_reverse_edges(mode):
+    """The paper's kNN digraph is not symmetric; neither path may assume that it is."""
+    d = small_random(50, n=2000, groups=False, weights=False, s=5, M=5.0)
+    keep = np.random.default_rng(3).random(len(d["col_idx"])) < 0.6          # drop 40 % of the directed edges
+    rows = np.repeat(np.arange(d["n"]), np.diff(d["row_ptr"]))
+    d["col_idx"] = d["col_idx"][keep]
+    d["row_ptr"] = np.concatenate([[0], np.cumsum(np.bincount(rows[keep], minlength=d["n"]))]).astype(np.int32)
+    O = c_oracle.COracle(**d)
+    _, g_ref, _ = O.epoch(d["theta0"], 0)
+    with make_nomad(d, mode) as nm:
+        nm.epoch(0)
+        assert grad_err(nm.get_gradient(), g_ref) < GRAD_TOL
+
+
 def test_coincident_points_closed_form():
     """All rows equal: every q is 1, the loss is log(1+|M|) and no force acts (closed form, no oracle)."""
     d = small_random(30, groups=False, weights=False, s=5, M=5.0)
@@ -305,14 +320,6 @@ def test_errors_are_codes_not_crashes():
     bad(cluster_of=cl)
     grp = d["cluster_group"].copy(); grp[1] = -2
     bad(cluster_group=grp)
-    # asymmetric graph: fine for the atomic path, refused by the deterministic one
-    col = d["col_idx"].copy()
-    a0 = d["row_ptr"][0]
-    others = np.setdiff1d(np.arange(1, d["n"]), col[a0:d["row_ptr"][1]])
-    col[a0] = others[-1]
-    bad(col_idx=col)
-    with Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], 1, SCATTER_ATOMIC) as nm2:
-        nm2.set_graph(d["row_ptr"], col, d["weights"], d["cluster_of"], d["cluster_group"])
     # after a failed set_graph the context has no graph
     with pytest.raises(NomadError, match="ORDER"):
         nm.epoch(0)
