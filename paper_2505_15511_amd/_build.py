@@ -6,7 +6,7 @@ import subprocess
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
-LIB_PATH = os.path.join(_PKG, "libnomad.so")
+LIB_PATH = os.environ.get("NOMAD_LIBRARY_PATH") or os.path.join(_PKG, "libnomad.so")
 SOURCES = [os.path.join(_PKG, "csrc", "nomad.hip")]
 HEADERS = [os.path.join(_PKG, "csrc", "nomad_kernels.h"), os.path.join(_ROOT, "include", "nomad.h")]
 

@@ -51,7 +51,7 @@ struct nomad_ctx {
     bool binned = false;
     int n_wg = 0;
     uint32_t n_bins = 0, max_chunks = 0;
-    uint32_t *pool = nullptr, *chunk_bin = nullptr, *chunk_fill = nullptr, *pool_next = nullptr, *bin_count = nullptr,
+    uint32_t *pool = nullptr, *chunk_bin = nullptr, *chunk_fill = nullptr, *wg_pool_begin = nullptr, *bin_count = nullptr,
              *bin_start = nullptr, *bin_cursor = nullptr, *bin_chunks = nullptr;
     int32_t* wg_row_begin = nullptr;
     int* overflow = nullptr;
@@ -105,7 +105,7 @@ void free_graph(nomad_ctx* c) {
     dev_free(c->theta); dev_free(c->g); dev_free(c->ghead); dev_free(c->mu); dev_free(c->B); dev_free(c->cinfo);
     dev_free(c->A); dev_free(c->gfix); dev_free(c->loss_partial); dev_free(c->loss_out);
     dev_free(c->flags);
-    dev_free(c->pool); dev_free(c->chunk_bin); dev_free(c->chunk_fill); dev_free(c->pool_next); dev_free(c->bin_count);
+    dev_free(c->pool); dev_free(c->chunk_bin); dev_free(c->chunk_fill); dev_free(c->wg_pool_begin); dev_free(c->bin_count);
     dev_free(c->bin_start); dev_free(c->bin_cursor); dev_free(c->bin_chunks); dev_free(c->wg_row_begin);
     dev_free(c->overflow);
     c->binned = false;
@@ -174,7 +174,7 @@ void launch_edges(nomad_ctx* c, const EdgeArgs& a) {
 
 BinArgs bin_args(nomad_ctx* c) {
     BinArgs q{};
-    q.pool = c->pool; q.chunk_bin = c->chunk_bin; q.chunk_fill = c->chunk_fill; q.pool_next = c->pool_next;
+    q.pool = c->pool; q.chunk_bin = c->chunk_bin; q.chunk_fill = c->chunk_fill; q.wg_pool_begin = c->wg_pool_begin;
     q.max_chunks = c->max_chunks; q.n_bins = c->n_bins; q.wg_row_begin = c->wg_row_begin; q.overflow = c->overflow;
     return q;
 }
@@ -478,12 +478,12 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 per_cu = std::max(1, std::min(per_cu, atoi(knob)));
             c->n_wg = std::max(1, prop.multiProcessorCount) * per_cu;
             c->n_bins = n_bins;
-            const uint64_t want = (uint64_t)E * (uint64_t)(s + 1) / kChunk + (uint64_t)c->n_wg * n_bins + 1;
+            const uint64_t want = (uint64_t)E * (uint64_t)(s + 1) / kChunk + (uint64_t)c->n_wg * (n_bins + 1) + 1;
             if (want < (1ull << 31)) {
                 c->max_chunks = (uint32_t)want;
                 bool ok = dev_alloc(c, &c->pool, (size_t)c->max_chunks * kChunk * 3) == NOMAD_OK &&
                           dev_alloc(c, &c->chunk_bin, c->max_chunks) == NOMAD_OK && dev_alloc(c, &c->chunk_fill, c->max_chunks) == NOMAD_OK &&
-                          dev_alloc(c, &c->bin_chunks, c->max_chunks) == NOMAD_OK && dev_alloc(c, &c->pool_next, 1) == NOMAD_OK &&
+                          dev_alloc(c, &c->bin_chunks, c->max_chunks) == NOMAD_OK && dev_alloc(c, &c->wg_pool_begin, (size_t)c->n_wg + 1) == NOMAD_OK &&
                           dev_alloc(c, &c->bin_count, n_bins) == NOMAD_OK && dev_alloc(c, &c->bin_start, (size_t)n_bins + 1) == NOMAD_OK &&
                           dev_alloc(c, &c->bin_cursor, n_bins) == NOMAD_OK && dev_alloc(c, &c->wg_row_begin, (size_t)c->n_wg + 1) == NOMAD_OK &&
                           dev_alloc(c, &c->overflow, 1) == NOMAD_OK;
@@ -492,10 +492,12 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                     HTRY(hipMemsetAsync(c->overflow, 0, sizeof(int), st));
                     hipLaunchKernelGGL(k_wg_rows, dim3(blocks_for(c->n_wg + 1)), dim3(kBlock), 0, st, c->row_ptr, n, E, c->n_wg,
                                        c->wg_row_begin);
+                    hipLaunchKernelGGL(k_wg_pools, dim3(1), dim3(64), 0, st, c->row_ptr, c->wg_row_begin, c->n_wg, s + 1, n_bins,
+                                       c->wg_pool_begin);
                     c->binned = true;
                 } else {
                     (void)hipGetLastError();
-                    dev_free(c->pool); dev_free(c->chunk_bin); dev_free(c->chunk_fill); dev_free(c->bin_chunks); dev_free(c->pool_next);
+                    dev_free(c->pool); dev_free(c->chunk_bin); dev_free(c->chunk_fill); dev_free(c->bin_chunks); dev_free(c->wg_pool_begin);
                     dev_free(c->bin_count); dev_free(c->bin_start); dev_free(c->bin_cursor); dev_free(c->wg_row_begin);
                     dev_free(c->overflow);
                     c->err.clear();
@@ -545,14 +547,14 @@ int nomad_epoch(nomad_ctx* c, int32_t t) {
           launch_edges<kModeAtomic>(c, a); }
     } else if (c->binned) {
         { Timed tm(c, NOMAD_K_EDGES);
-          hipLaunchKernelGGL(k_bin_reset, dim3(blocks_for(c->n_bins)), dim3(kBlock), 0, c->stream, c->bin_count, c->n_bins, c->pool_next);
+          hipLaunchKernelGGL(k_bin_reset, dim3(blocks_for(std::max(c->max_chunks, c->n_bins))), dim3(kBlock), 0, c->stream, c->bin_count,
+                             c->n_bins, c->chunk_bin, c->max_chunks);
           launch_edges_binned(c, a); }
         { Timed tm(c, NOMAD_K_BINS);
           const dim3 cg(blocks_for(c->max_chunks));
-          hipLaunchKernelGGL(k_chunk_census, cg, dim3(kBlock), 0, c->stream, c->chunk_bin, c->pool_next, c->max_chunks, c->bin_count);
+          hipLaunchKernelGGL(k_chunk_census, cg, dim3(kBlock), 0, c->stream, c->chunk_bin, c->max_chunks, c->bin_count);
           hipLaunchKernelGGL(k_bin_scan, dim3(1), dim3(kBinBlock), 0, c->stream, c->bin_count, c->n_bins, c->bin_start, c->bin_cursor);
-          hipLaunchKernelGGL(k_chunk_lists, cg, dim3(kBlock), 0, c->stream, c->chunk_bin, c->pool_next, c->max_chunks, c->bin_cursor,
-                             c->bin_chunks); }
+          hipLaunchKernelGGL(k_chunk_lists, cg, dim3(kBlock), 0, c->stream, c->chunk_bin, c->max_chunks, c->bin_cursor, c->bin_chunks); }
         { Timed tm(c, NOMAD_K_TILES);
           hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 * kTile, c->stream,
                              c->pool, c->chunk_fill, c->bin_start, c->bin_chunks, c->ghead, c->g, n); }

@@ -485,10 +485,12 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
 //
 //   k_edges_binned   persistent workgroups, each owning a contiguous, edge-balanced range of rows.
 //                    Every (workgroup, tile) pair appends 12-byte records (local index, force x, y)
-//                    to its own chain of kChunk-record chunks taken from one global pool; the chain
-//                    state lives in LDS, a global atomic is spent only per new chunk.  Work is done
-//                    in rounds of one edge per lane with workgroup barriers, so that appends never
-//                    wait on one another (no spin loops).
+//                    to its own chain of kChunk-record chunks.  A workgroup takes chunks from a
+//                    private range of the pool, sized at set-up for the records its rows can emit
+//                    (edges * (s+1) / kChunk, plus one partly filled chunk per tile), so handing out
+//                    a chunk is an LDS operation: no global atomics anywhere.  Work is done in rounds
+//                    of one edge per lane with workgroup barriers, so that appends never wait on one
+//                    another (no spin loops).
 //   k_chunk_*        bucket the chunks by tile (tiny).
 //   k_tile_accumulate one workgroup per tile adds its records into 2 x 64-bit fixed-point
 //                    accumulators per point in LDS.  Integer addition is associative, so the result
@@ -505,11 +507,11 @@ struct BinArgs {
     uint32_t* pool;               // [max_chunks][kChunk][3]
     uint32_t* chunk_bin;          // [max_chunks] tile of each chunk
     uint32_t* chunk_fill;         // [max_chunks] records in each chunk
-    uint32_t* pool_next;          // chunks handed out so far
+    const uint32_t* wg_pool_begin;// [gridDim.x + 1] each workgroup's private range of chunk ids
     uint32_t max_chunks;
     uint32_t n_bins;
     const int32_t* wg_row_begin;  // [gridDim.x + 1]
-    int* overflow;                // set if the pool bound were ever exceeded (it cannot be)
+    int* overflow;                // set if a workgroup's chunk range were ever exceeded (it cannot be)
 };
 
 template <int S>
@@ -523,10 +525,12 @@ __global__ void __launch_bounds__(kBinBlock, 8) k_edges_binned(const EdgeArgs P,
     uint32_t* base = lds_bins + 3 * B;// first chunk allocated this round
     __shared__ int next_row;
     __shared__ int any_active[2];
+    __shared__ uint32_t pool_cursor;
     const int tid = threadIdx.x, lane = tid % LPR;
     const int32_t r1 = Q.wg_row_begin[blockIdx.x + 1];
+    const uint32_t pool_end = min(Q.wg_pool_begin[blockIdx.x + 1], Q.max_chunks);
     for (uint32_t b = tid; b < B; b += kBinBlock) { fill[b] = kChunk; chunk[b] = kNoChunk; cnt[b] = 0; base[b] = 0; }
-    if (tid == 0) { next_row = Q.wg_row_begin[blockIdx.x]; any_active[0] = 0; any_active[1] = 0; }
+    if (tid == 0) { next_row = Q.wg_row_begin[blockIdx.x]; any_active[0] = 0; any_active[1] = 0; pool_cursor = Q.wg_pool_begin[blockIdx.x]; }
     __syncthreads();
 
     int32_t row = -1, e_next = 0, e_end = 0;
@@ -578,11 +582,11 @@ __global__ void __launch_bounds__(kBinBlock, 8) k_edges_binned(const EdgeArgs P,
             const uint32_t f = fill[b];
             if (f + c > (uint32_t)kChunk) {
                 const uint32_t k = (f + c - 1) / kChunk;
-                const uint32_t nb = atomicAdd(Q.pool_next, k);
+                const uint32_t nb = atomicAdd(&pool_cursor, k);
                 base[b] = nb;
-                if (nb + k > Q.max_chunks) *Q.overflow = 1;
-                if (chunk[b] < Q.max_chunks) Q.chunk_fill[chunk[b]] = kChunk;   // kNoChunk is above any valid id
-                for (uint32_t x = 0; x < k && nb + x < Q.max_chunks; ++x) {
+                if (nb + k > pool_end) *Q.overflow = 1;
+                if (chunk[b] < pool_end) Q.chunk_fill[chunk[b]] = kChunk;   // kNoChunk is above any valid id
+                for (uint32_t x = 0; x < k && nb + x < pool_end; ++x) {
                     Q.chunk_bin[nb + x] = b;
                     Q.chunk_fill[nb + x] = kChunk;   // the last one is corrected when it is closed
                 }
@@ -598,7 +602,7 @@ __global__ void __launch_bounds__(kBinBlock, 8) k_edges_binned(const EdgeArgs P,
                 uint32_t ch, off;
                 if (pos < (uint32_t)kChunk) { ch = chunk[b]; off = pos; }
                 else { ch = base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
-                if (ch < Q.max_chunks) {
+                if (ch < pool_end) {
                     uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
                     dst[0] = dst_pt[k] & (kTile - 1);
                     dst[1] = __float_as_uint(fx[k]);
@@ -624,7 +628,7 @@ __global__ void __launch_bounds__(kBinBlock, 8) k_edges_binned(const EdgeArgs P,
     }
     // close the open chunks
     for (uint32_t b = tid; b < B; b += kBinBlock)
-        if (chunk[b] < Q.max_chunks) Q.chunk_fill[chunk[b]] = fill[b];   // kNoChunk is above any valid id
+        if (chunk[b] < pool_end) Q.chunk_fill[chunk[b]] = fill[b];   // kNoChunk is above any valid id
 }
 
 // first row of each persistent workgroup: rows split so that every workgroup gets ~E/W edges
@@ -641,16 +645,30 @@ __global__ void k_wg_rows(const int32_t* __restrict__ row_ptr, int64_t n, int64_
     wg_row_begin[w] = (int32_t)lo;
 }
 
-__global__ void k_bin_reset(uint32_t* __restrict__ bin_count, uint32_t B, uint32_t* pool_next) {
-    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < B) bin_count[b] = 0;
-    if (b == 0) *pool_next = 0;
+// private chunk-id range of each workgroup: enough for every record its rows can emit, plus one
+// partly filled chunk per tile (one thread: W is a few hundred)
+__global__ void k_wg_pools(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ wg_row_begin, int W, int records_per_edge,
+                           uint32_t n_bins, uint32_t* __restrict__ wg_pool_begin) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    uint64_t run = 0;
+    for (int w = 0; w < W; ++w) {
+        wg_pool_begin[w] = (uint32_t)run;
+        const uint64_t edges = (uint64_t)(row_ptr[wg_row_begin[w + 1]] - row_ptr[wg_row_begin[w]]);
+        run += edges * (uint64_t)records_per_edge / kChunk + n_bins + 1;
+    }
+    wg_pool_begin[W] = (uint32_t)run;
 }
 
-__global__ void k_chunk_census(const uint32_t* __restrict__ chunk_bin, const uint32_t* __restrict__ pool_next, uint32_t max_chunks,
-                               uint32_t* __restrict__ bin_count) {
+// every chunk id starts an epoch marked unused
+__global__ void k_bin_reset(uint32_t* __restrict__ bin_count, uint32_t B, uint32_t* __restrict__ chunk_bin, uint32_t max_chunks) {
+    const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
+    if (x < B) bin_count[x] = 0;
+    if (x < max_chunks) chunk_bin[x] = kNoChunk;
+}
+
+__global__ void k_chunk_census(const uint32_t* __restrict__ chunk_bin, uint32_t max_chunks, uint32_t* __restrict__ bin_count) {
     const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c < min(*pool_next, max_chunks)) atomicAdd(&bin_count[chunk_bin[c]], 1u);
+    if (c < max_chunks && chunk_bin[c] != kNoChunk) atomicAdd(&bin_count[chunk_bin[c]], 1u);
 }
 
 // exclusive scan of the per-tile chunk counts (one block; B is a few thousand)
@@ -673,10 +691,10 @@ __global__ void __launch_bounds__(kBinBlock) k_bin_scan(const uint32_t* __restri
     for (uint32_t b = b0; b < b1; ++b) { bin_start[b] = run; bin_cursor[b] = run; run += bin_count[b]; }
 }
 
-__global__ void k_chunk_lists(const uint32_t* __restrict__ chunk_bin, const uint32_t* __restrict__ pool_next, uint32_t max_chunks,
-                              uint32_t* __restrict__ bin_cursor, uint32_t* __restrict__ bin_chunks) {
+__global__ void k_chunk_lists(const uint32_t* __restrict__ chunk_bin, uint32_t max_chunks, uint32_t* __restrict__ bin_cursor,
+                              uint32_t* __restrict__ bin_chunks) {
     const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c < min(*pool_next, max_chunks)) bin_chunks[atomicAdd(&bin_cursor[chunk_bin[c]], 1u)] = c;
+    if (c < max_chunks && chunk_bin[c] != kNoChunk) bin_chunks[atomicAdd(&bin_cursor[chunk_bin[c]], 1u)] = c;
 }
 
 __global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const uint32_t* __restrict__ pool, const uint32_t* __restrict__ chunk_fill,

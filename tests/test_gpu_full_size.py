@@ -1,0 +1,150 @@
+"""Parity at the benchmark configurations' full sizes, in the launch configuration bench.py times
+(deterministic mode, device-resident graph)."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import c_oracle
+from paper_2505_15511_amd import Nomad, SCATTER_ATOMIC, SCATTER_DETERMINISTIC, workloads
+from tests.np_metric import neighbourhood_preservation
+
+pytestmark = pytest.mark.gpu
+GRAD_TOL = 1e-5
+LOSS_TOL = 1e-5
+NP_TOL = 0.01
+
+
+def note(msg):
+    print(msg, flush=True)
+
+
+def grad_err(g, ref):
+    return np.abs(np.asarray(g, dtype=np.float64) - ref).max() / np.abs(ref).max()
+
+
+def device_nomad(w, mode=SCATTER_DETERMINISTIC):
+    dev = "cuda"
+    nm = Nomad(w.n, w.n_clusters, w.n_neg, w.noise_count, w.n_epochs, w.lr0, w.seed, mode)
+    nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None, w.cluster_of.to(dev),
+                 None if w.cluster_group is None else w.cluster_group.to(dev))
+    nm.set_embedding(w.theta0.to(dev))
+    return nm
+
+
+def train_both(w, mode=SCATTER_DETERMINISTIC):
+    """Full training on the GPU and in the oracle from the same theta_0 with the same negatives."""
+    d = w.numpy()
+    O = c_oracle.COracle(**d)
+    t0 = time.time()
+    th_ref, curve_ref = O.train(d["theta0"])
+    t_or = time.time() - t0
+    with device_nomad(w, mode) as nm:
+        t0 = time.time()
+        curve = []
+        for t in range(w.n_epochs):
+            if t % 25 == 0:
+                curve.append((t, nm.loss(t)))
+            nm.epoch(t)
+        th = nm.get_embedding()
+        t_gpu = time.time() - t0
+    note(f"  {w.name}: oracle {t_or:.1f} s, gpu {t_gpu:.1f} s")
+    return th, th_ref, curve, curve_ref
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_full_training_preserves_neighbourhoods_like_the_oracle_gmm(cfg):
+    note(f"full training config {cfg}")
+    w = workloads.make_config(cfg, device="cuda" if cfg == 2 else "cpu")
+    th, th_ref, curve, curve_ref = train_both(w)
+    rng = np.random.default_rng(cfg)
+    q = np.arange(w.n) if w.n <= 20000 else rng.choice(w.n, 10000, replace=False)
+    ref = w.out_nbrs.cpu().numpy()
+    np_gpu = neighbourhood_preservation(th, ref, 15, q)
+    np_or = neighbourhood_preservation(th_ref, ref, 15, q)
+    note(f"  NP@15 gpu {np_gpu:.4f} oracle {np_or:.4f}; loss curve gpu {curve[:3]} oracle {curve_ref[[0, 25, 50]]}")
+    assert abs(np_gpu - np_or) < NP_TOL
+    assert np_gpu > 10 * 15 / w.n                      # far above chance
+    assert abs(curve[0][1] - curve_ref[0]) < 1e-6 * curve_ref[0]
+    for t, L in curve[1:]:     # trajectories are chaotic point-wise; the loss curves stay together
+        assert abs(L - curve_ref[t]) < 0.02 * curve_ref[t]
+
+
+def test_full_training_config3_matches_the_oracle_statistically():
+    note("full training config 3 (1M points, 200 epochs)")
+    w = workloads.make_config(3, device="cuda")
+    th, th_ref, curve, curve_ref = train_both(w)
+    q = np.random.default_rng(3).choice(w.n, 10000, replace=False)
+    ref = w.out_nbrs.cpu().numpy()
+    np_gpu = neighbourhood_preservation(th, ref, 15, q)
+    np_or = neighbourhood_preservation(th_ref, ref, 15, q)
+    note(f"  NP@15 gpu {np_gpu:.4f} oracle {np_or:.4f}")
+    assert abs(np_gpu - np_or) < NP_TOL
+    assert abs(curve[-1][1] - curve_ref[curve[-1][0]]) < 0.02 * curve_ref[curve[-1][0]]
+
+
+def test_config4_one_epoch_and_mid_run_against_the_oracle():
+    """10 M points, 299 M edges: negatives on sampled edge ranges, the full gradient of epoch 0, the
+    loss after it, and the gradient of a later epoch restarted from the GPU's embedding."""
+    note("config 4 full size")
+    w = workloads.make_config(4, device="cuda")
+    d = w.numpy()
+    O = c_oracle.COracle(**d)
+    E = O.n_edges
+    with device_nomad(w) as nm:
+        for e0 in np.random.default_rng(4).integers(0, E - 30000, 100):
+            assert np.array_equal(nm.get_negatives(2, int(e0), int(e0) + 30000), O.negatives(2, int(e0), int(e0) + 30000))
+        note("  negatives ok")
+        t0 = time.time()
+        th1, g_ref, _ = O.epoch(d["theta0"], 0)
+        note(f"  oracle epoch {time.time() - t0:.1f} s")
+        nm.epoch(0)
+        err = grad_err(nm.get_gradient(), g_ref)
+        L_ref, _ = O.loss_and_grad(th1, 1, want_grad=False)
+        L = nm.loss(1)
+        note(f"  epoch 0: grad err {err:.2e}, loss {L:.8f} vs {L_ref:.8f}")
+        assert err < GRAD_TOL and abs(L - L_ref) < LOSS_TOL * L_ref
+        for t in range(1, 12):
+            nm.epoch(t)
+        theta = nm.get_embedding()
+        nm.epoch(12)
+        g = nm.get_gradient()
+        _, g_ref = O.loss_and_grad(theta, 12)
+        err = grad_err(g, g_ref)
+        note(f"  epoch 12: grad err {err:.2e}")
+        assert err < GRAD_TOL
+    # the atomic path on the same inputs
+    with device_nomad(w, SCATTER_ATOMIC) as nm:
+        nm.set_embedding(theta)
+        nm.epoch(12)
+        err = grad_err(nm.get_gradient(), g_ref)
+        note(f"  epoch 12, atomic path: grad err {err:.2e}")
+        assert err < GRAD_TOL
+
+
+@pytest.mark.parametrize("scale", [0.1])
+def test_config5_sampled_gradient_rows(scale):
+    """Config 5's shape (every cluster its own group, s = 2, |M| = 5, k = 10) at a size whose full
+    mean-field sum the host cannot afford: gradient rows of sampled points, each computed by the
+    oracle from every edge that touches the point."""
+    note(f"config 5 at scale {scale}")
+    w = workloads.make_config(5, scale=scale, device="cuda")
+    d = w.numpy()
+    O = c_oracle.COracle(**d)
+    rng = np.random.default_rng(5)
+    pts = np.unique(np.concatenate([rng.choice(w.n, 1500, replace=False), [0, w.n - 1]]))
+    with device_nomad(w) as nm:
+        E = nm.num_edges()
+        assert np.array_equal(nm.get_negatives(1, E // 2, E // 2 + 100000), O.negatives(1, E // 2, E // 2 + 100000))
+        for t in range(3):
+            nm.epoch(t)
+        theta = nm.get_embedding()
+        nm.epoch(3)
+        g = nm.get_gradient()
+    t0 = time.time()
+    g_ref = O.grad_at(theta, 3, pts)
+    note(f"  oracle rows {time.time() - t0:.1f} s")
+    err = np.abs(g[pts].astype(np.float64) - g_ref).max() / np.abs(g_ref).max()
+    note(f"  grad err on {len(pts)} sampled rows {err:.2e} (max |g| {np.abs(g_ref).max():.3e})")
+    assert err < GRAD_TOL
