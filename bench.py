@@ -50,6 +50,24 @@ def algorithmic_bytes(kernel, n, E, s, R, grouped, weighted, deterministic):
     raise KeyError(kernel)
 
 
+def copy_probe_gbs(torch, gib=4, steps=10):
+    """Streaming copy of `gib` GiB with the library's probe kernel: read + write GB/s."""
+    from paper_2505_15511_amd import binding
+    src = torch.ones(gib << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    binding.copy_probe(dst, src)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(steps):
+        binding.copy_probe(dst, src)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / steps
+    nbytes = src.numel() * 4
+    return dict(probe="copy", bytes_read=nbytes, bytes_written=nbytes, ms=ms, gbs_read_plus_write=2 * nbytes / ms / 1e6)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -60,6 +78,8 @@ def main():
     ap.add_argument("--mode", choices=["det", "atomic"], default="det")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--groups", type=int, default=None, help="deal the clusters into this many groups")
+    ap.add_argument("--probe", choices=["copy"], default=None,
+                    help="run only the streaming-copy probe (counter calibration / practical HBM ceiling)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build covers one GPU's share of the path; run with --gpus 1", file=sys.stderr)
@@ -73,6 +93,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = "cuda"
+    if args.probe == "copy":
+        print(json.dumps(copy_probe_gbs(torch, steps=args.steps)))
+        return
     t0 = time.time()
     w = workloads.make_config(args.config, scale=args.scale, device=dev if args.config >= 3 else "cpu",
                               n_groups=args.groups)
@@ -140,6 +163,7 @@ def main():
         "setup_s": round(setup_s, 3), "generate_s": round(gen_s, 3),
         "roofline": roofline,
     }
+    out["copy_probe_gbs"] = round(copy_probe_gbs(torch, gib=2, steps=5)["gbs_read_plus_write"], 1)
 
     if not args.no_cpu_baseline:
         from oracle import c_oracle

@@ -153,6 +153,14 @@ int nomad_profile(nomad_ctx* ctx, int enable);
  * timing was switched on. */
 int nomad_profile_read(nomad_ctx* ctx, int kind, double* total_ms, int64_t* launches);
 
+/*
+ * Bandwidth probe: enqueue one streaming device-to-device copy of `bytes` bytes (a multiple of 16,
+ * both pointers 16-byte aligned, device memory of the current device) on `stream`.  Reads `bytes`
+ * and writes `bytes`: the kernel of known traffic used to calibrate profiler byte counters and to
+ * measure the practical HBM ceiling next to the epoch kernels.  Returns without waiting.
+ */
+int nomad_copy_probe(void* dst, const void* src, uint64_t bytes, void* stream);
+
 /* Text of the last error of this context ("" if none).  Valid until the next call on it. */
 const char* nomad_last_error(const nomad_ctx* ctx);
 

@@ -22,7 +22,8 @@ ERRORS = {-1: "NOMAD_E_INVALID_ARG", -2: "NOMAD_E_BAD_GRAPH", -3: "NOMAD_E_ORDER
 
 EXPORTS = ["nomad_create", "nomad_destroy", "nomad_set_graph", "nomad_set_embedding", "nomad_epoch", "nomad_loss",
            "nomad_get_embedding", "nomad_get_gradient", "nomad_get_negatives", "nomad_get_means",
-           "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error"]
+           "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error",
+           "nomad_copy_probe"]
 
 
 class NomadConfig(C.Structure):
@@ -67,6 +68,7 @@ def load_library():
     lib.nomad_num_edges.restype = i64
     lib.nomad_profile.argtypes = [vp, C.c_int]
     lib.nomad_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.nomad_copy_probe.argtypes = [vp, vp, C.c_uint64, vp]
     lib.nomad_last_error.argtypes = [vp]
     lib.nomad_last_error.restype = C.c_char_p
     _lib = lib
@@ -92,6 +94,19 @@ def _marshal(x, np_dtype, count=None):
     if count is not None and a.size != count:
         raise ValueError(f"expected {count} elements, got {a.size}")
     return a.ctypes.data_as(C.c_void_p), NOMAD_HOST, a
+
+
+def copy_probe(dst, src, stream=None):
+    """Enqueue the library's streaming copy kernel between two device tensors of equal size."""
+    import torch
+    lib = load_library()
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes and src.is_cuda and dst.is_cuda
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    rc = lib.nomad_copy_probe(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes, C.c_void_p(stream or None))
+    if rc:
+        raise NomadError(rc, "nomad_copy_probe")
 
 
 class Nomad:
