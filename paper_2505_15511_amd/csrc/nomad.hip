@@ -51,9 +51,9 @@ struct nomad_ctx {
     bool binned = false;
     int n_wg = 0;
     uint32_t n_bins = 0, max_chunks = 0;
-    uint32_t *pool = nullptr, *chunk_bin = nullptr, *chunk_fill = nullptr, *wg_pool_begin = nullptr, *bin_count = nullptr,
-             *bin_start = nullptr, *bin_cursor = nullptr, *bin_chunks = nullptr;
-    int32_t* wg_row_begin = nullptr;
+    int tile_bits = kMaxTileBits;
+    uint32_t *pool = nullptr, *chunk_prev = nullptr, *chain_head = nullptr, *chain_fill = nullptr, *wg_pool_begin = nullptr;
+    int32_t* head = nullptr;
     int* overflow = nullptr;
     double *loss_partial = nullptr, *loss_out = nullptr;
     uint32_t edge_grid = 0;
@@ -105,9 +105,8 @@ void free_graph(nomad_ctx* c) {
     dev_free(c->theta); dev_free(c->g); dev_free(c->ghead); dev_free(c->mu); dev_free(c->B); dev_free(c->cinfo);
     dev_free(c->A); dev_free(c->gfix); dev_free(c->loss_partial); dev_free(c->loss_out);
     dev_free(c->flags);
-    dev_free(c->pool); dev_free(c->chunk_bin); dev_free(c->chunk_fill); dev_free(c->wg_pool_begin); dev_free(c->bin_count);
-    dev_free(c->bin_start); dev_free(c->bin_cursor); dev_free(c->bin_chunks); dev_free(c->wg_row_begin);
-    dev_free(c->overflow);
+    dev_free(c->pool); dev_free(c->chunk_prev); dev_free(c->chain_head); dev_free(c->chain_fill); dev_free(c->wg_pool_begin);
+    dev_free(c->head); dev_free(c->overflow);
     c->binned = false;
     c->has_graph = c->has_theta = c->has_grad = false;
     c->E = 0;
@@ -174,23 +173,24 @@ void launch_edges(nomad_ctx* c, const EdgeArgs& a) {
 
 BinArgs bin_args(nomad_ctx* c) {
     BinArgs q{};
-    q.pool = c->pool; q.chunk_bin = c->chunk_bin; q.chunk_fill = c->chunk_fill; q.wg_pool_begin = c->wg_pool_begin;
-    q.max_chunks = c->max_chunks; q.n_bins = c->n_bins; q.wg_row_begin = c->wg_row_begin; q.overflow = c->overflow;
+    q.head = c->head; q.pool = c->pool; q.chunk_prev = c->chunk_prev; q.chain_head = c->chain_head; q.chain_fill = c->chain_fill;
+    q.wg_pool_begin = c->wg_pool_begin; q.ghead = c->ghead; q.E = c->E; q.max_chunks = c->max_chunks; q.n_bins = c->n_bins;
+    q.tile_bits = c->tile_bits; q.overflow = c->overflow;
     return q;
 }
 
-size_t binned_lds_bytes(uint32_t n_bins) { return (size_t)n_bins * 4 * sizeof(uint32_t); }
+constexpr size_t kMaxLdsBytes = 160 * 1024 - 256;   // per workgroup on gfx950, less the kernels' static LDS
 
 template <int S>
 int prepare_binned_kernel(nomad_ctx* c) {
     HIP_TRY(c, hipFuncSetAttribute((const void*)k_edges_binned<S>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)binned_lds_bytes(c->n_bins)));
+                                   (int)binned_lds_bytes(c->n_bins, S)));
     return NOMAD_OK;
 }
 
 int prepare_binned(nomad_ctx* c) {
     HIP_TRY(c, hipFuncSetAttribute((const void*)k_tile_accumulate, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)(sizeof(unsigned long long) * 2 * kTile)));
+                                   (int)(sizeof(unsigned long long) * 2 << c->tile_bits)));
     switch (c->cfg.n_neg) {
         case 0: return prepare_binned_kernel<0>(c);
         case 1: return prepare_binned_kernel<1>(c); case 2: return prepare_binned_kernel<2>(c);
@@ -204,7 +204,7 @@ int prepare_binned(nomad_ctx* c) {
 void launch_edges_binned(nomad_ctx* c, const EdgeArgs& a) {
     const BinArgs q = bin_args(c);
     const dim3 grid(c->n_wg), block(kBinBlock);
-    const size_t lds = binned_lds_bytes(c->n_bins);
+    const size_t lds = binned_lds_bytes(c->n_bins, c->cfg.n_neg);
     switch (c->cfg.n_neg) {
 #define NOMAD_CASE(S) case S: hipLaunchKernelGGL((k_edges_binned<S>), grid, block, lds, c->stream, a, q); break;
         NOMAD_CASE(0) NOMAD_CASE(1) NOMAD_CASE(2) NOMAD_CASE(3) NOMAD_CASE(4) NOMAD_CASE(5) NOMAD_CASE(6) NOMAD_CASE(7) NOMAD_CASE(8)
@@ -466,42 +466,50 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
     TRY(dev_alloc(c, &c->loss_out, 1));
     if (c->cfg.scatter_mode == NOMAD_SCATTER_DETERMINISTIC) {
         TRY(dev_alloc(c, &c->ghead, (size_t)n));
-        // Binned scatter of the tail and negative forces: needs a compile-time s and a tile table
-        // that fits LDS; if its record pool cannot be allocated, fixed-point global atomics remain
+        // Binned scatter of the tail and negative forces: needs a compile-time s and per-tile tables
+        // that fit LDS; if its record pool cannot be allocated, fixed-point global atomics remain
         // as the fallback.
-        const uint32_t n_bins = (uint32_t)((n + kTile - 1) / kTile);
-        if (s <= 8 && E > 0 && binned_lds_bytes(n_bins) <= 144 * 1024) {
+        int tile_bits = kMinTileBits;   // about a thousand tiles when n allows, never above 8192 points a tile
+        while (tile_bits < kMaxTileBits && (n >> tile_bits) > 1024) ++tile_bits;
+        const uint32_t n_bins = (uint32_t)((n + ((int64_t)1 << tile_bits) - 1) >> tile_bits);
+        if (s <= 8 && E > 0 && n_bins <= (uint32_t)kMaxBinsPerThread * kBinBlock && binned_lds_bytes(n_bins, s) <= kMaxLdsBytes &&
+            !getenv("NOMAD_NO_BINNING")) {
             hipDeviceProp_t prop;
             HTRY(hipGetDeviceProperties(&prop, c->cfg.device));
-            int per_cu = binned_lds_bytes(n_bins) <= 72 * 1024 ? 2 : 1;
-            if (const char* knob = getenv("NOMAD_WG_PER_CU"))   // tuning knob: persistent workgroups per compute unit
-                per_cu = std::max(1, std::min(per_cu, atoi(knob)));
-            c->n_wg = std::max(1, prop.multiProcessorCount) * per_cu;
+            c->n_wg = std::max(1, prop.multiProcessorCount);   // one persistent workgroup per compute unit
             c->n_bins = n_bins;
-            const uint64_t want = (uint64_t)E * (uint64_t)(s + 1) / kChunk + (uint64_t)c->n_wg * (n_bins + 1) + 1;
-            if (want < (1ull << 31)) {
+            c->tile_bits = tile_bits;
+            unsigned long long* total_dev = nullptr;
+            unsigned long long want = 0;
+            bool ok = dev_alloc(c, &c->wg_pool_begin, (size_t)c->n_wg + 1) == NOMAD_OK && dev_alloc(c, &total_dev, 1) == NOMAD_OK;
+            if (ok) {
+                hipLaunchKernelGGL(k_wg_pools, dim3(1), dim3(64), 0, st, E, c->n_wg, s + 1, n_bins, c->wg_pool_begin, total_dev);
+                ok = hipMemcpyAsync(&want, total_dev, sizeof(want), hipMemcpyDeviceToHost, st) == hipSuccess &&
+                     hipStreamSynchronize(st) == hipSuccess;
+            }
+            dev_free(total_dev);
+            if (ok && want < (1ull << 31)) {
                 c->max_chunks = (uint32_t)want;
-                bool ok = dev_alloc(c, &c->pool, (size_t)c->max_chunks * kChunk * 3) == NOMAD_OK &&
-                          dev_alloc(c, &c->chunk_bin, c->max_chunks) == NOMAD_OK && dev_alloc(c, &c->chunk_fill, c->max_chunks) == NOMAD_OK &&
-                          dev_alloc(c, &c->bin_chunks, c->max_chunks) == NOMAD_OK && dev_alloc(c, &c->wg_pool_begin, (size_t)c->n_wg + 1) == NOMAD_OK &&
-                          dev_alloc(c, &c->bin_count, n_bins) == NOMAD_OK && dev_alloc(c, &c->bin_start, (size_t)n_bins + 1) == NOMAD_OK &&
-                          dev_alloc(c, &c->bin_cursor, n_bins) == NOMAD_OK && dev_alloc(c, &c->wg_row_begin, (size_t)c->n_wg + 1) == NOMAD_OK &&
-                          dev_alloc(c, &c->overflow, 1) == NOMAD_OK;
+                const size_t chains = (size_t)c->n_wg * n_bins;
+                ok = dev_alloc(c, &c->pool, (size_t)c->max_chunks * kChunk * 3) == NOMAD_OK &&
+                     dev_alloc(c, &c->chunk_prev, c->max_chunks) == NOMAD_OK && dev_alloc(c, &c->chain_head, chains) == NOMAD_OK &&
+                     dev_alloc(c, &c->chain_fill, chains) == NOMAD_OK && dev_alloc(c, &c->head, (size_t)E) == NOMAD_OK &&
+                     dev_alloc(c, &c->overflow, 1) == NOMAD_OK;
                 if (ok) ok = prepare_binned(c) == NOMAD_OK;
                 if (ok) {
                     HTRY(hipMemsetAsync(c->overflow, 0, sizeof(int), st));
-                    hipLaunchKernelGGL(k_wg_rows, dim3(blocks_for(c->n_wg + 1)), dim3(kBlock), 0, st, c->row_ptr, n, E, c->n_wg,
-                                       c->wg_row_begin);
-                    hipLaunchKernelGGL(k_wg_pools, dim3(1), dim3(64), 0, st, c->row_ptr, c->wg_row_begin, c->n_wg, s + 1, n_bins,
-                                       c->wg_pool_begin);
+                    hipLaunchKernelGGL(k_edge_heads, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->row_ptr, n, c->head);
+                    hipLaunchKernelGGL(k_zero_f2, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->ghead, n);
                     c->binned = true;
-                } else {
-                    (void)hipGetLastError();
-                    dev_free(c->pool); dev_free(c->chunk_bin); dev_free(c->chunk_fill); dev_free(c->bin_chunks); dev_free(c->wg_pool_begin);
-                    dev_free(c->bin_count); dev_free(c->bin_start); dev_free(c->bin_cursor); dev_free(c->wg_row_begin);
-                    dev_free(c->overflow);
-                    c->err.clear();
                 }
+            } else {
+                ok = false;
+            }
+            if (!ok) {
+                (void)hipGetLastError();
+                dev_free(c->pool); dev_free(c->chunk_prev); dev_free(c->chain_head); dev_free(c->chain_fill); dev_free(c->wg_pool_begin);
+                dev_free(c->head); dev_free(c->overflow);
+                c->err.clear();
             }
         }
         if (!c->binned) {
@@ -547,17 +555,10 @@ int nomad_epoch(nomad_ctx* c, int32_t t) {
           launch_edges<kModeAtomic>(c, a); }
     } else if (c->binned) {
         { Timed tm(c, NOMAD_K_EDGES);
-          hipLaunchKernelGGL(k_bin_reset, dim3(blocks_for(std::max(c->max_chunks, c->n_bins))), dim3(kBlock), 0, c->stream, c->bin_count,
-                             c->n_bins, c->chunk_bin, c->max_chunks);
           launch_edges_binned(c, a); }
-        { Timed tm(c, NOMAD_K_BINS);
-          const dim3 cg(blocks_for(c->max_chunks));
-          hipLaunchKernelGGL(k_chunk_census, cg, dim3(kBlock), 0, c->stream, c->chunk_bin, c->max_chunks, c->bin_count);
-          hipLaunchKernelGGL(k_bin_scan, dim3(1), dim3(kBinBlock), 0, c->stream, c->bin_count, c->n_bins, c->bin_start, c->bin_cursor);
-          hipLaunchKernelGGL(k_chunk_lists, cg, dim3(kBlock), 0, c->stream, c->chunk_bin, c->max_chunks, c->bin_cursor, c->bin_chunks); }
         { Timed tm(c, NOMAD_K_TILES);
-          hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 * kTile, c->stream,
-                             c->pool, c->chunk_fill, c->bin_start, c->bin_chunks, c->ghead, c->g, n); }
+          hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 << c->tile_bits,
+                             c->stream, bin_args(c), (uint32_t)c->n_wg, c->g, n); }
     } else {
         { Timed tm(c, NOMAD_K_EDGES);
           launch_edges<kModeDet>(c, a); }

@@ -479,264 +479,295 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
 
 // ------------------------------------------------------------------ K3 + K4, binned: the fast deterministic path
 // Global atomics run at a fixed ~21 G/s on this GPU whatever the locality, far too slow for the
-// E*s negative forces of an epoch.  Instead the edge pass *bins* every negative's force by the
-// destination's tile of kTile points and a second kernel accumulates each tile in LDS
-// (a segmented sum over destination tiles):
+// E*(s+1) forces an epoch sends to tails and negatives.  Instead the edge pass *bins* every such
+// force by the destination's tile of 2^tile_bits points and a second kernel accumulates each tile
+// in LDS (a segmented sum over destination tiles):
 //
-//   k_edges_binned   persistent workgroups, each owning a contiguous, edge-balanced range of rows.
-//                    Every (workgroup, tile) pair appends 12-byte records (local index, force x, y)
-//                    to its own chain of kChunk-record chunks.  A workgroup takes chunks from a
-//                    private range of the pool, sized at set-up for the records its rows can emit
-//                    (edges * (s+1) / kChunk, plus one partly filled chunk per tile), so handing out
-//                    a chunk is an LDS operation: no global atomics anywhere.  Work is done in rounds
-//                    of one edge per lane with workgroup barriers, so that appends never wait on one
-//                    another (no spin loops).
-//   k_chunk_*        bucket the chunks by tile (tiny).
-//   k_tile_accumulate one workgroup per tile adds its records into 2 x 64-bit fixed-point
-//                    accumulators per point in LDS.  Integer addition is associative, so the result
-//                    does not depend on the order records were appended or read in.  It then adds
-//                    the head sums and writes g.
-// The force on a tail is a record like the forces on negatives (slot 0 of every edge).
-constexpr int kTileBits = 13;
-constexpr int kTile = 1 << kTileBits;   // 8192 points: 128 KB of accumulators
-constexpr int kChunk = 256;             // records per chunk
+//   k_edges_binned   one persistent workgroup per compute unit, each owning a contiguous range of
+//                    CSR positions; in every round each lane takes one directed edge.  The round's
+//                    records (destination, force x, force y) are counting-sorted by tile in LDS and
+//                    then written with consecutive lanes on consecutive records, so the records of
+//                    one tile leave the workgroup as one contiguous run instead of one partial line
+//                    per lane.  Every (workgroup, tile) pair appends to its own chain of chunks of
+//                    kChunk records; a workgroup takes chunks from a private range of the pool,
+//                    sized at set-up for the records its edges can emit, so handing out a chunk is
+//                    an LDS operation: no global atomics, no spin loops, only workgroup barriers.
+//                    Head sums are reduced over the lanes of a row with a segmented scan in lane
+//                    order; rows that lie inside one wavefront store their sum directly, the few
+//                    that straddle a wavefront hand their partial sums on as records.
+//   k_tile_accumulate one workgroup per tile walks the chains of all workgroups for its tile and
+//                    adds the records into 2 x 64-bit fixed-point accumulators per point in LDS.
+//                    Integer addition is associative, so the result does not depend on the order
+//                    records were appended or read in.  It then adds the head sums and writes g.
+constexpr int kMaxTileBits = 13;        // 8192 points: 128 KB of accumulators
+constexpr int kMinTileBits = 8;
+constexpr int kChunk = 1024;            // records per chunk (12 KB)
 constexpr int kBinBlock = 1024;
+constexpr int kBinWaves = kBinBlock / 64;
+constexpr int kMaxBinsPerThread = 8;    // tiles one thread owns in the per-round scan
 constexpr uint32_t kNoChunk = 0xFFFFFFFFu;
 
 struct BinArgs {
-    uint32_t* pool;               // [max_chunks][kChunk][3]
-    uint32_t* chunk_bin;          // [max_chunks] tile of each chunk
-    uint32_t* chunk_fill;         // [max_chunks] records in each chunk
-    const uint32_t* wg_pool_begin;// [gridDim.x + 1] each workgroup's private range of chunk ids
+    const int32_t* head;          // [E] head of every CSR position
+    uint32_t* pool;               // [max_chunks][kChunk][3]: (index inside the tile, force x, force y)
+    uint32_t* chunk_prev;         // [max_chunks] previous chunk of the same chain
+    uint32_t* chain_head;         // [n_bins][n_wg] last chunk of every (tile, workgroup) chain, kNoChunk if empty
+    uint32_t* chain_fill;         // [n_bins][n_wg] records in that last chunk (all earlier chunks are full)
+    const uint32_t* wg_pool_begin;// [n_wg + 1] each workgroup's private range of chunk ids
+    float2* ghead;                // head sums of rows that lie inside one wavefront (others: records)
+    int64_t E;
     uint32_t max_chunks;
     uint32_t n_bins;
-    const int32_t* wg_row_begin;  // [gridDim.x + 1]
+    int tile_bits;
     int* overflow;                // set if a workgroup's chunk range were ever exceeded (it cannot be)
 };
 
+// LDS of k_edges_binned: per tile (record count / first sorted slot, fill of the open chunk, open
+// chunk, first chunk allocated this round) and the round's records, sorted by tile.
+__host__ __device__ inline size_t binned_records_per_round(int s) { return (size_t)kBinBlock * (s + 1) + 2 * kBinWaves; }
+__host__ __device__ inline size_t binned_lds_bytes(uint32_t n_bins, int s) {
+    return ((size_t)4 * n_bins + 1 + 3 * binned_records_per_round(s)) * sizeof(uint32_t);
+}
+
 template <int S>
-__global__ void __launch_bounds__(kBinBlock, 8) k_edges_binned(const EdgeArgs P, const BinArgs Q) {
-    constexpr int LPR = 16;
+__global__ void __launch_bounds__(kBinBlock) k_edges_binned(const EdgeArgs P, const BinArgs Q) {
+    constexpr int SS = S > 0 ? S : 1;
+    constexpr int NREC = kBinBlock * (S + 1) + 2 * kBinWaves;
     extern __shared__ uint32_t lds_bins[];
     const uint32_t B = Q.n_bins;
-    uint32_t* fill = lds_bins;        // records already in the open chunk (kChunk: none / full)
-    uint32_t* chunk = lds_bins + B;   // open chunk of this (workgroup, tile)
-    uint32_t* cnt = lds_bins + 2 * B; // records this round
-    uint32_t* base = lds_bins + 3 * B;// first chunk allocated this round
-    __shared__ int next_row;
-    __shared__ int any_active[2];
+    uint32_t* start = lds_bins;             // [B+1] A: records this round per tile; after the scan: first sorted slot
+    uint32_t* fill = start + B + 1;         // [B] records in the open chunk (kChunk: none open / full)
+    uint32_t* chunk = fill + B;             // [B] open chunk of this (workgroup, tile)
+    uint32_t* base = chunk + B;             // [B] first chunk allocated this round
+    uint32_t* rec_pt = base + B;            // [NREC] destination point
+    uint32_t* rec_x = rec_pt + NREC;        // [NREC] force x (float bits)
+    uint32_t* rec_y = rec_x + NREC;         // [NREC]
+    __shared__ uint32_t wave_total[kBinWaves];
     __shared__ uint32_t pool_cursor;
-    const int tid = threadIdx.x, lane = tid % LPR;
-    const int32_t r1 = Q.wg_row_begin[blockIdx.x + 1];
-    const uint32_t pool_end = min(Q.wg_pool_begin[blockIdx.x + 1], Q.max_chunks);
-    for (uint32_t b = tid; b < B; b += kBinBlock) { fill[b] = kChunk; chunk[b] = kNoChunk; cnt[b] = 0; base[b] = 0; }
-    if (tid == 0) { next_row = Q.wg_row_begin[blockIdx.x]; any_active[0] = 0; any_active[1] = 0; pool_cursor = Q.wg_pool_begin[blockIdx.x]; }
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tb = Q.tile_bits;
+    const uint32_t W = gridDim.x, w = blockIdx.x;
+    const int64_t e_begin = Q.E * (int64_t)w / W, e_end = Q.E * (int64_t)(w + 1) / W;
+    const uint32_t pool_end = min(Q.wg_pool_begin[w + 1], Q.max_chunks);
+    const uint32_t per = (B + kBinBlock - 1) / kBinBlock;   // tiles owned by one thread, contiguous
+    const uint32_t b0 = min(B, (uint32_t)tid * per), b1 = min(B, b0 + per);
+    for (uint32_t b = tid; b < B; b += kBinBlock) { start[b] = 0; fill[b] = kChunk; chunk[b] = kNoChunk; base[b] = 0; }
+    if (tid == 0) { start[B] = 0; pool_cursor = Q.wg_pool_begin[w]; }
     __syncthreads();
 
-    int32_t row = -1, e_next = 0, e_end = 0;
-    bool out_of_rows = false;
-    float hx = 0.f, hy = 0.f;
-    HeadCtx h{};
-    for (int round = 0;; ++round) {
-        // a row group that has used up its row stores the head sum and takes the next row
-        while (!out_of_rows && e_next >= e_end) {
-            if (row >= 0) {
-                const float sx = rowgroup_sum<LPR>(hx), sy = rowgroup_sum<LPR>(hy);
-                if (lane == 0) P.ghead[row] = make_float2(sx, sy);
-                hx = 0.f; hy = 0.f;
+    const int64_t n_rounds = (e_end - e_begin + kBinBlock - 1) / kBinBlock;
+    for (int64_t round = 0; round < n_rounds; ++round) {
+        // ---- A: one edge per lane; records: slot 0 the tail (force -a d_ij), slots 1..S the negatives,
+        //         slot S+1 the partial head sum of a row that straddles this wavefront
+        const int64_t e64 = e_begin + round * kBinBlock + tid;
+        const bool has = e64 < e_end;
+        const int32_t e = (int32_t)e64;
+        uint32_t dst_pt[S + 2], rank[S + 2];
+        float fx[S + 2], fy[S + 2];
+        bool head_rec = false;
+        {
+            int32_t i = -1, ea = 0, eb = 0;
+            float hx = 0.f, hy = 0.f;
+            if (has) {
+                i = Q.head[e];
+                ea = P.row_ptr[i];
+                eb = P.row_ptr[i + 1];
+                const HeadCtx h = load_head(P, i, ea, eb);
+                EdgeOut<SS> o;
+                edge_terms<S, false>(P, h, e, o);
+                hx = o.hx;
+                hy = o.hy;
+                dst_pt[0] = (uint32_t)o.j; fx[0] = -o.a * o.dx; fy[0] = -o.a * o.dy;
+#pragma unroll
+                for (int k = 0; k < S; ++k) { dst_pt[k + 1] = (uint32_t)o.m[k]; fx[k + 1] = o.rx[k]; fy[k + 1] = o.ry[k]; }
             }
-            int32_t r = 0;
-            if (lane == 0) r = atomicAdd(&next_row, 1);
-            r = __shfl(r, 0, LPR);
-            if (r >= r1) { out_of_rows = true; row = -1; break; }
-            row = r;
-            e_next = P.row_ptr[r];
-            e_end = P.row_ptr[r + 1];
-            h = load_head(P, r, e_next, e_end);
+            // head sum of each row: segmented inclusive scan over the lanes of the row, in lane order
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const float ux = __shfl_up(hx, d, 64), uy = __shfl_up(hy, d, 64);
+                const int32_t ui = __shfl_up(i, d, 64);
+                if (lane >= d && ui == i) { hx += ux; hy += uy; }
+            }
+            const int32_t i_next = __shfl_down(i, 1, 64);
+            const bool row_end = has && (lane == 63 || i_next != i);
+            if (row_end) {
+                const int64_t wave_e0 = e64 - lane;
+                const bool inside = (int64_t)ea >= wave_e0 && (int64_t)eb <= min(wave_e0 + 64, e_end);
+                if (inside) Q.ghead[i] = make_float2(hx, hy);
+                else { head_rec = true; dst_pt[S + 1] = (uint32_t)i; fx[S + 1] = hx; fy[S + 1] = hy; }
+            }
         }
-        const int32_t e = e_next + lane;
-        const bool has = !out_of_rows && e < e_end;
-        if (!out_of_rows) e_next += LPR;
-        // records of this lane's edge: slot 0 is the tail (force -a d_ij), slots 1..S the negatives
-        uint32_t dst_pt[S + 1];
-        float fx[S + 1], fy[S + 1];
-        uint32_t rank[S + 1];
         if (has) {
-            EdgeOut<(S > 0 ? S : 1)> o;
-            edge_terms<S, false>(P, h, e, o);
-            hx += o.hx;
-            hy += o.hy;
-            dst_pt[0] = (uint32_t)o.j; fx[0] = -o.a * o.dx; fy[0] = -o.a * o.dy;
 #pragma unroll
-            for (int k = 0; k < S; ++k) { dst_pt[k + 1] = (uint32_t)o.m[k]; fx[k + 1] = o.rx[k]; fy[k + 1] = o.ry[k]; }
-#pragma unroll
-            for (int k = 0; k <= S; ++k) rank[k] = atomicAdd(&cnt[dst_pt[k] >> kTileBits], 1u);
-            any_active[round & 1] = 1;
+            for (int k = 0; k <= S; ++k) rank[k] = atomicAdd(&start[dst_pt[k] >> tb], 1u);
         }
+        if (head_rec) rank[S + 1] = atomicAdd(&start[dst_pt[S + 1] >> tb], 1u);
         __syncthreads();
-        if (!any_active[round & 1]) break;
-        // tiles whose open chunk cannot take this round's records get new chunks
-        for (uint32_t b = tid; b < B; b += kBinBlock) {
-            const uint32_t c = cnt[b];
-            if (c == 0) continue;
-            const uint32_t f = fill[b];
-            if (f + c > (uint32_t)kChunk) {
-                const uint32_t k = (f + c - 1) / kChunk;
-                const uint32_t nb = atomicAdd(&pool_cursor, k);
-                base[b] = nb;
-                if (nb + k > pool_end) *Q.overflow = 1;
-                if (chunk[b] < pool_end) Q.chunk_fill[chunk[b]] = kChunk;   // kNoChunk is above any valid id
-                for (uint32_t x = 0; x < k && nb + x < pool_end; ++x) {
-                    Q.chunk_bin[nb + x] = b;
-                    Q.chunk_fill[nb + x] = kChunk;   // the last one is corrected when it is closed
+        // ---- B: exclusive scan of the per-tile counts (each thread owns `per` adjacent tiles)
+        uint32_t cnt_own[kMaxBinsPerThread];
+        uint32_t own_sum = 0;
+#pragma unroll
+        for (int x = 0; x < kMaxBinsPerThread; ++x) {
+            cnt_own[x] = (b0 + x < b1) ? start[b0 + x] : 0u;
+            own_sum += cnt_own[x];
+        }
+        uint32_t incl = own_sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t u = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += u;
+        }
+        if (lane == 63) wave_total[wave] = incl;
+        __syncthreads();
+        uint32_t run = incl - own_sum;
+        for (int v = 0; v < wave; ++v) run += wave_total[v];
+        if (tid == kBinBlock - 1) start[B] = run + own_sum;
+        // tiles whose open chunk cannot take this round's records get new chunks, linked to the chain
+#pragma unroll
+        for (int x = 0; x < kMaxBinsPerThread; ++x) {
+            const uint32_t b = b0 + x;
+            if (b < b1) {
+                const uint32_t c = cnt_own[x];
+                start[b] = run;
+                run += c;
+                const uint32_t f = fill[b];
+                if (c != 0 && f + c > (uint32_t)kChunk) {
+                    const uint32_t k = (f + c - 1) / kChunk;
+                    const uint32_t nb = atomicAdd(&pool_cursor, k);
+                    base[b] = nb;
+                    if (nb + k > pool_end) *Q.overflow = 1;
+                    uint32_t prev = chunk[b];
+                    for (uint32_t y = 0; y < k && nb + y < pool_end; ++y) { Q.chunk_prev[nb + y] = prev; prev = nb + y; }
                 }
             }
         }
-        if (tid == 0) any_active[(round + 1) & 1] = 0;
         __syncthreads();
+        // ---- C: records to their sorted slots
         if (has) {
 #pragma unroll
             for (int k = 0; k <= S; ++k) {
-                const uint32_t b = dst_pt[k] >> kTileBits;
-                const uint32_t pos = fill[b] + rank[k];
-                uint32_t ch, off;
-                if (pos < (uint32_t)kChunk) { ch = chunk[b]; off = pos; }
-                else { ch = base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
-                if (ch < pool_end) {
-                    uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
-                    dst[0] = dst_pt[k] & (kTile - 1);
-                    dst[1] = __float_as_uint(fx[k]);
-                    dst[2] = __float_as_uint(fy[k]);
+                const uint32_t p = start[dst_pt[k] >> tb] + rank[k];
+                rec_pt[p] = dst_pt[k]; rec_x[p] = __float_as_uint(fx[k]); rec_y[p] = __float_as_uint(fy[k]);
+            }
+        }
+        if (head_rec) {
+            const uint32_t p = start[dst_pt[S + 1] >> tb] + rank[S + 1];
+            rec_pt[p] = dst_pt[S + 1]; rec_x[p] = __float_as_uint(fx[S + 1]); rec_y[p] = __float_as_uint(fy[S + 1]);
+        }
+        __syncthreads();
+        // ---- D: consecutive lanes write consecutive sorted records to the chains
+        const uint32_t total = start[B];
+        for (uint32_t p = tid; p < total; p += kBinBlock) {
+            const uint32_t pt = rec_pt[p];
+            const uint32_t b = pt >> tb;
+            const uint32_t pos = fill[b] + (p - start[b]);
+            uint32_t ch, off;
+            if (pos < (uint32_t)kChunk) { ch = chunk[b]; off = pos; }
+            else { ch = base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
+            if (ch < pool_end) {   // kNoChunk is above any valid id
+                uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
+                dst[0] = pt & ((1u << tb) - 1u);
+                dst[1] = rec_x[p];
+                dst[2] = rec_y[p];
+            }
+        }
+        __syncthreads();
+        // ---- E: chain state after this round; counts back to zero
+#pragma unroll
+        for (int x = 0; x < kMaxBinsPerThread; ++x) {
+            const uint32_t b = b0 + x;
+            if (b < b1) {
+                const uint32_t c = cnt_own[x];
+                if (c != 0) {
+                    const uint32_t f = fill[b];
+                    if (f + c > (uint32_t)kChunk) {
+                        const uint32_t k = (f + c - 1) / kChunk;
+                        chunk[b] = base[b] + k - 1;
+                        fill[b] = f + c - k * kChunk;
+                    } else {
+                        fill[b] = f + c;
+                    }
                 }
+                start[b] = 0;
             }
         }
         __syncthreads();
-        for (uint32_t b = tid; b < B; b += kBinBlock) {
-            const uint32_t c = cnt[b];
-            if (c == 0) continue;
-            const uint32_t f = fill[b];
-            if (f + c > (uint32_t)kChunk) {
-                const uint32_t k = (f + c - 1) / kChunk;
-                chunk[b] = base[b] + k - 1;
-                fill[b] = f + c - k * kChunk;
-            } else {
-                fill[b] = f + c;
-            }
-            cnt[b] = 0;
-        }
-        __syncthreads();
     }
-    // close the open chunks
-    for (uint32_t b = tid; b < B; b += kBinBlock)
-        if (chunk[b] < pool_end) Q.chunk_fill[chunk[b]] = fill[b];   // kNoChunk is above any valid id
+    // the last chunk of every chain and how full it is
+    for (uint32_t b = tid; b < B; b += kBinBlock) {
+        const uint32_t ch = chunk[b];
+        Q.chain_head[(size_t)b * W + w] = ch < pool_end ? ch : kNoChunk;
+        Q.chain_fill[(size_t)b * W + w] = fill[b];
+    }
 }
 
-// first row of each persistent workgroup: rows split so that every workgroup gets ~E/W edges
-__global__ void k_wg_rows(const int32_t* __restrict__ row_ptr, int64_t n, int64_t E, int W, int32_t* __restrict__ wg_row_begin) {
-    const int w = blockIdx.x * blockDim.x + threadIdx.x;
-    if (w > W) return;
-    if (w == W) { wg_row_begin[w] = (int32_t)n; return; }
-    const int64_t target = E * (int64_t)w / W;
-    int64_t lo = 0, hi = n;   // first row with row_ptr[row] >= target
-    while (lo < hi) {
-        const int64_t mid = (lo + hi) >> 1;
-        if ((int64_t)row_ptr[mid] < target) lo = mid + 1; else hi = mid;
-    }
-    wg_row_begin[w] = (int32_t)lo;
-}
-
-// private chunk-id range of each workgroup: enough for every record its rows can emit, plus one
-// partly filled chunk per tile (one thread: W is a few hundred)
-__global__ void k_wg_pools(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ wg_row_begin, int W, int records_per_edge,
-                           uint32_t n_bins, uint32_t* __restrict__ wg_pool_begin) {
+// private chunk-id range of each workgroup: enough for every record its edges can emit (s+1 per
+// edge, plus at most two partial head sums per wavefront and round), plus one partly filled chunk
+// per tile (one thread: W is a few hundred)
+__global__ void k_wg_pools(int64_t E, int W, int records_per_edge, uint32_t n_bins, uint32_t* __restrict__ wg_pool_begin,
+                           unsigned long long* __restrict__ total) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     uint64_t run = 0;
     for (int w = 0; w < W; ++w) {
-        wg_pool_begin[w] = (uint32_t)run;
-        const uint64_t edges = (uint64_t)(row_ptr[wg_row_begin[w + 1]] - row_ptr[wg_row_begin[w]]);
-        run += edges * (uint64_t)records_per_edge / kChunk + n_bins + 1;
+        wg_pool_begin[w] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
+        const uint64_t edges = (uint64_t)(E * (int64_t)(w + 1) / W - E * (int64_t)w / W);
+        const uint64_t rounds = (edges + kBinBlock - 1) / kBinBlock;
+        const uint64_t records = edges * (uint64_t)records_per_edge + rounds * 2 * kBinWaves;
+        run += records / kChunk + n_bins + 1;
     }
-    wg_pool_begin[W] = (uint32_t)run;
+    wg_pool_begin[W] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
+    *total = run;
 }
 
-// every chunk id starts an epoch marked unused
-__global__ void k_bin_reset(uint32_t* __restrict__ bin_count, uint32_t B, uint32_t* __restrict__ chunk_bin, uint32_t max_chunks) {
-    const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
-    if (x < B) bin_count[x] = 0;
-    if (x < max_chunks) chunk_bin[x] = kNoChunk;
+// head[e] = row of CSR position e (one thread per row)
+__global__ void __launch_bounds__(kBlock) k_edge_heads(const int32_t* __restrict__ row_ptr, int64_t n, int32_t* __restrict__ head) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    for (int32_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) head[e] = (int32_t)i;
 }
 
-__global__ void k_chunk_census(const uint32_t* __restrict__ chunk_bin, uint32_t max_chunks, uint32_t* __restrict__ bin_count) {
-    const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c < max_chunks && chunk_bin[c] != kNoChunk) atomicAdd(&bin_count[chunk_bin[c]], 1u);
-}
-
-// exclusive scan of the per-tile chunk counts (one block; B is a few thousand)
-__global__ void __launch_bounds__(kBinBlock) k_bin_scan(const uint32_t* __restrict__ bin_count, uint32_t B, uint32_t* __restrict__ bin_start,
-                                                       uint32_t* __restrict__ bin_cursor) {
-    __shared__ uint32_t part[kBinBlock];
-    const uint32_t per = (B + kBinBlock - 1) / kBinBlock;
-    const uint32_t b0 = threadIdx.x * per, b1 = min(B, b0 + per);
-    uint32_t sum = 0;
-    for (uint32_t b = b0; b < b1; ++b) sum += bin_count[b];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int t = 0; t < kBinBlock; ++t) { const uint32_t v = part[t]; part[t] = run; run += v; }
-        bin_start[B] = run;
-    }
-    __syncthreads();
-    uint32_t run = part[threadIdx.x];
-    for (uint32_t b = b0; b < b1; ++b) { bin_start[b] = run; bin_cursor[b] = run; run += bin_count[b]; }
-}
-
-__global__ void k_chunk_lists(const uint32_t* __restrict__ chunk_bin, uint32_t max_chunks, uint32_t* __restrict__ bin_cursor,
-                              uint32_t* __restrict__ bin_chunks) {
-    const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c < max_chunks && chunk_bin[c] != kNoChunk) bin_chunks[atomicAdd(&bin_cursor[chunk_bin[c]], 1u)] = c;
-}
-
-__global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const uint32_t* __restrict__ pool, const uint32_t* __restrict__ chunk_fill,
-                                                              const uint32_t* __restrict__ bin_start,
-                                                              const uint32_t* __restrict__ bin_chunks, const float2* __restrict__ ghead,
-                                                              float2* __restrict__ g, int64_t n) {
-    extern __shared__ unsigned long long acc[];   // [kTile][2]
-    constexpr int kPerIter = kBinBlock / kChunk;   // chunks one sweep of the block covers
-    constexpr int kUnroll = 4;
+__global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const BinArgs Q, uint32_t n_wg, float2* __restrict__ g, int64_t n) {
+    extern __shared__ unsigned long long acc[];   // [2 << tile_bits]
+    constexpr int kPerLane = kChunk / 64;         // records one lane takes from a full chunk
+    constexpr int kBatch = 8;                     // loads in flight per lane
     const uint32_t b = blockIdx.x;
-    for (int l = threadIdx.x; l < 2 * kTile; l += kBinBlock) acc[l] = 0ull;
+    const int tile = 1 << Q.tile_bits;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int l = threadIdx.x; l < 2 * tile; l += kBinBlock) acc[l] = 0ull;
     __syncthreads();
-    const uint32_t c_end = bin_start[b + 1];
-    const uint32_t off = threadIdx.x % kChunk;
-    for (uint32_t c0 = bin_start[b] + threadIdx.x / kChunk; c0 < c_end; c0 += kPerIter * kUnroll) {
-        uint32_t rec[kUnroll][3];
-        bool ok[kUnroll];
+    for (uint32_t w = wave; w < n_wg; w += kBinWaves) {
+        uint32_t ch = Q.chain_head[(size_t)b * n_wg + w];
+        uint32_t cnt = Q.chain_fill[(size_t)b * n_wg + w];
+        while (ch != kNoChunk) {
+            const uint32_t prev = Q.chunk_prev[ch];
+            const uint32_t* src = Q.pool + (size_t)ch * kChunk * 3;
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t ci = c0 + u * kPerIter;
-            ok[u] = false;
-            if (ci < c_end) {
-                const uint32_t ch = bin_chunks[ci];
-                if (off < chunk_fill[ch]) {
-                    const uint32_t* src = pool + ((size_t)ch * kChunk + off) * 3;
-                    rec[u][0] = src[0]; rec[u][1] = src[1]; rec[u][2] = src[2];
-                    ok[u] = true;
+            for (int r0 = 0; r0 < kPerLane; r0 += kBatch) {
+                uint32_t rec[kBatch][3];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const uint32_t r = (uint32_t)(r0 + u) * 64u + lane;
+                    if (r < cnt) { rec[u][0] = src[3 * r]; rec[u][1] = src[3 * r + 1]; rec[u][2] = src[3 * r + 2]; }
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const uint32_t r = (uint32_t)(r0 + u) * 64u + lane;
+                    if (r < cnt) {
+                        const uint32_t ml = rec[u][0] & (uint32_t)(tile - 1);
+                        atomicAdd(&acc[2 * ml], (unsigned long long)__float2ll_rn(__uint_as_float(rec[u][1]) * kFixScale));
+                        atomicAdd(&acc[2 * ml + 1], (unsigned long long)__float2ll_rn(__uint_as_float(rec[u][2]) * kFixScale));
+                    }
                 }
             }
+            ch = prev;
+            cnt = kChunk;
         }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            if (ok[u]) {
-                const uint32_t ml = rec[u][0] & (kTile - 1);
-                atomicAdd(&acc[2 * ml], (unsigned long long)__float2ll_rn(__uint_as_float(rec[u][1]) * kFixScale));
-                atomicAdd(&acc[2 * ml + 1], (unsigned long long)__float2ll_rn(__uint_as_float(rec[u][2]) * kFixScale));
-            }
     }
     __syncthreads();
-    const int64_t p0 = (int64_t)b * kTile;
-    for (int l = threadIdx.x; l < kTile && p0 + l < n; l += kBinBlock) {
-        const float2 hd = ghead[p0 + l];
+    const int64_t p0 = (int64_t)b << Q.tile_bits;
+    for (int l = threadIdx.x; l < tile && p0 + l < n; l += kBinBlock) {
+        const float2 hd = Q.ghead[p0 + l];
+        Q.ghead[p0 + l] = make_float2(0.f, 0.f);   // consumed: rows that hand their head sum on as records rely on this
         g[p0 + l] = make_float2((float)((double)hd.x + (double)(long long)acc[2 * l] * kFixInv),
                                 (float)((double)hd.y + (double)(long long)acc[2 * l + 1] * kFixInv));
     }
