@@ -49,7 +49,7 @@ struct nomad_ctx {
     unsigned long long* gfix = nullptr;
     // binned deterministic scatter
     bool binned = false;
-    int n_wg = 0;
+    int n_wg = 0, bin_block = 1024;
     uint32_t n_bins = 0, max_chunks = 0;
     int tile_bits = kMaxTileBits;
     uint32_t *pool = nullptr, *chunk_prev = nullptr, *chain_head = nullptr, *chain_fill = nullptr, *wg_pool_begin = nullptr;
@@ -183,8 +183,11 @@ constexpr size_t kMaxLdsBytes = 160 * 1024 - 256;   // per workgroup on gfx950, 
 
 template <int S>
 int prepare_binned_kernel(nomad_ctx* c) {
-    HIP_TRY(c, hipFuncSetAttribute((const void*)k_edges_binned<S>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)binned_lds_bytes(c->n_bins, S)));
+    const int lds = (int)binned_lds_bytes(c->n_bins, S, c->bin_block);
+    if (c->bin_block == 512)
+        HIP_TRY(c, hipFuncSetAttribute((const void*)k_edges_binned<S, 512>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    else
+        HIP_TRY(c, hipFuncSetAttribute((const void*)k_edges_binned<S, 1024>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     return NOMAD_OK;
 }
 
@@ -203,10 +206,14 @@ int prepare_binned(nomad_ctx* c) {
 
 void launch_edges_binned(nomad_ctx* c, const EdgeArgs& a) {
     const BinArgs q = bin_args(c);
-    const dim3 grid(c->n_wg), block(kBinBlock);
-    const size_t lds = binned_lds_bytes(c->n_bins, c->cfg.n_neg);
+    const dim3 grid(c->n_wg), block(c->bin_block);
+    const size_t lds = binned_lds_bytes(c->n_bins, c->cfg.n_neg, c->bin_block);
     switch (c->cfg.n_neg) {
-#define NOMAD_CASE(S) case S: hipLaunchKernelGGL((k_edges_binned<S>), grid, block, lds, c->stream, a, q); break;
+#define NOMAD_CASE(S)                                                                                          \
+    case S:                                                                                                    \
+        if (c->bin_block == 512) hipLaunchKernelGGL((k_edges_binned<S, 512>), grid, block, lds, c->stream, a, q); \
+        else hipLaunchKernelGGL((k_edges_binned<S, 1024>), grid, block, lds, c->stream, a, q);                   \
+        break;
         NOMAD_CASE(0) NOMAD_CASE(1) NOMAD_CASE(2) NOMAD_CASE(3) NOMAD_CASE(4) NOMAD_CASE(5) NOMAD_CASE(6) NOMAD_CASE(7) NOMAD_CASE(8)
 #undef NOMAD_CASE
         default: break;
@@ -472,18 +479,28 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         int tile_bits = kMinTileBits;   // about a thousand tiles when n allows, never above 8192 points a tile
         while (tile_bits < kMaxTileBits && (n >> tile_bits) > 1024) ++tile_bits;
         const uint32_t n_bins = (uint32_t)((n + ((int64_t)1 << tile_bits) - 1) >> tile_bits);
-        if (s <= 8 && E > 0 && n_bins <= (uint32_t)kMaxBinsPerThread * kBinBlock && binned_lds_bytes(n_bins, s) <= kMaxLdsBytes &&
-            !getenv("NOMAD_NO_BINNING")) {
+        // One persistent workgroup of 1024 lanes per compute unit: the more records a round sorts, the longer the
+        // contiguous run each tile receives.  (Two workgroups of 512 per compute unit measured 17 % slower at
+        // 10 M points; NOMAD_BIN_BLOCK=512 selects them for experiments when their LDS fits.)
+        int bin_block = 0, wg_per_cu = 1;
+        if (n_bins <= (uint32_t)kMaxBinsPerThread * 1024 && binned_lds_bytes(n_bins, s, 1024) <= kMaxLdsBytes) bin_block = 1024;
+        if (const char* knob = getenv("NOMAD_BIN_BLOCK"))
+            if (atoi(knob) == 512 && n_bins <= (uint32_t)kMaxBinsPerThread * 512 &&
+                2 * (binned_lds_bytes(n_bins, s, 512) + 256) <= 160 * 1024) { bin_block = 512; wg_per_cu = 2; }
+        if (const char* knob = getenv("NOMAD_WG_PER_CU"))   // tuning knob: persistent workgroups per compute unit
+            wg_per_cu = std::max(1, std::min(8, atoi(knob)));
+        if (s <= 8 && E > 0 && bin_block && !getenv("NOMAD_NO_BINNING")) {
             hipDeviceProp_t prop;
             HTRY(hipGetDeviceProperties(&prop, c->cfg.device));
-            c->n_wg = std::max(1, prop.multiProcessorCount);   // one persistent workgroup per compute unit
+            c->bin_block = bin_block;
+            c->n_wg = std::max(1, prop.multiProcessorCount) * wg_per_cu;
             c->n_bins = n_bins;
             c->tile_bits = tile_bits;
             unsigned long long* total_dev = nullptr;
             unsigned long long want = 0;
             bool ok = dev_alloc(c, &c->wg_pool_begin, (size_t)c->n_wg + 1) == NOMAD_OK && dev_alloc(c, &total_dev, 1) == NOMAD_OK;
             if (ok) {
-                hipLaunchKernelGGL(k_wg_pools, dim3(1), dim3(64), 0, st, E, c->n_wg, s + 1, n_bins, c->wg_pool_begin, total_dev);
+                hipLaunchKernelGGL(k_wg_pools, dim3(1), dim3(64), 0, st, E, c->n_wg, s + 1, c->bin_block, n_bins, c->wg_pool_begin, total_dev);
                 ok = hipMemcpyAsync(&want, total_dev, sizeof(want), hipMemcpyDeviceToHost, st) == hipSuccess &&
                      hipStreamSynchronize(st) == hipSuccess;
             }

@@ -502,8 +502,7 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
 constexpr int kMaxTileBits = 13;        // 8192 points: 128 KB of accumulators
 constexpr int kMinTileBits = 8;
 constexpr int kChunk = 1024;            // records per chunk (12 KB)
-constexpr int kBinBlock = 1024;
-constexpr int kBinWaves = kBinBlock / 64;
+constexpr int kBinBlock = 1024;          // threads of the tile pass and of the large edge-pass workgroup
 constexpr int kMaxBinsPerThread = 8;    // tiles one thread owns in the per-round scan
 constexpr uint32_t kNoChunk = 0xFFFFFFFFu;
 
@@ -524,15 +523,25 @@ struct BinArgs {
 
 // LDS of k_edges_binned: per tile (record count / first sorted slot, fill of the open chunk, open
 // chunk, first chunk allocated this round) and the round's records, sorted by tile.
-__host__ __device__ inline size_t binned_records_per_round(int s) { return (size_t)kBinBlock * (s + 1) + 2 * kBinWaves; }
-__host__ __device__ inline size_t binned_lds_bytes(uint32_t n_bins, int s) {
-    return ((size_t)4 * n_bins + 1 + 3 * binned_records_per_round(s)) * sizeof(uint32_t);
+__host__ __device__ inline size_t binned_records_per_round(int s, int block) { return (size_t)block * (s + 1) + 2 * (block / 64); }
+__host__ __device__ inline size_t binned_lds_bytes(uint32_t n_bins, int s, int block) {
+    return ((size_t)4 * n_bins + 1 + 3 * binned_records_per_round(s, block)) * sizeof(uint32_t);
 }
 
-template <int S>
-__global__ void __launch_bounds__(kBinBlock) k_edges_binned(const EdgeArgs P, const BinArgs Q) {
+// Workgroup barrier that orders LDS accesses only.  The edge pass never reads back, inside the
+// kernel, anything it wrote to global memory, so its barriers need not wait for outstanding global
+// loads and stores (a full __syncthreads() would drain them every round).
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <int S, int BS>
+__global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const BinArgs Q) {
     constexpr int SS = S > 0 ? S : 1;
-    constexpr int NREC = kBinBlock * (S + 1) + 2 * kBinWaves;
+    constexpr int kWaves = BS / 64;
+    constexpr int NREC = BS * (S + 1) + 2 * kWaves;
     extern __shared__ uint32_t lds_bins[];
     const uint32_t B = Q.n_bins;
     uint32_t* start = lds_bins;             // [B+1] A: records this round per tile; after the scan: first sorted slot
@@ -542,67 +551,68 @@ __global__ void __launch_bounds__(kBinBlock) k_edges_binned(const EdgeArgs P, co
     uint32_t* rec_pt = base + B;            // [NREC] destination point
     uint32_t* rec_x = rec_pt + NREC;        // [NREC] force x (float bits)
     uint32_t* rec_y = rec_x + NREC;         // [NREC]
-    __shared__ uint32_t wave_total[kBinWaves];
+    __shared__ uint32_t wave_total[kWaves];
     __shared__ uint32_t pool_cursor;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tb = Q.tile_bits;
     const uint32_t W = gridDim.x, w = blockIdx.x;
     const int64_t e_begin = Q.E * (int64_t)w / W, e_end = Q.E * (int64_t)(w + 1) / W;
     const uint32_t pool_end = min(Q.wg_pool_begin[w + 1], Q.max_chunks);
-    const uint32_t per = (B + kBinBlock - 1) / kBinBlock;   // tiles owned by one thread, contiguous
+    const uint32_t per = (B + BS - 1) / BS;   // tiles owned by one thread, contiguous
     const uint32_t b0 = min(B, (uint32_t)tid * per), b1 = min(B, b0 + per);
-    for (uint32_t b = tid; b < B; b += kBinBlock) { start[b] = 0; fill[b] = kChunk; chunk[b] = kNoChunk; base[b] = 0; }
+    for (uint32_t b = tid; b < B; b += BS) { start[b] = 0; fill[b] = kChunk; chunk[b] = kNoChunk; base[b] = 0; }
     if (tid == 0) { start[B] = 0; pool_cursor = Q.wg_pool_begin[w]; }
-    __syncthreads();
+    lds_barrier();
 
-    const int64_t n_rounds = (e_end - e_begin + kBinBlock - 1) / kBinBlock;
+    const int64_t n_rounds = (e_end - e_begin + BS - 1) / BS;
     for (int64_t round = 0; round < n_rounds; ++round) {
         // ---- A: one edge per lane; records: slot 0 the tail (force -a d_ij), slots 1..S the negatives,
         //         slot S+1 the partial head sum of a row that straddles this wavefront
-        const int64_t e64 = e_begin + round * kBinBlock + tid;
+        const int64_t e64 = e_begin + round * BS + tid;
         const bool has = e64 < e_end;
         const int32_t e = (int32_t)e64;
-        uint32_t dst_pt[S + 2], rank[S + 2];
-        float fx[S + 2], fy[S + 2];
-        bool head_rec = false;
-        {
-            int32_t i = -1, ea = 0, eb = 0;
-            float hx = 0.f, hy = 0.f;
-            if (has) {
-                i = Q.head[e];
-                ea = P.row_ptr[i];
-                eb = P.row_ptr[i + 1];
-                const HeadCtx h = load_head(P, i, ea, eb);
-                EdgeOut<SS> o;
-                edge_terms<S, false>(P, h, e, o);
-                hx = o.hx;
-                hy = o.hy;
-                dst_pt[0] = (uint32_t)o.j; fx[0] = -o.a * o.dx; fy[0] = -o.a * o.dy;
+        uint32_t dst_pt[S + 1], rank[S + 1];
+        float fx[S + 1], fy[S + 1];
 #pragma unroll
-                for (int k = 0; k < S; ++k) { dst_pt[k + 1] = (uint32_t)o.m[k]; fx[k + 1] = o.rx[k]; fy[k + 1] = o.ry[k]; }
-            }
-            // head sum of each row: segmented inclusive scan over the lanes of the row, in lane order
+        for (int k = 0; k <= S; ++k) { dst_pt[k] = 0u; rank[k] = 0u; fx[k] = 0.f; fy[k] = 0.f; }
+        int32_t i = -1, ea = 0, eb = 0;
+        float hx = 0.f, hy = 0.f;
+        if (has) {
+            i = Q.head[e];
+            ea = P.row_ptr[i];
+            eb = P.row_ptr[i + 1];
+            const HeadCtx h = load_head(P, i, ea, eb);
+            EdgeOut<SS> o;
+            edge_terms<S, false>(P, h, e, o);
+            hx = o.hx;
+            hy = o.hy;
+            dst_pt[0] = (uint32_t)o.j; fx[0] = -o.a * o.dx; fy[0] = -o.a * o.dy;
 #pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const float ux = __shfl_up(hx, d, 64), uy = __shfl_up(hy, d, 64);
-                const int32_t ui = __shfl_up(i, d, 64);
-                if (lane >= d && ui == i) { hx += ux; hy += uy; }
-            }
-            const int32_t i_next = __shfl_down(i, 1, 64);
-            const bool row_end = has && (lane == 63 || i_next != i);
-            if (row_end) {
-                const int64_t wave_e0 = e64 - lane;
-                const bool inside = (int64_t)ea >= wave_e0 && (int64_t)eb <= min(wave_e0 + 64, e_end);
-                if (inside) Q.ghead[i] = make_float2(hx, hy);
-                else { head_rec = true; dst_pt[S + 1] = (uint32_t)i; fx[S + 1] = hx; fy[S + 1] = hy; }
-            }
+            for (int k = 0; k < S; ++k) { dst_pt[k + 1] = (uint32_t)o.m[k]; fx[k + 1] = o.rx[k]; fy[k + 1] = o.ry[k]; }
         }
+        // head sum of each row: segmented inclusive scan over the lanes of the row, in lane order
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const float ux = __shfl_up(hx, d, 64), uy = __shfl_up(hy, d, 64);
+            const int32_t ui = __shfl_up(i, d, 64);
+            if (lane >= d && ui == i) { hx += ux; hy += uy; }
+        }
+        // the last lane of a row holds the row's sum: stored directly when the whole row lies inside this
+        // wavefront, else handed on as one more record (hx, hy for point i)
+        const int32_t i_next = __shfl_down(i, 1, 64);
+        const bool row_end = has && (lane == 63 || i_next != i);
+        const int64_t wave_e0 = e64 - lane;
+        const bool inside = (int64_t)ea >= wave_e0 && (int64_t)eb <= min(wave_e0 + 64, e_end);
+        const bool head_rec = row_end && !inside;
+        const uint32_t head_bin = head_rec ? (uint32_t)i >> tb : 0u;
+        uint32_t head_rank = 0u;
+        if (row_end && inside) Q.ghead[i] = make_float2(hx, hy);
         if (has) {
 #pragma unroll
             for (int k = 0; k <= S; ++k) rank[k] = atomicAdd(&start[dst_pt[k] >> tb], 1u);
         }
-        if (head_rec) rank[S + 1] = atomicAdd(&start[dst_pt[S + 1] >> tb], 1u);
-        __syncthreads();
+        if (head_rec) head_rank = atomicAdd(&start[head_bin], 1u);
+        lds_barrier();
         // ---- B: exclusive scan of the per-tile counts (each thread owns `per` adjacent tiles)
         uint32_t cnt_own[kMaxBinsPerThread];
         uint32_t own_sum = 0;
@@ -618,10 +628,10 @@ __global__ void __launch_bounds__(kBinBlock) k_edges_binned(const EdgeArgs P, co
             if (lane >= d) incl += u;
         }
         if (lane == 63) wave_total[wave] = incl;
-        __syncthreads();
+        lds_barrier();
         uint32_t run = incl - own_sum;
         for (int v = 0; v < wave; ++v) run += wave_total[v];
-        if (tid == kBinBlock - 1) start[B] = run + own_sum;
+        if (tid == BS - 1) start[B] = run + own_sum;
         // tiles whose open chunk cannot take this round's records get new chunks, linked to the chain
 #pragma unroll
         for (int x = 0; x < kMaxBinsPerThread; ++x) {
@@ -641,7 +651,7 @@ __global__ void __launch_bounds__(kBinBlock) k_edges_binned(const EdgeArgs P, co
                 }
             }
         }
-        __syncthreads();
+        lds_barrier();
         // ---- C: records to their sorted slots
         if (has) {
 #pragma unroll
@@ -651,13 +661,13 @@ __global__ void __launch_bounds__(kBinBlock) k_edges_binned(const EdgeArgs P, co
             }
         }
         if (head_rec) {
-            const uint32_t p = start[dst_pt[S + 1] >> tb] + rank[S + 1];
-            rec_pt[p] = dst_pt[S + 1]; rec_x[p] = __float_as_uint(fx[S + 1]); rec_y[p] = __float_as_uint(fy[S + 1]);
+            const uint32_t p = start[head_bin] + head_rank;
+            rec_pt[p] = (uint32_t)i; rec_x[p] = __float_as_uint(hx); rec_y[p] = __float_as_uint(hy);
         }
-        __syncthreads();
+        lds_barrier();
         // ---- D: consecutive lanes write consecutive sorted records to the chains
         const uint32_t total = start[B];
-        for (uint32_t p = tid; p < total; p += kBinBlock) {
+        for (uint32_t p = tid; p < total; p += BS) {
             const uint32_t pt = rec_pt[p];
             const uint32_t b = pt >> tb;
             const uint32_t pos = fill[b] + (p - start[b]);
@@ -671,7 +681,7 @@ __global__ void __launch_bounds__(kBinBlock) k_edges_binned(const EdgeArgs P, co
                 dst[2] = rec_y[p];
             }
         }
-        __syncthreads();
+        lds_barrier();
         // ---- E: chain state after this round; counts back to zero
 #pragma unroll
         for (int x = 0; x < kMaxBinsPerThread; ++x) {
@@ -691,10 +701,10 @@ __global__ void __launch_bounds__(kBinBlock) k_edges_binned(const EdgeArgs P, co
                 start[b] = 0;
             }
         }
-        __syncthreads();
+        lds_barrier();
     }
     // the last chunk of every chain and how full it is
-    for (uint32_t b = tid; b < B; b += kBinBlock) {
+    for (uint32_t b = tid; b < B; b += BS) {
         const uint32_t ch = chunk[b];
         Q.chain_head[(size_t)b * W + w] = ch < pool_end ? ch : kNoChunk;
         Q.chain_fill[(size_t)b * W + w] = fill[b];
@@ -704,15 +714,15 @@ __global__ void __launch_bounds__(kBinBlock) k_edges_binned(const EdgeArgs P, co
 // private chunk-id range of each workgroup: enough for every record its edges can emit (s+1 per
 // edge, plus at most two partial head sums per wavefront and round), plus one partly filled chunk
 // per tile (one thread: W is a few hundred)
-__global__ void k_wg_pools(int64_t E, int W, int records_per_edge, uint32_t n_bins, uint32_t* __restrict__ wg_pool_begin,
+__global__ void k_wg_pools(int64_t E, int W, int records_per_edge, int block, uint32_t n_bins, uint32_t* __restrict__ wg_pool_begin,
                            unsigned long long* __restrict__ total) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     uint64_t run = 0;
     for (int w = 0; w < W; ++w) {
         wg_pool_begin[w] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
         const uint64_t edges = (uint64_t)(E * (int64_t)(w + 1) / W - E * (int64_t)w / W);
-        const uint64_t rounds = (edges + kBinBlock - 1) / kBinBlock;
-        const uint64_t records = edges * (uint64_t)records_per_edge + rounds * 2 * kBinWaves;
+        const uint64_t rounds = (edges + block - 1) / block;
+        const uint64_t records = edges * (uint64_t)records_per_edge + rounds * 2 * (block / 64);
         run += records / kChunk + n_bins + 1;
     }
     wg_pool_begin[W] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
@@ -735,7 +745,7 @@ __global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const BinArgs Q, 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int l = threadIdx.x; l < 2 * tile; l += kBinBlock) acc[l] = 0ull;
     __syncthreads();
-    for (uint32_t w = wave; w < n_wg; w += kBinWaves) {
+    for (uint32_t w = wave; w < n_wg; w += kBinBlock / 64) {
         uint32_t ch = Q.chain_head[(size_t)b * n_wg + w];
         uint32_t cnt = Q.chain_fill[(size_t)b * n_wg + w];
         while (ch != kNoChunk) {
