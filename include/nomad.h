@@ -142,9 +142,8 @@ int64_t nomad_num_edges(const nomad_ctx* ctx);
 #define NOMAD_K_UPDATE 4     /* SGD step                           */
 #define NOMAD_K_LOSS 5       /* loss terms + reduction             */
 #define NOMAD_K_ZERO 6       /* clearing of accumulators           */
-#define NOMAD_K_BINS 7       /* bucketing of record chunks by tile */
-#define NOMAD_K_TILES 8      /* per-tile accumulation of negatives */
-#define NOMAD_K_COUNT 9
+#define NOMAD_K_TILES 7      /* per-tile accumulation of the binned forces */
+#define NOMAD_K_COUNT 8
 
 /* Switch per-launch timing on (1) or off (0); switching on clears earlier samples. */
 int nomad_profile(nomad_ctx* ctx, int enable);

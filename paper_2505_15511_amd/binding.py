@@ -15,8 +15,8 @@ from . import _build
 
 NOMAD_HOST, NOMAD_DEVICE = 0, 1
 SCATTER_DETERMINISTIC, SCATTER_ATOMIC = 0, 1
-K_MEANS, K_MEANFIELD, K_EDGES, K_SCATTER, K_UPDATE, K_LOSS, K_ZERO, K_BINS, K_TILES = range(9)
-KERNEL_NAMES = ["means", "mean_field", "edges", "scatter", "update", "loss", "zero", "bins", "tiles"]
+K_MEANS, K_MEANFIELD, K_EDGES, K_SCATTER, K_UPDATE, K_LOSS, K_ZERO, K_TILES = range(8)
+KERNEL_NAMES = ["means", "mean_field", "edges", "scatter", "update", "loss", "zero", "tiles"]
 ERRORS = {-1: "NOMAD_E_INVALID_ARG", -2: "NOMAD_E_BAD_GRAPH", -3: "NOMAD_E_ORDER", -4: "NOMAD_E_TOO_LARGE",
           -5: "NOMAD_E_OOM", -6: "NOMAD_E_HIP"}
 

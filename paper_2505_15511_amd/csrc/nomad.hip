@@ -45,6 +45,8 @@ struct nomad_ctx {
     // state
     float2 *theta = nullptr, *g = nullptr, *ghead = nullptr, *mu = nullptr, *B = nullptr;
     float4* cinfo = nullptr;
+    int32_t* cell_slot = nullptr;   // grouped: slot of each cell in the group-ordered cell table
+    int2* group_slots = nullptr;    // grouped: slot range [lo, hi) of each group's cells
     float* A = nullptr;
     unsigned long long* gfix = nullptr;
     // binned deterministic scatter
@@ -103,6 +105,7 @@ void free_graph(nomad_ctx* c) {
     dev_free(c->pe); dev_free(c->counts); dev_free(c->gbase); dev_free(c->gcount); dev_free(c->chunk_start);
     dev_free(c->gomega); dev_free(c->gmembers); dev_free(c->cmembers); dev_free(c->chunks); dev_free(c->mean_partial);
     dev_free(c->theta); dev_free(c->g); dev_free(c->ghead); dev_free(c->mu); dev_free(c->B); dev_free(c->cinfo);
+    dev_free(c->cell_slot); dev_free(c->group_slots);
     dev_free(c->A); dev_free(c->gfix); dev_free(c->loss_partial); dev_free(c->loss_out);
     dev_free(c->flags);
     dev_free(c->pool); dev_free(c->chunk_prev); dev_free(c->chain_head); dev_free(c->chain_fill); dev_free(c->wg_pool_begin);
@@ -227,8 +230,8 @@ int run_means(nomad_ctx* c) {
         hipLaunchKernelGGL(k_mean_chunks, dim3(c->n_chunks), dim3(kBlock), 0, c->stream, c->theta, c->cmembers, c->chunks,
                            c->mean_partial);
     hipLaunchKernelGGL(k_mean_finish, dim3(blocks_for((int64_t)c->R * 64)), dim3(kBlock), 0, c->stream, c->mean_partial,
-                       c->chunk_start, c->counts, c->grouped ? c->group_of_cluster : nullptr, c->R, 1.0 / (double)c->n, c->mu,
-                       c->cinfo);
+                       c->chunk_start, c->counts, c->grouped ? c->group_of_cluster : nullptr, c->grouped ? c->cell_slot : nullptr,
+                       c->R, 1.0 / (double)c->n, c->mu, c->cinfo);
     return NOMAD_OK;
 }
 
@@ -236,7 +239,7 @@ int run_mean_field(nomad_ctx* c) {
     if (!c->grouped) return NOMAD_OK;
     Timed tm(c, NOMAD_K_MEANFIELD);
     hipLaunchKernelGGL(k_mean_field, dim3(blocks_for(c->n)), dim3(kBlock), 0, c->stream, c->theta, c->cluster_of,
-                       c->group_of_cluster, c->cinfo, c->R, c->n, c->A, c->B);
+                       c->group_of_cluster, c->cinfo, c->group_slots, c->R, c->n, c->A, c->B);
     return NOMAD_OK;
 }
 
@@ -461,6 +464,20 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         HTRY(hipMemcpy(c->gomega, gomega.data(), sizeof(float) * (size_t)R, hipMemcpyHostToDevice));
         TRY(dev_alloc(c, &c->A, (size_t)n));
         TRY(dev_alloc(c, &c->B, (size_t)n));
+        // cell table ordered group by group (stable in the cell id): the mean-field pass skips a head's own
+        // group as one slot range
+        std::vector<int32_t> gcells(R, 0), slot(R);
+        std::vector<int2> gslots(R);
+        for (int32_t r = 0; r < R; ++r) gcells[hgroup[r]]++;
+        int32_t run_slot = 0;
+        for (int32_t g = 0; g < R; ++g) { gslots[g] = make_int2(run_slot, run_slot + gcells[g]); run_slot += gcells[g]; }
+        std::vector<int32_t> next_slot(R);
+        for (int32_t g = 0; g < R; ++g) next_slot[g] = gslots[g].x;
+        for (int32_t r = 0; r < R; ++r) slot[r] = next_slot[hgroup[r]]++;
+        TRY(dev_alloc(c, &c->cell_slot, (size_t)R));
+        TRY(dev_alloc(c, &c->group_slots, (size_t)R));
+        HTRY(hipMemcpy(c->cell_slot, slot.data(), sizeof(int32_t) * (size_t)R, hipMemcpyHostToDevice));
+        HTRY(hipMemcpy(c->group_slots, gslots.data(), sizeof(int2) * (size_t)R, hipMemcpyHostToDevice));
     }
 
     // ---- state buffers

@@ -161,11 +161,13 @@ __global__ void __launch_bounds__(kBlock) k_mean_chunks(const float2* __restrict
     }
 }
 
-// cinfo[r] = (mu_x, mu_y, p_r, group label as bits); one wavefront per cell
+// cinfo[slot of r] = (mu_x, mu_y, p_r, group label as bits), the table ordered group by group when
+// cells are grouped; one wavefront per cell
 __global__ void __launch_bounds__(kBlock) k_mean_finish(const double2* __restrict__ partial,
                                                         const uint32_t* __restrict__ chunk_start,
                                                         const uint32_t* __restrict__ counts,
-                                                        const int32_t* __restrict__ group_of_cluster, int32_t R, double inv_n,
+                                                        const int32_t* __restrict__ group_of_cluster,
+                                                        const int32_t* __restrict__ cell_slot, int32_t R, double inv_n,
                                                         float2* __restrict__ mu, float4* __restrict__ cinfo) {
     const int32_t r = (int32_t)((blockIdx.x * (uint32_t)kBlock + threadIdx.x) >> 6);
     if (r >= R) return;
@@ -182,41 +184,85 @@ __global__ void __launch_bounds__(kBlock) k_mean_finish(const double2* __restric
         const float mx = cnt ? (float)(ax / (double)cnt) : 0.0f;
         const float my = cnt ? (float)(ay / (double)cnt) : 0.0f;
         mu[r] = make_float2(mx, my);
-        cinfo[r] = make_float4(mx, my, (float)((double)cnt * inv_n), __int_as_float(group_of_cluster ? group_of_cluster[r] : 0));
+        cinfo[cell_slot ? cell_slot[r] : r] =
+            make_float4(mx, my, (float)((double)cnt * inv_n), __int_as_float(group_of_cluster ? group_of_cluster[r] : 0));
     }
 }
 
 // ------------------------------------------------------------------ K2: mean-field sums (Eq. 5)
-// One lane per head; the cell table is read with wave-uniform addresses.  Partial sums are folded
-// into the totals every 64 cells to keep float32 round-off from growing with |R|.
+// One lane per head; the cell table is read with wave-uniform addresses (scalar loads), eight
+// cells per batch.  The table is ordered group by group, so the cells a head does NOT approximate
+// (its own group) are one slot range [lo, hi).  Points are usually numbered cluster by cluster,
+// which makes that range the same for all 64 lanes of most wavefronts: those skip the range and
+// need no per-cell test; mixed wavefronts test every cell.  Partial sums are folded into the
+// totals every 64 cells to keep float32 round-off from growing with |R|.
+struct MeanFieldSum { float a, bx, by; };
+
+template <bool TEST>
+__device__ __forceinline__ void mean_field_add(float q, float dx, float dy, const float4 c, int32_t gi, MeanFieldSum& s) {
+    const float w = (TEST && __float_as_int(c.w) == gi) ? 0.0f : c.z;
+    const float wq = w * q;
+    s.a += wq;
+    const float wq2 = wq * q;
+    s.bx = fmaf(wq2, dx, s.bx);
+    s.by = fmaf(wq2, dy, s.by);
+}
+
+template <bool TEST>
+__device__ __forceinline__ void mean_field_cell(const float2 ti, const float4 c, int32_t gi, MeanFieldSum& s) {
+    const float dx = ti.x - c.x, dy = ti.y - c.y;
+    mean_field_add<TEST>(cauchy(dx, dy), dx, dy, c, gi, s);
+}
+
+// Two cells share one reciprocal (the slowest instruction of the loop): with t = 1 + d^2,
+// 1/t0 = t1 / (t0 t1) and 1/t1 = t0 / (t0 t1).
+template <bool TEST>
+__device__ __forceinline__ void mean_field_pair(const float2 ti, const float4 c0, const float4 c1, int32_t gi, MeanFieldSum& s) {
+    const float dx0 = ti.x - c0.x, dy0 = ti.y - c0.y, dx1 = ti.x - c1.x, dy1 = ti.y - c1.y;
+    const float t0 = fmaf(dx0, dx0, fmaf(dy0, dy0, 1.0f)), t1 = fmaf(dx1, dx1, fmaf(dy1, dy1, 1.0f));
+    const float r = __builtin_amdgcn_rcpf(t0 * t1);
+    mean_field_add<TEST>(r * t1, dx0, dy0, c0, gi, s);
+    mean_field_add<TEST>(r * t0, dx1, dy1, c1, gi, s);
+}
+
+template <bool TEST>
+__device__ __forceinline__ void mean_field_range(const float2 ti, const float4* __restrict__ cinfo, int32_t r_begin, int32_t r_end,
+                                                 int32_t gi, MeanFieldSum& total) {
+    for (int32_t r0 = r_begin; r0 < r_end; r0 += 64) {
+        MeanFieldSum s{0.f, 0.f, 0.f};
+        const int32_t r1 = min(r_end, r0 + 64);
+        int32_t r = r0;
+        for (; r + 8 <= r1; r += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; u += 2) mean_field_pair<TEST>(ti, cinfo[r + u], cinfo[r + u + 1], gi, s);
+        }
+        for (; r < r1; ++r) mean_field_cell<TEST>(ti, cinfo[r], gi, s);
+        total.a += s.a; total.bx += s.bx; total.by += s.by;
+    }
+}
+
 __global__ void __launch_bounds__(kBlock) k_mean_field(const float2* __restrict__ theta,
                                                        const int32_t* __restrict__ cluster_of,
                                                        const int32_t* __restrict__ group_of_cluster,
-                                                       const float4* __restrict__ cinfo, int32_t R, int64_t n,
-                                                       float* __restrict__ A, float2* __restrict__ B) {
+                                                       const float4* __restrict__ cinfo, const int2* __restrict__ group_slots,
+                                                       int32_t R, int64_t n, float* __restrict__ A, float2* __restrict__ B) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const float2 ti = theta[i];
-    const int32_t gi = group_of_cluster[cluster_of[i]];
-    float At = 0.f, Bx = 0.f, By = 0.f;
-    for (int32_t r0 = 0; r0 < R; r0 += 64) {
-        float a = 0.f, bx = 0.f, by = 0.f;
-        const int32_t r1 = min(R, r0 + 64);
-        for (int32_t r = r0; r < r1; ++r) {
-            const float4 c = cinfo[r];
-            const float w = (__float_as_int(c.w) == gi) ? 0.0f : c.z;
-            const float dx = ti.x - c.x, dy = ti.y - c.y;
-            const float q = cauchy(dx, dy);
-            const float wq = w * q;
-            a += wq;
-            const float wq2 = wq * q;
-            bx = fmaf(wq2, dx, bx);
-            by = fmaf(wq2, dy, by);
-        }
-        At += a; Bx += bx; By += by;
+    const int64_t ic = min(i, n - 1);   // lanes past the end compute a copy of the last head and store nothing
+    const float2 ti = theta[ic];
+    const int32_t gi = group_of_cluster[cluster_of[ic]];
+    MeanFieldSum t{0.f, 0.f, 0.f};
+    const int32_t g0 = __builtin_amdgcn_readfirstlane(gi);
+    if (__all(gi == g0)) {
+        const int2 own = group_slots[g0];   // wave-uniform
+        mean_field_range<false>(ti, cinfo, 0, own.x, gi, t);
+        mean_field_range<false>(ti, cinfo, own.y, R, gi, t);
+    } else {
+        mean_field_range<true>(ti, cinfo, 0, R, gi, t);
     }
-    A[i] = At;
-    B[i] = make_float2(Bx, By);
+    if (i < n) {
+        A[i] = t.a;
+        B[i] = make_float2(t.bx, t.by);
+    }
 }
 
 // ------------------------------------------------------------------ K3: the edge pass
@@ -293,30 +339,19 @@ struct EdgeOut {
     float rx[S], ry[S];
 };
 
+// The arithmetic of one edge, given the embedding rows it touches (tj the tail, tm[k] the negatives).
 template <int S, bool LOSS>
-__device__ __forceinline__ void edge_terms(const EdgeArgs& P, const HeadCtx& h, int32_t e, EdgeOut<(S > 0 ? S : 1)>& o) {
-    const int32_t j = P.col[e];
-    o.j = j;
-    const float2 tj = P.theta[j];
-    const float pe = P.pe ? P.pe[e] : h.inv_deg;
+__device__ __forceinline__ void edge_math(const HeadCtx& h, float pe, float2 tj, const float2 (&tm)[S > 0 ? S : 1],
+                                          EdgeOut<(S > 0 ? S : 1)>& o) {
     o.dx = h.ti.x - tj.x;
     o.dy = h.ti.y - tj.y;
     const float qij = cauchy(o.dx, o.dy);
-#pragma unroll
-    for (int b = 0; b < (S + 3) / 4; ++b) {
-        uint32_t w[4];
-        philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
-#pragma unroll
-        for (int l = 0; l < 4; ++l)
-            if (4 * b + l < S) o.m[4 * b + l] = draw_index(w[l], h.pop);
-    }
     float qm[S > 0 ? S : 1];
     float qsum = 0.f;
 #pragma unroll
     for (int k = 0; k < S; ++k) {
-        const float2 tm = P.theta[o.m[k]];
-        o.rx[k] = h.ti.x - tm.x;
-        o.ry[k] = h.ti.y - tm.y;
+        o.rx[k] = h.ti.x - tm[k].x;
+        o.ry[k] = h.ti.y - tm[k].y;
         qm[k] = cauchy(o.rx[k], o.ry[k]);
         qsum += qm[k];
     }
@@ -340,6 +375,32 @@ __device__ __forceinline__ void edge_terms(const EdgeArgs& P, const HeadCtx& h, 
     const float c = 2.0f * pe * inv_S;
     o.hx = fx - c * h.MBx;
     o.hy = fy - c * h.MBy;
+}
+
+// The s negatives of CSR position e in epoch P.epoch: Philox words mapped onto the head's population.
+template <int S>
+__device__ __forceinline__ void draw_negatives(const EdgeArgs& P, const Population& pop, int32_t e, int32_t (&m)[S > 0 ? S : 1]) {
+#pragma unroll
+    for (int b = 0; b < (S + 3) / 4; ++b) {
+        uint32_t w[4];
+        philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
+#pragma unroll
+        for (int l = 0; l < 4; ++l)
+            if (4 * b + l < S) m[4 * b + l] = draw_index(w[l], pop);
+    }
+}
+
+template <int S, bool LOSS>
+__device__ __forceinline__ void edge_terms(const EdgeArgs& P, const HeadCtx& h, int32_t e, EdgeOut<(S > 0 ? S : 1)>& o) {
+    const int32_t j = P.col[e];
+    o.j = j;
+    const float2 tj = P.theta[j];
+    const float pe = P.pe ? P.pe[e] : h.inv_deg;
+    draw_negatives<S>(P, h.pop, e, o.m);
+    float2 tm[S > 0 ? S : 1];
+#pragma unroll
+    for (int k = 0; k < S; ++k) tm[k] = P.theta[o.m[k]];
+    edge_math<S, LOSS>(h, pe, tj, tm, o);
 }
 
 // Blocks are handed to the 8 XCDs round-robin; giving XCD x the x-th contiguous eighth of the
@@ -537,11 +598,39 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// What one lane has in flight for its edge of the next round: issued a round ahead, so that the
+// random gathers of round r+1 are served while round r is being sorted and written out.
+template <int S>
+struct EdgeFetch {
+    bool has;
+    int32_t e, i, j, ea, eb;
+    float pe;
+    HeadCtx h;
+    int32_t m[S > 0 ? S : 1];
+    float2 tj, tm[S > 0 ? S : 1];
+};
+
+template <int S>
+__device__ __forceinline__ void issue_edge(const EdgeArgs& P, bool has, int32_t e, int32_t i, int32_t j, EdgeFetch<S>& f) {
+    f.has = has;
+    f.e = e; f.i = has ? i : -1; f.j = j; f.ea = 0; f.eb = 0; f.pe = 0.f;
+    if (!has) return;
+    f.ea = P.row_ptr[i];
+    f.eb = P.row_ptr[i + 1];
+    f.h = load_head(P, i, f.ea, f.eb);
+    f.tj = P.theta[j];
+    f.pe = P.pe ? P.pe[e] : f.h.inv_deg;
+    draw_negatives<S>(P, f.h.pop, e, f.m);
+#pragma unroll
+    for (int k = 0; k < S; ++k) f.tm[k] = P.theta[f.m[k]];
+}
+
 template <int S, int BS>
 __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const BinArgs Q) {
     constexpr int SS = S > 0 ? S : 1;
     constexpr int kWaves = BS / 64;
     constexpr int NREC = BS * (S + 1) + 2 * kWaves;
+    constexpr int kFlushIters = (NREC + BS - 1) / BS;
     extern __shared__ uint32_t lds_bins[];
     const uint32_t B = Q.n_bins;
     uint32_t* start = lds_bins;             // [B+1] A: records this round per tile; after the scan: first sorted slot
@@ -565,30 +654,42 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
     lds_barrier();
 
     const int64_t n_rounds = (e_end - e_begin + BS - 1) / BS;
+    // Software pipeline over rounds: (head, tail) indices are read two rounds ahead, the embedding rows
+    // one round ahead.
+    EdgeFetch<S> f;
+    int32_t i_next = 0, j_next = 0;
+    {
+        const int64_t e0 = e_begin + tid, e1 = e0 + BS;
+        int32_t i0 = 0, j0 = 0;
+        if (e0 < e_end) { i0 = Q.head[e0]; j0 = P.col[e0]; }
+        if (e1 < e_end) { i_next = Q.head[e1]; j_next = P.col[e1]; }
+        issue_edge<S>(P, e0 < e_end, (int32_t)e0, i0, j0, f);
+    }
     for (int64_t round = 0; round < n_rounds; ++round) {
-        // ---- A: one edge per lane; records: slot 0 the tail (force -a d_ij), slots 1..S the negatives,
-        //         slot S+1 the partial head sum of a row that straddles this wavefront
+        // ---- A: one edge per lane; records: slot 0 the tail (force -a d_ij), slots 1..S the negatives
         const int64_t e64 = e_begin + round * BS + tid;
-        const bool has = e64 < e_end;
-        const int32_t e = (int32_t)e64;
+        const bool has = f.has;
+        const int32_t i = f.i, ea = f.ea, eb = f.eb;
         uint32_t dst_pt[S + 1], rank[S + 1];
         float fx[S + 1], fy[S + 1];
 #pragma unroll
         for (int k = 0; k <= S; ++k) { dst_pt[k] = 0u; rank[k] = 0u; fx[k] = 0.f; fy[k] = 0.f; }
-        int32_t i = -1, ea = 0, eb = 0;
         float hx = 0.f, hy = 0.f;
         if (has) {
-            i = Q.head[e];
-            ea = P.row_ptr[i];
-            eb = P.row_ptr[i + 1];
-            const HeadCtx h = load_head(P, i, ea, eb);
             EdgeOut<SS> o;
-            edge_terms<S, false>(P, h, e, o);
+            edge_math<S, false>(f.h, f.pe, f.tj, f.tm, o);
             hx = o.hx;
             hy = o.hy;
-            dst_pt[0] = (uint32_t)o.j; fx[0] = -o.a * o.dx; fy[0] = -o.a * o.dy;
+            dst_pt[0] = (uint32_t)f.j; fx[0] = -o.a * o.dx; fy[0] = -o.a * o.dy;
 #pragma unroll
-            for (int k = 0; k < S; ++k) { dst_pt[k + 1] = (uint32_t)o.m[k]; fx[k + 1] = o.rx[k]; fy[k + 1] = o.ry[k]; }
+            for (int k = 0; k < S; ++k) { dst_pt[k + 1] = (uint32_t)f.m[k]; fx[k + 1] = o.rx[k]; fy[k + 1] = o.ry[k]; }
+        }
+        // the loads of the next round go out before this round is sorted and written
+        {
+            const int64_t e1 = e64 + BS, e2 = e1 + BS;
+            const int32_t i1 = i_next, j1 = j_next;
+            if (e2 < e_end) { i_next = Q.head[e2]; j_next = P.col[e2]; }
+            issue_edge<S>(P, e1 < e_end, (int32_t)e1, i1, j1, f);
         }
         // head sum of each row: segmented inclusive scan over the lanes of the row, in lane order
 #pragma unroll
@@ -599,8 +700,8 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
         }
         // the last lane of a row holds the row's sum: stored directly when the whole row lies inside this
         // wavefront, else handed on as one more record (hx, hy for point i)
-        const int32_t i_next = __shfl_down(i, 1, 64);
-        const bool row_end = has && (lane == 63 || i_next != i);
+        const int32_t i_after = __shfl_down(i, 1, 64);
+        const bool row_end = has && (lane == 63 || i_after != i);
         const int64_t wave_e0 = e64 - lane;
         const bool inside = (int64_t)ea >= wave_e0 && (int64_t)eb <= min(wave_e0 + 64, e_end);
         const bool head_rec = row_end && !inside;
@@ -640,9 +741,9 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
                 const uint32_t c = cnt_own[x];
                 start[b] = run;
                 run += c;
-                const uint32_t f = fill[b];
-                if (c != 0 && f + c > (uint32_t)kChunk) {
-                    const uint32_t k = (f + c - 1) / kChunk;
+                const uint32_t fl = fill[b];
+                if (c != 0 && fl + c > (uint32_t)kChunk) {
+                    const uint32_t k = (fl + c - 1) / kChunk;
                     const uint32_t nb = atomicAdd(&pool_cursor, k);
                     base[b] = nb;
                     if (nb + k > pool_end) *Q.overflow = 1;
@@ -654,11 +755,11 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
         lds_barrier();
         // ---- C: records to their sorted slots
         if (has) {
+            uint32_t p[S + 1];
 #pragma unroll
-            for (int k = 0; k <= S; ++k) {
-                const uint32_t p = start[dst_pt[k] >> tb] + rank[k];
-                rec_pt[p] = dst_pt[k]; rec_x[p] = __float_as_uint(fx[k]); rec_y[p] = __float_as_uint(fy[k]);
-            }
+            for (int k = 0; k <= S; ++k) p[k] = start[dst_pt[k] >> tb] + rank[k];
+#pragma unroll
+            for (int k = 0; k <= S; ++k) { rec_pt[p[k]] = dst_pt[k]; rec_x[p[k]] = __float_as_uint(fx[k]); rec_y[p[k]] = __float_as_uint(fy[k]); }
         }
         if (head_rec) {
             const uint32_t p = start[head_bin] + head_rank;
@@ -667,18 +768,22 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
         lds_barrier();
         // ---- D: consecutive lanes write consecutive sorted records to the chains
         const uint32_t total = start[B];
-        for (uint32_t p = tid; p < total; p += BS) {
-            const uint32_t pt = rec_pt[p];
-            const uint32_t b = pt >> tb;
-            const uint32_t pos = fill[b] + (p - start[b]);
-            uint32_t ch, off;
-            if (pos < (uint32_t)kChunk) { ch = chunk[b]; off = pos; }
-            else { ch = base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
-            if (ch < pool_end) {   // kNoChunk is above any valid id
-                uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
-                dst[0] = pt & ((1u << tb) - 1u);
-                dst[1] = rec_x[p];
-                dst[2] = rec_y[p];
+#pragma unroll
+        for (int it = 0; it < kFlushIters; ++it) {
+            const uint32_t p = (uint32_t)tid + (uint32_t)it * BS;
+            if (p < total) {
+                const uint32_t pt = rec_pt[p];
+                const uint32_t b = pt >> tb;
+                const uint32_t pos = fill[b] + (p - start[b]);
+                uint32_t ch, off;
+                if (pos < (uint32_t)kChunk) { ch = chunk[b]; off = pos; }
+                else { ch = base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
+                if (ch < pool_end) {   // kNoChunk is above any valid id
+                    uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
+                    dst[0] = pt & ((1u << tb) - 1u);
+                    dst[1] = rec_x[p];
+                    dst[2] = rec_y[p];
+                }
             }
         }
         lds_barrier();
@@ -689,13 +794,13 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
             if (b < b1) {
                 const uint32_t c = cnt_own[x];
                 if (c != 0) {
-                    const uint32_t f = fill[b];
-                    if (f + c > (uint32_t)kChunk) {
-                        const uint32_t k = (f + c - 1) / kChunk;
+                    const uint32_t fl = fill[b];
+                    if (fl + c > (uint32_t)kChunk) {
+                        const uint32_t k = (fl + c - 1) / kChunk;
                         chunk[b] = base[b] + k - 1;
-                        fill[b] = f + c - k * kChunk;
+                        fill[b] = fl + c - k * kChunk;
                     } else {
-                        fill[b] = f + c;
+                        fill[b] = fl + c;
                     }
                 }
                 start[b] = 0;

@@ -198,6 +198,50 @@ def test_resume_from_embedding_and_epoch_index_is_bit_exact():
         assert np.array_equal(nm.get_embedding(), straight)
 
 
+# ------------------------------------------------------------------ the binned deterministic path
+def skewed_degree_graph(seed, n=6000, hubs=3):
+    """Directed graph whose rows range from one edge to several thousand: rows that end inside a wavefront,
+    rows that straddle wavefronts, and hub rows that span several rounds and workgroups of the edge pass."""
+    rng = np.random.default_rng(seed)
+    deg = rng.integers(1, 40, n)
+    deg[rng.choice(n, 40, replace=False)] = rng.integers(65, 300, 40)
+    deg[rng.choice(n, hubs, replace=False)] = rng.integers(1500, 4000, hubs)
+    deg[rng.choice(n, 50, replace=False)] = 0
+    rows, cols = [], []
+    for i in range(n):
+        c = rng.choice(n - 1, int(deg[i]), replace=False)
+        c[c >= i] += 1                               # no self loops, distinct tails
+        cols.append(np.sort(c))
+    row_ptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    R = 7
+    return dict(n=n, row_ptr=row_ptr, col_idx=np.concatenate(cols).astype(np.int32), weights=None,
+                cluster_of=rng.integers(0, R, n).astype(np.int32), n_clusters=R, cluster_group=None,
+                theta0=(rng.normal(size=(n, 2)) * 0.7).astype(np.float32), n_neg=5, noise_count=5.0, n_epochs=10, lr0=0.2,
+                seed=seed + 99)
+
+
+@pytest.mark.parametrize("env", [{}, {"NOMAD_BIN_BLOCK": "512"}, {"NOMAD_WG_PER_CU": "3"}, {"NOMAD_NO_BINNING": "1"}],
+                         ids=["1024-lane", "512-lane", "3-per-cu", "fixed-point-atomics"])
+def test_deterministic_variants_on_skewed_degrees(env, monkeypatch):
+    """Every launch shape of the deterministic path gives the oracle's gradient, and the same embedding bit for bit
+    when run twice, on rows of very different lengths."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    d = skewed_degree_graph(4)
+    O = c_oracle.COracle(**d)
+    th1, g_ref, _ = O.epoch(d["theta0"], 0)
+    out = []
+    for _ in range(2):
+        with make_nomad(d, SCATTER_DETERMINISTIC) as nm:
+            nm.epoch(0)
+            g = nm.get_gradient()
+            nm.epoch(1)
+            out.append((g, nm.get_embedding()))
+    note(f"  {env}: grad err {grad_err(out[0][0], g_ref):.2e}")
+    assert grad_err(out[0][0], g_ref) < GRAD_TOL
+    assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
+
+
 # ------------------------------------------------------------------ degenerate and edge cases
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("s", [0, 1, 4, 8, 9, 16])
