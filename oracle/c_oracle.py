@@ -25,7 +25,8 @@ def build(force: bool = False) -> str:
 class _Problem(C.Structure):
     _fields_ = [("n", C.c_int64), ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("weights", C.c_void_p),
                 ("cluster_of", C.c_void_p), ("n_clusters", C.c_int32), ("cluster_group", C.c_void_p),
-                ("n_neg", C.c_int32), ("noise_count", C.c_double), ("seed", C.c_uint64)]
+                ("n_neg", C.c_int32), ("noise_count", C.c_double), ("seed", C.c_uint64),
+                ("pool_size", C.c_int32), ("pool_block", C.c_int32)]
 
 
 def _load():
@@ -50,7 +51,7 @@ class COracle:
     """Holds int32/fp32 copies of a problem and calls the C oracle on them."""
 
     def __init__(self, *, n, row_ptr, col_idx, cluster_of, n_clusters, n_neg, noise_count, seed=0, n_epochs=1,
-                 lr0=1.0, weights=None, cluster_group=None, **_ignored):
+                 lr0=1.0, weights=None, cluster_group=None, pool_size=0, pool_block=0, **_ignored):
         self.lib = _load()
         self.n = int(n)
         self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
@@ -64,8 +65,12 @@ class COracle:
         self.seed = int(seed)
         self.n_epochs = int(n_epochs)
         self.lr0 = float(lr0)
+        self.pool_size, self.pool_block = int(pool_size), int(pool_block)
+        assert (self.pool_size == 0) == (self.pool_block == 0), "pool_size and pool_block go together"
+        assert self.pool_size == 0 or self.cluster_group is None, "the pooled sampler needs a single population"
         self.P = _Problem(self.n, _ptr(self.row_ptr), _ptr(self.col_idx), _ptr(self.weights), _ptr(self.cluster_of),
-                          self.n_clusters, _ptr(self.cluster_group), self.n_neg, self.noise_count, self.seed)
+                          self.n_clusters, _ptr(self.cluster_group), self.n_neg, self.noise_count, self.seed,
+                          self.pool_size, self.pool_block)
 
     @property
     def n_edges(self):

@@ -39,6 +39,8 @@ typedef struct {
     int32_t n_neg;                /* s                                                */
     double noise_count;           /* |M|                                              */
     uint64_t seed;
+    int32_t pool_size;            /* pooled sampler: points per pool (0 = i.i.d. per-edge sampler) */
+    int32_t pool_block;           /* pooled sampler: consecutive CSR positions that share a pool   */
 } oracle_problem;
 
 /* ---- Philox4x32-10 (published algorithm: Salmon, Moraes, Dror, Shaw, SC'11) ---- */
@@ -108,7 +110,14 @@ static inline int32_t group_of_point(const oracle_problem* P, int64_t i) {
     return P->cluster_group ? P->cluster_group[P->cluster_of[i]] : 0;
 }
 
-/* negatives of edge e with head i: m[slot], slot < s */
+/* negatives of edge e with head i: m[slot], slot < s.
+ * i.i.d. sampler: word (slot & 3) of Philox(counter (lo32 e, hi32 e, t, slot >> 2)) picks a point of the
+ * head's population.
+ * pooled sampler (opt-in variant, not the paper's i.i.d. noise samples; needs a single population): the
+ * pool_block consecutive CSR positions of block beta = e / pool_block share a pool of pool_size points,
+ * pool[u] = point picked by word (u & 3) of Philox(counter (beta, 0xFFFFFFFF, t, u >> 2)); the same
+ * per-edge word as above picks the pool entry u instead of a point.  Every negative is still uniform
+ * over the points; negatives of different edges of a block are no longer independent. */
 static void edge_negatives(const oracle_problem* P, const oracle_tables* T, int64_t e, int64_t i, int32_t t, int32_t* m) {
     int32_t g = group_of_point(P, i);
     int64_t base = T->gstart[g];
@@ -119,8 +128,18 @@ static void edge_negatives(const oracle_problem* P, const oracle_tables* T, int6
         uint32_t w[4];
         oracle_philox4x32_10(ctr, key, w);
         for (int32_t lane = 0; lane < 4 && 4 * blk + lane < P->n_neg; ++lane) {
-            uint64_t u = ((uint64_t)w[lane] * nloc) >> 32;
-            m[4 * blk + lane] = T->members[base + (int64_t)u];
+            if (P->pool_size > 0) {
+                uint64_t u = ((uint64_t)w[lane] * (uint64_t)P->pool_size) >> 32;
+                uint64_t beta = (uint64_t)e / (uint64_t)P->pool_block;
+                uint32_t pctr[4] = {(uint32_t)beta, 0xFFFFFFFFu, (uint32_t)t, (uint32_t)(u >> 2)};
+                uint32_t pw[4];
+                oracle_philox4x32_10(pctr, key, pw);
+                uint64_t pt = ((uint64_t)pw[u & 3] * nloc) >> 32;
+                m[4 * blk + lane] = T->members[base + (int64_t)pt];
+            } else {
+                uint64_t u = ((uint64_t)w[lane] * nloc) >> 32;
+                m[4 * blk + lane] = T->members[base + (int64_t)u];
+            }
         }
     }
 }

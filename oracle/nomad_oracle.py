@@ -27,6 +27,9 @@ Readings where the paper is silent (each one is listed in the design notes):
     negatives; the step uses n * grad(L) so lr0 is in per-point units;
   - negatives: Philox4x32-10, counter (lo32(e), hi32(e), t, slot>>2), key (lo32(seed),
     hi32(seed)), word slot&3, index = high word of x * n_loc(i); no rejection;
+  - opt-in pooled sampler (a variant, not the paper's i.i.d. noise samples): blocks of
+    pool_block consecutive CSR positions share a pool of pool_size uniformly drawn points and
+    the per-edge word picks a pool entry (see negatives());
   - the cells approximated for head i are those whose group differs from the group of
     i's own cluster; negatives are drawn from the points of i's own group (ascending
     index order) and weighted by omega_i = |M| * (n_loc(i)/n) / s;
@@ -106,6 +109,8 @@ class Problem:
     lr0: float = 1.0
     weights: Optional[np.ndarray] = None      # [E] or None = unit
     cluster_group: Optional[np.ndarray] = None  # [n_clusters] or None = one group
+    pool_size: int = 0                        # pooled sampler: points per pool (0 = i.i.d. per-edge sampler)
+    pool_block: int = 0                       # pooled sampler: consecutive CSR positions that share a pool
 
     def __post_init__(self):
         self.row_ptr = np.asarray(self.row_ptr, dtype=np.int64)
@@ -117,6 +122,8 @@ class Problem:
             self.cluster_group = np.asarray(self.cluster_group, dtype=np.int64)
         if self.noise_count <= 0:
             self.noise_count = float(self.n_neg)
+        assert (self.pool_size == 0) == (self.pool_block == 0), "pool_size and pool_block go together"
+        assert self.pool_size == 0 or self.cluster_group is None, "the pooled sampler needs a single population"
 
     @property
     def n_edges(self) -> int:
@@ -127,7 +134,7 @@ class Problem:
         d = dict(n=w["n"], row_ptr=w["row_ptr"], col_idx=w["col_idx"], cluster_of=w["cluster_of"],
                  n_clusters=w["n_clusters"], n_neg=w["n_neg"], noise_count=w["noise_count"], seed=w["seed"],
                  n_epochs=w["n_epochs"], lr0=w["lr0"], weights=w.get("weights"),
-                 cluster_group=w.get("cluster_group"))
+                 cluster_group=w.get("cluster_group"), pool_size=w.get("pool_size", 0), pool_block=w.get("pool_block", 0))
         d.update(over)
         return cls(**d)
 
@@ -205,8 +212,25 @@ def mean_field(P: Problem, theta: np.ndarray, p_r: np.ndarray, mu: np.ndarray):
     return A, B
 
 
+def pool_of_block(P: Problem, beta: int, t: int) -> np.ndarray:
+    """Pooled sampler: the pool_size points shared by the CSR positions of block beta in epoch t.
+    Entry u is picked by word u & 3 of Philox(counter (beta, 0xFFFFFFFF, t, u >> 2)) (the second
+    counter word keeps this stream apart from the per-edge one, whose second word is hi32(e) = 0)."""
+    k0, k1 = P.seed & _MASK32, (P.seed >> 32) & _MASK32
+    pool = np.zeros(P.pool_size, dtype=np.int64)
+    for u in range(P.pool_size):
+        words = philox4x32_10((beta & _MASK32, _MASK32, t, u >> 2), (k0, k1))
+        pool[u] = (words[u & 3] * P.n) >> 32
+    return pool
+
+
 def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None) -> np.ndarray:
-    """Sampled negative indices m[e, slot] for the CSR edges e_begin..e_end-1 of epoch t."""
+    """Sampled negative indices m[e, slot] for the CSR edges e_begin..e_end-1 of epoch t.
+
+    i.i.d. sampler (the paper's |M| i.i.d. noise samples per edge, Section 3.1/3.3): the per-edge
+    Philox word picks a point of the head's population.  Pooled sampler (opt-in variant): the same
+    word picks an entry of the pool shared by the edge's block of pool_block CSR positions; each
+    negative is still uniform over the points, negatives of one block are no longer independent."""
     if e_end is None:
         e_end = P.n_edges
     s = P.n_neg
@@ -217,6 +241,7 @@ def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None)
     head = np.searchsorted(P.row_ptr, np.arange(e_begin, e_end), side="right") - 1
     e = np.arange(e_begin, e_end, dtype=np.uint64)
     k0, k1 = P.seed & _MASK32, (P.seed >> 32) & _MASK32
+    pools = {}
     for blk in range((s + 3) // 4):
         words = philox4x32_10_array(e & np.uint64(_MASK32), e >> np.uint64(32), np.uint64(t), np.uint64(blk), k0, k1)
         for lane in range(4):
@@ -225,9 +250,15 @@ def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None)
                 break
             x = words[lane]
             for idx in range(e_end - e_begin):
-                pop = members[int(gop[head[idx]])]
-                u = (int(x[idx]) * len(pop)) >> 32
-                out[idx, slot] = pop[u]
+                if P.pool_size > 0:
+                    beta = (e_begin + idx) // P.pool_block
+                    if beta not in pools:
+                        pools[beta] = pool_of_block(P, beta, t)
+                    out[idx, slot] = pools[beta][(int(x[idx]) * P.pool_size) >> 32]
+                else:
+                    pop = members[int(gop[head[idx]])]
+                    u = (int(x[idx]) * len(pop)) >> 32
+                    out[idx, slot] = pop[u]
     return out
 
 

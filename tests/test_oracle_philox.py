@@ -109,3 +109,57 @@ def test_uniformity_chi_square():
     # slots are not copies of one another
     assert (neg[:, 0] != neg[:, 1]).mean() > 0.99
     assert (neg[:, 3] != neg[:, 4]).mean() > 0.99
+
+
+# ------------------------------------------------------------------ pooled sampler (opt-in variant)
+@pytest.mark.parametrize("impl", ["py", "c"])
+def test_pooled_negative_is_pool_entry_picked_by_the_edge_word(impl):
+    """m[e,slot] = pool_beta[floor(x * P / 2^32)], beta = e // G, x the per-edge word of the i.i.d. sampler,
+    pool_beta[u] = floor(y * n / 2^32) with y = word u&3 of Philox(counter=(beta, 0xFFFFFFFF, t, u>>2))."""
+    n, s, seed, t, P, G = 1000, 6, (7 << 32) | 99, 4, 48, 128
+    row_ptr, col = _ring(n)
+    O = IMPLS[impl](n=n, row_ptr=row_ptr, col_idx=col, cluster_of=np.zeros(n, int), n_clusters=1, n_neg=s,
+                    noise_count=s, seed=seed, pool_size=P, pool_block=G)
+    neg = O.negatives(t)
+    key = (seed & 0xFFFFFFFF, seed >> 32)
+    for e in (0, 127, 128, 1031, 2 * n - 1):
+        for slot in range(s):
+            x = po.philox4x32_10((e, 0, t, slot >> 2), key)[slot & 3]
+            u = (x * P) >> 32
+            y = po.philox4x32_10((e // G, 0xFFFFFFFF, t, u >> 2), key)[u & 3]
+            assert neg[e, slot] == (y * n) >> 32
+    assert np.array_equal(O.negatives(t, 100, 300), neg[100:300])      # a range that crosses a block boundary
+    assert not np.array_equal(O.negatives(t + 1), neg)
+
+
+def test_pooled_blocks_share_at_most_pool_size_points_and_differ_between_blocks():
+    n, s, P, G = 5000, 5, 32, 512
+    row_ptr, col = _ring(n)
+    O = IMPLS["c"](n=n, row_ptr=row_ptr, col_idx=col, cluster_of=np.zeros(n, int), n_clusters=1, n_neg=s,
+                   noise_count=s, seed=5, pool_size=P, pool_block=G)
+    neg = O.negatives(0)
+    pools = [set(neg[b * G:(b + 1) * G].reshape(-1).tolist()) for b in range(len(neg) // G)]
+    assert all(len(p) <= P for p in pools)
+    assert all(len(p) >= P - 2 for p in pools)          # 2560 picks among 32 entries hit every entry; entries may coincide
+    assert len(pools[0] & pools[1]) <= 2                # independent pools of 32 among 5000 points
+    # one entry per pool: every negative of a block is the same point (degenerate case, closed form)
+    O1 = IMPLS["c"](n=n, row_ptr=row_ptr, col_idx=col, cluster_of=np.zeros(n, int), n_clusters=1, n_neg=s,
+                    noise_count=s, seed=5, pool_size=1, pool_block=G)
+    neg1 = O1.negatives(0)
+    for b in range(3):
+        assert len(set(neg1[b * G:(b + 1) * G].reshape(-1).tolist())) == 1
+
+
+def test_pool_entries_are_uniform_over_the_points():
+    """The pool entries are the only place where points are drawn: chi-square on 500 pools of 64 entries.
+    (The pick of an entry does not look at the pool, so every negative inherits this marginal.)"""
+    n = 4000
+    row_ptr, col = _ring(n)
+    P = po.Problem(n=n, row_ptr=row_ptr, col_idx=col, cluster_of=np.zeros(n, int), n_clusters=1, n_neg=5,
+                   noise_count=5, seed=77, pool_size=64, pool_block=16)
+    draws = np.concatenate([po.pool_of_block(P, beta, 2) for beta in range(500)])
+    bins = np.bincount(draws * 50 // n, minlength=50).astype(float)
+    exp = draws.size / 50
+    assert ((bins - exp) ** 2 / exp).sum() < 100.0      # 49 dof: mean 49, sd 9.9
+    assert not np.array_equal(po.pool_of_block(P, 0, 2), po.pool_of_block(P, 0, 3))
+    assert not np.array_equal(po.pool_of_block(P, 0, 2), po.pool_of_block(P, 1, 2))

@@ -369,6 +369,25 @@ def test_sample_weight_makes_the_negative_term_unbiased():
     assert abs((est - want).mean()) < 0.003 * want.mean()
 
 
+def test_pooled_sampler_keeps_the_negative_term_unbiased():
+    """Pool entries are uniform over the points and the pick ignores the pool, so the pooled sample sum has the
+    same expectation as the i.i.d. one: |M| (1/n) sum_l q_il for every edge."""
+    n = 40
+    kw = _random_problem(n, 23, groups=False, s=4, M=6.0)
+    O = IMPLS["c"](**kw, pool_size=8, pool_block=16)
+    theta = _grid_theta(n, 23).astype(np.float64)
+    head = np.searchsorted(kw["row_ptr"], np.arange(len(kw["col_idx"])), side="right") - 1
+    q = 1.0 / (1.0 + ((theta[:, None, :] - theta[None, :, :]) ** 2).sum(-1))
+    est = np.zeros(len(head))
+    T = 3000
+    for t in range(T):
+        est += (6.0 / 4) * q[head[:, None], O.negatives(t)].sum(1)
+    est /= T
+    want = 6.0 * q[head].mean(1)
+    assert np.abs(est - want).max() < 0.05 * want.max()
+    assert abs((est - want).mean()) < 0.003 * want.mean()
+
+
 # ---------------------------------------------------------------- means, update, weights, metric
 @BOTH
 def test_cluster_statistics(impl):
