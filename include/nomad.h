@@ -65,7 +65,24 @@ typedef struct {
     int32_t batches_per_epoch; /* reserved, must be 1                                                 */
     int32_t device;            /* HIP device ordinal                                                  */
     void* stream;              /* hipStream_t borrowed from the caller; NULL = the null stream        */
+    int32_t pool_size;         /* 0: the paper's i.i.d. negatives per edge.  1..NOMAD_MAX_POOL: opt-in */
+                               /* pooled sampler, points per pool (see below)                         */
+    int32_t pool_block;        /* pooled sampler: consecutive CSR positions sharing one pool, >= 1;    */
+                               /* must be 0 exactly when pool_size is 0                               */
 } nomad_config;
+
+/*
+ * Pooled sampler (opt-in variant; NOT the i.i.d. noise samples of Section 3.1/3.3).  The CSR positions
+ * are cut into blocks of pool_block consecutive positions.  Block beta draws, per epoch t, a pool of
+ * pool_size points, entry u = point picked by word (u & 3) of Philox(counter (beta, 0xFFFFFFFF, t, u >> 2),
+ * key seed).  Slot k of edge e takes the pool entry picked by the same per-edge word that would pick a
+ * point under the i.i.d. sampler.  Every negative is still uniform over the points, so the sampled loss
+ * stays an unbiased estimate of Eq. 2; negatives of one block are no longer independent.  The pool lives
+ * in LDS, which replaces s random 128-byte line fetches and s scattered force records per edge by
+ * pool_size of each per block.  Needs cluster_group = NULL (one sampling population).  The fast kernel
+ * applies when pool_block is a multiple of 1024; other values run the general kernels.
+ */
+#define NOMAD_MAX_POOL 4096
 
 /* Create a context.  Allocates nothing on the device yet.  *out is set only on success. */
 int nomad_create(const nomad_config* cfg, nomad_ctx** out);

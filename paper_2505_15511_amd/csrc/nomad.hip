@@ -153,6 +153,7 @@ EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
     a.A = c->A; a.B = c->B;
     a.noise_count = c->noise_count; a.omega0 = c->omega0;
     a.key0 = (uint32_t)c->cfg.seed; a.key1 = (uint32_t)(c->cfg.seed >> 32); a.epoch = t;
+    a.pool_size = (uint32_t)c->cfg.pool_size; a.pool_block = (uint32_t)c->cfg.pool_block;
     a.s = c->cfg.n_neg; a.n = c->n;
     a.g = c->g; a.ghead = c->ghead; a.gfix = c->gfix; a.loss_partial = c->loss_partial;
     return a;
@@ -273,6 +274,8 @@ int nomad_create(const nomad_config* cfg, nomad_ctx** out) {
         cfg->batches_per_epoch != 1 || !(cfg->lr0 >= 0.f) || !std::isfinite(cfg->lr0) || !std::isfinite(cfg->noise_count) ||
         (cfg->scatter_mode != NOMAD_SCATTER_DETERMINISTIC && cfg->scatter_mode != NOMAD_SCATTER_ATOMIC) || cfg->device < 0)
         return NOMAD_E_INVALID_ARG;
+    if (cfg->pool_size < 0 || cfg->pool_size > NOMAD_MAX_POOL || cfg->pool_block < 0 || (cfg->pool_size == 0) != (cfg->pool_block == 0))
+        return NOMAD_E_INVALID_ARG;
     if (cfg->n_points >= ((int64_t)1 << 31) || cfg->n_clusters > cfg->n_points) return cfg->n_points >= ((int64_t)1 << 31) ? NOMAD_E_TOO_LARGE : NOMAD_E_INVALID_ARG;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device >= ndev) return NOMAD_E_HIP;
@@ -345,6 +348,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
             if (hgroup[r] < 0 || hgroup[r] >= R) { dev_free(wdev); free_graph(c); return fail(c, NOMAD_E_BAD_GRAPH, "cluster_group[%d] = %d is outside 0..|R|-1", r, hgroup[r]); }
         for (int32_t r = 1; r < R; ++r)
             if (hgroup[r] != hgroup[0]) c->grouped = true;   // one label everywhere == nothing approximated
+        if (c->grouped && c->cfg.pool_size > 0) { dev_free(wdev); free_graph(c); return fail(c, NOMAD_E_INVALID_ARG, "the pooled sampler needs a single sampling population (cluster_group = NULL)"); }
         if (c->grouped) {
             rc = dev_alloc(c, &c->group_of_cluster, (size_t)R);
             if (rc == NOMAD_OK && hipMemcpy(c->group_of_cluster, hgroup.data(), sizeof(int32_t) * (size_t)R, hipMemcpyHostToDevice) != hipSuccess) rc = fail(c, NOMAD_E_HIP, "upload of cluster_group failed");

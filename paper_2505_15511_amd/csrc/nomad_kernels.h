@@ -282,6 +282,7 @@ struct EdgeArgs {
     float noise_count;             // |M|
     float omega0;                  // single-group omega
     uint32_t key0, key1, epoch;
+    uint32_t pool_size, pool_block;   // pooled sampler (0, 0 = i.i.d. negatives per edge)
     int32_t s;
     int64_t n;
     uint32_t rows_per_xcd_span;    // for the block -> row remap
@@ -377,7 +378,18 @@ __device__ __forceinline__ void edge_math(const HeadCtx& h, float pe, float2 tj,
     o.hy = fy - c * h.MBy;
 }
 
-// The s negatives of CSR position e in epoch P.epoch: Philox words mapped onto the head's population.
+// Point picked by one 32-bit word x of the per-edge stream.  i.i.d. sampler: a point of the head's
+// population.  Pooled sampler: entry u = hi32(x * pool_size) of the pool of the edge's block, itself the
+// point picked by word u & 3 of Philox(counter (block, 0xFFFFFFFF, epoch, u >> 2)).
+__device__ __forceinline__ int32_t pick_negative(const EdgeArgs& P, const Population& pop, int32_t e, uint32_t x) {
+    if (P.pool_size == 0) return draw_index(x, pop);
+    const uint32_t u = __umulhi(x, P.pool_size);
+    uint32_t w[4];
+    philox4x32_10((uint32_t)e / P.pool_block, 0xFFFFFFFFu, P.epoch, u >> 2, P.key0, P.key1, w);
+    return draw_index(w[u & 3u], pop);
+}
+
+// The s negatives of CSR position e in epoch P.epoch.
 template <int S>
 __device__ __forceinline__ void draw_negatives(const EdgeArgs& P, const Population& pop, int32_t e, int32_t (&m)[S > 0 ? S : 1]) {
 #pragma unroll
@@ -386,7 +398,7 @@ __device__ __forceinline__ void draw_negatives(const EdgeArgs& P, const Populati
         philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
 #pragma unroll
         for (int l = 0; l < 4; ++l)
-            if (4 * b + l < S) m[4 * b + l] = draw_index(w[l], pop);
+            if (4 * b + l < S) m[4 * b + l] = pick_negative(P, pop, e, w[l]);
     }
 }
 
@@ -427,7 +439,7 @@ __device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const Head
         uint32_t w[4];
         philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
         for (int l = 0; l < 4 && 4 * b + l < s; ++l) {
-            const float2 tm = P.theta[draw_index(w[l], h.pop)];
+            const float2 tm = P.theta[pick_negative(P, h.pop, e, w[l])];
             qsum += cauchy(h.ti.x - tm.x, h.ti.y - tm.y);
         }
     }
@@ -441,7 +453,7 @@ __device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const Head
         uint32_t w[4];
         philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
         for (int l = 0; l < 4 && 4 * b + l < s; ++l) {
-            const int32_t mk = draw_index(w[l], h.pop);
+            const int32_t mk = pick_negative(P, h.pop, e, w[l]);
             const float2 tm = P.theta[mk];
             const float gx = h.ti.x - tm.x, gy = h.ti.y - tm.y;
             const float q = cauchy(gx, gy);
@@ -972,7 +984,7 @@ __global__ void __launch_bounds__(kBlock) k_negatives(const EdgeArgs P, int64_t 
     for (int b = 0; 4 * b < P.s; ++b) {
         uint32_t w[4];
         philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
-        for (int l = 0; l < 4 && 4 * b + l < P.s; ++l) out[(e - e_begin) * P.s + 4 * b + l] = draw_index(w[l], pop);
+        for (int l = 0; l < 4 && 4 * b + l < P.s; ++l) out[(e - e_begin) * P.s + 4 * b + l] = pick_negative(P, pop, (int32_t)e, w[l]);
     }
 }
 

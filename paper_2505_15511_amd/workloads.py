@@ -48,6 +48,8 @@ class Workload:
     out_nbrs: Optional[torch.Tensor] = None        # int32 [n,k]: planted / exact kNN lists before symmetrisation
     X: Optional[torch.Tensor] = None               # float32 [n,dim] high-d points (GMM configs only)
     k: int = 15
+    pool_size: int = 0             # opt-in pooled sampler: points per pool (0 = i.i.d. negatives per edge)
+    pool_block: int = 0            # opt-in pooled sampler: consecutive CSR positions sharing a pool
 
     @property
     def n_edges(self) -> int:
@@ -60,7 +62,7 @@ class Workload:
             n=self.n, row_ptr=h(self.row_ptr), col_idx=h(self.col_idx), weights=h(self.weights),
             cluster_of=h(self.cluster_of), n_clusters=self.n_clusters, cluster_group=h(self.cluster_group),
             theta0=h(self.theta0), n_neg=self.n_neg, noise_count=self.noise_count,
-            n_epochs=self.n_epochs, lr0=self.lr0, seed=self.seed,
+            n_epochs=self.n_epochs, lr0=self.lr0, seed=self.seed, pool_size=self.pool_size, pool_block=self.pool_block,
         )
 
 

@@ -39,9 +39,10 @@ def test_only_the_abi_is_exported():
 
 
 def test_config_struct_layout_matches_header():
-    # uint32 | int64 | int32 int32 | float int32 | float (pad) | uint64 | int32 int32 | int32 (pad) | void*
-    assert C.sizeof(binding.NomadConfig) == 72
+    # uint32 | int64 | int32 int32 | float int32 | float (pad) | uint64 | int32 int32 | int32 (pad) | void* | int32 int32
+    assert C.sizeof(binding.NomadConfig) == 80
     assert binding.NomadConfig.seed.offset == 40 and binding.NomadConfig.stream.offset == 64
+    assert binding.NomadConfig.pool_size.offset == 72 and binding.NomadConfig.pool_block.offset == 76
 
 
 def test_argument_errors_before_any_device_work(lib):

@@ -53,7 +53,8 @@ def small_random(seed, n=3000, R=12, groups=True, weights=True, contiguous=False
 
 
 def make_nomad(d, mode):
-    nm = Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode)
+    nm = Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
+               pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0))
     nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
     nm.set_embedding(d["theta0"])
     return nm
@@ -240,6 +241,48 @@ def test_deterministic_variants_on_skewed_degrees(env, monkeypatch):
     note(f"  {env}: grad err {grad_err(out[0][0], g_ref):.2e}")
     assert grad_err(out[0][0], g_ref) < GRAD_TOL
     assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
+
+
+# ------------------------------------------------------------------ the opt-in pooled sampler
+POOLS = [pytest.param((48, 100), id="P48-G100-general-kernels"), pytest.param((2048, 4096), id="P2048-G4096"),
+         pytest.param((1000, 1024), id="P1000-G1024"), pytest.param((4096, 2048), id="P4096-G2048")]
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("pool", POOLS)
+def test_pooled_sampler_negatives_gradient_and_loss(pool, mode):
+    for case in ("config3@0.05", "skewed"):
+        d = dict(workload(3, 0.05).numpy()) if case != "skewed" else skewed_degree_graph(6)
+        d["pool_size"], d["pool_block"] = pool
+        O = c_oracle.COracle(**d)
+        th1, g_ref, _ = O.epoch(d["theta0"], 0)
+        L_ref, _ = O.loss_and_grad(th1, 1, want_grad=False)
+        with make_nomad(d, mode) as nm:
+            assert np.array_equal(nm.get_negatives(0), O.negatives(0))
+            assert np.array_equal(nm.get_negatives(3, 1000, 9000), O.negatives(3, 1000, 9000))
+            nm.epoch(0)
+            err = grad_err(nm.get_gradient(), g_ref)
+            L = nm.loss(1)
+        note(f"  pooled {pool} {case} mode={mode}: grad err {err:.2e}  loss {L:.8f} vs {L_ref:.8f}")
+        assert err < GRAD_TOL
+        assert abs(L - L_ref) < LOSS_TOL * abs(L_ref)
+
+
+def test_pooled_sampler_is_bit_reproducible_and_needs_one_population():
+    d = dict(workload(3, 0.05).numpy())
+    d["pool_size"], d["pool_block"] = 2048, 4096
+    runs = []
+    for _ in range(2):
+        with make_nomad(d, SCATTER_DETERMINISTIC) as nm:
+            for t in range(4):
+                nm.epoch(t)
+            runs.append(nm.get_embedding())
+    assert np.array_equal(runs[0], runs[1])
+    g = small_random(6)
+    g["pool_size"], g["pool_block"] = 64, 256
+    with pytest.raises(NomadError) as ei:
+        make_nomad(g, SCATTER_DETERMINISTIC)
+    assert ei.value.code == -1
 
 
 # ------------------------------------------------------------------ degenerate and edge cases
