@@ -25,16 +25,21 @@ MEAN_FIELD_FLOPS = 14.0        # per (head, cell): 2 differences, 1 + d^2 (4), r
                                # p q^2 (1), two multiply-adds for the derivative factor (4)
 
 
-def algorithmic_bytes(kernel, n, E, s, R, grouped, weighted, deterministic):
+def algorithmic_bytes(kernel, n, E, s, R, grouped, weighted, deterministic, pool=None):
     """Bytes the method has to move per launch of each kernel, every gather / scatter counted at
-    its useful size (8 B per embedding row, 4 B per index), an accumulation counted once."""
+    its useful size (8 B per embedding row, 4 B per index), an accumulation counted once.
+    pool = (pool_size, pool_block) for the pooled sampler: the rows of the negatives are read and their
+    forces handed on once per pool entry and block instead of once per negative."""
     w = 4 if weighted else 0
     mf = 12 if grouped else 0                    # A_i, B_i
     if kernel == "edges":
-        per_edge = 4 + w + 8 + 8 * s             # col_idx, [p_e], theta_j, theta_m
-        per_edge += 8 * s                        # negatives' gradient contributions (handed on as records in binned mode)
+        per_edge = 4 + w + 8                     # col_idx, [p_e], theta_j
         per_edge += 4 if deterministic else 8    # a_e written / tail gradient accumulated
-        return per_edge * E + (4 + 8 + 8 + mf) * n   # row_ptr, theta_i, head gradient, [A,B]
+        if pool:
+            negatives = (8 + 8) * pool[0] * ((E + pool[1] - 1) // pool[1])
+        else:
+            negatives = (8 + 8) * s * E          # theta_m read, the negatives' gradient contributions
+        return per_edge * E + negatives + (4 + 8 + 8 + mf) * n   # row_ptr, theta_i, head gradient, [A,B]
     if kernel == "tiles":                        # accumulation of the binned forces: implementation traffic,
         return 8 * n                             # algorithmically only the per-point result
     if kernel == "scatter":                      # fallback: combine of the fixed-point sums
@@ -95,6 +100,8 @@ def main():
     ap.add_argument("--mode", choices=["det", "atomic"], default="det")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--groups", type=int, default=None, help="deal the clusters into this many groups")
+    ap.add_argument("--pool", default=None, metavar="P,G",
+                    help="opt-in pooled sampler: pool size and block length (e.g. 2048,4096); not the benchmark's sampler")
     ap.add_argument("--probe", choices=["copy"], default=None,
                     help="run only the streaming-copy probe (counter calibration / practical HBM ceiling)")
     args = ap.parse_args()
@@ -118,12 +125,16 @@ def main():
                               n_groups=args.groups)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
+    pool = None
+    if args.pool:
+        pool = tuple(int(x) for x in args.pool.split(","))
+        w.pool_size, w.pool_block = pool
     n, E, s, R = w.n, w.n_edges, w.n_neg, w.n_clusters
     steps, warmup = args.steps, args.warmup
     if warmup + steps > w.n_epochs:
         steps = max(1, w.n_epochs - warmup)
     mode = SCATTER_DETERMINISTIC if args.mode == "det" else SCATTER_ATOMIC
-    nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode)
+    nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode, pool_size=w.pool_size, pool_block=w.pool_block)
     t0 = time.time()
     nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None, w.cluster_of.to(dev),
                  None if w.cluster_group is None else w.cluster_group.to(dev))
@@ -149,7 +160,7 @@ def main():
     kernels = {}
     for name, (ms, cnt) in prof.items():
         if cnt:
-            ab = algorithmic_bytes(name, n, E, s, R, grouped, False, mode == SCATTER_DETERMINISTIC)
+            ab = algorithmic_bytes(name, n, E, s, R, grouped, False, mode == SCATTER_DETERMINISTIC, pool)
             kernels[name] = dict(ms=ms / cnt, launches=cnt, algorithmic_gb=ab / 1e9, gbs=ab / (ms / cnt) / 1e6)
     dom = max(kernels, key=lambda k: kernels[k]["ms"])
     if dom == "mean_field":
@@ -161,9 +172,9 @@ def main():
     else:
         roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s", traffic=None)
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    if args.scale == 1.0 and args.groups is None:
+    if args.scale == 1.0 and args.groups is None and pool is None:
         roofline["traffic"] = measured_traffic(dom, args.config, args.mode)
-    epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, False, mode == SCATTER_DETERMINISTIC) for k in kernels
+    epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, False, mode == SCATTER_DETERMINISTIC, pool) for k in kernels
                       if k != "mean_field")
     out = {
         "metric": "positive+negative edge updates/sec per epoch at 1 GPU",
@@ -173,7 +184,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: n={n}, E={E} directed edges, |R|={R} clusters, s={s} negatives/edge, "
                                f"|M|={w.noise_count:g}, {'grouped (mean-field)' if grouped else 'no approximated cells'}",
-                   "scatter_mode": args.mode},
+                   "scatter_mode": args.mode,
+                   "sampler": "iid per edge" if pool is None else f"pooled, {pool[0]} points per block of {pool[1]} edges (opt-in variant)"},
         "edges_per_sec": E / (elapsed / steps),
         "epoch_model_gb": epoch_bytes / 1e9,
         "epoch_hbm_frac_model": epoch_bytes / (elapsed / steps) / 1e9 / HBM_PEAK_GBS,

@@ -75,8 +75,9 @@ typedef struct {
  * Pooled sampler (opt-in variant; NOT the i.i.d. noise samples of Section 3.1/3.3).  The CSR positions
  * are cut into blocks of pool_block consecutive positions.  Block beta draws, per epoch t, a pool of
  * pool_size points, entry u = point picked by word (u & 3) of Philox(counter (beta, 0xFFFFFFFF, t, u >> 2),
- * key seed).  Slot k of edge e takes the pool entry picked by the same per-edge word that would pick a
- * point under the i.i.d. sampler.  Every negative is still uniform over the points, so the sampled loss
+ * key seed).  Slot k of edge e takes pool entry (x16 * pool_size) >> 16, x16 = 16-bit half (k & 1) of word
+ * ((k >> 1) & 3) of the per-edge Philox(counter (lo32 e, hi32 e, t, k >> 3)): one Philox call serves eight
+ * slots.  Every negative is still uniform over the points, so the sampled loss
  * stays an unbiased estimate of Eq. 2; negatives of one block are no longer independent.  The pool lives
  * in LDS, which replaces s random 128-byte line fetches and s scattered force records per edge by
  * pool_size of each per block.  Needs cluster_group = NULL (one sampling population).  The fast kernel

@@ -115,31 +115,38 @@ static inline int32_t group_of_point(const oracle_problem* P, int64_t i) {
  * head's population.
  * pooled sampler (opt-in variant, not the paper's i.i.d. noise samples; needs a single population): the
  * pool_block consecutive CSR positions of block beta = e / pool_block share a pool of pool_size points,
- * pool[u] = point picked by word (u & 3) of Philox(counter (beta, 0xFFFFFFFF, t, u >> 2)); the same
- * per-edge word as above picks the pool entry u instead of a point.  Every negative is still uniform
- * over the points; negatives of different edges of a block are no longer independent. */
+ * pool[u] = point picked by word (u & 3) of Philox(counter (beta, 0xFFFFFFFF, t, u >> 2)).  Slot k of
+ * edge e picks the pool entry u = (x16 * pool_size) >> 16, x16 = 16-bit half (k & 1) of word
+ * ((k >> 1) & 3) of Philox(counter (lo32 e, hi32 e, t, k >> 3)): eight slots per Philox call.  Every
+ * negative is still uniform over the points; negatives of different edges of a block are no longer
+ * independent. */
 static void edge_negatives(const oracle_problem* P, const oracle_tables* T, int64_t e, int64_t i, int32_t t, int32_t* m) {
     int32_t g = group_of_point(P, i);
     int64_t base = T->gstart[g];
     uint64_t nloc = (uint64_t)(T->gstart[g + 1] - base);
     uint32_t key[2] = {(uint32_t)P->seed, (uint32_t)(P->seed >> 32)};
+    if (P->pool_size > 0) {
+        uint64_t beta = (uint64_t)e / (uint64_t)P->pool_block;
+        for (int32_t k = 0; k < P->n_neg; ++k) {
+            uint32_t ctr[4] = {(uint32_t)(uint64_t)e, (uint32_t)((uint64_t)e >> 32), (uint32_t)t, (uint32_t)(k >> 3)};
+            uint32_t w[4], pw[4];
+            oracle_philox4x32_10(ctr, key, w);
+            uint32_t x16 = (w[(k >> 1) & 3] >> (16 * (k & 1))) & 0xFFFFu;
+            uint32_t u = (x16 * (uint32_t)P->pool_size) >> 16;
+            uint32_t pctr[4] = {(uint32_t)beta, 0xFFFFFFFFu, (uint32_t)t, u >> 2};
+            oracle_philox4x32_10(pctr, key, pw);
+            uint64_t pt = ((uint64_t)pw[u & 3] * nloc) >> 32;
+            m[k] = T->members[base + (int64_t)pt];
+        }
+        return;
+    }
     for (int32_t blk = 0; 4 * blk < P->n_neg; ++blk) {
         uint32_t ctr[4] = {(uint32_t)(uint64_t)e, (uint32_t)((uint64_t)e >> 32), (uint32_t)t, (uint32_t)blk};
         uint32_t w[4];
         oracle_philox4x32_10(ctr, key, w);
         for (int32_t lane = 0; lane < 4 && 4 * blk + lane < P->n_neg; ++lane) {
-            if (P->pool_size > 0) {
-                uint64_t u = ((uint64_t)w[lane] * (uint64_t)P->pool_size) >> 32;
-                uint64_t beta = (uint64_t)e / (uint64_t)P->pool_block;
-                uint32_t pctr[4] = {(uint32_t)beta, 0xFFFFFFFFu, (uint32_t)t, (uint32_t)(u >> 2)};
-                uint32_t pw[4];
-                oracle_philox4x32_10(pctr, key, pw);
-                uint64_t pt = ((uint64_t)pw[u & 3] * nloc) >> 32;
-                m[4 * blk + lane] = T->members[base + (int64_t)pt];
-            } else {
-                uint64_t u = ((uint64_t)w[lane] * nloc) >> 32;
-                m[4 * blk + lane] = T->members[base + (int64_t)u];
-            }
+            uint64_t u = ((uint64_t)w[lane] * nloc) >> 32;
+            m[4 * blk + lane] = T->members[base + (int64_t)u];
         }
     }
 }

@@ -29,7 +29,7 @@ Readings where the paper is silent (each one is listed in the design notes):
     hi32(seed)), word slot&3, index = high word of x * n_loc(i); no rejection;
   - opt-in pooled sampler (a variant, not the paper's i.i.d. noise samples): blocks of
     pool_block consecutive CSR positions share a pool of pool_size uniformly drawn points and
-    the per-edge word picks a pool entry (see negatives());
+    16 bits of the per-edge Philox words pick a pool entry per slot (see negatives());
   - the cells approximated for head i are those whose group differs from the group of
     i's own cluster; negatives are drawn from the points of i's own group (ascending
     index order) and weighted by omega_i = |M| * (n_loc(i)/n) / s;
@@ -227,21 +227,34 @@ def pool_of_block(P: Problem, beta: int, t: int) -> np.ndarray:
 def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None) -> np.ndarray:
     """Sampled negative indices m[e, slot] for the CSR edges e_begin..e_end-1 of epoch t.
 
-    i.i.d. sampler (the paper's |M| i.i.d. noise samples per edge, Section 3.1/3.3): the per-edge
-    Philox word picks a point of the head's population.  Pooled sampler (opt-in variant): the same
-    word picks an entry of the pool shared by the edge's block of pool_block CSR positions; each
-    negative is still uniform over the points, negatives of one block are no longer independent."""
+    i.i.d. sampler (the paper's |M| i.i.d. noise samples per edge, Section 3.1/3.3): word slot & 3 of
+    Philox(counter (lo32 e, hi32 e, t, slot >> 2)) picks a point of the head's population.
+    Pooled sampler (opt-in variant): slot k picks entry u = (x16 * pool_size) >> 16 of the pool shared
+    by the edge's block of pool_block CSR positions, x16 = 16-bit half k & 1 of word (k >> 1) & 3 of
+    Philox(counter (lo32 e, hi32 e, t, k >> 3)).  Each negative is still uniform over the points,
+    negatives of one block are no longer independent."""
     if e_end is None:
         e_end = P.n_edges
     s = P.n_neg
     out = np.zeros((e_end - e_begin, s), dtype=np.int64)
     if s == 0 or e_end == e_begin:
         return out
-    gop, members = local_sets(P)
-    head = np.searchsorted(P.row_ptr, np.arange(e_begin, e_end), side="right") - 1
     e = np.arange(e_begin, e_end, dtype=np.uint64)
     k0, k1 = P.seed & _MASK32, (P.seed >> 32) & _MASK32
-    pools = {}
+    if P.pool_size > 0:
+        pools = {}
+        for call in range((s + 7) // 8):
+            words = philox4x32_10_array(e & np.uint64(_MASK32), e >> np.uint64(32), np.uint64(t), np.uint64(call), k0, k1)
+            for k in range(8 * call, min(s, 8 * call + 8)):
+                x16 = (words[(k >> 1) & 3] >> np.uint64(16 * (k & 1))) & np.uint64(0xFFFF)
+                for idx in range(e_end - e_begin):
+                    beta = (e_begin + idx) // P.pool_block
+                    if beta not in pools:
+                        pools[beta] = pool_of_block(P, beta, t)
+                    out[idx, k] = pools[beta][(int(x16[idx]) * P.pool_size) >> 16]
+        return out
+    gop, members = local_sets(P)
+    head = np.searchsorted(P.row_ptr, np.arange(e_begin, e_end), side="right") - 1
     for blk in range((s + 3) // 4):
         words = philox4x32_10_array(e & np.uint64(_MASK32), e >> np.uint64(32), np.uint64(t), np.uint64(blk), k0, k1)
         for lane in range(4):
@@ -250,15 +263,9 @@ def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None)
                 break
             x = words[lane]
             for idx in range(e_end - e_begin):
-                if P.pool_size > 0:
-                    beta = (e_begin + idx) // P.pool_block
-                    if beta not in pools:
-                        pools[beta] = pool_of_block(P, beta, t)
-                    out[idx, slot] = pools[beta][(int(x[idx]) * P.pool_size) >> 32]
-                else:
-                    pop = members[int(gop[head[idx]])]
-                    u = (int(x[idx]) * len(pop)) >> 32
-                    out[idx, slot] = pop[u]
+                pop = members[int(gop[head[idx]])]
+                u = (int(x[idx]) * len(pop)) >> 32
+                out[idx, slot] = pop[u]
     return out
 
 

@@ -52,6 +52,7 @@ struct nomad_ctx {
     // binned deterministic scatter
     bool binned = false;
     int n_wg = 0, bin_block = 1024;
+    int pool_rounds = 0;            // > 0: the pooled edge pass runs, pool_block = 1024 * pool_rounds
     uint32_t n_bins = 0, max_chunks = 0;
     int tile_bits = kMaxTileBits;
     uint32_t *pool = nullptr, *chunk_prev = nullptr, *chain_head = nullptr, *chain_fill = nullptr, *wg_pool_begin = nullptr;
@@ -111,6 +112,7 @@ void free_graph(nomad_ctx* c) {
     dev_free(c->pool); dev_free(c->chunk_prev); dev_free(c->chain_head); dev_free(c->chain_fill); dev_free(c->wg_pool_begin);
     dev_free(c->head); dev_free(c->overflow);
     c->binned = false;
+    c->pool_rounds = 0;
     c->has_graph = c->has_theta = c->has_grad = false;
     c->E = 0;
 }
@@ -185,43 +187,58 @@ BinArgs bin_args(nomad_ctx* c) {
 
 constexpr size_t kMaxLdsBytes = 160 * 1024 - 256;   // per workgroup on gfx950, less the kernels' static LDS
 
-template <int S>
-int prepare_binned_kernel(nomad_ctx* c) {
-    const int lds = (int)binned_lds_bytes(c->n_bins, S, c->bin_block);
-    if (c->bin_block == 512)
-        HIP_TRY(c, hipFuncSetAttribute((const void*)k_edges_binned<S, 512>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    else
-        HIP_TRY(c, hipFuncSetAttribute((const void*)k_edges_binned<S, 1024>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    return NOMAD_OK;
+size_t edge_pass_lds_bytes(const nomad_ctx* c) {
+    return c->pool_rounds ? pooled_lds_bytes(c->n_bins, c->pool_rounds, (uint32_t)c->cfg.pool_size)
+                          : binned_lds_bytes(c->n_bins, c->cfg.n_neg, c->bin_block);
+}
+
+// Calls `fn(kernel)` with the edge-pass kernel that matches the context: number of negatives, sampler, launch shape.
+using EdgePassKernel = void (*)(const EdgeArgs, const BinArgs);
+
+template <int S, typename Fn>
+void with_edge_pass_kernel_s(const nomad_ctx* c, Fn fn) {
+    EdgePassKernel k = k_edges_binned<S, 1024>;
+    if (c->pool_rounds == 1) k = k_edges_pooled<S, 1>;
+    else if (c->pool_rounds == 2) k = k_edges_pooled<S, 2>;
+    else if (c->pool_rounds == 4) k = k_edges_pooled<S, 4>;
+    else if (c->pool_rounds == 8) k = k_edges_pooled<S, 8>;
+    else if (c->bin_block == 512) k = k_edges_binned<S, 512>;
+    fn(k);
+}
+
+template <typename Fn>
+bool with_edge_pass_kernel(const nomad_ctx* c, Fn fn) {
+    switch (c->cfg.n_neg) {
+        case 0: with_edge_pass_kernel_s<0>(c, fn); return true;
+        case 1: with_edge_pass_kernel_s<1>(c, fn); return true;
+        case 2: with_edge_pass_kernel_s<2>(c, fn); return true;
+        case 3: with_edge_pass_kernel_s<3>(c, fn); return true;
+        case 4: with_edge_pass_kernel_s<4>(c, fn); return true;
+        case 5: with_edge_pass_kernel_s<5>(c, fn); return true;
+        case 6: with_edge_pass_kernel_s<6>(c, fn); return true;
+        case 7: with_edge_pass_kernel_s<7>(c, fn); return true;
+        case 8: with_edge_pass_kernel_s<8>(c, fn); return true;
+    }
+    return false;
 }
 
 int prepare_binned(nomad_ctx* c) {
     HIP_TRY(c, hipFuncSetAttribute((const void*)k_tile_accumulate, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)(sizeof(unsigned long long) * 2 << c->tile_bits)));
-    switch (c->cfg.n_neg) {
-        case 0: return prepare_binned_kernel<0>(c);
-        case 1: return prepare_binned_kernel<1>(c); case 2: return prepare_binned_kernel<2>(c);
-        case 3: return prepare_binned_kernel<3>(c); case 4: return prepare_binned_kernel<4>(c);
-        case 5: return prepare_binned_kernel<5>(c); case 6: return prepare_binned_kernel<6>(c);
-        case 7: return prepare_binned_kernel<7>(c); case 8: return prepare_binned_kernel<8>(c);
-    }
-    return NOMAD_E_INVALID_ARG;
+    hipError_t err = hipErrorInvalidValue;
+    const int lds = (int)edge_pass_lds_bytes(c);
+    with_edge_pass_kernel(c, [&](EdgePassKernel kernel) {
+        err = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    });
+    HIP_TRY(c, err);
+    return NOMAD_OK;
 }
 
 void launch_edges_binned(nomad_ctx* c, const EdgeArgs& a) {
     const BinArgs q = bin_args(c);
-    const dim3 grid(c->n_wg), block(c->bin_block);
-    const size_t lds = binned_lds_bytes(c->n_bins, c->cfg.n_neg, c->bin_block);
-    switch (c->cfg.n_neg) {
-#define NOMAD_CASE(S)                                                                                          \
-    case S:                                                                                                    \
-        if (c->bin_block == 512) hipLaunchKernelGGL((k_edges_binned<S, 512>), grid, block, lds, c->stream, a, q); \
-        else hipLaunchKernelGGL((k_edges_binned<S, 1024>), grid, block, lds, c->stream, a, q);                   \
-        break;
-        NOMAD_CASE(0) NOMAD_CASE(1) NOMAD_CASE(2) NOMAD_CASE(3) NOMAD_CASE(4) NOMAD_CASE(5) NOMAD_CASE(6) NOMAD_CASE(7) NOMAD_CASE(8)
-#undef NOMAD_CASE
-        default: break;
-    }
+    const dim3 grid(c->n_wg), block(c->pool_rounds ? kPoolBlockLanes : c->bin_block);
+    const size_t lds = edge_pass_lds_bytes(c);
+    with_edge_pass_kernel(c, [&](EdgePassKernel kernel) { hipLaunchKernelGGL(kernel, grid, block, lds, c->stream, a, q); });
 }
 
 // cell means of the current embedding -> mu, cinfo
@@ -510,10 +527,20 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 2 * (binned_lds_bytes(n_bins, s, 512) + 256) <= 160 * 1024) { bin_block = 512; wg_per_cu = 2; }
         if (const char* knob = getenv("NOMAD_WG_PER_CU"))   // tuning knob: persistent workgroups per compute unit
             wg_per_cu = std::max(1, std::min(8, atoi(knob)));
+        // Pooled sampler: its own edge pass (pool in LDS) when the block is 1, 2, 4 or 8 rounds of 1024 positions.
+        int pool_rounds = 0;
+        if (c->cfg.pool_size > 0 && c->cfg.pool_block % kPoolBlockLanes == 0 && !getenv("NOMAD_NO_POOL_KERNEL")) {
+            const int r = c->cfg.pool_block / kPoolBlockLanes;
+            if ((r == 1 || r == 2 || r == 4 || r == 8) && n_bins <= (uint32_t)kMaxBinsPerThread * kPoolBlockLanes &&
+                pooled_lds_bytes(n_bins, r, (uint32_t)c->cfg.pool_size) <= kMaxLdsBytes)
+                pool_rounds = r;
+        }
+        if (pool_rounds) { bin_block = kPoolBlockLanes; wg_per_cu = 1; }
         if (s <= 8 && E > 0 && bin_block && !getenv("NOMAD_NO_BINNING")) {
             hipDeviceProp_t prop;
             HTRY(hipGetDeviceProperties(&prop, c->cfg.device));
             c->bin_block = bin_block;
+            c->pool_rounds = pool_rounds;
             c->n_wg = std::max(1, prop.multiProcessorCount) * wg_per_cu;
             c->n_bins = n_bins;
             c->tile_bits = tile_bits;
@@ -521,7 +548,11 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
             unsigned long long want = 0;
             bool ok = dev_alloc(c, &c->wg_pool_begin, (size_t)c->n_wg + 1) == NOMAD_OK && dev_alloc(c, &total_dev, 1) == NOMAD_OK;
             if (ok) {
-                hipLaunchKernelGGL(k_wg_pools, dim3(1), dim3(64), 0, st, E, c->n_wg, s + 1, c->bin_block, n_bins, c->wg_pool_begin, total_dev);
+                if (c->pool_rounds)
+                    hipLaunchKernelGGL(k_wg_pools_pooled, dim3(1), dim3(64), 0, st, E, c->n_wg, (int64_t)c->cfg.pool_block,
+                                       (uint32_t)c->cfg.pool_size, n_bins, c->wg_pool_begin, total_dev);
+                else
+                    hipLaunchKernelGGL(k_wg_pools, dim3(1), dim3(64), 0, st, E, c->n_wg, s + 1, c->bin_block, n_bins, c->wg_pool_begin, total_dev);
                 ok = hipMemcpyAsync(&want, total_dev, sizeof(want), hipMemcpyDeviceToHost, st) == hipSuccess &&
                      hipStreamSynchronize(st) == hipSuccess;
             }

@@ -378,27 +378,48 @@ __device__ __forceinline__ void edge_math(const HeadCtx& h, float pe, float2 tj,
     o.hy = fy - c * h.MBy;
 }
 
-// Point picked by one 32-bit word x of the per-edge stream.  i.i.d. sampler: a point of the head's
-// population.  Pooled sampler: entry u = hi32(x * pool_size) of the pool of the edge's block, itself the
-// point picked by word u & 3 of Philox(counter (block, 0xFFFFFFFF, epoch, u >> 2)).
-__device__ __forceinline__ int32_t pick_negative(const EdgeArgs& P, const Population& pop, int32_t e, uint32_t x) {
-    if (P.pool_size == 0) return draw_index(x, pop);
-    const uint32_t u = __umulhi(x, P.pool_size);
+// Pooled sampler: pool entry of slot k given the four words of the per-edge Philox call k >> 3
+// (16-bit half k & 1 of word (k >> 1) & 3, scaled to the pool size), and the point behind a pool entry
+// (word u & 3 of Philox(counter (block, 0xFFFFFFFF, epoch, u >> 2)) mapped onto the population).
+__device__ __forceinline__ uint32_t pool_slot(const uint32_t (&w)[4], int k, uint32_t pool_size) {
+    const uint32_t x16 = (w[(k >> 1) & 3] >> (16 * (k & 1))) & 0xFFFFu;
+    return (x16 * pool_size) >> 16;
+}
+
+__device__ __forceinline__ int32_t pool_point(const EdgeArgs& P, const Population& pop, uint32_t block, uint32_t u) {
     uint32_t w[4];
-    philox4x32_10((uint32_t)e / P.pool_block, 0xFFFFFFFFu, P.epoch, u >> 2, P.key0, P.key1, w);
+    philox4x32_10(block, 0xFFFFFFFFu, P.epoch, u >> 2, P.key0, P.key1, w);
     return draw_index(w[u & 3u], pop);
+}
+
+// Negative of slot k of CSR position e in epoch P.epoch (general form, any s).
+__device__ __forceinline__ int32_t negative_of_slot(const EdgeArgs& P, const Population& pop, int32_t e, int k) {
+    uint32_t w[4];
+    if (P.pool_size == 0) {
+        philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)(k >> 2), P.key0, P.key1, w);
+        return draw_index(w[k & 3], pop);
+    }
+    philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)(k >> 3), P.key0, P.key1, w);
+    return pool_point(P, pop, (uint32_t)e / P.pool_block, pool_slot(w, k, P.pool_size));
 }
 
 // The s negatives of CSR position e in epoch P.epoch.
 template <int S>
 __device__ __forceinline__ void draw_negatives(const EdgeArgs& P, const Population& pop, int32_t e, int32_t (&m)[S > 0 ? S : 1]) {
+    if (P.pool_size == 0) {
 #pragma unroll
-    for (int b = 0; b < (S + 3) / 4; ++b) {
+        for (int b = 0; b < (S + 3) / 4; ++b) {
+            uint32_t w[4];
+            philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
+#pragma unroll
+            for (int l = 0; l < 4; ++l)
+                if (4 * b + l < S) m[4 * b + l] = draw_index(w[l], pop);
+        }
+    } else {
         uint32_t w[4];
-        philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
+        philox4x32_10((uint32_t)e, 0u, P.epoch, 0u, P.key0, P.key1, w);   // S <= 8 here: one call
 #pragma unroll
-        for (int l = 0; l < 4; ++l)
-            if (4 * b + l < S) m[4 * b + l] = pick_negative(P, pop, e, w[l]);
+        for (int k = 0; k < S; ++k) m[k] = pool_point(P, pop, (uint32_t)e / P.pool_block, pool_slot(w, k, P.pool_size));
     }
 }
 
@@ -435,13 +456,9 @@ __device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const Head
     dy = h.ti.y - tj.y;
     const float qij = cauchy(dx, dy);
     float qsum = 0.f;
-    for (int b = 0; 4 * b < s; ++b) {
-        uint32_t w[4];
-        philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
-        for (int l = 0; l < 4 && 4 * b + l < s; ++l) {
-            const float2 tm = P.theta[pick_negative(P, h.pop, e, w[l])];
-            qsum += cauchy(h.ti.x - tm.x, h.ti.y - tm.y);
-        }
+    for (int k = 0; k < s; ++k) {
+        const float2 tm = P.theta[negative_of_slot(P, h.pop, e, k)];
+        qsum += cauchy(h.ti.x - tm.x, h.ti.y - tm.y);
     }
     const float Se = qij + h.MA + h.omega * qsum;
     if (LOSS) { log_term = pe * logf(Se / qij); return; }
@@ -449,19 +466,15 @@ __device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const Head
     a = 2.0f * pe * qij * (1.0f - qij * inv_S);
     float fx = a * dx, fy = a * dy;
     const float bscale = 2.0f * pe * h.omega * inv_S;
-    for (int b = 0; 4 * b < s; ++b) {
-        uint32_t w[4];
-        philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
-        for (int l = 0; l < 4 && 4 * b + l < s; ++l) {
-            const int32_t mk = pick_negative(P, h.pop, e, w[l]);
-            const float2 tm = P.theta[mk];
-            const float gx = h.ti.x - tm.x, gy = h.ti.y - tm.y;
-            const float q = cauchy(gx, gy);
-            const float bb = bscale * q * q;
-            fx -= bb * gx;
-            fy -= bb * gy;
-            emit(mk, bb * gx, bb * gy);
-        }
+    for (int k = 0; k < s; ++k) {
+        const int32_t mk = negative_of_slot(P, h.pop, e, k);
+        const float2 tm = P.theta[mk];
+        const float gx = h.ti.x - tm.x, gy = h.ti.y - tm.y;
+        const float q = cauchy(gx, gy);
+        const float bb = bscale * q * q;
+        fx -= bb * gx;
+        fy -= bb * gy;
+        emit(mk, bb * gx, bb * gy);
     }
     const float c = 2.0f * pe * inv_S;
     hx = fx - c * h.MBx;
@@ -610,9 +623,180 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// LDS tables of one edge-pass workgroup (see k_edges_binned): per tile the record count of the round
+// (after the scan: first sorted slot), the fill of the open chunk, the open chunk and the first chunk
+// allocated this round; then the round's records sorted by tile.
+struct BinLds {
+    uint32_t* start;    // [B+1]
+    uint32_t* fill;     // [B] records in the open chunk (kChunk: none open / full)
+    uint32_t* chunk;    // [B] open chunk of this (workgroup, tile)
+    uint32_t* base;     // [B] first chunk allocated this round
+    uint32_t* rec_pt;   // [nrec] destination point
+    uint32_t* rec_x;    // [nrec] force x (float bits)
+    uint32_t* rec_y;    // [nrec]
+    uint32_t B;
+    int tile_bits;
+};
+
+__device__ __forceinline__ BinLds carve_bin_lds(uint32_t* mem, uint32_t B, uint32_t nrec, int tile_bits) {
+    BinLds L;
+    L.start = mem; L.fill = L.start + B + 1; L.chunk = L.fill + B; L.base = L.chunk + B;
+    L.rec_pt = L.base + B; L.rec_x = L.rec_pt + nrec; L.rec_y = L.rec_x + nrec;
+    L.B = B; L.tile_bits = tile_bits;
+    return L;
+}
+
+template <int BS>
+__device__ __forceinline__ void init_bin_lds(const BinLds& L) {
+    for (uint32_t b = threadIdx.x; b < L.B; b += BS) { L.start[b] = 0; L.fill[b] = kChunk; L.chunk[b] = kNoChunk; L.base[b] = 0; }
+    if (threadIdx.x == 0) L.start[L.B] = 0;
+}
+
+// rank of a new record among this round's records of its tile
+__device__ __forceinline__ uint32_t take_rank(const BinLds& L, uint32_t pt) { return atomicAdd(&L.start[pt >> L.tile_bits], 1u); }
+
+// One round of the binned scatter for a workgroup of BS lanes.  Every lane brings up to NR records
+// (valid[k], destination pt[k], force (fx[k], fy[k]), rank[k] from take_rank).  The records are
+// counting-sorted by tile in LDS and appended to the (workgroup, tile) chains with consecutive lanes
+// on consecutive records.  FLUSH_ITERS * BS bounds the records of one round.  All lanes must call.
+template <int NR, int BS, int FLUSH_ITERS>
+__device__ __forceinline__ void sort_and_flush(const BinLds& L, const BinArgs& Q, uint32_t pool_end, uint32_t* pool_cursor,
+                                               uint32_t* wave_total, const bool (&valid)[NR], const uint32_t (&pt)[NR],
+                                               const uint32_t (&rank)[NR], const float (&fx)[NR], const float (&fy)[NR]) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t B = L.B;
+    const int tb = L.tile_bits;
+    const uint32_t per = (B + BS - 1) / BS;   // tiles owned by one thread, contiguous
+    const uint32_t b0 = min(B, (uint32_t)tid * per), b1 = min(B, b0 + per);
+    lds_barrier();
+    // ---- exclusive scan of the per-tile counts
+    uint32_t cnt_own[kMaxBinsPerThread];
+    uint32_t own_sum = 0;
+#pragma unroll
+    for (int x = 0; x < kMaxBinsPerThread; ++x) {
+        cnt_own[x] = (b0 + x < b1) ? L.start[b0 + x] : 0u;
+        own_sum += cnt_own[x];
+    }
+    uint32_t incl = own_sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t u = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += u;
+    }
+    if (lane == 63) wave_total[wave] = incl;
+    lds_barrier();
+    uint32_t run = incl - own_sum;
+    for (int v = 0; v < wave; ++v) run += wave_total[v];
+    if (tid == BS - 1) L.start[B] = run + own_sum;
+    // tiles whose open chunk cannot take this round's records get new chunks, linked to the chain
+#pragma unroll
+    for (int x = 0; x < kMaxBinsPerThread; ++x) {
+        const uint32_t b = b0 + x;
+        if (b < b1) {
+            const uint32_t c = cnt_own[x];
+            L.start[b] = run;
+            run += c;
+            const uint32_t fl = L.fill[b];
+            if (c != 0 && fl + c > (uint32_t)kChunk) {
+                const uint32_t k = (fl + c - 1) / kChunk;
+                const uint32_t nb = atomicAdd(pool_cursor, k);
+                L.base[b] = nb;
+                if (nb + k > pool_end) *Q.overflow = 1;
+                uint32_t prev = L.chunk[b];
+                for (uint32_t y = 0; y < k && nb + y < pool_end; ++y) { Q.chunk_prev[nb + y] = prev; prev = nb + y; }
+            }
+        }
+    }
+    lds_barrier();
+    // ---- records to their sorted slots
+    {
+        uint32_t p[NR];
+#pragma unroll
+        for (int k = 0; k < NR; ++k) p[k] = valid[k] ? L.start[pt[k] >> tb] + rank[k] : 0u;
+#pragma unroll
+        for (int k = 0; k < NR; ++k)
+            if (valid[k]) { L.rec_pt[p[k]] = pt[k]; L.rec_x[p[k]] = __float_as_uint(fx[k]); L.rec_y[p[k]] = __float_as_uint(fy[k]); }
+    }
+    lds_barrier();
+    // ---- consecutive lanes write consecutive sorted records to the chains
+    const uint32_t total = L.start[B];
+#pragma unroll
+    for (int it = 0; it < FLUSH_ITERS; ++it) {
+        const uint32_t p = (uint32_t)tid + (uint32_t)it * BS;
+        if (p < total) {
+            const uint32_t dpt = L.rec_pt[p];
+            const uint32_t b = dpt >> tb;
+            const uint32_t pos = L.fill[b] + (p - L.start[b]);
+            uint32_t ch, off;
+            if (pos < (uint32_t)kChunk) { ch = L.chunk[b]; off = pos; }
+            else { ch = L.base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
+            if (ch < pool_end) {   // kNoChunk is above any valid id
+                uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
+                dst[0] = dpt & ((1u << tb) - 1u);
+                dst[1] = L.rec_x[p];
+                dst[2] = L.rec_y[p];
+            }
+        }
+    }
+    lds_barrier();
+    // ---- chain state after this round; counts back to zero
+#pragma unroll
+    for (int x = 0; x < kMaxBinsPerThread; ++x) {
+        const uint32_t b = b0 + x;
+        if (b < b1) {
+            const uint32_t c = cnt_own[x];
+            if (c != 0) {
+                const uint32_t fl = L.fill[b];
+                if (fl + c > (uint32_t)kChunk) {
+                    const uint32_t k = (fl + c - 1) / kChunk;
+                    L.chunk[b] = L.base[b] + k - 1;
+                    L.fill[b] = fl + c - k * kChunk;
+                } else {
+                    L.fill[b] = fl + c;
+                }
+            }
+            L.start[b] = 0;
+        }
+    }
+    lds_barrier();
+}
+
+// the last chunk of every chain and how full it is (end of the edge pass)
+template <int BS>
+__device__ __forceinline__ void publish_chains(const BinLds& L, const BinArgs& Q, uint32_t pool_end) {
+    const uint32_t W = gridDim.x, w = blockIdx.x;
+    for (uint32_t b = threadIdx.x; b < L.B; b += BS) {
+        const uint32_t ch = L.chunk[b];
+        Q.chain_head[(size_t)b * W + w] = ch < pool_end ? ch : kNoChunk;
+        Q.chain_fill[(size_t)b * W + w] = L.fill[b];
+    }
+}
+
+// Head sum of each row: segmented inclusive scan over the lanes of the row, in lane order.  The last
+// lane of a row then holds the row's sum; it is stored directly when the whole row lies inside this
+// wavefront (positions wave_e0 .. wave_e0+63, below e_end), else it has to be handed on as a record
+// (returns true on that lane).  i = head of the lane's edge, -1 on lanes without an edge.
+__device__ __forceinline__ bool reduce_head_sums(const BinArgs& Q, bool has, int32_t i, int32_t ea, int32_t eb, int64_t e64,
+                                                 int64_t e_end, float& hx, float& hy) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float ux = __shfl_up(hx, d, 64), uy = __shfl_up(hy, d, 64);
+        const int32_t ui = __shfl_up(i, d, 64);
+        if (lane >= d && ui == i) { hx += ux; hy += uy; }
+    }
+    const int32_t i_after = __shfl_down(i, 1, 64);
+    const bool row_end = has && (lane == 63 || i_after != i);
+    const int64_t wave_e0 = e64 - lane;
+    const bool inside = (int64_t)ea >= wave_e0 && (int64_t)eb <= min(wave_e0 + 64, e_end);
+    if (row_end && inside) Q.ghead[i] = make_float2(hx, hy);
+    return row_end && !inside;
+}
+
 // What one lane has in flight for its edge of the next round: issued a round ahead, so that the
-// random gathers of round r+1 are served while round r is being sorted and written out.
-template <int S>
+// gathers of round r+1 are served while round r is being sorted and written out.  GATHER: also the
+// rows of the negatives (i.i.d. sampler); the pooled sampler reads them from its pool in LDS.
+template <int S, bool GATHER>
 struct EdgeFetch {
     bool has;
     int32_t e, i, j, ea, eb;
@@ -622,8 +806,8 @@ struct EdgeFetch {
     float2 tj, tm[S > 0 ? S : 1];
 };
 
-template <int S>
-__device__ __forceinline__ void issue_edge(const EdgeArgs& P, bool has, int32_t e, int32_t i, int32_t j, EdgeFetch<S>& f) {
+template <int S, bool GATHER>
+__device__ __forceinline__ void issue_edge(const EdgeArgs& P, bool has, int32_t e, int32_t i, int32_t j, EdgeFetch<S, GATHER>& f) {
     f.has = has;
     f.e = e; f.i = has ? i : -1; f.j = j; f.ea = 0; f.eb = 0; f.pe = 0.f;
     if (!has) return;
@@ -632,9 +816,11 @@ __device__ __forceinline__ void issue_edge(const EdgeArgs& P, bool has, int32_t 
     f.h = load_head(P, i, f.ea, f.eb);
     f.tj = P.theta[j];
     f.pe = P.pe ? P.pe[e] : f.h.inv_deg;
-    draw_negatives<S>(P, f.h.pop, e, f.m);
+    if (GATHER) {
+        draw_negatives<S>(P, f.h.pop, e, f.m);
 #pragma unroll
-    for (int k = 0; k < S; ++k) f.tm[k] = P.theta[f.m[k]];
+        for (int k = 0; k < S; ++k) f.tm[k] = P.theta[f.m[k]];
+    }
 }
 
 template <int S, int BS>
@@ -642,50 +828,41 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
     constexpr int SS = S > 0 ? S : 1;
     constexpr int kWaves = BS / 64;
     constexpr int NREC = BS * (S + 1) + 2 * kWaves;
-    constexpr int kFlushIters = (NREC + BS - 1) / BS;
+    constexpr int NR = S + 2;   // per lane: the tail, the negatives, and possibly a partial head sum
     extern __shared__ uint32_t lds_bins[];
-    const uint32_t B = Q.n_bins;
-    uint32_t* start = lds_bins;             // [B+1] A: records this round per tile; after the scan: first sorted slot
-    uint32_t* fill = start + B + 1;         // [B] records in the open chunk (kChunk: none open / full)
-    uint32_t* chunk = fill + B;             // [B] open chunk of this (workgroup, tile)
-    uint32_t* base = chunk + B;             // [B] first chunk allocated this round
-    uint32_t* rec_pt = base + B;            // [NREC] destination point
-    uint32_t* rec_x = rec_pt + NREC;        // [NREC] force x (float bits)
-    uint32_t* rec_y = rec_x + NREC;         // [NREC]
+    const BinLds L = carve_bin_lds(lds_bins, Q.n_bins, NREC, Q.tile_bits);
     __shared__ uint32_t wave_total[kWaves];
     __shared__ uint32_t pool_cursor;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tb = Q.tile_bits;
+    const int tid = threadIdx.x;
     const uint32_t W = gridDim.x, w = blockIdx.x;
     const int64_t e_begin = Q.E * (int64_t)w / W, e_end = Q.E * (int64_t)(w + 1) / W;
     const uint32_t pool_end = min(Q.wg_pool_begin[w + 1], Q.max_chunks);
-    const uint32_t per = (B + BS - 1) / BS;   // tiles owned by one thread, contiguous
-    const uint32_t b0 = min(B, (uint32_t)tid * per), b1 = min(B, b0 + per);
-    for (uint32_t b = tid; b < B; b += BS) { start[b] = 0; fill[b] = kChunk; chunk[b] = kNoChunk; base[b] = 0; }
-    if (tid == 0) { start[B] = 0; pool_cursor = Q.wg_pool_begin[w]; }
+    init_bin_lds<BS>(L);
+    if (tid == 0) pool_cursor = Q.wg_pool_begin[w];
     lds_barrier();
 
     const int64_t n_rounds = (e_end - e_begin + BS - 1) / BS;
     // Software pipeline over rounds: (head, tail) indices are read two rounds ahead, the embedding rows
     // one round ahead.
-    EdgeFetch<S> f;
+    EdgeFetch<S, true> f;
     int32_t i_next = 0, j_next = 0;
     {
         const int64_t e0 = e_begin + tid, e1 = e0 + BS;
         int32_t i0 = 0, j0 = 0;
         if (e0 < e_end) { i0 = Q.head[e0]; j0 = P.col[e0]; }
         if (e1 < e_end) { i_next = Q.head[e1]; j_next = P.col[e1]; }
-        issue_edge<S>(P, e0 < e_end, (int32_t)e0, i0, j0, f);
+        issue_edge<S, true>(P, e0 < e_end, (int32_t)e0, i0, j0, f);
     }
     for (int64_t round = 0; round < n_rounds; ++round) {
-        // ---- A: one edge per lane; records: slot 0 the tail (force -a d_ij), slots 1..S the negatives
+        // one edge per lane; records: slot 0 the tail (force -a d_ij), slots 1..S the negatives
         const int64_t e64 = e_begin + round * BS + tid;
         const bool has = f.has;
         const int32_t i = f.i, ea = f.ea, eb = f.eb;
-        uint32_t dst_pt[S + 1], rank[S + 1];
-        float fx[S + 1], fy[S + 1];
+        bool valid[NR];
+        uint32_t dst_pt[NR], rank[NR];
+        float fx[NR], fy[NR];
 #pragma unroll
-        for (int k = 0; k <= S; ++k) { dst_pt[k] = 0u; rank[k] = 0u; fx[k] = 0.f; fy[k] = 0.f; }
+        for (int k = 0; k < NR; ++k) { valid[k] = k <= S && has; dst_pt[k] = 0u; rank[k] = 0u; fx[k] = 0.f; fy[k] = 0.f; }
         float hx = 0.f, hy = 0.f;
         if (has) {
             EdgeOut<SS> o;
@@ -701,131 +878,164 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
             const int64_t e1 = e64 + BS, e2 = e1 + BS;
             const int32_t i1 = i_next, j1 = j_next;
             if (e2 < e_end) { i_next = Q.head[e2]; j_next = P.col[e2]; }
-            issue_edge<S>(P, e1 < e_end, (int32_t)e1, i1, j1, f);
+            issue_edge<S, true>(P, e1 < e_end, (int32_t)e1, i1, j1, f);
         }
-        // head sum of each row: segmented inclusive scan over the lanes of the row, in lane order
+        valid[S + 1] = reduce_head_sums(Q, has, i, ea, eb, e64, e_end, hx, hy);
+        dst_pt[S + 1] = valid[S + 1] ? (uint32_t)i : 0u;
+        fx[S + 1] = hx;
+        fy[S + 1] = hy;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const float ux = __shfl_up(hx, d, 64), uy = __shfl_up(hy, d, 64);
-            const int32_t ui = __shfl_up(i, d, 64);
-            if (lane >= d && ui == i) { hx += ux; hy += uy; }
-        }
-        // the last lane of a row holds the row's sum: stored directly when the whole row lies inside this
-        // wavefront, else handed on as one more record (hx, hy for point i)
-        const int32_t i_after = __shfl_down(i, 1, 64);
-        const bool row_end = has && (lane == 63 || i_after != i);
-        const int64_t wave_e0 = e64 - lane;
-        const bool inside = (int64_t)ea >= wave_e0 && (int64_t)eb <= min(wave_e0 + 64, e_end);
-        const bool head_rec = row_end && !inside;
-        const uint32_t head_bin = head_rec ? (uint32_t)i >> tb : 0u;
-        uint32_t head_rank = 0u;
-        if (row_end && inside) Q.ghead[i] = make_float2(hx, hy);
-        if (has) {
-#pragma unroll
-            for (int k = 0; k <= S; ++k) rank[k] = atomicAdd(&start[dst_pt[k] >> tb], 1u);
-        }
-        if (head_rec) head_rank = atomicAdd(&start[head_bin], 1u);
-        lds_barrier();
-        // ---- B: exclusive scan of the per-tile counts (each thread owns `per` adjacent tiles)
-        uint32_t cnt_own[kMaxBinsPerThread];
-        uint32_t own_sum = 0;
-#pragma unroll
-        for (int x = 0; x < kMaxBinsPerThread; ++x) {
-            cnt_own[x] = (b0 + x < b1) ? start[b0 + x] : 0u;
-            own_sum += cnt_own[x];
-        }
-        uint32_t incl = own_sum;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t u = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += u;
-        }
-        if (lane == 63) wave_total[wave] = incl;
-        lds_barrier();
-        uint32_t run = incl - own_sum;
-        for (int v = 0; v < wave; ++v) run += wave_total[v];
-        if (tid == BS - 1) start[B] = run + own_sum;
-        // tiles whose open chunk cannot take this round's records get new chunks, linked to the chain
-#pragma unroll
-        for (int x = 0; x < kMaxBinsPerThread; ++x) {
-            const uint32_t b = b0 + x;
-            if (b < b1) {
-                const uint32_t c = cnt_own[x];
-                start[b] = run;
-                run += c;
-                const uint32_t fl = fill[b];
-                if (c != 0 && fl + c > (uint32_t)kChunk) {
-                    const uint32_t k = (fl + c - 1) / kChunk;
-                    const uint32_t nb = atomicAdd(&pool_cursor, k);
-                    base[b] = nb;
-                    if (nb + k > pool_end) *Q.overflow = 1;
-                    uint32_t prev = chunk[b];
-                    for (uint32_t y = 0; y < k && nb + y < pool_end; ++y) { Q.chunk_prev[nb + y] = prev; prev = nb + y; }
-                }
-            }
-        }
-        lds_barrier();
-        // ---- C: records to their sorted slots
-        if (has) {
-            uint32_t p[S + 1];
-#pragma unroll
-            for (int k = 0; k <= S; ++k) p[k] = start[dst_pt[k] >> tb] + rank[k];
-#pragma unroll
-            for (int k = 0; k <= S; ++k) { rec_pt[p[k]] = dst_pt[k]; rec_x[p[k]] = __float_as_uint(fx[k]); rec_y[p[k]] = __float_as_uint(fy[k]); }
-        }
-        if (head_rec) {
-            const uint32_t p = start[head_bin] + head_rank;
-            rec_pt[p] = (uint32_t)i; rec_x[p] = __float_as_uint(hx); rec_y[p] = __float_as_uint(hy);
-        }
-        lds_barrier();
-        // ---- D: consecutive lanes write consecutive sorted records to the chains
-        const uint32_t total = start[B];
-#pragma unroll
-        for (int it = 0; it < kFlushIters; ++it) {
-            const uint32_t p = (uint32_t)tid + (uint32_t)it * BS;
-            if (p < total) {
-                const uint32_t pt = rec_pt[p];
-                const uint32_t b = pt >> tb;
-                const uint32_t pos = fill[b] + (p - start[b]);
-                uint32_t ch, off;
-                if (pos < (uint32_t)kChunk) { ch = chunk[b]; off = pos; }
-                else { ch = base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
-                if (ch < pool_end) {   // kNoChunk is above any valid id
-                    uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
-                    dst[0] = pt & ((1u << tb) - 1u);
-                    dst[1] = rec_x[p];
-                    dst[2] = rec_y[p];
-                }
-            }
-        }
-        lds_barrier();
-        // ---- E: chain state after this round; counts back to zero
-#pragma unroll
-        for (int x = 0; x < kMaxBinsPerThread; ++x) {
-            const uint32_t b = b0 + x;
-            if (b < b1) {
-                const uint32_t c = cnt_own[x];
-                if (c != 0) {
-                    const uint32_t fl = fill[b];
-                    if (fl + c > (uint32_t)kChunk) {
-                        const uint32_t k = (fl + c - 1) / kChunk;
-                        chunk[b] = base[b] + k - 1;
-                        fill[b] = fl + c - k * kChunk;
-                    } else {
-                        fill[b] = fl + c;
-                    }
-                }
-                start[b] = 0;
-            }
-        }
-        lds_barrier();
+        for (int k = 0; k < NR; ++k)
+            if (valid[k]) rank[k] = take_rank(L, dst_pt[k]);
+        sort_and_flush<NR, BS, (NREC + BS - 1) / BS>(L, Q, pool_end, &pool_cursor, wave_total, valid, dst_pt, rank, fx, fy);
     }
-    // the last chunk of every chain and how full it is
-    for (uint32_t b = tid; b < B; b += BS) {
-        const uint32_t ch = chunk[b];
-        Q.chain_head[(size_t)b * W + w] = ch < pool_end ? ch : kNoChunk;
-        Q.chain_fill[(size_t)b * W + w] = fill[b];
+    publish_chains<BS>(L, Q, pool_end);
+}
+
+// ------------------------------------------------------------------ K3 + K4 with the pooled sampler
+// Same scatter machinery, but the negatives of a block of ROUNDS * 1024 consecutive CSR positions come
+// from the block's pool of P.pool_size points, which lives in LDS: pool_th (their embedding rows, one
+// gather per pool entry and block instead of one per negative) and pool_acc (64-bit fixed-point sums
+// of the forces they receive, handed on as one record per pool entry and block).  The rounds of a
+// block run without barriers; the records of the whole block (tails, partial head sums, pool entries)
+// are sorted and written once per block.
+constexpr int kPoolBlockLanes = 1024;
+constexpr int kMaxPoolPerLane = 4;   // NOMAD_MAX_POOL / kPoolBlockLanes
+
+__host__ __device__ inline size_t pooled_records_per_block(int rounds, uint32_t pool_size) {
+    return (size_t)kPoolBlockLanes * rounds + 2 * (kPoolBlockLanes / 64) * rounds + pool_size;
+}
+__host__ __device__ inline size_t pooled_lds_bytes(uint32_t n_bins, int rounds, uint32_t pool_size) {
+    return (size_t)pool_size * 28 + ((size_t)4 * n_bins + 2 + 3 * pooled_records_per_block(rounds, pool_size)) * sizeof(uint32_t);
+}
+
+template <int S, int ROUNDS>
+__global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs P, const BinArgs Q) {
+    constexpr int BS = kPoolBlockLanes;
+    constexpr int SS = S > 0 ? S : 1;
+    constexpr int kWaves = BS / 64;
+    constexpr int NP = kMaxPoolPerLane;
+    constexpr int NR = 2 * ROUNDS + NP;   // per lane and block: ROUNDS tails, ROUNDS possible partial head sums, NP pool entries
+    constexpr int FLUSH_ITERS = ROUNDS + 1 + NP;
+    extern __shared__ unsigned long long lds_pool[];
+    const uint32_t PS = P.pool_size;
+    unsigned long long* pool_acc = lds_pool;                         // [2 PS] fixed-point force sums
+    float2* pool_th = (float2*)(pool_acc + 2 * (size_t)PS);          // [PS] embedding rows of the pool
+    uint32_t* pool_pt = (uint32_t*)(pool_th + PS);                   // [PS] the points
+    const uint32_t nrec = (uint32_t)pooled_records_per_block(ROUNDS, PS);
+    const BinLds L = carve_bin_lds(pool_pt + PS, Q.n_bins, nrec, Q.tile_bits);
+    __shared__ uint32_t wave_total[kWaves];
+    __shared__ uint32_t pool_cursor;
+    const int tid = threadIdx.x;
+    const uint32_t W = gridDim.x, w = blockIdx.x;
+    constexpr int64_t G = (int64_t)BS * ROUNDS;                       // = P.pool_block
+    const int64_t n_blocks = (Q.E + G - 1) / G;
+    const int64_t blk_begin = n_blocks * (int64_t)w / W, blk_end = n_blocks * (int64_t)(w + 1) / W;
+    const int64_t e_begin = blk_begin * G, e_end = min(blk_end * G, Q.E);
+    const uint32_t pool_end = min(Q.wg_pool_begin[w + 1], Q.max_chunks);
+    init_bin_lds<BS>(L);
+    if (tid == 0) pool_cursor = Q.wg_pool_begin[w];
+
+    // pool of the first block (later blocks: fetched one block ahead).  One Philox call yields four
+    // consecutive entries, so lane t fetches entries 4t .. 4t+3 (lanes beyond pool_size / 4 idle).
+    uint32_t next_pt[NP];
+    float2 next_th[NP];
+    auto fetch_pool = [&](int64_t blk) {
+#pragma unroll
+        for (int k = 0; k < NP; ++k) { next_pt[k] = 0u; next_th[k] = make_float2(0.f, 0.f); }
+        const uint32_t u0 = 4u * (uint32_t)tid;
+        if (u0 < PS && blk < blk_end) {
+            uint32_t wd[4];
+            philox4x32_10((uint32_t)blk, 0xFFFFFFFFu, P.epoch, (uint32_t)tid, P.key0, P.key1, wd);
+#pragma unroll
+            for (int k = 0; k < NP; ++k)
+                if (u0 + k < PS) { next_pt[k] = __umulhi(wd[k], (uint32_t)P.n); next_th[k] = P.theta[next_pt[k]]; }
+        }
+    };
+    fetch_pool(blk_begin);
+    EdgeFetch<S, false> f;
+    int32_t i_next = 0, j_next = 0;
+    {
+        const int64_t e0 = e_begin + tid, e1 = e0 + BS;
+        int32_t i0 = 0, j0 = 0;
+        if (e0 < e_end) { i0 = Q.head[e0]; j0 = P.col[e0]; }
+        if (e1 < e_end) { i_next = Q.head[e1]; j_next = P.col[e1]; }
+        issue_edge<S, false>(P, e0 < e_end, (int32_t)e0, i0, j0, f);
     }
+    for (int64_t blk = blk_begin; blk < blk_end; ++blk) {
+        // ---- this block's pool into LDS, the next block's pool into flight
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            const uint32_t u = 4u * (uint32_t)tid + (uint32_t)k;
+            if (u < PS) { pool_pt[u] = next_pt[k]; pool_th[u] = next_th[k]; pool_acc[2 * u] = 0ull; pool_acc[2 * u + 1] = 0ull; }
+        }
+        fetch_pool(blk + 1);
+        lds_barrier();
+        bool valid[NR];
+        uint32_t dst_pt[NR], rank[NR];
+        float fx[NR], fy[NR];
+#pragma unroll
+        for (int k = 0; k < NR; ++k) { valid[k] = false; dst_pt[k] = 0u; rank[k] = 0u; fx[k] = 0.f; fy[k] = 0.f; }
+        // ---- ROUNDS rounds of one edge per lane, no barriers in between
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const int64_t e64 = blk * G + (int64_t)r * BS + tid;
+            const bool has = f.has;
+            const int32_t i = f.i, ea = f.ea, eb = f.eb;
+            float hx = 0.f, hy = 0.f;
+            if (has) {
+                uint32_t slot[SS];
+                float2 tm[SS];
+                {
+                    uint32_t wd[4];
+                    philox4x32_10((uint32_t)f.e, 0u, P.epoch, 0u, P.key0, P.key1, wd);   // S <= 8: one call
+#pragma unroll
+                    for (int k = 0; k < S; ++k) slot[k] = pool_slot(wd, k, PS);
+                }
+#pragma unroll
+                for (int k = 0; k < S; ++k) tm[k] = pool_th[slot[k]];
+                EdgeOut<SS> o;
+                edge_math<S, false>(f.h, f.pe, f.tj, tm, o);
+                hx = o.hx;
+                hy = o.hy;
+#pragma unroll
+                for (int k = 0; k < S; ++k) {
+                    atomicAdd(&pool_acc[2 * slot[k]], (unsigned long long)__float2ll_rn(o.rx[k] * kFixScale));
+                    atomicAdd(&pool_acc[2 * slot[k] + 1], (unsigned long long)__float2ll_rn(o.ry[k] * kFixScale));
+                }
+                valid[r] = true; dst_pt[r] = (uint32_t)f.j; fx[r] = -o.a * o.dx; fy[r] = -o.a * o.dy;
+            }
+            {
+                const int64_t e1 = e64 + BS, e2 = e1 + BS;
+                const int32_t i1 = i_next, j1 = j_next;
+                if (e2 < e_end) { i_next = Q.head[e2]; j_next = P.col[e2]; }
+                issue_edge<S, false>(P, e1 < e_end, (int32_t)e1, i1, j1, f);
+            }
+            valid[ROUNDS + r] = reduce_head_sums(Q, has, i, ea, eb, e64, e_end, hx, hy);
+            dst_pt[ROUNDS + r] = valid[ROUNDS + r] ? (uint32_t)i : 0u;
+            fx[ROUNDS + r] = hx;
+            fy[ROUNDS + r] = hy;
+            if (valid[r]) rank[r] = take_rank(L, dst_pt[r]);
+            if (valid[ROUNDS + r]) rank[ROUNDS + r] = take_rank(L, dst_pt[ROUNDS + r]);
+        }
+        lds_barrier();
+        // ---- one record per pool entry that received a force
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            const uint32_t u = (uint32_t)tid + (uint32_t)k * BS;
+            const int q = 2 * ROUNDS + k;
+            if (u < PS) {
+                const long long ax = (long long)pool_acc[2 * u], ay = (long long)pool_acc[2 * u + 1];
+                valid[q] = (ax | ay) != 0;
+                dst_pt[q] = pool_pt[u];
+                fx[q] = (float)((double)ax * kFixInv);
+                fy[q] = (float)((double)ay * kFixInv);
+                if (valid[q]) rank[q] = take_rank(L, dst_pt[q]);
+            }
+        }
+        sort_and_flush<NR, BS, FLUSH_ITERS>(L, Q, pool_end, &pool_cursor, wave_total, valid, dst_pt, rank, fx, fy);
+    }
+    publish_chains<BS>(L, Q, pool_end);
 }
 
 // private chunk-id range of each workgroup: enough for every record its edges can emit (s+1 per
@@ -841,6 +1051,23 @@ __global__ void k_wg_pools(int64_t E, int W, int records_per_edge, int block, ui
         const uint64_t rounds = (edges + block - 1) / block;
         const uint64_t records = edges * (uint64_t)records_per_edge + rounds * 2 * (block / 64);
         run += records / kChunk + n_bins + 1;
+    }
+    wg_pool_begin[W] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
+    *total = run;
+}
+
+// the same bound for the pooled edge pass: workgroups own whole blocks of `block_edges` positions; records per
+// block = one tail per edge, two partial head sums per wavefront and round, one per pool entry
+__global__ void k_wg_pools_pooled(int64_t E, int W, int64_t block_edges, uint32_t pool_size, uint32_t n_bins,
+                                  uint32_t* __restrict__ wg_pool_begin, unsigned long long* __restrict__ total) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    const int64_t n_blocks = (E + block_edges - 1) / block_edges;
+    const uint64_t per_block = (uint64_t)block_edges + 2 * (kPoolBlockLanes / 64) * (uint64_t)(block_edges / kPoolBlockLanes) + pool_size;
+    uint64_t run = 0;
+    for (int w = 0; w < W; ++w) {
+        wg_pool_begin[w] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
+        const uint64_t blocks = (uint64_t)(n_blocks * (int64_t)(w + 1) / W - n_blocks * (int64_t)w / W);
+        run += blocks * per_block / kChunk + n_bins + 1;
     }
     wg_pool_begin[W] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
     *total = run;
@@ -981,11 +1208,7 @@ __global__ void __launch_bounds__(kBlock) k_negatives(const EdgeArgs P, int64_t 
         pop.count = (uint32_t)P.n;
         pop.members = nullptr;
     }
-    for (int b = 0; 4 * b < P.s; ++b) {
-        uint32_t w[4];
-        philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)b, P.key0, P.key1, w);
-        for (int l = 0; l < 4 && 4 * b + l < P.s; ++l) out[(e - e_begin) * P.s + 4 * b + l] = pick_negative(P, pop, (int32_t)e, w[l]);
-    }
+    for (int k = 0; k < P.s; ++k) out[(e - e_begin) * P.s + k] = negative_of_slot(P, pop, (int32_t)e, k);
 }
 
 }  // namespace nomad

@@ -26,7 +26,8 @@ def grad_err(g, ref):
 
 def device_nomad(w, mode=SCATTER_DETERMINISTIC):
     dev = "cuda"
-    nm = Nomad(w.n, w.n_clusters, w.n_neg, w.noise_count, w.n_epochs, w.lr0, w.seed, mode)
+    nm = Nomad(w.n, w.n_clusters, w.n_neg, w.noise_count, w.n_epochs, w.lr0, w.seed, mode,
+               pool_size=w.pool_size, pool_block=w.pool_block)
     nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None, w.cluster_of.to(dev),
                  None if w.cluster_group is None else w.cluster_group.to(dev))
     nm.set_embedding(w.theta0.to(dev))
@@ -148,3 +149,52 @@ def test_config5_sampled_gradient_rows(scale):
     err = np.abs(g[pts].astype(np.float64) - g_ref).max() / np.abs(g_ref).max()
     note(f"  grad err on {len(pts)} sampled rows {err:.2e} (max |g| {np.abs(g_ref).max():.3e})")
     assert err < GRAD_TOL
+
+
+# ------------------------------------------------------------------ the opt-in pooled sampler at full size
+@pytest.mark.parametrize("cfg", [1, 3])
+def test_pooled_sampler_trains_like_the_iid_sampler(cfg):
+    """Full training with pools of 2,048 points per 4,096 edges: the GPU follows the oracle run with the same
+    sampler (NP@15 within 0.01), and both end where the i.i.d. sampler ends (NP@15 within 0.02, final loss
+    within 3 %).  The second statement is about the variant's quality, not about parity."""
+    note(f"pooled sampler, full training config {cfg}")
+    w_iid = workloads.make_config(cfg, device="cuda" if cfg >= 2 else "cpu")
+    q = np.arange(w_iid.n) if w_iid.n <= 20000 else np.random.default_rng(cfg).choice(w_iid.n, 10000, replace=False)
+    ref = w_iid.out_nbrs.cpu().numpy()
+    with device_nomad(w_iid) as nm:
+        for t in range(w_iid.n_epochs):
+            nm.epoch(t)
+        np_iid = neighbourhood_preservation(nm.get_embedding(), ref, 15, q)
+        L_iid = nm.loss(w_iid.n_epochs)
+    w = workloads.make_config(cfg, device="cuda" if cfg >= 2 else "cpu")
+    w.pool_size, w.pool_block = 2048, 4096
+    th, th_ref, curve, curve_ref = train_both(w)
+    np_gpu = neighbourhood_preservation(th, ref, 15, q)
+    np_or = neighbourhood_preservation(th_ref, ref, 15, q)
+    note(f"  NP@15 pooled gpu {np_gpu:.4f} oracle {np_or:.4f}; i.i.d. gpu {np_iid:.4f}; "
+         f"last sampled loss pooled {curve[-1][1]:.4f} i.i.d. final {L_iid:.4f}")
+    assert abs(np_gpu - np_or) < NP_TOL
+    assert abs(np_gpu - np_iid) < 2 * NP_TOL
+    with device_nomad(w) as nm:
+        nm.set_embedding(th)
+        L_pool = nm.loss(w.n_epochs)
+    assert abs(L_pool - L_iid) < 0.03 * L_iid
+
+
+def test_pooled_sampler_config4_gradient_against_the_oracle():
+    note("config 4, pooled sampler 2048 / 4096")
+    w = workloads.make_config(4, device="cuda")
+    w.pool_size, w.pool_block = 2048, 4096
+    d = w.numpy()
+    O = c_oracle.COracle(**d)
+    E = O.n_edges
+    with device_nomad(w) as nm:
+        for e0 in np.random.default_rng(5).integers(0, E - 30000, 50):
+            assert np.array_equal(nm.get_negatives(1, int(e0), int(e0) + 30000), O.negatives(1, int(e0), int(e0) + 30000))
+        th1, g_ref, _ = O.epoch(d["theta0"], 0)
+        nm.epoch(0)
+        err = grad_err(nm.get_gradient(), g_ref)
+        L_ref, _ = O.loss_and_grad(th1, 1, want_grad=False)
+        L = nm.loss(1)
+        note(f"  epoch 0: grad err {err:.2e}, loss {L:.8f} vs {L_ref:.8f}")
+        assert err < GRAD_TOL and abs(L - L_ref) < LOSS_TOL * L_ref

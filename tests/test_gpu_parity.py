@@ -245,7 +245,8 @@ def test_deterministic_variants_on_skewed_degrees(env, monkeypatch):
 
 # ------------------------------------------------------------------ the opt-in pooled sampler
 POOLS = [pytest.param((48, 100), id="P48-G100-general-kernels"), pytest.param((2048, 4096), id="P2048-G4096"),
-         pytest.param((1000, 1024), id="P1000-G1024"), pytest.param((4096, 2048), id="P4096-G2048")]
+         pytest.param((1000, 1024), id="P1000-G1024"), pytest.param((4096, 2048), id="P4096-G2048"),
+         pytest.param((512, 8192), id="P512-G8192")]
 
 
 @pytest.mark.parametrize("mode", MODES)

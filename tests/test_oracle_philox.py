@@ -114,9 +114,10 @@ def test_uniformity_chi_square():
 # ------------------------------------------------------------------ pooled sampler (opt-in variant)
 @pytest.mark.parametrize("impl", ["py", "c"])
 def test_pooled_negative_is_pool_entry_picked_by_the_edge_word(impl):
-    """m[e,slot] = pool_beta[floor(x * P / 2^32)], beta = e // G, x the per-edge word of the i.i.d. sampler,
-    pool_beta[u] = floor(y * n / 2^32) with y = word u&3 of Philox(counter=(beta, 0xFFFFFFFF, t, u>>2))."""
-    n, s, seed, t, P, G = 1000, 6, (7 << 32) | 99, 4, 48, 128
+    """m[e,k] = pool_beta[(x16 * P) >> 16], beta = e // G, x16 = half k&1 of word (k>>1)&3 of
+    Philox(counter=(e, 0, t, k>>3)); pool_beta[u] = floor(y * n / 2^32), y = word u&3 of
+    Philox(counter=(beta, 0xFFFFFFFF, t, u>>2))."""
+    n, s, seed, t, P, G = 1000, 11, (7 << 32) | 99, 4, 48, 128
     row_ptr, col = _ring(n)
     O = IMPLS[impl](n=n, row_ptr=row_ptr, col_idx=col, cluster_of=np.zeros(n, int), n_clusters=1, n_neg=s,
                     noise_count=s, seed=seed, pool_size=P, pool_block=G)
@@ -124,8 +125,8 @@ def test_pooled_negative_is_pool_entry_picked_by_the_edge_word(impl):
     key = (seed & 0xFFFFFFFF, seed >> 32)
     for e in (0, 127, 128, 1031, 2 * n - 1):
         for slot in range(s):
-            x = po.philox4x32_10((e, 0, t, slot >> 2), key)[slot & 3]
-            u = (x * P) >> 32
+            x16 = (po.philox4x32_10((e, 0, t, slot >> 3), key)[(slot >> 1) & 3] >> (16 * (slot & 1))) & 0xFFFF
+            u = (x16 * P) >> 16
             y = po.philox4x32_10((e // G, 0xFFFFFFFF, t, u >> 2), key)[u & 3]
             assert neg[e, slot] == (y * n) >> 32
     assert np.array_equal(O.negatives(t, 100, 300), neg[100:300])      # a range that crosses a block boundary
