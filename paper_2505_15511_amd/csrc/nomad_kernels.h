@@ -361,7 +361,7 @@ __device__ __forceinline__ void edge_math(const HeadCtx& h, float pe, float2 tj,
         o.log_term = pe * logf(Se / qij);   // -log q + log S = log(S (1 + d^2))
         return;
     }
-    const float inv_S = 1.0f / Se;
+    const float inv_S = __builtin_amdgcn_rcpf(Se);   // 1 ulp; S_e >= q_ij > 0
     o.a = 2.0f * pe * qij * (1.0f - qij * inv_S);
     float fx = o.a * o.dx, fy = o.a * o.dy;
     const float bscale = 2.0f * pe * h.omega * inv_S;
@@ -462,7 +462,7 @@ __device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const Head
     }
     const float Se = qij + h.MA + h.omega * qsum;
     if (LOSS) { log_term = pe * logf(Se / qij); return; }
-    const float inv_S = 1.0f / Se;
+    const float inv_S = __builtin_amdgcn_rcpf(Se);   // 1 ulp; S_e >= q_ij > 0
     a = 2.0f * pe * qij * (1.0f - qij * inv_S);
     float fx = a * dx, fy = a * dy;
     const float bscale = 2.0f * pe * h.omega * inv_S;
