@@ -256,7 +256,7 @@ int run_means(nomad_ctx* c) {
 int run_mean_field(nomad_ctx* c) {
     if (!c->grouped) return NOMAD_OK;
     Timed tm(c, NOMAD_K_MEANFIELD);
-    hipLaunchKernelGGL(k_mean_field, dim3(blocks_for(c->n)), dim3(kBlock), 0, c->stream, c->theta, c->cluster_of,
+    hipLaunchKernelGGL(k_mean_field, dim3(blocks_for(c->n, kMeanFieldBlock * kMeanFieldHeads)), dim3(kMeanFieldBlock), 0, c->stream, c->theta, c->cluster_of,
                        c->group_of_cluster, c->cinfo, c->group_slots, c->R, c->n, c->A, c->B);
     return NOMAD_OK;
 }

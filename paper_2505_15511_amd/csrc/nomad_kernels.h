@@ -190,13 +190,16 @@ __global__ void __launch_bounds__(kBlock) k_mean_finish(const double2* __restric
 }
 
 // ------------------------------------------------------------------ K2: mean-field sums (Eq. 5)
-// One lane per head; the cell table is read with wave-uniform addresses (scalar loads), eight
-// cells per batch.  The table is ordered group by group, so the cells a head does NOT approximate
+// One lane per head; the cell table is staged through LDS, 1,024 cells at a time, and read with
+// wave-uniform addresses, eight cells per batch.  The table is ordered group by group, so the cells a head does NOT approximate
 // (its own group) are one slot range [lo, hi).  Points are usually numbered cluster by cluster,
 // which makes that range the same for all 64 lanes of most wavefronts: those skip the range and
 // need no per-cell test; mixed wavefronts test every cell.  Partial sums are folded into the
 // totals every 64 cells to keep float32 round-off from growing with |R|.
 struct MeanFieldSum { float a, bx, by; };
+
+constexpr int kMeanFieldBlock = 1024;   // lanes per workgroup = cells staged per step
+constexpr int kMeanFieldHeads = 1;      // heads per lane (2 measured 10 % slower: the loop is bound by vector ALU issue, not by LDS)
 
 template <bool TEST>
 __device__ __forceinline__ void mean_field_add(float q, float dx, float dy, const float4 c, int32_t gi, MeanFieldSum& s) {
@@ -225,43 +228,83 @@ __device__ __forceinline__ void mean_field_pair(const float2 ti, const float4 c0
     mean_field_add<TEST>(r * t0, dx1, dy1, c1, gi, s);
 }
 
+// cells [r_begin, r_end) of the staged part of the table (LDS; `cells` points at the slot that holds cell 0),
+// for the kMeanFieldHeads heads of this lane
 template <bool TEST>
-__device__ __forceinline__ void mean_field_range(const float2 ti, const float4* __restrict__ cinfo, int32_t r_begin, int32_t r_end,
-                                                 int32_t gi, MeanFieldSum& total) {
+__device__ __forceinline__ void mean_field_range(const float2 (&ti)[kMeanFieldHeads], const float4* cells, int32_t r_begin, int32_t r_end,
+                                                 const int32_t (&gi)[kMeanFieldHeads], MeanFieldSum (&total)[kMeanFieldHeads]) {
     for (int32_t r0 = r_begin; r0 < r_end; r0 += 64) {
-        MeanFieldSum s{0.f, 0.f, 0.f};
+        MeanFieldSum s[kMeanFieldHeads];
+#pragma unroll
+        for (int h = 0; h < kMeanFieldHeads; ++h) s[h] = MeanFieldSum{0.f, 0.f, 0.f};
         const int32_t r1 = min(r_end, r0 + 64);
         int32_t r = r0;
         for (; r + 8 <= r1; r += 8) {
 #pragma unroll
-            for (int u = 0; u < 8; u += 2) mean_field_pair<TEST>(ti, cinfo[r + u], cinfo[r + u + 1], gi, s);
+            for (int u = 0; u < 8; u += 2) {
+                const float4 c0 = cells[r + u], c1 = cells[r + u + 1];
+#pragma unroll
+                for (int h = 0; h < kMeanFieldHeads; ++h) mean_field_pair<TEST>(ti[h], c0, c1, gi[h], s[h]);
+            }
         }
-        for (; r < r1; ++r) mean_field_cell<TEST>(ti, cinfo[r], gi, s);
-        total.a += s.a; total.bx += s.bx; total.by += s.by;
+        for (; r < r1; ++r) {
+            const float4 c = cells[r];
+#pragma unroll
+            for (int h = 0; h < kMeanFieldHeads; ++h) mean_field_cell<TEST>(ti[h], c, gi[h], s[h]);
+        }
+#pragma unroll
+        for (int h = 0; h < kMeanFieldHeads; ++h) { total[h].a += s[h].a; total[h].bx += s[h].bx; total[h].by += s[h].by; }
     }
 }
 
-__global__ void __launch_bounds__(kBlock) k_mean_field(const float2* __restrict__ theta,
-                                                       const int32_t* __restrict__ cluster_of,
-                                                       const int32_t* __restrict__ group_of_cluster,
-                                                       const float4* __restrict__ cinfo, const int2* __restrict__ group_slots,
-                                                       int32_t R, int64_t n, float* __restrict__ A, float2* __restrict__ B) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t ic = min(i, n - 1);   // lanes past the end compute a copy of the last head and store nothing
-    const float2 ti = theta[ic];
-    const int32_t gi = group_of_cluster[cluster_of[ic]];
-    MeanFieldSum t{0.f, 0.f, 0.f};
-    const int32_t g0 = __builtin_amdgcn_readfirstlane(gi);
-    if (__all(gi == g0)) {
-        const int2 own = group_slots[g0];   // wave-uniform
-        mean_field_range<false>(ti, cinfo, 0, own.x, gi, t);
-        mean_field_range<false>(ti, cinfo, own.y, R, gi, t);
-    } else {
-        mean_field_range<true>(ti, cinfo, 0, R, gi, t);
+__global__ void __launch_bounds__(kMeanFieldBlock) k_mean_field(const float2* __restrict__ theta,
+                                                                const int32_t* __restrict__ cluster_of,
+                                                                const int32_t* __restrict__ group_of_cluster,
+                                                                const float4* __restrict__ cinfo, const int2* __restrict__ group_slots,
+                                                                int32_t R, int64_t n, float* __restrict__ A, float2* __restrict__ B) {
+    // Every wavefront needs the whole cell table.  Reading it straight from memory with wave-uniform loads makes
+    // each of the n/64 wavefronts pull all |R| x 16 bytes through the scalar cache (240 GB per launch at 60 M points
+    // and 16,384 cells); staged through LDS the table is read once per workgroup and broadcast to the lanes.
+    __shared__ float4 cells[kMeanFieldBlock];
+    // the heads of a lane are adjacent points, so that a wavefront covers 128 consecutive points (one group, usually)
+    const int64_t i0 = ((int64_t)blockIdx.x * kMeanFieldBlock + threadIdx.x) * kMeanFieldHeads;
+    float2 ti[kMeanFieldHeads];
+    int32_t gi[kMeanFieldHeads];
+    MeanFieldSum t[kMeanFieldHeads];
+#pragma unroll
+    for (int h = 0; h < kMeanFieldHeads; ++h) {
+        const int64_t ic = min(i0 + h, n - 1);   // heads past the end: a copy of the last one, not stored
+        ti[h] = theta[ic];
+        gi[h] = group_of_cluster[cluster_of[ic]];
+        t[h] = MeanFieldSum{0.f, 0.f, 0.f};
     }
-    if (i < n) {
-        A[i] = t.a;
-        B[i] = make_float2(t.bx, t.by);
+    const int32_t g0 = __builtin_amdgcn_readfirstlane(gi[0]);
+    bool same = true;
+#pragma unroll
+    for (int h = 0; h < kMeanFieldHeads; ++h) same = same && gi[h] == g0;
+    const bool uniform = __all(same);
+    int2 own = make_int2(0, 0);           // slot range to skip: the own group of a wavefront whose heads share it
+    if (uniform) own = group_slots[g0];
+    for (int32_t c0 = 0; c0 < R; c0 += kMeanFieldBlock) {
+        __syncthreads();
+        if (c0 + (int32_t)threadIdx.x < R) cells[threadIdx.x] = cinfo[c0 + threadIdx.x];
+        __syncthreads();
+        const int32_t c1 = min(R, c0 + kMeanFieldBlock);
+        const float4* base = cells - c0;
+        if (uniform) {
+            mean_field_range<false>(ti, base, c0, min(c1, max(c0, own.x)), gi, t);
+            mean_field_range<false>(ti, base, max(c0, min(c1, own.y)), c1, gi, t);
+        } else {
+            mean_field_range<true>(ti, base, c0, c1, gi, t);
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < kMeanFieldHeads; ++h) {
+        const int64_t i = i0 + h;
+        if (i < n) {
+            A[i] = t[h].a;
+            B[i] = make_float2(t[h].bx, t[h].by);
+        }
     }
 }
 
