@@ -37,6 +37,7 @@ struct nomad_ctx {
     // partition tables
     uint32_t *counts = nullptr, *gbase = nullptr, *gcount = nullptr, *chunk_start = nullptr;
     float* gomega = nullptr;
+    float4* hinfo = nullptr;
     int32_t *gmembers = nullptr, *cmembers = nullptr;
     MeanChunk* chunks = nullptr;
     uint32_t n_chunks = 0;
@@ -104,7 +105,7 @@ void dev_free(T*& p) {
 void free_graph(nomad_ctx* c) {
     dev_free(c->row_ptr); dev_free(c->col); dev_free(c->cluster_of); dev_free(c->group_of_cluster);
     dev_free(c->pe); dev_free(c->counts); dev_free(c->gbase); dev_free(c->gcount); dev_free(c->chunk_start);
-    dev_free(c->gomega); dev_free(c->gmembers); dev_free(c->cmembers); dev_free(c->chunks); dev_free(c->mean_partial);
+    dev_free(c->gomega); dev_free(c->hinfo); dev_free(c->gmembers); dev_free(c->cmembers); dev_free(c->chunks); dev_free(c->mean_partial);
     dev_free(c->theta); dev_free(c->g); dev_free(c->ghead); dev_free(c->mu); dev_free(c->B); dev_free(c->cinfo);
     dev_free(c->cell_slot); dev_free(c->group_slots);
     dev_free(c->A); dev_free(c->gfix); dev_free(c->loss_partial); dev_free(c->loss_out);
@@ -151,7 +152,7 @@ EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
     EdgeArgs a{};
     a.row_ptr = c->row_ptr; a.col = c->col; a.pe = c->pe; a.theta = c->theta;
     a.cluster_of = c->cluster_of; a.group_of_cluster = c->grouped ? c->group_of_cluster : nullptr;
-    a.gbase = c->gbase; a.gcount = c->gcount; a.gomega = c->gomega; a.gmembers = c->gmembers;
+    a.gbase = c->gbase; a.gcount = c->gcount; a.gomega = c->gomega; a.gmembers = c->gmembers; a.hinfo = c->hinfo;
     a.A = c->A; a.B = c->B;
     a.noise_count = c->noise_count; a.omega0 = c->omega0;
     a.key0 = (uint32_t)c->cfg.seed; a.key1 = (uint32_t)(c->cfg.seed >> 32); a.epoch = t;
@@ -483,6 +484,9 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         HTRY(hipMemcpy(c->gbase, gbase.data(), sizeof(uint32_t) * (size_t)R, hipMemcpyHostToDevice));
         HTRY(hipMemcpy(c->gcount, gcount.data(), sizeof(uint32_t) * (size_t)R, hipMemcpyHostToDevice));
         HTRY(hipMemcpy(c->gomega, gomega.data(), sizeof(float) * (size_t)R, hipMemcpyHostToDevice));
+        TRY(dev_alloc(c, &c->hinfo, (size_t)n));
+        hipLaunchKernelGGL(k_head_info, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->cluster_of, c->group_of_cluster, c->gbase,
+                           c->gcount, c->gomega, n, c->hinfo);
         TRY(dev_alloc(c, &c->A, (size_t)n));
         TRY(dev_alloc(c, &c->B, (size_t)n));
         // cell table ordered group by group (stable in the cell id): the mean-field pass skips a head's own

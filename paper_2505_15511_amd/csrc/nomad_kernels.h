@@ -127,6 +127,16 @@ __global__ void k_cluster_census(const int32_t* __restrict__ cluster_of, const i
     }
 }
 
+// hinfo[i] = (population base, population size, omega) of the group of point i (see EdgeArgs::hinfo)
+__global__ void __launch_bounds__(kBlock) k_head_info(const int32_t* __restrict__ cluster_of, const int32_t* __restrict__ group_of_cluster,
+                                                      const uint32_t* __restrict__ gbase, const uint32_t* __restrict__ gcount,
+                                                      const float* __restrict__ gomega, int64_t n, float4* __restrict__ hinfo) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int32_t g = group_of_cluster[cluster_of[i]];
+    hinfo[i] = make_float4(__uint_as_float(gbase[g]), __uint_as_float(gcount[g]), gomega[g], 0.f);
+}
+
 // ------------------------------------------------------------------ K1: cell means
 // Two stages, both in a fixed order: (a) one block per chunk of a cell's member list sums its
 // points in float64 (lane-strided partials, xor butterfly inside the wavefront, wavefront totals
@@ -320,6 +330,8 @@ struct EdgeArgs {
     const uint32_t* gcount;        // per group: population size
     const float* gomega;           // per group: weight of one sampled negative
     const int32_t* gmembers;       // nullptr when every group is an index range
+    const float4* hinfo;           // grouped: per point (population base, population size, omega, -) of its group,
+                                   // so that the edge pass needs one lookup per head instead of a chain of four
     const float* A;                // mean-field sums (grouped only)
     const float2* B;
     float noise_count;             // |M|
@@ -353,11 +365,11 @@ __device__ __forceinline__ HeadCtx load_head(const EdgeArgs& P, int64_t i, int32
     h.inv_deg = eb > ea ? 1.0f / (float)(eb - ea) : 0.f;
     h.MA = h.MBx = h.MBy = 0.f;
     if (P.group_of_cluster) {
-        const int32_t gi = P.group_of_cluster[P.cluster_of[i]];
-        h.pop.base = P.gbase[gi];
-        h.pop.count = P.gcount[gi];
+        const float4 hi = P.hinfo[i];
+        h.pop.base = __float_as_uint(hi.x);
+        h.pop.count = __float_as_uint(hi.y);
         h.pop.members = P.gmembers;
-        h.omega = P.gomega[gi];
+        h.omega = hi.z;
         h.MA = P.noise_count * P.A[i];
         const float2 b = P.B[i];
         h.MBx = P.noise_count * b.x;
