@@ -890,27 +890,31 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
     __shared__ uint32_t pool_cursor;
     const int tid = threadIdx.x;
     const uint32_t W = gridDim.x, w = blockIdx.x;
-    const int64_t e_begin = Q.E * (int64_t)w / W, e_end = Q.E * (int64_t)(w + 1) / W;
     const uint32_t pool_end = min(Q.wg_pool_begin[w + 1], Q.max_chunks);
     init_bin_lds<BS>(L);
     if (tid == 0) pool_cursor = Q.wg_pool_begin[w];
     lds_barrier();
 
-    const int64_t n_rounds = (e_end - e_begin + BS - 1) / BS;
+    // The CSR positions are dealt to the workgroups in slabs of BS positions, round-robin: slab w, w + W, ...
+    // (every workgroup then sends records to every tile at about the same rate, whatever the locality of the
+    // graph, which keeps the chains the tile pass walks equally long).
+    const int64_t n_slabs = (Q.E + BS - 1) / BS;
+    const int64_t stride = (int64_t)W * BS;
     // Software pipeline over rounds: (head, tail) indices are read two rounds ahead, the embedding rows
     // one round ahead.
     EdgeFetch<S, true> f;
     int32_t i_next = 0, j_next = 0;
     {
-        const int64_t e0 = e_begin + tid, e1 = e0 + BS;
+        const int64_t e0 = (int64_t)w * BS + tid, e1 = e0 + stride;
         int32_t i0 = 0, j0 = 0;
-        if (e0 < e_end) { i0 = Q.head[e0]; j0 = P.col[e0]; }
-        if (e1 < e_end) { i_next = Q.head[e1]; j_next = P.col[e1]; }
-        issue_edge<S, true>(P, e0 < e_end, (int32_t)e0, i0, j0, f);
+        if (e0 < Q.E) { i0 = Q.head[e0]; j0 = P.col[e0]; }
+        if (e1 < Q.E) { i_next = Q.head[e1]; j_next = P.col[e1]; }
+        issue_edge<S, true>(P, e0 < Q.E, (int32_t)e0, i0, j0, f);
     }
-    for (int64_t round = 0; round < n_rounds; ++round) {
+    for (int64_t slab = w; slab < n_slabs; slab += W) {
         // one edge per lane; records: slot 0 the tail (force -a d_ij), slots 1..S the negatives
-        const int64_t e64 = e_begin + round * BS + tid;
+        const int64_t e64 = slab * BS + tid;
+        const int64_t e_end = min((slab + 1) * BS, Q.E);
         const bool has = f.has;
         const int32_t i = f.i, ea = f.ea, eb = f.eb;
         bool valid[NR];
@@ -930,10 +934,10 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
         }
         // the loads of the next round go out before this round is sorted and written
         {
-            const int64_t e1 = e64 + BS, e2 = e1 + BS;
+            const int64_t e1 = e64 + stride, e2 = e1 + stride;
             const int32_t i1 = i_next, j1 = j_next;
-            if (e2 < e_end) { i_next = Q.head[e2]; j_next = P.col[e2]; }
-            issue_edge<S, true>(P, e1 < e_end, (int32_t)e1, i1, j1, f);
+            if (e2 < Q.E) { i_next = Q.head[e2]; j_next = P.col[e2]; }
+            issue_edge<S, true>(P, e1 < Q.E, (int32_t)e1, i1, j1, f);
         }
         valid[S + 1] = reduce_head_sums(Q, has, i, ea, eb, e64, e_end, hx, hy);
         dst_pt[S + 1] = valid[S + 1] ? (uint32_t)i : 0u;
@@ -984,9 +988,8 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
     const int tid = threadIdx.x;
     const uint32_t W = gridDim.x, w = blockIdx.x;
     constexpr int64_t G = (int64_t)BS * ROUNDS;                       // = P.pool_block
+    // blocks are dealt to the workgroups round-robin: block w, w + W, ...
     const int64_t n_blocks = (Q.E + G - 1) / G;
-    const int64_t blk_begin = n_blocks * (int64_t)w / W, blk_end = n_blocks * (int64_t)(w + 1) / W;
-    const int64_t e_begin = blk_begin * G, e_end = min(blk_end * G, Q.E);
     const uint32_t pool_end = min(Q.wg_pool_begin[w + 1], Q.max_chunks);
     init_bin_lds<BS>(L);
     if (tid == 0) pool_cursor = Q.wg_pool_begin[w];
@@ -999,7 +1002,7 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
 #pragma unroll
         for (int k = 0; k < NP; ++k) { next_pt[k] = 0u; next_th[k] = make_float2(0.f, 0.f); }
         const uint32_t u0 = 4u * (uint32_t)tid;
-        if (u0 < PS && blk < blk_end) {
+        if (u0 < PS && blk < n_blocks) {
             uint32_t wd[4];
             philox4x32_10((uint32_t)blk, 0xFFFFFFFFu, P.epoch, (uint32_t)tid, P.key0, P.key1, wd);
 #pragma unroll
@@ -1007,24 +1010,28 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
                 if (u0 + k < PS) { next_pt[k] = __umulhi(wd[k], (uint32_t)P.n); next_th[k] = P.theta[next_pt[k]]; }
         }
     };
-    fetch_pool(blk_begin);
+    fetch_pool(w);
+    // edge pipeline as in k_edges_binned; the position after the last one of a block is the first of this
+    // workgroup's next block
+    auto next_position = [&](int64_t e) { return (e + BS) % G < BS ? e + BS + (int64_t)(W - 1) * G : e + BS; };
     EdgeFetch<S, false> f;
     int32_t i_next = 0, j_next = 0;
     {
-        const int64_t e0 = e_begin + tid, e1 = e0 + BS;
+        const int64_t e0 = (int64_t)w * G + tid, e1 = next_position(e0);
         int32_t i0 = 0, j0 = 0;
-        if (e0 < e_end) { i0 = Q.head[e0]; j0 = P.col[e0]; }
-        if (e1 < e_end) { i_next = Q.head[e1]; j_next = P.col[e1]; }
-        issue_edge<S, false>(P, e0 < e_end, (int32_t)e0, i0, j0, f);
+        if (e0 < Q.E) { i0 = Q.head[e0]; j0 = P.col[e0]; }
+        if (e1 < Q.E) { i_next = Q.head[e1]; j_next = P.col[e1]; }
+        issue_edge<S, false>(P, e0 < Q.E, (int32_t)e0, i0, j0, f);
     }
-    for (int64_t blk = blk_begin; blk < blk_end; ++blk) {
+    for (int64_t blk = w; blk < n_blocks; blk += W) {
+        const int64_t e_end = min((blk + 1) * G, Q.E);
         // ---- this block's pool into LDS, the next block's pool into flight
 #pragma unroll
         for (int k = 0; k < NP; ++k) {
             const uint32_t u = 4u * (uint32_t)tid + (uint32_t)k;
             if (u < PS) { pool_pt[u] = next_pt[k]; pool_th[u] = next_th[k]; pool_acc[2 * u] = 0ull; pool_acc[2 * u + 1] = 0ull; }
         }
-        fetch_pool(blk + 1);
+        fetch_pool(blk + W);
         lds_barrier();
         bool valid[NR];
         uint32_t dst_pt[NR], rank[NR];
@@ -1061,10 +1068,10 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
                 valid[r] = true; dst_pt[r] = (uint32_t)f.j; fx[r] = -o.a * o.dx; fy[r] = -o.a * o.dy;
             }
             {
-                const int64_t e1 = e64 + BS, e2 = e1 + BS;
+                const int64_t e1 = next_position(e64), e2 = next_position(e1);
                 const int32_t i1 = i_next, j1 = j_next;
-                if (e2 < e_end) { i_next = Q.head[e2]; j_next = P.col[e2]; }
-                issue_edge<S, false>(P, e1 < e_end, (int32_t)e1, i1, j1, f);
+                if (e2 < Q.E) { i_next = Q.head[e2]; j_next = P.col[e2]; }
+                issue_edge<S, false>(P, e1 < Q.E, (int32_t)e1, i1, j1, f);
             }
             valid[ROUNDS + r] = reduce_head_sums(Q, has, i, ea, eb, e64, e_end, hx, hy);
             dst_pt[ROUNDS + r] = valid[ROUNDS + r] ? (uint32_t)i : 0u;
@@ -1093,18 +1100,18 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
     publish_chains<BS>(L, Q, pool_end);
 }
 
-// private chunk-id range of each workgroup: enough for every record its edges can emit (s+1 per
-// edge, plus at most two partial head sums per wavefront and round), plus one partly filled chunk
+// private chunk-id range of each workgroup: enough for every record its slabs can emit (s+1 per
+// position, plus at most two partial head sums per wavefront and round), plus one partly filled chunk
 // per tile (one thread: W is a few hundred)
 __global__ void k_wg_pools(int64_t E, int W, int records_per_edge, int block, uint32_t n_bins, uint32_t* __restrict__ wg_pool_begin,
                            unsigned long long* __restrict__ total) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    const uint64_t n_slabs = (uint64_t)((E + block - 1) / block);
     uint64_t run = 0;
     for (int w = 0; w < W; ++w) {
         wg_pool_begin[w] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
-        const uint64_t edges = (uint64_t)(E * (int64_t)(w + 1) / W - E * (int64_t)w / W);
-        const uint64_t rounds = (edges + block - 1) / block;
-        const uint64_t records = edges * (uint64_t)records_per_edge + rounds * 2 * (block / 64);
+        const uint64_t rounds = n_slabs / W + ((uint64_t)w < n_slabs % W ? 1 : 0);   // slabs w, w + W, ...
+        const uint64_t records = rounds * ((uint64_t)block * records_per_edge + 2 * (block / 64));
         run += records / kChunk + n_bins + 1;
     }
     wg_pool_begin[W] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
@@ -1121,7 +1128,7 @@ __global__ void k_wg_pools_pooled(int64_t E, int W, int64_t block_edges, uint32_
     uint64_t run = 0;
     for (int w = 0; w < W; ++w) {
         wg_pool_begin[w] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
-        const uint64_t blocks = (uint64_t)(n_blocks * (int64_t)(w + 1) / W - n_blocks * (int64_t)w / W);
+        const uint64_t blocks = (uint64_t)(n_blocks / W + ((int64_t)w < n_blocks % W ? 1 : 0));   // blocks w, w + W, ...
         run += blocks * per_block / kChunk + n_bins + 1;
     }
     wg_pool_begin[W] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
