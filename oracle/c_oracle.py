@@ -26,7 +26,8 @@ class _Problem(C.Structure):
     _fields_ = [("n", C.c_int64), ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("weights", C.c_void_p),
                 ("cluster_of", C.c_void_p), ("n_clusters", C.c_int32), ("cluster_group", C.c_void_p),
                 ("n_neg", C.c_int32), ("noise_count", C.c_double), ("seed", C.c_uint64),
-                ("pool_size", C.c_int32), ("pool_block", C.c_int32)]
+                ("pool_size", C.c_int32), ("pool_block", C.c_int32), ("batches_per_epoch", C.c_int32),
+                ("head_begin", C.c_int64), ("head_end", C.c_int64)]
 
 
 def _load():
@@ -51,7 +52,7 @@ class COracle:
     """Holds int32/fp32 copies of a problem and calls the C oracle on them."""
 
     def __init__(self, *, n, row_ptr, col_idx, cluster_of, n_clusters, n_neg, noise_count, seed=0, n_epochs=1,
-                 lr0=1.0, weights=None, cluster_group=None, pool_size=0, pool_block=0, **_ignored):
+                 lr0=1.0, weights=None, cluster_group=None, pool_size=0, pool_block=0, batches_per_epoch=1, **_ignored):
         self.lib = _load()
         self.n = int(n)
         self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
@@ -70,7 +71,8 @@ class COracle:
         assert self.pool_size == 0 or self.cluster_group is None, "the pooled sampler needs a single population"
         self.P = _Problem(self.n, _ptr(self.row_ptr), _ptr(self.col_idx), _ptr(self.weights), _ptr(self.cluster_of),
                           self.n_clusters, _ptr(self.cluster_group), self.n_neg, self.noise_count, self.seed,
-                          self.pool_size, self.pool_block)
+                          self.pool_size, self.pool_block, int(batches_per_epoch), 0, -1)
+        self.batches_per_epoch = int(batches_per_epoch)
 
     @property
     def n_edges(self):
@@ -95,7 +97,15 @@ class COracle:
         assert rc == 0, rc
         return counts, counts / float(self.n), mu
 
-    def loss_and_grad(self, theta, t, want_grad=True, mean_field=False, mu_fixed=None):
+    def loss_and_grad(self, theta, t, want_grad=True, mean_field=False, mu_fixed=None, head_range=None):
+        """head_range = (begin, end): only the edges of those heads (one sub-step of a minibatch epoch)."""
+        self.P.head_begin, self.P.head_end = (0, -1) if head_range is None else (int(head_range[0]), int(head_range[1]))
+        try:
+            return self._loss_and_grad(theta, t, want_grad, mean_field, mu_fixed)
+        finally:
+            self.P.head_begin, self.P.head_end = 0, -1
+
+    def _loss_and_grad(self, theta, t, want_grad, mean_field, mu_fixed):
         th = np.ascontiguousarray(theta, dtype=np.float32)
         muf = None if mu_fixed is None else np.ascontiguousarray(mu_fixed, dtype=np.float64)
         loss = C.c_double(0.0)

@@ -41,6 +41,9 @@ typedef struct {
     uint64_t seed;
     int32_t pool_size;            /* pooled sampler: points per pool (0 = i.i.d. per-edge sampler) */
     int32_t pool_block;           /* pooled sampler: consecutive CSR positions that share a pool   */
+    int32_t batches_per_epoch;    /* B >= 1 (0 is read as 1): sequential sub-steps of an epoch, see oracle_epoch */
+    int64_t head_begin, head_end; /* loss / gradient restricted to the edges of heads head_begin..head_end-1;   */
+                                  /* head_end < 0 = all heads                                                   */
 } oracle_problem;
 
 /* ---- Philox4x32-10 (published algorithm: Salmon, Moraes, Dror, Shaw, SC'11) ---- */
@@ -248,8 +251,10 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
         double* g = gbuf ? gbuf + (size_t)tid * (size_t)gn * 2 : NULL;
         int32_t* m = (int32_t*)malloc(sizeof(int32_t) * (size_t)(s > 0 ? s : 1));
         double* qim = (double*)malloc(sizeof(double) * (size_t)(s > 0 ? s : 1));
+        const int64_t h0 = P->head_end >= 0 ? P->head_begin : 0;
+        const int64_t h1 = P->head_end >= 0 ? P->head_end : n;
 #pragma omp for schedule(dynamic, 256)
-        for (int64_t i = 0; i < n; ++i) {
+        for (int64_t i = h0; i < h1; ++i) {
             const int64_t ea = P->row_ptr[i], eb = P->row_ptr[i + 1];
             const double xi = theta[2 * i], yi = theta[2 * i + 1];
             const int32_t gi = group_of_point(P, i);
@@ -332,16 +337,35 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
     return bad ? -2 : 0;
 }
 
-/* theta <- fp32( theta - lr0 (1 - t/T) g ); grad_out (may be NULL) receives g. */
+/* One epoch in place.  B = batches_per_epoch sequential sub-steps: sub-step b takes the heads
+ * floor(n b / B) .. floor(n (b+1) / B) - 1, evaluates the gradient of their edges at the current theta with the
+ * cell means of the start of the epoch, and applies theta <- fp32(theta - lr0 (1 - t/T) g_b).  B = 1 is the
+ * full-batch step.  grad_out (may be NULL) receives the gradient of the last sub-step; loss_out (may be NULL)
+ * the sum of the sub-steps' loss terms, each at the theta it was evaluated at (B = 1: the loss at theta). */
 int oracle_epoch(const oracle_problem* P, float* theta, int32_t t, int32_t T_epochs, double lr0, double* grad_out,
                  double* loss_out) {
     const int64_t n = P->n;
+    const int32_t B = P->batches_per_epoch > 1 ? P->batches_per_epoch : 1;
+    const int32_t R = P->n_clusters;
     double* g = grad_out ? grad_out : (double*)malloc(sizeof(double) * 2 * (size_t)n);
-    int rc = oracle_loss_grad(P, theta, t, loss_out, g, NULL, 0, NULL, NULL, NULL);
-    if (rc == 0) {
-        const double eta = lr0 * (1.0 - (double)t / (double)T_epochs);
-        for (int64_t x = 0; x < 2 * n; ++x) theta[x] = (float)((double)theta[x] - eta * g[x]);
+    int64_t* counts = (int64_t*)malloc(sizeof(int64_t) * (size_t)R);
+    double* mu0 = (double*)malloc(sizeof(double) * 2 * (size_t)R);
+    oracle_cluster_stats(P, theta, counts, mu0);
+    const double eta = lr0 * (1.0 - (double)t / (double)T_epochs);
+    double total = 0.0;
+    int rc = 0;
+    for (int32_t b = 0; b < B && rc == 0; ++b) {
+        oracle_problem Pb = *P;
+        Pb.head_begin = n * (int64_t)b / B;
+        Pb.head_end = n * (int64_t)(b + 1) / B;
+        double part = 0.0;
+        rc = oracle_loss_grad(&Pb, theta, t, &part, g, NULL, 0, NULL, NULL, mu0);
+        total += part;
+        if (rc == 0)
+            for (int64_t x = 0; x < 2 * n; ++x) theta[x] = (float)((double)theta[x] - eta * g[x]);
     }
+    if (loss_out) *loss_out = total;
+    free(counts); free(mu0);
     if (!grad_out) free(g);
     return rc;
 }

@@ -34,7 +34,9 @@ Readings where the paper is silent (each one is listed in the design notes):
     i's own cluster; negatives are drawn from the points of i's own group (ascending
     index order) and weighted by omega_i = |M| * (n_loc(i)/n) / s;
   - mu is a constant of the epoch (no gradient through it);
-  - eta_t = lr0 * (1 - t/T).
+  - eta_t = lr0 * (1 - t/T);
+  - optional minibatches: batches_per_epoch = B sequential sub-steps over consecutive head ranges, all with
+    eta_t and the cell means of the start of the epoch (see epoch()).
 
 parity status: every function here is pinned by tests/test_oracle_*.py (closed forms,
 finite differences, brute force, invariants, Philox known answers).  Absolute embedding
@@ -111,6 +113,7 @@ class Problem:
     cluster_group: Optional[np.ndarray] = None  # [n_clusters] or None = one group
     pool_size: int = 0                        # pooled sampler: points per pool (0 = i.i.d. per-edge sampler)
     pool_block: int = 0                       # pooled sampler: consecutive CSR positions that share a pool
+    batches_per_epoch: int = 1                # B: sequential sub-steps of an epoch over consecutive head ranges
 
     def __post_init__(self):
         self.row_ptr = np.asarray(self.row_ptr, dtype=np.int64)
@@ -134,7 +137,8 @@ class Problem:
         d = dict(n=w["n"], row_ptr=w["row_ptr"], col_idx=w["col_idx"], cluster_of=w["cluster_of"],
                  n_clusters=w["n_clusters"], n_neg=w["n_neg"], noise_count=w["noise_count"], seed=w["seed"],
                  n_epochs=w["n_epochs"], lr0=w["lr0"], weights=w.get("weights"),
-                 cluster_group=w.get("cluster_group"), pool_size=w.get("pool_size", 0), pool_block=w.get("pool_block", 0))
+                 cluster_group=w.get("cluster_group"), pool_size=w.get("pool_size", 0), pool_block=w.get("pool_block", 0),
+                 batches_per_epoch=w.get("batches_per_epoch", 1))
         d.update(over)
         return cls(**d)
 
@@ -290,10 +294,12 @@ def _as_positions(theta) -> np.ndarray:
     return theta.astype(np.float32).astype(np.float64)
 
 
-def loss_and_grad(P: Problem, theta: np.ndarray, t: int, want_grad: bool = True, mu_fixed=None):
+def loss_and_grad(P: Problem, theta: np.ndarray, t: int, want_grad: bool = True, mu_fixed=None, head_range=None):
     """Sampled NOMAD loss L_t(theta) (Eq. 4, uniform head marginal) and g = grad_theta(n * L_t)
     with the negatives of epoch index t.  Returns (L, g [n,2]).  ``mu_fixed`` replaces the cell
-    means (the gradient holds them constant; a finite-difference check must do the same)."""
+    means (the gradient holds them constant; a finite-difference check must do the same).
+    ``head_range`` = (begin, end) keeps only the terms of the heads begin..end-1 (one sub-step of a
+    minibatch epoch); the terms of all ranges of a partition add up to the full loss and gradient."""
     th = _as_positions(theta)
     n, s, Mn = P.n, P.n_neg, float(P.noise_count)
     pe = edge_probabilities(P)
@@ -305,7 +311,8 @@ def loss_and_grad(P: Problem, theta: np.ndarray, t: int, want_grad: bool = True,
     om = omega(P)
     g = np.zeros((n, 2), dtype=np.float64)
     total = 0.0
-    for i in range(n):
+    h0, h1 = (0, n) if head_range is None else head_range
+    for i in range(h0, h1):
         for e in range(int(P.row_ptr[i]), int(P.row_ptr[i + 1])):
             j = int(P.col_idx[e])
             d_ij = th[i] - th[j]
@@ -335,11 +342,27 @@ def learning_rate(P: Problem, t: int) -> float:
     return P.lr0 * (1.0 - t / float(P.n_epochs))
 
 
+def batch_ranges(P: Problem):
+    """Head ranges of the B = batches_per_epoch sub-steps of an epoch: floor(n b / B) .. floor(n (b+1) / B)."""
+    B = max(1, int(P.batches_per_epoch))
+    return [(P.n * b // B, P.n * (b + 1) // B) for b in range(B)]
+
+
 def epoch(P: Problem, theta: np.ndarray, t: int):
-    """One full-batch step.  Returns (theta_next fp32, g fp64, L at theta)."""
-    L, g = loss_and_grad(P, theta, t)
-    th = _as_positions(theta)
-    return (th - learning_rate(P, t) * g).astype(np.float32), g, L
+    """One epoch.  With B = batches_per_epoch = 1: one full-batch step.  With B > 1 (a reading of the paper's
+    "approximates the expectation over heads via random sampling", Section 3.3): B sequential sub-steps, sub-step
+    b over the heads of batch_ranges()[b], each evaluated at the current theta with the cell means of the start
+    of the epoch and followed by theta <- fp32(theta - eta_t g_b).  Returns (theta_next fp32, g of the last
+    sub-step fp64, sum of the sub-steps' loss terms)."""
+    th32 = np.asarray(theta, dtype=np.float32).copy()
+    _, _, mu0 = cluster_stats(P, _as_positions(th32))
+    eta = learning_rate(P, t)
+    total, g = 0.0, np.zeros((P.n, 2))
+    for (h0, h1) in batch_ranges(P):
+        L, g = loss_and_grad(P, th32, t, mu_fixed=mu0, head_range=(h0, h1))
+        total += L
+        th32 = (_as_positions(th32) - eta * g).astype(np.float32)
+    return th32, g, total
 
 
 def inverse_rank_weights(k: int) -> np.ndarray:

@@ -19,8 +19,8 @@ class PyOracle:
     def cluster_stats(self, theta):
         return po.cluster_stats(self.P, theta)
 
-    def loss_and_grad(self, theta, t, want_grad=True, mu_fixed=None):
-        return po.loss_and_grad(self.P, theta, t, want_grad, mu_fixed)
+    def loss_and_grad(self, theta, t, want_grad=True, mu_fixed=None, head_range=None):
+        return po.loss_and_grad(self.P, theta, t, want_grad, mu_fixed, head_range)
 
     def mean_field(self, theta):
         _, p_r, mu = po.cluster_stats(self.P, np.asarray(theta, dtype=np.float64))

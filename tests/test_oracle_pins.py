@@ -449,3 +449,57 @@ def test_neighbourhood_preservation_metric():
     assert po.neighbourhood_preservation(a, a) == 1.0
     b = np.array([[3, 2, 1], [0, 2, 9], [7, 8, 9], [0, 1, 2]])
     assert abs(po.neighbourhood_preservation(a, b) - (3 + 2 + 0 + 3) / 12.0) < 1e-15
+
+
+# ---------------------------------------------------------------- minibatch epochs
+@BOTH
+def test_batch_terms_partition_the_full_loss_and_gradient(impl):
+    """The head ranges of the sub-steps partition the heads, so at a fixed theta and fixed means their loss terms
+    and gradients add up to the full ones (whatever touches a point as tail or negative lands in the batch of the
+    edge's head)."""
+    n = 40
+    kw = _random_problem(n, 41)
+    O = IMPLS[impl](**kw)
+    theta = _grid_theta(n, 41)
+    _, _, mu = O.cluster_stats(theta)
+    L, g = O.loss_and_grad(theta, 3, mu_fixed=mu)
+    cuts = [0, 7, 7, 19, 33, n]                      # includes an empty range
+    parts = [O.loss_and_grad(theta, 3, mu_fixed=mu, head_range=(a, b)) for a, b in zip(cuts[:-1], cuts[1:])]
+    assert abs(sum(p[0] for p in parts) - L) < 1e-13
+    assert np.abs(sum(p[1] for p in parts) - g).max() < 1e-13
+    # a batch only moves points its edges touch: a head outside the range that is nobody's tail or negative stays put
+    assert np.all(parts[1][1] == 0) and parts[1][0] == 0.0
+
+
+@BOTH
+def test_minibatch_epoch_is_sequential_sgd_over_head_ranges(impl):
+    """epoch() with B sub-steps equals B hand-made steps: gradient of the batch's edges at the current theta with
+    the means of the start of the epoch, then theta <- fp32(theta - eta_t g); B = 1 is the full-batch epoch."""
+    n, B, t = 30, 4, 2
+    kw = _random_problem(n, 43)
+    kw.update(n_epochs=5, lr0=0.3)
+    O1 = IMPLS[impl](**kw)
+    OB = IMPLS[impl](**kw, batches_per_epoch=B)
+    theta = _grid_theta(n, 43).astype(np.float32)
+    _, _, mu0 = O1.cluster_stats(theta)
+    eta = 0.3 * (1 - t / 5)
+    th, total = theta.copy(), 0.0
+    for b in range(B):
+        L, g = O1.loss_and_grad(th, t, mu_fixed=mu0, head_range=(n * b // B, n * (b + 1) // B))
+        total += L
+        th = (th.astype(np.float64) - eta * g).astype(np.float32)
+    th_B, g_B, L_B = OB.epoch(theta, t)
+    assert np.array_equal(th_B, th) and np.abs(g_B - g).max() < 1e-15 and abs(L_B - total) < 1e-13
+    th_1, g_1, L_1 = O1.epoch(theta, t)
+    L_full, g_full = O1.loss_and_grad(theta, t)
+    assert np.array_equal(th_1, (theta.astype(np.float64) - eta * g_full).astype(np.float32)) and abs(L_1 - L_full) < 1e-13
+    assert not np.array_equal(th_1, th_B)            # the sub-steps see the moved points
+
+
+def test_minibatch_epochs_agree_between_the_two_implementations():
+    kw = _random_problem(60, 47, s=4)
+    kw.update(n_epochs=6, lr0=0.2)
+    theta = _grid_theta(60, 47).astype(np.float32)
+    a = IMPLS["py"](**kw, batches_per_epoch=5).epoch(theta, 1)
+    b = IMPLS["c"](**kw, batches_per_epoch=5).epoch(theta, 1)
+    assert np.array_equal(a[0], b[0]) and np.abs(a[1] - b[1]).max() < 1e-12 and abs(a[2] - b[2]) < 1e-12
