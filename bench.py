@@ -102,6 +102,7 @@ def main():
     ap.add_argument("--groups", type=int, default=None, help="deal the clusters into this many groups")
     ap.add_argument("--pool", default=None, metavar="P,G",
                     help="opt-in pooled sampler: pool size and block length (e.g. 2048,4096); not the benchmark's sampler")
+    ap.add_argument("--batches", type=int, default=1, help="sub-steps per epoch (minibatch epochs); the benchmark uses 1")
     ap.add_argument("--probe", choices=["copy"], default=None,
                     help="run only the streaming-copy probe (counter calibration / practical HBM ceiling)")
     args = ap.parse_args()
@@ -134,7 +135,8 @@ def main():
     if warmup + steps > w.n_epochs:
         steps = max(1, w.n_epochs - warmup)
     mode = SCATTER_DETERMINISTIC if args.mode == "det" else SCATTER_ATOMIC
-    nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode, pool_size=w.pool_size, pool_block=w.pool_block)
+    nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode, pool_size=w.pool_size, pool_block=w.pool_block,
+               batches_per_epoch=args.batches)
     t0 = time.time()
     nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None, w.cluster_of.to(dev),
                  None if w.cluster_group is None else w.cluster_group.to(dev))
@@ -172,7 +174,7 @@ def main():
     else:
         roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s", traffic=None)
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    if args.scale == 1.0 and args.groups is None and pool is None:
+    if args.scale == 1.0 and args.groups is None and pool is None and args.batches == 1:
         roofline["traffic"] = measured_traffic(dom, args.config, args.mode)
     epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, False, mode == SCATTER_DETERMINISTIC, pool) for k in kernels
                       if k != "mean_field")
@@ -185,6 +187,7 @@ def main():
         "config": {"workload": f"{w.name}: n={n}, E={E} directed edges, |R|={R} clusters, s={s} negatives/edge, "
                                f"|M|={w.noise_count:g}, {'grouped (mean-field)' if grouped else 'no approximated cells'}",
                    "scatter_mode": args.mode,
+                   "batches_per_epoch": args.batches,
                    "sampler": "iid per edge" if pool is None else f"pooled, {pool[0]} points per block of {pool[1]} edges (opt-in variant)"},
         "edges_per_sec": E / (elapsed / steps),
         "epoch_model_gb": epoch_bytes / 1e9,

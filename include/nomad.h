@@ -49,6 +49,7 @@ extern "C" {
 #define NOMAD_SCATTER_ATOMIC 1
 
 #define NOMAD_MAX_NEG 16
+#define NOMAD_MAX_BATCHES 4096
 
 typedef struct nomad_ctx nomad_ctx; /* opaque, library-owned */
 
@@ -62,7 +63,7 @@ typedef struct {
     float lr0;                 /* eta_0, applied to g = grad(n * L): per-point units                  */
     uint64_t seed;             /* key of the counter-based negative sampler                           */
     int32_t scatter_mode;      /* NOMAD_SCATTER_DETERMINISTIC or NOMAD_SCATTER_ATOMIC                 */
-    int32_t batches_per_epoch; /* reserved, must be 1                                                 */
+    int32_t batches_per_epoch; /* B, 1..NOMAD_MAX_BATCHES: sequential sub-steps of an epoch (see nomad_epoch) */
     int32_t device;            /* HIP device ordinal                                                  */
     void* stream;              /* hipStream_t borrowed from the caller; NULL = the null stream        */
     int32_t pool_size;         /* 0: the paper's i.i.d. negatives per edge.  1..NOMAD_MAX_POOL: opt-in */
@@ -118,7 +119,11 @@ int nomad_set_embedding(nomad_ctx* ctx, const float* theta, int mem);
 /*
  * One epoch with epoch index t, 0 <= t < T: fresh negatives keyed on (seed, t, edge, slot), the
  * gradient of the sampled loss (Eq. 4 with Eq. 5-6) and the SGD step with eta_t = lr0 (1 - t/T)
- * (Section 3.4).  Enqueued on the context's stream; returns without waiting.
+ * (Section 3.4).  With batches_per_epoch = B > 1 (a reading of "approximates the expectation over heads via
+ * random sampling", Section 3.3) the epoch is B sequential sub-steps: sub-step b takes the heads
+ * floor(n b / B) .. floor(n (b+1) / B) - 1, evaluates the gradient of their edges at the current embedding with
+ * the cell means of the start of the epoch, and applies it with eta_t.  Enqueued on the context's stream;
+ * returns without waiting.
  */
 int nomad_epoch(nomad_ctx* ctx, int32_t t);
 
@@ -134,7 +139,7 @@ int nomad_get_embedding(nomad_ctx* ctx, float* out, int mem);
 
 /* ---- test hooks (same conventions; all wait for the stream) ---- */
 
-/* g = grad(n * L_t) of the most recent nomad_epoch, as it was applied.  [n*2] fp32. */
+/* g = grad(n * L_t) of the most recent nomad_epoch (of its last sub-step), as it was applied.  [n*2] fp32. */
 int nomad_get_gradient(nomad_ctx* ctx, float* out, int mem);
 
 /* Negative indices of CSR edges e_begin..e_end-1 for epoch index t: [(e_end-e_begin)*s] int32. */

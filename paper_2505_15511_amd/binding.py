@@ -113,13 +113,13 @@ class Nomad:
     """One libnomad context.  Method names are the C entry points without the prefix."""
 
     def __init__(self, n_points, n_clusters, n_neg, noise_count=0.0, n_epochs=1, lr0=1.0, seed=0,
-                 scatter_mode=SCATTER_DETERMINISTIC, device=0, stream=None, pool_size=0, pool_block=0):
+                 scatter_mode=SCATTER_DETERMINISTIC, device=0, stream=None, pool_size=0, pool_block=0, batches_per_epoch=1):
         self.lib = load_library()
         if stream is None:
             import torch
             stream = torch.cuda.current_stream(device).cuda_stream
         self.cfg = NomadConfig(C.sizeof(NomadConfig), int(n_points), int(n_clusters), int(n_neg), float(noise_count),
-                               int(n_epochs), float(lr0), int(seed), int(scatter_mode), 1, int(device),
+                               int(n_epochs), float(lr0), int(seed), int(scatter_mode), int(batches_per_epoch), int(device),
                                C.c_void_p(int(stream) if stream else None), int(pool_size), int(pool_block))
         self.n, self.R, self.s = int(n_points), int(n_clusters), int(n_neg)
         self.device = int(device)
@@ -133,7 +133,8 @@ class Nomad:
     def from_workload(cls, w, scatter_mode=SCATTER_DETERMINISTIC, device=0, **over):
         kw = dict(n_points=w.n, n_clusters=w.n_clusters, n_neg=w.n_neg, noise_count=w.noise_count,
                   n_epochs=w.n_epochs, lr0=w.lr0, seed=w.seed, scatter_mode=scatter_mode, device=device,
-                  pool_size=getattr(w, "pool_size", 0), pool_block=getattr(w, "pool_block", 0))
+                  pool_size=getattr(w, "pool_size", 0), pool_block=getattr(w, "pool_block", 0),
+                  batches_per_epoch=getattr(w, "batches_per_epoch", 1))
         kw.update(over)
         nm = cls(**kw)
         nm.set_graph(w.row_ptr, w.col_idx, w.weights, w.cluster_of, w.cluster_group)

@@ -54,6 +54,7 @@ struct nomad_ctx {
     bool binned = false;
     int n_wg = 0, bin_block = 1024;
     int pool_rounds = 0;            // > 0: the pooled edge pass runs, pool_block = 1024 * pool_rounds
+    std::vector<int64_t> batch_row, batch_edge;   // [B + 1] first head / first CSR position of every sub-step
     uint32_t n_bins = 0, max_chunks = 0;
     int tile_bits = kMaxTileBits;
     uint32_t *pool = nullptr, *chunk_prev = nullptr, *chain_head = nullptr, *chain_fill = nullptr, *wg_pool_begin = nullptr;
@@ -157,7 +158,7 @@ EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
     a.noise_count = c->noise_count; a.omega0 = c->omega0;
     a.key0 = (uint32_t)c->cfg.seed; a.key1 = (uint32_t)(c->cfg.seed >> 32); a.epoch = t;
     a.pool_size = (uint32_t)c->cfg.pool_size; a.pool_block = (uint32_t)c->cfg.pool_block;
-    a.s = c->cfg.n_neg; a.n = c->n;
+    a.s = c->cfg.n_neg; a.n = c->n; a.row_begin = 0; a.row_end = c->n;
     a.g = c->g; a.ghead = c->ghead; a.gfix = c->gfix; a.loss_partial = c->loss_partial;
     return a;
 }
@@ -181,7 +182,8 @@ void launch_edges(nomad_ctx* c, const EdgeArgs& a) {
 BinArgs bin_args(nomad_ctx* c) {
     BinArgs q{};
     q.head = c->head; q.pool = c->pool; q.chunk_prev = c->chunk_prev; q.chain_head = c->chain_head; q.chain_fill = c->chain_fill;
-    q.wg_pool_begin = c->wg_pool_begin; q.ghead = c->ghead; q.E = c->E; q.max_chunks = c->max_chunks; q.n_bins = c->n_bins;
+    q.wg_pool_begin = c->wg_pool_begin; q.ghead = c->ghead; q.E = c->E; q.e_begin = 0; q.e_end = c->E;
+    q.max_chunks = c->max_chunks; q.n_bins = c->n_bins;
     q.tile_bits = c->tile_bits; q.overflow = c->overflow;
     return q;
 }
@@ -235,8 +237,10 @@ int prepare_binned(nomad_ctx* c) {
     return NOMAD_OK;
 }
 
-void launch_edges_binned(nomad_ctx* c, const EdgeArgs& a) {
-    const BinArgs q = bin_args(c);
+void launch_edges_binned(nomad_ctx* c, const EdgeArgs& a, int64_t e_begin, int64_t e_end) {
+    BinArgs q = bin_args(c);
+    q.e_begin = e_begin;
+    q.e_end = e_end;
     const dim3 grid(c->n_wg), block(c->pool_rounds ? kPoolBlockLanes : c->bin_block);
     const size_t lds = edge_pass_lds_bytes(c);
     with_edge_pass_kernel(c, [&](EdgePassKernel kernel) { hipLaunchKernelGGL(kernel, grid, block, lds, c->stream, a, q); });
@@ -254,11 +258,13 @@ int run_means(nomad_ctx* c) {
     return NOMAD_OK;
 }
 
-int run_mean_field(nomad_ctx* c) {
-    if (!c->grouped) return NOMAD_OK;
+// mean-field sums of the heads row_begin .. row_end-1
+int run_mean_field(nomad_ctx* c, int64_t row_begin, int64_t row_end) {
+    if (!c->grouped || row_end <= row_begin) return NOMAD_OK;
     Timed tm(c, NOMAD_K_MEANFIELD);
-    hipLaunchKernelGGL(k_mean_field, dim3(blocks_for(c->n, kMeanFieldBlock * kMeanFieldHeads)), dim3(kMeanFieldBlock), 0, c->stream, c->theta, c->cluster_of,
-                       c->group_of_cluster, c->cinfo, c->group_slots, c->R, c->n, c->A, c->B);
+    hipLaunchKernelGGL(k_mean_field, dim3(blocks_for(row_end - row_begin, kMeanFieldBlock * kMeanFieldHeads)), dim3(kMeanFieldBlock), 0,
+                       c->stream, c->theta, c->cluster_of, c->group_of_cluster, c->cinfo, c->group_slots, c->R, row_begin, row_end,
+                       c->A, c->B);
     return NOMAD_OK;
 }
 
@@ -289,7 +295,7 @@ int nomad_create(const nomad_config* cfg, nomad_ctx** out) {
     if (!cfg || !out) return NOMAD_E_INVALID_ARG;
     if (cfg->struct_size != sizeof(nomad_config)) return NOMAD_E_INVALID_ARG;
     if (cfg->n_points < 1 || cfg->n_clusters < 1 || cfg->n_neg < 0 || cfg->n_neg > NOMAD_MAX_NEG || cfg->n_epochs < 1 ||
-        cfg->batches_per_epoch != 1 || !(cfg->lr0 >= 0.f) || !std::isfinite(cfg->lr0) || !std::isfinite(cfg->noise_count) ||
+        cfg->batches_per_epoch < 1 || cfg->batches_per_epoch > NOMAD_MAX_BATCHES || !(cfg->lr0 >= 0.f) || !std::isfinite(cfg->lr0) || !std::isfinite(cfg->noise_count) ||
         (cfg->scatter_mode != NOMAD_SCATTER_DETERMINISTIC && cfg->scatter_mode != NOMAD_SCATTER_ATOMIC) || cfg->device < 0)
         return NOMAD_E_INVALID_ARG;
     if (cfg->pool_size < 0 || cfg->pool_size > NOMAD_MAX_POOL || cfg->pool_block < 0 || (cfg->pool_size == 0) != (cfg->pool_block == 0))
@@ -344,6 +350,17 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
     const int64_t E = E32;
     if (E > 0 && !col_idx) { free_graph(c); return fail(c, NOMAD_E_INVALID_ARG, "col_idx is null"); }
     c->E = E;
+    {   // sub-steps of an epoch: consecutive head ranges and the CSR positions they own
+        const int B = c->cfg.batches_per_epoch;
+        c->batch_row.assign((size_t)B + 1, 0);
+        c->batch_edge.assign((size_t)B + 1, 0);
+        for (int b = 0; b <= B; ++b) {
+            c->batch_row[b] = n * (int64_t)b / B;
+            int32_t off = 0;
+            HTRY(hipMemcpy(&off, c->row_ptr + c->batch_row[b], sizeof(int32_t), hipMemcpyDeviceToHost));
+            c->batch_edge[b] = off;
+        }
+    }
     TRY(dev_alloc(c, &c->col, (size_t)E));
     if (E) HTRY(hipMemcpy(c->col, col_idx, sizeof(int32_t) * (size_t)E, in_kind(mem)));
     TRY(dev_alloc(c, &c->cluster_of, (size_t)n));
@@ -618,29 +635,40 @@ int nomad_epoch(nomad_ctx* c, int32_t t) {
     if (t < 0 || t >= c->cfg.n_epochs) return fail(c, NOMAD_E_INVALID_ARG, "epoch index %d outside 0..T-1", t);
     HIP_TRY(c, hipSetDevice(c->cfg.device));
     const int64_t n = c->n;
-    run_means(c);
-    run_mean_field(c);
-    const EdgeArgs a = edge_args(c, (uint32_t)t);
-    if (c->cfg.scatter_mode == NOMAD_SCATTER_ATOMIC) {
-        { Timed tm(c, NOMAD_K_ZERO);
-          hipLaunchKernelGGL(k_zero_f2, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->g, n); }
-        { Timed tm(c, NOMAD_K_EDGES);
-          launch_edges<kModeAtomic>(c, a); }
-    } else if (c->binned) {
-        { Timed tm(c, NOMAD_K_EDGES);
-          launch_edges_binned(c, a); }
-        { Timed tm(c, NOMAD_K_TILES);
-          hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 << c->tile_bits,
-                             c->stream, bin_args(c), (uint32_t)c->n_wg, c->g, n); }
-    } else {
-        { Timed tm(c, NOMAD_K_EDGES);
-          launch_edges<kModeDet>(c, a); }
-        { Timed tm(c, NOMAD_K_SCATTER);
-          hipLaunchKernelGGL(k_combine_fixed, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->ghead, c->gfix, c->g, n); }
-    }
+    run_means(c);   // the cell means are constants of the epoch, also across its sub-steps
     const float eta = (float)((double)c->cfg.lr0 * (1.0 - (double)t / (double)c->cfg.n_epochs));
-    { Timed tm(c, NOMAD_K_UPDATE);
-      hipLaunchKernelGGL(k_update, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->theta, c->g, eta, n); }
+    const int B = c->cfg.batches_per_epoch;
+    for (int b = 0; b < B; ++b) {
+        const int64_t r0 = c->batch_row[b], r1 = c->batch_row[b + 1], e0 = c->batch_edge[b], e1 = c->batch_edge[b + 1];
+        if (e1 == e0) {   // no edge in this sub-step: nothing moves; the stored gradient is that of the last sub-step
+            if (b == B - 1 && B > 1)
+                hipLaunchKernelGGL(k_zero_f2, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->g, n);
+            if (B > 1) continue;
+        }
+        run_mean_field(c, r0, r1);
+        EdgeArgs a = edge_args(c, (uint32_t)t);
+        a.row_begin = r0;
+        a.row_end = r1;
+        if (c->cfg.scatter_mode == NOMAD_SCATTER_ATOMIC) {
+            { Timed tm(c, NOMAD_K_ZERO);
+              hipLaunchKernelGGL(k_zero_f2, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->g, n); }
+            { Timed tm(c, NOMAD_K_EDGES);
+              launch_edges<kModeAtomic>(c, a); }
+        } else if (c->binned) {
+            { Timed tm(c, NOMAD_K_EDGES);
+              launch_edges_binned(c, a, e0, e1); }
+            { Timed tm(c, NOMAD_K_TILES);
+              hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 << c->tile_bits,
+                                 c->stream, bin_args(c), (uint32_t)c->n_wg, c->g, n); }
+        } else {
+            { Timed tm(c, NOMAD_K_EDGES);
+              launch_edges<kModeDet>(c, a); }
+            { Timed tm(c, NOMAD_K_SCATTER);
+              hipLaunchKernelGGL(k_combine_fixed, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->ghead, c->gfix, c->g, n); }
+        }
+        { Timed tm(c, NOMAD_K_UPDATE);
+          hipLaunchKernelGGL(k_update, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->theta, c->g, eta, n); }
+    }
     HIP_TRY(c, hipGetLastError());
     c->has_grad = true;
     return NOMAD_OK;
@@ -652,7 +680,7 @@ int nomad_loss(nomad_ctx* c, int32_t t_sample, double* out_host) {
     if (!out_host || t_sample < 0) return fail(c, NOMAD_E_INVALID_ARG, "null output or negative epoch index");
     HIP_TRY(c, hipSetDevice(c->cfg.device));
     run_means(c);
-    run_mean_field(c);
+    run_mean_field(c, 0, c->n);
     const EdgeArgs a = edge_args(c, (uint32_t)t_sample);
     { Timed tm(c, NOMAD_K_LOSS);
       launch_edges<kModeLoss>(c, a);
@@ -741,7 +769,7 @@ int nomad_get_mean_field(nomad_ctx* c, float* A, float* B, int mem) {
         return NOMAD_OK;
     }
     run_means(c);
-    run_mean_field(c);
+    run_mean_field(c, 0, c->n);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     HIP_TRY(c, hipMemcpy(A, c->A, sizeof(float) * (size_t)c->n, out_kind(mem)));
     HIP_TRY(c, hipMemcpy(B, c->B, sizeof(float2) * (size_t)c->n, out_kind(mem)));

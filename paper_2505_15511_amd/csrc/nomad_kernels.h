@@ -271,13 +271,15 @@ __global__ void __launch_bounds__(kMeanFieldBlock) k_mean_field(const float2* __
                                                                 const int32_t* __restrict__ cluster_of,
                                                                 const int32_t* __restrict__ group_of_cluster,
                                                                 const float4* __restrict__ cinfo, const int2* __restrict__ group_slots,
-                                                                int32_t R, int64_t n, float* __restrict__ A, float2* __restrict__ B) {
+                                                                int32_t R, int64_t i_begin, int64_t n, float* __restrict__ A,
+                                                                float2* __restrict__ B) {
     // Every wavefront needs the whole cell table.  Reading it straight from memory with wave-uniform loads makes
     // each of the n/64 wavefronts pull all |R| x 16 bytes through the scalar cache (240 GB per launch at 60 M points
     // and 16,384 cells); staged through LDS the table is read once per workgroup and broadcast to the lanes.
     __shared__ float4 cells[kMeanFieldBlock];
     // the heads of a lane are adjacent points, so that a wavefront covers 128 consecutive points (one group, usually)
-    const int64_t i0 = ((int64_t)blockIdx.x * kMeanFieldBlock + threadIdx.x) * kMeanFieldHeads;
+    // heads i_begin .. n-1 (n = one past the last head of this launch)
+    const int64_t i0 = i_begin + ((int64_t)blockIdx.x * kMeanFieldBlock + threadIdx.x) * kMeanFieldHeads;
     float2 ti[kMeanFieldHeads];
     int32_t gi[kMeanFieldHeads];
     MeanFieldSum t[kMeanFieldHeads];
@@ -340,6 +342,7 @@ struct EdgeArgs {
     uint32_t pool_size, pool_block;   // pooled sampler (0, 0 = i.i.d. negatives per edge)
     int32_t s;
     int64_t n;
+    int64_t row_begin, row_end;    // heads this launch covers (a sub-step of a minibatch epoch; else 0, n)
     uint32_t rows_per_xcd_span;    // for the block -> row remap
     // outputs
     float2* g;                     // atomic mode: accumulators of every force
@@ -549,11 +552,11 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
     constexpr int ROWS = kBlock / LPR;
     constexpr int SS = S > 0 ? S : 1;
     const uint32_t lb = xcd_contiguous_block(blockIdx.x, gridDim.x);
-    const int64_t i = (int64_t)lb * ROWS + (threadIdx.x / LPR);
+    const int64_t i = P.row_begin + (int64_t)lb * ROWS + (threadIdx.x / LPR);
     const int lane = threadIdx.x % LPR;
     float hx = 0.f, hy = 0.f;
     double lsum = 0.0;
-    if (i < P.n) {
+    if (i < P.row_end) {
         const int32_t ea = P.row_ptr[i], eb = P.row_ptr[i + 1];
         const HeadCtx h = load_head(P, i, ea, eb);
         for (int32_t e = ea + lane; e < eb; e += LPR) {
@@ -608,7 +611,7 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
     }
     hx = rowgroup_sum<LPR>(hx);
     hy = rowgroup_sum<LPR>(hy);
-    if (lane == 0 && i < P.n) {
+    if (lane == 0 && i < P.row_end) {
         if (MODE == kModeAtomic) {
             unsafeAtomicAdd(&P.g[i].x, hx);
             unsafeAtomicAdd(&P.g[i].y, hy);
@@ -656,6 +659,7 @@ struct BinArgs {
     const uint32_t* wg_pool_begin;// [n_wg + 1] each workgroup's private range of chunk ids
     float2* ghead;                // head sums of rows that lie inside one wavefront (others: records)
     int64_t E;
+    int64_t e_begin, e_end;       // CSR positions this launch covers (a sub-step of a minibatch epoch; else 0, E)
     uint32_t max_chunks;
     uint32_t n_bins;
     int tile_bits;
@@ -898,23 +902,23 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
     // The CSR positions are dealt to the workgroups in slabs of BS positions, round-robin: slab w, w + W, ...
     // (every workgroup then sends records to every tile at about the same rate, whatever the locality of the
     // graph, which keeps the chains the tile pass walks equally long).
-    const int64_t n_slabs = (Q.E + BS - 1) / BS;
+    const int64_t n_slabs = (Q.e_end - Q.e_begin + BS - 1) / BS;
     const int64_t stride = (int64_t)W * BS;
     // Software pipeline over rounds: (head, tail) indices are read two rounds ahead, the embedding rows
     // one round ahead.
     EdgeFetch<S, true> f;
     int32_t i_next = 0, j_next = 0;
     {
-        const int64_t e0 = (int64_t)w * BS + tid, e1 = e0 + stride;
+        const int64_t e0 = Q.e_begin + (int64_t)w * BS + tid, e1 = e0 + stride;
         int32_t i0 = 0, j0 = 0;
-        if (e0 < Q.E) { i0 = Q.head[e0]; j0 = P.col[e0]; }
-        if (e1 < Q.E) { i_next = Q.head[e1]; j_next = P.col[e1]; }
-        issue_edge<S, true>(P, e0 < Q.E, (int32_t)e0, i0, j0, f);
+        if (e0 < Q.e_end) { i0 = Q.head[e0]; j0 = P.col[e0]; }
+        if (e1 < Q.e_end) { i_next = Q.head[e1]; j_next = P.col[e1]; }
+        issue_edge<S, true>(P, e0 < Q.e_end, (int32_t)e0, i0, j0, f);
     }
     for (int64_t slab = w; slab < n_slabs; slab += W) {
         // one edge per lane; records: slot 0 the tail (force -a d_ij), slots 1..S the negatives
-        const int64_t e64 = slab * BS + tid;
-        const int64_t e_end = min((slab + 1) * BS, Q.E);
+        const int64_t e64 = Q.e_begin + slab * BS + tid;
+        const int64_t e_end = min(Q.e_begin + (slab + 1) * BS, Q.e_end);
         const bool has = f.has;
         const int32_t i = f.i, ea = f.ea, eb = f.eb;
         bool valid[NR];
@@ -936,8 +940,8 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
         {
             const int64_t e1 = e64 + stride, e2 = e1 + stride;
             const int32_t i1 = i_next, j1 = j_next;
-            if (e2 < Q.E) { i_next = Q.head[e2]; j_next = P.col[e2]; }
-            issue_edge<S, true>(P, e1 < Q.E, (int32_t)e1, i1, j1, f);
+            if (e2 < Q.e_end) { i_next = Q.head[e2]; j_next = P.col[e2]; }
+            issue_edge<S, true>(P, e1 < Q.e_end, (int32_t)e1, i1, j1, f);
         }
         valid[S + 1] = reduce_head_sums(Q, has, i, ea, eb, e64, e_end, hx, hy);
         dst_pt[S + 1] = valid[S + 1] ? (uint32_t)i : 0u;
@@ -988,8 +992,10 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
     const int tid = threadIdx.x;
     const uint32_t W = gridDim.x, w = blockIdx.x;
     constexpr int64_t G = (int64_t)BS * ROUNDS;                       // = P.pool_block
-    // blocks are dealt to the workgroups round-robin: block w, w + W, ...
-    const int64_t n_blocks = (Q.E + G - 1) / G;
+    // the blocks that meet this launch's positions are dealt to the workgroups round-robin: first_block + w, + W, ...
+    // (blocks are counted from CSR position 0 whatever the launch covers: a block's pool does not depend on it)
+    const int64_t first_block = Q.e_begin / G;
+    const int64_t n_blocks = (Q.e_end + G - 1) / G;   // one past the last block
     const uint32_t pool_end = min(Q.wg_pool_begin[w + 1], Q.max_chunks);
     init_bin_lds<BS>(L);
     if (tid == 0) pool_cursor = Q.wg_pool_begin[w];
@@ -1010,21 +1016,23 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
                 if (u0 + k < PS) { next_pt[k] = __umulhi(wd[k], (uint32_t)P.n); next_th[k] = P.theta[next_pt[k]]; }
         }
     };
-    fetch_pool(w);
+    fetch_pool(first_block + w);
     // edge pipeline as in k_edges_binned; the position after the last one of a block is the first of this
     // workgroup's next block
     auto next_position = [&](int64_t e) { return (e + BS) % G < BS ? e + BS + (int64_t)(W - 1) * G : e + BS; };
     EdgeFetch<S, false> f;
     int32_t i_next = 0, j_next = 0;
     {
-        const int64_t e0 = (int64_t)w * G + tid, e1 = next_position(e0);
+        auto covered = [&](int64_t e) { return e >= Q.e_begin && e < Q.e_end; };
+        const int64_t e0 = (first_block + w) * G + tid, e1 = next_position(e0);
         int32_t i0 = 0, j0 = 0;
-        if (e0 < Q.E) { i0 = Q.head[e0]; j0 = P.col[e0]; }
-        if (e1 < Q.E) { i_next = Q.head[e1]; j_next = P.col[e1]; }
-        issue_edge<S, false>(P, e0 < Q.E, (int32_t)e0, i0, j0, f);
+        if (covered(e0)) { i0 = Q.head[e0]; j0 = P.col[e0]; }
+        if (covered(e1)) { i_next = Q.head[e1]; j_next = P.col[e1]; }
+        issue_edge<S, false>(P, covered(e0), (int32_t)e0, i0, j0, f);
     }
-    for (int64_t blk = w; blk < n_blocks; blk += W) {
-        const int64_t e_end = min((blk + 1) * G, Q.E);
+    auto covered = [&](int64_t e) { return e >= Q.e_begin && e < Q.e_end; };
+    for (int64_t blk = first_block + w; blk < n_blocks; blk += W) {
+        const int64_t e_end = min((blk + 1) * G, Q.e_end);
         // ---- this block's pool into LDS, the next block's pool into flight
 #pragma unroll
         for (int k = 0; k < NP; ++k) {
@@ -1070,8 +1078,8 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
             {
                 const int64_t e1 = next_position(e64), e2 = next_position(e1);
                 const int32_t i1 = i_next, j1 = j_next;
-                if (e2 < Q.E) { i_next = Q.head[e2]; j_next = P.col[e2]; }
-                issue_edge<S, false>(P, e1 < Q.E, (int32_t)e1, i1, j1, f);
+                if (covered(e2)) { i_next = Q.head[e2]; j_next = P.col[e2]; }
+                issue_edge<S, false>(P, covered(e1), (int32_t)e1, i1, j1, f);
             }
             valid[ROUNDS + r] = reduce_head_sums(Q, has, i, ea, eb, e64, e_end, hx, hy);
             dst_pt[ROUNDS + r] = valid[ROUNDS + r] ? (uint32_t)i : 0u;
@@ -1102,37 +1110,30 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
 
 // private chunk-id range of each workgroup: enough for every record its slabs can emit (s+1 per
 // position, plus at most two partial head sums per wavefront and round), plus one partly filled chunk
-// per tile (one thread: W is a few hundred)
+// per tile.  The same bound for every workgroup, valid for a launch over any sub-range of the positions.
 __global__ void k_wg_pools(int64_t E, int W, int records_per_edge, int block, uint32_t n_bins, uint32_t* __restrict__ wg_pool_begin,
                            unsigned long long* __restrict__ total) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     const uint64_t n_slabs = (uint64_t)((E + block - 1) / block);
-    uint64_t run = 0;
-    for (int w = 0; w < W; ++w) {
-        wg_pool_begin[w] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
-        const uint64_t rounds = n_slabs / W + ((uint64_t)w < n_slabs % W ? 1 : 0);   // slabs w, w + W, ...
-        const uint64_t records = rounds * ((uint64_t)block * records_per_edge + 2 * (block / 64));
-        run += records / kChunk + n_bins + 1;
-    }
-    wg_pool_begin[W] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
-    *total = run;
+    const uint64_t rounds = (n_slabs + W - 1) / W;   // slabs w, w + W, ...
+    const uint64_t records = rounds * ((uint64_t)block * records_per_edge + 2 * (block / 64));
+    const uint64_t per_wg = records / kChunk + n_bins + 1;
+    for (int w = 0; w <= W; ++w) wg_pool_begin[w] = (uint32_t)min(per_wg * (uint64_t)w, (uint64_t)0xFFFFFFFFull);
+    *total = per_wg * (uint64_t)W;
 }
 
 // the same bound for the pooled edge pass: workgroups own whole blocks of `block_edges` positions; records per
-// block = one tail per edge, two partial head sums per wavefront and round, one per pool entry
+// block = one tail per edge, two partial head sums per wavefront and round, one per pool entry.  A sub-range of
+// the positions may cut one more block than the full range has.
 __global__ void k_wg_pools_pooled(int64_t E, int W, int64_t block_edges, uint32_t pool_size, uint32_t n_bins,
                                   uint32_t* __restrict__ wg_pool_begin, unsigned long long* __restrict__ total) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
-    const int64_t n_blocks = (E + block_edges - 1) / block_edges;
+    const uint64_t n_blocks = (uint64_t)((E + block_edges - 1) / block_edges) + 1;
     const uint64_t per_block = (uint64_t)block_edges + 2 * (kPoolBlockLanes / 64) * (uint64_t)(block_edges / kPoolBlockLanes) + pool_size;
-    uint64_t run = 0;
-    for (int w = 0; w < W; ++w) {
-        wg_pool_begin[w] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
-        const uint64_t blocks = (uint64_t)(n_blocks / W + ((int64_t)w < n_blocks % W ? 1 : 0));   // blocks w, w + W, ...
-        run += blocks * per_block / kChunk + n_bins + 1;
-    }
-    wg_pool_begin[W] = (uint32_t)min(run, (uint64_t)0xFFFFFFFFull);
-    *total = run;
+    const uint64_t blocks = (n_blocks + W - 1) / W;   // blocks first + w, first + w + W, ...
+    const uint64_t per_wg = blocks * per_block / kChunk + n_bins + 1;
+    for (int w = 0; w <= W; ++w) wg_pool_begin[w] = (uint32_t)min(per_wg * (uint64_t)w, (uint64_t)0xFFFFFFFFull);
+    *total = per_wg * (uint64_t)W;
 }
 
 // head[e] = row of CSR position e (one thread per row)

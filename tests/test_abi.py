@@ -54,7 +54,8 @@ def test_argument_errors_before_any_device_work(lib):
     assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1
     cfg.struct_size = C.sizeof(binding.NomadConfig)
     for field, bad in (("n_points", 0), ("n_clusters", 0), ("n_neg", 17), ("n_neg", -1), ("n_epochs", 0),
-                       ("scatter_mode", 2), ("batches_per_epoch", 2), ("lr0", float("nan")), ("n_clusters", 11)):
+                       ("scatter_mode", 2), ("batches_per_epoch", 0), ("batches_per_epoch", 4097), ("lr0", float("nan")),
+                       ("n_clusters", 11), ("pool_size", 4097), ("pool_size", 64)):
         good = getattr(cfg, field)
         setattr(cfg, field, bad)
         assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1, field

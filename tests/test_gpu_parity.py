@@ -54,7 +54,8 @@ def small_random(seed, n=3000, R=12, groups=True, weights=True, contiguous=False
 
 def make_nomad(d, mode):
     nm = Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
-               pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0))
+               pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0),
+               batches_per_epoch=d.get("batches_per_epoch", 1))
     nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
     nm.set_embedding(d["theta0"])
     return nm
@@ -284,6 +285,51 @@ def test_pooled_sampler_is_bit_reproducible_and_needs_one_population():
     with pytest.raises(NomadError) as ei:
         make_nomad(g, SCATTER_DETERMINISTIC)
     assert ei.value.code == -1
+
+
+# ------------------------------------------------------------------ minibatch epochs
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("case,B,pool", [("config1", 3, None), ("config3@0.05", 7, None), ("random-groups", 4, None),
+                                         ("skewed", 5, None), ("config3@0.05", 6, (2048, 4096)), ("skewed", 50, (64, 1024))])
+def test_minibatch_epoch_matches_the_oracle(case, B, pool, mode):
+    """An epoch of B sequential sub-steps over head ranges: embedding after the epoch, gradient of the last
+    sub-step, loss after it; then a second epoch from the GPU's embedding."""
+    d = dict(skewed_degree_graph(8) if case == "skewed" else _case(case))
+    d["batches_per_epoch"] = B
+    if pool:
+        d["pool_size"], d["pool_block"] = pool
+    O = c_oracle.COracle(**d)
+    th1, g_ref, _ = O.epoch(d["theta0"], 0)
+    L_ref, _ = O.loss_and_grad(th1, 1, want_grad=False)
+    with make_nomad(d, mode) as nm:
+        nm.epoch(0)
+        g, th, L = nm.get_gradient(), nm.get_embedding(), nm.loss(1)
+        th2_ref, g2_ref, _ = O.epoch(th, 1)
+        nm.epoch(1)
+        g2, th2 = nm.get_gradient(), nm.get_embedding()
+    scale = max(np.abs(g_ref).max(), 1e-30)
+    note(f"  minibatch {case} B={B} pool={pool} mode={mode}: last-step grad err {np.abs(g - g_ref).max() / scale:.2e}, "
+         f"theta err {np.abs(th - th1).max():.2e}")
+    # the sub-steps compound fp32 differences of the earlier ones: compare against the size of a full-epoch gradient
+    _, g_full = c_oracle.COracle(**{**d, "batches_per_epoch": 1}).loss_and_grad(d["theta0"], 0)
+    assert np.abs(g - g_ref).max() < GRAD_TOL * max(np.abs(g_full).max(), scale)
+    assert np.abs(th - th1).max() < 1e-5 * max(1.0, np.abs(th1).max())
+    assert abs(L - L_ref) < LOSS_TOL * abs(L_ref)
+    assert np.abs(th2 - th2_ref).max() < 1e-5 * max(1.0, np.abs(th2_ref).max())
+    assert np.abs(g2 - g2_ref).max() < GRAD_TOL * max(np.abs(g_full).max(), np.abs(g2_ref).max())
+
+
+def test_minibatch_epochs_are_bit_reproducible_and_one_batch_is_the_plain_epoch():
+    d = dict(workload(3, 0.05).numpy())
+    runs = []
+    for B in (1, 1, 9, 9):
+        d["batches_per_epoch"] = B
+        with make_nomad(d, SCATTER_DETERMINISTIC) as nm:
+            for t in range(3):
+                nm.epoch(t)
+            runs.append(nm.get_embedding())
+    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[2], runs[3])
+    assert not np.array_equal(runs[0], runs[2])
 
 
 # ------------------------------------------------------------------ degenerate and edge cases
