@@ -4,10 +4,13 @@
 // (Eq. 1), ij = directed kNN edge with head i and tail j, m = sampled negative, mu_r / p_r = mean
 // and mass of cell r, |M| = noise-sample count, s = negatives drawn per edge.
 //
-// Mapping: a *row group* of LPR adjacent lanes walks the CSR row of one head i, LPR edges at a
-// time, so neighbour indices are read as contiguous 4*LPR-byte runs and consecutive row groups
-// read consecutive runs.  Head-side sums are reduced inside the row group with a fixed xor
-// butterfly, which makes them independent of scheduling.
+// Two mappings of edges to lanes:
+//   k_edges_binned / k_edges_pooled (the deterministic epoch): one directed edge per lane, consecutive
+//     lanes on consecutive CSR positions; forces to tails and negatives leave as records binned by
+//     destination tile; head sums are segmented scans in lane order.
+//   k_edges (atomic mode, the loss, and the fallback without binning): a *row group* of LPR adjacent
+//     lanes walks the CSR row of one head i, LPR edges at a time; head sums are reduced inside the
+//     row group with a fixed xor butterfly.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -343,7 +346,6 @@ struct EdgeArgs {
     int32_t s;
     int64_t n;
     int64_t row_begin, row_end;    // heads this launch covers (a sub-step of a minibatch epoch; else 0, n)
-    uint32_t rows_per_xcd_span;    // for the block -> row remap
     // outputs
     float2* g;                     // atomic mode: accumulators of every force
     float2* ghead;                 // deterministic mode: head-side sums
