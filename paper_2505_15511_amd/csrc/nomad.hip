@@ -18,7 +18,7 @@
 using namespace nomad;
 
 struct KernelTimer {
-    std::vector<hipEvent_t> begin, end;
+    std::vector<hipEvent_t> begin, end;   // events borrowed from the context's pool
 };
 
 struct nomad_ctx {
@@ -66,6 +66,8 @@ struct nomad_ctx {
     // timing
     bool profiling = false;
     KernelTimer timers[NOMAD_K_COUNT];
+    std::vector<hipEvent_t> event_pool;   // created when timing is switched on, so that a timed launch only records
+    size_t event_next = 0;
 };
 
 namespace {
@@ -124,12 +126,27 @@ hipMemcpyKind out_kind(int mem) { return mem == NOMAD_DEVICE ? hipMemcpyDeviceTo
 
 inline uint32_t blocks_for(int64_t items, int per_block = kBlock) { return (uint32_t)((items + per_block - 1) / per_block); }
 
+bool grow_event_pool(nomad_ctx* c, size_t count) {
+    for (size_t k = 0; k < count; ++k) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return false;
+        c->event_pool.push_back(e);
+    }
+    return true;
+}
+
+hipEvent_t take_event(nomad_ctx* c) {
+    if (c->event_next == c->event_pool.size() && !grow_event_pool(c, 1024)) return nullptr;
+    return c->event_pool[c->event_next++];
+}
+
 struct Timed {  // records a begin/end event pair around one launch when timing is on
     nomad_ctx* c; int kind; hipEvent_t e1 = nullptr;
     Timed(nomad_ctx* ctx, int k) : c(ctx), kind(k) {
         if (!c->profiling) return;
-        hipEvent_t e0 = nullptr;
-        if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { e1 = nullptr; return; }
+        hipEvent_t e0 = take_event(c);
+        e1 = take_event(c);
+        if (!e0 || !e1) { e1 = nullptr; return; }
         (void)hipEventRecord(e0, c->stream);
         c->timers[kind].begin.push_back(e0);
     }
@@ -142,11 +159,16 @@ struct Timed {  // records a begin/end event pair around one launch when timing 
 
 void clear_timers(nomad_ctx* c) {
     for (auto& t : c->timers) {
-        for (auto e : t.begin) (void)hipEventDestroy(e);
-        for (auto e : t.end) (void)hipEventDestroy(e);
         t.begin.clear();
         t.end.clear();
     }
+    c->event_next = 0;
+}
+
+void destroy_event_pool(nomad_ctx* c) {
+    clear_timers(c);
+    for (auto e : c->event_pool) (void)hipEventDestroy(e);
+    c->event_pool.clear();
 }
 
 EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
@@ -318,7 +340,7 @@ void nomad_destroy(nomad_ctx* c) {
     if (!c) return;
     (void)hipSetDevice(c->cfg.device);
     (void)hipStreamSynchronize(c->stream);
-    clear_timers(c);
+    destroy_event_pool(c);
     free_graph(c);
     delete c;
 }
@@ -781,6 +803,7 @@ int nomad_profile(nomad_ctx* c, int enable) {
     HIP_TRY(c, hipSetDevice(c->cfg.device));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     clear_timers(c);
+    if (enable && c->event_pool.empty() && !grow_event_pool(c, 4096)) return fail(c, NOMAD_E_HIP, "hipEventCreate failed");
     c->profiling = enable != 0;
     return NOMAD_OK;
 }
