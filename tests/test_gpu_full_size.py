@@ -124,7 +124,7 @@ def test_config4_one_epoch_and_mid_run_against_the_oracle():
         assert err < GRAD_TOL
 
 
-@pytest.mark.parametrize("scale", [0.1])
+@pytest.mark.parametrize("scale", [0.1, 1.0])
 def test_config5_sampled_gradient_rows(scale):
     """Config 5's shape (every cluster its own group, s = 2, |M| = 5, k = 10) at a size whose full
     mean-field sum the host cannot afford: gradient rows of sampled points, each computed by the
@@ -134,7 +134,7 @@ def test_config5_sampled_gradient_rows(scale):
     d = w.numpy()
     O = c_oracle.COracle(**d)
     rng = np.random.default_rng(5)
-    pts = np.unique(np.concatenate([rng.choice(w.n, 1500, replace=False), [0, w.n - 1]]))
+    pts = np.unique(np.concatenate([rng.choice(w.n, 1500 if scale < 1 else 400, replace=False), [0, w.n - 1]]))
     with device_nomad(w) as nm:
         E = nm.num_edges()
         assert np.array_equal(nm.get_negatives(1, E // 2, E // 2 + 100000), O.negatives(1, E // 2, E // 2 + 100000))
