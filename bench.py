@@ -40,8 +40,8 @@ def algorithmic_bytes(kernel, n, E, s, R, grouped, weighted, deterministic, pool
         else:
             negatives = (8 + 8) * s * E          # theta_m read, the negatives' gradient contributions
         return per_edge * E + negatives + (4 + 8 + 8 + mf) * n   # row_ptr, theta_i, head gradient, [A,B]
-    if kernel == "tiles":                        # accumulation of the binned forces: implementation traffic,
-        return 8 * n                             # algorithmically only the per-point result
+    if kernel == "tiles":                        # accumulation of the binned forces (implementation traffic, not counted)
+        return 24 * n                            # + the SGD step it takes: theta read and written, g written
     if kernel == "scatter":                      # fallback: combine of the fixed-point sums
         return (8 + 16 + 8) * n
     if kernel == "update":

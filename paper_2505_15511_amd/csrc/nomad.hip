@@ -657,7 +657,7 @@ int nomad_epoch(nomad_ctx* c, int32_t t) {
     if (t < 0 || t >= c->cfg.n_epochs) return fail(c, NOMAD_E_INVALID_ARG, "epoch index %d outside 0..T-1", t);
     HIP_TRY(c, hipSetDevice(c->cfg.device));
     const int64_t n = c->n;
-    run_means(c);   // the cell means are constants of the epoch, also across its sub-steps
+    if (c->grouped) run_means(c);   // constants of the epoch, also across its sub-steps; unused when no cell is approximated
     const float eta = (float)((double)c->cfg.lr0 * (1.0 - (double)t / (double)c->cfg.n_epochs));
     const int B = c->cfg.batches_per_epoch;
     for (int b = 0; b < B; ++b) {
@@ -671,17 +671,19 @@ int nomad_epoch(nomad_ctx* c, int32_t t) {
         EdgeArgs a = edge_args(c, (uint32_t)t);
         a.row_begin = r0;
         a.row_end = r1;
+        if (c->cfg.scatter_mode == NOMAD_SCATTER_DETERMINISTIC && c->binned) {
+            { Timed tm(c, NOMAD_K_EDGES);
+              launch_edges_binned(c, a, e0, e1); }
+            { Timed tm(c, NOMAD_K_TILES);   // accumulates the records of every tile and takes the SGD step for its points
+              hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 << c->tile_bits,
+                                 c->stream, bin_args(c), (uint32_t)c->n_wg, c->g, n, c->theta, eta); }
+            continue;
+        }
         if (c->cfg.scatter_mode == NOMAD_SCATTER_ATOMIC) {
             { Timed tm(c, NOMAD_K_ZERO);
               hipLaunchKernelGGL(k_zero_f2, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->g, n); }
             { Timed tm(c, NOMAD_K_EDGES);
               launch_edges<kModeAtomic>(c, a); }
-        } else if (c->binned) {
-            { Timed tm(c, NOMAD_K_EDGES);
-              launch_edges_binned(c, a, e0, e1); }
-            { Timed tm(c, NOMAD_K_TILES);
-              hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 << c->tile_bits,
-                                 c->stream, bin_args(c), (uint32_t)c->n_wg, c->g, n); }
         } else {
             { Timed tm(c, NOMAD_K_EDGES);
               launch_edges<kModeDet>(c, a); }

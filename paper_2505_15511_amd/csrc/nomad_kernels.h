@@ -1145,7 +1145,10 @@ __global__ void __launch_bounds__(kBlock) k_edge_heads(const int32_t* __restrict
     for (int32_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) head[e] = (int32_t)i;
 }
 
-__global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const BinArgs Q, uint32_t n_wg, float2* __restrict__ g, int64_t n) {
+// With `theta` given it also takes the SGD step of Section 3.4 for its points, theta <- theta - eta g (the
+// edge pass that read theta has finished by then).
+__global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const BinArgs Q, uint32_t n_wg, float2* __restrict__ g, int64_t n,
+                                                              float2* __restrict__ theta, float eta) {
     extern __shared__ unsigned long long acc[];   // [2 << tile_bits]
     constexpr int kPerLane = kChunk / 64;         // records one lane takes from a full chunk
     constexpr int kBatch = 8;                     // loads in flight per lane
@@ -1187,8 +1190,15 @@ __global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const BinArgs Q, 
     for (int l = threadIdx.x; l < tile && p0 + l < n; l += kBinBlock) {
         const float2 hd = Q.ghead[p0 + l];
         Q.ghead[p0 + l] = make_float2(0.f, 0.f);   // consumed: rows that hand their head sum on as records rely on this
-        g[p0 + l] = make_float2((float)((double)hd.x + (double)(long long)acc[2 * l] * kFixInv),
-                                (float)((double)hd.y + (double)(long long)acc[2 * l + 1] * kFixInv));
+        const float2 gi = make_float2((float)((double)hd.x + (double)(long long)acc[2 * l] * kFixInv),
+                                      (float)((double)hd.y + (double)(long long)acc[2 * l + 1] * kFixInv));
+        g[p0 + l] = gi;
+        if (theta) {
+            float2 t = theta[p0 + l];
+            t.x = fmaf(-eta, gi.x, t.x);
+            t.y = fmaf(-eta, gi.y, t.y);
+            theta[p0 + l] = t;
+        }
     }
 }
 
