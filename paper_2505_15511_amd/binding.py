@@ -50,6 +50,9 @@ def load_library():
     if not os.path.exists(_build.LIB_PATH):
         raise RuntimeError(f"{_build.LIB_PATH} is missing: build the HIP library first "
                            "(python -c 'import __graft_entry__ as g; g.build()'); there is no fallback path")
+    # torch (the harness's source of device memory and streams) brings its own copy of the HIP runtime: load it
+    # first, so that this process ends up with one runtime and libnomad.so binds to the one torch allocates with
+    import torch  # noqa: F401
     lib = C.CDLL(_build.LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     lib.nomad_create.argtypes = [C.POINTER(NomadConfig), C.POINTER(vp)]

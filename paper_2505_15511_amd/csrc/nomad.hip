@@ -627,6 +627,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         if (!c->binned) {
             TRY(dev_alloc(c, &c->gfix, (size_t)n * 2));
             hipLaunchKernelGGL(k_zero_u64, dim3(blocks_for(n * 2)), dim3(kBlock), 0, st, c->gfix, n * 2);
+            hipLaunchKernelGGL(k_zero_f2, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->ghead, n);
         }
     }
     HTRY(hipStreamSynchronize(st));

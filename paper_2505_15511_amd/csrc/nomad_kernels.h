@@ -416,13 +416,14 @@ __device__ __forceinline__ void edge_math(const HeadCtx& h, float pe, float2 tj,
         qm[k] = cauchy(o.rx[k], o.ry[k]);
         qsum += qm[k];
     }
-    const float Se = qij + h.MA + h.omega * qsum;
+    const float rest = h.MA + h.omega * qsum;   // S_e - q_ij: the noise part of the denominator
+    const float Se = qij + rest;
     if (LOSS) {
         o.log_term = pe * logf(Se / qij);   // -log q + log S = log(S (1 + d^2))
         return;
     }
     const float inv_S = __builtin_amdgcn_rcpf(Se);   // 1 ulp; S_e >= q_ij > 0
-    o.a = 2.0f * pe * qij * (1.0f - qij * inv_S);
+    o.a = 2.0f * pe * qij * rest * inv_S;       // 1 - q_ij / S_e = (S_e - q_ij) / S_e without the cancellation
     float fx = o.a * o.dx, fy = o.a * o.dy;
     const float bscale = 2.0f * pe * h.omega * inv_S;
 #pragma unroll
@@ -520,10 +521,11 @@ __device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const Head
         const float2 tm = P.theta[negative_of_slot(P, h.pop, e, k)];
         qsum += cauchy(h.ti.x - tm.x, h.ti.y - tm.y);
     }
-    const float Se = qij + h.MA + h.omega * qsum;
+    const float rest = h.MA + h.omega * qsum;   // S_e - q_ij
+    const float Se = qij + rest;
     if (LOSS) { log_term = pe * logf(Se / qij); return; }
     const float inv_S = __builtin_amdgcn_rcpf(Se);   // 1 ulp; S_e >= q_ij > 0
-    a = 2.0f * pe * qij * (1.0f - qij * inv_S);
+    a = 2.0f * pe * qij * rest * inv_S;
     float fx = a * dx, fy = a * dy;
     const float bscale = 2.0f * pe * h.omega * inv_S;
     for (int k = 0; k < s; ++k) {
@@ -1219,13 +1221,13 @@ __global__ void __launch_bounds__(kBlock) k_loss_finish(const double* __restrict
 }
 
 // ------------------------------------------------------------------ K4 (fallback): combine
-// g = head sum + fixed-point sum of tail and negative forces; clears the accumulators for the
-// next epoch.
-__global__ void __launch_bounds__(kBlock) k_combine_fixed(const float2* __restrict__ ghead, unsigned long long* __restrict__ gfix,
+// g = head sum + fixed-point sum of tail and negative forces; clears both for the next launch.
+__global__ void __launch_bounds__(kBlock) k_combine_fixed(float2* __restrict__ ghead, unsigned long long* __restrict__ gfix,
                                                           float2* __restrict__ g, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const float2 h = ghead[i];
+    ghead[i] = make_float2(0.f, 0.f);   // consumed: a sub-step over other heads must not see this one again
     const double sx = (double)(long long)gfix[2 * i] * kFixInv, sy = (double)(long long)gfix[2 * i + 1] * kFixInv;
     gfix[2 * i] = 0ull;
     gfix[2 * i + 1] = 0ull;

@@ -1,0 +1,68 @@
+"""Seeded random problems of many shapes through the C ABI against the C oracle: negatives bit for bit, gradient
+and embedding after one epoch.  Every case is generated from its seed alone."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import c_oracle
+from paper_2505_15511_amd import Nomad, SCATTER_ATOMIC, SCATTER_DETERMINISTIC
+
+pytestmark = pytest.mark.gpu
+GRAD_TOL = 1e-5
+
+
+def random_case(seed):
+    """Directed graph with a skewed degree distribution (isolated points, rows of one edge, a few hubs), optional
+    weights, clusters in arbitrary point order, optional groups, any s, optional pooled sampler and minibatches."""
+    rng = np.random.default_rng(seed)
+    n = int(rng.choice([1, 2, 3, 17, 64, 65, 300, 1025, 4000, 9000]))
+    R = int(min(n, rng.choice([1, 2, 5, 31])))
+    deg = np.minimum(rng.geometric(0.08, n), max(n - 1, 0))
+    deg[rng.random(n) < 0.1] = 0
+    if n > 500:
+        deg[rng.choice(n, 2, replace=False)] = min(n - 1, int(rng.integers(200, 3000)))
+    cols = []
+    for i in range(n):
+        c = rng.choice(n - 1, int(deg[i]), replace=False) if deg[i] else np.zeros(0, np.int64)
+        c[c >= i] += 1
+        cols.append(np.sort(c))
+    row_ptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    col = (np.concatenate(cols) if n else np.zeros(0)).astype(np.int32)
+    s = int(rng.choice([0, 1, 2, 3, 5, 8, 11]))
+    pooled = bool(rng.random() < 0.4) and s > 0
+    grouped = bool(rng.random() < 0.4) and R > 1 and not pooled
+    d = dict(n=n, row_ptr=row_ptr, col_idx=col,
+             weights=rng.uniform(0.1, 3.0, len(col)).astype(np.float32) if rng.random() < 0.4 else None,
+             cluster_of=(rng.integers(0, R, n) if rng.random() < 0.5 else np.sort(rng.integers(0, R, n))).astype(np.int32),
+             n_clusters=R, cluster_group=rng.integers(0, max(2, R // 2), R).astype(np.int32) if grouped else None,
+             theta0=(rng.normal(size=(n, 2)) * rng.choice([0.01, 1.0, 30.0])).astype(np.float32), n_neg=s,
+             noise_count=float(rng.choice([0.0, 2.5, 7.0])), n_epochs=5, lr0=float(rng.choice([0.05, 0.5])), seed=int(seed) * 7919 + 1,
+             batches_per_epoch=int(rng.choice([1, 1, 2, 5])))
+    if pooled:
+        d["pool_size"], d["pool_block"] = [(1, 1024), (37, 50), (512, 1024), (2048, 4096), (4096, 2048), (300, 8192)][int(rng.integers(6))]
+    return d
+
+
+@pytest.mark.parametrize("mode", [pytest.param(SCATTER_DETERMINISTIC, id="det"), pytest.param(SCATTER_ATOMIC, id="atomic")])
+@pytest.mark.parametrize("seed", range(int(os.environ.get("NOMAD_RANDOM_CASES_FROM", 0)), int(os.environ.get("NOMAD_RANDOM_CASES_TO", 40))))
+def test_random_case_against_the_oracle(seed, mode):
+    d = random_case(seed)
+    O = c_oracle.COracle(**d)
+    th_ref, g_ref, _ = O.epoch(d["theta0"], 1)
+    with Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
+               pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0), batches_per_epoch=d["batches_per_epoch"]) as nm:
+        nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
+        nm.set_embedding(d["theta0"])
+        if d["n_neg"] and len(d["col_idx"]):
+            assert np.array_equal(nm.get_negatives(1), O.negatives(1))
+        nm.epoch(1)
+        g, th = nm.get_gradient(), nm.get_embedding()
+    _, g_full = c_oracle.COracle(**{**d, "batches_per_epoch": 1}).loss_and_grad(d["theta0"], 1)
+    # A gradient that vanishes by cancellation (a negative that coincides with the tail, say) leaves fp32 residue of
+    # the size of the cancelled forces, each at most p(j|i) <= 1: the error is measured against at least 1e-2.
+    scale = max(np.abs(g_full).max(), np.abs(g_ref).max(), 1e-2)
+    print(f"  seed {seed}: n={d['n']} E={len(d['col_idx'])} s={d['n_neg']} B={d['batches_per_epoch']} pool={d.get('pool_size', 0)} "
+          f"groups={d['cluster_group'] is not None} grad err {np.abs(g - g_ref).max() / scale:.2e}", flush=True)
+    assert np.abs(g - g_ref).max() <= GRAD_TOL * scale
+    assert np.abs(th - th_ref).max() <= 1e-5 * max(1.0, np.abs(th_ref).max())
