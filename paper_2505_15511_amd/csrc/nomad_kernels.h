@@ -24,6 +24,14 @@ constexpr int kBlock = 256;
 constexpr float kFixScale = 68719476736.0f;          // 2^36
 constexpr double kFixInv = 1.0 / 68719476736.0;
 
+// v * 2^36 rounded to the nearest integer (ties to even) as a 64-bit two's complement number, for |v| < 2^15.
+// Adding 1.5 * 2^52 in double precision leaves that integer in the low mantissa bits: three instructions
+// where the float -> int64 conversion takes a dozen.
+__device__ __forceinline__ unsigned long long to_fixed(float v) {
+    const double d = fma((double)v, 68719476736.0, 6755399441055744.0);
+    return (unsigned long long)(__double_as_longlong(d) - 0x4338000000000000LL);
+}
+
 // ------------------------------------------------------------------ sampler
 // Philox4x32 with 10 rounds (Salmon et al., SC'11): the counter-based generator behind the
 // uniform noise distribution over tails (Section 3.3).  Counter = (edge lo, edge hi, epoch,
@@ -544,8 +552,8 @@ __device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const Head
 }
 
 __device__ __forceinline__ void add_fixed(unsigned long long* gfix, int64_t m, float rx, float ry) {
-    atomicAdd(&gfix[2 * m], (unsigned long long)__float2ll_rn(rx * kFixScale));
-    atomicAdd(&gfix[2 * m + 1], (unsigned long long)__float2ll_rn(ry * kFixScale));
+    atomicAdd(&gfix[2 * m], to_fixed(rx));
+    atomicAdd(&gfix[2 * m + 1], to_fixed(ry));
 }
 
 // The edge pass with forces scattered straight from the kernel: global fp32 atomics (kModeAtomic),
@@ -838,19 +846,19 @@ __device__ __forceinline__ void publish_chains(const BinLds& L, const BinArgs& Q
 // Head sum of each row: segmented inclusive scan over the lanes of the row, in lane order.  The last
 // lane of a row then holds the row's sum; it is stored directly when the whole row lies inside this
 // wavefront (positions wave_e0 .. wave_e0+63, below e_end), else it has to be handed on as a record
-// (returns true on that lane).  i = head of the lane's edge, -1 on lanes without an edge.
+// (returns true on that lane).  A row is a run of consecutive CSR positions ea .. eb-1, so the first lane of a
+// lane's segment follows from ea: no lane has to look at its neighbours' heads.
 __device__ __forceinline__ bool reduce_head_sums(const BinArgs& Q, bool has, int32_t i, int32_t ea, int32_t eb, int64_t e64,
                                                  int64_t e_end, float& hx, float& hy) {
     const int lane = threadIdx.x & 63;
+    const int64_t wave_e0 = e64 - lane;
+    const int seg0 = has ? (int)max((int64_t)ea - wave_e0, (int64_t)0) : lane;   // first lane of this lane's row
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
         const float ux = __shfl_up(hx, d, 64), uy = __shfl_up(hy, d, 64);
-        const int32_t ui = __shfl_up(i, d, 64);
-        if (lane >= d && ui == i) { hx += ux; hy += uy; }
+        if (lane - d >= seg0) { hx += ux; hy += uy; }
     }
-    const int32_t i_after = __shfl_down(i, 1, 64);
-    const bool row_end = has && (lane == 63 || i_after != i);
-    const int64_t wave_e0 = e64 - lane;
+    const bool row_end = has && (lane == 63 || e64 + 1 >= min((int64_t)eb, e_end));
     const bool inside = (int64_t)ea >= wave_e0 && (int64_t)eb <= min(wave_e0 + 64, e_end);
     if (row_end && inside) Q.ghead[i] = make_float2(hx, hy);
     return row_end && !inside;
@@ -960,39 +968,66 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
 }
 
 // ------------------------------------------------------------------ K3 + K4 with the pooled sampler
-// Same scatter machinery, but the negatives of a block of ROUNDS * 1024 consecutive CSR positions come
-// from the block's pool of P.pool_size points, which lives in LDS: pool_th (their embedding rows, one
-// gather per pool entry and block instead of one per negative) and pool_acc (64-bit fixed-point sums
-// of the forces they receive, handed on as one record per pool entry and block).  The rounds of a
-// block run without barriers; the records of the whole block (tails, partial head sums, pool entries)
-// are sorted and written once per block.
+// The negatives of a block of ROUNDS * 1024 consecutive CSR positions come from the block's pool of
+// P.pool_size points, which lives in LDS: pool_th (their embedding rows, one gather per pool entry and block
+// instead of one per negative) and pool_acc (64-bit fixed-point sums of the forces they receive, handed on as
+// one record per pool entry and block).  The rounds of a block run without barriers.  Records (one tail per
+// edge, the pool entries, the few partial head sums) are not sorted: a record takes its rank among the block's
+// records of its tile from an LDS counter when it is made, and once the tiles' chains have been extended every
+// lane writes its own records at fill + rank.  Tails of one wavefront mostly share a tile and get consecutive
+// ranks, so their writes still coalesce; a pool entry's record is alone in its tile whichever way it is written.
 constexpr int kPoolBlockLanes = 1024;
 constexpr int kMaxPoolPerLane = 4;   // NOMAD_MAX_POOL / kPoolBlockLanes
 
+__host__ __device__ inline size_t pooled_side_records(int rounds) { return (size_t)2 * (kPoolBlockLanes / 64) * rounds; }
 __host__ __device__ inline size_t pooled_records_per_block(int rounds, uint32_t pool_size) {
-    return (size_t)kPoolBlockLanes * rounds + 2 * (kPoolBlockLanes / 64) * rounds + pool_size;
+    return (size_t)kPoolBlockLanes * rounds + pooled_side_records(rounds) + pool_size;
 }
 __host__ __device__ inline size_t pooled_lds_bytes(uint32_t n_bins, int rounds, uint32_t pool_size) {
-    return (size_t)pool_size * 28 + ((size_t)4 * n_bins + 2 + 3 * pooled_records_per_block(rounds, pool_size)) * sizeof(uint32_t);
+    return (size_t)pool_size * 28 + ((size_t)4 * n_bins + 3 * pooled_side_records(rounds)) * sizeof(uint32_t);
+}
+
+// What a lane of the pooled edge pass has in flight for its next edge (no groups there: one population, no mean field).
+struct PoolFetch {
+    bool has;
+    int32_t e, i, j, ea, eb;
+    float pe;
+    float2 ti, tj;
+};
+
+__device__ __forceinline__ void issue_pool_edge(const EdgeArgs& P, bool has, int32_t e, int32_t i, int32_t j, PoolFetch& f) {
+    f.has = has;
+    f.e = e; f.i = has ? i : -1; f.j = j; f.ea = 0; f.eb = 0; f.pe = 0.f;
+    f.ti = make_float2(0.f, 0.f);
+    f.tj = make_float2(0.f, 0.f);
+    if (!has) return;
+    f.ea = P.row_ptr[i];
+    f.eb = P.row_ptr[i + 1];
+    f.ti = P.theta[i];
+    f.tj = P.theta[j];
+    if (P.pe) f.pe = P.pe[e];
 }
 
 template <int S, int ROUNDS>
 __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs P, const BinArgs Q) {
     constexpr int BS = kPoolBlockLanes;
     constexpr int SS = S > 0 ? S : 1;
-    constexpr int kWaves = BS / 64;
     constexpr int NP = kMaxPoolPerLane;
-    constexpr int NR = 2 * ROUNDS + NP;   // per lane and block: ROUNDS tails, ROUNDS possible partial head sums, NP pool entries
-    constexpr int FLUSH_ITERS = ROUNDS + 1 + NP;
+    constexpr int kSide = 2 * (BS / 64) * ROUNDS;    // partial head sums a block can produce
     extern __shared__ unsigned long long lds_pool[];
-    const uint32_t PS = P.pool_size;
+    const uint32_t PS = P.pool_size, B = Q.n_bins;
+    const int tb = Q.tile_bits;
     unsigned long long* pool_acc = lds_pool;                         // [2 PS] fixed-point force sums
     float2* pool_th = (float2*)(pool_acc + 2 * (size_t)PS);          // [PS] embedding rows of the pool
     uint32_t* pool_pt = (uint32_t*)(pool_th + PS);                   // [PS] the points
-    const uint32_t nrec = (uint32_t)pooled_records_per_block(ROUNDS, PS);
-    const BinLds L = carve_bin_lds(pool_pt + PS, Q.n_bins, nrec, Q.tile_bits);
-    __shared__ uint32_t wave_total[kWaves];
-    __shared__ uint32_t pool_cursor;
+    uint32_t* cnt = pool_pt + PS;                                    // [B] records of this block per tile
+    uint32_t* fill = cnt + B;                                        // [B] records in the open chunk (kChunk: none open / full)
+    uint32_t* chunk = fill + B;                                      // [B] open chunk of this (workgroup, tile)
+    uint32_t* base = chunk + B;                                      // [B] first chunk allocated for this block
+    uint32_t* side_pt = base + B;                                    // [kSide] partial head sums: the head
+    float* side_x = (float*)(side_pt + kSide);                       // [kSide]
+    float* side_y = side_x + kSide;                                  // [kSide]
+    __shared__ uint32_t pool_cursor, side_n;
     const int tid = threadIdx.x;
     const uint32_t W = gridDim.x, w = blockIdx.x;
     constexpr int64_t G = (int64_t)BS * ROUNDS;                       // = P.pool_block
@@ -1001,11 +1036,12 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
     const int64_t first_block = Q.e_begin / G;
     const int64_t n_blocks = (Q.e_end + G - 1) / G;   // one past the last block
     const uint32_t pool_end = min(Q.wg_pool_begin[w + 1], Q.max_chunks);
-    init_bin_lds<BS>(L);
-    if (tid == 0) pool_cursor = Q.wg_pool_begin[w];
+    for (uint32_t b = tid; b < B; b += BS) { cnt[b] = 0; fill[b] = kChunk; chunk[b] = kNoChunk; base[b] = 0; }
+    for (uint32_t u = tid; u < 2 * PS; u += BS) pool_acc[u] = 0ull;
+    if (tid == 0) { pool_cursor = Q.wg_pool_begin[w]; side_n = 0; }
 
-    // pool of the first block (later blocks: fetched one block ahead).  One Philox call yields four
-    // consecutive entries, so lane t fetches entries 4t .. 4t+3 (lanes beyond pool_size / 4 idle).
+    // One Philox call yields four consecutive pool entries, so lane t fetches entries 4t .. 4t+3 (lanes beyond
+    // pool_size / 4 idle); a block's pool is fetched while the block before it is written out.
     uint32_t next_pt[NP];
     float2 next_th[NP];
     auto fetch_pool = [&](int64_t blk) {
@@ -1020,36 +1056,52 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
                 if (u0 + k < PS) { next_pt[k] = __umulhi(wd[k], (uint32_t)P.n); next_th[k] = P.theta[next_pt[k]]; }
         }
     };
+    auto stage_pool = [&]() {
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            const uint32_t u = 4u * (uint32_t)tid + (uint32_t)k;
+            if (u < PS) { pool_pt[u] = next_pt[k]; pool_th[u] = next_th[k]; }
+        }
+    };
     fetch_pool(first_block + w);
-    // edge pipeline as in k_edges_binned; the position after the last one of a block is the first of this
-    // workgroup's next block
+    stage_pool();
+    // edge pipeline: (head, tail) indices two rounds ahead, embedding rows one round ahead; the position after the
+    // last one of a block is the first of this workgroup's next block
     auto next_position = [&](int64_t e) { return (e + BS) % G < BS ? e + BS + (int64_t)(W - 1) * G : e + BS; };
-    EdgeFetch<S, false> f;
+    auto covered = [&](int64_t e) { return e >= Q.e_begin && e < Q.e_end; };
+    PoolFetch f;
     int32_t i_next = 0, j_next = 0;
     {
-        auto covered = [&](int64_t e) { return e >= Q.e_begin && e < Q.e_end; };
         const int64_t e0 = (first_block + w) * G + tid, e1 = next_position(e0);
         int32_t i0 = 0, j0 = 0;
         if (covered(e0)) { i0 = Q.head[e0]; j0 = P.col[e0]; }
         if (covered(e1)) { i_next = Q.head[e1]; j_next = P.col[e1]; }
-        issue_edge<S, false>(P, covered(e0), (int32_t)e0, i0, j0, f);
+        issue_pool_edge(P, covered(e0), (int32_t)e0, i0, j0, f);
     }
-    auto covered = [&](int64_t e) { return e >= Q.e_begin && e < Q.e_end; };
+    // a record goes to position fill + rank of its tile's chain
+    auto emit = [&](bool valid, uint32_t pt, uint32_t rank, float x, float y) {
+        if (!valid) return;
+        const uint32_t b = pt >> tb;
+        const uint32_t pos = fill[b] + rank;
+        uint32_t ch, off;
+        if (pos < (uint32_t)kChunk) { ch = chunk[b]; off = pos; }
+        else { ch = base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
+        if (ch < pool_end) {   // kNoChunk is above any valid id
+            uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
+            dst[0] = pt & ((1u << tb) - 1u);
+            dst[1] = __float_as_uint(x);
+            dst[2] = __float_as_uint(y);
+        }
+    };
+    HeadCtx h;
+    h.omega = P.omega0;
+    h.MA = h.MBx = h.MBy = 0.f;
     for (int64_t blk = first_block + w; blk < n_blocks; blk += W) {
         const int64_t e_end = min((blk + 1) * G, Q.e_end);
-        // ---- this block's pool into LDS, the next block's pool into flight
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-            const uint32_t u = 4u * (uint32_t)tid + (uint32_t)k;
-            if (u < PS) { pool_pt[u] = next_pt[k]; pool_th[u] = next_th[k]; pool_acc[2 * u] = 0ull; pool_acc[2 * u + 1] = 0ull; }
-        }
-        fetch_pool(blk + W);
-        lds_barrier();
-        bool valid[NR];
-        uint32_t dst_pt[NR], rank[NR];
-        float fx[NR], fy[NR];
-#pragma unroll
-        for (int k = 0; k < NR; ++k) { valid[k] = false; dst_pt[k] = 0u; rank[k] = 0u; fx[k] = 0.f; fy[k] = 0.f; }
+        lds_barrier();   // the block's pool is in LDS, the tile tables are those left by the block before
+        bool tv[ROUNDS];
+        uint32_t tpt[ROUNDS], trk[ROUNDS];
+        float tfx[ROUNDS], tfy[ROUNDS];
         // ---- ROUNDS rounds of one edge per lane, no barriers in between
 #pragma unroll
         for (int r = 0; r < ROUNDS; ++r) {
@@ -1057,6 +1109,7 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
             const bool has = f.has;
             const int32_t i = f.i, ea = f.ea, eb = f.eb;
             float hx = 0.f, hy = 0.f;
+            tv[r] = has; tpt[r] = 0u; trk[r] = 0u; tfx[r] = 0.f; tfy[r] = 0.f;
             if (has) {
                 uint32_t slot[SS];
                 float2 tm[SS];
@@ -1068,48 +1121,102 @@ __global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs
                 }
 #pragma unroll
                 for (int k = 0; k < S; ++k) tm[k] = pool_th[slot[k]];
+                h.ti = f.ti;
                 EdgeOut<SS> o;
-                edge_math<S, false>(f.h, f.pe, f.tj, tm, o);
+                edge_math<S, false>(h, P.pe ? f.pe : 1.0f / (float)(eb - ea), f.tj, tm, o);
                 hx = o.hx;
                 hy = o.hy;
 #pragma unroll
                 for (int k = 0; k < S; ++k) {
-                    atomicAdd(&pool_acc[2 * slot[k]], (unsigned long long)__float2ll_rn(o.rx[k] * kFixScale));
-                    atomicAdd(&pool_acc[2 * slot[k] + 1], (unsigned long long)__float2ll_rn(o.ry[k] * kFixScale));
+                    atomicAdd(&pool_acc[2 * slot[k]], to_fixed(o.rx[k]));
+                    atomicAdd(&pool_acc[2 * slot[k] + 1], to_fixed(o.ry[k]));
                 }
-                valid[r] = true; dst_pt[r] = (uint32_t)f.j; fx[r] = -o.a * o.dx; fy[r] = -o.a * o.dy;
+                tpt[r] = (uint32_t)f.j; tfx[r] = -o.a * o.dx; tfy[r] = -o.a * o.dy;
+                trk[r] = atomicAdd(&cnt[tpt[r] >> tb], 1u);
             }
             {
                 const int64_t e1 = next_position(e64), e2 = next_position(e1);
                 const int32_t i1 = i_next, j1 = j_next;
                 if (covered(e2)) { i_next = Q.head[e2]; j_next = P.col[e2]; }
-                issue_edge<S, false>(P, covered(e1), (int32_t)e1, i1, j1, f);
+                issue_pool_edge(P, covered(e1), (int32_t)e1, i1, j1, f);
             }
-            valid[ROUNDS + r] = reduce_head_sums(Q, has, i, ea, eb, e64, e_end, hx, hy);
-            dst_pt[ROUNDS + r] = valid[ROUNDS + r] ? (uint32_t)i : 0u;
-            fx[ROUNDS + r] = hx;
-            fy[ROUNDS + r] = hy;
-            if (valid[r]) rank[r] = take_rank(L, dst_pt[r]);
-            if (valid[ROUNDS + r]) rank[ROUNDS + r] = take_rank(L, dst_pt[ROUNDS + r]);
+            if (reduce_head_sums(Q, has, i, ea, eb, e64, e_end, hx, hy)) {
+                const uint32_t k = atomicAdd(&side_n, 1u);
+                side_pt[k] = (uint32_t)i; side_x[k] = hx; side_y[k] = hy;
+            }
         }
-        lds_barrier();
-        // ---- one record per pool entry that received a force
+        fetch_pool(blk + W);
+        lds_barrier();   // every force of the block is in pool_acc, the side list is complete
+        // ---- one record per pool entry that received a force, one per partial head sum
+        bool pv[NP];
+        uint32_t ppt[NP], prk[NP];
+        float pfx[NP], pfy[NP];
 #pragma unroll
         for (int k = 0; k < NP; ++k) {
             const uint32_t u = (uint32_t)tid + (uint32_t)k * BS;
-            const int q = 2 * ROUNDS + k;
+            pv[k] = false; ppt[k] = 0u; prk[k] = 0u; pfx[k] = 0.f; pfy[k] = 0.f;
             if (u < PS) {
                 const long long ax = (long long)pool_acc[2 * u], ay = (long long)pool_acc[2 * u + 1];
-                valid[q] = (ax | ay) != 0;
-                dst_pt[q] = pool_pt[u];
-                fx[q] = (float)((double)ax * kFixInv);
-                fy[q] = (float)((double)ay * kFixInv);
-                if (valid[q]) rank[q] = take_rank(L, dst_pt[q]);
+                pv[k] = (ax | ay) != 0;
+                if (pv[k]) {
+                    pool_acc[2 * u] = 0ull;
+                    pool_acc[2 * u + 1] = 0ull;
+                    ppt[k] = pool_pt[u];
+                    pfx[k] = (float)((double)ax * kFixInv);
+                    pfy[k] = (float)((double)ay * kFixInv);
+                    prk[k] = atomicAdd(&cnt[ppt[k] >> tb], 1u);
+                }
             }
         }
-        sort_and_flush<NR, BS, FLUSH_ITERS>(L, Q, pool_end, &pool_cursor, wave_total, valid, dst_pt, rank, fx, fy);
+        const bool sv = (uint32_t)tid < side_n;
+        uint32_t spt = 0u, srk = 0u;
+        float sx = 0.f, sy = 0.f;
+        if (sv) { spt = side_pt[tid]; sx = side_x[tid]; sy = side_y[tid]; srk = atomicAdd(&cnt[spt >> tb], 1u); }
+        lds_barrier();   // the counts are complete
+        // ---- tiles whose open chunk cannot take this block's records get new chunks, linked to the chain
+        for (uint32_t b = tid; b < B; b += BS) {
+            const uint32_t c = cnt[b], fl = fill[b];
+            if (c != 0 && fl + c > (uint32_t)kChunk) {
+                const uint32_t k = (fl + c - 1) / kChunk;
+                const uint32_t nb = atomicAdd(&pool_cursor, k);
+                base[b] = nb;
+                if (nb + k > pool_end) *Q.overflow = 1;
+                uint32_t prev = chunk[b];
+                for (uint32_t y = 0; y < k && nb + y < pool_end; ++y) { Q.chunk_prev[nb + y] = prev; prev = nb + y; }
+            }
+        }
+        lds_barrier();
+        // ---- every lane writes its own records
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) emit(tv[r], tpt[r], trk[r], tfx[r], tfy[r]);
+#pragma unroll
+        for (int k = 0; k < NP; ++k) emit(pv[k], ppt[k], prk[k], pfx[k], pfy[k]);
+        emit(sv, spt, srk, sx, sy);
+        lds_barrier();   // the tables have been read
+        // ---- chain state after this block, counts back to zero; the next block's pool into LDS
+        for (uint32_t b = tid; b < B; b += BS) {
+            const uint32_t c = cnt[b];
+            if (c != 0) {
+                const uint32_t fl = fill[b];
+                if (fl + c > (uint32_t)kChunk) {
+                    const uint32_t k = (fl + c - 1) / kChunk;
+                    chunk[b] = base[b] + k - 1;
+                    fill[b] = fl + c - k * kChunk;
+                } else {
+                    fill[b] = fl + c;
+                }
+                cnt[b] = 0;
+            }
+        }
+        if (tid == 0) side_n = 0;
+        stage_pool();
     }
-    publish_chains<BS>(L, Q, pool_end);
+    lds_barrier();
+    for (uint32_t b = tid; b < B; b += BS) {
+        const uint32_t ch = chunk[b];
+        Q.chain_head[(size_t)b * W + w] = ch < pool_end ? ch : kNoChunk;
+        Q.chain_fill[(size_t)b * W + w] = fill[b];
+    }
 }
 
 // private chunk-id range of each workgroup: enough for every record its slabs can emit (s+1 per
@@ -1178,8 +1285,8 @@ __global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const BinArgs Q, 
                     const uint32_t r = (uint32_t)(r0 + u) * 64u + lane;
                     if (r < cnt) {
                         const uint32_t ml = rec[u][0] & (uint32_t)(tile - 1);
-                        atomicAdd(&acc[2 * ml], (unsigned long long)__float2ll_rn(__uint_as_float(rec[u][1]) * kFixScale));
-                        atomicAdd(&acc[2 * ml + 1], (unsigned long long)__float2ll_rn(__uint_as_float(rec[u][2]) * kFixScale));
+                        atomicAdd(&acc[2 * ml], to_fixed(__uint_as_float(rec[u][1])));
+                        atomicAdd(&acc[2 * ml + 1], to_fixed(__uint_as_float(rec[u][2])));
                     }
                 }
             }
