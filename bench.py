@@ -102,6 +102,9 @@ def main():
     ap.add_argument("--groups", type=int, default=None, help="deal the clusters into this many groups")
     ap.add_argument("--pool", default=None, metavar="P,G",
                     help="opt-in pooled sampler: pool size and block length (e.g. 2048,4096); not the benchmark's sampler")
+    ap.add_argument("--graph", choices=["symmetrised", "paper"], default="symmetrised",
+                    help="paper: the directed kNN graph with inverse-rank weights of Section 3.1 / Eq. 7 (planted configs); "
+                         "the benchmark uses the symmetrised unit-weight graph")
     ap.add_argument("--batches", type=int, default=1, help="sub-steps per epoch (minibatch epochs); the benchmark uses 1")
     ap.add_argument("--probe", choices=["copy"], default=None,
                     help="run only the streaming-copy probe (counter calibration / practical HBM ceiling)")
@@ -123,7 +126,7 @@ def main():
         return
     t0 = time.time()
     w = workloads.make_config(args.config, scale=args.scale, device=dev if args.config >= 3 else "cpu",
-                              n_groups=args.groups)
+                              n_groups=args.groups, paper_graph=args.graph == "paper")
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     pool = None
@@ -138,7 +141,7 @@ def main():
     nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode, pool_size=w.pool_size, pool_block=w.pool_block,
                batches_per_epoch=args.batches)
     t0 = time.time()
-    nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None, w.cluster_of.to(dev),
+    nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None if w.weights is None else w.weights.to(dev), w.cluster_of.to(dev),
                  None if w.cluster_group is None else w.cluster_group.to(dev))
     nm.set_embedding(w.theta0.to(dev))
     torch.cuda.synchronize()
@@ -162,7 +165,7 @@ def main():
     kernels = {}
     for name, (ms, cnt) in prof.items():
         if cnt:
-            ab = algorithmic_bytes(name, n, E, s, R, grouped, False, mode == SCATTER_DETERMINISTIC, pool)
+            ab = algorithmic_bytes(name, n, E, s, R, grouped, w.weights is not None, mode == SCATTER_DETERMINISTIC, pool)
             kernels[name] = dict(ms=ms / cnt, launches=cnt, algorithmic_gb=ab / 1e9, gbs=ab / (ms / cnt) / 1e6)
     dom = max(kernels, key=lambda k: kernels[k]["ms"])
     if dom == "mean_field":
@@ -174,9 +177,9 @@ def main():
     else:
         roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s", traffic=None)
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    if args.scale == 1.0 and args.groups is None and pool is None and args.batches == 1:
+    if args.scale == 1.0 and args.groups is None and pool is None and args.batches == 1 and args.graph == "symmetrised":
         roofline["traffic"] = measured_traffic(dom, args.config, args.mode)
-    epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, False, mode == SCATTER_DETERMINISTIC, pool) for k in kernels
+    epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, w.weights is not None, mode == SCATTER_DETERMINISTIC, pool) for k in kernels
                       if k != "mean_field")
     out = {
         "metric": "positive+negative edge updates/sec per epoch at 1 GPU",

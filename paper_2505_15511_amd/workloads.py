@@ -217,6 +217,24 @@ def planted_knn_graph(n: int, n_clusters: int, k: int, cross_frac: float, seed: 
                 out_nbrs=nbrs32, sizes=sizes_np)
 
 
+def inverse_rank_weights(k: int) -> np.ndarray:
+    """p(j|i) of the inverse-rank edge model (Eq. 7) for the neighbour of rank rho = 1..k: e^(1/rho) over the sum of
+    the k terms.  float64 [k]; an input of the path, not part of its arithmetic."""
+    w = np.exp(1.0 / np.arange(1, k + 1, dtype=np.float64))
+    return w / w.sum()
+
+
+def directed_rank_csr(out_nbrs: torch.Tensor):
+    """The kNN digraph as Section 3.1 has it: row i holds i's k out-neighbours in rank order (no transposed
+    edges added), weighted by the inverse-rank model.  Returns (row_ptr int32 [n+1], col_idx int32 [n k],
+    weights float32 [n k])."""
+    n, k = out_nbrs.shape
+    dev = out_nbrs.device
+    row_ptr = (torch.arange(n + 1, dtype=torch.int64, device=dev) * k).to(torch.int32)
+    wk = torch.from_numpy(inverse_rank_weights(k).astype(np.float32)).to(dev)
+    return row_ptr, out_nbrs.reshape(-1).to(torch.int32).contiguous(), wk.repeat(n).contiguous()
+
+
 def init_embedding(n: int, seed: int, std: float = 0.01, device="cpu") -> torch.Tensor:
     """theta_0 ~ N(0, std^2 I) in fp32, generated on the host so that it does not depend on the device."""
     g = _gen(seed, "cpu")
@@ -236,13 +254,16 @@ _CONFIGS = {
 }
 
 
-def make_config(cfg: int, *, scale: float = 1.0, device="cpu", n_groups: Optional[int] = None) -> Workload:
+def make_config(cfg: int, *, scale: float = 1.0, device="cpu", n_groups: Optional[int] = None,
+                paper_graph: bool = False) -> Workload:
     """Build benchmark configuration ``cfg`` (1-5).
 
     ``scale`` < 1 shrinks n (and, for the planted graphs, the cluster count) proportionally so
     that the same structure can be exercised in seconds.  Seeds: 1000+cfg for data and graph,
     2000+cfg for theta_0, 3000+cfg for the sampler.  ``n_groups`` (planted configs) deals the
-    clusters greedily into that many size-balanced groups."""
+    clusters greedily into that many size-balanced groups.  ``paper_graph`` (planted configs) keeps the graph
+    directed, k out-edges per point in rank order with inverse-rank weights (Section 3.1, Eq. 7), instead of the
+    symmetrised unit-weight graph; a cross-cluster replacement may then repeat a neighbour of the row."""
     c = dict(_CONFIGS[cfg])
     n = max(64, int(round(c["n"] * scale)))
     name = f"config{cfg}" + ("" if scale == 1.0 else f"@{scale:g}")
@@ -263,7 +284,11 @@ def make_config(cfg: int, *, scale: float = 1.0, device="cpu", n_groups: Optiona
         group = torch.arange(R, dtype=torch.int32, device=device)
     if n_groups is not None:
         group = torch.from_numpy(balanced_groups(pg["sizes"], n_groups)).to(device)
-    return Workload(name=name, n=n, row_ptr=pg["row_ptr"], col_idx=pg["col_idx"], cluster_of=pg["cluster_of"],
+    weights = None
+    if paper_graph:
+        pg["row_ptr"], pg["col_idx"], weights = directed_rank_csr(pg["out_nbrs"])
+        name += "+directed-rank"
+    return Workload(name=name, n=n, row_ptr=pg["row_ptr"], col_idx=pg["col_idx"], cluster_of=pg["cluster_of"], weights=weights,
                     n_clusters=R, theta0=init_embedding(n, 2000 + cfg, device=device), n_neg=c["s"],
                     noise_count=c["M"], n_epochs=c["T"], lr0=1.0, seed=3000 + cfg, cluster_group=group,
                     out_nbrs=pg["out_nbrs"], k=c["k"])

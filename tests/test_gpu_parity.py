@@ -387,6 +387,27 @@ def test_directed_graph_without_reverse_edges(mode):
         assert grad_err(nm.get_gradient(), g_ref) < GRAD_TOL
 
 
+@pytest.mark.parametrize("mode", MODES)
+def test_paper_graph_directed_with_inverse_rank_weights(mode):
+    """Section 3.1's own input: the directed kNN graph (no transposed edges), p(j|i) from the inverse-rank model, Eq. 7."""
+    d = workload(3, 0.03, paper_graph=True).numpy()
+    assert d["weights"] is not None and len(d["col_idx"]) == d["n"] * 15
+    O = c_oracle.COracle(**d)
+    _, g_ref, _ = O.epoch(d["theta0"], 0)
+    with make_nomad(d, mode) as nm:
+        assert np.array_equal(nm.get_negatives(0, 0, 4000), O.negatives(0)[:4000])
+        assert abs(nm.loss(0) - O.loss_and_grad(d["theta0"], 0)[0]) < LOSS_TOL * abs(O.loss_and_grad(d["theta0"], 0)[0])
+        nm.epoch(0)
+        assert grad_err(nm.get_gradient(), g_ref) < GRAD_TOL
+        th = nm.get_embedding()
+        for t in range(1, 4):
+            nm.epoch(t)
+        th_ref = th.astype(np.float32)
+        for t in range(1, 4):
+            th_ref, g_ref, _ = O.epoch(th_ref, t)
+        assert np.abs(nm.get_embedding() - th_ref).max() < 1e-5 * max(1.0, np.abs(th_ref).max())
+
+
 def test_coincident_points_closed_form():
     """All rows equal: every q is 1, the loss is log(1+|M|) and no force acts (closed form, no oracle)."""
     d = small_random(30, groups=False, weights=False, s=5, M=5.0)

@@ -444,6 +444,21 @@ def test_inverse_rank_model_is_a_distribution():
     assert np.all(np.diff(p15) < 0)
 
 
+def test_paper_graph_workload_matches_the_inverse_rank_model():
+    """The directed workload: k out-edges per point in rank order, weights = the oracle's Eq. 7 model, rows sum to one."""
+    from paper_2505_15511_amd import workloads
+    w = workloads.make_config(3, scale=0.003, paper_graph=True)
+    d = w.numpy()
+    k = w.k
+    assert np.array_equal(d["row_ptr"], np.arange(w.n + 1) * k)
+    assert np.array_equal(d["col_idx"].reshape(w.n, k), w.out_nbrs.numpy())
+    assert np.allclose(d["weights"].reshape(w.n, k), po.inverse_rank_weights(k)[None, :], rtol=1e-7, atol=0)
+    assert np.allclose(d["weights"].reshape(w.n, k).sum(1), 1.0, atol=1e-6)
+    assert not np.any(d["col_idx"].reshape(w.n, k) == np.arange(w.n)[:, None])
+    sym = workloads.make_config(3, scale=0.003).numpy()
+    assert len(sym["col_idx"]) > len(d["col_idx"])          # the benchmark graph adds the transposed edges
+
+
 def test_neighbourhood_preservation_metric():
     a = np.array([[1, 2, 3], [0, 2, 3], [0, 1, 3], [0, 1, 2]])
     assert po.neighbourhood_preservation(a, a) == 1.0
