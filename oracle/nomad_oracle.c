@@ -44,6 +44,8 @@ typedef struct {
     int32_t batches_per_epoch;    /* B >= 1 (0 is read as 1): sequential sub-steps of an epoch, see oracle_epoch */
     int64_t head_begin, head_end; /* loss / gradient restricted to the edges of heads head_begin..head_end-1;   */
                                   /* head_end < 0 = all heads                                                   */
+    int32_t sampled_far_field;    /* opt-in variant of Eq. 5: negatives are drawn from all points; one whose cell is  */
+                                  /* approximated for the head enters through the cell mean and receives no force     */
 } oracle_problem;
 
 /* ---- Philox4x32-10 (published algorithm: Salmon, Moraes, Dror, Shaw, SC'11) ---- */
@@ -122,7 +124,8 @@ static inline int32_t group_of_point(const oracle_problem* P, int64_t i) {
  * edge e picks the pool entry u = (x16 * pool_size) >> 16, x16 = 16-bit half (k & 1) of word
  * ((k >> 1) & 3) of Philox(counter (lo32 e, hi32 e, t, k >> 3)): eight slots per Philox call.  Every
  * negative is still uniform over the points; negatives of different edges of a block are no longer
- * independent. */
+ * independent.
+ * sampled far field: the i.i.d. sampler with every head's population = all n points. */
 static void edge_negatives(const oracle_problem* P, const oracle_tables* T, int64_t e, int64_t i, int32_t t, int32_t* m) {
     int32_t g = group_of_point(P, i);
     int64_t base = T->gstart[g];
@@ -148,6 +151,10 @@ static void edge_negatives(const oracle_problem* P, const oracle_tables* T, int6
         uint32_t w[4];
         oracle_philox4x32_10(ctr, key, w);
         for (int32_t lane = 0; lane < 4 && 4 * blk + lane < P->n_neg; ++lane) {
+            if (P->sampled_far_field) {
+                m[4 * blk + lane] = (int32_t)(((uint64_t)w[lane] * (uint64_t)P->n) >> 32);
+                continue;
+            }
             uint64_t u = ((uint64_t)w[lane] * nloc) >> 32;
             m[4 * blk + lane] = T->members[base + (int64_t)u];
         }
@@ -196,7 +203,7 @@ static inline double cauchy(double ax, double ay, double bx, double by) {
 static void mean_field_sums(const oracle_problem* P, const int64_t* counts, const double* mu, double xi, double yi,
                             int32_t gi, double* Ai, double* Bx, double* By) {
     *Ai = 0.0; *Bx = 0.0; *By = 0.0;
-    if (!P->cluster_group) return;
+    if (!P->cluster_group || P->sampled_far_field) return;
     for (int32_t r = 0; r < P->n_clusters; ++r) {
         if (P->cluster_group[r] == gi || counts[r] == 0) continue;
         const double pr = (double)counts[r] / (double)P->n;
@@ -251,6 +258,9 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
         double* g = gbuf ? gbuf + (size_t)tid * (size_t)gn * 2 : NULL;
         int32_t* m = (int32_t*)malloc(sizeof(int32_t) * (size_t)(s > 0 ? s : 1));
         double* qim = (double*)malloc(sizeof(double) * (size_t)(s > 0 ? s : 1));
+        double* nx = (double*)malloc(sizeof(double) * (size_t)(s > 0 ? s : 1));   /* where each negative sits */
+        double* ny = (double*)malloc(sizeof(double) * (size_t)(s > 0 ? s : 1));
+        int* moved = (int*)malloc(sizeof(int) * (size_t)(s > 0 ? s : 1));          /* does it receive its force? */
         const int64_t h0 = P->head_end >= 0 ? P->head_begin : 0;
         const int64_t h1 = P->head_end >= 0 ? P->head_end : n;
 #pragma omp for schedule(dynamic, 256)
@@ -259,7 +269,7 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
             const double xi = theta[2 * i], yi = theta[2 * i + 1];
             const int32_t gi = group_of_point(P, i);
             const double nloc = (double)(T.gstart[gi + 1] - T.gstart[gi]);
-            const double om = s > 0 ? Mn * (nloc / (double)n) / (double)s : 0.0;
+            const double om = s > 0 ? Mn * (P->sampled_far_field ? 1.0 : nloc / (double)n) / (double)s : 0.0;
             double wsum = 0.0;
             if (P->weights)
                 for (int64_t e = ea; e < eb; ++e) wsum += (double)P->weights[e];
@@ -293,7 +303,13 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
                 const double qij = 1.0 / (1.0 + dx * dx + dy * dy);
                 double qs = 0.0;
                 for (int32_t k = 0; k < s; ++k) {
-                    qim[k] = cauchy(xi, yi, theta[2 * (int64_t)m[k]], theta[2 * (int64_t)m[k] + 1]);
+                    /* sampled far field: a negative of another group stands for its cell and enters through the mean */
+                    const int32_t rk = P->cluster_of[m[k]];
+                    const int far = P->sampled_far_field && P->cluster_group && P->cluster_group[rk] != gi;
+                    nx[k] = far ? mu[2 * rk] : (double)theta[2 * (int64_t)m[k]];
+                    ny[k] = far ? mu[2 * rk + 1] : (double)theta[2 * (int64_t)m[k] + 1];
+                    moved[k] = !far;
+                    qim[k] = cauchy(xi, yi, nx[k], ny[k]);
                     qs += qim[k];
                 }
                 const double S = qij + Mn * Ai + om * qs;
@@ -307,10 +323,10 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
                 for (int32_t k = 0; k < s; ++k) {
                     const int64_t mk = m[k];
                     const int64_t sm = target_slot ? target_slot[mk] : mk;
-                    const double ex = xi - (double)theta[2 * mk], ey = yi - (double)theta[2 * mk + 1];
+                    const double ex = xi - nx[k], ey = yi - ny[k];
                     const double b = 2.0 * pe * om * qim[k] * qim[k] / S;
                     if (si >= 0) { g[2 * si] -= b * ex; g[2 * si + 1] -= b * ey; }
-                    if (sm >= 0) { g[2 * sm] += b * ex; g[2 * sm + 1] += b * ey; }
+                    if (sm >= 0 && moved[k]) { g[2 * sm] += b * ex; g[2 * sm + 1] += b * ey; }
                 }
                 if (si >= 0) {
                     const double c = 2.0 * pe * Mn / S;
@@ -321,6 +337,7 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
         }
         free(m);
         free(qim);
+        free(nx); free(ny); free(moved);
     }
     if (grad) {
 #pragma omp parallel for schedule(static)

@@ -114,6 +114,7 @@ class Problem:
     pool_size: int = 0                        # pooled sampler: points per pool (0 = i.i.d. per-edge sampler)
     pool_block: int = 0                       # pooled sampler: consecutive CSR positions that share a pool
     batches_per_epoch: int = 1                # B: sequential sub-steps of an epoch over consecutive head ranges
+    sampled_far_field: bool = False           # opt-in: Eq. 5's sum over approximated cells estimated from the samples
 
     def __post_init__(self):
         self.row_ptr = np.asarray(self.row_ptr, dtype=np.int64)
@@ -127,6 +128,7 @@ class Problem:
             self.noise_count = float(self.n_neg)
         assert (self.pool_size == 0) == (self.pool_block == 0), "pool_size and pool_block go together"
         assert self.pool_size == 0 or self.cluster_group is None, "the pooled sampler needs a single population"
+        assert not (self.sampled_far_field and self.pool_size), "sampled far field and pooled sampler do not combine"
 
     @property
     def n_edges(self) -> int:
@@ -138,7 +140,7 @@ class Problem:
                  n_clusters=w["n_clusters"], n_neg=w["n_neg"], noise_count=w["noise_count"], seed=w["seed"],
                  n_epochs=w["n_epochs"], lr0=w["lr0"], weights=w.get("weights"),
                  cluster_group=w.get("cluster_group"), pool_size=w.get("pool_size", 0), pool_block=w.get("pool_block", 0),
-                 batches_per_epoch=w.get("batches_per_epoch", 1))
+                 batches_per_epoch=w.get("batches_per_epoch", 1), sampled_far_field=w.get("sampled_far_field", False))
         d.update(over)
         return cls(**d)
 
@@ -201,7 +203,7 @@ def mean_field(P: Problem, theta: np.ndarray, p_r: np.ndarray, mu: np.ndarray):
     n = P.n
     A = np.zeros(n, dtype=np.float64)
     B = np.zeros((n, 2), dtype=np.float64)
-    if P.cluster_group is None:
+    if P.cluster_group is None or P.sampled_far_field:
         return A, B
     th = np.asarray(theta, dtype=np.float64)
     grp = P.cluster_group
@@ -236,7 +238,8 @@ def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None)
     Pooled sampler (opt-in variant): slot k picks entry u = (x16 * pool_size) >> 16 of the pool shared
     by the edge's block of pool_block CSR positions, x16 = 16-bit half k & 1 of word (k >> 1) & 3 of
     Philox(counter (lo32 e, hi32 e, t, k >> 3)).  Each negative is still uniform over the points,
-    negatives of one block are no longer independent."""
+    negatives of one block are no longer independent.
+    Sampled far field (opt-in variant): the i.i.d. sampler with every head's population = all n points."""
     if e_end is None:
         e_end = P.n_edges
     s = P.n_neg
@@ -267,7 +270,7 @@ def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None)
                 break
             x = words[lane]
             for idx in range(e_end - e_begin):
-                pop = members[int(gop[head[idx]])]
+                pop = np.arange(P.n) if P.sampled_far_field else members[int(gop[head[idx]])]
                 u = (int(x[idx]) * len(pop)) >> 32
                 out[idx, slot] = pop[u]
     return out
@@ -282,6 +285,8 @@ def omega(P: Problem) -> np.ndarray:
         return w
     for g, pop in members.items():
         w[gop == g] = P.noise_count * (len(pop) / float(P.n)) / P.n_neg
+    if P.sampled_far_field:       # every head samples all points
+        w[:] = P.noise_count / P.n_neg
     return w
 
 
@@ -299,7 +304,13 @@ def loss_and_grad(P: Problem, theta: np.ndarray, t: int, want_grad: bool = True,
     with the negatives of epoch index t.  Returns (L, g [n,2]).  ``mu_fixed`` replaces the cell
     means (the gradient holds them constant; a finite-difference check must do the same).
     ``head_range`` = (begin, end) keeps only the terms of the heads begin..end-1 (one sub-step of a
-    minibatch epoch); the terms of all ranges of a partition add up to the full loss and gradient."""
+    minibatch epoch); the terms of all ranges of a partition add up to the full loss and gradient.
+
+    Sampled far field (opt-in variant of Eq. 5): a negative m drawn from all points whose cell r is approximated
+    for the head (another group) enters through the cell mean, q(theta_i, mu_r), and receives no force (the means
+    are constants of the epoch); a negative of the head's own group enters as itself.  With m uniform over the
+    points, E[(|M|/s) sum_k q_k] = |M| sum_{r in Rtilde} p_r q(theta_i, mu_r) + (|M|/n) sum_{m in own group}
+    q(theta_i, theta_m): Eq. 5 plus the expectation of the sampled term of Eq. 6, with no sum over the cells."""
     th = _as_positions(theta)
     n, s, Mn = P.n, P.n_neg, float(P.noise_count)
     pe = edge_probabilities(P)
@@ -312,14 +323,23 @@ def loss_and_grad(P: Problem, theta: np.ndarray, t: int, want_grad: bool = True,
     g = np.zeros((n, 2), dtype=np.float64)
     total = 0.0
     h0, h1 = (0, n) if head_range is None else head_range
+    grp = P.cluster_group
+
+    def through_mean(i, m):
+        """sampled far field: is negative m of head i replaced by the mean of its cell?"""
+        return P.sampled_far_field and grp is not None and grp[P.cluster_of[m]] != grp[P.cluster_of[i]]
+
     for i in range(h0, h1):
         for e in range(int(P.row_ptr[i]), int(P.row_ptr[i + 1])):
             j = int(P.col_idx[e])
             d_ij = th[i] - th[j]
             q_ij = 1.0 / (1.0 + d_ij @ d_ij)
             q_im = np.zeros(s)
+            where = []
             for kap in range(s):
-                q_im[kap] = cauchy(th[i], th[neg[e, kap]])
+                m = int(neg[e, kap])
+                where.append(mu[P.cluster_of[m]] if through_mean(i, m) else th[m])
+                q_im[kap] = cauchy(th[i], where[kap])
             S = q_ij + Mn * A[i] + om[i] * q_im.sum()
             total += pe[e] * (-math.log(q_ij) + math.log(S))
             if not want_grad:
@@ -329,10 +349,11 @@ def loss_and_grad(P: Problem, theta: np.ndarray, t: int, want_grad: bool = True,
             g[j] -= a_e * d_ij
             for kap in range(s):
                 m = int(neg[e, kap])
-                d_im = th[i] - th[m]
+                d_im = th[i] - where[kap]
                 b = 2.0 * pe[e] * om[i] * q_im[kap] ** 2 / S
                 g[i] -= b * d_im
-                g[m] += b * d_im
+                if not through_mean(i, m):
+                    g[m] += b * d_im
             g[i] -= 2.0 * pe[e] * Mn * B[i] / S
     return total / n, g
 
