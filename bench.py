@@ -105,6 +105,9 @@ def main():
     ap.add_argument("--graph", choices=["symmetrised", "paper"], default="symmetrised",
                     help="paper: the directed kNN graph with inverse-rank weights of Section 3.1 / Eq. 7 (planted configs); "
                          "the benchmark uses the symmetrised unit-weight graph")
+    ap.add_argument("--far-field", choices=["exact", "sampled"], default="exact",
+                    help="sampled: estimate Eq. 5's sum over the approximated cells from the samples (opt-in variant; "
+                         "grouped configurations); the benchmark sums it exactly")
     ap.add_argument("--batches", type=int, default=1, help="sub-steps per epoch (minibatch epochs); the benchmark uses 1")
     ap.add_argument("--probe", choices=["copy"], default=None,
                     help="run only the streaming-copy probe (counter calibration / practical HBM ceiling)")
@@ -138,8 +141,9 @@ def main():
     if warmup + steps > w.n_epochs:
         steps = max(1, w.n_epochs - warmup)
     mode = SCATTER_DETERMINISTIC if args.mode == "det" else SCATTER_ATOMIC
+    w.sampled_far_field = args.far_field == "sampled"
     nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode, pool_size=w.pool_size, pool_block=w.pool_block,
-               batches_per_epoch=args.batches)
+               batches_per_epoch=args.batches, sampled_far_field=w.sampled_far_field)
     t0 = time.time()
     nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None if w.weights is None else w.weights.to(dev), w.cluster_of.to(dev),
                  None if w.cluster_group is None else w.cluster_group.to(dev))
@@ -177,7 +181,8 @@ def main():
     else:
         roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s", traffic=None)
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    if args.scale == 1.0 and args.groups is None and pool is None and args.batches == 1 and args.graph == "symmetrised":
+    if args.scale == 1.0 and args.groups is None and pool is None and args.batches == 1 and args.graph == "symmetrised" \
+            and not w.sampled_far_field:
         roofline["traffic"] = measured_traffic(dom, args.config, args.mode)
     epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, w.weights is not None, mode == SCATTER_DETERMINISTIC, pool) for k in kernels
                       if k != "mean_field")
@@ -191,7 +196,9 @@ def main():
                                f"|M|={w.noise_count:g}, {'grouped (mean-field)' if grouped else 'no approximated cells'}",
                    "scatter_mode": args.mode,
                    "batches_per_epoch": args.batches,
-                   "sampler": "iid per edge" if pool is None else f"pooled, {pool[0]} points per block of {pool[1]} edges (opt-in variant)"},
+                   "sampler": "iid per edge" if pool is None else f"pooled, {pool[0]} points per block of {pool[1]} edges (opt-in variant)",
+                   "far_field": "Eq. 5 summed over the approximated cells" if not w.sampled_far_field else
+                                "estimated from the samples (opt-in variant)"},
         "edges_per_sec": E / (elapsed / steps),
         "epoch_model_gb": epoch_bytes / 1e9,
         "epoch_hbm_frac_model": epoch_bytes / (elapsed / steps) / 1e9 / HBM_PEAK_GBS,

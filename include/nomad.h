@@ -70,7 +70,24 @@ typedef struct {
                                /* pooled sampler, points per pool (see below)                         */
     int32_t pool_block;        /* pooled sampler: consecutive CSR positions sharing one pool, >= 1;    */
                                /* must be 0 exactly when pool_size is 0                               */
+    int32_t far_field;         /* NOMAD_FAR_FIELD_EXACT (Eq. 5 summed over the approximated cells) or    */
+                               /* NOMAD_FAR_FIELD_SAMPLED (opt-in estimate of it, see below)            */
 } nomad_config;
+
+/*
+ * Sampled far field (opt-in variant; needs pool_size = 0).  Eq. 5 replaces the points of the approximated cells
+ * by their means and sums over those cells for every head: n |R| kernel evaluations per epoch.  With
+ * NOMAD_FAR_FIELD_SAMPLED that sum is estimated by the s samples instead: the negatives of every edge are drawn
+ * uniformly from ALL n points (same Philox words, multiply-high onto 0..n-1); a negative whose cell belongs to
+ * another group than the head's stands for its cell, enters S_e as q(theta_i, mu_cell) and receives no force (the
+ * means are constants of the epoch); a negative of the head's own group enters as itself.  Every sample weighs
+ * |M| / s.  The sample sum then has the expectation |M| sum_{r approximated} p_r q(theta_i, mu_r) +
+ * (|M| / n) sum_{m in own group} q(theta_i, theta_m), i.e. Eq. 5 plus the expectation of Eq. 6's sampled term, at
+ * the cost of one extra index lookup per negative.  Without cluster_group it is the plain sampler.
+ * nomad_get_mean_field returns zeros in this mode.
+ */
+#define NOMAD_FAR_FIELD_EXACT 0
+#define NOMAD_FAR_FIELD_SAMPLED 1
 
 /*
  * Pooled sampler (opt-in variant; NOT the i.i.d. noise samples of Section 3.1/3.3).  The CSR positions

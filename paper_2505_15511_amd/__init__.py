@@ -3,4 +3,4 @@
 Importing the package loads nothing; ``binding.load_library()`` opens the shared library and
 raises if it has not been built."""
 from .binding import (Nomad, NomadError, NomadConfig, load_library, SCATTER_ATOMIC, SCATTER_DETERMINISTIC,
-                      NOMAD_DEVICE, NOMAD_HOST)  # noqa: F401
+                      NOMAD_DEVICE, NOMAD_HOST, FAR_FIELD_EXACT, FAR_FIELD_SAMPLED)  # noqa: F401

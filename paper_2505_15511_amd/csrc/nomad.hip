@@ -177,6 +177,7 @@ EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
     a.cluster_of = c->cluster_of; a.group_of_cluster = c->grouped ? c->group_of_cluster : nullptr;
     a.gbase = c->gbase; a.gcount = c->gcount; a.gomega = c->gomega; a.gmembers = c->gmembers; a.hinfo = c->hinfo;
     a.A = c->A; a.B = c->B;
+    a.mu = c->mu; a.far = (c->grouped && c->cfg.far_field == NOMAD_FAR_FIELD_SAMPLED) ? 1 : 0;
     a.noise_count = c->noise_count; a.omega0 = c->omega0;
     a.key0 = (uint32_t)c->cfg.seed; a.key1 = (uint32_t)(c->cfg.seed >> 32); a.epoch = t;
     a.pool_size = (uint32_t)c->cfg.pool_size; a.pool_block = (uint32_t)c->cfg.pool_block;
@@ -282,7 +283,7 @@ int run_means(nomad_ctx* c) {
 
 // mean-field sums of the heads row_begin .. row_end-1
 int run_mean_field(nomad_ctx* c, int64_t row_begin, int64_t row_end) {
-    if (!c->grouped || row_end <= row_begin) return NOMAD_OK;
+    if (!c->grouped || row_end <= row_begin || c->cfg.far_field == NOMAD_FAR_FIELD_SAMPLED) return NOMAD_OK;
     Timed tm(c, NOMAD_K_MEANFIELD);
     hipLaunchKernelGGL(k_mean_field, dim3(blocks_for(row_end - row_begin, kMeanFieldBlock * kMeanFieldHeads)), dim3(kMeanFieldBlock), 0,
                        c->stream, c->theta, c->cluster_of, c->group_of_cluster, c->cinfo, c->group_slots, c->R, row_begin, row_end,
@@ -321,6 +322,9 @@ int nomad_create(const nomad_config* cfg, nomad_ctx** out) {
         (cfg->scatter_mode != NOMAD_SCATTER_DETERMINISTIC && cfg->scatter_mode != NOMAD_SCATTER_ATOMIC) || cfg->device < 0)
         return NOMAD_E_INVALID_ARG;
     if (cfg->pool_size < 0 || cfg->pool_size > NOMAD_MAX_POOL || cfg->pool_block < 0 || (cfg->pool_size == 0) != (cfg->pool_block == 0))
+        return NOMAD_E_INVALID_ARG;
+    if ((cfg->far_field != NOMAD_FAR_FIELD_EXACT && cfg->far_field != NOMAD_FAR_FIELD_SAMPLED) ||
+        (cfg->far_field == NOMAD_FAR_FIELD_SAMPLED && cfg->pool_size > 0))
         return NOMAD_E_INVALID_ARG;
     if (cfg->n_points >= ((int64_t)1 << 31) || cfg->n_clusters > cfg->n_points) return cfg->n_points >= ((int64_t)1 << 31) ? NOMAD_E_TOO_LARGE : NOMAD_E_INVALID_ARG;
     int ndev = 0;
@@ -782,7 +786,7 @@ int nomad_get_mean_field(nomad_ctx* c, float* A, float* B, int mem) {
     if (rc) return rc;
     if (!A || !B || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return fail(c, NOMAD_E_INVALID_ARG, "null pointer or bad mem");
     HIP_TRY(c, hipSetDevice(c->cfg.device));
-    if (!c->grouped) {
+    if (!c->grouped || c->cfg.far_field == NOMAD_FAR_FIELD_SAMPLED) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         if (mem == NOMAD_DEVICE) {
             HIP_TRY(c, hipMemset(A, 0, sizeof(float) * (size_t)c->n));

@@ -138,14 +138,14 @@ __global__ void k_cluster_census(const int32_t* __restrict__ cluster_of, const i
     }
 }
 
-// hinfo[i] = (population base, population size, omega) of the group of point i (see EdgeArgs::hinfo)
+// hinfo[i] = (population base, population size, omega, group label) of the group of point i (see EdgeArgs::hinfo)
 __global__ void __launch_bounds__(kBlock) k_head_info(const int32_t* __restrict__ cluster_of, const int32_t* __restrict__ group_of_cluster,
                                                       const uint32_t* __restrict__ gbase, const uint32_t* __restrict__ gcount,
                                                       const float* __restrict__ gomega, int64_t n, float4* __restrict__ hinfo) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int32_t g = group_of_cluster[cluster_of[i]];
-    hinfo[i] = make_float4(__uint_as_float(gbase[g]), __uint_as_float(gcount[g]), gomega[g], 0.f);
+    hinfo[i] = make_float4(__uint_as_float(gbase[g]), __uint_as_float(gcount[g]), gomega[g], __int_as_float(g));
 }
 
 // ------------------------------------------------------------------ K1: cell means
@@ -343,8 +343,10 @@ struct EdgeArgs {
     const uint32_t* gcount;        // per group: population size
     const float* gomega;           // per group: weight of one sampled negative
     const int32_t* gmembers;       // nullptr when every group is an index range
-    const float4* hinfo;           // grouped: per point (population base, population size, omega, -) of its group,
+    const float4* hinfo;           // grouped: per point (population base, population size, omega, group) of its group,
                                    // so that the edge pass needs one lookup per head instead of a chain of four
+    const float2* mu;              // cell means (sampled far field only)
+    int32_t far;                   // sampled far field: negatives from all points, other groups' through their cell mean
     const float* A;                // mean-field sums (grouped only)
     const float2* B;
     float noise_count;             // |M|
@@ -369,6 +371,7 @@ struct HeadCtx {
     float inv_deg;
     float omega;          // weight of one sampled negative (Eq. 6 estimate)
     float MA, MBx, MBy;   // |M| A_i and |M| B_i (Eq. 5 and its derivative factor)
+    int32_t group;        // group label of the head (0 without groups)
     Population pop;
 };
 
@@ -377,8 +380,16 @@ __device__ __forceinline__ HeadCtx load_head(const EdgeArgs& P, int64_t i, int32
     h.ti = P.theta[i];
     h.inv_deg = eb > ea ? 1.0f / (float)(eb - ea) : 0.f;
     h.MA = h.MBx = h.MBy = 0.f;
-    if (P.group_of_cluster) {
+    h.group = 0;
+    if (P.group_of_cluster && P.far) {   // every head samples all points; Eq. 5's sum is left to the samples
+        h.group = __float_as_int(P.hinfo[i].w);
+        h.pop.base = 0;
+        h.pop.count = (uint32_t)P.n;
+        h.pop.members = nullptr;
+        h.omega = P.omega0;
+    } else if (P.group_of_cluster) {
         const float4 hi = P.hinfo[i];
+        h.group = __float_as_int(hi.w);
         h.pop.base = __float_as_uint(hi.x);
         h.pop.count = __float_as_uint(hi.y);
         h.pop.members = P.gmembers;
@@ -492,6 +503,16 @@ __device__ __forceinline__ void draw_negatives(const EdgeArgs& P, const Populati
     }
 }
 
+// Where negative m sits for a head of group `group`.  Sampled far field: a point of another group stands for its
+// cell and enters through the cell mean (Eq. 5 estimated from the samples); it then receives no force (m = -1).
+__device__ __forceinline__ float2 negative_row(const EdgeArgs& P, int32_t group, int32_t& m) {
+    if (P.far) {
+        const int32_t r = P.cluster_of[m];
+        if (P.group_of_cluster[r] != group) { m = -1; return P.mu[r]; }
+    }
+    return P.theta[m];
+}
+
 template <int S, bool LOSS>
 __device__ __forceinline__ void edge_terms(const EdgeArgs& P, const HeadCtx& h, int32_t e, EdgeOut<(S > 0 ? S : 1)>& o) {
     const int32_t j = P.col[e];
@@ -501,7 +522,7 @@ __device__ __forceinline__ void edge_terms(const EdgeArgs& P, const HeadCtx& h, 
     draw_negatives<S>(P, h.pop, e, o.m);
     float2 tm[S > 0 ? S : 1];
 #pragma unroll
-    for (int k = 0; k < S; ++k) tm[k] = P.theta[o.m[k]];
+    for (int k = 0; k < S; ++k) tm[k] = negative_row(P, h.group, o.m[k]);
     edge_math<S, LOSS>(h, pe, tj, tm, o);
 }
 
@@ -526,7 +547,8 @@ __device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const Head
     const float qij = cauchy(dx, dy);
     float qsum = 0.f;
     for (int k = 0; k < s; ++k) {
-        const float2 tm = P.theta[negative_of_slot(P, h.pop, e, k)];
+        int32_t mk = negative_of_slot(P, h.pop, e, k);
+        const float2 tm = negative_row(P, h.group, mk);
         qsum += cauchy(h.ti.x - tm.x, h.ti.y - tm.y);
     }
     const float rest = h.MA + h.omega * qsum;   // S_e - q_ij
@@ -537,14 +559,14 @@ __device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const Head
     float fx = a * dx, fy = a * dy;
     const float bscale = 2.0f * pe * h.omega * inv_S;
     for (int k = 0; k < s; ++k) {
-        const int32_t mk = negative_of_slot(P, h.pop, e, k);
-        const float2 tm = P.theta[mk];
+        int32_t mk = negative_of_slot(P, h.pop, e, k);
+        const float2 tm = negative_row(P, h.group, mk);
         const float gx = h.ti.x - tm.x, gy = h.ti.y - tm.y;
         const float q = cauchy(gx, gy);
         const float bb = bscale * q * q;
         fx -= bb * gx;
         fy -= bb * gy;
-        emit(mk, bb * gx, bb * gy);
+        if (mk >= 0) emit(mk, bb * gx, bb * gy);
     }
     const float c = 2.0f * pe * inv_S;
     hx = fx - c * h.MBx;
@@ -580,6 +602,7 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
                 a = o.a; dx = o.dx; dy = o.dy; ehx = o.hx; ehy = o.hy;
 #pragma unroll
                 for (int k = 0; k < SS; ++k) {
+                    if (o.m[k] < 0) continue;   // stood for a cell mean: no force
                     if (MODE == kModeAtomic) {
                         unsafeAtomicAdd(&P.g[o.m[k]].x, o.rx[k]);
                         unsafeAtomicAdd(&P.g[o.m[k]].y, o.ry[k]);
@@ -874,7 +897,7 @@ struct EdgeFetch {
     float pe;
     HeadCtx h;
     int32_t m[S > 0 ? S : 1];
-    float2 tj, tm[S > 0 ? S : 1];
+    float2 tj, tm[S > 0 ? S : 1];   // sampled far field: tm[k].x carries the cell of m[k] until the round resolves it
 };
 
 template <int S, bool GATHER>
@@ -889,8 +912,32 @@ __device__ __forceinline__ void issue_edge(const EdgeArgs& P, bool has, int32_t 
     f.pe = P.pe ? P.pe[e] : f.h.inv_deg;
     if (GATHER) {
         draw_negatives<S>(P, f.h.pop, e, f.m);
+        if (P.far) {
 #pragma unroll
-        for (int k = 0; k < S; ++k) f.tm[k] = P.theta[f.m[k]];
+            for (int k = 0; k < S; ++k) f.tm[k] = make_float2(__int_as_float(P.cluster_of[f.m[k]]), 0.f);
+        } else {
+#pragma unroll
+            for (int k = 0; k < S; ++k) f.tm[k] = P.theta[f.m[k]];
+        }
+    }
+}
+
+// Sampled far field: with the cells of the negatives in hand, fetch what each stands for: the mean of its cell
+// when the cell belongs to another group than the head's (then m = -1: no force goes back), else its own row.
+template <int S>
+__device__ __forceinline__ void resolve_far_negatives(const EdgeArgs& P, EdgeFetch<S, true>& f) {
+    int32_t grp[S > 0 ? S : 1];
+    float2 mean[S > 0 ? S : 1];
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+        const int32_t r = __float_as_int(f.tm[k].x);
+        grp[k] = P.group_of_cluster[r];
+        mean[k] = P.mu[r];
+    }
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+        if (grp[k] != f.h.group) { f.tm[k] = mean[k]; f.m[k] = -1; }
+        else f.tm[k] = P.theta[f.m[k]];
     }
 }
 
@@ -940,13 +987,19 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
         for (int k = 0; k < NR; ++k) { valid[k] = k <= S && has; dst_pt[k] = 0u; rank[k] = 0u; fx[k] = 0.f; fy[k] = 0.f; }
         float hx = 0.f, hy = 0.f;
         if (has) {
+            if (P.far) resolve_far_negatives<S>(P, f);
             EdgeOut<SS> o;
             edge_math<S, false>(f.h, f.pe, f.tj, f.tm, o);
             hx = o.hx;
             hy = o.hy;
             dst_pt[0] = (uint32_t)f.j; fx[0] = -o.a * o.dx; fy[0] = -o.a * o.dy;
 #pragma unroll
-            for (int k = 0; k < S; ++k) { dst_pt[k + 1] = (uint32_t)f.m[k]; fx[k + 1] = o.rx[k]; fy[k + 1] = o.ry[k]; }
+            for (int k = 0; k < S; ++k) {
+                valid[k + 1] = f.m[k] >= 0;
+                dst_pt[k + 1] = f.m[k] >= 0 ? (uint32_t)f.m[k] : 0u;
+                fx[k + 1] = o.rx[k];
+                fy[k + 1] = o.ry[k];
+            }
         }
         // the loads of the next round go out before this round is sorted and written
         {
@@ -1382,7 +1435,7 @@ __global__ void __launch_bounds__(kBlock) k_negatives(const EdgeArgs P, int64_t 
     }
     const int64_t i = lo;
     Population pop;
-    if (P.group_of_cluster) {
+    if (P.group_of_cluster && !P.far) {
         const int32_t gi = P.group_of_cluster[P.cluster_of[i]];
         pop.base = P.gbase[gi];
         pop.count = P.gcount[gi];

@@ -55,7 +55,7 @@ def small_random(seed, n=3000, R=12, groups=True, weights=True, contiguous=False
 def make_nomad(d, mode):
     nm = Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
                pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0),
-               batches_per_epoch=d.get("batches_per_epoch", 1))
+               batches_per_epoch=d.get("batches_per_epoch", 1), sampled_far_field=d.get("sampled_far_field", False))
     nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
     nm.set_embedding(d["theta0"])
     return nm
@@ -492,3 +492,59 @@ def test_errors_are_codes_not_crashes():
         nm.get_negatives(0, 5, nm.num_edges() + 1)
     nm.epoch(0)
     nm.close()
+
+
+# ------------------------------------------------------------------ sampled far field (opt-in variant of Eq. 5)
+def _far_cases():
+    yield "random-groups", dict(small_random(60, n=5000, s=3), sampled_far_field=True)
+    yield "random-groups-s11", dict(small_random(61, n=3000, s=11, weights=False), sampled_far_field=True)      # run-time s path
+    yield "config5@2e-3", dict(workload(5, 2e-3).numpy(), sampled_far_field=True)                                 # every cluster its own group
+    yield "config4@5e-3-8groups", dict(workload(4, 5e-3, n_groups=8).numpy(), sampled_far_field=True)
+    yield "no-groups", dict(small_random(62, groups=False, s=4), sampled_far_field=True)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("case", [c for c, _ in _far_cases()])
+def test_sampled_far_field_matches_the_oracle(case, mode):
+    d = dict(_far_cases())[case]
+    note(f"sampled far field {case}")
+    O = c_oracle.COracle(**d)
+    with make_nomad(d, mode) as nm:
+        E = len(d["col_idx"])
+        assert np.array_equal(nm.get_negatives(2, 0, min(E, 20000)), O.negatives(2, 0, min(E, 20000)))
+        L_ref, _ = O.loss_and_grad(d["theta0"], 1, want_grad=False)
+        assert abs(nm.loss(1) - L_ref) < LOSS_TOL * abs(L_ref)
+        th = np.asarray(d["theta0"], dtype=np.float32)
+        for t in range(3):           # three epochs, each checked from the library's own embedding
+            th_ref, g_ref, _ = O.epoch(th, t)
+            nm.epoch(t)
+            assert grad_err(nm.get_gradient(), g_ref) < GRAD_TOL, t
+            th_new = nm.get_embedding()
+            assert np.abs(th_new - th_ref).max() < 1e-5 * max(1.0, np.abs(th_ref).max())
+            th = th_new
+        A, B = nm.get_mean_field()
+        assert not A.any() and not B.any()
+
+
+def test_sampled_far_field_with_sub_steps_and_fallback_scatter():
+    d = dict(small_random(63, n=4000, s=3), sampled_far_field=True, batches_per_epoch=4)
+    O = c_oracle.COracle(**d)
+    th_ref, g_ref, _ = O.epoch(d["theta0"], 0)
+    for mode in (SCATTER_DETERMINISTIC, SCATTER_ATOMIC):
+        with make_nomad(d, mode) as nm:
+            nm.epoch(0)
+            assert grad_err(nm.get_gradient(), g_ref) < GRAD_TOL
+            assert np.abs(nm.get_embedding() - th_ref).max() < 1e-5
+
+
+def test_sampled_far_field_estimates_the_exact_far_field_loss():
+    """Averaged over the epochs' samples the sampled loss approaches the loss with Eq. 5 summed exactly (both have
+    the same noise term in expectation; log is concave, so the sampled mean sits slightly below)."""
+    d = workload(4, 5e-3, n_groups=8).numpy()
+    rng = np.random.default_rng(5)
+    d["theta0"] = (rng.normal(size=(d["n"], 2)) * 2.0).astype(np.float32)
+    with make_nomad(d, SCATTER_DETERMINISTIC) as exact, make_nomad(dict(d, sampled_far_field=True), SCATTER_DETERMINISTIC) as far:
+        L_exact = np.mean([exact.loss(t) for t in range(20)])
+        L_far = np.mean([far.loss(t) for t in range(20)])
+    note(f"loss with exact far field {L_exact:.5f}, sampled {L_far:.5f}")
+    assert abs(L_far - L_exact) < 0.02 * L_exact

@@ -14,7 +14,8 @@ GRAD_TOL = 1e-5
 
 def random_case(seed):
     """Directed graph with a skewed degree distribution (isolated points, rows of one edge, a few hubs), optional
-    weights, clusters in arbitrary point order, optional groups, any s, optional pooled sampler and minibatches."""
+    weights, clusters in arbitrary point order, optional groups (with the far field summed or sampled), any s, optional
+    pooled sampler and minibatches."""
     rng = np.random.default_rng(seed)
     n = int(rng.choice([1, 2, 3, 17, 64, 65, 300, 1025, 4000, 9000]))
     R = int(min(n, rng.choice([1, 2, 5, 31])))
@@ -41,6 +42,8 @@ def random_case(seed):
              batches_per_epoch=int(rng.choice([1, 1, 2, 5])))
     if pooled:
         d["pool_size"], d["pool_block"] = [(1, 1024), (37, 50), (512, 1024), (2048, 4096), (4096, 2048), (300, 8192)][int(rng.integers(6))]
+    if grouped and rng.random() < 0.5:
+        d["sampled_far_field"] = True
     return d
 
 
@@ -51,7 +54,8 @@ def test_random_case_against_the_oracle(seed, mode):
     O = c_oracle.COracle(**d)
     th_ref, g_ref, _ = O.epoch(d["theta0"], 1)
     with Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
-               pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0), batches_per_epoch=d["batches_per_epoch"]) as nm:
+               pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0), batches_per_epoch=d["batches_per_epoch"],
+               sampled_far_field=d.get("sampled_far_field", False)) as nm:
         nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
         nm.set_embedding(d["theta0"])
         if d["n_neg"] and len(d["col_idx"]):
@@ -63,7 +67,7 @@ def test_random_case_against_the_oracle(seed, mode):
     # the size of the cancelled forces, each at most p(j|i) <= 1: the error is measured against at least 1e-2.
     scale = max(np.abs(g_full).max(), np.abs(g_ref).max(), 1e-2)
     print(f"  seed {seed}: n={d['n']} E={len(d['col_idx'])} s={d['n_neg']} B={d['batches_per_epoch']} pool={d.get('pool_size', 0)} "
-          f"groups={d['cluster_group'] is not None} grad err {np.abs(g - g_ref).max() / scale:.2e}", flush=True)
+          f"groups={d['cluster_group'] is not None} far={d.get('sampled_far_field', False)} grad err {np.abs(g - g_ref).max() / scale:.2e}", flush=True)
     # fp32 atomics round once per addition against the running sum: a pool of one point makes that point the target
     # of pool_block * s additions per block (1e5 and more here), whose rounding walk exceeds the bar that holds for
     # ordinary in-degrees; the fixed-point deterministic mode keeps the bar there as well.
