@@ -53,7 +53,7 @@ struct nomad_ctx {
     // binned deterministic scatter
     bool binned = false;
     int n_wg = 0, bin_block = 1024;
-    int pool_rounds = 0;            // > 0: the pooled edge pass runs, pool_block = 1024 * pool_rounds
+    int pool_rounds = 0;            // > 0: the pooled edge pass runs, pool_block = bin_block * pool_rounds
     std::vector<int64_t> batch_row, batch_edge;   // [B + 1] first head / first CSR position of every sub-step
     uint32_t n_bins = 0, max_chunks = 0;
     int tile_bits = kMaxTileBits;
@@ -214,7 +214,7 @@ BinArgs bin_args(nomad_ctx* c) {
 constexpr size_t kMaxLdsBytes = 160 * 1024 - 256;   // per workgroup on gfx950, less the kernels' static LDS
 
 size_t edge_pass_lds_bytes(const nomad_ctx* c) {
-    return c->pool_rounds ? pooled_lds_bytes(c->n_bins, c->pool_rounds, (uint32_t)c->cfg.pool_size)
+    return c->pool_rounds ? pooled_lds_bytes(c->n_bins, c->cfg.pool_block, (uint32_t)c->cfg.pool_size)
                           : binned_lds_bytes(c->n_bins, c->cfg.n_neg, c->bin_block);
 }
 
@@ -224,10 +224,10 @@ using EdgePassKernel = void (*)(const EdgeArgs, const BinArgs);
 template <int S, typename Fn>
 void with_edge_pass_kernel_s(const nomad_ctx* c, Fn fn) {
     EdgePassKernel k = k_edges_binned<S, 1024>;
-    if (c->pool_rounds == 1) k = k_edges_pooled<S, 1>;
-    else if (c->pool_rounds == 2) k = k_edges_pooled<S, 2>;
-    else if (c->pool_rounds == 4) k = k_edges_pooled<S, 4>;
-    else if (c->pool_rounds == 8) k = k_edges_pooled<S, 8>;
+    if (c->pool_rounds == 1) k = k_edges_pooled<S, 1, 1024>;
+    else if (c->pool_rounds == 2) k = k_edges_pooled<S, 2, 1024>;
+    else if (c->pool_rounds == 4) k = k_edges_pooled<S, 4, 1024>;
+    else if (c->pool_rounds == 8) k = k_edges_pooled<S, 8, 1024>;
     else if (c->bin_block == 512) k = k_edges_binned<S, 512>;
     fn(k);
 }
@@ -264,7 +264,7 @@ void launch_edges_binned(nomad_ctx* c, const EdgeArgs& a, int64_t e_begin, int64
     BinArgs q = bin_args(c);
     q.e_begin = e_begin;
     q.e_end = e_end;
-    const dim3 grid(c->n_wg), block(c->pool_rounds ? kPoolBlockLanes : c->bin_block);
+    const dim3 grid(c->n_wg), block(c->bin_block);
     const size_t lds = edge_pass_lds_bytes(c);
     with_edge_pass_kernel(c, [&](EdgePassKernel kernel) { hipLaunchKernelGGL(kernel, grid, block, lds, c->stream, a, q); });
 }
@@ -574,15 +574,17 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 2 * (binned_lds_bytes(n_bins, s, 512) + 256) <= 160 * 1024) { bin_block = 512; wg_per_cu = 2; }
         if (const char* knob = getenv("NOMAD_WG_PER_CU"))   // tuning knob: persistent workgroups per compute unit
             wg_per_cu = std::max(1, std::min(8, atoi(knob)));
-        // Pooled sampler: its own edge pass (pool in LDS) when the block is 1, 2, 4 or 8 rounds of 1024 positions.
+        // Pooled sampler: its own edge pass (pool in LDS) when the block is 1, 2, 4 or 8 rounds of 1024 positions, one
+        // workgroup per compute unit.  (Two workgroups of 512 lanes per compute unit, which lets one block's
+        // bookkeeping overlap the other's rounds, measured 4 % slower: the rounds are bound by vector-ALU issue.)
         int pool_rounds = 0;
-        if (c->cfg.pool_size > 0 && c->cfg.pool_block % kPoolBlockLanes == 0 && !getenv("NOMAD_NO_POOL_KERNEL")) {
-            const int r = c->cfg.pool_block / kPoolBlockLanes;
-            if ((r == 1 || r == 2 || r == 4 || r == 8) && n_bins <= (uint32_t)kMaxBinsPerThread * kPoolBlockLanes &&
-                pooled_lds_bytes(n_bins, r, (uint32_t)c->cfg.pool_size) <= kMaxLdsBytes)
+        if (c->cfg.pool_size > 0 && c->cfg.pool_block % 1024 == 0 && !getenv("NOMAD_NO_POOL_KERNEL")) {
+            const int r = c->cfg.pool_block / 1024;
+            if ((r == 1 || r == 2 || r == 4 || r == 8) &&
+                pooled_lds_bytes(n_bins, c->cfg.pool_block, (uint32_t)c->cfg.pool_size) <= kMaxLdsBytes)
                 pool_rounds = r;
         }
-        if (pool_rounds) { bin_block = kPoolBlockLanes; wg_per_cu = 1; }
+        if (pool_rounds) { bin_block = 1024; wg_per_cu = 1; }
         if (s <= 8 && E > 0 && bin_block && !getenv("NOMAD_NO_BINNING")) {
             hipDeviceProp_t prop;
             HTRY(hipGetDeviceProperties(&prop, c->cfg.device));

@@ -21,8 +21,7 @@ constexpr int kBlock = 256;
 // 64-bit fixed point used for order-independent accumulation of the negatives' gradient in
 // deterministic mode: one unit = 2^-36.  Every single contribution is bounded by p(j|i) <= 1 in
 // magnitude, so 2^27 contributions per point still fit.
-constexpr float kFixScale = 68719476736.0f;          // 2^36
-constexpr double kFixInv = 1.0 / 68719476736.0;
+constexpr double kFixInv = 1.0 / 68719476736.0;       // 2^-36
 
 // v * 2^36 rounded to the nearest integer (ties to even) as a 64-bit two's complement number, for |v| < 2^15.
 // Adding 1.5 * 2^52 in double precision leaves that integer in the low mantissa bits: three instructions
@@ -1029,15 +1028,12 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
 // records of its tile from an LDS counter when it is made, and once the tiles' chains have been extended every
 // lane writes its own records at fill + rank.  Tails of one wavefront mostly share a tile and get consecutive
 // ranks, so their writes still coalesce; a pool entry's record is alone in its tile whichever way it is written.
-constexpr int kPoolBlockLanes = 1024;
-constexpr int kMaxPoolPerLane = 4;   // NOMAD_MAX_POOL / kPoolBlockLanes
+constexpr int kMaxPoolPerLane = 4;   // pool entries one lane fetches and hands on: pool_size <= 4 * workgroup size
 
-__host__ __device__ inline size_t pooled_side_records(int rounds) { return (size_t)2 * (kPoolBlockLanes / 64) * rounds; }
-__host__ __device__ inline size_t pooled_records_per_block(int rounds, uint32_t pool_size) {
-    return (size_t)kPoolBlockLanes * rounds + pooled_side_records(rounds) + pool_size;
-}
-__host__ __device__ inline size_t pooled_lds_bytes(uint32_t n_bins, int rounds, uint32_t pool_size) {
-    return (size_t)pool_size * 28 + ((size_t)4 * n_bins + 3 * pooled_side_records(rounds)) * sizeof(uint32_t);
+// partial head sums a block can produce: two per wavefront and round
+__host__ __device__ inline size_t pooled_side_records(int64_t block_edges) { return (size_t)(block_edges / 32); }
+__host__ __device__ inline size_t pooled_lds_bytes(uint32_t n_bins, int64_t block_edges, uint32_t pool_size) {
+    return (size_t)pool_size * 28 + ((size_t)4 * n_bins + 3 * pooled_side_records(block_edges)) * sizeof(uint32_t);
 }
 
 // What a lane of the pooled edge pass has in flight for its next edge (no groups there: one population, no mean field).
@@ -1061,9 +1057,8 @@ __device__ __forceinline__ void issue_pool_edge(const EdgeArgs& P, bool has, int
     if (P.pe) f.pe = P.pe[e];
 }
 
-template <int S, int ROUNDS>
-__global__ void __launch_bounds__(kPoolBlockLanes) k_edges_pooled(const EdgeArgs P, const BinArgs Q) {
-    constexpr int BS = kPoolBlockLanes;
+template <int S, int ROUNDS, int BS>
+__global__ void __launch_bounds__(BS) k_edges_pooled(const EdgeArgs P, const BinArgs Q) {
     constexpr int SS = S > 0 ? S : 1;
     constexpr int NP = kMaxPoolPerLane;
     constexpr int kSide = 2 * (BS / 64) * ROUNDS;    // partial head sums a block can produce
@@ -1293,7 +1288,7 @@ __global__ void k_wg_pools_pooled(int64_t E, int W, int64_t block_edges, uint32_
                                   uint32_t* __restrict__ wg_pool_begin, unsigned long long* __restrict__ total) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     const uint64_t n_blocks = (uint64_t)((E + block_edges - 1) / block_edges) + 1;
-    const uint64_t per_block = (uint64_t)block_edges + 2 * (kPoolBlockLanes / 64) * (uint64_t)(block_edges / kPoolBlockLanes) + pool_size;
+    const uint64_t per_block = (uint64_t)block_edges + pooled_side_records(block_edges) + pool_size;
     const uint64_t blocks = (n_blocks + W - 1) / W;   // blocks first + w, first + w + W, ...
     const uint64_t per_wg = blocks * per_block / kChunk + n_bins + 1;
     for (int w = 0; w <= W; ++w) wg_pool_begin[w] = (uint32_t)min(per_wg * (uint64_t)w, (uint64_t)0xFFFFFFFFull);
