@@ -651,10 +651,10 @@ int nomad_set_embedding(nomad_ctx* c, const float* theta, int mem) {
     if (rc) return rc;
     if (!theta || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return fail(c, NOMAD_E_INVALID_ARG, "null pointer or bad mem");
     HIP_TRY(c, hipSetDevice(c->cfg.device));
+    // on the context's own stream (which may not synchronise with the null stream), and complete on return
+    HIP_TRY(c, hipMemcpyAsync(c->theta, theta, sizeof(float2) * (size_t)c->n, in_kind(mem), c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    HIP_TRY(c, hipMemcpy(c->theta, theta, sizeof(float2) * (size_t)c->n, in_kind(mem)));
-    c->has_theta = true;
-    c->has_grad = false;
+    c->has_theta = true;   // the stored gradient stays that of the most recent epoch
     return NOMAD_OK;
 }
 
