@@ -27,7 +27,8 @@ class _Problem(C.Structure):
                 ("cluster_of", C.c_void_p), ("n_clusters", C.c_int32), ("cluster_group", C.c_void_p),
                 ("n_neg", C.c_int32), ("noise_count", C.c_double), ("seed", C.c_uint64),
                 ("pool_size", C.c_int32), ("pool_block", C.c_int32), ("batches_per_epoch", C.c_int32),
-                ("head_begin", C.c_int64), ("head_end", C.c_int64), ("sampled_far_field", C.c_int32)]
+                ("head_begin", C.c_int64), ("head_end", C.c_int64), ("sampled_far_field", C.c_int32),
+                ("mean_gradient", C.c_int32)]
 
 
 def _load():
@@ -53,7 +54,7 @@ class COracle:
 
     def __init__(self, *, n, row_ptr, col_idx, cluster_of, n_clusters, n_neg, noise_count, seed=0, n_epochs=1,
                  lr0=1.0, weights=None, cluster_group=None, pool_size=0, pool_block=0, batches_per_epoch=1,
-                 sampled_far_field=False, **_ignored):
+                 sampled_far_field=False, mean_gradient=False, **_ignored):
         self.lib = _load()
         self.n = int(n)
         self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
@@ -72,7 +73,10 @@ class COracle:
         assert self.pool_size == 0 or self.cluster_group is None, "the pooled sampler needs a single population"
         self.P = _Problem(self.n, _ptr(self.row_ptr), _ptr(self.col_idx), _ptr(self.weights), _ptr(self.cluster_of),
                           self.n_clusters, _ptr(self.cluster_group), self.n_neg, self.noise_count, self.seed,
-                          self.pool_size, self.pool_block, int(batches_per_epoch), 0, -1, int(bool(sampled_far_field)))
+                          self.pool_size, self.pool_block, int(batches_per_epoch), 0, -1, int(bool(sampled_far_field)),
+                          int(bool(mean_gradient)))
+        assert not (mean_gradient and (sampled_far_field or int(batches_per_epoch) > 1)), \
+            "gradient through the means: exact far field, one step per epoch"
         assert not (sampled_far_field and self.pool_size), "sampled far field and pooled sampler do not combine"
         self.batches_per_epoch = int(batches_per_epoch)
 

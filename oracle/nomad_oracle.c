@@ -46,6 +46,8 @@ typedef struct {
                                   /* head_end < 0 = all heads                                                   */
     int32_t sampled_far_field;    /* opt-in variant of Eq. 5: negatives are drawn from all points; one whose cell is  */
                                   /* approximated for the head enters through the cell mean and receives no force     */
+    int32_t mean_gradient;        /* opt-in: the gradient also flows through mu_r = (1/n_r) sum_{l in r} theta_l: every */
+                                  /* member of cell r receives (1/n_r) d(n L)/d mu_r (full mode, exact far field only)  */
 } oracle_problem;
 
 /* ---- Philox4x32-10 (published algorithm: Salmon, Moraes, Dror, Shaw, SC'11) ---- */
@@ -246,6 +248,9 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
 #endif
     double* gbuf = NULL;
     if (grad) gbuf = (double*)calloc((size_t)nthreads * (size_t)gn * 2, sizeof(double));
+    const int through_means = P->mean_gradient && P->cluster_group && grad;
+    if (through_means && (target_slot || P->sampled_far_field)) { free(counts); free(mu); free(gbuf); free_tables(&T); return -3; }
+    double* mbuf = through_means ? (double*)calloc((size_t)nthreads * (size_t)R * 2, sizeof(double)) : NULL; /* d(nL)/d mu_r */
     double total = 0.0;
     int bad = 0;
 
@@ -256,6 +261,7 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
         tid = omp_get_thread_num();
 #endif
         double* g = gbuf ? gbuf + (size_t)tid * (size_t)gn * 2 : NULL;
+        double* gm = mbuf ? mbuf + (size_t)tid * (size_t)R * 2 : NULL;
         int32_t* m = (int32_t*)malloc(sizeof(int32_t) * (size_t)(s > 0 ? s : 1));
         double* qim = (double*)malloc(sizeof(double) * (size_t)(s > 0 ? s : 1));
         double* nx = (double*)malloc(sizeof(double) * (size_t)(s > 0 ? s : 1));   /* where each negative sits */
@@ -281,6 +287,7 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
                 if (A_out) { A_out[i] = Ai; B_out[2 * i] = Bx; B_out[2 * i + 1] = By; }
             }
             const int head_wanted = !target_slot || target_slot[i] >= 0;
+            double c_head = 0.0; /* sum over the row of 2 p_e / S_e */
             for (int64_t e = ea; e < eb; ++e) {
                 const int64_t j = P->col_idx[e];
                 if (j < 0 || j >= n) {
@@ -333,7 +340,16 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
                     g[2 * si] -= c * Bx;
                     g[2 * si + 1] -= c * By;
                 }
+                c_head += 2.0 * pe / S;
             }
+            if (gm && c_head != 0.0) /* d S_e / d mu_r = |M| p_r 2 q^2 (theta_i - mu_r) for every approximated cell r */
+                for (int32_t r = 0; r < R; ++r) {
+                    if (P->cluster_group[r] == gi || counts[r] == 0) continue;
+                    const double pr = (double)counts[r] / (double)n;
+                    const double q = cauchy(xi, yi, mu[2 * r], mu[2 * r + 1]);
+                    gm[2 * r] += c_head * Mn * pr * q * q * (xi - mu[2 * r]);
+                    gm[2 * r + 1] += c_head * Mn * pr * q * q * (yi - mu[2 * r + 1]);
+                }
         }
         free(m);
         free(qim);
@@ -347,6 +363,19 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
             grad[x] = acc;
         }
         free(gbuf);
+        if (mbuf) {
+            for (int32_t r = 0; r < R; ++r)
+                for (int th = 1; th < nthreads; ++th) {
+                    mbuf[2 * r] += mbuf[(size_t)th * (size_t)R * 2 + 2 * r];
+                    mbuf[2 * r + 1] += mbuf[(size_t)th * (size_t)R * 2 + 2 * r + 1];
+                }
+            for (int64_t l = 0; l < n; ++l) { /* mu_r is the mean of its members: each takes 1/n_r of its gradient */
+                const int32_t r = P->cluster_of[l];
+                grad[2 * l] += mbuf[2 * r] / (double)counts[r];
+                grad[2 * l + 1] += mbuf[2 * r + 1] / (double)counts[r];
+            }
+            free(mbuf);
+        }
     }
     if (loss) *loss = total / (double)n;
     free(counts); free(mu);

@@ -115,6 +115,7 @@ class Problem:
     pool_block: int = 0                       # pooled sampler: consecutive CSR positions that share a pool
     batches_per_epoch: int = 1                # B: sequential sub-steps of an epoch over consecutive head ranges
     sampled_far_field: bool = False           # opt-in: Eq. 5's sum over approximated cells estimated from the samples
+    mean_gradient: bool = False               # opt-in: the gradient also flows through the cell means mu_r(theta)
 
     def __post_init__(self):
         self.row_ptr = np.asarray(self.row_ptr, dtype=np.int64)
@@ -129,6 +130,8 @@ class Problem:
         assert (self.pool_size == 0) == (self.pool_block == 0), "pool_size and pool_block go together"
         assert self.pool_size == 0 or self.cluster_group is None, "the pooled sampler needs a single population"
         assert not (self.sampled_far_field and self.pool_size), "sampled far field and pooled sampler do not combine"
+        assert not (self.sampled_far_field and self.mean_gradient), "gradient through the means needs the exact far field"
+        assert not (self.mean_gradient and self.batches_per_epoch > 1), "sub-steps hold the means of the epoch start constant"
 
     @property
     def n_edges(self) -> int:
@@ -140,7 +143,8 @@ class Problem:
                  n_clusters=w["n_clusters"], n_neg=w["n_neg"], noise_count=w["noise_count"], seed=w["seed"],
                  n_epochs=w["n_epochs"], lr0=w["lr0"], weights=w.get("weights"),
                  cluster_group=w.get("cluster_group"), pool_size=w.get("pool_size", 0), pool_block=w.get("pool_block", 0),
-                 batches_per_epoch=w.get("batches_per_epoch", 1), sampled_far_field=w.get("sampled_far_field", False))
+                 batches_per_epoch=w.get("batches_per_epoch", 1), sampled_far_field=w.get("sampled_far_field", False),
+                 mean_gradient=w.get("mean_gradient", False))
         d.update(over)
         return cls(**d)
 
@@ -310,7 +314,13 @@ def loss_and_grad(P: Problem, theta: np.ndarray, t: int, want_grad: bool = True,
     for the head (another group) enters through the cell mean, q(theta_i, mu_r), and receives no force (the means
     are constants of the epoch); a negative of the head's own group enters as itself.  With m uniform over the
     points, E[(|M|/s) sum_k q_k] = |M| sum_{r in Rtilde} p_r q(theta_i, mu_r) + (|M|/n) sum_{m in own group}
-    q(theta_i, theta_m): Eq. 5 plus the expectation of the sampled term of Eq. 6, with no sum over the cells."""
+    q(theta_i, theta_m): Eq. 5 plus the expectation of the sampled term of Eq. 6, with no sum over the cells.
+
+    Gradient through the means (opt-in; the default holds the means constant): mu_r = (1/n_r) sum_{l in r} theta_l, so
+    every member l of an approximated cell r also receives (1/n_r) d(n L)/d mu_r, with
+    d(n L)/d mu_r = sum_{i: r in Rtilde_i} sum_{e in row i} p_e (|M| p_r / S_e) 2 q(theta_i, mu_r)^2 (theta_i - mu_r).
+    Not defined together with ``mu_fixed`` or a head range whose means come from elsewhere: the means are those
+    of ``theta``."""
     th = _as_positions(theta)
     n, s, Mn = P.n, P.n_neg, float(P.noise_count)
     pe = edge_probabilities(P)
@@ -321,6 +331,7 @@ def loss_and_grad(P: Problem, theta: np.ndarray, t: int, want_grad: bool = True,
     neg = negatives(P, t)
     om = omega(P)
     g = np.zeros((n, 2), dtype=np.float64)
+    G_mu = np.zeros((P.n_clusters, 2), dtype=np.float64)      # d(n L)/d mu_r, used with mean_gradient
     total = 0.0
     h0, h1 = (0, n) if head_range is None else head_range
     grp = P.cluster_group
@@ -355,6 +366,15 @@ def loss_and_grad(P: Problem, theta: np.ndarray, t: int, want_grad: bool = True,
                 if not through_mean(i, m):
                     g[m] += b * d_im
             g[i] -= 2.0 * pe[e] * Mn * B[i] / S
+            if P.mean_gradient and grp is not None:
+                for r in range(P.n_clusters):
+                    if grp[r] != grp[P.cluster_of[i]] and p_r[r] > 0.0:
+                        q = cauchy(th[i], mu[r])
+                        G_mu[r] += pe[e] * (Mn * p_r[r] / S) * 2.0 * q * q * (th[i] - mu[r])
+    if P.mean_gradient and want_grad:
+        counts = np.bincount(P.cluster_of, minlength=P.n_clusters)
+        for l in range(n):
+            g[l] += G_mu[P.cluster_of[l]] / counts[P.cluster_of[l]]
     return total / n, g
 
 

@@ -813,7 +813,7 @@ __device__ __forceinline__ void sort_and_flush(const BinLds& L, const BinArgs& Q
     lds_barrier();
     // ---- consecutive lanes write consecutive sorted records to the chains
     const uint32_t total = L.start[B];
-#pragma unroll
+#pragma nounroll
     for (int it = 0; it < FLUSH_ITERS; ++it) {
         const uint32_t p = (uint32_t)tid + (uint32_t)it * BS;
         if (p < total) {
