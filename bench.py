@@ -52,6 +52,8 @@ def algorithmic_bytes(kernel, n, E, s, R, grouped, weighted, deterministic, pool
         return 8 * n
     if kernel == "mean_field":
         return (8 + 4 + 12) * n
+    if kernel == "mean_gradient":                # per-edge coefficients read back, theta and the row sums of every head
+        return 4 * E + (4 + 8 + 4 + 4) * n
     if kernel == "loss":
         return (4 + w + 8 + 8 * s) * E + (4 + 8 + mf) * n
     raise KeyError(kernel)
@@ -148,6 +150,9 @@ def main():
     ap.add_argument("--hip-graph", action="store_true",
                     help="record the timed epochs into one HIP graph on a side stream and time its replay (shows what the "
                          "launch-bound small configurations cost without per-kernel launches; prints a reduced line)")
+    ap.add_argument("--mean-gradient", action="store_true",
+                    help="let the gradient flow through the cell means (opt-in; grouped configurations); the benchmark "
+                         "holds them constant within an epoch")
     ap.add_argument("--batches", type=int, default=1, help="sub-steps per epoch (minibatch epochs); the benchmark uses 1")
     ap.add_argument("--probe", choices=["copy"], default=None,
                     help="run only the streaming-copy probe (counter calibration / practical HBM ceiling)")
@@ -182,10 +187,11 @@ def main():
         steps = max(1, w.n_epochs - warmup)
     mode = SCATTER_DETERMINISTIC if args.mode == "det" else SCATTER_ATOMIC
     w.sampled_far_field = args.far_field == "sampled"
+    w.mean_gradient = args.mean_gradient
     if args.hip_graph:
         return hip_graph_run(args, torch, Nomad, w, mode, warmup, steps)
     nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode, pool_size=w.pool_size, pool_block=w.pool_block,
-               batches_per_epoch=args.batches, sampled_far_field=w.sampled_far_field)
+               batches_per_epoch=args.batches, sampled_far_field=w.sampled_far_field, mean_gradient=w.mean_gradient)
     t0 = time.time()
     nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None if w.weights is None else w.weights.to(dev), w.cluster_of.to(dev),
                  None if w.cluster_group is None else w.cluster_group.to(dev))
@@ -214,7 +220,7 @@ def main():
             ab = algorithmic_bytes(name, n, E, s, R, grouped, w.weights is not None, mode == SCATTER_DETERMINISTIC, pool)
             kernels[name] = dict(ms=ms / cnt, launches=cnt, algorithmic_gb=ab / 1e9, gbs=ab / (ms / cnt) / 1e6)
     dom = max(kernels, key=lambda k: kernels[k]["ms"])
-    if dom == "mean_field":
+    if dom in ("mean_field", "mean_gradient"):
         # n * |R| kernel evaluations (Eq. 5 and its derivative factor): plain-ALU bound, not HBM bound
         evals = float(n) * float(R)
         flops = MEAN_FIELD_FLOPS * evals
@@ -224,10 +230,10 @@ def main():
         roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s", traffic=None)
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     if args.scale == 1.0 and args.groups is None and pool is None and args.batches == 1 and args.graph == "symmetrised" \
-            and not w.sampled_far_field:
+            and not w.sampled_far_field and not w.mean_gradient:
         roofline["traffic"] = measured_traffic(dom, args.config, args.mode)
     epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, w.weights is not None, mode == SCATTER_DETERMINISTIC, pool) for k in kernels
-                      if k != "mean_field")
+                      if k not in ("mean_field", "mean_gradient"))
     out = {
         "metric": "positive+negative edge updates/sec per epoch at 1 GPU",
         "value": E * (1 + s) / (elapsed / steps),
@@ -240,7 +246,8 @@ def main():
                    "batches_per_epoch": args.batches,
                    "sampler": "iid per edge" if pool is None else f"pooled, {pool[0]} points per block of {pool[1]} edges (opt-in variant)",
                    "far_field": "Eq. 5 summed over the approximated cells" if not w.sampled_far_field else
-                                "estimated from the samples (opt-in variant)"},
+                                "estimated from the samples (opt-in variant)",
+                   "means": "constants of the epoch" if not w.mean_gradient else "differentiated (opt-in variant)"},
         "edges_per_sec": E / (elapsed / steps),
         "epoch_model_gb": epoch_bytes / 1e9,
         "epoch_hbm_frac_model": epoch_bytes / (elapsed / steps) / 1e9 / HBM_PEAK_GBS,

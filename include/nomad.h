@@ -72,7 +72,19 @@ typedef struct {
                                /* must be 0 exactly when pool_size is 0                               */
     int32_t far_field;         /* NOMAD_FAR_FIELD_EXACT (Eq. 5 summed over the approximated cells) or    */
                                /* NOMAD_FAR_FIELD_SAMPLED (opt-in estimate of it, see below)            */
+    int32_t mean_gradient;     /* 0: the cell means are constants of an epoch (no gradient flows through */
+                               /* them); 1: opt-in, see below                                            */
 } nomad_config;
+
+/*
+ * Gradient through the means (opt-in; needs far_field = NOMAD_FAR_FIELD_EXACT and batches_per_epoch = 1; has no
+ * effect without cluster_group).  mu_r below Eq. 6 is the mean of the cell's members, mu_r = (1/n_r) sum_{l in r}
+ * theta_l.  With mean_gradient = 1 the gradient of Eq. 4 also flows through it: every member l of a cell r receives
+ * (1/n_r) d(n L)/d mu_r, where d(n L)/d mu_r = |M| p_r sum_{i: r approximated for i} c_i q(theta_i, mu_r)^2
+ * (theta_i - mu_r) and c_i = sum_{e in row i} 2 p_e / S_e.  The gradient is then the derivative of the sampled loss
+ * as a function of the embedding alone (forces cancel, no net torque).  Costs a second pass over all (head, cell)
+ * pairs per epoch.
+ */
 
 /*
  * Sampled far field (opt-in variant; needs pool_size = 0).  Eq. 5 replaces the points of the approximated cells
@@ -183,7 +195,8 @@ int64_t nomad_num_edges(const nomad_ctx* ctx);
 #define NOMAD_K_LOSS 5       /* loss terms + reduction             */
 #define NOMAD_K_ZERO 6       /* clearing of accumulators           */
 #define NOMAD_K_TILES 7      /* per-tile accumulation of the binned forces */
-#define NOMAD_K_COUNT 8
+#define NOMAD_K_MEANGRAD 8   /* gradient through the means: head coefficients, sum over heads per cell */
+#define NOMAD_K_COUNT 9
 
 /* Switch per-launch timing on (1) or off (0); switching on clears earlier samples. */
 int nomad_profile(nomad_ctx* ctx, int enable);

@@ -17,7 +17,7 @@ NOMAD_HOST, NOMAD_DEVICE = 0, 1
 SCATTER_DETERMINISTIC, SCATTER_ATOMIC = 0, 1
 FAR_FIELD_EXACT, FAR_FIELD_SAMPLED = 0, 1
 K_MEANS, K_MEANFIELD, K_EDGES, K_SCATTER, K_UPDATE, K_LOSS, K_ZERO, K_TILES = range(8)
-KERNEL_NAMES = ["means", "mean_field", "edges", "scatter", "update", "loss", "zero", "tiles"]
+KERNEL_NAMES = ["means", "mean_field", "edges", "scatter", "update", "loss", "zero", "tiles", "mean_gradient"]
 ERRORS = {-1: "NOMAD_E_INVALID_ARG", -2: "NOMAD_E_BAD_GRAPH", -3: "NOMAD_E_ORDER", -4: "NOMAD_E_TOO_LARGE",
           -5: "NOMAD_E_OOM", -6: "NOMAD_E_HIP"}
 
@@ -31,7 +31,8 @@ class NomadConfig(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("n_points", C.c_int64), ("n_clusters", C.c_int32), ("n_neg", C.c_int32),
                 ("noise_count", C.c_float), ("n_epochs", C.c_int32), ("lr0", C.c_float), ("seed", C.c_uint64),
                 ("scatter_mode", C.c_int32), ("batches_per_epoch", C.c_int32), ("device", C.c_int32),
-                ("stream", C.c_void_p), ("pool_size", C.c_int32), ("pool_block", C.c_int32), ("far_field", C.c_int32)]
+                ("stream", C.c_void_p), ("pool_size", C.c_int32), ("pool_block", C.c_int32), ("far_field", C.c_int32),
+                ("mean_gradient", C.c_int32)]
 
 
 class NomadError(RuntimeError):
@@ -118,7 +119,7 @@ class Nomad:
 
     def __init__(self, n_points, n_clusters, n_neg, noise_count=0.0, n_epochs=1, lr0=1.0, seed=0,
                  scatter_mode=SCATTER_DETERMINISTIC, device=0, stream=None, pool_size=0, pool_block=0, batches_per_epoch=1,
-                 sampled_far_field=False):
+                 sampled_far_field=False, mean_gradient=False):
         self.lib = load_library()
         if stream is None:
             import torch
@@ -126,7 +127,7 @@ class Nomad:
         self.cfg = NomadConfig(C.sizeof(NomadConfig), int(n_points), int(n_clusters), int(n_neg), float(noise_count),
                                int(n_epochs), float(lr0), int(seed), int(scatter_mode), int(batches_per_epoch), int(device),
                                C.c_void_p(int(stream) if stream else None), int(pool_size), int(pool_block),
-                               FAR_FIELD_SAMPLED if sampled_far_field else FAR_FIELD_EXACT)
+                               FAR_FIELD_SAMPLED if sampled_far_field else FAR_FIELD_EXACT, int(bool(mean_gradient)))
         self.n, self.R, self.s = int(n_points), int(n_clusters), int(n_neg)
         self.device = int(device)
         self.ctx = C.c_void_p()
@@ -141,7 +142,8 @@ class Nomad:
                   n_epochs=w.n_epochs, lr0=w.lr0, seed=w.seed, scatter_mode=scatter_mode, device=device,
                   pool_size=getattr(w, "pool_size", 0), pool_block=getattr(w, "pool_block", 0),
                   batches_per_epoch=getattr(w, "batches_per_epoch", 1),
-                  sampled_far_field=getattr(w, "sampled_far_field", False))
+                  sampled_far_field=getattr(w, "sampled_far_field", False),
+                  mean_gradient=getattr(w, "mean_gradient", False))
         kw.update(over)
         nm = cls(**kw)
         nm.set_graph(w.row_ptr, w.col_idx, w.weights, w.cluster_of, w.cluster_group)

@@ -50,6 +50,11 @@ struct nomad_ctx {
     int2* group_slots = nullptr;    // grouped: slot range [lo, hi) of each group's cells
     float* A = nullptr;
     unsigned long long* gfix = nullptr;
+    // gradient through the means (opt-in, grouped graphs)
+    bool through_means = false;
+    float *cS = nullptr, *chead = nullptr;   // 2 p_e / S_e per edge, its row sums
+    unsigned long long* Gfix = nullptr;      // [2 R] fixed-point sums over the heads, per cell
+    float2* gmean = nullptr;                 // [R] what every member of a cell adds to its gradient
     // binned deterministic scatter
     bool binned = false;
     int n_wg = 0, bin_block = 1024;
@@ -112,6 +117,8 @@ void free_graph(nomad_ctx* c) {
     dev_free(c->theta); dev_free(c->g); dev_free(c->ghead); dev_free(c->mu); dev_free(c->B); dev_free(c->cinfo);
     dev_free(c->cell_slot); dev_free(c->group_slots);
     dev_free(c->A); dev_free(c->gfix); dev_free(c->loss_partial); dev_free(c->loss_out);
+    dev_free(c->cS); dev_free(c->chead); dev_free(c->Gfix); dev_free(c->gmean);
+    c->through_means = false;
     dev_free(c->flags);
     dev_free(c->pool); dev_free(c->chunk_prev); dev_free(c->chain_head); dev_free(c->chain_fill); dev_free(c->wg_pool_begin);
     dev_free(c->head); dev_free(c->overflow);
@@ -183,6 +190,7 @@ EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
     a.pool_size = (uint32_t)c->cfg.pool_size; a.pool_block = (uint32_t)c->cfg.pool_block;
     a.s = c->cfg.n_neg; a.n = c->n; a.row_begin = 0; a.row_end = c->n;
     a.g = c->g; a.ghead = c->ghead; a.gfix = c->gfix; a.loss_partial = c->loss_partial;
+    a.cS = nullptr;   // set by nomad_epoch when the gradient flows through the means
     return a;
 }
 
@@ -291,6 +299,23 @@ int run_mean_field(nomad_ctx* c, int64_t row_begin, int64_t row_end) {
     return NOMAD_OK;
 }
 
+// Gradient through the means: c_i of the heads of this step from the edge pass's per-edge values, the sum over
+// those heads for every cell, and the vector every member of a cell adds to its gradient.
+int run_mean_gradient(nomad_ctx* c, int64_t row_begin, int64_t row_end) {
+    if (!c->through_means) return NOMAD_OK;
+    Timed tm(c, NOMAD_K_MEANGRAD);
+    if (row_end > row_begin) {
+        hipLaunchKernelGGL(k_head_coefficients, dim3(blocks_for(row_end - row_begin)), dim3(kBlock), 0, c->stream, c->row_ptr, c->cS,
+                           row_begin, row_end, c->chead);
+        const dim3 grid(blocks_for(c->R), blocks_for(row_end - row_begin, kMeanGradHeads));
+        hipLaunchKernelGGL(k_mean_gradient, grid, dim3(kBlock), 0, c->stream, c->theta, c->chead, c->hinfo, c->mu, c->group_of_cluster,
+                           c->R, row_begin, row_end, c->Gfix);
+    }
+    hipLaunchKernelGGL(k_mean_gradient_finish, dim3(blocks_for(c->R)), dim3(kBlock), 0, c->stream, c->Gfix, c->counts, c->R,
+                       (double)c->noise_count / (double)c->n, c->gmean);
+    return NOMAD_OK;
+}
+
 int check_ready(nomad_ctx* c, bool need_theta) {
     if (!c) return NOMAD_E_INVALID_ARG;
     if (!c->has_graph) return fail(c, NOMAD_E_ORDER, "no graph: call nomad_set_graph first");
@@ -325,6 +350,9 @@ int nomad_create(const nomad_config* cfg, nomad_ctx** out) {
         return NOMAD_E_INVALID_ARG;
     if ((cfg->far_field != NOMAD_FAR_FIELD_EXACT && cfg->far_field != NOMAD_FAR_FIELD_SAMPLED) ||
         (cfg->far_field == NOMAD_FAR_FIELD_SAMPLED && cfg->pool_size > 0))
+        return NOMAD_E_INVALID_ARG;
+    if ((cfg->mean_gradient != 0 && cfg->mean_gradient != 1) ||
+        (cfg->mean_gradient && (cfg->far_field == NOMAD_FAR_FIELD_SAMPLED || cfg->batches_per_epoch > 1)))
         return NOMAD_E_INVALID_ARG;
     if (cfg->n_points >= ((int64_t)1 << 31) || cfg->n_clusters > cfg->n_points) return cfg->n_points >= ((int64_t)1 << 31) ? NOMAD_E_TOO_LARGE : NOMAD_E_INVALID_ARG;
     int ndev = 0;
@@ -532,6 +560,15 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                            c->gcount, c->gomega, n, c->hinfo);
         TRY(dev_alloc(c, &c->A, (size_t)n));
         TRY(dev_alloc(c, &c->B, (size_t)n));
+        if (c->cfg.mean_gradient) {
+            c->through_means = true;
+            TRY(dev_alloc(c, &c->cS, (size_t)E));
+            TRY(dev_alloc(c, &c->chead, (size_t)n));
+            TRY(dev_alloc(c, &c->Gfix, (size_t)R * 2));
+            TRY(dev_alloc(c, &c->gmean, (size_t)R));
+            HTRY(hipMemsetAsync(c->Gfix, 0, sizeof(unsigned long long) * 2 * (size_t)R, st));
+            HTRY(hipMemsetAsync(c->cS, 0, sizeof(float) * (size_t)std::max<int64_t>(E, 1), st));
+        }
         // cell table ordered group by group (stable in the cell id): the mean-field pass skips a head's own
         // group as one slot range
         std::vector<int32_t> gcells(R, 0), slot(R);
@@ -678,12 +715,15 @@ int nomad_epoch(nomad_ctx* c, int32_t t) {
         EdgeArgs a = edge_args(c, (uint32_t)t);
         a.row_begin = r0;
         a.row_end = r1;
+        if (c->through_means) a.cS = c->cS;
         if (c->cfg.scatter_mode == NOMAD_SCATTER_DETERMINISTIC && c->binned) {
             { Timed tm(c, NOMAD_K_EDGES);
               launch_edges_binned(c, a, e0, e1); }
+            run_mean_gradient(c, r0, r1);
             { Timed tm(c, NOMAD_K_TILES);   // accumulates the records of every tile and takes the SGD step for its points
               hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 << c->tile_bits,
-                                 c->stream, bin_args(c), (uint32_t)c->n_wg, c->g, n, c->theta, eta); }
+                                 c->stream, bin_args(c), (uint32_t)c->n_wg, c->g, n, c->theta, eta,
+                                 c->through_means ? c->cluster_of : nullptr, c->through_means ? c->gmean : nullptr); }
             continue;
         }
         if (c->cfg.scatter_mode == NOMAD_SCATTER_ATOMIC) {
@@ -696,6 +736,11 @@ int nomad_epoch(nomad_ctx* c, int32_t t) {
               launch_edges<kModeDet>(c, a); }
             { Timed tm(c, NOMAD_K_SCATTER);
               hipLaunchKernelGGL(k_combine_fixed, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->ghead, c->gfix, c->g, n); }
+        }
+        if (c->through_means) {
+            run_mean_gradient(c, r0, r1);
+            Timed tm(c, NOMAD_K_MEANGRAD);
+            hipLaunchKernelGGL(k_add_mean_gradient, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->g, c->cluster_of, c->gmean, n);
         }
         { Timed tm(c, NOMAD_K_UPDATE);
           hipLaunchKernelGGL(k_update, dim3(blocks_for(n)), dim3(kBlock), 0, c->stream, c->theta, c->g, eta, n); }

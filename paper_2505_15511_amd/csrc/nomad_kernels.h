@@ -360,6 +360,7 @@ struct EdgeArgs {
     float2* ghead;                 // deterministic mode: head-side sums
     unsigned long long* gfix;      // deterministic fallback: fixed-point sums of tail and negative forces [n*2]
     double* loss_partial;          // loss mode: one partial per block
+    float* cS;                     // gradient through the means: 2 p_e / S_e of every edge, or nullptr
 };
 
 enum EdgeMode { kModeAtomic = 0, kModeDet = 1, kModeLoss = 2 };
@@ -413,6 +414,7 @@ __device__ __forceinline__ HeadCtx load_head(const EdgeArgs& P, int64_t i, int32
 template <int S>
 struct EdgeOut {
     float a, dx, dy, hx, hy, log_term;
+    float c;              // 2 p_e / S_e: what the edge multiplies d S_e / d(anything) with
     int32_t j;
     int32_t m[S];
     float rx[S], ry[S];
@@ -452,9 +454,9 @@ __device__ __forceinline__ void edge_math(const HeadCtx& h, float pe, float2 tj,
         fx -= o.rx[k];
         fy -= o.ry[k];
     }
-    const float c = 2.0f * pe * inv_S;
-    o.hx = fx - c * h.MBx;
-    o.hy = fy - c * h.MBy;
+    o.c = 2.0f * pe * inv_S;
+    o.hx = fx - o.c * h.MBx;
+    o.hy = fy - o.c * h.MBy;
 }
 
 // Pooled sampler: pool entry of slot k given the four words of the per-edge Philox call k >> 3
@@ -570,6 +572,7 @@ __device__ __forceinline__ void edge_terms_dynamic(const EdgeArgs& P, const Head
     const float c = 2.0f * pe * inv_S;
     hx = fx - c * h.MBx;
     hy = fy - c * h.MBy;
+    if (P.cS) P.cS[e] = c;
 }
 
 __device__ __forceinline__ void add_fixed(unsigned long long* gfix, int64_t m, float rx, float ry) {
@@ -599,6 +602,7 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
                 edge_terms<SS, MODE == kModeLoss>(P, h, e, o);
                 if (MODE == kModeLoss) { lsum += (double)o.log_term; continue; }
                 a = o.a; dx = o.dx; dy = o.dy; ehx = o.hx; ehy = o.hy;
+                if (P.cS) P.cS[e] = o.c;
 #pragma unroll
                 for (int k = 0; k < SS; ++k) {
                     if (o.m[k] < 0) continue;   // stood for a cell mean: no force
@@ -991,6 +995,7 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
             edge_math<S, false>(f.h, f.pe, f.tj, f.tm, o);
             hx = o.hx;
             hy = o.hy;
+            if (P.cS) P.cS[f.e] = o.c;
             dst_pt[0] = (uint32_t)f.j; fx[0] = -o.a * o.dx; fy[0] = -o.a * o.dy;
 #pragma unroll
             for (int k = 0; k < S; ++k) {
@@ -1302,10 +1307,104 @@ __global__ void __launch_bounds__(kBlock) k_edge_heads(const int32_t* __restrict
     for (int32_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) head[e] = (int32_t)i;
 }
 
+// ------------------------------------------------------------------ opt-in: gradient through the cell means
+// mu_r = (1/n_r) sum_{l in r} theta_l.  d(n L)/d mu_r = |M| p_r sum_{i: r approximated for i} c_i q(theta_i, mu_r)^2
+// (theta_i - mu_r) with c_i = sum_{e in row i} 2 p_e / S_e (Eq. 4 with Eq. 5 differentiated in mu_r), and every
+// member of cell r receives 1/n_r of it.  Three steps: c_i from the edge pass's per-edge values (row order), the
+// sum over heads for every cell (the mean-field pass with the roles of heads and cells exchanged), the per-cell
+// vector that the tile pass adds to its points.
+
+// c_i of the heads row_begin .. row_end-1: the row's values added in CSR order
+__global__ void __launch_bounds__(kBlock) k_head_coefficients(const int32_t* __restrict__ row_ptr, const float* __restrict__ cS,
+                                                             int64_t row_begin, int64_t row_end, float* __restrict__ chead) {
+    const int64_t i = row_begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= row_end) return;
+    float c = 0.f;
+    for (int32_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) c += cS[e];
+    chead[i] = c;
+}
+
+// 2^-24 fixed point for the per-cell sums (the sums over up to n heads can be large; what is left after the division
+// by n_r is far below the gradient's resolution)
+constexpr double kCellFixInv = 1.0 / 16777216.0;
+__device__ __forceinline__ unsigned long long to_cell_fixed(float v) {
+    const double d = fma((double)v, 16777216.0, 6755399441055744.0);
+    return (unsigned long long)(__double_as_longlong(d) - 0x4338000000000000LL);
+}
+
+constexpr int kMeanGradHeads = 16384;   // heads per workgroup
+
+// One lane per cell, the heads of the workgroup's chunk staged through LDS 256 at a time:
+// Gfix[r] += sum_i [group(i) != group(r)] c_i q(theta_i, mu_r)^2 (theta_i - mu_r), in fixed point (order-independent).
+__global__ void __launch_bounds__(kBlock) k_mean_gradient(const float2* __restrict__ theta, const float* __restrict__ chead,
+                                                         const float4* __restrict__ hinfo, const float2* __restrict__ mu,
+                                                         const int32_t* __restrict__ group_of_cluster, int32_t R, int64_t i_begin,
+                                                         int64_t i_end, unsigned long long* __restrict__ Gfix) {
+    __shared__ float4 heads[kBlock];   // (theta_i, c_i, group of i)
+    const int32_t r = (int32_t)blockIdx.x * kBlock + threadIdx.x;
+    const bool live = r < R;
+    const float2 m = live ? mu[r] : make_float2(0.f, 0.f);
+    const int32_t gr = live ? group_of_cluster[r] : -1;
+    const int64_t h0 = i_begin + (int64_t)blockIdx.y * kMeanGradHeads, h1 = min(i_end, h0 + kMeanGradHeads);
+    float Gx = 0.f, Gy = 0.f;
+    for (int64_t b0 = h0; b0 < h1; b0 += kBlock) {
+        __syncthreads();
+        const int64_t i = b0 + threadIdx.x;
+        float4 hd = make_float4(0.f, 0.f, 0.f, __int_as_float(-1));
+        if (i < h1) {
+            const float2 t = theta[i];
+            hd = make_float4(t.x, t.y, chead[i], hinfo[i].w);
+        }
+        heads[threadIdx.x] = hd;
+        __syncthreads();
+        const int cnt = (int)min((int64_t)kBlock, h1 - b0);
+        float sx = 0.f, sy = 0.f;   // folded into the totals every 256 heads to keep float32 round-off from growing
+        for (int k = 0; k < cnt; ++k) {
+            const float4 hk = heads[k];
+            const float dx = hk.x - m.x, dy = hk.y - m.y;
+            const float q = cauchy(dx, dy);
+            const float w = (__float_as_int(hk.w) == gr) ? 0.f : hk.z * q * q;
+            sx = fmaf(w, dx, sx);
+            sy = fmaf(w, dy, sy);
+        }
+        Gx += sx;
+        Gy += sy;
+    }
+    if (live && (Gx != 0.f || Gy != 0.f)) {
+        atomicAdd(&Gfix[2 * r], to_cell_fixed(Gx));
+        atomicAdd(&Gfix[2 * r + 1], to_cell_fixed(Gy));
+    }
+}
+
+// gmean[r] = |M| p_r G_r / n_r: what every member of cell r adds to its gradient; the sums are cleared for the next use
+__global__ void __launch_bounds__(kBlock) k_mean_gradient_finish(unsigned long long* __restrict__ Gfix, const uint32_t* __restrict__ counts,
+                                                                int32_t R, double noise_over_n, float2* __restrict__ gmean) {
+    const int32_t r = (int32_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= R) return;
+    const double gx = (double)(long long)Gfix[2 * r] * kCellFixInv, gy = (double)(long long)Gfix[2 * r + 1] * kCellFixInv;
+    Gfix[2 * r] = 0ull;
+    Gfix[2 * r + 1] = 0ull;
+    // |M| p_r / n_r = |M| / n for every non-empty cell
+    gmean[r] = counts[r] ? make_float2((float)(gx * noise_over_n), (float)(gy * noise_over_n)) : make_float2(0.f, 0.f);
+}
+
+// g_l += gmean[cell of l] (the scatter paths whose last kernel does not take the step itself)
+__global__ void __launch_bounds__(kBlock) k_add_mean_gradient(float2* __restrict__ g, const int32_t* __restrict__ cluster_of,
+                                                             const float2* __restrict__ gmean, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float2 m = gmean[cluster_of[i]];
+    float2 v = g[i];
+    v.x += m.x;
+    v.y += m.y;
+    g[i] = v;
+}
+
 // With `theta` given it also takes the SGD step of Section 3.4 for its points, theta <- theta - eta g (the
 // edge pass that read theta has finished by then).
 __global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const BinArgs Q, uint32_t n_wg, float2* __restrict__ g, int64_t n,
-                                                              float2* __restrict__ theta, float eta) {
+                                                              float2* __restrict__ theta, float eta,
+                                                              const int32_t* __restrict__ cluster_of, const float2* __restrict__ gmean) {
     extern __shared__ unsigned long long acc[];   // [2 << tile_bits]
     constexpr int kPerLane = kChunk / 64;         // records one lane takes from a full chunk
     constexpr int kBatch = 8;                     // loads in flight per lane
@@ -1347,8 +1446,13 @@ __global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const BinArgs Q, 
     for (int l = threadIdx.x; l < tile && p0 + l < n; l += kBinBlock) {
         const float2 hd = Q.ghead[p0 + l];
         Q.ghead[p0 + l] = make_float2(0.f, 0.f);   // consumed: rows that hand their head sum on as records rely on this
-        const float2 gi = make_float2((float)((double)hd.x + (double)(long long)acc[2 * l] * kFixInv),
-                                      (float)((double)hd.y + (double)(long long)acc[2 * l + 1] * kFixInv));
+        float2 gi = make_float2((float)((double)hd.x + (double)(long long)acc[2 * l] * kFixInv),
+                                (float)((double)hd.y + (double)(long long)acc[2 * l + 1] * kFixInv));
+        if (gmean) {   // gradient through the means: every member's share of its cell's term
+            const float2 gm = gmean[cluster_of[p0 + l]];
+            gi.x += gm.x;
+            gi.y += gm.y;
+        }
         g[p0 + l] = gi;
         if (theta) {
             float2 t = theta[p0 + l];

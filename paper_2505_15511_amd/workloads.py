@@ -52,6 +52,7 @@ class Workload:
     pool_block: int = 0            # opt-in pooled sampler: consecutive CSR positions sharing a pool
     batches_per_epoch: int = 1     # sequential sub-steps of an epoch over consecutive head ranges
     sampled_far_field: bool = False   # opt-in: the sum over approximated cells estimated from the samples
+    mean_gradient: bool = False       # opt-in: the gradient also flows through the cell means
 
     @property
     def n_edges(self) -> int:
@@ -66,6 +67,7 @@ class Workload:
             theta0=h(self.theta0), n_neg=self.n_neg, noise_count=self.noise_count,
             n_epochs=self.n_epochs, lr0=self.lr0, seed=self.seed, pool_size=self.pool_size, pool_block=self.pool_block,
             batches_per_epoch=self.batches_per_epoch, sampled_far_field=self.sampled_far_field,
+            mean_gradient=self.mean_gradient,
         )
 
 

@@ -39,11 +39,11 @@ def test_only_the_abi_is_exported():
 
 
 def test_config_struct_layout_matches_header():
-    # uint32 | int64 | int32 int32 | float int32 | float (pad) | uint64 | int32 int32 | int32 (pad) | void* | int32 int32 | int32 (pad)
+    # uint32 | int64 | int32 int32 | float int32 | float (pad) | uint64 | int32 int32 | int32 (pad) | void* | int32 int32 | int32 int32
     assert C.sizeof(binding.NomadConfig) == 88
     assert binding.NomadConfig.seed.offset == 40 and binding.NomadConfig.stream.offset == 64
     assert binding.NomadConfig.pool_size.offset == 72 and binding.NomadConfig.pool_block.offset == 76
-    assert binding.NomadConfig.far_field.offset == 80
+    assert binding.NomadConfig.far_field.offset == 80 and binding.NomadConfig.mean_gradient.offset == 84
 
 
 def test_argument_errors_before_any_device_work(lib):
@@ -56,7 +56,7 @@ def test_argument_errors_before_any_device_work(lib):
     cfg.struct_size = C.sizeof(binding.NomadConfig)
     for field, bad in (("n_points", 0), ("n_clusters", 0), ("n_neg", 17), ("n_neg", -1), ("n_epochs", 0),
                        ("scatter_mode", 2), ("batches_per_epoch", 0), ("batches_per_epoch", 4097), ("lr0", float("nan")),
-                       ("n_clusters", 11), ("pool_size", 4097), ("pool_size", 64), ("far_field", 2), ("far_field", -1)):
+                       ("n_clusters", 11), ("pool_size", 4097), ("pool_size", 64), ("far_field", 2), ("far_field", -1), ("mean_gradient", 2)):
         good = getattr(cfg, field)
         setattr(cfg, field, bad)
         assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1, field
@@ -64,6 +64,11 @@ def test_argument_errors_before_any_device_work(lib):
     cfg.pool_size, cfg.pool_block, cfg.far_field = 64, 1024, 1      # the sampled far field has no pooled form
     assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1
     cfg.pool_size, cfg.pool_block, cfg.far_field = 0, 0, 0
+    cfg.mean_gradient, cfg.far_field = 1, 1                           # gradient through the means: exact far field only
+    assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1
+    cfg.far_field, cfg.batches_per_epoch = 0, 2                       # ... and one step per epoch
+    assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1
+    cfg.mean_gradient, cfg.batches_per_epoch = 0, 1
     cfg.n_points = 2 ** 31
     assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -4
     assert not ctx.value

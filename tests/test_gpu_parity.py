@@ -55,7 +55,8 @@ def small_random(seed, n=3000, R=12, groups=True, weights=True, contiguous=False
 def make_nomad(d, mode):
     nm = Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
                pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0),
-               batches_per_epoch=d.get("batches_per_epoch", 1), sampled_far_field=d.get("sampled_far_field", False))
+               batches_per_epoch=d.get("batches_per_epoch", 1), sampled_far_field=d.get("sampled_far_field", False),
+               mean_gradient=d.get("mean_gradient", False))
     nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
     nm.set_embedding(d["theta0"])
     return nm
@@ -548,3 +549,43 @@ def test_sampled_far_field_estimates_the_exact_far_field_loss():
         L_far = np.mean([far.loss(t) for t in range(20)])
     note(f"loss with exact far field {L_exact:.5f}, sampled {L_far:.5f}")
     assert abs(L_far - L_exact) < 0.02 * L_exact
+
+
+# ------------------------------------------------------------------ gradient through the cell means (opt-in)
+def _mean_gradient_cases():
+    yield "random-groups", dict(small_random(70, n=5000, s=3), mean_gradient=True)
+    yield "random-groups-s11", dict(small_random(71, n=3000, s=11, weights=False), mean_gradient=True)          # run-time s path
+    yield "config5@1e-3", dict(workload(5, 1e-3).numpy(), mean_gradient=True)                                    # every cluster its own group
+    yield "config4@5e-3-8groups", dict(workload(4, 5e-3, n_groups=8).numpy(), mean_gradient=True)
+    yield "no-groups", dict(small_random(72, groups=False, s=4), mean_gradient=True)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("case", [c for c, _ in _mean_gradient_cases()])
+def test_gradient_through_the_means_matches_the_oracle(case, mode):
+    d = dict(_mean_gradient_cases())[case]
+    note(f"gradient through the means {case}")
+    O = c_oracle.COracle(**d)
+    g_const = None
+    with make_nomad(d, mode) as nm:
+        th = np.asarray(d["theta0"], dtype=np.float32)
+        if case != "no-groups":                # spread the points so that the means' term is not negligible
+            th = (np.random.default_rng(7).normal(size=th.shape) * 1.5).astype(np.float32)
+            nm.set_embedding(th)
+        for t in range(3):           # three epochs, each checked from the library's own embedding
+            th_ref, g_ref, _ = O.epoch(th, t)
+            nm.epoch(t)
+            g = nm.get_gradient()
+            assert grad_err(g, g_ref) < GRAD_TOL, t
+            if d["cluster_group"] is not None:
+                assert np.abs(g.astype(np.float64).sum(0)).max() < 1e-4 * np.abs(g_ref).max() * np.sqrt(d["n"])   # forces cancel
+            th_new = nm.get_embedding()
+            assert np.abs(th_new - th_ref).max() < 1e-5 * max(1.0, np.abs(th_ref).max())
+            th = th_new
+    if d["cluster_group"] is not None:         # and the term is there: the default gradient differs
+        with make_nomad(dict(d, mean_gradient=False), mode) as nm:
+            nm.set_embedding(th)
+            nm.epoch(3)
+            g_const = nm.get_gradient()
+        _, g_ref, _ = O.epoch(th, 3)
+        assert grad_err(g_const, g_ref) > 1e-4

@@ -14,7 +14,7 @@ GRAD_TOL = 1e-5
 
 def random_case(seed):
     """Directed graph with a skewed degree distribution (isolated points, rows of one edge, a few hubs), optional
-    weights, clusters in arbitrary point order, optional groups (with the far field summed or sampled), any s, optional
+    weights, clusters in arbitrary point order, optional groups (with the far field summed or sampled, the means constant or differentiated), any s, optional
     pooled sampler and minibatches."""
     rng = np.random.default_rng(seed)
     n = int(rng.choice([1, 2, 3, 17, 64, 65, 300, 1025, 4000, 9000]))
@@ -44,6 +44,8 @@ def random_case(seed):
         d["pool_size"], d["pool_block"] = [(1, 1024), (37, 50), (512, 1024), (2048, 4096), (4096, 2048), (300, 8192)][int(rng.integers(6))]
     if grouped and rng.random() < 0.5:
         d["sampled_far_field"] = True
+    elif grouped and d["batches_per_epoch"] == 1 and rng.random() < 0.5:
+        d["mean_gradient"] = True
     return d
 
 
@@ -55,7 +57,7 @@ def test_random_case_against_the_oracle(seed, mode):
     th_ref, g_ref, _ = O.epoch(d["theta0"], 1)
     with Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
                pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0), batches_per_epoch=d["batches_per_epoch"],
-               sampled_far_field=d.get("sampled_far_field", False)) as nm:
+               sampled_far_field=d.get("sampled_far_field", False), mean_gradient=d.get("mean_gradient", False)) as nm:
         nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
         nm.set_embedding(d["theta0"])
         if d["n_neg"] and len(d["col_idx"]):
