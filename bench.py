@@ -92,6 +92,35 @@ def copy_probe_gbs(torch, gib=4, steps=10):
     return dict(probe="copy", bytes_read=nbytes, bytes_written=nbytes, ms=ms, gbs_read_plus_write=2 * nbytes / ms / 1e6)
 
 
+def knn_index_run(args, torch, workloads):
+    """nomad_knn_in_clusters on an equal-weight Gaussian mixture, clusters = components, data resident on the device.
+    Reports point pairs per second of the whole call and the float32 matrix-core rate of its contraction."""
+    from paper_2505_15511_amd import knn_in_clusters
+    n, d, R, k = args.index_n, args.index_d, args.index_clusters, args.index_k
+    X, c = workloads.gmm_points(n, d, R, 16.0, 4242, mix="equal", interleave=True)
+    X, c = X.cuda(), c.cuda()
+    torch.cuda.synchronize()
+    times = []
+    st = None
+    for rep in range(args.warmup + args.steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out, st = knn_in_clusters(X, c, R, k, return_stats=True)
+        torch.cuda.synchronize()
+        if rep >= args.warmup:
+            times.append(time.perf_counter() - t0)
+    dt = sum(times) / len(times)
+    flops = 2.0 * d * st["filter_pairs"]
+    print(json.dumps({
+        "metric": "in-cluster exact kNN, point pairs/sec at 1 GPU", "value": st["filter_pairs"] / dt, "unit": "pairs/s", "n_gpus": 1,
+        "steps": len(times), "warmup": args.warmup, "ms_per_step": 1e3 * dt, "higher_is_better": True, "dtype": "f32 filter, f64 decision",
+        "data": "synthetic",
+        "config": {"workload": f"Gaussian mixture n={n}, d={d}, {R} equal clusters, k={k}"},
+        "fallback_queries": st["fallback_queries"],
+        "roofline": {"bound": "mfma", "kernel": "knn_filter (whole call timed: grouping, norms, filter, refinement)",
+                     "achieved": flops / dt / 1e12, "peak": 157.3, "unit": "TFLOP/s", "frac": flops / dt / 1e12 / 157.3, "traffic": None}}))
+
+
 def hip_graph_run(args, torch, Nomad, w, mode, warmup, steps):
     """The timed epochs recorded once into a HIP graph (nomad_epoch only enqueues kernels on the caller's stream) and
     replayed: one graph launch for 2 x steps kernels."""
@@ -153,6 +182,13 @@ def main():
     ap.add_argument("--mean-gradient", action="store_true",
                     help="let the gradient flow through the cell means (opt-in; grouped configurations); the benchmark "
                          "holds them constant within an epoch")
+    ap.add_argument("--index", choices=["knn"], default=None,
+                    help="knn: time nomad_knn_in_clusters (the upstream index of Section 3.2) on a Gaussian mixture of "
+                         "--index-n points in --index-d dimensions and --index-clusters clusters instead of the epoch path")
+    ap.add_argument("--index-n", type=int, default=1_000_000)
+    ap.add_argument("--index-d", type=int, default=128)
+    ap.add_argument("--index-clusters", type=int, default=256)
+    ap.add_argument("--index-k", type=int, default=15)
     ap.add_argument("--batches", type=int, default=1, help="sub-steps per epoch (minibatch epochs); the benchmark uses 1")
     ap.add_argument("--probe", choices=["copy"], default=None,
                     help="run only the streaming-copy probe (counter calibration / practical HBM ceiling)")
@@ -172,6 +208,8 @@ def main():
     if args.probe == "copy":
         print(json.dumps(copy_probe_gbs(torch, steps=args.steps)))
         return
+    if args.index == "knn":
+        return knn_index_run(args, torch, workloads)
     t0 = time.time()
     w = workloads.make_config(args.config, scale=args.scale, device=dev if args.config >= 3 else "cpu",
                               n_groups=args.groups, paper_graph=args.graph == "paper")

@@ -213,6 +213,33 @@ int nomad_profile_read(nomad_ctx* ctx, int kind, double* total_ms, int64_t* laun
  */
 int nomad_copy_probe(void* dst, const void* src, uint64_t bytes, void* stream);
 
+/*
+ * ---- the upstream index: exact nearest neighbours inside clusters (Section 3.2) ----
+ *
+ * The paper builds its kNN graph from a K-Means partition: the candidates for a point's neighbours are the points of
+ * its own cluster, and among those the nearest neighbours are computed exactly.  This call is that second half; the
+ * partition is an input.
+ *
+ *   X          [n*d] fp32 row-major, the high-dimensional vectors; 1 <= d <= NOMAD_KNN_MAX_DIM
+ *   cluster_of [n]   int32, 0 <= id < n_clusters
+ *   out_nbrs   [n*k] int32: for every point its k nearest other points of the same cluster in ascending distance,
+ *                    ties to the lower point index; -1 in the slots a cluster with fewer than k+1 points cannot fill
+ *   mem        where X, cluster_of and out_nbrs live (NOMAD_HOST or NOMAD_DEVICE of `device`)
+ *   stats      NULL, or [2] host int64: queries that needed the exact fallback, point pairs the filter evaluated
+ *
+ * Distance: sum over t = 0..d-1, in that order, of (x_t - y_t)^2 with every operation in float64.  The result is that
+ * definition exactly: a float32 pass on the matrix cores only selects k + 8 candidates per point, their distances are
+ * recomputed in float64, and a point whose candidates cannot be proven complete (the float32 error bound against
+ * the first key left out) is redone against its whole cluster.  Inputs must be finite.  Stand-alone: needs no context;
+ * allocates its work space on `device` and frees it before it returns; waits for `stream`.
+ * Errors: NOMAD_E_INVALID_ARG, NOMAD_E_TOO_LARGE (n >= 2^31), NOMAD_E_BAD_GRAPH (cluster id out of range), NOMAD_E_OOM,
+ * NOMAD_E_HIP.
+ */
+#define NOMAD_KNN_MAX_K 32
+#define NOMAD_KNN_MAX_DIM 768
+int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const int32_t* cluster_of, int32_t n_clusters, int32_t k,
+                          int32_t* out_nbrs, int mem, int32_t device, void* stream, int64_t* stats);
+
 /* Text of the last error of this context ("" if none).  Valid until the next call on it. */
 const char* nomad_last_error(const nomad_ctx* ctx);
 

@@ -7,8 +7,9 @@ import subprocess
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 LIB_PATH = os.environ.get("NOMAD_LIBRARY_PATH") or os.path.join(_PKG, "libnomad.so")
-SOURCES = [os.path.join(_PKG, "csrc", "nomad.hip")]
-HEADERS = [os.path.join(_PKG, "csrc", "nomad_kernels.h"), os.path.join(_ROOT, "include", "nomad.h")]
+SOURCES = [os.path.join(_PKG, "csrc", "nomad.hip"), os.path.join(_PKG, "csrc", "knn.hip")]
+HEADERS = [os.path.join(_PKG, "csrc", "nomad_kernels.h"), os.path.join(_PKG, "csrc", "knn_kernels.h"),
+           os.path.join(_ROOT, "include", "nomad.h")]
 
 
 def hipcc_command(out: str = LIB_PATH) -> list:

@@ -24,7 +24,7 @@ ERRORS = {-1: "NOMAD_E_INVALID_ARG", -2: "NOMAD_E_BAD_GRAPH", -3: "NOMAD_E_ORDER
 EXPORTS = ["nomad_create", "nomad_destroy", "nomad_set_graph", "nomad_set_embedding", "nomad_epoch", "nomad_loss",
            "nomad_get_embedding", "nomad_get_gradient", "nomad_get_negatives", "nomad_get_means",
            "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error",
-           "nomad_copy_probe"]
+           "nomad_copy_probe", "nomad_knn_in_clusters"]
 
 
 class NomadConfig(C.Structure):
@@ -74,6 +74,7 @@ def load_library():
     lib.nomad_profile.argtypes = [vp, C.c_int]
     lib.nomad_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.nomad_copy_probe.argtypes = [vp, vp, C.c_uint64, vp]
+    lib.nomad_knn_in_clusters.argtypes = [vp, i64, i32, vp, i32, i32, vp, C.c_int, i32, vp, vp]
     lib.nomad_last_error.argtypes = [vp]
     lib.nomad_last_error.restype = C.c_char_p
     _lib = lib
@@ -112,6 +113,33 @@ def copy_probe(dst, src, stream=None):
     rc = lib.nomad_copy_probe(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes, C.c_void_p(stream or None))
     if rc:
         raise NomadError(rc, "nomad_copy_probe")
+
+
+def knn_in_clusters(X, cluster_of, n_clusters, k, device=0, stream=None, return_stats=False):
+    """nomad_knn_in_clusters: the k nearest other points of every point inside its own cluster (int32 [n, k], -1 where
+    the cluster is too small).  X and cluster_of: both torch tensors on the device, or both host arrays / CPU tensors;
+    the result lives where the inputs live."""
+    lib = load_library()
+    n, d = int(X.shape[0]), int(X.shape[1])
+    px, m0, keep_x = _marshal(X, np.float32, n * d)
+    pc, m1, keep_c = _marshal(cluster_of, np.int32, n)
+    if m0 != m1:
+        raise ValueError("X and cluster_of must live in the same memory space")
+    if m0 == NOMAD_DEVICE:
+        import torch
+        out = torch.empty((n, int(k)), dtype=torch.int32, device=keep_x.device)
+        po = C.c_void_p(out.data_ptr())
+        if stream is None:
+            stream = torch.cuda.current_stream(device).cuda_stream
+    else:
+        out = np.empty((n, int(k)), dtype=np.int32)
+        po = out.ctypes.data_as(C.c_void_p)
+    stats = np.zeros(2, dtype=np.int64)
+    rc = lib.nomad_knn_in_clusters(px, n, d, pc, int(n_clusters), int(k), po, m0, int(device), C.c_void_p(int(stream) if stream else None),
+                                   stats.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise NomadError(rc, "nomad_knn_in_clusters")
+    return (out, dict(fallback_queries=int(stats[0]), filter_pairs=int(stats[1]))) if return_stats else out
 
 
 class Nomad:
