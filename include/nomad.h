@@ -232,7 +232,7 @@ int nomad_copy_probe(void* dst, const void* src, uint64_t bytes, void* stream);
  * recomputed in float64, and a point whose candidates cannot be proven complete (the float32 error bound against
  * the first key left out) is redone against its whole cluster.  Inputs must be finite.  Stand-alone: needs no context;
  * allocates its work space on `device` and frees it before it returns; waits for `stream`.
- * Errors: NOMAD_E_INVALID_ARG, NOMAD_E_TOO_LARGE (n >= 2^31), NOMAD_E_BAD_GRAPH (cluster id out of range), NOMAD_E_OOM,
+ * Errors: NOMAD_E_INVALID_ARG, NOMAD_E_TOO_LARGE (n >= 2^31 - 256), NOMAD_E_BAD_GRAPH (cluster id out of range), NOMAD_E_OOM,
  * NOMAD_E_HIP.
  */
 #define NOMAD_KNN_MAX_K 32

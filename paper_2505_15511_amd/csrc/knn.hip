@@ -32,13 +32,25 @@ struct Buffers {   // device allocations of one call, released on every path
 
 inline uint32_t blocks_of(int64_t items, int per) { return (uint32_t)((items + per - 1) / per); }
 
-template <int D4>
-hipError_t launch_filter(hipStream_t st, uint32_t n_blocks, size_t lds, const float* X, int32_t d, const float* norm, const int32_t* members,
-                         const uint32_t* start, const KnnBlock* blocks, int32_t list_len, int32_t* cand, float* tau) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_knn_filter<D4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+template <int D4, int L>
+hipError_t launch_filter_dl(hipStream_t st, uint32_t n_blocks, const float* X, int32_t d, const float* norm, const int32_t* members,
+                            const uint32_t* start, const KnnBlock* blocks, int32_t list_len, int32_t* cand, float* tau) {
+    const size_t lds = knn_filter_lds_bytes(D4, L);
+    hipError_t e = hipFuncSetAttribute((const void*)k_knn_filter<D4, L>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_knn_filter<D4>, dim3(n_blocks), dim3(kFilterBlock), lds, st, X, d, norm, members, start, blocks, list_len, cand, tau);
+    hipLaunchKernelGGL((k_knn_filter<D4, L>), dim3(n_blocks), dim3(64 * knn_filter_waves(D4)), lds, st, X, d, norm, members, start, blocks,
+                       list_len, cand, tau);
     return hipGetLastError();
+}
+
+template <int D4>
+hipError_t launch_filter(hipStream_t st, uint32_t n_blocks, const float* X, int32_t d, const float* norm, const int32_t* members,
+                         const uint32_t* start, const KnnBlock* blocks, int32_t list_len, int32_t* cand, float* tau) {
+    switch (knn_filter_list_class(list_len)) {
+        case 8: return launch_filter_dl<D4, 8>(st, n_blocks, X, d, norm, members, start, blocks, list_len, cand, tau);
+        case 12: return launch_filter_dl<D4, 12>(st, n_blocks, X, d, norm, members, start, blocks, list_len, cand, tau);
+        default: return launch_filter_dl<D4, 20>(st, n_blocks, X, d, norm, members, start, blocks, list_len, cand, tau);
+    }
 }
 
 }  // namespace
@@ -48,7 +60,7 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
                                      int32_t* out_nbrs, int mem, int32_t device, void* stream, int64_t* stats) {
     if (!X || !cluster_of || !out_nbrs || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return NOMAD_E_INVALID_ARG;
     if (n < 1 || d < 1 || d > NOMAD_KNN_MAX_DIM || n_clusters < 1 || k < 1 || k > NOMAD_KNN_MAX_K || device < 0) return NOMAD_E_INVALID_ARG;
-    if (n >= ((int64_t)1 << 31)) return NOMAD_E_TOO_LARGE;
+    if (n >= ((int64_t)1 << 31) - 256) return NOMAD_E_TOO_LARGE;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) return NOMAD_E_HIP;
     KTRY(hipSetDevice(device));
@@ -93,6 +105,7 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     KTRY(hipMemsetAsync(max_norm, 0, sizeof(uint32_t) * (size_t)R, st));
     KTRY(hipMemsetAsync(n_flagged, 0, sizeof(uint32_t), st));
     KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
+    KTRY(hipMemsetAsync(cand, 0xFF, sizeof(int32_t) * (size_t)n * list_len, st));   // every slot "no candidate" until the filter fills it
     hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, 256)), dim3(256), 0, st, dC, n, R, counts, bad);
     std::vector<uint32_t> hcounts(R), hstart((size_t)R + 1, 0);
     int hbad = 0;
@@ -100,10 +113,14 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     KTRY(hipMemcpyAsync(&hbad, bad, sizeof(int), hipMemcpyDeviceToHost, st));
     KTRY(hipStreamSynchronize(st));
     if (hbad) return NOMAD_E_BAD_GRAPH;   // a cluster id outside 0..n_clusters-1
+    // the width class of the filter kernel decides how many queries a workgroup takes
+    const int d4 = (d + 3) / 4;
+    const int d4_class = d4 <= 8 ? 8 : d4 <= 16 ? 16 : d4 <= 32 ? 32 : d4 <= 64 ? 64 : d4 <= 128 ? 128 : 192;
+    const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(d4_class));
     std::vector<KnnBlock> hblocks;
     for (int32_t r = 0; r < R; ++r) {
         hstart[r + 1] = hstart[r] + hcounts[r];
-        for (uint32_t q0 = 0; q0 < hcounts[r]; q0 += kBlockQueries) hblocks.push_back(KnnBlock{r, (int32_t)q0});
+        for (uint32_t q0 = 0; q0 < hcounts[r]; q0 += block_queries) hblocks.push_back(KnnBlock{r, (int32_t)q0});
     }
     KnnBlock* blocks = nullptr;
     KTRY(buf.alloc(&blocks, hblocks.size()));
@@ -113,16 +130,15 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, dX, n, d, dC, norm, max_norm);
 
     // stage 1: float32 filter on the matrix cores
-    const int d4 = (d + 3) / 4;
     hipError_t e = hipErrorInvalidValue;
     const uint32_t nb = (uint32_t)hblocks.size();
 #define NOMAD_KNN_CASE(D4)                                                                                             \
-    e = launch_filter<D4>(st, nb, knn_filter_lds_bytes(D4, list_len), dX, d, norm, members, start, blocks, list_len, cand, tau)
-    if (d4 <= 8) NOMAD_KNN_CASE(8);
-    else if (d4 <= 16) NOMAD_KNN_CASE(16);
-    else if (d4 <= 32) NOMAD_KNN_CASE(32);
-    else if (d4 <= 64) NOMAD_KNN_CASE(64);
-    else if (d4 <= 128) NOMAD_KNN_CASE(128);
+    e = launch_filter<D4>(st, nb, dX, d, norm, members, start, blocks, list_len, cand, tau)
+    if (d4_class == 8) NOMAD_KNN_CASE(8);
+    else if (d4_class == 16) NOMAD_KNN_CASE(16);
+    else if (d4_class == 32) NOMAD_KNN_CASE(32);
+    else if (d4_class == 64) NOMAD_KNN_CASE(64);
+    else if (d4_class == 128) NOMAD_KNN_CASE(128);
     else NOMAD_KNN_CASE(192);
 #undef NOMAD_KNN_CASE
     KTRY(e);

@@ -22,9 +22,11 @@ constexpr int kPad = 8;            // extra candidates the filter keeps
 constexpr int kMaxList = kMaxK + kPad;
 constexpr int kWaveQueries = 16;   // queries per wavefront (the N of the 16x16x4 tile)
 constexpr int kTile = 16;          // candidates per tile (the M of the 16x16x4 tile)
-constexpr int kFilterWaves = 4;
-constexpr int kFilterBlock = 64 * kFilterWaves;
-constexpr int kBlockQueries = kWaveQueries * kFilterWaves;   // 64 queries per workgroup
+constexpr int32_t kEmptyPoint = 0x7fffff00;   // stand-ins for empty list slots: above every point index (n < 2^31 - 256)
+// wavefronts per workgroup of the filter: 8 (128 queries share every staged tile); 4 at the widest rows (d > 256),
+// where a lane's share of its query's row and its candidate list need more than the 256 registers that two
+// wavefronts per SIMD leave it
+__host__ __device__ constexpr int knn_filter_waves(int d4) { return d4 >= 128 ? 4 : 8; }
 
 struct KnnBlock { int32_t cluster; int32_t q0; };   // queries members[start[cluster] + q0 ..] of one workgroup
 
@@ -65,44 +67,50 @@ __global__ void __launch_bounds__(256) k_knn_group(const int32_t* __restrict__ c
 }
 
 // ---------------------------------------------------------------- stage 1: the float32 filter on the matrix cores
-// One workgroup = 64 queries of one cluster (4 wavefronts x 16), looping over the cluster's points 16 at a time.
+// One workgroup = 128 queries of one cluster (8 wavefronts x 16; 64 at the widest rows), looping over the cluster's
+// points 16 at a time.
 // 16x16x4 tile: A = the 16 candidates (lane l supplies A[i = l % 16][k = l / 16]), B = the 16 queries (lane l supplies
 // B[k = l / 16][j = l % 16]), D[i][j] in lane l for j = l % 16, i = 4 (l / 16) + v, v = 0..3.  The queries' rows stay in
-// registers for the whole loop (D4 = ceil(d / 4) values per lane); the candidates' rows are staged through LDS,
-// double-buffered (their point ids one tile further ahead, so that the row loads do not wait for an index load),
-// rows padded to 4 D4 + 2 words so that the 32 lanes of a half wavefront hit 32 different banks.  (Four planes by
-// column mod 4 with one 16-byte LDS load per four multiplications measured 10-60 % slower: bank conflicts.)
+// registers for the whole loop (D4 = ceil(d / 4) values per lane).
 //
-// Selection: every query owns an unsorted array of (key, point) pairs in LDS with room for K' + kSpare entries and a
-// threshold tau (inf until K' pairs are there).  A candidate with key < tau is appended (one LDS counter increment, two
-// stores: no search, no shifting).  When fewer than 16 free slots are left (one tile can bring 16 per query) the
-// wavefront compacts that query's array together: every lane takes an entry, counts the entries that precede it in
-// (key, point), the K' first stay, tau becomes the K'-th key.  Everything rejected or dropped has key >= the final tau.
-constexpr int kSpare = 40;
-template <int D4>
-__global__ void __launch_bounds__(kFilterBlock) k_knn_filter(const float* __restrict__ X, int32_t d, const float* __restrict__ norm,
-                                                            const int32_t* __restrict__ members, const uint32_t* __restrict__ start,
-                                                            const KnnBlock* __restrict__ blocks, int32_t list_len,
-                                                            int32_t* __restrict__ cand, float* __restrict__ tau_out) {
+// The candidates' rows are scattered over memory (a cluster's points are wherever the data set has them).  Thread t
+// always copies the same 16-byte chunks of one row (32 threads per row, 16 at the widest rows); the
+// loads of tile T+2 go out while tile T is multiplied (two register sets, the loop unrolled by two), tile T+1 is
+// written to the other LDS buffer after the multiplications; the point behind each row is fetched one tile further
+// ahead still, first thing in the iteration, so that no row load waits for an index.  LDS rows are padded to 4 D4 + 2
+// words: the 32 lanes of a half wavefront then read 32 different banks.
+//
+// Selection: each of the four lanes of a query sees a quarter of the candidates (four per tile) and keeps the L
+// smallest keys of that quarter, with their points, sorted in registers; a new key is pushed through the list with
+// compare-and-swap steps, for all lanes at once whenever any lane of the wavefront has a key below its list's last.
+// Every wavefront does the same work in every tile, so the tile barrier costs no waiting (an earlier version that
+// compacted per-query arrays in LDS on demand spent 70 % of its time at that barrier).  At the end the four lists of
+// a query are merged: the K' smallest keys go on, tau = min(K'-th key of the union, the four lists' last keys):
+// every candidate that is not passed on has key >= tau.
+template <int D4, int L>
+__global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const float* __restrict__ X, int32_t d, const float* __restrict__ norm,
+                                                                         const int32_t* __restrict__ members, const uint32_t* __restrict__ start,
+                                                                         const KnnBlock* __restrict__ blocks, int32_t list_len,
+                                                                         int32_t* __restrict__ cand, float* __restrict__ tau_out) {
+    constexpr int kFilterBlock = 64 * knn_filter_waves(D4);
     constexpr int kRow = 4 * D4 + 2;
     constexpr int kTileWords = kTile * kRow;
-    const int cap = list_len + kSpare;                        // <= 128: two entries per lane in a compaction
+    constexpr int kRowThreads = kFilterBlock / kTile;          // 32 threads copy one row (16 at the widest rows)
+    constexpr int kChunks = (D4 + kRowThreads - 1) / kRowThreads;   // 16-byte chunks per thread and tile
+    constexpr bool kTwoAhead = D4 <= 64;                      // two tiles of rows in flight where the registers allow it
+    constexpr int kMerge = 4 * L;                             // entries of a query's four lists
     extern __shared__ float lds[];
     float* tile = lds;                                        // [2][kTile][kRow]
     float* tnorm = tile + 2 * kTileWords;                     // [2][kTile]
     int32_t* tile_pt = (int32_t*)(tnorm + 2 * kTile);         // [2][kTile] point of each staged candidate (-1: none)
-    int32_t* ahead_pt = tile_pt + 2 * kTile;                  // [2][kTile] points of the tile after the staged one
-    float* akey = (float*)(ahead_pt + 2 * kTile);             // [kBlockQueries][cap]
-    int32_t* apt = (int32_t*)(akey + kBlockQueries * cap);    // [kBlockQueries][cap]
-    uint32_t* fill = (uint32_t*)(apt + kBlockQueries * cap);  // [kBlockQueries]
-    float* qtau = (float*)(fill + kBlockQueries);             // [kBlockQueries]
+    float* mkey = (float*)(tile_pt + 2 * kTile);              // [waves][kMerge] merge scratch of one query per wavefront
+    int32_t* mpt = (int32_t*)(mkey + knn_filter_waves(D4) * kMerge);   // [waves][kMerge]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const KnnBlock blk = blocks[blockIdx.x];
     const uint32_t c0 = start[blk.cluster], c1 = start[blk.cluster + 1];
     const int32_t n_r = (int32_t)(c1 - c0);
     // this lane's query and its slice of the row
-    const int jq = wave * kWaveQueries + (lane & 15);          // query of the workgroup this lane works for
-    const int32_t qpos = blk.q0 + jq;
+    const int32_t qpos = blk.q0 + wave * kWaveQueries + (lane & 15);
     const int32_t qpt = qpos < n_r ? members[c0 + qpos] : -1;
     float breg[D4];
 #pragma unroll
@@ -110,130 +118,188 @@ __global__ void __launch_bounds__(kFilterBlock) k_knn_filter(const float* __rest
         const int col = 4 * t + (lane >> 4);
         breg[t] = (qpt >= 0 && col < d) ? X[(int64_t)qpt * d + col] : 0.f;
     }
-    for (int x = tid; x < kBlockQueries; x += kFilterBlock) { fill[x] = 0u; qtau[x] = __builtin_inff(); }
-    // staging: the loads of a tile's rows go out before the tile in the other buffer is multiplied, the values are
-    // written to LDS after it; the points of the tile after that are fetched one iteration earlier still
-    constexpr int kPerLane = (kTile * D4 * 4 + kFilterBlock - 1) / kFilterBlock;
-    float sval[kPerLane];
-    int32_t spt = -1, apt_next = -1;
-    float snorm = 0.f;
+    float lk[L];      // this lane's L smallest keys so far, ascending
+    int32_t lp[L];    // and their points
+#pragma unroll
+    for (int x = 0; x < L; ++x) { lk[x] = __builtin_inff(); lp[x] = -1; }
+
+    // ---- staging
+    const int srow = tid / kRowThreads, sthr = tid % kRowThreads;   // this thread's row of every tile and its place in it
+    const bool vec = (d & 3) == 0;                                  // rows are 16-byte aligned
+    struct Staged { float4 v[kChunks]; int32_t pt; float nrm; };
     auto point_at = [&](int32_t pos) { return pos < n_r ? members[c0 + pos] : -1; };
-    auto fetch = [&](int which, int32_t t0) {   // rows of the tile whose points sit in ahead_pt[which]
+    // loads of this thread's chunks of the row of point pt (any valid row when pt < 0; masked when it is stored)
+    auto fetch = [&](Staged& S, int32_t pt) {
+        S.pt = pt;
+        const float* row = X + (int64_t)max(pt, 0) * d;
+        S.nrm = norm[max(pt, 0)];
 #pragma unroll
-        for (int u = 0; u < kPerLane; ++u) {
-            const int x = min(tid + u * kFilterBlock, kTile * D4 * 4 - 1);
-            const int row = x / (D4 * 4), col = x % (D4 * 4);
-            const int32_t pt = ahead_pt[which * kTile + row];
-            sval[u] = X[(int64_t)max(pt, 0) * d + min(col, d - 1)];   // always a valid address; masked when it is stored
-        }
-        if (tid < kTile) {
-            spt = ahead_pt[which * kTile + tid];
-            snorm = spt >= 0 ? norm[spt] : 0.f;
-            apt_next = point_at(t0 + kTile + tid);            // the points of the tile after this one
+        for (int u = 0; u < kChunks; ++u) {
+            const int col = 4 * (sthr + u * kRowThreads);
+            if (vec) {
+                S.v[u] = *(const float4*)(row + min(col, d - 4));
+            } else {
+                S.v[u].x = row[min(col, d - 1)];
+                S.v[u].y = row[min(col + 1, d - 1)];
+                S.v[u].z = row[min(col + 2, d - 1)];
+                S.v[u].w = row[min(col + 3, d - 1)];
+            }
         }
     };
-    auto stash = [&](int buf, int which) {
+    // (nothing touches the loaded values before they are stored: the loads stay in flight until then)
+    auto stash = [&](const Staged& S, int buf) {
+        float* dst = tile + buf * kTileWords + srow * kRow;
 #pragma unroll
-        for (int u = 0; u < kPerLane; ++u) {
-            const int x = tid + u * kFilterBlock;
-            const int row = x / (D4 * 4), col = x % (D4 * 4);
-            if (x < kTile * D4 * 4)   // (nothing touches the loaded value before this point: the load stays in flight)
-                tile[buf * kTileWords + row * kRow + col] = (ahead_pt[which * kTile + row] >= 0 && col < d) ? sval[u] : 0.f;
+        for (int u = 0; u < kChunks; ++u) {
+            const int col = 4 * (sthr + u * kRowThreads);
+            if (col < 4 * D4) {
+                const bool live = S.pt >= 0;
+                float2 lo = make_float2((live && col < d) ? S.v[u].x : 0.f, (live && col + 1 < d) ? S.v[u].y : 0.f);
+                float2 hi = make_float2((live && col + 2 < d) ? S.v[u].z : 0.f, (live && col + 3 < d) ? S.v[u].w : 0.f);
+                *(float2*)(dst + col) = lo;        // rows start on even words: 8-byte stores
+                *(float2*)(dst + col + 2) = hi;
+            }
         }
-        if (tid < kTile) {
-            tile_pt[buf * kTile + tid] = spt;
-            tnorm[buf * kTile + tid] = snorm;
-            ahead_pt[(which ^ 1) * kTile + tid] = apt_next;
+        if (sthr == 0) { tile_pt[buf * kTile + srow] = S.pt; tnorm[buf * kTile + srow] = S.pt >= 0 ? S.nrm : 0.f; }
+    };
+    // multiply the tile in LDS buffer `buf` with this wavefront's queries, push what beats the lists' last keys
+    auto consume = [&](int buf) {
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        const float* arow = tile + buf * kTileWords + (lane & 15) * kRow + (lane >> 4);
+#pragma unroll
+        for (int t = 0; t < D4; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(arow[4 * t], breg[t], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int i = 4 * (lane >> 4) + v;
+            const int32_t cpt = tile_pt[buf * kTile + i];
+            float key = tnorm[buf * kTile + i] - 2.f * acc[v];
+            if (cpt < 0 || cpt == qpt || qpt < 0) key = __builtin_inff();
+            if (__any(key < lk[L - 1])) {
+                float xk = key;       // an infinite key changes nothing below
+                int32_t xp = cpt;
+#pragma unroll
+                for (int x = 0; x < L; ++x) {
+                    const bool take = xk < lk[x];
+                    const float ok = lk[x];
+                    const int32_t op = lp[x];
+                    lk[x] = take ? xk : ok;
+                    lp[x] = take ? xp : op;
+                    xk = take ? ok : xk;
+                    xp = take ? op : xp;
+                }
+            }
         }
     };
-    if (tid < kTile) ahead_pt[tid] = point_at(tid);
-    __syncthreads();
-    fetch(0, 0);
-    stash(0, 0);     // tile 0 in buffer 0, the points of tile 1 in ahead_pt[1]
-    __syncthreads();
-    // compaction of query j's array by the whole wavefront (j is the same for all lanes)
-    auto compact = [&](int j) {
-        float* ak = akey + j * cap;
-        int32_t* ap = apt + j * cap;
-        const int cnt = (int)min(fill[j], (uint32_t)cap);
+
+    // tile T sits in LDS buffer T & 1
+    if (kTwoAhead) {
+        // Registers: S0 / S1 hold the rows of the even / odd tile that is on its way, pt_ahead the point of this
+        // thread's row one tile beyond those.
+        Staged S0, S1;
+        fetch(S0, point_at(srow));                         // tile 0
+        stash(S0, 0);
+        fetch(S1, point_at(kTile + srow));                 // tile 1, stored at the end of iteration 0
+        int32_t pt_ahead = point_at(2 * kTile + srow);     // tile 2's point
+        __syncthreads();
+        for (int32_t t0 = 0; t0 < n_r; t0 += 2 * kTile) {
+            // ---- even tile T (buffer 0): tile T+2's rows go out into S0, tile T+1 (S1) is stored afterwards
+            {
+                const int32_t pt_use = pt_ahead;
+                pt_ahead = point_at(t0 + 3 * kTile + srow);
+                fetch(S0, pt_use);
+                consume(0);
+                stash(S1, 1);
+                __syncthreads();
+            }
+            if (t0 + kTile >= n_r) break;
+            // ---- odd tile T+1 (buffer 1): tile T+3's rows go out into S1, tile T+2 (S0) is stored afterwards
+            {
+                const int32_t pt_use = pt_ahead;
+                pt_ahead = point_at(t0 + 4 * kTile + srow);
+                fetch(S1, pt_use);
+                consume(1);
+                stash(S0, 0);
+                __syncthreads();
+            }
+        }
+    } else {
+        // one tile of rows in flight (the multiplications of a tile take thousands of cycles at these widths)
+        Staged S;
+        fetch(S, point_at(srow));
+        stash(S, 0);
+        int32_t pt_ahead = point_at(kTile + srow);         // tile 1's point
+        __syncthreads();
+        int buf = 0;
+        for (int32_t t0 = 0; t0 < n_r; t0 += kTile, buf ^= 1) {
+            const int32_t pt_use = pt_ahead;
+            pt_ahead = point_at(t0 + 2 * kTile + srow);
+            fetch(S, pt_use);                              // tile T+1
+            consume(buf);
+            stash(S, buf ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- merge the four lists of every query, one query of the wavefront at a time
+    float* mk = mkey + wave * kMerge;
+    int32_t* mp = mpt + wave * kMerge;
+    // the smallest of the four lists' last keys: what this query's lanes may have turned away
+    float thr = lk[L - 1];
+    thr = fminf(thr, __shfl_xor(thr, 16, 64));
+    thr = fminf(thr, __shfl_xor(thr, 32, 64));
+    for (int j = 0; j < kWaveQueries; ++j) {
+        if ((lane & 15) == j) {
+#pragma unroll
+            for (int x = 0; x < L; ++x) { mk[(lane >> 4) * L + x] = lk[x]; mp[(lane >> 4) * L + x] = lp[x]; }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // every lane takes up to two of the 4 L entries and counts those that precede them in (key, point)
         float k0 = __builtin_inff(), k1 = __builtin_inff();
-        int32_t p0 = 0x7fffffff, p1 = 0x7fffffff;
-        if (lane < cnt) { k0 = ak[lane]; p0 = ap[lane]; }
-        if (lane + 64 < cnt) { k1 = ak[lane + 64]; p1 = ap[lane + 64]; }
-        int r0 = 0, r1 = 0;   // entries that precede this lane's in (key, point); the others' entries come by lane broadcast
-        const int first = min(cnt, 64), second = max(cnt - 64, 0);
-        for (int o = 0; o < first; ++o) {
+        int32_t p0 = -1, p1 = -1;
+        if (lane < kMerge) { k0 = mk[lane]; p0 = mp[lane]; }
+        if (lane + 64 < kMerge) { k1 = mk[lane + 64]; p1 = mp[lane + 64]; }
+        // an empty slot (point -1) sorts after every real entry; empty slots get distinct stand-in points so that the
+        // ranks stay a permutation and every one of the K' output slots is written
+        if (p0 < 0) p0 = kEmptyPoint + lane;
+        if (p1 < 0) p1 = kEmptyPoint + 64 + lane;
+        int r0 = 0, r1 = 0;
+        for (int o = 0; o < (kMerge < 64 ? kMerge : 64); ++o) {
             const float ko = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(k0), o));
             const int32_t po = __builtin_amdgcn_readlane(p0, o);
             r0 += (ko < k0 || (ko == k0 && po < p0)) ? 1 : 0;
             r1 += (ko < k1 || (ko == k1 && po < p1)) ? 1 : 0;
         }
-        for (int o = 0; o < second; ++o) {
+        for (int o = 0; o < kMerge - 64; ++o) {
             const float ko = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(k1), o));
             const int32_t po = __builtin_amdgcn_readlane(p1, o);
             r0 += (ko < k0 || (ko == k0 && po < p0)) ? 1 : 0;
             r1 += (ko < k1 || (ko == k1 && po < p1)) ? 1 : 0;
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        if (lane < cnt && r0 < list_len) { ak[r0] = k0; ap[r0] = p0; }
-        if (lane + 64 < cnt && r1 < list_len) { ak[r1] = k1; ap[r1] = p1; }
-        if (cnt >= list_len) {
-            if (lane < cnt && r0 == list_len - 1) qtau[j] = k0;
-            if (lane + 64 < cnt && r1 == list_len - 1) qtau[j] = k1;
-            if (lane == 0) fill[j] = (uint32_t)list_len;
+        // the query's point and position, from the lane that owns it
+        const int32_t jq_pt = __shfl(qpt, j, 64);
+        const int32_t jq_pos = __shfl(qpos, j, 64);
+        const float jq_thr = __shfl(thr, j, 64);
+        if (jq_pt >= 0) {
+            const int64_t p = (int64_t)c0 + jq_pos;
+            if (lane < kMerge && r0 < list_len) cand[p * list_len + r0] = p0 >= kEmptyPoint ? -1 : p0;
+            if (lane + 64 < kMerge && r1 < list_len) cand[p * list_len + r1] = p1 >= kEmptyPoint ? -1 : p1;
+            // tau: the K'-th key of the union (inf if there is none) and the lists' last keys
+            if (lane < kMerge && r0 == list_len - 1) tau_out[p] = fminf(k0, jq_thr);
+            if (lane + 64 < kMerge && r1 == list_len - 1) tau_out[p] = fminf(k1, jq_thr);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    };
-    int buf = 0;
-    for (int32_t t0 = 0; t0 < n_r; t0 += kTile, buf ^= 1) {
-        const bool more = t0 + kTile < n_r;
-        if (more) fetch(buf ^ 1, t0 + kTile);   // the next tile's rows are on their way while this one is multiplied
-        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-        const float* arow = tile + buf * kTileWords + (lane & 15) * kRow + (lane >> 4);
-#pragma unroll
-        for (int t = 0; t < D4; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(arow[4 * t], breg[t], acc, 0, 0, 0);
-        const float tau = qtau[jq];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int i = 4 * (lane >> 4) + v;
-            const int32_t cpt = tile_pt[buf * kTile + i];
-            const float key = tnorm[buf * kTile + i] - 2.f * acc[v];
-            if (cpt >= 0 && cpt != qpt && qpt >= 0 && key < tau) {
-                const uint32_t slot = atomicAdd(&fill[jq], 1u);   // a tile brings at most 16 per query: room is kept below
-                akey[jq * cap + slot] = key;
-                apt[jq * cap + slot] = cpt;
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // queries of this wavefront whose array could not take another tile
-        unsigned long long need = __ballot((lane < kWaveQueries) && fill[wave * kWaveQueries + lane] + kTile > (uint32_t)cap);
-        while (need) {
-            const int j = __builtin_ctzll(need);
-            need &= need - 1;
-            compact(wave * kWaveQueries + j);
-        }
-        if (more) stash(buf ^ 1, buf ^ 1);
-        __syncthreads();   // the other buffer is staged, this one is free
-    }
-    // the K' best of every query and the K'-th key (inf while fewer than K' were ever there: then nothing was left out)
-    for (int j = 0; j < kWaveQueries; ++j) compact(wave * kWaveQueries + j);
-    if ((lane >> 4) == 0 && qpt >= 0) {
-        const int64_t p = (int64_t)c0 + qpos;
-        const int cnt = (int)min(fill[jq], (uint32_t)list_len);
-        for (int x = 0; x < list_len; ++x) cand[p * list_len + x] = x < cnt ? apt[jq * cap + x] : -1;
-        tau_out[p] = qtau[jq];
     }
 }
 
-__host__ __device__ inline size_t knn_filter_lds_bytes(int d4, int list_len) {
-    return ((size_t)2 * kTile * (4 * d4 + 2) + 6 * kTile + (size_t)2 * kBlockQueries * (list_len + kSpare) + 2 * kBlockQueries) * 4;
+__host__ __device__ inline size_t knn_filter_lds_bytes(int d4, int L) {
+    return ((size_t)2 * kTile * (4 * d4 + 2) + 4 * kTile + (size_t)2 * knn_filter_waves(d4) * 4 * L) * 4;
 }
+// entries per lane's list for K' = list_len candidates per query: half of K', so that the four lists of a query hold 2 K'
+__host__ inline int knn_filter_list_class(int list_len) { return list_len <= 16 ? 8 : list_len <= 24 ? 12 : 20; }
 
 // the oracle's distance: difference, product and running sum each rounded once, in float64, t = 0..d-1 in order
 __device__ __forceinline__ double exact_distance(const float* __restrict__ x, const float* __restrict__ y, int32_t d) {
@@ -275,7 +341,8 @@ __global__ void __launch_bounds__(256) k_knn_refine(const float* __restrict__ X,
     if (p >= n) return;
     const int32_t q = members[p];
     const float* xq = X + (int64_t)q * d;
-    const int32_t c = lane < list_len ? cand[p * list_len + lane] : -1;
+    int32_t c = lane < list_len ? cand[p * list_len + lane] : -1;
+    if (c >= n) c = -1;   // never an address outside X, whatever the list holds
     const double D = c >= 0 ? exact_distance(xq, X + (int64_t)c * d, d) : __builtin_inf();
     int rank = 0, cnt = 0;
     for (int o = 0; o < list_len; ++o) {
