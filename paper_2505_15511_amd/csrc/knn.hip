@@ -34,22 +34,22 @@ inline uint32_t blocks_of(int64_t items, int per) { return (uint32_t)((items + p
 
 template <int D4, int L>
 hipError_t launch_filter_dl(hipStream_t st, uint32_t n_blocks, const float* X, int32_t d, const float* norm, const int32_t* members,
-                            const uint32_t* start, const KnnBlock* blocks, int32_t list_len, int32_t* cand, float* tau) {
+                            const uint32_t* start, const KnnBlock* blocks, const float* centre, int32_t list_len, int32_t* cand, float* tau) {
     const size_t lds = knn_filter_lds_bytes(D4, L);
     hipError_t e = hipFuncSetAttribute((const void*)k_knn_filter<D4, L>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((k_knn_filter<D4, L>), dim3(n_blocks), dim3(64 * knn_filter_waves(D4)), lds, st, X, d, norm, members, start, blocks,
-                       list_len, cand, tau);
+                       centre, list_len, cand, tau);
     return hipGetLastError();
 }
 
 template <int D4>
 hipError_t launch_filter(hipStream_t st, uint32_t n_blocks, const float* X, int32_t d, const float* norm, const int32_t* members,
-                         const uint32_t* start, const KnnBlock* blocks, int32_t list_len, int32_t* cand, float* tau) {
+                         const uint32_t* start, const KnnBlock* blocks, const float* centre, int32_t list_len, int32_t* cand, float* tau) {
     switch (knn_filter_list_class(list_len)) {
-        case 8: return launch_filter_dl<D4, 8>(st, n_blocks, X, d, norm, members, start, blocks, list_len, cand, tau);
-        case 12: return launch_filter_dl<D4, 12>(st, n_blocks, X, d, norm, members, start, blocks, list_len, cand, tau);
-        default: return launch_filter_dl<D4, 20>(st, n_blocks, X, d, norm, members, start, blocks, list_len, cand, tau);
+        case 8: return launch_filter_dl<D4, 8>(st, n_blocks, X, d, norm, members, start, blocks, centre, list_len, cand, tau);
+        case 12: return launch_filter_dl<D4, 12>(st, n_blocks, X, d, norm, members, start, blocks, centre, list_len, cand, tau);
+        default: return launch_filter_dl<D4, 20>(st, n_blocks, X, d, norm, members, start, blocks, centre, list_len, cand, tau);
     }
 }
 
@@ -87,7 +87,7 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     // members grouped by cluster
     uint32_t *counts = nullptr, *start = nullptr, *cursor = nullptr, *max_norm = nullptr, *n_flagged = nullptr;
     int32_t *members = nullptr, *cand = nullptr, *flagged = nullptr;
-    float *norm = nullptr, *tau = nullptr;
+    float *norm = nullptr, *tau = nullptr, *centre = nullptr;
     int* bad = nullptr;
     KTRY(buf.alloc(&counts, (size_t)R));
     KTRY(buf.alloc(&start, (size_t)R + 1));
@@ -98,6 +98,8 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     KTRY(buf.alloc(&members, (size_t)n));
     KTRY(buf.alloc(&norm, (size_t)n));
     KTRY(buf.alloc(&tau, (size_t)n));
+    KTRY(buf.alloc(&centre, (size_t)R * d));
+    KTRY(hipMemsetAsync(centre, 0, sizeof(float) * (size_t)R * d, st));
     KTRY(buf.alloc(&cand, (size_t)n * list_len));
     KTRY(buf.alloc(&flagged, (size_t)n));
     KTRY(hipMemsetAsync(counts, 0, sizeof(uint32_t) * (size_t)R, st));
@@ -117,23 +119,28 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     const int d4 = (d + 3) / 4;
     const int d4_class = d4 <= 8 ? 8 : d4 <= 16 ? 16 : d4 <= 32 ? 32 : d4 <= 64 ? 64 : d4 <= 128 ? 128 : 192;
     const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(d4_class));
-    std::vector<KnnBlock> hblocks;
+    std::vector<KnnBlock> hblocks, hslabs;
     for (int32_t r = 0; r < R; ++r) {
         hstart[r + 1] = hstart[r] + hcounts[r];
         for (uint32_t q0 = 0; q0 < hcounts[r]; q0 += block_queries) hblocks.push_back(KnnBlock{r, (int32_t)q0});
+        for (uint32_t q0 = 0; q0 < hcounts[r]; q0 += kCentroidRows) hslabs.push_back(KnnBlock{r, (int32_t)q0});
     }
-    KnnBlock* blocks = nullptr;
+    KnnBlock *blocks = nullptr, *slabs = nullptr;
     KTRY(buf.alloc(&blocks, hblocks.size()));
+    KTRY(buf.alloc(&slabs, hslabs.size()));
+    KTRY(hipMemcpyAsync(slabs, hslabs.data(), sizeof(KnnBlock) * hslabs.size(), hipMemcpyHostToDevice, st));
     KTRY(hipMemcpyAsync(start, hstart.data(), sizeof(uint32_t) * ((size_t)R + 1), hipMemcpyHostToDevice, st));
     KTRY(hipMemcpyAsync(blocks, hblocks.data(), sizeof(KnnBlock) * hblocks.size(), hipMemcpyHostToDevice, st));
     hipLaunchKernelGGL(k_knn_group, dim3(blocks_of(n, 256)), dim3(256), 0, st, dC, n, start, cursor, members);
-    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, dX, n, d, dC, norm, max_norm);
+    hipLaunchKernelGGL(k_knn_centroid_sums, dim3((uint32_t)hslabs.size()), dim3(256), 0, st, dX, d, members, start, slabs, centre);
+    hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of((int64_t)R * d, 256)), dim3(256), 0, st, centre, start, R, d);
+    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, dX, n, d, dC, centre, norm, max_norm);
 
     // stage 1: float32 filter on the matrix cores
     hipError_t e = hipErrorInvalidValue;
     const uint32_t nb = (uint32_t)hblocks.size();
 #define NOMAD_KNN_CASE(D4)                                                                                             \
-    e = launch_filter<D4>(st, nb, dX, d, norm, members, start, blocks, list_len, cand, tau)
+    e = launch_filter<D4>(st, nb, dX, d, norm, members, start, blocks, centre, list_len, cand, tau)
     if (d4_class == 8) NOMAD_KNN_CASE(8);
     else if (d4_class == 16) NOMAD_KNN_CASE(16);
     else if (d4_class == 32) NOMAD_KNN_CASE(32);
@@ -144,8 +151,8 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     KTRY(e);
 
     // stage 2: exact distances of the candidates, certification
-    hipLaunchKernelGGL(k_knn_refine, dim3(blocks_of(n, 4)), dim3(256), 0, st, dX, d, members, dC, max_norm, cand, tau, n, k, list_len, dOut,
-                       flagged, n_flagged);
+    hipLaunchKernelGGL(k_knn_refine, dim3(blocks_of(n, 4)), dim3(256), 0, st, dX, d, members, dC, max_norm, centre, cand, tau, n, k, list_len,
+                       dOut, flagged, n_flagged);
     uint32_t hflag = 0;
     KTRY(hipMemcpyAsync(&hflag, n_flagged, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     KTRY(hipStreamSynchronize(st));

@@ -27,23 +27,48 @@ constexpr int32_t kEmptyPoint = 0x7fffff00;   // stand-ins for empty list slots:
 // where a lane's share of its query's row and its candidate list need more than the 256 registers that two
 // wavefronts per SIMD leave it
 __host__ __device__ constexpr int knn_filter_waves(int d4) { return d4 >= 128 ? 4 : 8; }
+// LDS buffers for the staged candidate tile: two, or one at the widest rows (see the kernel)
+__host__ __device__ constexpr int knn_filter_buffers(int d4) { return d4 > 64 ? 1 : 2; }
 
 struct KnnBlock { int32_t cluster; int32_t q0; };   // queries members[start[cluster] + q0 ..] of one workgroup
 
-// |x|^2 of every point in float32 (t = 0..d-1 in order) and the largest one per cluster
+// Distances do not change when a cluster is moved as a whole, and the float32 error of the filter grows with |x|^2:
+// the filter therefore works on rows centred on their cluster, x' = fl(x - c_r), c_r = the cluster's mean in float32.
+// Column sums of a cluster, a slab of rows per block, one thread per column:
+constexpr int kCentroidRows = 1024;
+__global__ void __launch_bounds__(256) k_knn_centroid_sums(const float* __restrict__ X, int32_t d, const int32_t* __restrict__ members,
+                                                           const uint32_t* __restrict__ start, const KnnBlock* __restrict__ slabs,
+                                                           float* __restrict__ centre) {
+    const KnnBlock sl = slabs[blockIdx.x];   // rows q0 .. q0 + kCentroidRows of cluster sl.cluster
+    const uint32_t c0 = start[sl.cluster], c1 = start[sl.cluster + 1];
+    const uint32_t r0 = c0 + (uint32_t)sl.q0, r1 = min(c1, r0 + (uint32_t)kCentroidRows);
+    for (int col = threadIdx.x; col < d; col += 256) {
+        float s = 0.f;
+        for (uint32_t r = r0; r < r1; ++r) s += X[(int64_t)members[r] * d + col];
+        atomicAdd(&centre[(int64_t)sl.cluster * d + col], s);
+    }
+}
+__global__ void __launch_bounds__(256) k_knn_centroid_finish(float* __restrict__ centre, const uint32_t* __restrict__ start, int32_t R, int32_t d) {
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= (int64_t)R * d) return;
+    const int32_t r = (int32_t)(x / d);
+    const uint32_t cnt = start[r + 1] - start[r];
+    centre[x] = cnt ? centre[x] / (float)cnt : 0.f;
+}
+
+// |x'|^2 of every centred row in float32 (t = 0..d-1 in order) and the largest one per cluster
 __global__ void __launch_bounds__(256) k_knn_norms(const float* __restrict__ X, int64_t n, int32_t d, const int32_t* __restrict__ cluster_of,
-                                                   float* __restrict__ norm, uint32_t* __restrict__ max_norm_bits) {
+                                                   const float* __restrict__ centre, float* __restrict__ norm,
+                                                   uint32_t* __restrict__ max_norm_bits) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const float* x = X + i * d;
+    const float* c = centre + (int64_t)cluster_of[i] * d;
     float s = 0.f;
-    int t = 0;
-    if ((d & 3) == 0)
-        for (; t < d; t += 4) {
-            const float4 a = *(const float4*)(x + t);
-            s = fmaf(a.x, a.x, s); s = fmaf(a.y, a.y, s); s = fmaf(a.z, a.z, s); s = fmaf(a.w, a.w, s);
-        }
-    for (; t < d; ++t) s = fmaf(x[t], x[t], s);
+    for (int t = 0; t < d; ++t) {
+        const float v = x[t] - c[t];
+        s = fmaf(v, v, s);
+    }
     norm[i] = s;
     atomicMax(&max_norm_bits[cluster_of[i]], __float_as_uint(s));   // non-negative floats order like their bit patterns
 }
@@ -90,18 +115,19 @@ __global__ void __launch_bounds__(256) k_knn_group(const int32_t* __restrict__ c
 template <int D4, int L>
 __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const float* __restrict__ X, int32_t d, const float* __restrict__ norm,
                                                                          const int32_t* __restrict__ members, const uint32_t* __restrict__ start,
-                                                                         const KnnBlock* __restrict__ blocks, int32_t list_len,
-                                                                         int32_t* __restrict__ cand, float* __restrict__ tau_out) {
+                                                                         const KnnBlock* __restrict__ blocks, const float* __restrict__ centre,
+                                                                         int32_t list_len, int32_t* __restrict__ cand, float* __restrict__ tau_out) {
     constexpr int kFilterBlock = 64 * knn_filter_waves(D4);
     constexpr int kRow = 4 * D4 + 2;
     constexpr int kTileWords = kTile * kRow;
     constexpr int kRowThreads = kFilterBlock / kTile;          // 32 threads copy one row (16 at the widest rows)
     constexpr int kChunks = (D4 + kRowThreads - 1) / kRowThreads;   // 16-byte chunks per thread and tile
     constexpr bool kTwoAhead = D4 <= 64;                      // two tiles of rows in flight where the registers allow it
+    constexpr int kBuffers = knn_filter_buffers(D4);          // LDS tile buffers
     constexpr int kMerge = 4 * L;                             // entries of a query's four lists
     extern __shared__ float lds[];
-    float* tile = lds;                                        // [2][kTile][kRow]
-    float* tnorm = tile + 2 * kTileWords;                     // [2][kTile]
+    float* tile = lds;                                        // [kBuffers][kTile][kRow]
+    float* tnorm = tile + kBuffers * kTileWords;              // [2][kTile]
     int32_t* tile_pt = (int32_t*)(tnorm + 2 * kTile);         // [2][kTile] point of each staged candidate (-1: none)
     float* mkey = (float*)(tile_pt + 2 * kTile);              // [waves][kMerge] merge scratch of one query per wavefront
     int32_t* mpt = (int32_t*)(mkey + knn_filter_waves(D4) * kMerge);   // [waves][kMerge]
@@ -112,11 +138,12 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
     // this lane's query and its slice of the row
     const int32_t qpos = blk.q0 + wave * kWaveQueries + (lane & 15);
     const int32_t qpt = qpos < n_r ? members[c0 + qpos] : -1;
+    const float* ctr = centre + (int64_t)blk.cluster * d;      // the cluster's centre: every row enters as x - centre
     float breg[D4];
 #pragma unroll
     for (int t = 0; t < D4; ++t) {
         const int col = 4 * t + (lane >> 4);
-        breg[t] = (qpt >= 0 && col < d) ? X[(int64_t)qpt * d + col] : 0.f;
+        breg[t] = (qpt >= 0 && col < d) ? X[(int64_t)qpt * d + col] - ctr[col] : 0.f;
     }
     float lk[L];      // this lane's L smallest keys so far, ascending
     int32_t lp[L];    // and their points
@@ -127,6 +154,13 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
     const int srow = tid / kRowThreads, sthr = tid % kRowThreads;   // this thread's row of every tile and its place in it
     const bool vec = (d & 3) == 0;                                  // rows are 16-byte aligned
     struct Staged { float4 v[kChunks]; int32_t pt; float nrm; };
+    float4 cchunk[kChunks];                                         // the centre at this thread's columns
+#pragma unroll
+    for (int u = 0; u < kChunks; ++u) {
+        const int col = 4 * (sthr + u * kRowThreads);
+        cchunk[u] = make_float4(col < d ? ctr[col] : 0.f, col + 1 < d ? ctr[col + 1] : 0.f, col + 2 < d ? ctr[col + 2] : 0.f,
+                                col + 3 < d ? ctr[col + 3] : 0.f);
+    }
     auto point_at = [&](int32_t pos) { return pos < n_r ? members[c0 + pos] : -1; };
     // loads of this thread's chunks of the row of point pt (any valid row when pt < 0; masked when it is stored)
     auto fetch = [&](Staged& S, int32_t pt) {
@@ -154,8 +188,8 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
             const int col = 4 * (sthr + u * kRowThreads);
             if (col < 4 * D4) {
                 const bool live = S.pt >= 0;
-                float2 lo = make_float2((live && col < d) ? S.v[u].x : 0.f, (live && col + 1 < d) ? S.v[u].y : 0.f);
-                float2 hi = make_float2((live && col + 2 < d) ? S.v[u].z : 0.f, (live && col + 3 < d) ? S.v[u].w : 0.f);
+                float2 lo = make_float2((live && col < d) ? S.v[u].x - cchunk[u].x : 0.f, (live && col + 1 < d) ? S.v[u].y - cchunk[u].y : 0.f);
+                float2 hi = make_float2((live && col + 2 < d) ? S.v[u].z - cchunk[u].z : 0.f, (live && col + 3 < d) ? S.v[u].w - cchunk[u].w : 0.f);
                 *(float2*)(dst + col) = lo;        // rows start on even words: 8-byte stores
                 *(float2*)(dst + col + 2) = hi;
             }
@@ -223,19 +257,21 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
             }
         }
     } else {
-        // one tile of rows in flight (the multiplications of a tile take thousands of cycles at these widths)
+        // Wide rows: one tile of rows in flight (its multiplications take thousands of cycles) and a single LDS
+        // buffer, which is what lets more than one workgroup share a compute unit: the next tile waits in registers
+        // until every wavefront is done with the current one.
         Staged S;
         fetch(S, point_at(srow));
         stash(S, 0);
         int32_t pt_ahead = point_at(kTile + srow);         // tile 1's point
         __syncthreads();
-        int buf = 0;
-        for (int32_t t0 = 0; t0 < n_r; t0 += kTile, buf ^= 1) {
+        for (int32_t t0 = 0; t0 < n_r; t0 += kTile) {
             const int32_t pt_use = pt_ahead;
             pt_ahead = point_at(t0 + 2 * kTile + srow);
             fetch(S, pt_use);                              // tile T+1
-            consume(buf);
-            stash(S, buf ^ 1);
+            consume(0);
+            __syncthreads();
+            stash(S, 0);
             __syncthreads();
         }
     }
@@ -296,7 +332,7 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
 }
 
 __host__ __device__ inline size_t knn_filter_lds_bytes(int d4, int L) {
-    return ((size_t)2 * kTile * (4 * d4 + 2) + 4 * kTile + (size_t)2 * knn_filter_waves(d4) * 4 * L) * 4;
+    return ((size_t)knn_filter_buffers(d4) * kTile * (4 * d4 + 2) + 4 * kTile + (size_t)2 * knn_filter_waves(d4) * 4 * L) * 4;
 }
 // entries per lane's list for K' = list_len candidates per query: half of K', so that the four lists of a query hold 2 K'
 __host__ inline int knn_filter_list_class(int list_len) { return list_len <= 16 ? 8 : list_len <= 24 ? 12 : 20; }
@@ -329,11 +365,13 @@ __device__ __forceinline__ double exact_distance(const float* __restrict__ x, co
 // ---------------------------------------------------------------- stage 2: exact distances of the candidates
 // One wavefront per query, one lane per candidate.  rank = number of candidates that come before in (distance, point).
 // The answer is certified when the k-th exact key, D_k - |q|^2, lies below tau by more than eps: every point the
-// filter left out has float32 key >= tau, hence exact key >= tau - eps.  eps = 4 (d + 4) 2^-24 max|x|^2 bounds the
-// rounding of the float32 norm, dot product and their combination for any pair of the cluster.
+// filter left out has float32 key >= tau, hence exact key >= tau - eps.  With x' = fl(x - centre) the rows the filter
+// saw and M = max |x'|^2 over the cluster, eps = (4 (d + 4) + 8) 2^-24 M bounds the rounding of the float32 norm,
+// dot product and their combination (4 (d + 4) u M) plus what centring in float32 moves a distance by (8 u M).
 __global__ void __launch_bounds__(256) k_knn_refine(const float* __restrict__ X, int32_t d, const int32_t* __restrict__ members,
                                                     const int32_t* __restrict__ cluster_of, const uint32_t* __restrict__ max_norm_bits,
-                                                    const int32_t* __restrict__ cand, const float* __restrict__ tau, int64_t n,
+                                                    const float* __restrict__ centre, const int32_t* __restrict__ cand,
+                                                    const float* __restrict__ tau, int64_t n,
                                                     int32_t k, int32_t list_len, int32_t* __restrict__ out,
                                                     int32_t* __restrict__ flagged, uint32_t* __restrict__ n_flagged) {
     const int64_t p = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // position in the member order
@@ -358,10 +396,14 @@ __global__ void __launch_bounds__(256) k_knn_refine(const float* __restrict__ X,
     // certification by the lane that holds the k-th neighbour (only needed when something was left out)
     const float t = tau[p];
     if (c >= 0 && rank == min(k, cnt) - 1 && t < __builtin_inff() && cnt >= k) {
-        double qn = 0.0;
-        for (int x = 0; x < d; ++x) qn = fma((double)xq[x], (double)xq[x], qn);
+        const float* ctr = centre + (int64_t)cluster_of[q] * d;
+        double qn = 0.0;   // |q'|^2 of the centred query as the filter saw it
+        for (int x = 0; x < d; ++x) {
+            const double v = (double)(xq[x] - ctr[x]);
+            qn = fma(v, v, qn);
+        }
         const double M = (double)__uint_as_float(max_norm_bits[cluster_of[q]]);
-        const double eps = 4.0 * (double)(d + 4) * 5.9604644775390625e-08 * M * 1.01 + 1e-12 * M;
+        const double eps = (4.0 * (double)(d + 4) + 8.0) * 5.9604644775390625e-08 * M * 1.01 + 1e-12 * M;
         if (!(D - qn + eps < (double)t)) flagged[atomicAdd(n_flagged, 1u)] = q;
     }
 }
