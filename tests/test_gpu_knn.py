@@ -81,3 +81,29 @@ def test_bad_arguments_are_codes():
         knn_in_clusters(np.zeros((10, 769), np.float32), c, 1, 3)
     with pytest.raises(NomadError):
         knn_in_clusters(X, np.full(10, 5, np.int32), 2, 3)       # cluster id out of range
+
+
+def test_index_output_feeds_the_epoch_path():
+    """Section 3.2 end to end on the device: clusters (given) -> in-cluster exact kNN -> symmetrised graph -> NOMAD
+    epochs.  Every edge stays inside its cluster, and the embedding keeps the clusters' neighbourhoods."""
+    from paper_2505_15511_amd import Nomad, SCATTER_DETERMINISTIC
+    from tests.np_metric import neighbourhood_preservation
+    n, d, comps, k = 20000, 64, 20, 15
+    X, c = workloads.gmm_points(n, d, comps, 16.0, 9, mix="equal", interleave=True)
+    nb = knn_in_clusters(X.cuda(), c.cuda(), comps, k)
+    assert (nb >= 0).all()
+    assert (c.cuda()[nb.long()] == c.cuda()[:, None]).all()                       # each cluster is a component of the graph
+    row_ptr, col = workloads.knn_lists_to_symmetric_csr(n, nb.cpu())
+    T = 100
+    with Nomad(n, comps, 5, 5.0, T, 1.0, 1, SCATTER_DETERMINISTIC) as nm:
+        nm.set_graph(row_ptr, col, None, c, None)
+        nm.set_embedding(workloads.init_embedding(n, 3))
+        L0 = nm.loss(0)
+        for t in range(T):
+            nm.epoch(t)
+        L1 = nm.loss(T)
+        theta = nm.get_embedding()
+    q = np.random.default_rng(0).choice(n, 4000, replace=False)
+    np15 = neighbourhood_preservation(theta, nb.cpu().numpy(), 15, q)
+    note(f"  loss {L0:.4f} -> {L1:.4f}, NP@15 against the index's own neighbours {np15:.4f}")
+    assert L1 < 0.5 * L0 and np15 > 0.02         # chance is 15 / 20000; isotropic blobs have little inner structure
