@@ -240,6 +240,26 @@ int nomad_copy_probe(void* dst, const void* src, uint64_t bytes, void* stream);
 int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const int32_t* cluster_of, int32_t n_clusters, int32_t k,
                           int32_t* out_nbrs, int mem, int32_t device, void* stream, int64_t* stats);
 
+/*
+ * Lloyd's iterations of the K-Means clustering behind the index (Section 3.2: "expectation maximization until
+ * convergence"; the initial centroids are the caller's: the paper's locality-sensitive-hash start is not specified).
+ *
+ *   X          [n*d] fp32 row-major
+ *   centroids  [K*d] fp32, in: the initial centroids, out: the final ones; 1 <= K <= n
+ *   labels     [n]   int32 out: the cluster of every point
+ *   max_iters  >= 1: E steps at most
+ *   iters_out  host int32, may be NULL: E steps run;  inertia_out  host double, may be NULL: sum over the points of
+ *              the distance to their centroid at the last E step
+ *
+ * One iteration: E step, label_i = argmin_j D(x_i, c_j) with the float64 distance of nomad_knn_in_clusters, ties to
+ * the lower j, computed with the same matrix-core filter, float64 refinement and exact fallback (so the labels are
+ * that definition exactly); M step, c_j = float32(sum of the rows of cluster j in float64, in ascending point order,
+ * / n_j), an empty cluster keeps its centroid.  Stops when an E step changes no label.  Deterministic.
+ * Same conventions, limits and errors as nomad_knn_in_clusters.
+ */
+int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t K, float* centroids, int32_t max_iters, int32_t* labels,
+                       int32_t* iters_out, double* inertia_out, int mem, int32_t device, void* stream);
+
 /* Text of the last error of this context ("" if none).  Valid until the next call on it. */
 const char* nomad_last_error(const nomad_ctx* ctx);
 

@@ -2,5 +2,5 @@
 
 Importing the package loads nothing; ``binding.load_library()`` opens the shared library and
 raises if it has not been built."""
-from .binding import (Nomad, NomadError, NomadConfig, load_library, knn_in_clusters, SCATTER_ATOMIC, SCATTER_DETERMINISTIC,
+from .binding import (Nomad, NomadError, NomadConfig, load_library, knn_in_clusters, kmeans_lloyd, SCATTER_ATOMIC, SCATTER_DETERMINISTIC,
                       NOMAD_DEVICE, NOMAD_HOST, FAR_FIELD_EXACT, FAR_FIELD_SAMPLED)  # noqa: F401

@@ -24,7 +24,7 @@ ERRORS = {-1: "NOMAD_E_INVALID_ARG", -2: "NOMAD_E_BAD_GRAPH", -3: "NOMAD_E_ORDER
 EXPORTS = ["nomad_create", "nomad_destroy", "nomad_set_graph", "nomad_set_embedding", "nomad_epoch", "nomad_loss",
            "nomad_get_embedding", "nomad_get_gradient", "nomad_get_negatives", "nomad_get_means",
            "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error",
-           "nomad_copy_probe", "nomad_knn_in_clusters"]
+           "nomad_copy_probe", "nomad_knn_in_clusters", "nomad_kmeans_lloyd"]
 
 
 class NomadConfig(C.Structure):
@@ -75,6 +75,7 @@ def load_library():
     lib.nomad_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.nomad_copy_probe.argtypes = [vp, vp, C.c_uint64, vp]
     lib.nomad_knn_in_clusters.argtypes = [vp, i64, i32, vp, i32, i32, vp, C.c_int, i32, vp, vp]
+    lib.nomad_kmeans_lloyd.argtypes = [vp, i64, i32, i32, vp, i32, vp, C.POINTER(i32), C.POINTER(C.c_double), C.c_int, i32, vp]
     lib.nomad_last_error.argtypes = [vp]
     lib.nomad_last_error.restype = C.c_char_p
     _lib = lib
@@ -140,6 +141,38 @@ def knn_in_clusters(X, cluster_of, n_clusters, k, device=0, stream=None, return_
     if rc:
         raise NomadError(rc, "nomad_knn_in_clusters")
     return (out, dict(fallback_queries=int(stats[0]), filter_pairs=int(stats[1]))) if return_stats else out
+
+
+def kmeans_lloyd(X, centroids, max_iters, device=0, stream=None):
+    """nomad_kmeans_lloyd: Lloyd's iterations from the given centroids.  X and centroids: both torch tensors on the
+    device, or both host arrays.  Returns (centroids [K, d] float32, labels [n] int32, iterations, inertia), the arrays
+    where the inputs live; the input centroids are not modified."""
+    lib = load_library()
+    n, d = int(X.shape[0]), int(X.shape[1])
+    K = int(centroids.shape[0])
+    px, m0, keep_x = _marshal(X, np.float32, n * d)
+    if _is_torch(centroids):
+        cen = centroids.to(dtype=keep_x.dtype if _is_torch(keep_x) else None).clone().contiguous()
+    else:
+        cen = np.array(centroids, dtype=np.float32, order="C", copy=True)
+    pc, m1, keep_c = _marshal(cen, np.float32, K * d)
+    if m0 != m1:
+        raise ValueError("X and centroids must live in the same memory space")
+    if m0 == NOMAD_DEVICE:
+        import torch
+        labels = torch.empty(n, dtype=torch.int32, device=keep_x.device)
+        pl = C.c_void_p(labels.data_ptr())
+        if stream is None:
+            stream = torch.cuda.current_stream(device).cuda_stream
+    else:
+        labels = np.empty(n, dtype=np.int32)
+        pl = labels.ctypes.data_as(C.c_void_p)
+    iters, inertia = C.c_int32(0), C.c_double(0.0)
+    rc = lib.nomad_kmeans_lloyd(px, n, d, K, pc, int(max_iters), pl, C.byref(iters), C.byref(inertia), m0, int(device),
+                                C.c_void_p(int(stream) if stream else None))
+    if rc:
+        raise NomadError(rc, "nomad_kmeans_lloyd")
+    return keep_c, labels, int(iters.value), float(inertia.value)
 
 
 class Nomad:

@@ -1,5 +1,6 @@
 // libnomad: the in-cluster exact nearest-neighbour index behind the C ABI of include/nomad.h (host side).
 #include <hip/hip_runtime.h>
+#include <hipcub/hipcub.hpp>
 
 #include <algorithm>
 #include <cmath>
@@ -33,24 +34,59 @@ struct Buffers {   // device allocations of one call, released on every path
 inline uint32_t blocks_of(int64_t items, int per) { return (uint32_t)((items + per - 1) / per); }
 
 template <int D4, int L>
-hipError_t launch_filter_dl(hipStream_t st, uint32_t n_blocks, const float* X, int32_t d, const float* norm, const int32_t* members,
-                            const uint32_t* start, const KnnBlock* blocks, const float* centre, int32_t list_len, int32_t* cand, float* tau) {
+hipError_t launch_filter_dl(hipStream_t st, uint32_t n_blocks, const KnnSets& P, const KnnBlock* blocks, int32_t list_len, int32_t* cand,
+                            float* tau) {
     const size_t lds = knn_filter_lds_bytes(D4, L);
     hipError_t e = hipFuncSetAttribute((const void*)k_knn_filter<D4, L>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((k_knn_filter<D4, L>), dim3(n_blocks), dim3(64 * knn_filter_waves(D4)), lds, st, X, d, norm, members, start, blocks,
-                       centre, list_len, cand, tau);
+    hipLaunchKernelGGL((k_knn_filter<D4, L>), dim3(n_blocks), dim3(64 * knn_filter_waves(D4)), lds, st, P, blocks, list_len, cand, tau);
     return hipGetLastError();
 }
 
 template <int D4>
-hipError_t launch_filter(hipStream_t st, uint32_t n_blocks, const float* X, int32_t d, const float* norm, const int32_t* members,
-                         const uint32_t* start, const KnnBlock* blocks, const float* centre, int32_t list_len, int32_t* cand, float* tau) {
+hipError_t launch_filter_d(hipStream_t st, uint32_t n_blocks, const KnnSets& P, const KnnBlock* blocks, int32_t list_len, int32_t* cand,
+                           float* tau) {
     switch (knn_filter_list_class(list_len)) {
-        case 8: return launch_filter_dl<D4, 8>(st, n_blocks, X, d, norm, members, start, blocks, centre, list_len, cand, tau);
-        case 12: return launch_filter_dl<D4, 12>(st, n_blocks, X, d, norm, members, start, blocks, centre, list_len, cand, tau);
-        default: return launch_filter_dl<D4, 20>(st, n_blocks, X, d, norm, members, start, blocks, centre, list_len, cand, tau);
+        case 8: return launch_filter_dl<D4, 8>(st, n_blocks, P, blocks, list_len, cand, tau);
+        case 12: return launch_filter_dl<D4, 12>(st, n_blocks, P, blocks, list_len, cand, tau);
+        default: return launch_filter_dl<D4, 20>(st, n_blocks, P, blocks, list_len, cand, tau);
     }
+}
+
+// width class of the filter kernel for rows of d values
+inline int width_class(int32_t d) {
+    const int d4 = (d + 3) / 4;
+    return d4 <= 8 ? 8 : d4 <= 16 ? 16 : d4 <= 32 ? 32 : d4 <= 64 ? 64 : d4 <= 128 ? 128 : 192;
+}
+
+hipError_t launch_filter(hipStream_t st, uint32_t n_blocks, const KnnSets& P, const KnnBlock* blocks, int32_t list_len, int32_t* cand,
+                         float* tau) {
+    switch (width_class(P.d)) {
+        case 8: return launch_filter_d<8>(st, n_blocks, P, blocks, list_len, cand, tau);
+        case 16: return launch_filter_d<16>(st, n_blocks, P, blocks, list_len, cand, tau);
+        case 32: return launch_filter_d<32>(st, n_blocks, P, blocks, list_len, cand, tau);
+        case 64: return launch_filter_d<64>(st, n_blocks, P, blocks, list_len, cand, tau);
+        case 128: return launch_filter_d<128>(st, n_blocks, P, blocks, list_len, cand, tau);
+        default: return launch_filter_d<192>(st, n_blocks, P, blocks, list_len, cand, tau);
+    }
+}
+
+// The k nearest candidates of every query inside its group (filter, refinement, exact fallback).  `cand` [n_q * (k + kPad)],
+// `tau` [n_q], `flagged` [n_q], `n_flagged` [1] are work space; blocks: the filter's work list (n_blocks entries).
+int nearest_in_groups(hipStream_t st, const KnnSets& P, const KnnBlock* blocks, uint32_t n_blocks, int32_t k, int32_t* cand, float* tau,
+                      int32_t* flagged, uint32_t* n_flagged, int32_t* out, uint32_t* flagged_count) {
+    const int32_t list_len = k + kPad;
+    KTRY(hipMemsetAsync(cand, 0xFF, sizeof(int32_t) * (size_t)P.n_q * list_len, st));   // every slot "no candidate" until the filter fills it
+    KTRY(hipMemsetAsync(n_flagged, 0, sizeof(uint32_t), st));
+    KTRY(launch_filter(st, n_blocks, P, blocks, list_len, cand, tau));
+    hipLaunchKernelGGL(k_knn_refine, dim3(blocks_of(P.n_q, 4)), dim3(256), 0, st, P, cand, tau, k, list_len, out, flagged, n_flagged);
+    uint32_t hflag = 0;
+    KTRY(hipMemcpyAsync(&hflag, n_flagged, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    KTRY(hipStreamSynchronize(st));
+    if (hflag) hipLaunchKernelGGL(k_knn_exact, dim3(hflag), dim3(256), 0, st, P, flagged, k, out);
+    KTRY(hipGetLastError());
+    *flagged_count = hflag;
+    return NOMAD_OK;
 }
 
 }  // namespace
@@ -105,9 +141,7 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     KTRY(hipMemsetAsync(counts, 0, sizeof(uint32_t) * (size_t)R, st));
     KTRY(hipMemsetAsync(cursor, 0, sizeof(uint32_t) * (size_t)R, st));
     KTRY(hipMemsetAsync(max_norm, 0, sizeof(uint32_t) * (size_t)R, st));
-    KTRY(hipMemsetAsync(n_flagged, 0, sizeof(uint32_t), st));
     KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
-    KTRY(hipMemsetAsync(cand, 0xFF, sizeof(int32_t) * (size_t)n * list_len, st));   // every slot "no candidate" until the filter fills it
     hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, 256)), dim3(256), 0, st, dC, n, R, counts, bad);
     std::vector<uint32_t> hcounts(R), hstart((size_t)R + 1, 0);
     int hbad = 0;
@@ -116,9 +150,7 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     KTRY(hipStreamSynchronize(st));
     if (hbad) return NOMAD_E_BAD_GRAPH;   // a cluster id outside 0..n_clusters-1
     // the width class of the filter kernel decides how many queries a workgroup takes
-    const int d4 = (d + 3) / 4;
-    const int d4_class = d4 <= 8 ? 8 : d4 <= 16 ? 16 : d4 <= 32 ? 32 : d4 <= 64 ? 64 : d4 <= 128 ? 128 : 192;
-    const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(d4_class));
+    const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(width_class(d)));
     std::vector<KnnBlock> hblocks, hslabs;
     for (int32_t r = 0; r < R; ++r) {
         hstart[r + 1] = hstart[r] + hcounts[r];
@@ -136,30 +168,13 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of((int64_t)R * d, 256)), dim3(256), 0, st, centre, start, R, d);
     hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, dX, n, d, dC, centre, norm, max_norm);
 
-    // stage 1: float32 filter on the matrix cores
-    hipError_t e = hipErrorInvalidValue;
-    const uint32_t nb = (uint32_t)hblocks.size();
-#define NOMAD_KNN_CASE(D4)                                                                                             \
-    e = launch_filter<D4>(st, nb, dX, d, norm, members, start, blocks, centre, list_len, cand, tau)
-    if (d4_class == 8) NOMAD_KNN_CASE(8);
-    else if (d4_class == 16) NOMAD_KNN_CASE(16);
-    else if (d4_class == 32) NOMAD_KNN_CASE(32);
-    else if (d4_class == 64) NOMAD_KNN_CASE(64);
-    else if (d4_class == 128) NOMAD_KNN_CASE(128);
-    else NOMAD_KNN_CASE(192);
-#undef NOMAD_KNN_CASE
-    KTRY(e);
-
-    // stage 2: exact distances of the candidates, certification
-    hipLaunchKernelGGL(k_knn_refine, dim3(blocks_of(n, 4)), dim3(256), 0, st, dX, d, members, dC, max_norm, centre, cand, tau, n, k, list_len,
-                       dOut, flagged, n_flagged);
+    // filter on the matrix cores, float64 refinement, exact fallback
+    KnnSets P{};
+    P.XQ = dX; P.XC = dX; P.qmembers = members; P.cmembers = members; P.qstart = start; P.cstart = start;
+    P.cnorm = norm; P.centre = centre; P.group_of_q = dC; P.max_norm_bits = max_norm; P.n_q = n; P.n_c = n; P.d = d; P.same_set = 1;
     uint32_t hflag = 0;
-    KTRY(hipMemcpyAsync(&hflag, n_flagged, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-    KTRY(hipStreamSynchronize(st));
-
-    // stage 3: what could not be certified, exactly
-    if (hflag) hipLaunchKernelGGL(k_knn_exact, dim3(hflag), dim3(256), 0, st, dX, d, members, start, dC, flagged, k, dOut);
-    KTRY(hipGetLastError());
+    int rc = nearest_in_groups(st, P, blocks, (uint32_t)hblocks.size(), k, cand, tau, flagged, n_flagged, dOut, &hflag);
+    if (rc) return rc;
     if (mem == NOMAD_HOST) KTRY(hipMemcpyAsync(out_nbrs, dOut, sizeof(int32_t) * (size_t)n * k, hipMemcpyDeviceToHost, st));
     KTRY(hipStreamSynchronize(st));
     if (stats) {
@@ -168,6 +183,124 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
         for (int32_t r = 0; r < R; ++r) pairs += (int64_t)hcounts[r] * (int64_t)hcounts[r];
         stats[1] = pairs;
     }
+    return NOMAD_OK;
+}
+
+extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t K, float* centroids, int32_t max_iters, int32_t* labels,
+                                  int32_t* iters_out, double* inertia_out, int mem, int32_t device, void* stream) {
+    if (!X || !centroids || !labels || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return NOMAD_E_INVALID_ARG;
+    if (n < 1 || d < 1 || d > NOMAD_KNN_MAX_DIM || K < 1 || K > n || max_iters < 1 || device < 0) return NOMAD_E_INVALID_ARG;
+    if (n >= ((int64_t)1 << 31) - 256) return NOMAD_E_TOO_LARGE;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) return NOMAD_E_HIP;
+    KTRY(hipSetDevice(device));
+    hipStream_t st = (hipStream_t)stream;
+    Buffers buf;
+    const int32_t k = 1, list_len = k + kPad;
+
+    const float* dX = X;
+    float* dC = centroids;
+    int32_t* dLab = labels;
+    if (mem == NOMAD_HOST) {
+        float *x = nullptr, *c = nullptr;
+        int32_t* l = nullptr;
+        KTRY(buf.alloc(&x, (size_t)n * d));
+        KTRY(buf.alloc(&c, (size_t)K * d));
+        KTRY(buf.alloc(&l, (size_t)n));
+        KTRY(hipMemcpyAsync(x, X, sizeof(float) * (size_t)n * d, hipMemcpyHostToDevice, st));
+        KTRY(hipMemcpyAsync(c, centroids, sizeof(float) * (size_t)K * d, hipMemcpyHostToDevice, st));
+        dX = x; dC = c; dLab = l;
+    }
+    // work space
+    uint32_t *qstart = nullptr, *cstart = nullptr, *lstart = nullptr, *counts = nullptr, *max_pts = nullptr, *max_norm = nullptr, *n_flagged = nullptr;
+    int32_t *new_lab = nullptr, *cand = nullptr, *flagged = nullptr, *ids_in = nullptr, *ids = nullptr, *keys = nullptr;
+    float *cnorm = nullptr, *tau = nullptr, *centre = nullptr, *c_used = nullptr;
+    unsigned long long* changed = nullptr;
+    double* inertia = nullptr;
+    int* bad = nullptr;
+    KnnBlock *blocks = nullptr, *slabs = nullptr;
+    KTRY(buf.alloc(&qstart, 2)); KTRY(buf.alloc(&cstart, 2)); KTRY(buf.alloc(&lstart, (size_t)K + 1)); KTRY(buf.alloc(&counts, (size_t)K));
+    KTRY(buf.alloc(&max_pts, 1)); KTRY(buf.alloc(&max_norm, 1)); KTRY(buf.alloc(&n_flagged, 1)); KTRY(buf.alloc(&bad, 1));
+    KTRY(buf.alloc(&new_lab, (size_t)n)); KTRY(buf.alloc(&cand, (size_t)n * list_len)); KTRY(buf.alloc(&flagged, (size_t)n));
+    KTRY(buf.alloc(&ids_in, (size_t)n)); KTRY(buf.alloc(&ids, (size_t)n)); KTRY(buf.alloc(&keys, (size_t)n));
+    KTRY(buf.alloc(&cnorm, (size_t)K)); KTRY(buf.alloc(&tau, (size_t)n)); KTRY(buf.alloc(&centre, (size_t)d)); KTRY(buf.alloc(&c_used, (size_t)K * d));
+    KTRY(buf.alloc(&changed, 1)); KTRY(buf.alloc(&inertia, 1));
+    const uint32_t hq[2] = {0u, (uint32_t)n}, hc[2] = {0u, (uint32_t)K};
+    KTRY(hipMemcpyAsync(qstart, hq, sizeof(hq), hipMemcpyHostToDevice, st));
+    KTRY(hipMemcpyAsync(cstart, hc, sizeof(hc), hipMemcpyHostToDevice, st));
+    const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(width_class(d)));
+    std::vector<KnnBlock> hblocks, hslabs;
+    for (int64_t q0 = 0; q0 < n; q0 += block_queries) hblocks.push_back(KnnBlock{0, (int32_t)q0});
+    for (int64_t q0 = 0; q0 < n; q0 += kCentroidRows) hslabs.push_back(KnnBlock{0, (int32_t)q0});
+    KTRY(buf.alloc(&blocks, hblocks.size()));
+    KTRY(buf.alloc(&slabs, hslabs.size()));
+    KTRY(hipMemcpyAsync(blocks, hblocks.data(), sizeof(KnnBlock) * hblocks.size(), hipMemcpyHostToDevice, st));
+    KTRY(hipMemcpyAsync(slabs, hslabs.data(), sizeof(KnnBlock) * hslabs.size(), hipMemcpyHostToDevice, st));
+    // both sides are centred on the mean of the points; the largest centred |x|^2 of the points, once
+    KTRY(hipMemsetAsync(centre, 0, sizeof(float) * (size_t)d, st));
+    KTRY(hipMemsetAsync(max_pts, 0, sizeof(uint32_t), st));
+    hipLaunchKernelGGL(k_knn_centroid_sums, dim3((uint32_t)hslabs.size()), dim3(256), 0, st, dX, d, (const int32_t*)nullptr, qstart, slabs, centre);
+    hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of(d, 256)), dim3(256), 0, st, centre, qstart, 1, d);
+    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, dX, n, d, (const int32_t*)nullptr, centre, (float*)nullptr, max_pts);
+    hipLaunchKernelGGL(k_iota, dim3(blocks_of(n, 256)), dim3(256), 0, st, ids_in, n);
+    // radix sort work space (points sorted by label, stable: ascending inside a cluster)
+    int end_bit = 1;
+    while (((int64_t)1 << end_bit) < K) ++end_bit;
+    size_t sort_bytes = 0;
+    KTRY(hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const int32_t*)dLab, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
+    void* sort_tmp = nullptr;
+    KTRY(buf.alloc((char**)&sort_tmp, sort_bytes));
+
+    KnnSets P{};
+    P.XQ = dX; P.XC = dC; P.qmembers = nullptr; P.cmembers = nullptr; P.qstart = qstart; P.cstart = cstart;
+    P.cnorm = cnorm; P.centre = centre; P.group_of_q = nullptr; P.max_norm_bits = max_norm; P.n_q = n; P.n_c = K; P.d = d; P.same_set = 0;
+    int32_t it = 0;
+    bool have_labels = false;
+    std::vector<uint32_t> hcounts(K), hstart((size_t)K + 1, 0);
+    while (it < max_iters) {
+        // E step: the nearest centroid of every point, exactly
+        KTRY(hipMemcpyAsync(max_norm, max_pts, sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
+        hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(K, 256)), dim3(256), 0, st, (const float*)dC, (int64_t)K, d, (const int32_t*)nullptr, centre, cnorm,
+                           max_norm);
+        uint32_t hflag = 0;
+        int rc = nearest_in_groups(st, P, blocks, (uint32_t)hblocks.size(), k, cand, tau, flagged, n_flagged, new_lab, &hflag);
+        if (rc) return rc;
+        ++it;
+        KTRY(hipMemcpyAsync(c_used, dC, sizeof(float) * (size_t)K * d, hipMemcpyDeviceToDevice, st));
+        unsigned long long hchanged = 1;
+        if (have_labels) {
+            KTRY(hipMemsetAsync(changed, 0, sizeof(unsigned long long), st));
+            hipLaunchKernelGGL(k_kmeans_changed, dim3(blocks_of(n, 256)), dim3(256), 0, st, (const int32_t*)new_lab, (const int32_t*)dLab, n, changed);
+            KTRY(hipMemcpyAsync(&hchanged, changed, sizeof(hchanged), hipMemcpyDeviceToHost, st));
+            KTRY(hipStreamSynchronize(st));
+        }
+        if (have_labels && hchanged == 0) break;   // nothing moved: the centroids are the means of these labels already
+        KTRY(hipMemcpyAsync(dLab, new_lab, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, st));
+        have_labels = true;
+        // M step
+        KTRY(hipMemsetAsync(counts, 0, sizeof(uint32_t) * (size_t)K, st));
+        KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
+        hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, 256)), dim3(256), 0, st, (const int32_t*)dLab, n, K, counts, bad);
+        KTRY(hipMemcpyAsync(hcounts.data(), counts, sizeof(uint32_t) * (size_t)K, hipMemcpyDeviceToHost, st));
+        KTRY(hipStreamSynchronize(st));
+        for (int32_t j = 0; j < K; ++j) hstart[j + 1] = hstart[j] + hcounts[j];
+        KTRY(hipMemcpyAsync(lstart, hstart.data(), sizeof(uint32_t) * ((size_t)K + 1), hipMemcpyHostToDevice, st));
+        KTRY(hipcub::DeviceRadixSort::SortPairs(sort_tmp, sort_bytes, (const int32_t*)dLab, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
+        hipLaunchKernelGGL(k_kmeans_update, dim3(blocks_of((int64_t)K * d, 256)), dim3(256), 0, st, dX, d, (const int32_t*)ids, (const uint32_t*)lstart, K, dC);
+    }
+    // inertia of the labels against the centroids they were computed from
+    double hinertia = 0.0;
+    KTRY(hipMemsetAsync(inertia, 0, sizeof(double), st));
+    hipLaunchKernelGGL(k_kmeans_inertia, dim3(blocks_of(n, 256)), dim3(256), 0, st, dX, (const float*)c_used, d, (const int32_t*)dLab, n, inertia);
+    KTRY(hipMemcpyAsync(&hinertia, inertia, sizeof(double), hipMemcpyDeviceToHost, st));
+    KTRY(hipGetLastError());
+    if (mem == NOMAD_HOST) {
+        KTRY(hipMemcpyAsync(centroids, dC, sizeof(float) * (size_t)K * d, hipMemcpyDeviceToHost, st));
+        KTRY(hipMemcpyAsync(labels, dLab, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost, st));
+    }
+    KTRY(hipStreamSynchronize(st));
+    if (iters_out) *iters_out = it;
+    if (inertia_out) *inertia_out = hinertia;
     return NOMAD_OK;
 }
 #pragma GCC visibility pop

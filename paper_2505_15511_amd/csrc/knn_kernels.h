@@ -30,7 +30,27 @@ __host__ __device__ constexpr int knn_filter_waves(int d4) { return d4 >= 128 ? 
 // LDS buffers for the staged candidate tile: two, or one at the widest rows (see the kernel)
 __host__ __device__ constexpr int knn_filter_buffers(int d4) { return d4 > 64 ? 1 : 2; }
 
-struct KnnBlock { int32_t cluster; int32_t q0; };   // queries members[start[cluster] + q0 ..] of one workgroup
+struct KnnBlock { int32_t cluster; int32_t q0; };   // queries q0 .. of group `cluster`: one workgroup's share
+
+// Queries and candidates, both cut into the same groups (group g: queries qmembers[qstart[g] .. qstart[g+1]), candidates
+// cmembers[cstart[g] .. cstart[g+1])).  Nearest neighbours inside clusters: both are the data set grouped by cluster.
+// K-Means assignment: one group, the queries are the points, the candidates the centroids.
+struct KnnSets {
+    const float* XQ;             // query rows
+    const float* XC;             // candidate rows
+    const int32_t* qmembers;     // query row of every position, or nullptr = the position itself
+    const int32_t* cmembers;     // candidate row of every position, or nullptr = the position itself
+    const uint32_t* qstart;      // [groups + 1]
+    const uint32_t* cstart;      // [groups + 1]
+    const float* cnorm;          // |c'|^2 of every candidate row (centred, float32)
+    const float* centre;         // [groups][d] what both sides are centred on
+    const int32_t* group_of_q;   // group of every query row, or nullptr = group 0
+    const uint32_t* max_norm_bits;   // [groups] largest centred |.|^2 over the group's queries and candidates
+    int64_t n_q, n_c;            // rows of XQ, XC
+    int32_t d;
+    int32_t same_set;            // 1: queries and candidates are the same rows: a row is not its own neighbour
+};
+__device__ __forceinline__ int32_t knn_row(const int32_t* members, uint32_t pos) { return members ? members[pos] : (int32_t)pos; }
 
 // Distances do not change when a cluster is moved as a whole, and the float32 error of the filter grows with |x|^2:
 // the filter therefore works on rows centred on their cluster, x' = fl(x - c_r), c_r = the cluster's mean in float32.
@@ -44,7 +64,7 @@ __global__ void __launch_bounds__(256) k_knn_centroid_sums(const float* __restri
     const uint32_t r0 = c0 + (uint32_t)sl.q0, r1 = min(c1, r0 + (uint32_t)kCentroidRows);
     for (int col = threadIdx.x; col < d; col += 256) {
         float s = 0.f;
-        for (uint32_t r = r0; r < r1; ++r) s += X[(int64_t)members[r] * d + col];
+        for (uint32_t r = r0; r < r1; ++r) s += X[(int64_t)knn_row(members, r) * d + col];
         atomicAdd(&centre[(int64_t)sl.cluster * d + col], s);
     }
 }
@@ -63,14 +83,15 @@ __global__ void __launch_bounds__(256) k_knn_norms(const float* __restrict__ X, 
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const float* x = X + i * d;
-    const float* c = centre + (int64_t)cluster_of[i] * d;
+    const int32_t g = cluster_of ? cluster_of[i] : 0;
+    const float* c = centre + (int64_t)g * d;
     float s = 0.f;
     for (int t = 0; t < d; ++t) {
         const float v = x[t] - c[t];
         s = fmaf(v, v, s);
     }
-    norm[i] = s;
-    atomicMax(&max_norm_bits[cluster_of[i]], __float_as_uint(s));   // non-negative floats order like their bit patterns
+    if (norm) norm[i] = s;
+    atomicMax(&max_norm_bits[g], __float_as_uint(s));   // non-negative floats order like their bit patterns
 }
 
 __global__ void __launch_bounds__(256) k_knn_count(const int32_t* __restrict__ cluster_of, int64_t n, int32_t R, uint32_t* __restrict__ counts,
@@ -113,10 +134,11 @@ __global__ void __launch_bounds__(256) k_knn_group(const int32_t* __restrict__ c
 // a query are merged: the K' smallest keys go on, tau = min(K'-th key of the union, the four lists' last keys):
 // every candidate that is not passed on has key >= tau.
 template <int D4, int L>
-__global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const float* __restrict__ X, int32_t d, const float* __restrict__ norm,
-                                                                         const int32_t* __restrict__ members, const uint32_t* __restrict__ start,
-                                                                         const KnnBlock* __restrict__ blocks, const float* __restrict__ centre,
-                                                                         int32_t list_len, int32_t* __restrict__ cand, float* __restrict__ tau_out) {
+__global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const KnnSets P, const KnnBlock* __restrict__ blocks, int32_t list_len,
+                                                                         int32_t* __restrict__ cand, float* __restrict__ tau_out) {
+    const float* __restrict__ X = P.XC;        // candidate rows (the loop's stream)
+    const float* __restrict__ norm = P.cnorm;
+    const int32_t d = P.d;
     constexpr int kFilterBlock = 64 * knn_filter_waves(D4);
     constexpr int kRow = 4 * D4 + 2;
     constexpr int kTileWords = kTile * kRow;
@@ -133,17 +155,20 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
     int32_t* mpt = (int32_t*)(mkey + knn_filter_waves(D4) * kMerge);   // [waves][kMerge]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const KnnBlock blk = blocks[blockIdx.x];
-    const uint32_t c0 = start[blk.cluster], c1 = start[blk.cluster + 1];
-    const int32_t n_r = (int32_t)(c1 - c0);
+    const uint32_t c0 = P.cstart[blk.cluster], c1 = P.cstart[blk.cluster + 1];
+    const int32_t n_r = (int32_t)(c1 - c0);                    // candidates of the group
+    const uint32_t q0g = P.qstart[blk.cluster];
+    const int32_t n_qg = (int32_t)(P.qstart[blk.cluster + 1] - q0g);   // queries of the group
     // this lane's query and its slice of the row
     const int32_t qpos = blk.q0 + wave * kWaveQueries + (lane & 15);
-    const int32_t qpt = qpos < n_r ? members[c0 + qpos] : -1;
-    const float* ctr = centre + (int64_t)blk.cluster * d;      // the cluster's centre: every row enters as x - centre
+    const int32_t qpt = qpos < n_qg ? knn_row(P.qmembers, q0g + qpos) : -1;
+    const int32_t self = P.same_set ? qpt : -1;               // the candidate that is the query itself, if any
+    const float* ctr = P.centre + (int64_t)blk.cluster * d;    // the group's centre: every row enters as x - centre
     float breg[D4];
 #pragma unroll
     for (int t = 0; t < D4; ++t) {
         const int col = 4 * t + (lane >> 4);
-        breg[t] = (qpt >= 0 && col < d) ? X[(int64_t)qpt * d + col] - ctr[col] : 0.f;
+        breg[t] = (qpt >= 0 && col < d) ? P.XQ[(int64_t)qpt * d + col] - ctr[col] : 0.f;
     }
     float lk[L];      // this lane's L smallest keys so far, ascending
     int32_t lp[L];    // and their points
@@ -161,7 +186,7 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
         cchunk[u] = make_float4(col < d ? ctr[col] : 0.f, col + 1 < d ? ctr[col + 1] : 0.f, col + 2 < d ? ctr[col + 2] : 0.f,
                                 col + 3 < d ? ctr[col + 3] : 0.f);
     }
-    auto point_at = [&](int32_t pos) { return pos < n_r ? members[c0 + pos] : -1; };
+    auto point_at = [&](int32_t pos) { return pos < n_r ? knn_row(P.cmembers, c0 + pos) : -1; };
     // loads of this thread's chunks of the row of point pt (any valid row when pt < 0; masked when it is stored)
     auto fetch = [&](Staged& S, int32_t pt) {
         S.pt = pt;
@@ -207,7 +232,7 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
             const int i = 4 * (lane >> 4) + v;
             const int32_t cpt = tile_pt[buf * kTile + i];
             float key = tnorm[buf * kTile + i] - 2.f * acc[v];
-            if (cpt < 0 || cpt == qpt || qpt < 0) key = __builtin_inff();
+            if (cpt < 0 || cpt == self || qpt < 0) key = __builtin_inff();
             if (__any(key < lk[L - 1])) {
                 float xk = key;       // an infinite key changes nothing below
                 int32_t xp = cpt;
@@ -318,7 +343,7 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
         const int32_t jq_pos = __shfl(qpos, j, 64);
         const float jq_thr = __shfl(thr, j, 64);
         if (jq_pt >= 0) {
-            const int64_t p = (int64_t)c0 + jq_pos;
+            const int64_t p = (int64_t)q0g + jq_pos;
             if (lane < kMerge && r0 < list_len) cand[p * list_len + r0] = p0 >= kEmptyPoint ? -1 : p0;
             if (lane + 64 < kMerge && r1 < list_len) cand[p * list_len + r1] = p1 >= kEmptyPoint ? -1 : p1;
             // tau: the K'-th key of the union (inf if there is none) and the lists' last keys
@@ -368,20 +393,18 @@ __device__ __forceinline__ double exact_distance(const float* __restrict__ x, co
 // filter left out has float32 key >= tau, hence exact key >= tau - eps.  With x' = fl(x - centre) the rows the filter
 // saw and M = max |x'|^2 over the cluster, eps = (4 (d + 4) + 8) 2^-24 M bounds the rounding of the float32 norm,
 // dot product and their combination (4 (d + 4) u M) plus what centring in float32 moves a distance by (8 u M).
-__global__ void __launch_bounds__(256) k_knn_refine(const float* __restrict__ X, int32_t d, const int32_t* __restrict__ members,
-                                                    const int32_t* __restrict__ cluster_of, const uint32_t* __restrict__ max_norm_bits,
-                                                    const float* __restrict__ centre, const int32_t* __restrict__ cand,
-                                                    const float* __restrict__ tau, int64_t n,
+__global__ void __launch_bounds__(256) k_knn_refine(const KnnSets P, const int32_t* __restrict__ cand, const float* __restrict__ tau,
                                                     int32_t k, int32_t list_len, int32_t* __restrict__ out,
                                                     int32_t* __restrict__ flagged, uint32_t* __restrict__ n_flagged) {
-    const int64_t p = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // position in the member order
+    const int64_t p = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // position in the grouped query order
     const int lane = threadIdx.x & 63;
-    if (p >= n) return;
-    const int32_t q = members[p];
-    const float* xq = X + (int64_t)q * d;
+    const int32_t d = P.d;
+    if (p >= P.n_q) return;
+    const int32_t q = knn_row(P.qmembers, (uint32_t)p);
+    const float* xq = P.XQ + (int64_t)q * d;
     int32_t c = lane < list_len ? cand[p * list_len + lane] : -1;
-    if (c >= n) c = -1;   // never an address outside X, whatever the list holds
-    const double D = c >= 0 ? exact_distance(xq, X + (int64_t)c * d, d) : __builtin_inf();
+    if (c >= P.n_c) c = -1;   // never an address outside the candidate rows, whatever the list holds
+    const double D = c >= 0 ? exact_distance(xq, P.XC + (int64_t)c * d, d) : __builtin_inf();
     int rank = 0, cnt = 0;
     for (int o = 0; o < list_len; ++o) {
         const double Do = __shfl(D, o, 64);
@@ -392,17 +415,18 @@ __global__ void __launch_bounds__(256) k_knn_refine(const float* __restrict__ X,
         }
     }
     if (c >= 0 && rank < k) out[(int64_t)q * k + rank] = c;
-    if (lane >= cnt && lane < k) out[(int64_t)q * k + lane] = -1;   // cluster smaller than k + 1
+    if (lane >= cnt && lane < k) out[(int64_t)q * k + lane] = -1;   // fewer than k candidates in the group
     // certification by the lane that holds the k-th neighbour (only needed when something was left out)
     const float t = tau[p];
     if (c >= 0 && rank == min(k, cnt) - 1 && t < __builtin_inff() && cnt >= k) {
-        const float* ctr = centre + (int64_t)cluster_of[q] * d;
+        const int32_t g = P.group_of_q ? P.group_of_q[q] : 0;
+        const float* ctr = P.centre + (int64_t)g * d;
         double qn = 0.0;   // |q'|^2 of the centred query as the filter saw it
         for (int x = 0; x < d; ++x) {
             const double v = (double)(xq[x] - ctr[x]);
             qn = fma(v, v, qn);
         }
-        const double M = (double)__uint_as_float(max_norm_bits[cluster_of[q]]);
+        const double M = (double)__uint_as_float(P.max_norm_bits[g]);
         const double eps = (4.0 * (double)(d + 4) + 8.0) * 5.9604644775390625e-08 * M * 1.01 + 1e-12 * M;
         if (!(D - qn + eps < (double)t)) flagged[atomicAdd(n_flagged, 1u)] = q;
     }
@@ -410,24 +434,24 @@ __global__ void __launch_bounds__(256) k_knn_refine(const float* __restrict__ X,
 
 // ---------------------------------------------------------------- stage 3: flagged queries, exactly, against the whole cluster
 // One workgroup per flagged query: k rounds, each picking the smallest (distance, point) above the one picked before.
-__global__ void __launch_bounds__(256) k_knn_exact(const float* __restrict__ X, int32_t d, const int32_t* __restrict__ members,
-                                                   const uint32_t* __restrict__ start, const int32_t* __restrict__ cluster_of,
-                                                   const int32_t* __restrict__ flagged, int32_t k, int32_t* __restrict__ out) {
+__global__ void __launch_bounds__(256) k_knn_exact(const KnnSets P, const int32_t* __restrict__ flagged, int32_t k, int32_t* __restrict__ out) {
     __shared__ double sD[256];
     __shared__ int32_t sP[256];
+    const int32_t d = P.d;
     const int32_t q = flagged[blockIdx.x];
-    const int32_t r = cluster_of[q];
-    const uint32_t c0 = start[r], c1 = start[r + 1];
-    const float* xq = X + (int64_t)q * d;
+    const int32_t r = P.group_of_q ? P.group_of_q[q] : 0;
+    const uint32_t c0 = P.cstart[r], c1 = P.cstart[r + 1];
+    const float* xq = P.XQ + (int64_t)q * d;
+    const int32_t self = P.same_set ? q : -1;
     double lastD = -1.0;
     int32_t lastP = -1;
     for (int m = 0; m < k; ++m) {
         double bestD = __builtin_inf();
         int32_t bestP = -1;
         for (uint32_t pos = c0 + threadIdx.x; pos < c1; pos += 256) {
-            const int32_t c = members[pos];
-            if (c == q) continue;
-            const double D = exact_distance(xq, X + (int64_t)c * d, d);
+            const int32_t c = knn_row(P.cmembers, pos);
+            if (c == self) continue;
+            const double D = exact_distance(xq, P.XC + (int64_t)c * d, d);
             const bool after = D > lastD || (D == lastD && c > lastP);
             const bool better = D < bestD || (D == bestD && (bestP < 0 || c < bestP));
             if (after && better) { bestD = D; bestP = c; }
@@ -446,13 +470,56 @@ __global__ void __launch_bounds__(256) k_knn_exact(const float* __restrict__ X, 
         }
         lastD = sD[0];
         lastP = sP[0];
-        if (threadIdx.x == 0) out[(int64_t)q * k + m] = lastP;   // -1 once the cluster is exhausted
+        if (threadIdx.x == 0) out[(int64_t)q * k + m] = lastP;   // -1 once the group is exhausted
         __syncthreads();
         if (lastP < 0) {   // nothing left: the remaining slots stay empty
             for (int x = m + 1 + threadIdx.x; x < k; x += 256) out[(int64_t)q * k + x] = -1;
             break;
         }
     }
+}
+
+// ---------------------------------------------------------------- Lloyd's iterations (the K-Means index of Section 3.2)
+__global__ void __launch_bounds__(256) k_iota(int32_t* __restrict__ v, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) v[i] = (int32_t)i;
+}
+
+// how many points changed their cluster
+__global__ void __launch_bounds__(256) k_kmeans_changed(const int32_t* __restrict__ a, const int32_t* __restrict__ b, int64_t n,
+                                                        unsigned long long* __restrict__ changed) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool diff = i < n && a[i] != b[i];
+    const unsigned long long m = __ballot(diff);
+    if ((threadIdx.x & 63) == 0 && m) atomicAdd(changed, (unsigned long long)__popcll(m));
+}
+
+// M step: centroid j = float32(sum of its rows / count), the rows added in ascending point order in float64 (ids: the
+// points sorted by cluster, ascending inside a cluster; one thread per (cluster, column)); an empty cluster keeps its row.
+__global__ void __launch_bounds__(256) k_kmeans_update(const float* __restrict__ X, int32_t d, const int32_t* __restrict__ ids,
+                                                       const uint32_t* __restrict__ start, int32_t K, float* __restrict__ C) {
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= (int64_t)K * d) return;
+    const int32_t j = (int32_t)(x / d), col = (int32_t)(x % d);
+    const uint32_t r0 = start[j], r1 = start[j + 1];
+    if (r1 == r0) return;
+    double sum = 0.0;
+    for (uint32_t r = r0; r < r1; ++r) sum = __dadd_rn(sum, (double)X[(int64_t)ids[r] * d + col]);
+    C[x] = (float)(sum / (double)(r1 - r0));
+}
+
+// sum over the points of the exact distance to their centroid (added in no particular order)
+__global__ void __launch_bounds__(256) k_kmeans_inertia(const float* __restrict__ X, const float* __restrict__ C, int32_t d,
+                                                        const int32_t* __restrict__ labels, int64_t n, double* __restrict__ out) {
+    __shared__ double part[256];
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    part[threadIdx.x] = i < n ? exact_distance(X + i * d, C + (int64_t)labels[i] * d, d) : 0.0;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) atomicAdd(out, part[0]);
 }
 
 }  // namespace nomad_knn

@@ -1,0 +1,69 @@
+"""nomad_kmeans_lloyd against the oracle: labels bit for bit, centroids bit for bit (the M step adds in the oracle's
+order), iteration by iteration from the same centroids and as a whole run."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kmeans_oracle as km
+from paper_2505_15511_amd import NomadError, kmeans_lloyd, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def note(msg):
+    print(msg, flush=True)
+
+
+def _data(n, d, comps, seed):
+    X, _ = workloads.gmm_points(n, d, comps, 16.0, seed, mix="dirichlet", interleave=True)
+    return X.numpy()
+
+
+@pytest.mark.parametrize("n,d,K", [(5000, 16, 7), (8000, 64, 40), (3000, 130, 300), (2000, 5, 1), (4000, 768, 12)])
+def test_one_iteration_matches_the_oracle_exactly(n, d, K):
+    note(f"kmeans one step n={n} d={d} K={K}")
+    X = _data(n, d, max(2, K // 3), 200 + d)
+    rng = np.random.default_rng(K)
+    C0 = X[rng.choice(n, K, replace=False)].copy()
+    lab_ref, dist_ref = km.assign(X, C0)
+    C_ref = km.update(X, lab_ref, C0)
+    C, lab, it, inertia = kmeans_lloyd(X, C0, 1)
+    assert it == 1 and np.array_equal(lab.astype(np.int64), lab_ref)
+    assert np.array_equal(C, C_ref)
+    assert abs(inertia - dist_ref.sum()) < 1e-9 * dist_ref.sum()
+
+
+def test_full_run_matches_the_oracle_and_converges():
+    n, d, K = 6000, 24, 12
+    X = _data(n, d, 12, 300)
+    C0 = X[np.random.default_rng(1).choice(n, K, replace=False)].copy()
+    C_ref, lab_ref, it_ref, inertia_ref = km.lloyd(X, C0, 100)
+    C, lab, it, inertia = kmeans_lloyd(torch.from_numpy(X).cuda(), torch.from_numpy(C0).cuda(), 100)
+    note(f"  converged after {it} E steps (oracle {it_ref}), inertia {inertia:.6e}")
+    assert it == it_ref and it < 100
+    assert np.array_equal(lab.cpu().numpy().astype(np.int64), lab_ref) and np.array_equal(C.cpu().numpy(), C_ref)
+    assert abs(inertia - inertia_ref) < 1e-9 * inertia_ref
+    # stopping early gives the oracle's intermediate state
+    C3_ref, lab3_ref, it3, _ = km.lloyd(X, C0, 3)
+    C3, lab3, it3g, _ = kmeans_lloyd(X, C0, 3)
+    assert it3 == it3g == 3 and np.array_equal(lab3.astype(np.int64), lab3_ref) and np.array_equal(C3, C3_ref)
+
+
+def test_duplicate_centroids_empty_clusters_and_ties():
+    rng = np.random.default_rng(7)
+    X = rng.integers(0, 4, size=(1500, 3)).astype(np.float32)            # grid points: exact ties in bulk
+    C0 = np.array([[0, 0, 0], [3, 3, 3], [0, 0, 0], [1.5, 1.5, 1.5], [50, 50, 50]], dtype=np.float32)   # a duplicate, a far one
+    C_ref, lab_ref, it_ref, _ = km.lloyd(X, C0, 20)
+    C, lab, it, _ = kmeans_lloyd(X, C0, 20)
+    assert it == it_ref and np.array_equal(lab.astype(np.int64), lab_ref) and np.array_equal(C, C_ref)
+    assert not (lab == 4).any() and np.array_equal(C[4], C0[4])           # the far centroid stays empty and where it was
+    C1, lab1, _, _ = kmeans_lloyd(X, C0, 1)
+    assert not (lab1 == 2).any() and np.array_equal(C1[2], C0[2])         # in the first E step the duplicate loses every tie
+
+
+def test_bad_arguments_are_codes():
+    X = np.zeros((10, 4), np.float32)
+    with pytest.raises(NomadError):
+        kmeans_lloyd(X, np.zeros((11, 4), np.float32), 5)        # more centroids than points
+    with pytest.raises(NomadError):
+        kmeans_lloyd(X, np.zeros((2, 4), np.float32), 0)
