@@ -121,6 +121,28 @@ def knn_index_run(args, torch, workloads):
                      "achieved": flops / dt / 1e12, "peak": 157.3, "unit": "TFLOP/s", "frac": flops / dt / 1e12 / 157.3, "traffic": None}}))
 
 
+def kmeans_index_run(args, torch, workloads):
+    """nomad_kmeans_lloyd: --steps Lloyd iterations on a Gaussian mixture from centroids picked among the points."""
+    from paper_2505_15511_amd import kmeans_lloyd
+    n, d, K = args.index_n, args.index_d, args.index_clusters
+    X, _ = workloads.gmm_points(n, d, K, 16.0, 4242, mix="equal", interleave=True)
+    X = X.cuda()
+    C0 = X[torch.randperm(n, generator=torch.Generator().manual_seed(1))[:K].cuda()].clone()
+    kmeans_lloyd(X, C0, 1)                           # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    C, labels, iters, inertia = kmeans_lloyd(X, C0, args.steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    flops = 2.0 * d * n * K * iters
+    print(json.dumps({
+        "metric": "K-Means Lloyd iterations, point-centroid pairs/sec at 1 GPU", "value": n * K * iters / dt, "unit": "pairs/s", "n_gpus": 1,
+        "steps": iters, "warmup": 1, "ms_per_step": 1e3 * dt / iters, "higher_is_better": True, "dtype": "f32 filter, f64 decision",
+        "data": "synthetic", "config": {"workload": f"Gaussian mixture n={n}, d={d}, K={K}"}, "inertia": inertia,
+        "roofline": {"bound": "mfma", "kernel": "knn_filter (whole iteration timed: E step, sort, M step)",
+                     "achieved": flops / dt / 1e12, "peak": 157.3, "unit": "TFLOP/s", "frac": flops / dt / 1e12 / 157.3, "traffic": None}}))
+
+
 def hip_graph_run(args, torch, Nomad, w, mode, warmup, steps):
     """The timed epochs recorded once into a HIP graph (nomad_epoch only enqueues kernels on the caller's stream) and
     replayed: one graph launch for 2 x steps kernels."""
@@ -182,7 +204,7 @@ def main():
     ap.add_argument("--mean-gradient", action="store_true",
                     help="let the gradient flow through the cell means (opt-in; grouped configurations); the benchmark "
                          "holds them constant within an epoch")
-    ap.add_argument("--index", choices=["knn"], default=None,
+    ap.add_argument("--index", choices=["knn", "kmeans"], default=None,
                     help="knn: time nomad_knn_in_clusters (the upstream index of Section 3.2) on a Gaussian mixture of "
                          "--index-n points in --index-d dimensions and --index-clusters clusters instead of the epoch path")
     ap.add_argument("--index-n", type=int, default=1_000_000)
@@ -210,6 +232,8 @@ def main():
         return
     if args.index == "knn":
         return knn_index_run(args, torch, workloads)
+    if args.index == "kmeans":
+        return kmeans_index_run(args, torch, workloads)
     t0 = time.time()
     w = workloads.make_config(args.config, scale=args.scale, device=dev if args.config >= 3 else "cpu",
                               n_groups=args.groups, paper_graph=args.graph == "paper")

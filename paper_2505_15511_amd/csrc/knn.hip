@@ -79,7 +79,12 @@ int nearest_in_groups(hipStream_t st, const KnnSets& P, const KnnBlock* blocks, 
     KTRY(hipMemsetAsync(cand, 0xFF, sizeof(int32_t) * (size_t)P.n_q * list_len, st));   // every slot "no candidate" until the filter fills it
     KTRY(hipMemsetAsync(n_flagged, 0, sizeof(uint32_t), st));
     KTRY(launch_filter(st, n_blocks, P, blocks, list_len, cand, tau));
-    hipLaunchKernelGGL(k_knn_refine, dim3(blocks_of(P.n_q, 4)), dim3(256), 0, st, P, cand, tau, k, list_len, out, flagged, n_flagged);
+    if (list_len <= 16)
+        hipLaunchKernelGGL(k_knn_refine<16>, dim3(blocks_of(P.n_q, 16)), dim3(256), 0, st, P, cand, tau, k, list_len, out, flagged, n_flagged);
+    else if (list_len <= 32)
+        hipLaunchKernelGGL(k_knn_refine<32>, dim3(blocks_of(P.n_q, 8)), dim3(256), 0, st, P, cand, tau, k, list_len, out, flagged, n_flagged);
+    else
+        hipLaunchKernelGGL(k_knn_refine<64>, dim3(blocks_of(P.n_q, 4)), dim3(256), 0, st, P, cand, tau, k, list_len, out, flagged, n_flagged);
     uint32_t hflag = 0;
     KTRY(hipMemcpyAsync(&hflag, n_flagged, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     KTRY(hipStreamSynchronize(st));
@@ -142,7 +147,7 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     KTRY(hipMemsetAsync(cursor, 0, sizeof(uint32_t) * (size_t)R, st));
     KTRY(hipMemsetAsync(max_norm, 0, sizeof(uint32_t) * (size_t)R, st));
     KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
-    hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, 256)), dim3(256), 0, st, dC, n, R, counts, bad);
+    hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, kCountSpan)), dim3(256), 0, st, dC, n, R, counts, bad);
     std::vector<uint32_t> hcounts(R), hstart((size_t)R + 1, 0);
     int hbad = 0;
     KTRY(hipMemcpyAsync(hcounts.data(), counts, sizeof(uint32_t) * (size_t)R, hipMemcpyDeviceToHost, st));
@@ -280,7 +285,7 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
         // M step
         KTRY(hipMemsetAsync(counts, 0, sizeof(uint32_t) * (size_t)K, st));
         KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
-        hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, 256)), dim3(256), 0, st, (const int32_t*)dLab, n, K, counts, bad);
+        hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, kCountSpan)), dim3(256), 0, st, (const int32_t*)dLab, n, K, counts, bad);
         KTRY(hipMemcpyAsync(hcounts.data(), counts, sizeof(uint32_t) * (size_t)K, hipMemcpyDeviceToHost, st));
         KTRY(hipStreamSynchronize(st));
         for (int32_t j = 0; j < K; ++j) hstart[j + 1] = hstart[j] + hcounts[j];

@@ -81,26 +81,56 @@ __global__ void __launch_bounds__(256) k_knn_norms(const float* __restrict__ X, 
                                                    const float* __restrict__ centre, float* __restrict__ norm,
                                                    uint32_t* __restrict__ max_norm_bits) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const float* x = X + i * d;
-    const int32_t g = cluster_of ? cluster_of[i] : 0;
-    const float* c = centre + (int64_t)g * d;
+    const bool valid = i < n;
+    int32_t g = 0;
     float s = 0.f;
-    for (int t = 0; t < d; ++t) {
-        const float v = x[t] - c[t];
-        s = fmaf(v, v, s);
+    if (valid) {
+        const float* x = X + i * d;
+        g = cluster_of ? cluster_of[i] : 0;
+        const float* c = centre + (int64_t)g * d;
+        for (int t = 0; t < d; ++t) {
+            const float v = x[t] - c[t];
+            s = fmaf(v, v, s);
+        }
+        if (norm) norm[i] = s;
     }
-    if (norm) norm[i] = s;
-    atomicMax(&max_norm_bits[g], __float_as_uint(s));   // non-negative floats order like their bit patterns
+    // non-negative floats order like their bit patterns; one atomic per wavefront where it lies inside one group
+    const unsigned long long live = __ballot(valid);
+    if (!live) return;
+    const int first = __ffsll((long long)live) - 1;
+    const int32_t g0 = __shfl(g, first, 64);
+    uint32_t bits = valid ? __float_as_uint(s) : 0u;
+    if (__all(!valid || g == g0)) {
+        for (int w = 32; w > 0; w >>= 1) bits = max(bits, (uint32_t)__shfl_xor((int)bits, w, 64));
+        if ((int)(threadIdx.x & 63) == first) atomicMax(&max_norm_bits[g0], bits);
+    } else if (valid) {
+        atomicMax(&max_norm_bits[g], bits);
+    }
 }
 
+// cluster sizes; a block counts kCountSpan labels in LDS first where the clusters are few enough to fit there
+constexpr int kCountSpan = 16384;
+constexpr int kCountLds = 4096;
 __global__ void __launch_bounds__(256) k_knn_count(const int32_t* __restrict__ cluster_of, int64_t n, int32_t R, uint32_t* __restrict__ counts,
                                                    int* __restrict__ bad) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int32_t r = cluster_of[i];
-    if (r < 0 || r >= R) { *bad = 1; return; }
-    atomicAdd(&counts[r], 1u);
+    __shared__ uint32_t h[kCountLds];
+    const bool local = R <= kCountLds;
+    if (local) {
+        for (int r = threadIdx.x; r < R; r += 256) h[r] = 0u;
+        __syncthreads();
+    }
+    const int64_t i0 = (int64_t)blockIdx.x * kCountSpan, i1 = min(n, i0 + kCountSpan);
+    for (int64_t i = i0 + threadIdx.x; i < i1; i += 256) {
+        const int32_t r = cluster_of[i];
+        if (r < 0 || r >= R) { *bad = 1; continue; }
+        if (local) atomicAdd(&h[r], 1u);
+        else atomicAdd(&counts[r], 1u);
+    }
+    if (local) {
+        __syncthreads();
+        for (int r = threadIdx.x; r < R; r += 256)
+            if (h[r]) atomicAdd(&counts[r], h[r]);
+    }
 }
 
 // members grouped by cluster (any order inside a cluster: ties are broken by the point index, not by position)
@@ -367,6 +397,22 @@ __device__ __forceinline__ double exact_distance(const float* __restrict__ x, co
     double acc = 0.0;
     int t = 0;
     if ((d & 3) == 0) {   // rows are 16-byte aligned: four values per load, still added one by one in order
+        for (; t + 16 <= d; t += 16) {   // eight loads in flight before the first dependent addition
+            float4 a[4], b[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { a[u] = *(const float4*)(x + t + 4 * u); b[u] = *(const float4*)(y + t + 4 * u); }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                double diff = (double)a[u].x - (double)b[u].x;
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                diff = (double)a[u].y - (double)b[u].y;
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                diff = (double)a[u].z - (double)b[u].z;
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                diff = (double)a[u].w - (double)b[u].w;
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+            }
+        }
         for (; t < d; t += 4) {
             const float4 a = *(const float4*)(x + t), b = *(const float4*)(y + t);
             double diff = (double)a.x - (double)b.x;
@@ -388,27 +434,30 @@ __device__ __forceinline__ double exact_distance(const float* __restrict__ x, co
 }
 
 // ---------------------------------------------------------------- stage 2: exact distances of the candidates
-// One wavefront per query, one lane per candidate.  rank = number of candidates that come before in (distance, point).
+// One lane per candidate.  rank = number of candidates that come before in (distance, point).
 // The answer is certified when the k-th exact key, D_k - |q|^2, lies below tau by more than eps: every point the
 // filter left out has float32 key >= tau, hence exact key >= tau - eps.  With x' = fl(x - centre) the rows the filter
 // saw and M = max |x'|^2 over the cluster, eps = (4 (d + 4) + 8) 2^-24 M bounds the rounding of the float32 norm,
 // dot product and their combination (4 (d + 4) u M) plus what centring in float32 moves a distance by (8 u M).
+// G lanes per query (16, 32 or 64, at least the list length): short lists share a wavefront between several queries.
+template <int G>
 __global__ void __launch_bounds__(256) k_knn_refine(const KnnSets P, const int32_t* __restrict__ cand, const float* __restrict__ tau,
                                                     int32_t k, int32_t list_len, int32_t* __restrict__ out,
                                                     int32_t* __restrict__ flagged, uint32_t* __restrict__ n_flagged) {
-    const int64_t p = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // position in the grouped query order
-    const int lane = threadIdx.x & 63;
+    const int64_t p = (int64_t)blockIdx.x * (256 / G) + (threadIdx.x / G);   // position in the grouped query order
+    const int lane = threadIdx.x % G;
     const int32_t d = P.d;
     if (p >= P.n_q) return;
-    const int32_t q = knn_row(P.qmembers, (uint32_t)p);
+    int32_t q = knn_row(P.qmembers, (uint32_t)p);
+    if (G == 64) q = __builtin_amdgcn_readfirstlane(q);   // the same for the whole wavefront
     const float* xq = P.XQ + (int64_t)q * d;
     int32_t c = lane < list_len ? cand[p * list_len + lane] : -1;
     if (c >= P.n_c) c = -1;   // never an address outside the candidate rows, whatever the list holds
     const double D = c >= 0 ? exact_distance(xq, P.XC + (int64_t)c * d, d) : __builtin_inf();
     int rank = 0, cnt = 0;
     for (int o = 0; o < list_len; ++o) {
-        const double Do = __shfl(D, o, 64);
-        const int32_t co = __shfl(c, o, 64);
+        const double Do = __shfl(D, o, G);
+        const int32_t co = __shfl(c, o, G);
         if (co >= 0) {
             ++cnt;
             if (Do < D || (Do == D && co < c)) ++rank;
@@ -504,7 +553,18 @@ __global__ void __launch_bounds__(256) k_kmeans_update(const float* __restrict__
     const uint32_t r0 = start[j], r1 = start[j + 1];
     if (r1 == r0) return;
     double sum = 0.0;
-    for (uint32_t r = r0; r < r1; ++r) sum = __dadd_rn(sum, (double)X[(int64_t)ids[r] * d + col]);
+    uint32_t r = r0;
+    for (; r + 16 <= r1; r += 16) {                     // sixteen rows in flight; the additions keep their order
+        int32_t id[16];
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) id[u] = ids[r + u];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = X[(int64_t)id[u] * d + col];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sum = __dadd_rn(sum, (double)v[u]);
+    }
+    for (; r < r1; ++r) sum = __dadd_rn(sum, (double)X[(int64_t)ids[r] * d + col]);
     C[x] = (float)(sum / (double)(r1 - r0));
 }
 
