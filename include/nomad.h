@@ -260,6 +260,43 @@ int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const int32_t* c
 int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t K, float* centroids, int32_t max_iters, int32_t* labels,
                        int32_t* iters_out, double* inertia_out, int mem, int32_t device, void* stream);
 
+/*
+ * Neighbourhood preservation at k (Section 4: the average overlap between the k-neighbourhoods of a point in the
+ * data space and in the projection).
+ *
+ *   X          [n*d] fp32 row-major: the data;  Y [n*d_low] fp32 row-major: the projection; n >= 2
+ *   k          1..NOMAD_KNN_MAX_K; d, d_low <= NOMAD_KNN_MAX_DIM
+ *   queries    NULL (every point; then n_queries is 0 or n), or [n_queries] int32 point indices: the points whose
+ *              neighbourhoods are compared (a sample at large n; repeats count as often as they are listed)
+ *   hits_out   host int64: common members of the two neighbourhoods, summed over the queries; the measure is
+ *              hits / (k * queries)
+ *
+ * A neighbourhood is the k nearest other points among all n under the float64 distance of nomad_knn_in_clusters,
+ * ties to the lower index, exactly (same filter, refinement and fallback).  Cost: queries * n distance
+ * evaluations per space.  X, Y and queries live in `mem`; same conventions and errors as nomad_knn_in_clusters
+ * (a query outside 0..n-1: NOMAD_E_INVALID_ARG).
+ */
+int nomad_neighbourhood_preservation(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low, int32_t k,
+                                     const int32_t* queries, int64_t n_queries, int64_t* hits_out, int mem, int32_t device,
+                                     void* stream);
+
+/*
+ * Random triplet accuracy (Section 4: the probability that a random triplet of points has the same ordering of its
+ * pairwise distances in the data space and in the projection).
+ *
+ *   X, Y       as above; n >= 3; any d, d_low >= 1
+ *   n_triplets triplets drawn, 0 .. 2^40
+ *   agree_out  host int64: triplets that agree; the measure is agree / n_triplets
+ *
+ * Triplet t = anchor i and two other points j, k, all distinct and uniform: with (o0, o1, o2, .) =
+ * Philox4x32-10(counter = (lo32 t, hi32 t, 0x54524950, 0), key = (lo32 seed, hi32 seed)), i = floor(o0 n / 2^32),
+ * j = floor(o1 (n-1) / 2^32) moved up by one if >= i, k = floor(o2 (n-2) / 2^32) moved up by one if >= min(i,j) and by
+ * one more if >= max(i,j).  It agrees when [D_X(i,j) < D_X(i,k)] == [D_Y(i,j) < D_Y(i,k)], D the float64 distance of
+ * nomad_knn_in_clusters: the count is exact and reproducible.  Same conventions and errors.
+ */
+int nomad_random_triplet_accuracy(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low, int64_t n_triplets,
+                                  uint64_t seed, int64_t* agree_out, int mem, int32_t device, void* stream);
+
 /* Text of the last error of this context ("" if none).  Valid until the next call on it. */
 const char* nomad_last_error(const nomad_ctx* ctx);
 

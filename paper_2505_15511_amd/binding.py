@@ -24,7 +24,8 @@ ERRORS = {-1: "NOMAD_E_INVALID_ARG", -2: "NOMAD_E_BAD_GRAPH", -3: "NOMAD_E_ORDER
 EXPORTS = ["nomad_create", "nomad_destroy", "nomad_set_graph", "nomad_set_embedding", "nomad_epoch", "nomad_loss",
            "nomad_get_embedding", "nomad_get_gradient", "nomad_get_negatives", "nomad_get_means",
            "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error",
-           "nomad_copy_probe", "nomad_knn_in_clusters", "nomad_kmeans_lloyd"]
+           "nomad_copy_probe", "nomad_knn_in_clusters", "nomad_kmeans_lloyd", "nomad_neighbourhood_preservation",
+           "nomad_random_triplet_accuracy"]
 
 
 class NomadConfig(C.Structure):
@@ -76,6 +77,8 @@ def load_library():
     lib.nomad_copy_probe.argtypes = [vp, vp, C.c_uint64, vp]
     lib.nomad_knn_in_clusters.argtypes = [vp, i64, i32, vp, i32, i32, vp, C.c_int, i32, vp, vp]
     lib.nomad_kmeans_lloyd.argtypes = [vp, i64, i32, i32, vp, i32, vp, C.POINTER(i32), C.POINTER(C.c_double), C.c_int, i32, vp]
+    lib.nomad_neighbourhood_preservation.argtypes = [vp, i64, i32, vp, i32, i32, vp, i64, C.POINTER(i64), C.c_int, i32, vp]
+    lib.nomad_random_triplet_accuracy.argtypes = [vp, i64, i32, vp, i32, i64, C.c_uint64, C.POINTER(i64), C.c_int, i32, vp]
     lib.nomad_last_error.argtypes = [vp]
     lib.nomad_last_error.restype = C.c_char_p
     _lib = lib
@@ -173,6 +176,49 @@ def kmeans_lloyd(X, centroids, max_iters, device=0, stream=None):
     if rc:
         raise NomadError(rc, "nomad_kmeans_lloyd")
     return keep_c, labels, int(iters.value), float(inertia.value)
+
+
+def _two_spaces(X, Y, stream, device):
+    n, d, d_low = int(X.shape[0]), int(X.shape[1]), int(Y.shape[1])
+    if int(Y.shape[0]) != n:
+        raise ValueError("X and Y must have one row per point each")
+    px, m0, keep_x = _marshal(X, np.float32, n * d)
+    py, m1, keep_y = _marshal(Y, np.float32, n * d_low)
+    if m0 != m1:
+        raise ValueError("X and Y must live in the same memory space")
+    if m0 == NOMAD_DEVICE and stream is None:
+        import torch
+        stream = torch.cuda.current_stream(device).cuda_stream
+    return n, d, d_low, px, py, m0, C.c_void_p(int(stream) if stream else None), (keep_x, keep_y)
+
+
+def neighbourhood_preservation(X, Y, k, queries=None, device=0, stream=None):
+    """nomad_neighbourhood_preservation: (hits, hits / (k * queries)) for the data X [n, d] and the projection Y [n, d_low],
+    both torch tensors on the device or both host arrays; queries: None (all points) or int32 point indices in the
+    same memory space."""
+    lib = load_library()
+    n, d, d_low, px, py, mem, st, keep = _two_spaces(X, Y, stream, device)
+    pq, mq, keep_q = _marshal(queries, np.int32)
+    m = n if queries is None else int(keep_q.numel() if _is_torch(keep_q) else keep_q.size)
+    if queries is not None and mq != mem:
+        raise ValueError("queries must live where X and Y live")
+    hits = C.c_int64(0)
+    rc = lib.nomad_neighbourhood_preservation(px, n, d, py, d_low, int(k), pq, 0 if queries is None else m, C.byref(hits), mem,
+                                              int(device), st)
+    if rc:
+        raise NomadError(rc, "nomad_neighbourhood_preservation")
+    return int(hits.value), hits.value / (int(k) * m)
+
+
+def random_triplet_accuracy(X, Y, n_triplets, seed, device=0, stream=None):
+    """nomad_random_triplet_accuracy: (agreeing triplets, agreeing fraction)."""
+    lib = load_library()
+    n, d, d_low, px, py, mem, st, keep = _two_spaces(X, Y, stream, device)
+    agree = C.c_int64(0)
+    rc = lib.nomad_random_triplet_accuracy(px, n, d, py, d_low, int(n_triplets), int(seed), C.byref(agree), mem, int(device), st)
+    if rc:
+        raise NomadError(rc, "nomad_random_triplet_accuracy")
+    return int(agree.value), (agree.value / int(n_triplets) if n_triplets else float("nan"))
 
 
 class Nomad:

@@ -1,4 +1,5 @@
-// libnomad: the in-cluster exact nearest-neighbour index behind the C ABI of include/nomad.h (host side).
+// libnomad: the upstream index (K-Means, in-cluster exact nearest neighbours) and the quality measures behind the C ABI of
+// include/nomad.h (host side).
 #include <hip/hip_runtime.h>
 #include <hipcub/hipcub.hpp>
 
@@ -7,9 +8,11 @@
 #include <vector>
 
 #include "knn_kernels.h"
+#include "metrics_kernels.h"
 #include "nomad.h"
 
 using namespace nomad_knn;
+using namespace nomad_metrics;
 
 namespace {
 
@@ -306,6 +309,148 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
     KTRY(hipStreamSynchronize(st));
     if (iters_out) *iters_out = it;
     if (inertia_out) *inertia_out = hinertia;
+    return NOMAD_OK;
+}
+namespace {
+
+// Exact k nearest other points, among all n rows of A, of the rows listed in dQ (m of them; nullptr: every row).
+// out [m * k] on the device.
+int neighbours_of_queries(hipStream_t st, Buffers& buf, const float* A, int64_t n, int32_t d, const int32_t* dQ, int64_t m, int32_t k,
+                          int32_t* out) {
+    const int32_t list_len = k + kPad;
+    uint32_t *qstart = nullptr, *cstart = nullptr, *max_norm = nullptr, *n_flagged = nullptr;
+    int32_t *cand = nullptr, *flagged = nullptr, *self = nullptr;
+    float *cnorm = nullptr, *tau = nullptr, *centre = nullptr, *AQ = nullptr;
+    int* bad = nullptr;
+    KnnBlock *blocks = nullptr, *slabs = nullptr;
+    KTRY(buf.alloc(&qstart, 2)); KTRY(buf.alloc(&cstart, 2)); KTRY(buf.alloc(&max_norm, 1)); KTRY(buf.alloc(&n_flagged, 1));
+    KTRY(buf.alloc(&bad, 1));
+    KTRY(buf.alloc(&cand, (size_t)m * list_len)); KTRY(buf.alloc(&flagged, (size_t)m)); KTRY(buf.alloc(&tau, (size_t)m));
+    KTRY(buf.alloc(&cnorm, (size_t)n)); KTRY(buf.alloc(&centre, (size_t)d)); KTRY(buf.alloc(&AQ, (size_t)m * d));
+    const uint32_t hq[2] = {0u, (uint32_t)m}, hc[2] = {0u, (uint32_t)n};
+    KTRY(hipMemcpyAsync(qstart, hq, sizeof(hq), hipMemcpyHostToDevice, st));
+    KTRY(hipMemcpyAsync(cstart, hc, sizeof(hc), hipMemcpyHostToDevice, st));
+    const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(width_class(d)));
+    std::vector<KnnBlock> hblocks, hslabs;
+    for (int64_t q0 = 0; q0 < m; q0 += block_queries) hblocks.push_back(KnnBlock{0, (int32_t)q0});
+    for (int64_t q0 = 0; q0 < n; q0 += kCentroidRows) hslabs.push_back(KnnBlock{0, (int32_t)q0});
+    KTRY(buf.alloc(&blocks, hblocks.size()));
+    KTRY(buf.alloc(&slabs, hslabs.size()));
+    KTRY(hipMemcpyAsync(blocks, hblocks.data(), sizeof(KnnBlock) * hblocks.size(), hipMemcpyHostToDevice, st));
+    KTRY(hipMemcpyAsync(slabs, hslabs.data(), sizeof(KnnBlock) * hslabs.size(), hipMemcpyHostToDevice, st));
+    KTRY(hipMemsetAsync(centre, 0, sizeof(float) * (size_t)d, st));
+    KTRY(hipMemsetAsync(max_norm, 0, sizeof(uint32_t), st));
+    KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
+    // every row centred on the mean of A; the queries are rows of A, so the largest norm covers them
+    hipLaunchKernelGGL(k_knn_centroid_sums, dim3((uint32_t)hslabs.size()), dim3(256), 0, st, A, d, (const int32_t*)nullptr, cstart, slabs, centre);
+    hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of(d, 256)), dim3(256), 0, st, centre, cstart, 1, d);
+    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, A, n, d, (const int32_t*)nullptr, centre, cnorm, max_norm);
+    hipLaunchKernelGGL(k_gather_rows, dim3(blocks_of(m * d, 256)), dim3(256), 0, st, A, n, d, dQ, m, AQ, bad);
+    if (!dQ) {   // every row is a query: row p is its own candidate p
+        KTRY(buf.alloc(&self, (size_t)m));
+        hipLaunchKernelGGL(k_iota, dim3(blocks_of(m, 256)), dim3(256), 0, st, self, m);
+    }
+    int hbad = 0;
+    KTRY(hipMemcpyAsync(&hbad, bad, sizeof(int), hipMemcpyDeviceToHost, st));
+    KTRY(hipStreamSynchronize(st));
+    if (hbad) return NOMAD_E_INVALID_ARG;   // a query outside 0..n-1
+    KnnSets P{};
+    P.XQ = AQ; P.XC = A; P.qmembers = nullptr; P.cmembers = nullptr; P.qstart = qstart; P.cstart = cstart;
+    P.cnorm = cnorm; P.centre = centre; P.group_of_q = nullptr; P.max_norm_bits = max_norm; P.n_q = m; P.n_c = n; P.d = d; P.same_set = 0;
+    P.self_row = dQ ? dQ : self;
+    uint32_t hflag = 0;
+    return nearest_in_groups(st, P, blocks, (uint32_t)hblocks.size(), k, cand, tau, flagged, n_flagged, out, &hflag);
+}
+
+}  // namespace
+
+extern "C" int nomad_neighbourhood_preservation(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low, int32_t k,
+                                                const int32_t* queries, int64_t n_queries, int64_t* hits_out, int mem, int32_t device,
+                                                void* stream) {
+    if (!X || !Y || !hits_out || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return NOMAD_E_INVALID_ARG;
+    if (n < 2 || d < 1 || d > NOMAD_KNN_MAX_DIM || d_low < 1 || d_low > NOMAD_KNN_MAX_DIM || k < 1 || k > NOMAD_KNN_MAX_K || device < 0)
+        return NOMAD_E_INVALID_ARG;
+    if (queries ? n_queries < 1 : (n_queries != 0 && n_queries != n)) return NOMAD_E_INVALID_ARG;
+    if (n >= ((int64_t)1 << 31) - 256 || n_queries >= ((int64_t)1 << 31) - 256) return NOMAD_E_TOO_LARGE;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) return NOMAD_E_HIP;
+    KTRY(hipSetDevice(device));
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t m = queries ? n_queries : n;
+    const float *dX = X, *dY = Y;
+    const int32_t* dQ = queries;
+    Buffers io;
+    if (mem == NOMAD_HOST) {
+        float *x = nullptr, *y = nullptr;
+        KTRY(io.alloc(&x, (size_t)n * d));
+        KTRY(io.alloc(&y, (size_t)n * d_low));
+        KTRY(hipMemcpyAsync(x, X, sizeof(float) * (size_t)n * d, hipMemcpyHostToDevice, st));
+        KTRY(hipMemcpyAsync(y, Y, sizeof(float) * (size_t)n * d_low, hipMemcpyHostToDevice, st));
+        dX = x; dY = y;
+        if (queries) {
+            int32_t* q = nullptr;
+            KTRY(io.alloc(&q, (size_t)m));
+            KTRY(hipMemcpyAsync(q, queries, sizeof(int32_t) * (size_t)m, hipMemcpyHostToDevice, st));
+            dQ = q;
+        }
+    }
+    int32_t *high = nullptr, *low = nullptr;
+    unsigned long long* hits = nullptr;
+    KTRY(io.alloc(&high, (size_t)m * k));
+    KTRY(io.alloc(&low, (size_t)m * k));
+    KTRY(io.alloc(&hits, 1));
+    {
+        Buffers work;   // released before the second space takes its own
+        int rc = neighbours_of_queries(st, work, dX, n, d, dQ, m, k, high);
+        if (rc) return rc;
+        KTRY(hipStreamSynchronize(st));
+    }
+    {
+        Buffers work;
+        int rc = neighbours_of_queries(st, work, dY, n, d_low, dQ, m, k, low);
+        if (rc) return rc;
+        KTRY(hipStreamSynchronize(st));
+    }
+    unsigned long long hhits = 0;
+    KTRY(hipMemsetAsync(hits, 0, sizeof(unsigned long long), st));
+    hipLaunchKernelGGL(k_overlap, dim3(blocks_of(m, 256)), dim3(256), 0, st, (const int32_t*)high, (const int32_t*)low, k, m, hits);
+    KTRY(hipMemcpyAsync(&hhits, hits, sizeof(hhits), hipMemcpyDeviceToHost, st));
+    KTRY(hipGetLastError());
+    KTRY(hipStreamSynchronize(st));
+    *hits_out = (int64_t)hhits;
+    return NOMAD_OK;
+}
+
+extern "C" int nomad_random_triplet_accuracy(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low, int64_t n_triplets,
+                                             uint64_t seed, int64_t* agree_out, int mem, int32_t device, void* stream) {
+    if (!X || !Y || !agree_out || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return NOMAD_E_INVALID_ARG;
+    if (n < 3 || d < 1 || d_low < 1 || n_triplets < 0 || device < 0) return NOMAD_E_INVALID_ARG;
+    if (n >= ((int64_t)1 << 31) - 256 || n_triplets > ((int64_t)1 << 40)) return NOMAD_E_TOO_LARGE;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) return NOMAD_E_HIP;
+    KTRY(hipSetDevice(device));
+    hipStream_t st = (hipStream_t)stream;
+    const float *dX = X, *dY = Y;
+    Buffers buf;
+    if (mem == NOMAD_HOST) {
+        float *x = nullptr, *y = nullptr;
+        KTRY(buf.alloc(&x, (size_t)n * d));
+        KTRY(buf.alloc(&y, (size_t)n * d_low));
+        KTRY(hipMemcpyAsync(x, X, sizeof(float) * (size_t)n * d, hipMemcpyHostToDevice, st));
+        KTRY(hipMemcpyAsync(y, Y, sizeof(float) * (size_t)n * d_low, hipMemcpyHostToDevice, st));
+        dX = x; dY = y;
+    }
+    unsigned long long* agree = nullptr;
+    unsigned long long hagree = 0;
+    KTRY(buf.alloc(&agree, 1));
+    KTRY(hipMemsetAsync(agree, 0, sizeof(unsigned long long), st));
+    if (n_triplets > 0)
+        hipLaunchKernelGGL(k_triplets, dim3(blocks_of(n_triplets, 256)), dim3(256), 0, st, dX, d, dY, d_low, (uint32_t)n, n_triplets,
+                           (uint32_t)seed, (uint32_t)(seed >> 32), agree);
+    KTRY(hipMemcpyAsync(&hagree, agree, sizeof(hagree), hipMemcpyDeviceToHost, st));
+    KTRY(hipGetLastError());
+    KTRY(hipStreamSynchronize(st));
+    *agree_out = (int64_t)hagree;
     return NOMAD_OK;
 }
 #pragma GCC visibility pop

@@ -34,7 +34,8 @@ struct KnnBlock { int32_t cluster; int32_t q0; };   // queries q0 .. of group `c
 
 // Queries and candidates, both cut into the same groups (group g: queries qmembers[qstart[g] .. qstart[g+1]), candidates
 // cmembers[cstart[g] .. cstart[g+1])).  Nearest neighbours inside clusters: both are the data set grouped by cluster.
-// K-Means assignment: one group, the queries are the points, the candidates the centroids.
+// K-Means assignment: one group, the queries are the points, the candidates the centroids.  Neighbourhoods of a sample
+// of query points among all points: one group, the queries a gathered copy of the sampled rows.
 struct KnnSets {
     const float* XQ;             // query rows
     const float* XC;             // candidate rows
@@ -49,6 +50,7 @@ struct KnnSets {
     int64_t n_q, n_c;            // rows of XQ, XC
     int32_t d;
     int32_t same_set;            // 1: queries and candidates are the same rows: a row is not its own neighbour
+    const int32_t* self_row;     // or, per query row, the candidate row that is the query itself (nullptr: see same_set)
 };
 __device__ __forceinline__ int32_t knn_row(const int32_t* members, uint32_t pos) { return members ? members[pos] : (int32_t)pos; }
 
@@ -192,7 +194,8 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
     // this lane's query and its slice of the row
     const int32_t qpos = blk.q0 + wave * kWaveQueries + (lane & 15);
     const int32_t qpt = qpos < n_qg ? knn_row(P.qmembers, q0g + qpos) : -1;
-    const int32_t self = P.same_set ? qpt : -1;               // the candidate that is the query itself, if any
+    // the candidate that is the query itself, if any
+    const int32_t self = qpt < 0 ? -1 : P.self_row ? P.self_row[qpt] : P.same_set ? qpt : -1;
     const float* ctr = P.centre + (int64_t)blk.cluster * d;    // the group's centre: every row enters as x - centre
     float breg[D4];
 #pragma unroll
@@ -491,7 +494,7 @@ __global__ void __launch_bounds__(256) k_knn_exact(const KnnSets P, const int32_
     const int32_t r = P.group_of_q ? P.group_of_q[q] : 0;
     const uint32_t c0 = P.cstart[r], c1 = P.cstart[r + 1];
     const float* xq = P.XQ + (int64_t)q * d;
-    const int32_t self = P.same_set ? q : -1;
+    const int32_t self = P.self_row ? P.self_row[q] : P.same_set ? q : -1;
     double lastD = -1.0;
     int32_t lastP = -1;
     for (int m = 0; m < k; ++m) {
