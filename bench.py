@@ -143,6 +143,41 @@ def kmeans_index_run(args, torch, workloads):
                      "achieved": flops / dt / 1e12, "peak": 157.3, "unit": "TFLOP/s", "frac": flops / dt / 1e12 / 157.3, "traffic": None}}))
 
 
+def metrics_run(args, torch, workloads):
+    """The quality measures: random triplet accuracy over 10 triplets per point, neighbourhood preservation@15 on a
+    seeded sample of 10,000 queries; the projection is a noisy linear one (the timing does not depend on it)."""
+    from paper_2505_15511_amd import neighbourhood_preservation, random_triplet_accuracy
+    n, d = args.index_n, args.index_d
+    X, _ = workloads.gmm_points(n, d, args.index_clusters, 16.0, 4242, mix="equal", interleave=True)
+    X = X.cuda()
+    Y = (X[:, :2] + 0.5 * torch.randn(n, 2, generator=torch.Generator().manual_seed(2)).cuda()).contiguous()
+    q = torch.randperm(n, generator=torch.Generator().manual_seed(3))[:10000].to(torch.int32).cuda()
+    T = 10 * n
+    random_triplet_accuracy(X, Y, 1000, 1)
+    neighbourhood_preservation(X, Y, args.index_k, q[:256])
+    torch.cuda.synchronize()
+    times = {}
+    for name, fn in (("triplets", lambda: random_triplet_accuracy(X, Y, T, 1)),
+                     ("preservation", lambda: neighbourhood_preservation(X, Y, args.index_k, q))):
+        best = None
+        for _ in range(max(1, args.steps)):
+            t0 = time.perf_counter()
+            out = fn()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        times[name] = (best, out)
+    tb = 3.0 * (d + 2) * 4 * T                                    # three rows of each space per triplet
+    print(json.dumps({
+        "metric": "random triplets/sec at 1 GPU", "value": T / times["triplets"][0], "unit": "triplets/s", "n_gpus": 1,
+        "steps": max(1, args.steps), "warmup": 1, "ms_per_step": 1e3 * times["triplets"][0], "higher_is_better": True, "dtype": "f64",
+        "data": "synthetic", "config": {"workload": f"Gaussian mixture n={n}, d={d}; {T} triplets; preservation@{args.index_k} on 10000 queries"},
+        "triplet_accuracy": times["triplets"][1][1], "preservation": times["preservation"][1][1],
+        "preservation_ms": 1e3 * times["preservation"][0],
+        "roofline": {"bound": "hbm", "kernel": "k_triplets (whole call timed)", "achieved": tb / times["triplets"][0] / 1e9, "peak": 8000.0,
+                     "unit": "GB/s", "frac": tb / times["triplets"][0] / 8e12, "traffic": None}}))
+
+
 def hip_graph_run(args, torch, Nomad, w, mode, warmup, steps):
     """The timed epochs recorded once into a HIP graph (nomad_epoch only enqueues kernels on the caller's stream) and
     replayed: one graph launch for 2 x steps kernels."""
@@ -204,7 +239,7 @@ def main():
     ap.add_argument("--mean-gradient", action="store_true",
                     help="let the gradient flow through the cell means (opt-in; grouped configurations); the benchmark "
                          "holds them constant within an epoch")
-    ap.add_argument("--index", choices=["knn", "kmeans"], default=None,
+    ap.add_argument("--index", choices=["knn", "kmeans", "metrics"], default=None,
                     help="knn: time nomad_knn_in_clusters (the upstream index of Section 3.2) on a Gaussian mixture of "
                          "--index-n points in --index-d dimensions and --index-clusters clusters instead of the epoch path")
     ap.add_argument("--index-n", type=int, default=1_000_000)
@@ -234,6 +269,8 @@ def main():
         return knn_index_run(args, torch, workloads)
     if args.index == "kmeans":
         return kmeans_index_run(args, torch, workloads)
+    if args.index == "metrics":
+        return metrics_run(args, torch, workloads)
     t0 = time.time()
     w = workloads.make_config(args.config, scale=args.scale, device=dev if args.config >= 3 else "cpu",
                               n_groups=args.groups, paper_graph=args.graph == "paper")
