@@ -297,6 +297,27 @@ int nomad_neighbourhood_preservation(const float* X, int64_t n, int32_t d, const
 int nomad_random_triplet_accuracy(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low, int64_t n_triplets,
                                   uint64_t seed, int64_t* agree_out, int mem, int32_t device, void* stream);
 
+/*
+ * PCA initialisation of the projection (Section 3.5: the optimisation starts from a PCA of the data).
+ *
+ *   X          [n*d] fp32 row-major, n >= 2, 2 <= d <= NOMAD_KNN_MAX_DIM
+ *   std0       > 0: both coordinates are multiplied by std0 / sqrt(lambda_1), so the first has standard deviation std0;
+ *              <= 0: the scores as they are
+ *   theta_out  [n*2] fp32 out (in `mem`): theta_i = ((x_i - mean) . v_1, (x_i - mean) . v_2), v_1, v_2 the eigenvectors of
+ *              the covariance (1/n) sum (x_i - mean)(x_i - mean)^T with the largest eigenvalues lambda_1 >= lambda_2,
+ *              each oriented so that its entry of largest magnitude is positive; computed in float64, rounded once
+ *   stats      NULL, or [4] host double: lambda_1, lambda_2, the residual max_m |C v_m - lambda_m v_m| / lambda_1 reached,
+ *              iterations of the eigenvector solver
+ *
+ * Mean and covariance are exact sums in float64 (the covariance on the float64 matrix cores); the eigenvectors come
+ * from subspace iteration with Rayleigh-Ritz steps until the residual is below 1e-13 or 2,000 iterations have run
+ * (eigenvalues that nearly coincide with their successors converge slowly and leave the axes ill-defined anyway:
+ * stats[2] says what was reached).  Deterministic.  Same conventions and errors as nomad_knn_in_clusters;
+ * NOMAD_E_INVALID_ARG also when std0 > 0 and the data has no variance.
+ */
+int nomad_pca_init(const float* X, int64_t n, int32_t d, float std0, float* theta_out, double* stats, int mem, int32_t device,
+                   void* stream);
+
 /* Text of the last error of this context ("" if none).  Valid until the next call on it. */
 const char* nomad_last_error(const nomad_ctx* ctx);
 

@@ -25,7 +25,7 @@ EXPORTS = ["nomad_create", "nomad_destroy", "nomad_set_graph", "nomad_set_embedd
            "nomad_get_embedding", "nomad_get_gradient", "nomad_get_negatives", "nomad_get_means",
            "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error",
            "nomad_copy_probe", "nomad_knn_in_clusters", "nomad_kmeans_lloyd", "nomad_neighbourhood_preservation",
-           "nomad_random_triplet_accuracy"]
+           "nomad_random_triplet_accuracy", "nomad_pca_init"]
 
 
 class NomadConfig(C.Structure):
@@ -79,6 +79,7 @@ def load_library():
     lib.nomad_kmeans_lloyd.argtypes = [vp, i64, i32, i32, vp, i32, vp, C.POINTER(i32), C.POINTER(C.c_double), C.c_int, i32, vp]
     lib.nomad_neighbourhood_preservation.argtypes = [vp, i64, i32, vp, i32, i32, vp, i64, C.POINTER(i64), C.c_int, i32, vp]
     lib.nomad_random_triplet_accuracy.argtypes = [vp, i64, i32, vp, i32, i64, C.c_uint64, C.POINTER(i64), C.c_int, i32, vp]
+    lib.nomad_pca_init.argtypes = [vp, i64, i32, C.c_float, vp, C.POINTER(C.c_double), C.c_int, i32, vp]
     lib.nomad_last_error.argtypes = [vp]
     lib.nomad_last_error.restype = C.c_char_p
     _lib = lib
@@ -219,6 +220,29 @@ def random_triplet_accuracy(X, Y, n_triplets, seed, device=0, stream=None):
     if rc:
         raise NomadError(rc, "nomad_random_triplet_accuracy")
     return int(agree.value), (agree.value / int(n_triplets) if n_triplets else float("nan"))
+
+
+def pca_init(X, std0=0.0, device=0, stream=None, return_stats=False):
+    """nomad_pca_init: theta0 [n, 2] float32 where X lives (torch tensor on the device, or host array)."""
+    lib = load_library()
+    n, d = int(X.shape[0]), int(X.shape[1])
+    px, mem, keep = _marshal(X, np.float32, n * d)
+    if mem == NOMAD_DEVICE:
+        import torch
+        theta = torch.empty(n, 2, dtype=torch.float32, device=keep.device)
+        pt = C.c_void_p(theta.data_ptr())
+        if stream is None:
+            stream = torch.cuda.current_stream(device).cuda_stream
+    else:
+        theta = np.empty((n, 2), dtype=np.float32)
+        pt = theta.ctypes.data_as(C.c_void_p)
+    stats = (C.c_double * 4)()
+    rc = lib.nomad_pca_init(px, n, d, float(std0), pt, stats, mem, int(device), C.c_void_p(int(stream) if stream else None))
+    if rc:
+        raise NomadError(rc, "nomad_pca_init")
+    if return_stats:
+        return theta, dict(eigenvalues=(stats[0], stats[1]), residual=stats[2], iterations=int(stats[3]))
+    return theta
 
 
 class Nomad:

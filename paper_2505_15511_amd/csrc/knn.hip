@@ -7,6 +7,7 @@
 #include <cmath>
 #include <vector>
 
+#include "host_util.h"
 #include "knn_kernels.h"
 #include "metrics_kernels.h"
 #include "nomad.h"
@@ -16,25 +17,6 @@ using namespace nomad_metrics;
 
 namespace {
 
-struct Buffers {   // device allocations of one call, released on every path
-    std::vector<void*> ptrs;
-    ~Buffers() { for (void* p : ptrs) (void)hipFree(p); }
-    template <typename T>
-    hipError_t alloc(T** p, size_t count) {
-        *p = nullptr;
-        hipError_t e = hipMalloc((void**)p, std::max<size_t>(count, 1) * sizeof(T));
-        if (e == hipSuccess) ptrs.push_back(*p);
-        return e;
-    }
-};
-
-#define KTRY(call)                                                          \
-    do {                                                                    \
-        hipError_t e_ = (call);                                             \
-        if (e_ != hipSuccess) return e_ == hipErrorOutOfMemory ? NOMAD_E_OOM : NOMAD_E_HIP; \
-    } while (0)
-
-inline uint32_t blocks_of(int64_t items, int per) { return (uint32_t)((items + per - 1) / per); }
 
 template <int D4, int L>
 hipError_t launch_filter_dl(hipStream_t st, uint32_t n_blocks, const KnnSets& P, const KnnBlock* blocks, int32_t list_len, int32_t* cand,
