@@ -178,6 +178,30 @@ def metrics_run(args, torch, workloads):
                      "unit": "GB/s", "frac": tb / times["triplets"][0] / 8e12, "traffic": None}}))
 
 
+def pca_run(args, torch, workloads):
+    """nomad_pca_init on a Gaussian mixture; the contraction behind it is the covariance, n d^2 multiply-adds in float64."""
+    from paper_2505_15511_amd import pca_init
+    n, d = args.index_n, args.index_d
+    X, _ = workloads.gmm_points(n, d, args.index_clusters, 16.0, 4242, mix="equal", interleave=True)
+    X = X.cuda()
+    pca_init(X, 1e-2)
+    torch.cuda.synchronize()
+    best, st = None, None
+    for _ in range(max(1, args.steps)):
+        t0 = time.perf_counter()
+        _, st = pca_init(X, 1e-2, return_stats=True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    flops = 2.0 * n * d * d                                       # the full d x d covariance; the kernel computes one triangle of 64 x 64 tiles
+    print(json.dumps({
+        "metric": "PCA initialisation, points/sec at 1 GPU", "value": n / best, "unit": "points/s", "n_gpus": 1,
+        "steps": max(1, args.steps), "warmup": 1, "ms_per_step": 1e3 * best, "higher_is_better": True, "dtype": "f64",
+        "data": "synthetic", "config": {"workload": f"Gaussian mixture n={n}, d={d}"}, "solver": st,
+        "roofline": {"bound": "mfma", "kernel": "k_pca_cov (whole call timed)", "achieved": flops / best / 1e12, "peak": 78.6,
+                     "unit": "TFLOP/s", "frac": flops / best / 78.6e12, "traffic": None}}))
+
+
 def hip_graph_run(args, torch, Nomad, w, mode, warmup, steps):
     """The timed epochs recorded once into a HIP graph (nomad_epoch only enqueues kernels on the caller's stream) and
     replayed: one graph launch for 2 x steps kernels."""
@@ -239,7 +263,7 @@ def main():
     ap.add_argument("--mean-gradient", action="store_true",
                     help="let the gradient flow through the cell means (opt-in; grouped configurations); the benchmark "
                          "holds them constant within an epoch")
-    ap.add_argument("--index", choices=["knn", "kmeans", "metrics"], default=None,
+    ap.add_argument("--index", choices=["knn", "kmeans", "metrics", "pca"], default=None,
                     help="knn: time nomad_knn_in_clusters (the upstream index of Section 3.2) on a Gaussian mixture of "
                          "--index-n points in --index-d dimensions and --index-clusters clusters instead of the epoch path")
     ap.add_argument("--index-n", type=int, default=1_000_000)
@@ -271,6 +295,8 @@ def main():
         return kmeans_index_run(args, torch, workloads)
     if args.index == "metrics":
         return metrics_run(args, torch, workloads)
+    if args.index == "pca":
+        return pca_run(args, torch, workloads)
     t0 = time.time()
     w = workloads.make_config(args.config, scale=args.scale, device=dev if args.config >= 3 else "cpu",
                               n_groups=args.groups, paper_graph=args.graph == "paper")

@@ -310,7 +310,7 @@ int nomad_random_triplet_accuracy(const float* X, int64_t n, int32_t d, const fl
  *              iterations of the eigenvector solver
  *
  * Mean and covariance are exact sums in float64 (the covariance on the float64 matrix cores); the eigenvectors come
- * from subspace iteration with Rayleigh-Ritz steps until the residual is below 1e-13 or 2,000 iterations have run
+ * from subspace iteration with Rayleigh-Ritz steps until the residual is below 1e-12 or 2,000 steps have run
  * (eigenvalues that nearly coincide with their successors converge slowly and leave the axes ill-defined anyway:
  * stats[2] says what was reached).  Deterministic.  Same conventions and errors as nomad_knn_in_clusters;
  * NOMAD_E_INVALID_ARG also when std0 > 0 and the data has no variance.

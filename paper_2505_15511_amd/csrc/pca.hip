@@ -52,9 +52,11 @@ extern "C" int nomad_pca_init(const float* X, int64_t n, int32_t d, float std0, 
     hipLaunchKernelGGL(k_pca_cov_reduce, dim3(blocks_of((int64_t)n_pairs * kColBlock * kColBlock, 256)), dim3(256), 0, st,
                        (const double*)cov_partial, n_pairs, slabs, d, n, Cm);
     // leading eigenvectors: subspace iteration from a fixed pseudo-random block
-    double *Q = nullptr, *Z = nullptr, *lam = nullptr, *resid = nullptr, *factor = nullptr;
+    double *Q = nullptr, *Z = nullptr, *Z2 = nullptr, *Z3 = nullptr, *lam = nullptr, *resid = nullptr, *factor = nullptr;
     KTRY(buf.alloc(&Q, (size_t)d * kRitz));
     KTRY(buf.alloc(&Z, (size_t)d * kRitz));
+    KTRY(buf.alloc(&Z2, (size_t)d * kRitz));
+    KTRY(buf.alloc(&Z3, (size_t)d * kRitz));
     KTRY(buf.alloc(&lam, (size_t)kRitz));
     KTRY(buf.alloc(&resid, 1));
     KTRY(buf.alloc(&factor, 2));
@@ -63,14 +65,24 @@ extern "C" int nomad_pca_init(const float* X, int64_t n, int32_t d, float std0, 
     for (int32_t r = 0; r < d; ++r)
         for (int32_t m = 0; m < p; ++m) hQ[(size_t)r * kRitz + m] = (double)(gen() >> 11) * (2.0 / 9007199254740992.0) - 1.0;
     KTRY(hipMemcpyAsync(Q, hQ.data(), sizeof(double) * hQ.size(), hipMemcpyHostToDevice, st));
-    const double tol = 1e-13;
-    const int max_iters = 2000, check_every = 8;
+    // kPower applications of C per Rayleigh-Ritz step (that step is one workgroup, an application the whole chip).  Started
+    // from Ritz vectors, column m picks up the directions before it only at rounding level times (lambda_1 / lambda_m)^kPower,
+    // which Gram-Schmidt applied twice removes again.
+    constexpr int kPower = 4;
+    const double tol = 1e-12;
+    const int max_iters = 2000, check_every = 4;
     int iters = 0;
     double hresid = 1.0, hlam[kRitz] = {0};
     while (iters < max_iters) {
         for (int x = 0; x < check_every; ++x) {
             hipLaunchKernelGGL(k_pca_apply, dim3(blocks_of(d, 4)), dim3(256), 0, st, (const double*)Cm, (const double*)Q, d, Z);
-            hipLaunchKernelGGL(k_pca_ritz, dim3(1), dim3(256), 0, st, Q, (const double*)Z, d, p, lam, resid);
+            double *from = Z, *to = Z2;
+            for (int s = 1; s < kPower; ++s) {
+                hipLaunchKernelGGL(k_pca_apply, dim3(blocks_of(d, 4)), dim3(256), 0, st, (const double*)Cm, (const double*)from, d, to);
+                from = to;
+                to = to == Z2 ? Z3 : Z2;
+            }
+            hipLaunchKernelGGL(k_pca_ritz, dim3(1), dim3(256), 0, st, Q, (const double*)Z, (const double*)from, d, p, lam, resid);
         }
         iters += check_every;
         KTRY(hipMemcpyAsync(&hresid, resid, sizeof(double), hipMemcpyDeviceToHost, st));

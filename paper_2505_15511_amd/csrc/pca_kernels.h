@@ -157,20 +157,21 @@ __device__ __forceinline__ void block_sums(const double (&v)[COUNT], double (*sc
 }
 
 // Eigenpairs of the symmetric p x p matrix H (p <= kRitz) by cyclic Jacobi rotations, eigenvalues descending; one thread.
+// W is orthogonal whatever the number of sweeps; lam and W are the eigenpairs to the accuracy the sweeps reached.
 __device__ inline void jacobi_eigen(double (*H)[kRitz], int p, double (*W)[kRitz], double* lam) {
     for (int i = 0; i < kRitz; ++i)
         for (int j = 0; j < kRitz; ++j) W[i][j] = i == j ? 1.0 : 0.0;
-    for (int sweep = 0; sweep < 40; ++sweep) {
-        double off = 0.0, diag = 0.0;
-        for (int i = 0; i < p; ++i) {
-            diag += H[i][i] * H[i][i];
-            for (int j = i + 1; j < p; ++j) off += H[i][j] * H[i][j];
-        }
-        if (off <= 1e-32 * diag || off == 0.0) break;
+    // Two sweeps per call are enough: the caller iterates, and its basis is nearly the Ritz basis from the second
+    // call on (H nearly diagonal, where the rotations converge quadratically).  Rotations that would change nothing at
+    // float64 resolution are skipped.
+    for (int sweep = 0; sweep < 2; ++sweep) {
+        bool rotated = false;
         for (int i = 0; i < p; ++i)
             for (int j = i + 1; j < p; ++j) {
-                if (H[i][j] == 0.0) continue;
-                const double theta = (H[j][j] - H[i][i]) / (2.0 * H[i][j]);
+                const double hij = H[i][j];
+                if (hij * hij <= 1e-34 * fabs(H[i][i] * H[j][j]) || hij == 0.0) continue;
+                rotated = true;
+                const double theta = (H[j][j] - H[i][i]) / (2.0 * hij);
                 const double t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
                 const double c = 1.0 / sqrt(t * t + 1.0), s = t * c;
                 for (int k = 0; k < p; ++k) {   // H <- H J
@@ -189,6 +190,7 @@ __device__ inline void jacobi_eigen(double (*H)[kRitz], int p, double (*W)[kRitz
                     W[k][j] = s * wki + c * wkj;
                 }
             }
+        if (!rotated) break;
     }
     for (int i = 0; i < p; ++i) lam[i] = H[i][i];
     for (int i = 0; i < p; ++i) {   // selection sort, descending
@@ -207,8 +209,9 @@ __device__ inline void jacobi_eigen(double (*H)[kRitz], int p, double (*W)[kRitz
 // H = Q^T Z, H = W diag(lam) W^T; Ritz vectors Q W with images Z W; residual = max over the first two pairs of
 // |Z w - lam Q w| / lam_1; the next Q = the orthonormalised Z W (Gram-Schmidt, every column projected twice; a column
 // that vanishes -- C of lower rank than the block -- is replaced by a coordinate vector).
-__global__ void __launch_bounds__(256) k_pca_ritz(double* __restrict__ Q, const double* __restrict__ Z, int32_t d, int32_t p,
-                                                  double* __restrict__ lam_out, double* __restrict__ resid_out) {
+// Znext = C^s Q for some s >= 1 (Z itself when s = 1): the next basis is the orthonormalised Znext W, s power steps at once.
+__global__ void __launch_bounds__(256) k_pca_ritz(double* __restrict__ Q, const double* __restrict__ Z, const double* __restrict__ Znext,
+                                                  int32_t d, int32_t p, double* __restrict__ lam_out, double* __restrict__ resid_out) {
     __shared__ double scratch[4][64];
     __shared__ double sums[64];
     __shared__ double H[kRitz][kRitz], W[kRitz][kRitz], lam[kRitz];
@@ -273,6 +276,21 @@ __global__ void __launch_bounds__(256) k_pca_ritz(double* __restrict__ Q, const 
             for (int m = 0; m < kRitz; ++m) lam_out[m] = lam[m];
         }
     }
+    if (Znext != Z) {
+#pragma unroll
+        for (int x = 0; x < kRowsPerThread; ++x) {
+            const int row = tid + 256 * x;
+#pragma unroll
+            for (int m = 0; m < kRitz; ++m) z[x][m] = row < d ? Znext[row * kRitz + m] : 0.0;
+#pragma unroll
+            for (int m = 0; m < kRitz; ++m) {
+                double sz = 0.0;
+#pragma unroll
+                for (int a = 0; a < kRitz; ++a) sz = fma(z[x][a], W[a][m], sz);
+                rz[x][m] = sz;
+            }
+        }
+    }
     // the next basis: orthonormalise the images column by column (q is reused for the finished columns)
 #pragma unroll
     for (int m = 0; m < kRitz; ++m) {
@@ -283,7 +301,7 @@ __global__ void __launch_bounds__(256) k_pca_ritz(double* __restrict__ Q, const 
         }
         double v[kRowsPerThread];
 #pragma unroll
-        for (int x = 0; x < kRowsPerThread; ++x) v[x] = rz[x][m];
+        for (int x = 0; x < kRowsPerThread; ++x) v[x] = rz[x][m];   // by now: column m of Znext W
         for (int attempt = 0; attempt < 4; ++attempt) {
             double before[1] = {0.0};
 #pragma unroll

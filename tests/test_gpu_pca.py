@@ -34,7 +34,8 @@ def _check(X, std0=0.0, tol=1e-5):
 
 
 @pytest.mark.parametrize("n,d,scales", [(5000, 16, (9.0, 4.0)), (3000, 130, (6.0, 3.0, 2.0)), (20000, 64, (3.0, 2.5)), (2500, 768, (8.0, 5.0)),
-                                        (1000, 2, (3.0, 1.0)), (777, 5, (4.0, 2.0)), (40, 100, (9.0, 4.0))])
+                                        (1000, 2, (3.0, 1.0)), (777, 5, (4.0, 2.0)), (40, 100, (9.0, 4.0)),
+                                        (4000, 24, (3000.0, 40.0, 0.5)), (4000, 24, (5.0, 4.9, 4.8, 4.7, 4.6, 4.5, 4.4, 4.3, 4.2, 1.5))])
 def test_scores_match_the_oracle(n, d, scales):
     note(f"pca n={n} d={d}")
     _check(_anisotropic(n, d, 10 + d, scales))
