@@ -1,0 +1,56 @@
+"""The composed method (K-Means -> in-cluster kNN -> graph -> PCA start -> epochs -> quality measures) end to end on
+the GPU: the stages fit together, the embedding is better than its start and far better than chance."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_15511_amd import pipeline, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def note(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("graph", ["directed", "symmetric"])
+def test_project_and_evaluate(graph):
+    n, d, comps = 30000, 32, 12
+    X, _ = workloads.gmm_points(n, d, comps, 16.0, 21, mix="dirichlet", interleave=True)
+    X = X.cuda()
+    theta, info = pipeline.project(X, n_clusters=24, k=15, n_epochs=150, seed=3, graph=graph, return_info=True)
+    assert theta.shape == (n, 2) and torch.isfinite(theta).all()
+    nb = info["neighbours"]
+    lab = info["labels"].long()
+    ok = nb >= 0
+    assert (lab[nb.clamp(min=0).long()] == lab[:, None])[ok].all()               # every edge stays inside its cluster
+    assert info["edges"] >= int(ok.sum())
+    np_start, ta_start = pipeline.evaluate(X, info["theta0"], n_queries=3000, n_triplets=200000, seed=1)
+    np_end, ta_end = pipeline.evaluate(X, theta, n_queries=3000, n_triplets=200000, seed=1)
+    note(f"  {graph}: R={info['n_clusters']} kmeans {info['kmeans_iterations']} its, E={info['edges']}, "
+         f"NP@15 {np_start:.4f} -> {np_end:.4f}, triplets {ta_start:.4f} -> {ta_end:.4f}, seconds {info['seconds']}")
+    assert np_end > 10 * 15 / n and np_end > np_start                            # chance is k / n
+    assert ta_end > 0.6                                                          # global structure from the PCA start survives
+
+
+def test_random_start_and_sampler_options_pass_through():
+    X, _ = workloads.gmm_points(8000, 16, 6, 16.0, 22, mix="equal", interleave=True)
+    X = X.cuda()
+    theta = pipeline.project(X, n_clusters=8, n_epochs=40, init="random", seed=5, pool_size=256, pool_block=1024)
+    assert theta.shape == (8000, 2) and torch.isfinite(theta).all()
+    again = pipeline.project(X, n_clusters=8, n_epochs=40, init="random", seed=5, pool_size=256, pool_block=1024)
+    assert torch.equal(theta, again)                                             # deterministic end to end
+
+
+def test_small_clusters_leave_ragged_rows():
+    # 60 points in 20 clusters: most clusters have fewer than k + 1 members, rows are shorter than k
+    X, _ = workloads.gmm_points(60, 8, 3, 16.0, 23, mix="equal", interleave=True)
+    nbrs = torch.tensor([[1, 2, -1], [0, -1, -1], [-1, -1, -1], [0, 1, 2]], dtype=torch.int32).cuda()
+    row_ptr, col, w = pipeline.neighbour_lists_to_csr(nbrs, "directed")
+    assert row_ptr.tolist() == [0, 2, 3, 3, 6] and col.tolist() == [1, 2, 0, 0, 1, 2]
+    wk = workloads.inverse_rank_weights(3)
+    assert np.allclose(w.cpu().numpy(), [wk[0], wk[1], wk[0], wk[0], wk[1], wk[2]])
+    row_ptr, col, w = pipeline.neighbour_lists_to_csr(nbrs[:3], "symmetric")
+    assert w is None and row_ptr.tolist() == [0, 2, 3, 4] and col.tolist() == [1, 2, 0, 0]
+    theta = pipeline.project(X.cuda(), n_clusters=20, k=5, n_epochs=20, seed=1)
+    assert torch.isfinite(theta).all()
