@@ -202,6 +202,34 @@ def pca_run(args, torch, workloads):
                      "unit": "TFLOP/s", "frac": flops / best / 78.6e12, "traffic": None}}))
 
 
+def pipeline_run(args, torch, workloads):
+    """The composed method on --index-n points: partition, neighbours, graph, PCA start, --steps epochs, quality measures."""
+    from paper_2505_15511_amd import pipeline
+    n, d = args.index_n, args.index_d
+    X, _ = workloads.gmm_points(n, d, args.index_clusters, 16.0, 4242, mix="dirichlet", interleave=True)
+    X = X.cuda()
+    pipeline.project(X[:20000].contiguous(), 16, n_epochs=2)          # warm-up: library load, torch's sort and unique
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    theta, info = pipeline.project(X, args.index_clusters, k=args.index_k, n_epochs=args.steps, seed=1, return_info=True)
+    torch.cuda.synchronize()
+    total = time.perf_counter() - t0
+    t1 = time.perf_counter()
+    preservation, accuracy = pipeline.evaluate(X, theta, k=args.index_k, seed=1)
+    start_preservation, start_accuracy = pipeline.evaluate(X, info["theta0"], k=args.index_k, seed=1)
+    t_eval = (time.perf_counter() - t1) / 2
+    print(json.dumps({
+        "metric": "points projected/sec at 1 GPU, whole method", "value": n / total, "unit": "points/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": 0, "ms_per_step": 1e3 * info["seconds"]["epochs"] / max(1, args.steps), "higher_is_better": True, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"Gaussian mixture n={n}, d={d}, {info['n_clusters']} clusters, k={args.index_k}, {args.steps} epochs, "
+                               f"E={info['edges']} directed edges with inverse-rank weights"},
+        "seconds": {**{k: round(v, 4) for k, v in info["seconds"].items()}, "total": round(total, 4), "evaluate": round(t_eval, 4)},
+        "kmeans_iterations": info["kmeans_iterations"],
+        "preservation_at_k": {"pca_start": start_preservation, "final": preservation},
+        "triplet_accuracy": {"pca_start": start_accuracy, "final": accuracy}}))
+
+
 def hip_graph_run(args, torch, Nomad, w, mode, warmup, steps):
     """The timed epochs recorded once into a HIP graph (nomad_epoch only enqueues kernels on the caller's stream) and
     replayed: one graph launch for 2 x steps kernels."""
@@ -263,7 +291,7 @@ def main():
     ap.add_argument("--mean-gradient", action="store_true",
                     help="let the gradient flow through the cell means (opt-in; grouped configurations); the benchmark "
                          "holds them constant within an epoch")
-    ap.add_argument("--index", choices=["knn", "kmeans", "metrics", "pca"], default=None,
+    ap.add_argument("--index", choices=["knn", "kmeans", "metrics", "pca", "pipeline"], default=None,
                     help="knn: time nomad_knn_in_clusters (the upstream index of Section 3.2) on a Gaussian mixture of "
                          "--index-n points in --index-d dimensions and --index-clusters clusters instead of the epoch path")
     ap.add_argument("--index-n", type=int, default=1_000_000)
@@ -297,6 +325,8 @@ def main():
         return metrics_run(args, torch, workloads)
     if args.index == "pca":
         return pca_run(args, torch, workloads)
+    if args.index == "pipeline":
+        return pipeline_run(args, torch, workloads)
     t0 = time.time()
     w = workloads.make_config(args.config, scale=args.scale, device=dev if args.config >= 3 else "cpu",
                               n_groups=args.groups, paper_graph=args.graph == "paper")
