@@ -296,52 +296,78 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
 namespace {
 
 // Exact k nearest other points, among all n rows of A, of the rows listed in dQ (m of them; nullptr: every row).
-// out [m * k] on the device.
+// out [m * k] on the device.  A workgroup of the filter scans every candidate of its group, so few queries would leave
+// most of the chip idle: the candidates are then cut into slices, every slice is a group of its own with a copy of the
+// queries, and the per-slice answers are merged by exact distance.
 int neighbours_of_queries(hipStream_t st, Buffers& buf, const float* A, int64_t n, int32_t d, const int32_t* dQ, int64_t m, int32_t k,
                           int32_t* out) {
     const int32_t list_len = k + kPad;
+    const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(width_class(d)));
+    const int64_t base_blocks = (m + block_queries - 1) / block_queries;
+    int64_t G = std::max<int64_t>(1, 1024 / base_blocks);
+    G = std::min<int64_t>(G, 256 / k);                       // the merge ranks slices * k candidates in one workgroup
+    G = std::min<int64_t>(G, std::max<int64_t>(1, n / 4096));   // slices of at least 4,096 candidates
+    const int64_t slice = (n + G - 1) / G, mq = m * G;
+    if (mq >= ((int64_t)1 << 31) - 256) return NOMAD_E_TOO_LARGE;
     uint32_t *qstart = nullptr, *cstart = nullptr, *max_norm = nullptr, *n_flagged = nullptr;
-    int32_t *cand = nullptr, *flagged = nullptr, *self = nullptr;
+    int32_t *cand = nullptr, *flagged = nullptr, *self = nullptr, *group_of_q = nullptr, *slice_of = nullptr, *part = nullptr;
     float *cnorm = nullptr, *tau = nullptr, *centre = nullptr, *AQ = nullptr;
     int* bad = nullptr;
     KnnBlock *blocks = nullptr, *slabs = nullptr;
-    KTRY(buf.alloc(&qstart, 2)); KTRY(buf.alloc(&cstart, 2)); KTRY(buf.alloc(&max_norm, 1)); KTRY(buf.alloc(&n_flagged, 1));
-    KTRY(buf.alloc(&bad, 1));
-    KTRY(buf.alloc(&cand, (size_t)m * list_len)); KTRY(buf.alloc(&flagged, (size_t)m)); KTRY(buf.alloc(&tau, (size_t)m));
-    KTRY(buf.alloc(&cnorm, (size_t)n)); KTRY(buf.alloc(&centre, (size_t)d)); KTRY(buf.alloc(&AQ, (size_t)m * d));
-    const uint32_t hq[2] = {0u, (uint32_t)m}, hc[2] = {0u, (uint32_t)n};
-    KTRY(hipMemcpyAsync(qstart, hq, sizeof(hq), hipMemcpyHostToDevice, st));
-    KTRY(hipMemcpyAsync(cstart, hc, sizeof(hc), hipMemcpyHostToDevice, st));
-    const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(width_class(d)));
+    KTRY(buf.alloc(&qstart, (size_t)G + 1)); KTRY(buf.alloc(&cstart, (size_t)G + 1)); KTRY(buf.alloc(&max_norm, (size_t)G));
+    KTRY(buf.alloc(&n_flagged, 1)); KTRY(buf.alloc(&bad, 1));
+    KTRY(buf.alloc(&cand, (size_t)mq * list_len)); KTRY(buf.alloc(&flagged, (size_t)mq)); KTRY(buf.alloc(&tau, (size_t)mq));
+    KTRY(buf.alloc(&cnorm, (size_t)n)); KTRY(buf.alloc(&centre, (size_t)G * d)); KTRY(buf.alloc(&AQ, (size_t)mq * d));
+    KTRY(buf.alloc(&self, (size_t)mq));
+    std::vector<uint32_t> hq((size_t)G + 1), hc((size_t)G + 1);
     std::vector<KnnBlock> hblocks, hslabs;
-    for (int64_t q0 = 0; q0 < m; q0 += block_queries) hblocks.push_back(KnnBlock{0, (int32_t)q0});
-    for (int64_t q0 = 0; q0 < n; q0 += kCentroidRows) hslabs.push_back(KnnBlock{0, (int32_t)q0});
+    for (int64_t g = 0; g <= G; ++g) {
+        hq[g] = (uint32_t)(g * m);
+        hc[g] = (uint32_t)std::min<int64_t>(n, g * slice);
+    }
+    for (int64_t g = 0; g < G; ++g) {
+        for (int64_t q0 = 0; q0 < m; q0 += block_queries) hblocks.push_back(KnnBlock{(int32_t)g, (int32_t)q0});
+        for (int64_t q0 = 0; q0 < (int64_t)(hc[g + 1] - hc[g]); q0 += kCentroidRows) hslabs.push_back(KnnBlock{(int32_t)g, (int32_t)q0});
+    }
+    KTRY(hipMemcpyAsync(qstart, hq.data(), sizeof(uint32_t) * hq.size(), hipMemcpyHostToDevice, st));
+    KTRY(hipMemcpyAsync(cstart, hc.data(), sizeof(uint32_t) * hc.size(), hipMemcpyHostToDevice, st));
     KTRY(buf.alloc(&blocks, hblocks.size()));
     KTRY(buf.alloc(&slabs, hslabs.size()));
     KTRY(hipMemcpyAsync(blocks, hblocks.data(), sizeof(KnnBlock) * hblocks.size(), hipMemcpyHostToDevice, st));
     KTRY(hipMemcpyAsync(slabs, hslabs.data(), sizeof(KnnBlock) * hslabs.size(), hipMemcpyHostToDevice, st));
-    KTRY(hipMemsetAsync(centre, 0, sizeof(float) * (size_t)d, st));
-    KTRY(hipMemsetAsync(max_norm, 0, sizeof(uint32_t), st));
+    KTRY(hipMemsetAsync(centre, 0, sizeof(float) * (size_t)G * d, st));
+    KTRY(hipMemsetAsync(max_norm, 0, sizeof(uint32_t) * (size_t)G, st));
     KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
-    // every row centred on the mean of A; the queries are rows of A, so the largest norm covers them
-    hipLaunchKernelGGL(k_knn_centroid_sums, dim3((uint32_t)hslabs.size()), dim3(256), 0, st, A, d, (const int32_t*)nullptr, cstart, slabs, centre);
-    hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of(d, 256)), dim3(256), 0, st, centre, cstart, 1, d);
-    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, A, n, d, (const int32_t*)nullptr, centre, cnorm, max_norm);
-    hipLaunchKernelGGL(k_gather_rows, dim3(blocks_of(m * d, 256)), dim3(256), 0, st, A, n, d, dQ, m, AQ, bad);
-    if (!dQ) {   // every row is a query: row p is its own candidate p
-        KTRY(buf.alloc(&self, (size_t)m));
-        hipLaunchKernelGGL(k_iota, dim3(blocks_of(m, 256)), dim3(256), 0, st, self, m);
+    if (G > 1) {
+        KTRY(buf.alloc(&group_of_q, (size_t)mq));
+        KTRY(buf.alloc(&slice_of, (size_t)n));
+        KTRY(buf.alloc(&part, (size_t)mq * k));
+        hipLaunchKernelGGL(k_periodic_ids, dim3(blocks_of(n, 256)), dim3(256), 0, st, (const int32_t*)nullptr, slice, n, slice_of, (int32_t*)nullptr);
     }
+    // every slice centred on its own mean; the largest centred norm of a group covers its candidates and its queries
+    hipLaunchKernelGGL(k_periodic_ids, dim3(blocks_of(mq, 256)), dim3(256), 0, st, dQ, m, mq, group_of_q, self);
+    hipLaunchKernelGGL(k_gather_rows, dim3(blocks_of(mq * d, 256)), dim3(256), 0, st, A, n, d, dQ, m, mq, AQ, bad);
     int hbad = 0;
     KTRY(hipMemcpyAsync(&hbad, bad, sizeof(int), hipMemcpyDeviceToHost, st));
     KTRY(hipStreamSynchronize(st));
     if (hbad) return NOMAD_E_INVALID_ARG;   // a query outside 0..n-1
+    hipLaunchKernelGGL(k_knn_centroid_sums, dim3((uint32_t)hslabs.size()), dim3(256), 0, st, A, d, (const int32_t*)nullptr, cstart, slabs, centre);
+    hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of(G * d, 256)), dim3(256), 0, st, centre, cstart, (int32_t)G, d);
+    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, A, n, d, (const int32_t*)slice_of, centre, cnorm, max_norm);
+    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(mq, 256)), dim3(256), 0, st, (const float*)AQ, mq, d, (const int32_t*)group_of_q, centre,
+                       (float*)nullptr, max_norm);
     KnnSets P{};
     P.XQ = AQ; P.XC = A; P.qmembers = nullptr; P.cmembers = nullptr; P.qstart = qstart; P.cstart = cstart;
-    P.cnorm = cnorm; P.centre = centre; P.group_of_q = nullptr; P.max_norm_bits = max_norm; P.n_q = m; P.n_c = n; P.d = d; P.same_set = 0;
-    P.self_row = dQ ? dQ : self;
+    P.cnorm = cnorm; P.centre = centre; P.group_of_q = group_of_q; P.max_norm_bits = max_norm; P.n_q = mq; P.n_c = n; P.d = d; P.same_set = 0;
+    P.self_row = self;
     uint32_t hflag = 0;
-    return nearest_in_groups(st, P, blocks, (uint32_t)hblocks.size(), k, cand, tau, flagged, n_flagged, out, &hflag);
+    int rc = nearest_in_groups(st, P, blocks, (uint32_t)hblocks.size(), k, cand, tau, flagged, n_flagged, G > 1 ? part : out, &hflag);
+    if (rc) return rc;
+    if (G > 1) {
+        hipLaunchKernelGGL(k_merge_slices, dim3((uint32_t)m), dim3(256), 0, st, (const float*)AQ, A, d, (const int32_t*)part, (int32_t)G, m, k, out);
+        KTRY(hipGetLastError());
+    }
+    return NOMAD_OK;
 }
 
 }  // namespace

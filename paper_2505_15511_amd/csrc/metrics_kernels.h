@@ -7,22 +7,64 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "knn_kernels.h"
 #include "philox.h"
 
 namespace nomad_metrics {
 
 constexpr uint32_t kTripletStream = 0x54524950u;   // third counter word of the triplet generator
 
-// out[p] = X[rows[p]] (rows == nullptr: p itself); bad is set where a row lies outside [0, n)
+// out[p] = X[rows[p % period]] (rows == nullptr: row p % period) for p < m: the listed rows, repeated every `period`;
+// bad is set where a row lies outside [0, n)
 __global__ void __launch_bounds__(256) k_gather_rows(const float* __restrict__ X, int64_t n, int32_t d, const int32_t* __restrict__ rows,
-                                                     int64_t m, float* __restrict__ out, int* __restrict__ bad) {
+                                                     int64_t period, int64_t m, float* __restrict__ out, int* __restrict__ bad) {
     const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (x >= m * d) return;
     const int64_t p = x / d;
     const int32_t t = (int32_t)(x % d);
-    const int64_t r = rows ? rows[p] : p;
+    const int64_t r = rows ? rows[p % period] : p % period;
     if (r < 0 || r >= n) { *bad = 1; out[x] = 0.f; return; }
     out[x] = X[r * d + t];
+}
+
+// block[p] = p / period (may be nullptr); tiled[p] = rows[p % period] (rows == nullptr: p % period) (may be nullptr)
+__global__ void __launch_bounds__(256) k_periodic_ids(const int32_t* __restrict__ rows, int64_t period, int64_t m, int32_t* __restrict__ block,
+                                                      int32_t* __restrict__ tiled) {
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= m) return;
+    if (block) block[p] = (int32_t)(p / period);
+    if (tiled) tiled[p] = rows ? rows[p % period] : (int32_t)(p % period);
+}
+
+// The candidate set was cut into `slices` parts and query r has the k nearest of each part in
+// part_nbrs[(g * m + r) * k ..]: the k nearest overall are the k smallest (distance, index) among those slices * k <= 256
+// candidates.  One workgroup per query, one thread per candidate, rank by counting.
+__global__ void __launch_bounds__(256) k_merge_slices(const float* __restrict__ AQ, const float* __restrict__ A, int32_t d,
+                                                      const int32_t* __restrict__ part_nbrs, int32_t slices, int64_t m, int32_t k,
+                                                      int32_t* __restrict__ out) {
+    __shared__ double sD[256];
+    __shared__ int32_t sC[256];
+    const int64_t r = blockIdx.x;
+    const int t = threadIdx.x, total = slices * k;
+    int32_t c = -1;
+    double D = __builtin_inf();
+    if (t < total) {
+        c = part_nbrs[((int64_t)(t / k) * m + r) * k + t % k];
+        if (c >= 0) D = nomad_knn::exact_distance(AQ + r * d, A + (int64_t)c * d, d);
+    }
+    sD[t] = D;
+    sC[t] = c;
+    __syncthreads();
+    int rank = 0, found = 0;
+    for (int o = 0; o < total; ++o) {
+        const int32_t co = sC[o];
+        if (co < 0) continue;
+        ++found;
+        const double Do = sD[o];
+        if (Do < D || (Do == D && co < c)) ++rank;
+    }
+    if (c >= 0 && rank < k) out[r * k + rank] = c;
+    if (t >= found && t < k) out[r * k + t] = -1;   // fewer than k candidates in all
 }
 
 // common members of the two neighbour lists of every query (-1 = empty slot), summed
