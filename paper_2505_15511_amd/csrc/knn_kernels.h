@@ -30,6 +30,10 @@ __host__ __device__ constexpr int knn_filter_waves(int d4) { return d4 >= 128 ? 
 // LDS buffers for the staged candidate tile: two, or one at the widest rows (see the kernel)
 __host__ __device__ constexpr int knn_filter_buffers(int d4) { return d4 > 64 ? 1 : 2; }
 
+// wavefronts per SIMD the filter is compiled for: narrow rows and short lists fit two workgroups per compute unit (128
+// registers per lane), and the second workgroup is what hides the first one's tile barriers
+__host__ __device__ constexpr int knn_filter_waves_per_simd(int d4, int L) { return d4 <= 32 && L <= 12 ? 4 : d4 <= 64 ? 2 : 1; }
+
 struct KnnBlock { int32_t cluster; int32_t q0; };   // queries q0 .. of group `cluster`: one workgroup's share
 
 // Queries and candidates, both cut into the same groups (group g: queries qmembers[qstart[g] .. qstart[g+1]), candidates
@@ -166,7 +170,7 @@ __global__ void __launch_bounds__(256) k_knn_group(const int32_t* __restrict__ c
 // a query are merged: the K' smallest keys go on, tau = min(K'-th key of the union, the four lists' last keys):
 // every candidate that is not passed on has key >= tau.
 template <int D4, int L>
-__global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const KnnSets P, const KnnBlock* __restrict__ blocks, int32_t list_len,
+__global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_per_simd(D4, L)) k_knn_filter(const KnnSets P, const KnnBlock* __restrict__ blocks, int32_t list_len,
                                                                          int32_t* __restrict__ cand, float* __restrict__ tau_out) {
     const float* __restrict__ X = P.XC;        // candidate rows (the loop's stream)
     const float* __restrict__ norm = P.cnorm;
@@ -260,25 +264,41 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4)) k_knn_filter(const 
         const float* arow = tile + buf * kTileWords + (lane & 15) * kRow + (lane >> 4);
 #pragma unroll
         for (int t = 0; t < D4; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(arow[4 * t], breg[t], acc, 0, 0, 0);
+        float ck[4];      // this lane's four candidates of the tile
+        int32_t cp[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int i = 4 * (lane >> 4) + v;
-            const int32_t cpt = tile_pt[buf * kTile + i];
-            float key = tnorm[buf * kTile + i] - 2.f * acc[v];
-            if (cpt < 0 || cpt == self || qpt < 0) key = __builtin_inff();
-            if (__any(key < lk[L - 1])) {
-                float xk = key;       // an infinite key changes nothing below
-                int32_t xp = cpt;
+            cp[v] = tile_pt[buf * kTile + i];
+            ck[v] = tnorm[buf * kTile + i] - 2.f * acc[v];
+            if (cp[v] < 0 || cp[v] == self || qpt < 0) ck[v] = __builtin_inff();
+        }
+        // Insertion passes run for the whole wavefront, so they are spent on the lane's best remaining candidate: some lane
+        // has a hit in most tiles, a lane with two in one tile is rare, and the second pass is skipped when there is none.
 #pragma unroll
-                for (int x = 0; x < L; ++x) {
-                    const bool take = xk < lk[x];
-                    const float ok = lk[x];
-                    const int32_t op = lp[x];
-                    lk[x] = take ? xk : ok;
-                    lp[x] = take ? xp : op;
-                    xk = take ? ok : xk;
-                    xp = take ? op : xp;
-                }
+        for (int pass = 0; pass < 4; ++pass) {
+            float xk = ck[0];
+            int32_t xp = cp[0];
+            int sel = 0;
+#pragma unroll
+            for (int v = 1; v < 4; ++v) {
+                const bool less = ck[v] < xk;
+                xk = less ? ck[v] : xk;
+                xp = less ? cp[v] : xp;
+                sel = less ? v : sel;
+            }
+            if (!__any(xk < lk[L - 1])) break;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ck[v] = sel == v ? __builtin_inff() : ck[v];
+#pragma unroll
+            for (int x = 0; x < L; ++x) {   // an infinite key changes nothing
+                const bool take = xk < lk[x];
+                const float ok = lk[x];
+                const int32_t op = lp[x];
+                lk[x] = take ? xk : ok;
+                lp[x] = take ? xp : op;
+                xk = take ? ok : xk;
+                xp = take ? op : xp;
             }
         }
     };
