@@ -11,8 +11,16 @@ specified further).  One iteration, written out:
 
 Iterations stop when an E step changes no assignment (the centroids are then a fixed point) or after max_iters.
 
+The start from a locality-sensitive hash (one sentence in the paper, no detail) is read as random-hyperplane hashing:
+  * b hyperplanes, 2^b >= K; plane j has the normal h_j (float32, drawn by the caller) and passes through the data
+    point x_{a_j} (anchor indices drawn by the caller); bit j of a point is [ sum_t h_{j,t} (x_t - x_{a_j,t}) > 0 ], the
+    sum over t = 0..d-1 in order, difference, product and running sum each rounded once in float64;
+  * code = sum_j bit_j 2^j; bucket = floor(code K / 2^b); centroid j = the M step applied to bucket j;
+  * an empty bucket j takes the data point with index floor(j n / K) as its centroid.
+
 parity status: pinned in tests/test_oracle_kmeans.py (scipy's vq for the E step, closed forms, monotone inertia,
-the fixed-point property)."""
+the fixed-point property; for the hash start: numpy's matrix product for the bits, planes with sides known by
+construction, bucket means by a second route)."""
 from __future__ import annotations
 
 import numpy as np
@@ -65,3 +73,30 @@ def lloyd(X: np.ndarray, C0: np.ndarray, max_iters: int):
         labels = new_labels
         C = update(X, labels, C)
     return C, labels, it, inertia
+
+
+def lsh_buckets(X: np.ndarray, planes: np.ndarray, anchors: np.ndarray, K: int) -> np.ndarray:
+    """Bucket int64 [n] of every point under the random-hyperplane hash (planes float32 [b, d], anchors int [b])."""
+    X = np.asarray(X, dtype=np.float32)
+    planes = np.asarray(planes, dtype=np.float32)
+    b = len(planes)
+    if (1 << b) < K:
+        raise ValueError("2^planes must be at least K")
+    code = np.zeros(len(X), dtype=np.int64)
+    for j in range(b):
+        a = X[int(anchors[j])].astype(np.float64)
+        acc = np.zeros(len(X), dtype=np.float64)
+        for t in range(X.shape[1]):
+            diff = X[:, t].astype(np.float64) - a[t]
+            acc = acc + np.float64(planes[j, t]) * diff
+        code += (acc > 0).astype(np.int64) << j
+    return (code * K) >> b
+
+
+def lsh_init(X: np.ndarray, planes: np.ndarray, anchors: np.ndarray, K: int):
+    """(centroids float32 [K, d], buckets int64 [n])."""
+    X = np.asarray(X, dtype=np.float32)
+    n = len(X)
+    buckets = lsh_buckets(X, planes, anchors, K)
+    fallback = X[(np.arange(K, dtype=np.int64) * n) // K]
+    return update(X, buckets, fallback), buckets

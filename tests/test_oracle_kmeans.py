@@ -1,6 +1,7 @@
 """Pins for the K-Means oracle: scipy's vector quantiser for the E step, closed forms for the M step, the monotone
 inertia and the fixed point that Lloyd's iteration has."""
 import numpy as np
+import pytest
 from scipy.cluster.vq import vq
 
 from oracle import kmeans_oracle as km
@@ -59,3 +60,61 @@ def test_well_separated_blobs_are_recovered():
     X = (centres[truth] + rng.normal(size=(800, 2))).astype(np.float32)
     C, labels, ran, _ = km.lloyd(X, (centres + 3.0).astype(np.float32), 50)
     assert np.array_equal(labels, truth) and np.abs(C - centres).max() < 0.3 and ran <= 4
+
+
+# ---------------------------------------------------------------- the start from a locality-sensitive hash
+def _hash_inputs(n, d, b, seed):
+    rng = np.random.default_rng(seed)
+    X = rng.normal(size=(n, d)).astype(np.float32)
+    return X, rng.normal(size=(b, d)).astype(np.float32), rng.choice(n, b, replace=False)
+
+
+def test_hash_bits_against_a_matrix_product():
+    X, planes, anchors = _hash_inputs(4000, 24, 5, 1)
+    proj = (X.astype(np.float64)[:, None, :] - X.astype(np.float64)[anchors][None, :, :]) * planes.astype(np.float64)[None, :, :]
+    proj = proj.sum(axis=2)                                                  # another summation order: compare away from 0
+    code = ((proj > 0) * (1 << np.arange(5))).sum(axis=1)
+    clear = (np.abs(proj) > 1e-9).all(axis=1)
+    got = km.lsh_buckets(X, planes, anchors, 32)                             # K = 2^b: the bucket is the code
+    assert clear.mean() > 0.99 and np.array_equal(got[clear], code[clear])
+    for K in (7, 20, 31):
+        assert np.array_equal(km.lsh_buckets(X, planes, anchors, K)[clear], (code[clear] * K) // 32)
+    with pytest.raises(ValueError):
+        km.lsh_buckets(X, planes, anchors, 33)
+
+
+def test_hash_sides_known_by_construction():
+    # plane 0: normal e_0 through point 2 (x_0 = 1): bit 0 = [x_0 > 1]; plane 1: normal -e_1 through point 0 (x_1 = 0): bit 1 = [x_1 < 0]
+    X = np.array([[0, 0], [2, 0], [1, 5], [3, -1], [1, -2], [-4, -4]], dtype=np.float32)
+    planes = np.array([[1, 0], [0, -1]], dtype=np.float32)
+    buckets = km.lsh_buckets(X, planes, np.array([2, 0]), 4)
+    assert buckets.tolist() == [0, 1, 0, 3, 2, 2]        # a point on a plane (the anchors, and point 4 on plane 0) gets bit 0
+    C, _ = km.lsh_init(X, planes, np.array([2, 0]), 4)
+    assert np.array_equal(C, np.array([[0.5, 2.5], [2, 0], [-1.5, -3], [3, -1]], dtype=np.float32))
+    # three buckets from two planes: codes 0, 1 -> bucket 0, code 2 -> 1, code 3 -> 2
+    assert km.lsh_buckets(X, planes, np.array([2, 0]), 3).tolist() == [0, 0, 0, 2, 1, 1]
+
+
+def test_hash_start_means_and_empty_buckets():
+    X, planes, anchors = _hash_inputs(3000, 10, 4, 2)
+    C, buckets = km.lsh_init(X, planes, anchors, 16)
+    for j in range(16):
+        members = X[buckets == j].astype(np.float64)
+        if len(members):
+            assert np.allclose(C[j], members.mean(axis=0), rtol=0, atol=1e-6)
+        else:
+            assert np.array_equal(C[j], X[j * 3000 // 16])
+    assert len(np.unique(buckets)) >= 8
+    # every point on one side of the single plane used twice: buckets 1 and 2 of 4 are empty and take points n/4, n/2
+    Y = np.abs(X) + 1.0
+    Y[0] = 0.0
+    planes2 = np.ones((2, 10), dtype=np.float32)
+    C, buckets = km.lsh_init(Y, planes2, np.array([0, 0]), 4)
+    assert set(buckets.tolist()) == {0, 3} and np.count_nonzero(buckets == 0) == 1
+    assert np.array_equal(C[1], Y[750]) and np.array_equal(C[2], Y[1500]) and np.array_equal(C[0], Y[0])
+    # a start from the hash is a valid start: Lloyd's iterations lower the inertia from it
+    X3 = np.concatenate([X + 6.0, X - 6.0]).astype(np.float32)
+    C0, _ = km.lsh_init(X3, planes, anchors, 16)
+    _, d0 = km.assign(X3, C0)
+    _, _, _, inertia = km.lloyd(X3, C0, 10)
+    assert inertia < d0.sum()
