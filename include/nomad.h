@@ -261,6 +261,24 @@ int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t K, float* c
                        int32_t* iters_out, double* inertia_out, int mem, int32_t device, void* stream);
 
 /*
+ * Initial centroids for nomad_kmeans_lloyd from a locality-sensitive hash (Section 3.2 names such a start without
+ * detail; this is random-hyperplane hashing with the random draws made by the caller).
+ *
+ *   X            [n*d] fp32 row-major
+ *   planes       [n_planes*d] fp32: the normals h_j;  anchors [n_planes] int32: plane j passes through the data point
+ *                x_{anchors[j]};  1 <= n_planes <= 30 and 2^n_planes >= K
+ *   centroids_out [K*d] fp32 out;  buckets_out NULL or [n] int32 out: the bucket of every point
+ *
+ * bit j of a point = [ sum_t h_{j,t} (x_t - x_{anchors[j],t}) > 0 ], the sum over t = 0..d-1 in order with difference,
+ * product and running sum each rounded once in float64; code = sum_j bit_j 2^j; bucket = floor(code K / 2^n_planes);
+ * centroid j = float32 mean of bucket j (rows added in ascending point order in float64, as in the M step); an empty
+ * bucket takes the data point floor(j n / K).  Deterministic and exactly reproducible.  All arrays live in `mem`.
+ * Same conventions, limits and errors as nomad_knn_in_clusters (an anchor outside 0..n-1: NOMAD_E_INVALID_ARG).
+ */
+int nomad_kmeans_lsh_init(const float* X, int64_t n, int32_t d, int32_t K, const float* planes, const int32_t* anchors,
+                          int32_t n_planes, float* centroids_out, int32_t* buckets_out, int mem, int32_t device, void* stream);
+
+/*
  * Neighbourhood preservation at k (Section 4: the average overlap between the k-neighbourhoods of a point in the
  * data space and in the projection).
  *

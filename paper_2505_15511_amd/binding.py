@@ -25,7 +25,7 @@ EXPORTS = ["nomad_create", "nomad_destroy", "nomad_set_graph", "nomad_set_embedd
            "nomad_get_embedding", "nomad_get_gradient", "nomad_get_negatives", "nomad_get_means",
            "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error",
            "nomad_copy_probe", "nomad_knn_in_clusters", "nomad_kmeans_lloyd", "nomad_neighbourhood_preservation",
-           "nomad_random_triplet_accuracy", "nomad_pca_init"]
+           "nomad_random_triplet_accuracy", "nomad_pca_init", "nomad_kmeans_lsh_init"]
 
 
 class NomadConfig(C.Structure):
@@ -80,6 +80,7 @@ def load_library():
     lib.nomad_neighbourhood_preservation.argtypes = [vp, i64, i32, vp, i32, i32, vp, i64, C.POINTER(i64), C.c_int, i32, vp]
     lib.nomad_random_triplet_accuracy.argtypes = [vp, i64, i32, vp, i32, i64, C.c_uint64, C.POINTER(i64), C.c_int, i32, vp]
     lib.nomad_pca_init.argtypes = [vp, i64, i32, C.c_float, vp, C.POINTER(C.c_double), C.c_int, i32, vp]
+    lib.nomad_kmeans_lsh_init.argtypes = [vp, i64, i32, i32, vp, vp, i32, vp, vp, C.c_int, i32, vp]
     lib.nomad_last_error.argtypes = [vp]
     lib.nomad_last_error.restype = C.c_char_p
     _lib = lib
@@ -243,6 +244,34 @@ def pca_init(X, std0=0.0, device=0, stream=None, return_stats=False):
     if return_stats:
         return theta, dict(eigenvalues=(stats[0], stats[1]), residual=stats[2], iterations=int(stats[3]))
     return theta
+
+
+def kmeans_lsh_init(X, K, planes, anchors, device=0, stream=None, return_buckets=False):
+    """nomad_kmeans_lsh_init: initial centroids [K, d] from random-hyperplane hashing.  X, planes [b, d] and anchors [b]
+    (int32 point indices) all torch tensors on the device, or all host arrays."""
+    lib = load_library()
+    n, d = int(X.shape[0]), int(X.shape[1])
+    b = int(planes.shape[0])
+    px, m0, keep_x = _marshal(X, np.float32, n * d)
+    pp, m1, keep_p = _marshal(planes, np.float32, b * d)
+    pa, m2, keep_a = _marshal(anchors, np.int32, b)
+    if not (m0 == m1 == m2):
+        raise ValueError("X, planes and anchors must live in the same memory space")
+    if m0 == NOMAD_DEVICE:
+        import torch
+        cen = torch.empty(int(K), d, dtype=torch.float32, device=keep_x.device)
+        buckets = torch.empty(n, dtype=torch.int32, device=keep_x.device)
+        pc, pb = C.c_void_p(cen.data_ptr()), C.c_void_p(buckets.data_ptr())
+        if stream is None:
+            stream = torch.cuda.current_stream(device).cuda_stream
+    else:
+        cen = np.empty((int(K), d), dtype=np.float32)
+        buckets = np.empty(n, dtype=np.int32)
+        pc, pb = cen.ctypes.data_as(C.c_void_p), buckets.ctypes.data_as(C.c_void_p)
+    rc = lib.nomad_kmeans_lsh_init(px, n, d, int(K), pp, pa, b, pc, pb, m0, int(device), C.c_void_p(int(stream) if stream else None))
+    if rc:
+        raise NomadError(rc, "nomad_kmeans_lsh_init")
+    return (cen, buckets) if return_buckets else cen
 
 
 class Nomad:

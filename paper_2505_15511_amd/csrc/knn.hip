@@ -293,6 +293,79 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
     if (inertia_out) *inertia_out = hinertia;
     return NOMAD_OK;
 }
+extern "C" int nomad_kmeans_lsh_init(const float* X, int64_t n, int32_t d, int32_t K, const float* planes, const int32_t* anchors,
+                                     int32_t n_planes, float* centroids_out, int32_t* buckets_out, int mem, int32_t device, void* stream) {
+    if (!X || !planes || !anchors || !centroids_out || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return NOMAD_E_INVALID_ARG;
+    if (n < 1 || d < 1 || d > NOMAD_KNN_MAX_DIM || K < 1 || K > n || n_planes < 1 || n_planes > kMaxPlanes || device < 0) return NOMAD_E_INVALID_ARG;
+    if (((int64_t)1 << n_planes) < K) return NOMAD_E_INVALID_ARG;
+    if (n >= ((int64_t)1 << 31) - 256) return NOMAD_E_TOO_LARGE;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) return NOMAD_E_HIP;
+    KTRY(hipSetDevice(device));
+    hipStream_t st = (hipStream_t)stream;
+    Buffers buf;
+    const float *dX = X, *dP = planes;
+    const int32_t* dA = anchors;
+    float* dC = centroids_out;
+    int32_t* dB = buckets_out;
+    std::vector<int32_t> hanchors((size_t)n_planes);
+    if (mem == NOMAD_HOST) {
+        float *x = nullptr, *pl = nullptr, *c = nullptr;
+        int32_t* a = nullptr;
+        KTRY(buf.alloc(&x, (size_t)n * d));
+        KTRY(buf.alloc(&pl, (size_t)n_planes * d));
+        KTRY(buf.alloc(&a, (size_t)n_planes));
+        KTRY(buf.alloc(&c, (size_t)K * d));
+        KTRY(hipMemcpyAsync(x, X, sizeof(float) * (size_t)n * d, hipMemcpyHostToDevice, st));
+        KTRY(hipMemcpyAsync(pl, planes, sizeof(float) * (size_t)n_planes * d, hipMemcpyHostToDevice, st));
+        KTRY(hipMemcpyAsync(a, anchors, sizeof(int32_t) * (size_t)n_planes, hipMemcpyHostToDevice, st));
+        for (int32_t j = 0; j < n_planes; ++j) hanchors[j] = anchors[j];
+        dX = x; dP = pl; dA = a; dC = c;
+    } else {
+        KTRY(hipMemcpyAsync(hanchors.data(), anchors, sizeof(int32_t) * (size_t)n_planes, hipMemcpyDeviceToHost, st));
+        KTRY(hipStreamSynchronize(st));
+    }
+    for (int32_t j = 0; j < n_planes; ++j)
+        if (hanchors[j] < 0 || hanchors[j] >= n) return NOMAD_E_INVALID_ARG;   // an anchor that is no data point
+    if (!dB || mem == NOMAD_HOST) {
+        int32_t* bk = nullptr;
+        KTRY(buf.alloc(&bk, (size_t)n));
+        dB = bk;
+    }
+    uint32_t *counts = nullptr, *lstart = nullptr;
+    int32_t *ids_in = nullptr, *ids = nullptr, *keys = nullptr;
+    int* bad = nullptr;
+    KTRY(buf.alloc(&counts, (size_t)K)); KTRY(buf.alloc(&lstart, (size_t)K + 1)); KTRY(buf.alloc(&bad, 1));
+    KTRY(buf.alloc(&ids_in, (size_t)n)); KTRY(buf.alloc(&ids, (size_t)n)); KTRY(buf.alloc(&keys, (size_t)n));
+    hipLaunchKernelGGL(k_lsh_buckets, dim3(blocks_of(n, 256)), dim3(256), 0, st, dX, n, d, dP, dA, n_planes, K, dB);
+    hipLaunchKernelGGL(k_lsh_fallback, dim3(blocks_of((int64_t)K * d, 256)), dim3(256), 0, st, dX, n, d, K, dC);
+    // bucket means: the M step of Lloyd's iteration on the buckets
+    KTRY(hipMemsetAsync(counts, 0, sizeof(uint32_t) * (size_t)K, st));
+    KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
+    hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, kCountSpan)), dim3(256), 0, st, (const int32_t*)dB, n, K, counts, bad);
+    std::vector<uint32_t> hcounts(K), hstart((size_t)K + 1, 0);
+    KTRY(hipMemcpyAsync(hcounts.data(), counts, sizeof(uint32_t) * (size_t)K, hipMemcpyDeviceToHost, st));
+    KTRY(hipStreamSynchronize(st));
+    for (int32_t j = 0; j < K; ++j) hstart[j + 1] = hstart[j] + hcounts[j];
+    KTRY(hipMemcpyAsync(lstart, hstart.data(), sizeof(uint32_t) * ((size_t)K + 1), hipMemcpyHostToDevice, st));
+    hipLaunchKernelGGL(k_iota, dim3(blocks_of(n, 256)), dim3(256), 0, st, ids_in, n);
+    int end_bit = 1;
+    while (((int64_t)1 << end_bit) < K) ++end_bit;
+    size_t sort_bytes = 0;
+    KTRY(hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const int32_t*)dB, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
+    void* sort_tmp = nullptr;
+    KTRY(buf.alloc((char**)&sort_tmp, sort_bytes));
+    KTRY(hipcub::DeviceRadixSort::SortPairs(sort_tmp, sort_bytes, (const int32_t*)dB, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
+    hipLaunchKernelGGL(k_kmeans_update, dim3(blocks_of((int64_t)K * d, 256)), dim3(256), 0, st, dX, d, (const int32_t*)ids, (const uint32_t*)lstart, K, dC);
+    KTRY(hipGetLastError());
+    if (mem == NOMAD_HOST) {
+        KTRY(hipMemcpyAsync(centroids_out, dC, sizeof(float) * (size_t)K * d, hipMemcpyDeviceToHost, st));
+        if (buckets_out) KTRY(hipMemcpyAsync(buckets_out, dB, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost, st));
+    }
+    KTRY(hipStreamSynchronize(st));
+    return NOMAD_OK;
+}
+
 namespace {
 
 // Exact k nearest other points, among all n rows of A, of the rows listed in dQ (m of them; nullptr: every row).

@@ -591,6 +591,42 @@ __global__ void __launch_bounds__(256) k_kmeans_update(const float* __restrict__
     C[x] = (float)(sum / (double)(r1 - r0));
 }
 
+// The start from a locality-sensitive hash: bit j of a point = [ sum_t h_{j,t} (x_t - a_{j,t}) > 0 ], a_j the anchor row of
+// plane j, the sum over t = 0..d-1 in order with difference, product and running sum each rounded once in float64;
+// bucket = floor(code K / 2^b).  One thread per point, one accumulator per plane, the row read once.
+constexpr int kMaxPlanes = 30;
+__global__ void __launch_bounds__(256) k_lsh_buckets(const float* __restrict__ X, int64_t n, int32_t d, const float* __restrict__ planes,
+                                                     const int32_t* __restrict__ anchors, int32_t b, int32_t K, int32_t* __restrict__ bucket) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    double acc[kMaxPlanes];
+#pragma unroll
+    for (int j = 0; j < kMaxPlanes; ++j) acc[j] = 0.0;
+    const float* x = X + i * d;
+    for (int t = 0; t < d; ++t) {
+        const double xt = (double)x[t];
+#pragma unroll
+        for (int j = 0; j < kMaxPlanes; ++j)
+            if (j < b) {
+                const double diff = __dsub_rn(xt, (double)X[(int64_t)anchors[j] * d + t]);
+                acc[j] = __dadd_rn(acc[j], __dmul_rn((double)planes[(int64_t)j * d + t], diff));
+            }
+    }
+    uint64_t code = 0;
+#pragma unroll
+    for (int j = 0; j < kMaxPlanes; ++j)
+        if (j < b && acc[j] > 0.0) code |= (uint64_t)1 << j;
+    bucket[i] = (int32_t)((code * (uint64_t)K) >> b);
+}
+
+// centroid j starts as the data point floor(j n / K): what an empty bucket keeps
+__global__ void __launch_bounds__(256) k_lsh_fallback(const float* __restrict__ X, int64_t n, int32_t d, int32_t K, float* __restrict__ C) {
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= (int64_t)K * d) return;
+    const int64_t j = x / d;
+    C[x] = X[((j * n) / K) * d + x % d];
+}
+
 // sum over the points of the exact distance to their centroid (added in no particular order)
 __global__ void __launch_bounds__(256) k_kmeans_inertia(const float* __restrict__ X, const float* __restrict__ C, int32_t d,
                                                         const int32_t* __restrict__ labels, int64_t n, double* __restrict__ out) {

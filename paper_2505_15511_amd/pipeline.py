@@ -10,7 +10,7 @@ import numpy as np
 import torch
 
 from . import workloads
-from .binding import (SCATTER_DETERMINISTIC, Nomad, kmeans_lloyd, knn_in_clusters, neighbourhood_preservation, pca_init,
+from .binding import (SCATTER_DETERMINISTIC, Nomad, kmeans_lloyd, kmeans_lsh_init, knn_in_clusters, neighbourhood_preservation, pca_init,
                       random_triplet_accuracy)
 
 
@@ -43,12 +43,13 @@ def neighbour_lists_to_csr(nbrs: torch.Tensor, graph: str = "directed"):
 
 def project(X: torch.Tensor, n_clusters: int, k: int = 15, n_epochs: int = 200, n_neg: int = 5, noise_count: float = 0.0,
             lr0: float = 1.0, seed: int = 0, kmeans_iters: int = 25, init: str = "pca", std0: float = 0.01,
-            graph: str = "directed", device: int = 0, return_info: bool = False, **nomad_options):
+            graph: str = "directed", kmeans_start: str = "lsh", device: int = 0, return_info: bool = False, **nomad_options):
     """Project the rows of X (float32 tensor on the GPU) to the plane.  Returns theta [n, 2] on the device, and with
     return_info a dict of the intermediate results and the seconds each stage took.
 
-    The initial centroids are n_clusters of the points drawn with the seed (the paper's locality-sensitive-hash start
-    is not specified); clusters that end up empty are dropped.  Remaining keyword arguments go to Nomad (pool_size,
+    kmeans_start "lsh": the centroids start as the bucket means of a random-hyperplane hash (ceil(log2 n_clusters) planes
+    with Gaussian normals through randomly chosen points, all drawn here with the seed); "sample": as n_clusters of the
+    points.  Clusters that end up empty are dropped.  Remaining keyword arguments go to Nomad (pool_size,
     sampled_far_field, batches_per_epoch, ...)."""
     if not (X.is_cuda and X.dtype == torch.float32 and X.dim() == 2):
         raise ValueError("X must be a float32 [n, d] tensor on the GPU")
@@ -63,8 +64,17 @@ def project(X: torch.Tensor, n_clusters: int, k: int = 15, n_epochs: int = 200, 
         times[name] = time.perf_counter() - t0
         return out
 
-    pick = torch.randperm(n, generator=torch.Generator().manual_seed(seed))[:n_clusters].to(X.device)
-    _, labels, km_iters, inertia = timed("kmeans", lambda: kmeans_lloyd(X, X[pick], kmeans_iters, device=device))
+    gen = torch.Generator().manual_seed(seed)
+    if kmeans_start == "lsh":
+        b = max(1, int(np.ceil(np.log2(n_clusters))))
+        planes = torch.randn(b, X.shape[1], generator=gen, dtype=torch.float32).to(X.device)
+        anchors = torch.randperm(n, generator=gen)[:b].to(torch.int32).to(X.device)
+        start = timed("kmeans_start", lambda: kmeans_lsh_init(X, n_clusters, planes, anchors, device=device))
+    elif kmeans_start == "sample":
+        start = X[torch.randperm(n, generator=gen)[:n_clusters].to(X.device)]
+    else:
+        raise ValueError("kmeans_start must be 'lsh' or 'sample'")
+    _, labels, km_iters, inertia = timed("kmeans", lambda: kmeans_lloyd(X, start, kmeans_iters, device=device))
     used, labels = torch.unique(labels, return_inverse=True)
     labels = labels.to(torch.int32)
     R = int(used.numel())

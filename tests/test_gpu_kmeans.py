@@ -67,3 +67,45 @@ def test_bad_arguments_are_codes():
         kmeans_lloyd(X, np.zeros((11, 4), np.float32), 5)        # more centroids than points
     with pytest.raises(NomadError):
         kmeans_lloyd(X, np.zeros((2, 4), np.float32), 0)
+
+
+# ---------------------------------------------------------------- the start from a locality-sensitive hash
+@pytest.mark.parametrize("n,d,K,b", [(5000, 16, 8, 3), (8000, 64, 40, 6), (3000, 130, 300, 9), (2000, 5, 1, 1), (4000, 768, 12, 4), (300, 7, 300, 30)])
+def test_hash_start_matches_the_oracle_exactly(n, d, K, b):
+    from paper_2505_15511_amd import kmeans_lsh_init
+    note(f"kmeans hash start n={n} d={d} K={K} planes={b}")
+    X = _data(n, d, 5, 400 + d)
+    rng = np.random.default_rng(K)
+    planes = rng.normal(size=(b, d)).astype(np.float32)
+    anchors = rng.choice(n, b, replace=b > n).astype(np.int32)
+    C_ref, buckets_ref = km.lsh_init(X, planes, anchors, K)
+    C, buckets = kmeans_lsh_init(X, K, planes, anchors, return_buckets=True)
+    assert np.array_equal(buckets.astype(np.int64), buckets_ref)
+    assert np.array_equal(C, C_ref)
+    Cd, bd = kmeans_lsh_init(torch.from_numpy(X).cuda(), K, torch.from_numpy(planes).cuda(), torch.from_numpy(anchors).cuda(), return_buckets=True)
+    assert np.array_equal(Cd.cpu().numpy(), C_ref) and np.array_equal(bd.cpu().numpy().astype(np.int64), buckets_ref)
+
+
+def test_hash_start_on_a_grid_and_bad_arguments():
+    from paper_2505_15511_amd import kmeans_lsh_init
+    # integer grid with integer normals: many points lie exactly on a plane (sum = 0 -> bit 0) and several buckets are empty
+    rng = np.random.default_rng(6)
+    G = rng.integers(0, 3, size=(2000, 4)).astype(np.float32)
+    planes = rng.integers(-1, 2, size=(5, 4)).astype(np.float32)
+    anchors = rng.choice(2000, 5).astype(np.int32)
+    C_ref, b_ref = km.lsh_init(G, planes, anchors, 32)
+    C, b = kmeans_lsh_init(G, 32, planes, anchors, return_buckets=True)
+    assert np.array_equal(b.astype(np.int64), b_ref) and np.array_equal(C, C_ref)
+    assert len(np.unique(b_ref)) < 32                                             # the empty-bucket rule was exercised
+    with pytest.raises(NomadError):
+        kmeans_lsh_init(G, 64, planes, anchors)                                   # 2^5 < 64
+    with pytest.raises(NomadError):
+        kmeans_lsh_init(G, 8, planes, np.array([0, 1, 2, 3, 2000], dtype=np.int32))   # an anchor that is no data point
+    # the hash start feeds Lloyd's iterations, which agree with the oracle from it
+    X = _data(6000, 24, 12, 301)
+    pl = np.random.default_rng(1).normal(size=(4, 24)).astype(np.float32)
+    an = np.array([5, 50, 500, 5000], dtype=np.int32)
+    C0 = kmeans_lsh_init(X, 12, pl, an)
+    C_ref, lab_ref, it_ref, _ = km.lloyd(X, km.lsh_init(X, pl, an, 12)[0], 30)
+    Cg, lab, it, _ = kmeans_lloyd(X, C0, 30)
+    assert it == it_ref and np.array_equal(lab.astype(np.int64), lab_ref) and np.array_equal(Cg, C_ref)

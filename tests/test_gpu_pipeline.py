@@ -36,9 +36,9 @@ def test_project_and_evaluate(graph):
 def test_random_start_and_sampler_options_pass_through():
     X, _ = workloads.gmm_points(8000, 16, 6, 16.0, 22, mix="equal", interleave=True)
     X = X.cuda()
-    theta = pipeline.project(X, n_clusters=8, n_epochs=40, init="random", seed=5, pool_size=256, pool_block=1024)
+    theta = pipeline.project(X, n_clusters=8, n_epochs=40, init="random", kmeans_start="sample", seed=5, pool_size=256, pool_block=1024)
     assert theta.shape == (8000, 2) and torch.isfinite(theta).all()
-    again = pipeline.project(X, n_clusters=8, n_epochs=40, init="random", seed=5, pool_size=256, pool_block=1024)
+    again = pipeline.project(X, n_clusters=8, n_epochs=40, init="random", kmeans_start="sample", seed=5, pool_size=256, pool_block=1024)
     assert torch.equal(theta, again)                                             # deterministic end to end
 
 
