@@ -156,7 +156,7 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     hipLaunchKernelGGL(k_knn_group, dim3(blocks_of(n, 256)), dim3(256), 0, st, dC, n, start, cursor, members);
     hipLaunchKernelGGL(k_knn_centroid_sums, dim3((uint32_t)hslabs.size()), dim3(256), 0, st, dX, d, members, start, slabs, centre);
     hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of((int64_t)R * d, 256)), dim3(256), 0, st, centre, start, R, d);
-    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, dX, n, d, dC, centre, norm, max_norm);
+    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, kNormRows)), dim3(256), 0, st, dX, n, d, dC, centre, norm, max_norm);
 
     // filter on the matrix cores, float64 refinement, exact fallback
     KnnSets P{};
@@ -231,7 +231,7 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
     KTRY(hipMemsetAsync(max_pts, 0, sizeof(uint32_t), st));
     hipLaunchKernelGGL(k_knn_centroid_sums, dim3((uint32_t)hslabs.size()), dim3(256), 0, st, dX, d, (const int32_t*)nullptr, qstart, slabs, centre);
     hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of(d, 256)), dim3(256), 0, st, centre, qstart, 1, d);
-    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, dX, n, d, (const int32_t*)nullptr, centre, (float*)nullptr, max_pts);
+    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, kNormRows)), dim3(256), 0, st, dX, n, d, (const int32_t*)nullptr, centre, (float*)nullptr, max_pts);
     hipLaunchKernelGGL(k_iota, dim3(blocks_of(n, 256)), dim3(256), 0, st, ids_in, n);
     // radix sort work space (points sorted by label, stable: ascending inside a cluster)
     int end_bit = 1;
@@ -250,7 +250,7 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
     while (it < max_iters) {
         // E step: the nearest centroid of every point, exactly
         KTRY(hipMemcpyAsync(max_norm, max_pts, sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
-        hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(K, 256)), dim3(256), 0, st, (const float*)dC, (int64_t)K, d, (const int32_t*)nullptr, centre, cnorm,
+        hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(K, kNormRows)), dim3(256), 0, st, (const float*)dC, (int64_t)K, d, (const int32_t*)nullptr, centre, cnorm,
                            max_norm);
         uint32_t hflag = 0;
         int rc = nearest_in_groups(st, P, blocks, (uint32_t)hblocks.size(), k, cand, tau, flagged, n_flagged, new_lab, &hflag);
@@ -426,8 +426,8 @@ int neighbours_of_queries(hipStream_t st, Buffers& buf, const float* A, int64_t 
     if (hbad) return NOMAD_E_INVALID_ARG;   // a query outside 0..n-1
     hipLaunchKernelGGL(k_knn_centroid_sums, dim3((uint32_t)hslabs.size()), dim3(256), 0, st, A, d, (const int32_t*)nullptr, cstart, slabs, centre);
     hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of(G * d, 256)), dim3(256), 0, st, centre, cstart, (int32_t)G, d);
-    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, 256)), dim3(256), 0, st, A, n, d, (const int32_t*)slice_of, centre, cnorm, max_norm);
-    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(mq, 256)), dim3(256), 0, st, (const float*)AQ, mq, d, (const int32_t*)group_of_q, centre,
+    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, kNormRows)), dim3(256), 0, st, A, n, d, (const int32_t*)slice_of, centre, cnorm, max_norm);
+    hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(mq, kNormRows)), dim3(256), 0, st, (const float*)AQ, mq, d, (const int32_t*)group_of_q, centre,
                        (float*)nullptr, max_norm);
     KnnSets P{};
     P.XQ = AQ; P.XC = A; P.qmembers = nullptr; P.cmembers = nullptr; P.qstart = qstart; P.cstart = cstart;

@@ -82,11 +82,16 @@ __global__ void __launch_bounds__(256) k_knn_centroid_finish(float* __restrict__
     centre[x] = cnt ? centre[x] / (float)cnt : 0.f;
 }
 
-// |x'|^2 of every centred row in float32 (t = 0..d-1 in order) and the largest one per cluster
+// |x'|^2 of every centred row in float32 and the largest one per cluster.  Sixteen lanes share a row (a wavefront reads
+// four consecutive rows, each lane every sixteenth column or 16-byte chunk) and add their partial sums pairwise; any
+// summation order stays within the d u |x'|^2 that the filter's error bound allows for the norm.
+constexpr int kNormLanes = 16;
+constexpr int kNormRows = 256 / kNormLanes;   // rows per workgroup
 __global__ void __launch_bounds__(256) k_knn_norms(const float* __restrict__ X, int64_t n, int32_t d, const int32_t* __restrict__ cluster_of,
                                                    const float* __restrict__ centre, float* __restrict__ norm,
                                                    uint32_t* __restrict__ max_norm_bits) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = (int64_t)blockIdx.x * kNormRows + threadIdx.x / kNormLanes;
+    const int part = threadIdx.x % kNormLanes;
     const bool valid = i < n;
     int32_t g = 0;
     float s = 0.f;
@@ -94,12 +99,27 @@ __global__ void __launch_bounds__(256) k_knn_norms(const float* __restrict__ X, 
         const float* x = X + i * d;
         g = cluster_of ? cluster_of[i] : 0;
         const float* c = centre + (int64_t)g * d;
-        for (int t = 0; t < d; ++t) {
-            const float v = x[t] - c[t];
-            s = fmaf(v, v, s);
+        if ((d & 3) == 0) {
+            for (int t = 4 * part; t < d; t += 4 * kNormLanes) {
+                const float4 xv = *(const float4*)(x + t), cv = *(const float4*)(c + t);
+                float v = xv.x - cv.x;
+                s = fmaf(v, v, s);
+                v = xv.y - cv.y;
+                s = fmaf(v, v, s);
+                v = xv.z - cv.z;
+                s = fmaf(v, v, s);
+                v = xv.w - cv.w;
+                s = fmaf(v, v, s);
+            }
+        } else {
+            for (int t = part; t < d; t += kNormLanes) {
+                const float v = x[t] - c[t];
+                s = fmaf(v, v, s);
+            }
         }
-        if (norm) norm[i] = s;
     }
+    for (int w = kNormLanes / 2; w > 0; w >>= 1) s += __shfl_xor(s, w, kNormLanes);   // every lane of the row: the row's sum
+    if (valid && part == 0 && norm) norm[i] = s;
     // non-negative floats order like their bit patterns; one atomic per wavefront where it lies inside one group
     const unsigned long long live = __ballot(valid);
     if (!live) return;
@@ -108,8 +128,8 @@ __global__ void __launch_bounds__(256) k_knn_norms(const float* __restrict__ X, 
     uint32_t bits = valid ? __float_as_uint(s) : 0u;
     if (__all(!valid || g == g0)) {
         for (int w = 32; w > 0; w >>= 1) bits = max(bits, (uint32_t)__shfl_xor((int)bits, w, 64));
-        if ((int)(threadIdx.x & 63) == first) atomicMax(&max_norm_bits[g0], bits);
-    } else if (valid) {
+        if ((int)(threadIdx.x & 63) == first && bits > max_norm_bits[g0]) atomicMax(&max_norm_bits[g0], bits);
+    } else if (valid && part == 0 && bits > max_norm_bits[g]) {   // the maximum only grows: a stale read costs one atomic, not the result
         atomicMax(&max_norm_bits[g], bits);
     }
 }
