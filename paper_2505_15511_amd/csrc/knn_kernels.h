@@ -597,15 +597,25 @@ __global__ void __launch_bounds__(256) k_kmeans_update(const float* __restrict__
     if (r1 == r0) return;
     double sum = 0.0;
     uint32_t r = r0;
-    for (; r + 16 <= r1; r += 16) {                     // sixteen rows in flight; the additions keep their order
-        int32_t id[16];
-        float v[16];
+    for (; r + 64 <= r1; r += 64) {                     // 64 rows in flight (two memory round trips per batch); the
+        int32_t id[64];                                 // additions keep their order
+        float v[64];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) id[u] = ids[r + u];
+        for (int u = 0; u < 64; ++u) id[u] = ids[r + u];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) v[u] = X[(int64_t)id[u] * d + col];
+        for (int u = 0; u < 64; ++u) v[u] = X[(int64_t)id[u] * d + col];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) sum = __dadd_rn(sum, (double)v[u]);
+        for (int u = 0; u < 64; ++u) sum = __dadd_rn(sum, (double)v[u]);
+    }
+    for (; r + 8 <= r1; r += 8) {
+        int32_t id[8];
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) id[u] = ids[r + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = X[(int64_t)id[u] * d + col];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum = __dadd_rn(sum, (double)v[u]);
     }
     for (; r < r1; ++r) sum = __dadd_rn(sum, (double)X[(int64_t)ids[r] * d + col]);
     C[x] = (float)(sum / (double)(r1 - r0));
