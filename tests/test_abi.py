@@ -80,6 +80,37 @@ def test_argument_errors_before_any_device_work(lib):
     assert lib.nomad_last_error(None) == b"null context"
 
 
+def test_stand_alone_entry_points_check_arguments_before_any_device_work(lib):
+    import numpy as np
+    x = np.zeros((8, 4), dtype=np.float32)
+    lab = np.zeros(8, dtype=np.int32)
+    out = np.zeros((8, 2), dtype=np.int32)
+    px, pl, po = (a.ctypes.data_as(C.c_void_p) for a in (x, lab, out))
+    hits = C.c_int64(0)
+    st = (C.c_double * 4)()
+    H = binding.NOMAD_HOST
+    # null pointers, sizes out of range, an unknown memory space: NOMAD_E_INVALID_ARG (-1) without touching a device
+    assert lib.nomad_knn_in_clusters(None, 8, 4, pl, 1, 2, po, H, 0, None, None) == -1
+    assert lib.nomad_knn_in_clusters(px, 8, 4, pl, 1, 33, po, H, 0, None, None) == -1
+    assert lib.nomad_knn_in_clusters(px, 8, 769, pl, 1, 2, po, H, 0, None, None) == -1
+    assert lib.nomad_knn_in_clusters(px, 8, 4, pl, 1, 2, po, 7, 0, None, None) == -1
+    assert lib.nomad_knn_in_clusters(px, 2 ** 31, 4, pl, 1, 2, po, H, 0, None, None) == -4
+    assert lib.nomad_kmeans_lloyd(px, 8, 4, 9, px, 5, pl, None, None, H, 0, None) == -1           # more centroids than points
+    assert lib.nomad_kmeans_lloyd(px, 8, 4, 2, px, 0, pl, None, None, H, 0, None) == -1           # no iterations
+    assert lib.nomad_kmeans_lsh_init(px, 8, 4, 8, px, pl, 2, px, None, H, 0, None) == -1          # 2^2 planes' codes < 8 buckets
+    assert lib.nomad_kmeans_lsh_init(px, 8, 4, 2, px, pl, 31, px, None, H, 0, None) == -1
+    assert lib.nomad_neighbourhood_preservation(px, 8, 4, px, 4, 0, None, 0, C.byref(hits), H, 0, None) == -1
+    assert lib.nomad_neighbourhood_preservation(px, 8, 4, px, 4, 2, None, 5, C.byref(hits), H, 0, None) == -1   # all points, yet a count
+    assert lib.nomad_neighbourhood_preservation(px, 1, 4, px, 4, 2, None, 0, C.byref(hits), H, 0, None) == -1
+    assert lib.nomad_random_triplet_accuracy(px, 2, 4, px, 4, 10, 0, C.byref(hits), H, 0, None) == -1
+    assert lib.nomad_random_triplet_accuracy(px, 8, 4, px, 4, -1, 0, C.byref(hits), H, 0, None) == -1
+    assert lib.nomad_random_triplet_accuracy(px, 8, 4, px, 4, 10, 0, None, H, 0, None) == -1
+    assert lib.nomad_pca_init(px, 8, 1, 0.0, px, st, H, 0, None) == -1
+    assert lib.nomad_pca_init(px, 1, 4, 0.0, px, st, H, 0, None) == -1
+    assert lib.nomad_pca_init(px, 8, 4, float("nan"), px, st, H, 0, None) == -1
+    assert lib.nomad_pca_init(px, 8, 4, 0.0, px, st, H, -1, None) == -1
+
+
 def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(_build, "LIB_PATH", "/nonexistent/libnomad.so")
