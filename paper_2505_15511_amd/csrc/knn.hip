@@ -73,7 +73,8 @@ int nearest_in_groups(hipStream_t st, const KnnSets& P, const KnnBlock* blocks, 
     uint32_t hflag = 0;
     KTRY(hipMemcpyAsync(&hflag, n_flagged, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     KTRY(hipStreamSynchronize(st));
-    if (hflag) hipLaunchKernelGGL(k_knn_exact, dim3(hflag), dim3(256), 0, st, P, flagged, k, out);
+    if (hflag && k <= 16) hipLaunchKernelGGL(k_knn_exact<16>, dim3(hflag), dim3(256), 0, st, P, flagged, k, out);
+    else if (hflag) hipLaunchKernelGGL(k_knn_exact<kMaxK>, dim3(hflag), dim3(256), 0, st, P, flagged, k, out);
     KTRY(hipGetLastError());
     *flagged_count = hflag;
     return NOMAD_OK;

@@ -525,7 +525,10 @@ __global__ void __launch_bounds__(256) k_knn_refine(const KnnSets P, const int32
 }
 
 // ---------------------------------------------------------------- stage 3: flagged queries, exactly, against the whole cluster
-// One workgroup per flagged query: k rounds, each picking the smallest (distance, point) above the one picked before.
+// One workgroup per flagged query.  Every thread walks its share of the group once and keeps its own k smallest
+// (distance, point) pairs sorted in registers (KL >= k slots); the k smallest of the group are among those, and k rounds
+// pick them: each thread offers its smallest pair above the one picked before, the workgroup takes the smallest offer.
+template <int KL>
 __global__ void __launch_bounds__(256) k_knn_exact(const KnnSets P, const int32_t* __restrict__ flagged, int32_t k, int32_t* __restrict__ out) {
     __shared__ double sD[256];
     __shared__ int32_t sP[256];
@@ -535,18 +538,39 @@ __global__ void __launch_bounds__(256) k_knn_exact(const KnnSets P, const int32_
     const uint32_t c0 = P.cstart[r], c1 = P.cstart[r + 1];
     const float* xq = P.XQ + (int64_t)q * d;
     const int32_t self = P.self_row ? P.self_row[q] : P.same_set ? q : -1;
+    double lD[KL];      // ascending in (distance, point); empty slots: (inf, -1) at the end
+    int32_t lP[KL];
+#pragma unroll
+    for (int x = 0; x < KL; ++x) { lD[x] = __builtin_inf(); lP[x] = -1; }
+    for (uint32_t pos = c0 + threadIdx.x; pos < c1; pos += 256) {
+        const int32_t c = knn_row(P.cmembers, pos);
+        if (c == self) continue;
+        double xD = exact_distance(xq, P.XC + (int64_t)c * d, d);
+        int32_t xP = c;
+        // the list's last used slot is slot k - 1: anything not before it cannot be among this thread's k smallest
+#pragma unroll
+        for (int x = 0; x < KL; ++x) {
+            if (x < k) {
+                const bool take = xP >= 0 && (lP[x] < 0 || xD < lD[x] || (xD == lD[x] && xP < lP[x]));
+                const double oD = lD[x];
+                const int32_t oP = lP[x];
+                lD[x] = take ? xD : oD;
+                lP[x] = take ? xP : oP;
+                xD = take ? oD : xD;
+                xP = take ? oP : xP;
+            }
+        }
+    }
     double lastD = -1.0;
     int32_t lastP = -1;
     for (int m = 0; m < k; ++m) {
         double bestD = __builtin_inf();
         int32_t bestP = -1;
-        for (uint32_t pos = c0 + threadIdx.x; pos < c1; pos += 256) {
-            const int32_t c = knn_row(P.cmembers, pos);
-            if (c == self) continue;
-            const double D = exact_distance(xq, P.XC + (int64_t)c * d, d);
-            const bool after = D > lastD || (D == lastD && c > lastP);
-            const bool better = D < bestD || (D == bestD && (bestP < 0 || c < bestP));
-            if (after && better) { bestD = D; bestP = c; }
+#pragma unroll
+        for (int x = KL - 1; x >= 0; --x) {   // descending, so that the first pair after the last pick is what remains
+            const bool after = lP[x] >= 0 && (lD[x] > lastD || (lD[x] == lastD && lP[x] > lastP));
+            bestD = after ? lD[x] : bestD;
+            bestP = after ? lP[x] : bestP;
         }
         sD[threadIdx.x] = bestD;
         sP[threadIdx.x] = bestP;
