@@ -141,7 +141,7 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     KTRY(hipStreamSynchronize(st));
     if (hbad) return NOMAD_E_BAD_GRAPH;   // a cluster id outside 0..n_clusters-1
     // the width class of the filter kernel decides how many queries a workgroup takes
-    const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(width_class(d)));
+    const uint32_t block_queries = (uint32_t)knn_filter_block_queries(width_class(d));
     std::vector<KnnBlock> hblocks, hslabs;
     for (int32_t r = 0; r < R; ++r) {
         hstart[r + 1] = hstart[r] + hcounts[r];
@@ -219,7 +219,7 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
     const uint32_t hq[2] = {0u, (uint32_t)n}, hc[2] = {0u, (uint32_t)K};
     KTRY(hipMemcpyAsync(qstart, hq, sizeof(hq), hipMemcpyHostToDevice, st));
     KTRY(hipMemcpyAsync(cstart, hc, sizeof(hc), hipMemcpyHostToDevice, st));
-    const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(width_class(d)));
+    const uint32_t block_queries = (uint32_t)knn_filter_block_queries(width_class(d));
     std::vector<KnnBlock> hblocks, hslabs;
     for (int64_t q0 = 0; q0 < n; q0 += block_queries) hblocks.push_back(KnnBlock{0, (int32_t)q0});
     for (int64_t q0 = 0; q0 < n; q0 += kCentroidRows) hslabs.push_back(KnnBlock{0, (int32_t)q0});
@@ -376,7 +376,7 @@ namespace {
 int neighbours_of_queries(hipStream_t st, Buffers& buf, const float* A, int64_t n, int32_t d, const int32_t* dQ, int64_t m, int32_t k,
                           int32_t* out) {
     const int32_t list_len = k + kPad;
-    const uint32_t block_queries = (uint32_t)(kWaveQueries * knn_filter_waves(width_class(d)));
+    const uint32_t block_queries = (uint32_t)knn_filter_block_queries(width_class(d));
     const int64_t base_blocks = (m + block_queries - 1) / block_queries;
     int64_t G = std::max<int64_t>(1, 1024 / base_blocks);
     G = std::min<int64_t>(G, 256 / k);                       // the merge ranks slices * k candidates in one workgroup

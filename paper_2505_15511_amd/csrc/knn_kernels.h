@@ -23,16 +23,19 @@ constexpr int kMaxList = kMaxK + kPad;
 constexpr int kWaveQueries = 16;   // queries per wavefront (the N of the 16x16x4 tile)
 constexpr int kTile = 16;          // candidates per tile (the M of the 16x16x4 tile)
 constexpr int32_t kEmptyPoint = 0x7fffff00;   // stand-ins for empty list slots: above every point index (n < 2^31 - 256)
-// wavefronts per workgroup of the filter: 8 (128 queries share every staged tile); 4 at the widest rows (d > 256),
-// where a lane's share of its query's row and its candidate list need more than the 256 registers that two
-// wavefronts per SIMD leave it
-__host__ __device__ constexpr int knn_filter_waves(int d4) { return d4 >= 128 ? 4 : 8; }
+// The filter's workgroup is 8 wavefronts.  Up to d = 256 each wavefront has 16 queries of its own and the whole of their
+// rows in registers (128 queries share every staged tile).  At wider rows a lane's share of its query's row (d / 4
+// values) would leave one wavefront per SIMD, so two wavefronts share 16 queries and hold half of the columns each
+// (64 queries per workgroup): each multiplies its half, the two partial tiles are exchanged through LDS and added.
+__host__ __device__ constexpr int knn_filter_waves(int) { return 8; }
+__host__ __device__ constexpr int knn_filter_split(int d4) { return d4 >= 128 ? 2 : 1; }
+__host__ __device__ constexpr int knn_filter_block_queries(int d4) { return kWaveQueries * knn_filter_waves(d4) / knn_filter_split(d4); }
 // LDS buffers for the staged candidate tile: two, or one at the widest rows (see the kernel)
 __host__ __device__ constexpr int knn_filter_buffers(int d4) { return d4 > 64 ? 1 : 2; }
 
 // wavefronts per SIMD the filter is compiled for: narrow rows and short lists fit two workgroups per compute unit (128
 // registers per lane), and the second workgroup is what hides the first one's tile barriers
-__host__ __device__ constexpr int knn_filter_waves_per_simd(int d4, int L) { return d4 <= 32 && L <= 12 ? 4 : d4 <= 64 ? 2 : 1; }
+__host__ __device__ constexpr int knn_filter_waves_per_simd(int d4, int L) { return d4 <= 32 && L <= 12 ? 4 : 2; }
 
 struct KnnBlock { int32_t cluster; int32_t q0; };   // queries q0 .. of group `cluster`: one workgroup's share
 
@@ -176,7 +179,7 @@ __global__ void __launch_bounds__(256) k_knn_group(const int32_t* __restrict__ c
 // registers for the whole loop (D4 = ceil(d / 4) values per lane).
 //
 // The candidates' rows are scattered over memory (a cluster's points are wherever the data set has them).  Thread t
-// always copies the same 16-byte chunks of one row (32 threads per row, 16 at the widest rows); the
+// always copies the same 16-byte chunks of one row (32 threads per row); the
 // loads of tile T+2 go out while tile T is multiplied (two register sets, the loop unrolled by two), tile T+1 is
 // written to the other LDS buffer after the multiplications; the point behind each row is fetched one tile further
 // ahead still, first thing in the iteration, so that no row load waits for an index.  LDS rows are padded to 4 D4 + 2
@@ -198,7 +201,7 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
     constexpr int kFilterBlock = 64 * knn_filter_waves(D4);
     constexpr int kRow = 4 * D4 + 2;
     constexpr int kTileWords = kTile * kRow;
-    constexpr int kRowThreads = kFilterBlock / kTile;          // 32 threads copy one row (16 at the widest rows)
+    constexpr int kRowThreads = kFilterBlock / kTile;          // 32 threads copy one row
     constexpr int kChunks = (D4 + kRowThreads - 1) / kRowThreads;   // 16-byte chunks per thread and tile
     constexpr bool kTwoAhead = D4 <= 64;                      // two tiles of rows in flight where the registers allow it
     constexpr int kBuffers = knn_filter_buffers(D4);          // LDS tile buffers
@@ -209,22 +212,26 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
     int32_t* tile_pt = (int32_t*)(tnorm + 2 * kTile);         // [2][kTile] point of each staged candidate (-1: none)
     float* mkey = (float*)(tile_pt + 2 * kTile);              // [waves][kMerge] merge scratch of one query per wavefront
     int32_t* mpt = (int32_t*)(mkey + knn_filter_waves(D4) * kMerge);   // [waves][kMerge]
+    floatx4* xch = (floatx4*)(mpt + knn_filter_waves(D4) * kMerge);    // [waves][64] partial tiles (split rows only; 16-byte aligned)
+    constexpr int kSplit = knn_filter_split(D4);                       // wavefronts that share 16 queries
+    constexpr int KH = D4 / kSplit;                                    // 4-column steps per wavefront
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = wave % kSplit;                                    // which part of the columns this wavefront multiplies
     const KnnBlock blk = blocks[blockIdx.x];
     const uint32_t c0 = P.cstart[blk.cluster], c1 = P.cstart[blk.cluster + 1];
     const int32_t n_r = (int32_t)(c1 - c0);                    // candidates of the group
     const uint32_t q0g = P.qstart[blk.cluster];
     const int32_t n_qg = (int32_t)(P.qstart[blk.cluster + 1] - q0g);   // queries of the group
     // this lane's query and its slice of the row
-    const int32_t qpos = blk.q0 + wave * kWaveQueries + (lane & 15);
+    const int32_t qpos = blk.q0 + (wave / kSplit) * kWaveQueries + (lane & 15);
     const int32_t qpt = qpos < n_qg ? knn_row(P.qmembers, q0g + qpos) : -1;
     // the candidate that is the query itself, if any
     const int32_t self = qpt < 0 ? -1 : P.self_row ? P.self_row[qpt] : P.same_set ? qpt : -1;
     const float* ctr = P.centre + (int64_t)blk.cluster * d;    // the group's centre: every row enters as x - centre
-    float breg[D4];
+    float breg[KH];
 #pragma unroll
-    for (int t = 0; t < D4; ++t) {
-        const int col = 4 * t + (lane >> 4);
+    for (int t = 0; t < KH; ++t) {
+        const int col = 4 * (half * KH + t) + (lane >> 4);
         breg[t] = (qpt >= 0 && col < d) ? P.XQ[(int64_t)qpt * d + col] - ctr[col] : 0.f;
     }
     float lk[L];      // this lane's L smallest keys so far, ascending
@@ -236,12 +243,22 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
     const int srow = tid / kRowThreads, sthr = tid % kRowThreads;   // this thread's row of every tile and its place in it
     const bool vec = (d & 3) == 0;                                  // rows are 16-byte aligned
     struct Staged { float4 v[kChunks]; int32_t pt; float nrm; };
-    float4 cchunk[kChunks];                                         // the centre at this thread's columns
-#pragma unroll
-    for (int u = 0; u < kChunks; ++u) {
+    // the centre at this thread's columns: in registers, or at the widest rows (where registers are short) in LDS
+    constexpr bool kKeepCentre = D4 < 192;
+    float* lds_centre = (float*)(xch + (kSplit == 2 ? knn_filter_waves(D4) * 64 : 0));   // [4 D4] (widest rows only)
+    if (!kKeepCentre) {
+        for (int col = tid; col < 4 * D4; col += kFilterBlock) lds_centre[col] = col < d ? ctr[col] : 0.f;
+        __syncthreads();
+    }
+    auto centre_at = [&](int u) {
         const int col = 4 * (sthr + u * kRowThreads);
-        cchunk[u] = make_float4(col < d ? ctr[col] : 0.f, col + 1 < d ? ctr[col + 1] : 0.f, col + 2 < d ? ctr[col + 2] : 0.f,
-                                col + 3 < d ? ctr[col + 3] : 0.f);
+        return make_float4(col < d ? ctr[col] : 0.f, col + 1 < d ? ctr[col + 1] : 0.f, col + 2 < d ? ctr[col + 2] : 0.f,
+                           col + 3 < d ? ctr[col + 3] : 0.f);
+    };
+    float4 cchunk[kKeepCentre ? kChunks : 1];
+    if (kKeepCentre) {
+#pragma unroll
+        for (int u = 0; u < kChunks; ++u) cchunk[u] = centre_at(u);
     }
     auto point_at = [&](int32_t pos) { return pos < n_r ? knn_row(P.cmembers, c0 + pos) : -1; };
     // loads of this thread's chunks of the row of point pt (any valid row when pt < 0; masked when it is stored)
@@ -270,8 +287,9 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
             const int col = 4 * (sthr + u * kRowThreads);
             if (col < 4 * D4) {
                 const bool live = S.pt >= 0;
-                float2 lo = make_float2((live && col < d) ? S.v[u].x - cchunk[u].x : 0.f, (live && col + 1 < d) ? S.v[u].y - cchunk[u].y : 0.f);
-                float2 hi = make_float2((live && col + 2 < d) ? S.v[u].z - cchunk[u].z : 0.f, (live && col + 3 < d) ? S.v[u].w - cchunk[u].w : 0.f);
+                const float4 cc = kKeepCentre ? cchunk[kKeepCentre ? u : 0] : *(const float4*)(lds_centre + col);
+                float2 lo = make_float2((live && col < d) ? S.v[u].x - cc.x : 0.f, (live && col + 1 < d) ? S.v[u].y - cc.y : 0.f);
+                float2 hi = make_float2((live && col + 2 < d) ? S.v[u].z - cc.z : 0.f, (live && col + 3 < d) ? S.v[u].w - cc.w : 0.f);
                 *(float2*)(dst + col) = lo;        // rows start on even words: 8-byte stores
                 *(float2*)(dst + col + 2) = hi;
             }
@@ -281,9 +299,15 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
     // multiply the tile in LDS buffer `buf` with this wavefront's queries, push what beats the lists' last keys
     auto consume = [&](int buf) {
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-        const float* arow = tile + buf * kTileWords + (lane & 15) * kRow + (lane >> 4);
+        const float* arow = tile + buf * kTileWords + (lane & 15) * kRow + (lane >> 4) + 4 * half * KH;
 #pragma unroll
-        for (int t = 0; t < D4; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(arow[4 * t], breg[t], acc, 0, 0, 0);
+        for (int t = 0; t < KH; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(arow[4 * t], breg[t], acc, 0, 0, 0);
+        if (kSplit == 2) {   // the other half of the columns: a + b and b + a are the same number, both wavefronts go on alike
+            xch[wave * 64 + lane] = acc;
+            __syncthreads();
+            const floatx4 other = xch[(wave ^ 1) * 64 + lane];
+            acc[0] += other[0]; acc[1] += other[1]; acc[2] += other[2]; acc[3] += other[3];
+        }
         float ck[4];      // this lane's four candidates of the tile
         int32_t cp[4];
 #pragma unroll
@@ -374,7 +398,9 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
         }
     }
 
-    // ---- merge the four lists of every query, one query of the wavefront at a time
+    // ---- merge the four lists of every query, one query of the wavefront at a time (of two wavefronts that share their
+    // queries both hold the same lists: one of them reports)
+    if (half != 0) return;
     float* mk = mkey + wave * kMerge;
     int32_t* mp = mpt + wave * kMerge;
     // the smallest of the four lists' last keys: what this query's lanes may have turned away
@@ -430,7 +456,8 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
 }
 
 __host__ __device__ inline size_t knn_filter_lds_bytes(int d4, int L) {
-    return ((size_t)knn_filter_buffers(d4) * kTile * (4 * d4 + 2) + 4 * kTile + (size_t)2 * knn_filter_waves(d4) * 4 * L) * 4;
+    return ((size_t)knn_filter_buffers(d4) * kTile * (4 * d4 + 2) + 4 * kTile + (size_t)2 * knn_filter_waves(d4) * 4 * L) * 4 +
+           (knn_filter_split(d4) == 2 ? (size_t)knn_filter_waves(d4) * 64 * 16 : 0) + (d4 >= 192 ? (size_t)16 * d4 : 0);
 }
 // entries per lane's list for K' = list_len candidates per query: half of K', so that the four lists of a query hold 2 K'
 __host__ inline int knn_filter_list_class(int list_len) { return list_len <= 16 ? 8 : list_len <= 24 ? 12 : 20; }
