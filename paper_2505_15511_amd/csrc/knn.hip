@@ -41,7 +41,7 @@ hipError_t launch_filter_d(hipStream_t st, uint32_t n_blocks, const KnnSets& P, 
 // width class of the filter kernel for rows of d values
 inline int width_class(int32_t d) {
     const int d4 = (d + 3) / 4;
-    return d4 <= 8 ? 8 : d4 <= 16 ? 16 : d4 <= 32 ? 32 : d4 <= 64 ? 64 : d4 <= 128 ? 128 : 192;
+    return d4 <= 8 ? 8 : d4 <= 16 ? 16 : d4 <= 32 ? 32 : d4 <= 64 ? 64 : d4 <= 96 ? 96 : d4 <= 128 ? 128 : 192;
 }
 
 hipError_t launch_filter(hipStream_t st, uint32_t n_blocks, const KnnSets& P, const KnnBlock* blocks, int32_t list_len, int32_t* cand,
@@ -51,6 +51,7 @@ hipError_t launch_filter(hipStream_t st, uint32_t n_blocks, const KnnSets& P, co
         case 16: return launch_filter_d<16>(st, n_blocks, P, blocks, list_len, cand, tau);
         case 32: return launch_filter_d<32>(st, n_blocks, P, blocks, list_len, cand, tau);
         case 64: return launch_filter_d<64>(st, n_blocks, P, blocks, list_len, cand, tau);
+        case 96: return launch_filter_d<96>(st, n_blocks, P, blocks, list_len, cand, tau);
         case 128: return launch_filter_d<128>(st, n_blocks, P, blocks, list_len, cand, tau);
         default: return launch_filter_d<192>(st, n_blocks, P, blocks, list_len, cand, tau);
     }
