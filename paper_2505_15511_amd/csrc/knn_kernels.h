@@ -23,7 +23,7 @@ constexpr int kMaxList = kMaxK + kPad;
 constexpr int kWaveQueries = 16;   // queries per wavefront (the N of the 16x16x4 tile)
 constexpr int kTile = 16;          // candidates per tile (the M of the 16x16x4 tile)
 constexpr int32_t kEmptyPoint = 0x7fffff00;   // stand-ins for empty list slots: above every point index (n < 2^31 - 256)
-// The filter's workgroup is 8 wavefronts.  Up to d = 256 each wavefront has 16 queries of its own and the whole of their
+// The filter's workgroup is 8 wavefronts.  Up to d = 384 each wavefront has 16 queries of its own and the whole of their
 // rows in registers (128 queries share every staged tile).  At wider rows a lane's share of its query's row (d / 4
 // values) would leave one wavefront per SIMD, so two wavefronts share 16 queries and hold half of the columns each
 // (64 queries per workgroup): each multiplies its half, the two partial tiles are exchanged through LDS and added.
@@ -300,8 +300,30 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
     auto consume = [&](int buf) {
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
         const float* arow = tile + buf * kTileWords + (lane & 15) * kRow + (lane >> 4) + 4 * half * KH;
+        if (kSplit == 1) {
 #pragma unroll
-        for (int t = 0; t < KH; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(arow[4 * t], breg[t], acc, 0, 0, 0);
+            for (int t = 0; t < KH; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(arow[4 * t], breg[t], acc, 0, 0, 0);
+        } else {
+            // Long rows: the candidates' values come from LDS in batches of kBatch, the next batch on its way while this one
+            // is multiplied (left to itself the compiler reads each value right before its multiplication and waits for it).
+            constexpr int kBatch = 8;
+            float a_cur[kBatch], a_nxt[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) a_cur[u] = arow[4 * u];
+#pragma unroll
+            for (int tb = 0; tb < KH; tb += kBatch) {
+                if (tb + kBatch < KH) {
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) a_nxt[u] = arow[4 * (tb + kBatch + u)];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u], breg[tb + u], acc, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) a_cur[u] = a_nxt[u];
+            }
+        }
         if (kSplit == 2) {   // the other half of the columns: a + b and b + a are the same number, both wavefronts go on alike
             xch[wave * 64 + lane] = acc;
             __syncthreads();
