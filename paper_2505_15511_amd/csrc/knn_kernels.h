@@ -300,11 +300,11 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
     auto consume = [&](int buf) {
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
         const float* arow = tile + buf * kTileWords + (lane & 15) * kRow + (lane >> 4) + 4 * half * KH;
-        if (kSplit == 1) {
+        if (D4 < 64) {
 #pragma unroll
             for (int t = 0; t < KH; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(arow[4 * t], breg[t], acc, 0, 0, 0);
         } else {
-            // Long rows: the candidates' values come from LDS in batches of kBatch, the next batch on its way while this one
+            // Rows of 256 columns and more: the candidates' values come from LDS in batches of kBatch, the next batch on its way while this one
             // is multiplied (left to itself the compiler reads each value right before its multiplication and waits for it).
             constexpr int kBatch = 8;
             float a_cur[kBatch], a_nxt[kBatch];
