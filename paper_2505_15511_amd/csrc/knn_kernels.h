@@ -341,7 +341,7 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
         }
         // Insertion passes run for the whole wavefront, so they are spent on the lane's best remaining candidate: some lane
         // has a hit in most tiles, a lane with two in one tile is rare, and the second pass is skipped when there is none.
-#pragma unroll
+#pragma nounroll   // a real loop: unrolled, every early exit would copy the whole list into the registers of the next tile
         for (int pass = 0; pass < 4; ++pass) {
             float xk = ck[0];
             int32_t xp = cp[0];
