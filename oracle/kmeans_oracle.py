@@ -16,7 +16,11 @@ The start from a locality-sensitive hash (one sentence in the paper, no detail) 
     point x_{a_j} (anchor indices drawn by the caller); bit j of a point is [ sum_t h_{j,t} (x_t - x_{a_j,t}) > 0 ], the
     sum over t = 0..d-1 in order, difference, product and running sum each rounded once in float64;
   * code = sum_j bit_j 2^j; bucket = floor(code K / 2^b); centroid j = the M step applied to bucket j;
-  * an empty bucket j takes the data point with index floor(j n / K) as its centroid.
+  * an empty bucket j takes the data point with index floor(j n / K) as its centroid;
+  * when the caller draws no anchors, plane j passes through the median of a sample along its normal: the sample is the
+    m = min(1024, n) points floor(s n / m), their projections sum_t h_{j,t} x_t are accumulated over t = 0..d-1 in order
+    (product and running sum each rounded once in float64), and the anchor is the sample point of rank floor(m / 2) in
+    ascending (projection, point index): about half of the data on either side of every plane.
 
 parity status: pinned in tests/test_oracle_kmeans.py (scipy's vq for the E step, closed forms, monotone inertia,
 the fixed-point property; for the hash start: numpy's matrix product for the bits, planes with sides known by
@@ -100,3 +104,23 @@ def lsh_init(X: np.ndarray, planes: np.ndarray, anchors: np.ndarray, K: int):
     buckets = lsh_buckets(X, planes, anchors, K)
     fallback = X[(np.arange(K, dtype=np.int64) * n) // K]
     return update(X, buckets, fallback), buckets
+
+
+LSH_SAMPLE = 1024
+
+
+def lsh_median_anchors(X: np.ndarray, planes: np.ndarray) -> np.ndarray:
+    """Anchor point int64 [b] of every plane: the median of a strided sample along the plane's normal."""
+    X = np.asarray(X, dtype=np.float32)
+    planes = np.asarray(planes, dtype=np.float32)
+    n = len(X)
+    m = min(LSH_SAMPLE, n)
+    idx = (np.arange(m, dtype=np.int64) * n) // m
+    anchors = np.zeros(len(planes), dtype=np.int64)
+    for j in range(len(planes)):
+        proj = np.zeros(m, dtype=np.float64)
+        for t in range(X.shape[1]):
+            proj = proj + np.float64(planes[j, t]) * X[idx, t].astype(np.float64)
+        order = np.lexsort((idx, proj))
+        anchors[j] = idx[order[m // 2]]
+    return anchors

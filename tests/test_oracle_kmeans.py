@@ -118,3 +118,30 @@ def test_hash_start_means_and_empty_buckets():
     _, d0 = km.assign(X3, C0)
     _, _, _, inertia = km.lloyd(X3, C0, 10)
     assert inertia < d0.sum()
+
+
+def test_median_anchors_split_the_data_in_halves():
+    rng = np.random.default_rng(8)
+    X = (rng.normal(size=(5000, 12)) * rng.uniform(0.5, 3.0, size=12) + rng.normal(size=12) * 4).astype(np.float32)
+    planes = rng.normal(size=(6, 12)).astype(np.float32)
+    anchors = km.lsh_median_anchors(X, planes)
+    idx = (np.arange(1024) * 5000) // 1024
+    proj = X[idx].astype(np.float64) @ planes.astype(np.float64).T            # library route: the sample's projections
+    for j in range(6):
+        assert anchors[j] in idx
+        below = np.count_nonzero(proj[:, j] < proj[np.nonzero(idx == anchors[j])[0][0], j])
+        assert below == 512                                                   # rank m / 2 of 1024 distinct values
+    buckets = km.lsh_buckets(X, planes, anchors, 64)
+    bits = np.stack([(buckets >> j) & 1 for j in range(6)], axis=1)            # K = 2^b: the bucket is the code
+    assert np.abs(bits.mean(axis=0) - 0.5).max() < 0.05                        # every plane halves the data
+    counts = np.bincount(buckets, minlength=64)
+    assert counts.max() < 6 * 5000 / 64                                        # no giant bucket (planes through far points leave some)
+
+
+def test_median_anchor_by_hand_and_small_inputs():
+    # five points on a line, normal +e_0: projections 3, 1, 4, 1, 5 -> ascending (projection, index): 1, 3, 0, 2, 4; rank 2 = point 0
+    X = np.array([[3, 0], [1, 0], [4, 0], [1, 0], [5, 0]], dtype=np.float32)
+    assert km.lsh_median_anchors(X, np.array([[1, 0]], dtype=np.float32)).tolist() == [0]
+    assert km.lsh_median_anchors(X, np.array([[-1, 0]], dtype=np.float32)).tolist() == [0]      # -5 -4 -3 -1 -1: rank 2 = point 0
+    assert km.lsh_median_anchors(X, np.array([[0, 1]], dtype=np.float32)).tolist() == [2]       # all ties: by index
+    assert km.lsh_median_anchors(X[:1], np.array([[1, 0]], dtype=np.float32)).tolist() == [0]
