@@ -266,7 +266,9 @@ int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t K, float* c
  *
  *   X            [n*d] fp32 row-major
  *   planes       [n_planes*d] fp32: the normals h_j;  anchors [n_planes] int32: plane j passes through the data point
- *                x_{anchors[j]};  1 <= n_planes <= 30 and 2^n_planes >= K
+ *                x_{anchors[j]};  1 <= n_planes <= 30 and 2^n_planes >= K.  anchors == NULL: the library takes, for every
+ *                plane, the median along h_j of the sample of min(1024, n) points floor(s n / m) (projection sum_t h_{j,t} x_t
+ *                in sequential float64, rank floor(m / 2) in ascending (projection, point)): every plane then halves the data
  *   centroids_out [K*d] fp32 out;  buckets_out NULL or [n] int32 out: the bucket of every point
  *
  * bit j of a point = [ sum_t h_{j,t} (x_t - x_{anchors[j],t}) > 0 ], the sum over t = 0..d-1 in order with difference,

@@ -246,15 +246,18 @@ def pca_init(X, std0=0.0, device=0, stream=None, return_stats=False):
     return theta
 
 
-def kmeans_lsh_init(X, K, planes, anchors, device=0, stream=None, return_buckets=False):
+def kmeans_lsh_init(X, K, planes, anchors=None, device=0, stream=None, return_buckets=False):
     """nomad_kmeans_lsh_init: initial centroids [K, d] from random-hyperplane hashing.  X, planes [b, d] and anchors [b]
-    (int32 point indices) all torch tensors on the device, or all host arrays."""
+    (int32 point indices; None: the library puts every plane through a sample median) all torch tensors on the
+    device, or all host arrays."""
     lib = load_library()
     n, d = int(X.shape[0]), int(X.shape[1])
     b = int(planes.shape[0])
     px, m0, keep_x = _marshal(X, np.float32, n * d)
     pp, m1, keep_p = _marshal(planes, np.float32, b * d)
     pa, m2, keep_a = _marshal(anchors, np.int32, b)
+    if anchors is None:
+        m2 = m0
     if not (m0 == m1 == m2):
         raise ValueError("X, planes and anchors must live in the same memory space")
     if m0 == NOMAD_DEVICE:

@@ -297,7 +297,7 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
 }
 extern "C" int nomad_kmeans_lsh_init(const float* X, int64_t n, int32_t d, int32_t K, const float* planes, const int32_t* anchors,
                                      int32_t n_planes, float* centroids_out, int32_t* buckets_out, int mem, int32_t device, void* stream) {
-    if (!X || !planes || !anchors || !centroids_out || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return NOMAD_E_INVALID_ARG;
+    if (!X || !planes || !centroids_out || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return NOMAD_E_INVALID_ARG;
     if (n < 1 || d < 1 || d > NOMAD_KNN_MAX_DIM || K < 1 || K > n || n_planes < 1 || n_planes > kMaxPlanes || device < 0) return NOMAD_E_INVALID_ARG;
     if (((int64_t)1 << n_planes) < K) return NOMAD_E_INVALID_ARG;
     if (n >= ((int64_t)1 << 31) - 256) return NOMAD_E_TOO_LARGE;
@@ -310,25 +310,34 @@ extern "C" int nomad_kmeans_lsh_init(const float* X, int64_t n, int32_t d, int32
     const int32_t* dA = anchors;
     float* dC = centroids_out;
     int32_t* dB = buckets_out;
-    std::vector<int32_t> hanchors((size_t)n_planes);
+    std::vector<int32_t> hanchors((size_t)n_planes, 0);
     if (mem == NOMAD_HOST) {
         float *x = nullptr, *pl = nullptr, *c = nullptr;
-        int32_t* a = nullptr;
         KTRY(buf.alloc(&x, (size_t)n * d));
         KTRY(buf.alloc(&pl, (size_t)n_planes * d));
-        KTRY(buf.alloc(&a, (size_t)n_planes));
         KTRY(buf.alloc(&c, (size_t)K * d));
         KTRY(hipMemcpyAsync(x, X, sizeof(float) * (size_t)n * d, hipMemcpyHostToDevice, st));
         KTRY(hipMemcpyAsync(pl, planes, sizeof(float) * (size_t)n_planes * d, hipMemcpyHostToDevice, st));
-        KTRY(hipMemcpyAsync(a, anchors, sizeof(int32_t) * (size_t)n_planes, hipMemcpyHostToDevice, st));
-        for (int32_t j = 0; j < n_planes; ++j) hanchors[j] = anchors[j];
-        dX = x; dP = pl; dA = a; dC = c;
-    } else {
+        dX = x; dP = pl; dC = c;
+        if (anchors) {
+            int32_t* a = nullptr;
+            KTRY(buf.alloc(&a, (size_t)n_planes));
+            KTRY(hipMemcpyAsync(a, anchors, sizeof(int32_t) * (size_t)n_planes, hipMemcpyHostToDevice, st));
+            for (int32_t j = 0; j < n_planes; ++j) hanchors[j] = anchors[j];
+            dA = a;
+        }
+    } else if (anchors) {
         KTRY(hipMemcpyAsync(hanchors.data(), anchors, sizeof(int32_t) * (size_t)n_planes, hipMemcpyDeviceToHost, st));
         KTRY(hipStreamSynchronize(st));
     }
     for (int32_t j = 0; j < n_planes; ++j)
         if (hanchors[j] < 0 || hanchors[j] >= n) return NOMAD_E_INVALID_ARG;   // an anchor that is no data point
+    if (!anchors) {   // every plane through the median of a sample along its normal
+        int32_t* a = nullptr;
+        KTRY(buf.alloc(&a, (size_t)n_planes));
+        hipLaunchKernelGGL(k_lsh_median_anchors, dim3((uint32_t)n_planes), dim3(256), 0, st, dX, n, d, dP, a);
+        dA = a;
+    }
     if (!dB || mem == NOMAD_HOST) {
         int32_t* bk = nullptr;
         KTRY(buf.alloc(&bk, (size_t)n));

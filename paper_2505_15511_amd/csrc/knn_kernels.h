@@ -722,6 +722,32 @@ __global__ void __launch_bounds__(256) k_lsh_buckets(const float* __restrict__ X
     bucket[i] = (int32_t)((code * (uint64_t)K) >> b);
 }
 
+// Anchors the caller did not draw: plane j goes through the median of a strided sample along its normal.  The sample is the
+// m = min(kLshSample, n) points floor(s n / m); projection = sum_t h_{j,t} x_t over t = 0..d-1 in order (product and
+// running sum each rounded once in float64); the anchor is the sample point of rank floor(m / 2) in ascending
+// (projection, point).  One workgroup per plane: four sample points per thread, ranks by counting.
+constexpr int kLshSample = 1024;
+__global__ void __launch_bounds__(256) k_lsh_median_anchors(const float* __restrict__ X, int64_t n, int32_t d, const float* __restrict__ planes,
+                                                            int32_t* __restrict__ anchors) {
+    __shared__ double sproj[kLshSample];
+    const int j = blockIdx.x;
+    const int m = (int)min((int64_t)kLshSample, n);
+    const float* h = planes + (int64_t)j * d;
+    for (int s = threadIdx.x; s < m; s += 256) {
+        const float* x = X + (((int64_t)s * n) / m) * d;
+        double acc = 0.0;
+        for (int t = 0; t < d; ++t) acc = __dadd_rn(acc, __dmul_rn((double)h[t], (double)x[t]));
+        sproj[s] = acc;
+    }
+    __syncthreads();
+    for (int s = threadIdx.x; s < m; s += 256) {   // sample points are in ascending index order: ties go to the lower s
+        const double p = sproj[s];
+        int rank = 0;
+        for (int o = 0; o < m; ++o) rank += (sproj[o] < p || (sproj[o] == p && o < s)) ? 1 : 0;
+        if (rank == m / 2) anchors[j] = (int32_t)(((int64_t)s * n) / m);
+    }
+}
+
 // centroid j starts as the data point floor(j n / K): what an empty bucket keeps
 __global__ void __launch_bounds__(256) k_lsh_fallback(const float* __restrict__ X, int64_t n, int32_t d, int32_t K, float* __restrict__ C) {
     const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

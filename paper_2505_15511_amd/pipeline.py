@@ -48,7 +48,7 @@ def project(X: torch.Tensor, n_clusters: int, k: int = 15, n_epochs: int = 200, 
     return_info a dict of the intermediate results and the seconds each stage took.
 
     kmeans_start "lsh": the centroids start as the bucket means of a random-hyperplane hash (ceil(log2 n_clusters) planes
-    with Gaussian normals through randomly chosen points, all drawn here with the seed); "sample": as n_clusters of the
+    with Gaussian normals drawn here with the seed, each through the median of a sample along its normal); "sample": as n_clusters of the
     points.  Clusters that end up empty are dropped.  Remaining keyword arguments go to Nomad (pool_size,
     sampled_far_field, batches_per_epoch, ...)."""
     if not (X.is_cuda and X.dtype == torch.float32 and X.dim() == 2):
@@ -68,8 +68,7 @@ def project(X: torch.Tensor, n_clusters: int, k: int = 15, n_epochs: int = 200, 
     if kmeans_start == "lsh":
         b = max(1, int(np.ceil(np.log2(n_clusters))))
         planes = torch.randn(b, X.shape[1], generator=gen, dtype=torch.float32).to(X.device)
-        anchors = torch.randperm(n, generator=gen)[:b].to(torch.int32).to(X.device)
-        start = timed("kmeans_start", lambda: kmeans_lsh_init(X, n_clusters, planes, anchors, device=device))
+        start = timed("kmeans_start", lambda: kmeans_lsh_init(X, n_clusters, planes, None, device=device))   # planes through sample medians
     elif kmeans_start == "sample":
         start = X[torch.randperm(n, generator=gen)[:n_clusters].to(X.device)]
     else:

@@ -109,3 +109,23 @@ def test_hash_start_on_a_grid_and_bad_arguments():
     C_ref, lab_ref, it_ref, _ = km.lloyd(X, km.lsh_init(X, pl, an, 12)[0], 30)
     Cg, lab, it, _ = kmeans_lloyd(X, C0, 30)
     assert it == it_ref and np.array_equal(lab.astype(np.int64), lab_ref) and np.array_equal(Cg, C_ref)
+
+
+@pytest.mark.parametrize("n,d,K,b", [(5000, 16, 8, 3), (8000, 64, 40, 6), (700, 130, 300, 9), (4000, 768, 12, 4), (3, 5, 2, 1)])
+def test_hash_start_with_median_anchors_matches_the_oracle_exactly(n, d, K, b):
+    from paper_2505_15511_amd import kmeans_lsh_init
+    note(f"kmeans hash start, median anchors n={n} d={d} K={K} planes={b}")
+    X = _data(n, d, 5, 500 + d)
+    planes = np.random.default_rng(K + 1).normal(size=(b, d)).astype(np.float32)
+    anchors = km.lsh_median_anchors(X, planes)
+    C_ref, buckets_ref = km.lsh_init(X, planes, anchors, K)
+    C, buckets = kmeans_lsh_init(X, K, planes, None, return_buckets=True)
+    assert np.array_equal(buckets.astype(np.int64), buckets_ref) and np.array_equal(C, C_ref)
+    Cd, bd = kmeans_lsh_init(torch.from_numpy(X).cuda(), K, torch.from_numpy(planes).cuda(), None, return_buckets=True)
+    assert np.array_equal(Cd.cpu().numpy(), C_ref) and np.array_equal(bd.cpu().numpy().astype(np.int64), buckets_ref)
+    # ties in the projections (an integer grid): the rank rule decides alike on both sides
+    G = np.random.default_rng(n).integers(0, 3, size=(min(n, 2000), 4)).astype(np.float32)
+    pl = np.random.default_rng(b).integers(-1, 2, size=(3, 4)).astype(np.float32)
+    Cg_ref, bg_ref = km.lsh_init(G, pl, km.lsh_median_anchors(G, pl), min(8, len(G)))
+    Cg, bg = kmeans_lsh_init(G, min(8, len(G)), pl, None, return_buckets=True)
+    assert np.array_equal(bg.astype(np.int64), bg_ref) and np.array_equal(Cg, Cg_ref)
