@@ -246,6 +246,9 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
     KnnSets P{};
     P.XQ = dX; P.XC = dC; P.qmembers = nullptr; P.cmembers = nullptr; P.qstart = qstart; P.cstart = cstart;
     P.cnorm = cnorm; P.centre = centre; P.group_of_q = nullptr; P.max_norm_bits = max_norm; P.n_q = n; P.n_c = K; P.d = d; P.same_set = 0;
+    float* key2 = nullptr;   // the two smallest filter keys of every point: a clear winner skips the float64 refinement
+    KTRY(buf.alloc(&key2, (size_t)2 * n));
+    P.key2 = key2;
     int32_t it = 0;
     bool have_labels = false;
     std::vector<uint32_t> hcounts(K), hstart((size_t)K + 1, 0);

@@ -58,7 +58,14 @@ struct KnnSets {
     int32_t d;
     int32_t same_set;            // 1: queries and candidates are the same rows: a row is not its own neighbour
     const int32_t* self_row;     // or, per query row, the candidate row that is the query itself (nullptr: see same_set)
+    float* key2;                 // nullptr, or [2 n_q]: the filter leaves every query's two smallest float32 keys here and the
+                                 // refinement of a k = 1 search reads them (a clear winner needs no float64 distance)
 };
+
+// bound on |float32 key - exact key| of the filter for rows of d values whose centred squared norms are at most M
+__device__ __forceinline__ double knn_filter_eps(int32_t d, double M) {
+    return (4.0 * (double)(d + 4) + 8.0) * 5.9604644775390625e-08 * M * 1.01 + 1e-12 * M;
+}
 __device__ __forceinline__ int32_t knn_row(const int32_t* members, uint32_t pos) { return members ? members[pos] : (int32_t)pos; }
 
 // Distances do not change when a cluster is moved as a whole, and the float32 error of the filter grows with |x|^2:
@@ -470,6 +477,10 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
             // tau: the K'-th key of the union (inf if there is none) and the lists' last keys
             if (lane < kMerge && r0 == list_len - 1) tau_out[p] = fminf(k0, jq_thr);
             if (lane + 64 < kMerge && r1 == list_len - 1) tau_out[p] = fminf(k1, jq_thr);
+            if (P.key2) {
+                if (lane < kMerge && r0 < 2) P.key2[2 * p + r0] = k0;
+                if (lane + 64 < kMerge && r1 < 2) P.key2[2 * p + r1] = k1;
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -545,6 +556,18 @@ __global__ void __launch_bounds__(256) k_knn_refine(const KnnSets P, const int32
     const float* xq = P.XQ + (int64_t)q * d;
     int32_t c = lane < list_len ? cand[p * list_len + lane] : -1;
     if (c >= P.n_c) c = -1;   // never an address outside the candidate rows, whatever the list holds
+    if (k == 1 && P.key2) {
+        // One neighbour wanted: if the smallest float32 key lies below the second by more than twice the filter's error
+        // bound, its candidate is the nearest in exact arithmetic too (every other candidate's key, kept or turned away,
+        // is at least the second key), and no float64 distance is needed.
+        const int32_t g1 = P.group_of_q ? P.group_of_q[q] : 0;
+        const double eps1 = knn_filter_eps(d, (double)__uint_as_float(P.max_norm_bits[g1]));
+        const double key0 = (double)P.key2[2 * p], key1 = (double)P.key2[2 * p + 1];
+        if (key1 - key0 > 2.0 * eps1) {   // false for NaN (no candidate at all: inf - inf)
+            if (lane == 0) out[(int64_t)q] = c;   // list slot 0 holds the smallest key's candidate
+            return;
+        }
+    }
     const double D = c >= 0 ? exact_distance(xq, P.XC + (int64_t)c * d, d) : __builtin_inf();
     int rank = 0, cnt = 0;
     for (int o = 0; o < list_len; ++o) {
@@ -567,8 +590,7 @@ __global__ void __launch_bounds__(256) k_knn_refine(const KnnSets P, const int32
             const double v = (double)(xq[x] - ctr[x]);
             qn = fma(v, v, qn);
         }
-        const double M = (double)__uint_as_float(P.max_norm_bits[g]);
-        const double eps = (4.0 * (double)(d + 4) + 8.0) * 5.9604644775390625e-08 * M * 1.01 + 1e-12 * M;
+        const double eps = knn_filter_eps(d, (double)__uint_as_float(P.max_norm_bits[g]));
         if (!(D - qn + eps < (double)t)) flagged[atomicAdd(n_flagged, 1u)] = q;
     }
 }
