@@ -70,29 +70,36 @@ __global__ void __launch_bounds__(64) k_pca_cov(const float* __restrict__ X, int
 #pragma unroll
         for (int y = 0; y < 4; ++y) acc[x][y] = doublex4{0.0, 0.0, 0.0, 0.0};
     const int64_t r0 = (int64_t)slab * slab_rows, r1 = min(n, r0 + slab_rows);
-    float fa[4], fb[4];
-    auto fetch = [&](int64_t r) {   // this lane's row of the step that starts at row r; 0 stands for "no such element"
+    // loads run kAhead steps (of four rows) ahead of the multiplications: a step is 16 matrix instructions, about half a
+    // microsecond, and the rows come from HBM
+    constexpr int kAhead = 4;
+    float fa[kAhead][4], fb[kAhead][4];
+    auto fetch = [&](int slot, int64_t r) {   // this lane's row of the step that starts at row r; NaN stands for "no such element"
         const int64_t row = r + lr;
         const bool rv = row < r1;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            fa[u] = (rv && cola[u] < d) ? X[row * d + cola[u]] : __builtin_nanf("");
-            fb[u] = (rv && colb[u] < d) ? X[row * d + colb[u]] : __builtin_nanf("");
+            fa[slot][u] = (rv && cola[u] < d) ? X[row * d + cola[u]] : __builtin_nanf("");
+            fb[slot][u] = (rv && colb[u] < d) ? X[row * d + colb[u]] : __builtin_nanf("");
         }
     };
-    if (r0 < r1) fetch(r0);
-    for (int64_t r = r0; r < r1; r += 4) {
-        double xa[4], xb[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {   // NaN marks an absent element: it contributes nothing
-            xa[u] = fa[u] == fa[u] ? (double)fa[u] - ma[u] : 0.0;
-            xb[u] = fb[u] == fb[u] ? (double)fb[u] - mb[u] : 0.0;
+    for (int s = 0; s < kAhead; ++s) fetch(s, r0 + 4 * s);
+    for (int64_t r = r0; r < r1; r += 4 * kAhead) {
+#pragma unroll
+        for (int s = 0; s < kAhead; ++s) {   // slot s holds the step at row r + 4 s
+            double xa[4], xb[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {   // an absent element contributes nothing
+                xa[u] = fa[s][u] == fa[s][u] ? (double)fa[s][u] - ma[u] : 0.0;
+                xb[u] = fb[s][u] == fb[s][u] ? (double)fb[s][u] - mb[u] : 0.0;
+            }
+            fetch(s, r + 4 * (s + kAhead));   // beyond the slab: all NaN, no memory access
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+#pragma unroll
+                for (int y = 0; y < 4; ++y) acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64(xa[x], xb[y], acc[x][y], 0, 0, 0);
         }
-        if (r + 4 < r1) fetch(r + 4);   // the next step's loads fly during this step's multiplications
-#pragma unroll
-        for (int x = 0; x < 4; ++x)
-#pragma unroll
-            for (int y = 0; y < 4; ++y) acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64(xa[x], xb[y], acc[x][y], 0, 0, 0);
     }
     double* out = partial + (int64_t)blockIdx.x * (kColBlock * kColBlock);
 #pragma unroll
