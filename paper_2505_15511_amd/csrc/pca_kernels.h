@@ -385,20 +385,30 @@ __global__ void __launch_bounds__(256) k_pca_project(const float* __restrict__ X
     const int lane = threadIdx.x & 63;
     const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const double f0 = factor[0], f1 = factor[1];
-    for (int x = 0; x < kProjectRows; ++x) {
-        const int64_t row = w * kProjectRows + x;
-        if (row >= n) return;
-        double s0 = 0.0, s1 = 0.0;
+    for (int x = 0; x < kProjectRows; x += 4) {   // four rows at a time: their loads are in flight together
+        const int64_t row0 = w * kProjectRows + x;
+        if (row0 >= n) return;
+        double s0[4] = {0.0, 0.0, 0.0, 0.0}, s1[4] = {0.0, 0.0, 0.0, 0.0};
         for (int col = lane; col < d; col += 64) {
-            const double c = (double)X[row * d + col] - mean[col];
-            s0 = fma(c, Q[col * kRitz], s0);
-            s1 = fma(c, Q[col * kRitz + 1], s1);
+            const double m = mean[col], q0 = Q[col * kRitz], q1 = Q[col * kRitz + 1];
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = row0 + u < n ? X[(row0 + u) * d + col] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const double c = (double)v[u] - m;
+                s0[u] = fma(c, q0, s0[u]);
+                s1[u] = fma(c, q1, s1[u]);
+            }
         }
-        for (int o = 32; o > 0; o >>= 1) {
-            s0 += __shfl_xor(s0, o, 64);
-            s1 += __shfl_xor(s1, o, 64);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            for (int o = 32; o > 0; o >>= 1) {
+                s0[u] += __shfl_xor(s0[u], o, 64);
+                s1[u] += __shfl_xor(s1[u], o, 64);
+            }
+            if (lane == 0 && row0 + u < n) theta[row0 + u] = make_float2((float)(s0[u] * f0), (float)(s1[u] * f1));
         }
-        if (lane == 0) theta[row] = make_float2((float)(s0 * f0), (float)(s1 * f1));
     }
 }
 
