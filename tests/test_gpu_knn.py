@@ -19,7 +19,8 @@ def _gmm(n, d, comps, seed, interleave=True):
 
 
 @pytest.mark.parametrize("n,d,comps,k", [(3000, 50, 10, 15), (6000, 128, 7, 15), (2500, 7, 3, 32), (1500, 300, 4, 10), (900, 768, 2, 5),
-                                         (4000, 33, 1, 1)])
+                                         (4000, 33, 1, 1), (1301, 400, 5, 32), (1103, 700, 3, 20), (977, 330, 3, 15), (1999, 512, 2, 8),
+                                         (1500, 260, 1, 15)])
 def test_neighbours_match_the_oracle_bit_for_bit(n, d, comps, k):
     note(f"knn n={n} d={d} clusters={comps} k={k}")
     X, c = _gmm(n, d, comps, 100 + d)
