@@ -580,16 +580,21 @@ __global__ void __launch_bounds__(256) k_knn_refine(const KnnSets P, const int32
     }
     if (c >= 0 && rank < k) out[(int64_t)q * k + rank] = c;
     if (lane >= cnt && lane < k) out[(int64_t)q * k + lane] = -1;   // fewer than k candidates in the group
-    // certification by the lane that holds the k-th neighbour (only needed when something was left out)
+    // certification by the lane that holds the k-th neighbour (only needed when something was left out).  |q'|^2 of the
+    // centred query as the filter saw it: the group's lanes add a strided share each (the order is free: the value only
+    // enters an inequality with slack).
     const float t = tau[p];
-    if (c >= 0 && rank == min(k, cnt) - 1 && t < __builtin_inff() && cnt >= k) {
-        const int32_t g = P.group_of_q ? P.group_of_q[q] : 0;
+    const int32_t g = P.group_of_q ? P.group_of_q[q] : 0;
+    double qn = 0.0;
+    if (t < __builtin_inff() && cnt >= k) {   // the same for every lane of the group
         const float* ctr = P.centre + (int64_t)g * d;
-        double qn = 0.0;   // |q'|^2 of the centred query as the filter saw it
-        for (int x = 0; x < d; ++x) {
+        for (int x = lane; x < d; x += G) {
             const double v = (double)(xq[x] - ctr[x]);
             qn = fma(v, v, qn);
         }
+        for (int w = G / 2; w > 0; w >>= 1) qn += __shfl_xor(qn, w, G);
+    }
+    if (c >= 0 && rank == min(k, cnt) - 1 && t < __builtin_inff() && cnt >= k) {
         const double eps = knn_filter_eps(d, (double)__uint_as_float(P.max_norm_bits[g]));
         if (!(D - qn + eps < (double)t)) flagged[atomicAdd(n_flagged, 1u)] = q;
     }
