@@ -155,7 +155,7 @@ extern "C" int nomad_knn_in_clusters(const float* X, int64_t n, int32_t d, const
     KTRY(hipMemcpyAsync(slabs, hslabs.data(), sizeof(KnnBlock) * hslabs.size(), hipMemcpyHostToDevice, st));
     KTRY(hipMemcpyAsync(start, hstart.data(), sizeof(uint32_t) * ((size_t)R + 1), hipMemcpyHostToDevice, st));
     KTRY(hipMemcpyAsync(blocks, hblocks.data(), sizeof(KnnBlock) * hblocks.size(), hipMemcpyHostToDevice, st));
-    hipLaunchKernelGGL(k_knn_group, dim3(blocks_of(n, 256)), dim3(256), 0, st, dC, n, start, cursor, members);
+    hipLaunchKernelGGL(k_knn_group, dim3(blocks_of(n, kGroupSpan)), dim3(256), 0, st, dC, n, R, start, cursor, members);
     hipLaunchKernelGGL(k_knn_centroid_sums, dim3((uint32_t)hslabs.size()), dim3(256), 0, st, dX, d, members, start, slabs, centre);
     hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of((int64_t)R * d, 256)), dim3(256), 0, st, centre, start, R, d);
     hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, kNormRows)), dim3(256), 0, st, dX, n, d, dC, centre, norm, max_norm);

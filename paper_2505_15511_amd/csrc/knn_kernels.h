@@ -169,13 +169,39 @@ __global__ void __launch_bounds__(256) k_knn_count(const int32_t* __restrict__ c
     }
 }
 
-// members grouped by cluster (any order inside a cluster: ties are broken by the point index, not by position)
-__global__ void __launch_bounds__(256) k_knn_group(const int32_t* __restrict__ cluster_of, int64_t n, const uint32_t* __restrict__ start,
+// members grouped by cluster (any order inside a cluster: ties are broken by the point index, not by position).  A
+// workgroup takes kGroupSpan points: ranks inside the workgroup from an LDS counter per cluster, then one global
+// reservation per cluster it met (clusters beyond kCountLds: one global atomic per point).
+constexpr int kGroupSpan = 4096;
+__global__ void __launch_bounds__(256) k_knn_group(const int32_t* __restrict__ cluster_of, int64_t n, int32_t R, const uint32_t* __restrict__ start,
                                                    uint32_t* __restrict__ cursor, int32_t* __restrict__ members) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int32_t r = cluster_of[i];
-    members[start[r] + atomicAdd(&cursor[r], 1u)] = (int32_t)i;
+    __shared__ uint32_t h[kCountLds];     // count, then global base, of every cluster inside this workgroup's span
+    const int64_t i0 = (int64_t)blockIdx.x * kGroupSpan;
+    constexpr int kPer = kGroupSpan / 256;
+    if (R > kCountLds) {
+        for (int u = 0; u < kPer; ++u) {
+            const int64_t i = i0 + u * 256 + threadIdx.x;
+            if (i < n) { const int32_t r = cluster_of[i]; members[start[r] + atomicAdd(&cursor[r], 1u)] = (int32_t)i; }
+        }
+        return;
+    }
+    for (int r = threadIdx.x; r < R; r += 256) h[r] = 0u;
+    __syncthreads();
+    int32_t cl[kPer];
+    uint32_t rk[kPer];
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+        const int64_t i = i0 + u * 256 + threadIdx.x;
+        cl[u] = i < n ? cluster_of[i] : -1;
+        rk[u] = cl[u] >= 0 ? atomicAdd(&h[cl[u]], 1u) : 0u;
+    }
+    __syncthreads();
+    for (int r = threadIdx.x; r < R; r += 256)
+        if (h[r]) h[r] = start[r] + atomicAdd(&cursor[r], h[r]);
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kPer; ++u)
+        if (cl[u] >= 0) members[h[cl[u]] + rk[u]] = (int32_t)(i0 + u * 256 + threadIdx.x);
 }
 
 // ---------------------------------------------------------------- stage 1: the float32 filter on the matrix cores
