@@ -80,7 +80,18 @@ __global__ void __launch_bounds__(256) k_knn_centroid_sums(const float* __restri
     const uint32_t r0 = c0 + (uint32_t)sl.q0, r1 = min(c1, r0 + (uint32_t)kCentroidRows);
     for (int col = threadIdx.x; col < d; col += 256) {
         float s = 0.f;
-        for (uint32_t r = r0; r < r1; ++r) s += X[(int64_t)knn_row(members, r) * d + col];
+        uint32_t r = r0;
+        for (; r + 16 <= r1; r += 16) {   // sixteen rows in flight
+            int32_t row[16];
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) row[u] = knn_row(members, r + u);
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = X[(int64_t)row[u] * d + col];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) s += v[u];
+        }
+        for (; r < r1; ++r) s += X[(int64_t)knn_row(members, r) * d + col];
         atomicAdd(&centre[(int64_t)sl.cluster * d + col], s);
     }
 }
