@@ -25,7 +25,15 @@ __global__ void __launch_bounds__(256) k_pca_colsum(const float* __restrict__ X,
     const int64_t r0 = (int64_t)blockIdx.x * kMeanRows, r1 = min(n, r0 + kMeanRows);
     for (int col = threadIdx.x; col < d; col += 256) {
         double s = 0.0;
-        for (int64_t r = r0; r < r1; ++r) s += (double)X[r * d + col];
+        int64_t r = r0;
+        for (; r + 16 <= r1; r += 16) {   // sixteen rows in flight; added in row order
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = X[(r + u) * d + col];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) s += (double)v[u];
+        }
+        for (; r < r1; ++r) s += (double)X[r * d + col];
         partial[(int64_t)blockIdx.x * d + col] = s;
     }
 }
@@ -35,7 +43,15 @@ __global__ void __launch_bounds__(256) k_pca_mean(const double* __restrict__ par
     const int col = blockIdx.x * blockDim.x + threadIdx.x;
     if (col >= d) return;
     double s = 0.0;
-    for (int b = 0; b < blocks; ++b) s += partial[(int64_t)b * d + col];
+    int b = 0;
+    for (; b + 16 <= blocks; b += 16) {   // sixteen partial sums in flight; added in block order
+        double v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = partial[(int64_t)(b + u) * d + col];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) s += v[u];
+    }
+    for (; b < blocks; ++b) s += partial[(int64_t)b * d + col];
     mean[col] = s / (double)n;
 }
 
@@ -121,7 +137,16 @@ __global__ void __launch_bounds__(256) k_pca_cov_reduce(const double* __restrict
     const int gi = a * kColBlock + e / kColBlock, gj = b * kColBlock + e % kColBlock;
     if (gi >= d || gj >= d) return;
     double s = 0.0;
-    for (int sl = 0; sl < slabs; ++sl) s += partial[((int64_t)pair * slabs + sl) * (kColBlock * kColBlock) + e];
+    const double* src = partial + (int64_t)pair * slabs * (kColBlock * kColBlock) + e;
+    int sl = 0;
+    for (; sl + 16 <= slabs; sl += 16) {   // sixteen partial tiles in flight; added in slab order
+        double v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = src[(int64_t)(sl + u) * (kColBlock * kColBlock)];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) s += v[u];
+    }
+    for (; sl < slabs; ++sl) s += src[(int64_t)sl * (kColBlock * kColBlock)];
     s /= (double)n;
     C[(int64_t)gi * d + gj] = s;
     if (a != b) C[(int64_t)gj * d + gi] = s;
