@@ -400,15 +400,18 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
             if (!__any(xk < lk[L - 1])) break;
 #pragma unroll
             for (int v = 0; v < 4; ++v) ck[v] = sel == v ? __builtin_inff() : ck[v];
+            // From the last slot down: a slot takes its left neighbour if the new key goes before that one, the new key if
+            // it goes exactly here (L independent comparisons, no value carried along; an infinite key changes nothing).
 #pragma unroll
-            for (int x = 0; x < L; ++x) {   // an infinite key changes nothing
-                const bool take = xk < lk[x];
-                const float ok = lk[x];
-                const int32_t op = lp[x];
-                lk[x] = take ? xk : ok;
-                lp[x] = take ? xp : op;
-                xk = take ? ok : xk;
-                xp = take ? op : xp;
+            for (int x = L - 1; x >= 1; --x) {
+                const bool left = xk < lk[x - 1], here = xk < lk[x];
+                lk[x] = left ? lk[x - 1] : (here ? xk : lk[x]);
+                lp[x] = left ? lp[x - 1] : (here ? xp : lp[x]);
+            }
+            {
+                const bool here = xk < lk[0];
+                lk[0] = here ? xk : lk[0];
+                lp[0] = here ? xp : lp[0];
             }
         }
     };
