@@ -737,15 +737,21 @@ __global__ void __launch_bounds__(256) k_kmeans_update(const float* __restrict__
     if (r1 == r0) return;
     double sum = 0.0;
     uint32_t r = r0;
-    for (; r + 64 <= r1; r += 64) {                     // 64 rows in flight (two memory round trips per batch); the
-        int32_t id[64];                                 // additions keep their order
-        float v[64];
+    if (r + 64 <= r1) {   // batches of 64 rows in flight, the additions in order; the next batch's ids travel with this batch's rows
+        int32_t idn[64];
 #pragma unroll
-        for (int u = 0; u < 64; ++u) id[u] = ids[r + u];
+        for (int u = 0; u < 64; ++u) idn[u] = ids[r + u];
+        for (; r + 64 <= r1; r += 64) {
+            float v[64];
 #pragma unroll
-        for (int u = 0; u < 64; ++u) v[u] = X[(int64_t)id[u] * d + col];
+            for (int u = 0; u < 64; ++u) v[u] = X[(int64_t)idn[u] * d + col];
+            if (r + 128 <= r1) {
 #pragma unroll
-        for (int u = 0; u < 64; ++u) sum = __dadd_rn(sum, (double)v[u]);
+                for (int u = 0; u < 64; ++u) idn[u] = ids[r + 64 + u];
+            }
+#pragma unroll
+            for (int u = 0; u < 64; ++u) sum = __dadd_rn(sum, (double)v[u]);
+        }
     }
     for (; r + 8 <= r1; r += 8) {
         int32_t id[8];
