@@ -658,12 +658,15 @@ __global__ void __launch_bounds__(256) k_knn_exact(const KnnSets P, const int32_
     int32_t lP[KL];
 #pragma unroll
     for (int x = 0; x < KL; ++x) { lD[x] = __builtin_inf(); lP[x] = -1; }
+    double wD = __builtin_inf();   // the pair in slot k - 1 (point -1 while the list is not full)
+    int32_t wP = -1;
     for (uint32_t pos = c0 + threadIdx.x; pos < c1; pos += 256) {
         const int32_t c = knn_row(P.cmembers, pos);
         if (c == self) continue;
         double xD = exact_distance(xq, P.XC + (int64_t)c * d, d);
         int32_t xP = c;
-        // the list's last used slot is slot k - 1: anything not before it cannot be among this thread's k smallest
+        // slot k - 1 is the list's last used slot: what does not come before it cannot be among this thread's k smallest
+        if (!(wP < 0 || xD < wD || (xD == wD && xP < wP))) continue;
 #pragma unroll
         for (int x = 0; x < KL; ++x) {
             if (x < k) {
@@ -676,6 +679,9 @@ __global__ void __launch_bounds__(256) k_knn_exact(const KnnSets P, const int32_
                 xP = take ? oP : xP;
             }
         }
+#pragma unroll
+        for (int x = 0; x < KL; ++x)
+            if (x == k - 1) { wD = lD[x]; wP = lP[x]; }
     }
     double lastD = -1.0;
     int32_t lastP = -1;
