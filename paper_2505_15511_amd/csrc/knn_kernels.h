@@ -35,7 +35,7 @@ __host__ __device__ constexpr int knn_filter_buffers(int d4) { return d4 > 64 ? 
 
 // wavefronts per SIMD the filter is compiled for: narrow rows and short lists fit two workgroups per compute unit (128
 // registers per lane), and the second workgroup is what hides the first one's tile barriers
-__host__ __device__ constexpr int knn_filter_waves_per_simd(int d4, int L) { return d4 <= 32 && L <= 12 ? 4 : 2; }
+__host__ __device__ constexpr int knn_filter_waves_per_simd(int d4, int L) { return d4 <= 32 && L <= 12 ? 4 : 2; }   // (also the L = 4 lists of a one-neighbour search)
 
 struct KnnBlock { int32_t cluster; int32_t q0; };   // queries q0 .. of group `cluster`: one workgroup's share
 
@@ -533,7 +533,7 @@ __host__ __device__ inline size_t knn_filter_lds_bytes(int d4, int L) {
            (knn_filter_split(d4) == 2 ? (size_t)knn_filter_waves(d4) * 64 * 16 : 0) + (d4 >= 192 ? (size_t)16 * d4 : 0);
 }
 // entries per lane's list for K' = list_len candidates per query: half of K', so that the four lists of a query hold 2 K'
-__host__ inline int knn_filter_list_class(int list_len) { return list_len <= 16 ? 8 : list_len <= 24 ? 12 : 20; }
+__host__ inline int knn_filter_list_class(int list_len) { return list_len <= 9 ? 4 : list_len <= 16 ? 8 : list_len <= 24 ? 12 : 20; }
 
 // the oracle's distance: difference, product and running sum each rounded once, in float64, t = 0..d-1 in order
 __device__ __forceinline__ double exact_distance(const float* __restrict__ x, const float* __restrict__ y, int32_t d) {
