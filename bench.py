@@ -211,7 +211,10 @@ def pipeline_run(args, torch, workloads):
     pipeline.project(X[:20000].contiguous(), 16, n_epochs=2)          # warm-up: library load, torch's sort and unique
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    theta, info = pipeline.project(X, args.index_clusters, k=args.index_k, n_epochs=args.steps, seed=1, return_info=True)
+    opts = {}
+    if args.pool:                                                    # the opt-in pooled sampler for the epochs
+        opts["pool_size"], opts["pool_block"] = (int(x) for x in args.pool.split(","))
+    theta, info = pipeline.project(X, args.index_clusters, k=args.index_k, n_epochs=args.steps, seed=1, return_info=True, **opts)
     torch.cuda.synchronize()
     total = time.perf_counter() - t0
     t1 = time.perf_counter()
@@ -223,7 +226,8 @@ def pipeline_run(args, torch, workloads):
         "warmup": 0, "ms_per_step": 1e3 * info["seconds"]["epochs"] / max(1, args.steps), "higher_is_better": True, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"Gaussian mixture n={n}, d={d}, {info['n_clusters']} clusters, k={args.index_k}, {args.steps} epochs, "
-                               f"E={info['edges']} directed edges with inverse-rank weights"},
+                               f"E={info['edges']} directed edges with inverse-rank weights"
+                               + (f", pooled sampler {args.pool}" if args.pool else "")},
         "seconds": {**{k: round(v, 4) for k, v in info["seconds"].items()}, "total": round(total, 4), "evaluate": round(t_eval, 4)},
         "kmeans_iterations": info["kmeans_iterations"],
         "preservation_at_k": {"pca_start": start_preservation, "final": preservation},
