@@ -54,3 +54,26 @@ def test_small_clusters_leave_ragged_rows():
     assert w is None and row_ptr.tolist() == [0, 2, 3, 4] and col.tolist() == [1, 2, 0, 0]
     theta = pipeline.project(X.cuda(), n_clusters=20, k=5, n_epochs=20, seed=1)
     assert torch.isfinite(theta).all()
+
+
+def test_swiss_roll_local_structure_is_gained_and_global_structure_kept():
+    """A rolled-up sheet in 20 dimensions: PCA cannot unroll it (low neighbourhood preservation, good triplet accuracy);
+    the optimisation from the PCA start gains the neighbourhoods and keeps most of the global order, while a random
+    start gains neighbourhoods only (Section 3.5's reason for the PCA start)."""
+    rng = np.random.default_rng(0)
+    n = 30000
+    t = 1.5 * np.pi * (1 + 2 * rng.uniform(size=n))
+    F = np.stack([t * np.cos(t), 21 * rng.uniform(size=n), t * np.sin(t)], axis=1)
+    Q, _ = np.linalg.qr(rng.normal(size=(20, 20)))
+    X = (np.concatenate([F, np.zeros((n, 17))], axis=1) @ Q.T + 0.05 * rng.normal(size=(n, 20))).astype(np.float32)
+    X = torch.from_numpy(X).cuda()
+    theta, info = pipeline.project(X, n_clusters=16, k=15, n_epochs=200, seed=1, return_info=True)
+    np_start, ta_start = pipeline.evaluate(X, info["theta0"], n_queries=3000, n_triplets=200000, seed=1)
+    np_end, ta_end = pipeline.evaluate(X, theta, n_queries=3000, n_triplets=200000, seed=1)
+    rnd = pipeline.project(X, n_clusters=16, k=15, n_epochs=200, seed=1, init="random")
+    np_rnd, ta_rnd = pipeline.evaluate(X, rnd, n_queries=3000, n_triplets=200000, seed=1)
+    note(f"  swiss roll: NP@15 {np_start:.3f} -> {np_end:.3f} (random start {np_rnd:.3f}), "
+         f"triplets {ta_start:.3f} -> {ta_end:.3f} (random start {ta_rnd:.3f})")
+    assert np_start < 0.25 and np_end > 0.45 and np_end > 3 * np_start
+    assert ta_end > 0.7 and ta_end > ta_rnd + 0.15
+    assert np_rnd > 0.2
