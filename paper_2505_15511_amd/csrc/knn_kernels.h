@@ -254,9 +254,9 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
     float* tile = lds;                                        // [kBuffers][kTile][kRow]
     float* tnorm = tile + kBuffers * kTileWords;              // [2][kTile]
     int32_t* tile_pt = (int32_t*)(tnorm + 2 * kTile);         // [2][kTile] point of each staged candidate (-1: none)
-    float* mkey = (float*)(tile_pt + 2 * kTile);              // [waves][kMerge] merge scratch of one query per wavefront
-    int32_t* mpt = (int32_t*)(mkey + knn_filter_waves(D4) * kMerge);   // [waves][kMerge]
-    floatx4* xch = (floatx4*)(mpt + knn_filter_waves(D4) * kMerge);    // [waves][64] partial tiles (split rows only; 16-byte aligned)
+    float* mkey = (float*)(tile_pt + 2 * kTile);              // [waves][4][kMerge] merge scratch of four queries per wavefront
+    int32_t* mpt = (int32_t*)(mkey + knn_filter_waves(D4) * 4 * kMerge);   // [waves][4][kMerge]
+    floatx4* xch = (floatx4*)(mpt + knn_filter_waves(D4) * 4 * kMerge);    // [waves][64] partial tiles (split rows only; 16-byte aligned)
     constexpr int kSplit = knn_filter_split(D4);                       // wavefronts that share 16 queries
     constexpr int KH = D4 / kSplit;                                    // 4-column steps per wavefront
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -467,59 +467,64 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
         }
     }
 
-    // ---- merge the four lists of every query, one query of the wavefront at a time (of two wavefronts that share their
-    // queries both hold the same lists: one of them reports)
+    // ---- merge the four lists of every query, four queries of the wavefront at a time: sixteen lanes per query, each
+    // with up to kPerLane of the query's 4 L entries, which it ranks by counting the entries that precede them in
+    // (key, point).  (Of two wavefronts that share their queries both hold the same lists: one of them reports.)
     if (half != 0) return;
-    float* mk = mkey + wave * kMerge;
-    int32_t* mp = mpt + wave * kMerge;
+    constexpr int kPerLane = (kMerge + 15) / 16;
+    float* mk = mkey + wave * 4 * kMerge;        // [4 queries][kMerge]
+    int32_t* mp = mpt + wave * 4 * kMerge;
     // the smallest of the four lists' last keys: what this query's lanes may have turned away
     float thr = lk[L - 1];
     thr = fminf(thr, __shfl_xor(thr, 16, 64));
     thr = fminf(thr, __shfl_xor(thr, 32, 64));
-    for (int j = 0; j < kWaveQueries; ++j) {
-        if ((lane & 15) == j) {
+    for (int jb = 0; jb < kWaveQueries; jb += 4) {
+        if (((lane & 15) >> 2) == (jb >> 2)) {   // the lanes of queries jb .. jb + 3 lay their lists out
+            float* dk = mk + (lane & 3) * kMerge + (lane >> 4) * L;
+            int32_t* dp = mp + (lane & 3) * kMerge + (lane >> 4) * L;
 #pragma unroll
-            for (int x = 0; x < L; ++x) { mk[(lane >> 4) * L + x] = lk[x]; mp[(lane >> 4) * L + x] = lp[x]; }
+            for (int x = 0; x < L; ++x) { dk[x] = lk[x]; dp[x] = lp[x]; }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // every lane takes up to two of the 4 L entries and counts those that precede them in (key, point)
-        float k0 = __builtin_inff(), k1 = __builtin_inff();
-        int32_t p0 = -1, p1 = -1;
-        if (lane < kMerge) { k0 = mk[lane]; p0 = mp[lane]; }
-        if (lane + 64 < kMerge) { k1 = mk[lane + 64]; p1 = mp[lane + 64]; }
+        const int g = lane >> 4, sub = lane & 15;            // this lane now works for query jb + g
+        const float* qk = mk + g * kMerge;
+        const int32_t* qp = mp + g * kMerge;
         // an empty slot (point -1) sorts after every real entry; empty slots get distinct stand-in points so that the
         // ranks stay a permutation and every one of the K' output slots is written
-        if (p0 < 0) p0 = kEmptyPoint + lane;
-        if (p1 < 0) p1 = kEmptyPoint + 64 + lane;
-        int r0 = 0, r1 = 0;
-        for (int o = 0; o < (kMerge < 64 ? kMerge : 64); ++o) {
-            const float ko = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(k0), o));
-            const int32_t po = __builtin_amdgcn_readlane(p0, o);
-            r0 += (ko < k0 || (ko == k0 && po < p0)) ? 1 : 0;
-            r1 += (ko < k1 || (ko == k1 && po < p1)) ? 1 : 0;
+        float ek[kPerLane];
+        int32_t ep[kPerLane];
+        int er[kPerLane];
+#pragma unroll
+        for (int u = 0; u < kPerLane; ++u) {
+            const int e = sub + 16 * u;
+            ek[u] = e < kMerge ? qk[e] : __builtin_inff();
+            ep[u] = e < kMerge ? qp[e] : -1;
+            if (ep[u] < 0) ep[u] = kEmptyPoint + e;
+            er[u] = 0;
         }
-        for (int o = 0; o < kMerge - 64; ++o) {
-            const float ko = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(k1), o));
-            const int32_t po = __builtin_amdgcn_readlane(p1, o);
-            r0 += (ko < k0 || (ko == k0 && po < p0)) ? 1 : 0;
-            r1 += (ko < k1 || (ko == k1 && po < p1)) ? 1 : 0;
+#pragma unroll 4
+        for (int o = 0; o < kMerge; ++o) {
+            const float ko = qk[o];
+            int32_t po = qp[o];
+            if (po < 0) po = kEmptyPoint + o;
+#pragma unroll
+            for (int u = 0; u < kPerLane; ++u) er[u] += (ko < ek[u] || (ko == ek[u] && po < ep[u])) ? 1 : 0;
         }
-        // the query's point and position, from the lane that owns it
-        const int32_t jq_pt = __shfl(qpt, j, 64);
-        const int32_t jq_pos = __shfl(qpos, j, 64);
-        const float jq_thr = __shfl(thr, j, 64);
+        // the query's point, position and threshold, from a lane that owns it
+        const int32_t jq_pt = __shfl(qpt, jb + g, 64);
+        const int32_t jq_pos = __shfl(qpos, jb + g, 64);
+        const float jq_thr = __shfl(thr, jb + g, 64);
         if (jq_pt >= 0) {
             const int64_t p = (int64_t)q0g + jq_pos;
-            if (lane < kMerge && r0 < list_len) cand[p * list_len + r0] = p0 >= kEmptyPoint ? -1 : p0;
-            if (lane + 64 < kMerge && r1 < list_len) cand[p * list_len + r1] = p1 >= kEmptyPoint ? -1 : p1;
-            // tau: the K'-th key of the union (inf if there is none) and the lists' last keys
-            if (lane < kMerge && r0 == list_len - 1) tau_out[p] = fminf(k0, jq_thr);
-            if (lane + 64 < kMerge && r1 == list_len - 1) tau_out[p] = fminf(k1, jq_thr);
-            if (P.key2) {
-                if (lane < kMerge && r0 < 2) P.key2[2 * p + r0] = k0;
-                if (lane + 64 < kMerge && r1 < 2) P.key2[2 * p + r1] = k1;
+#pragma unroll
+            for (int u = 0; u < kPerLane; ++u) {
+                if (sub + 16 * u >= kMerge) continue;
+                if (er[u] < list_len) cand[p * list_len + er[u]] = ep[u] >= kEmptyPoint ? -1 : ep[u];
+                // tau: the K'-th key of the union (inf if there is none) and the lists' last keys
+                if (er[u] == list_len - 1) tau_out[p] = fminf(ek[u], jq_thr);
+                if (P.key2 && er[u] < 2) P.key2[2 * p + er[u]] = ek[u];
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -529,7 +534,7 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
 }
 
 __host__ __device__ inline size_t knn_filter_lds_bytes(int d4, int L) {
-    return ((size_t)knn_filter_buffers(d4) * kTile * (4 * d4 + 2) + 4 * kTile + (size_t)2 * knn_filter_waves(d4) * 4 * L) * 4 +
+    return ((size_t)knn_filter_buffers(d4) * kTile * (4 * d4 + 2) + 4 * kTile + (size_t)2 * knn_filter_waves(d4) * 16 * L) * 4 +
            (knn_filter_split(d4) == 2 ? (size_t)knn_filter_waves(d4) * 64 * 16 : 0) + (d4 >= 192 ? (size_t)16 * d4 : 0);
 }
 // entries per lane's list for K' = list_len candidates per query: half of K', so that the four lists of a query hold 2 K'
