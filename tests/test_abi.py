@@ -111,6 +111,20 @@ def test_stand_alone_entry_points_check_arguments_before_any_device_work(lib):
     assert lib.nomad_pca_init(px, 8, 4, 0.0, px, st, H, -1, None) == -1
 
 
+def test_header_is_plain_c(tmp_path):
+    import os
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "nomad.h"\nint main(void) { return sizeof(nomad_config) == 88 ? 0 : 1; }\n')
+    exe = tmp_path / "use_header"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I" + inc, str(src), "-o", str(exe)], check=True)
+    assert subprocess.run([str(exe)]).returncode == 0
+
+
 def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(_build, "LIB_PATH", "/nonexistent/libnomad.so")
