@@ -82,6 +82,46 @@ int nearest_in_groups(hipStream_t st, const KnnSets& P, const KnnBlock* blocks, 
     return NOMAD_OK;
 }
 
+// The M step of Lloyd's iteration: the points sorted by label with a stable radix sort (ascending point order inside a
+// cluster), then float64 sums in that order per (centroid, column); a label without points leaves its centroid as it is.
+struct MeanStep {
+    int64_t n = 0;
+    int32_t K = 0;
+    int end_bit = 1;
+    size_t sort_bytes = 0;
+    uint32_t *counts = nullptr, *lstart = nullptr;
+    int32_t *ids_in = nullptr, *ids = nullptr, *keys = nullptr;
+    int* bad = nullptr;
+    void* sort_tmp = nullptr;
+    std::vector<uint32_t> hcounts, hstart;
+
+    int init(Buffers& buf, hipStream_t st, int64_t n_, int32_t K_) {
+        n = n_; K = K_;
+        hcounts.assign((size_t)K, 0u);
+        hstart.assign((size_t)K + 1, 0u);
+        KTRY(buf.alloc(&counts, (size_t)K)); KTRY(buf.alloc(&lstart, (size_t)K + 1)); KTRY(buf.alloc(&bad, 1));
+        KTRY(buf.alloc(&ids_in, (size_t)n)); KTRY(buf.alloc(&ids, (size_t)n)); KTRY(buf.alloc(&keys, (size_t)n));
+        hipLaunchKernelGGL(k_iota, dim3(blocks_of(n, 256)), dim3(256), 0, st, ids_in, n);
+        while (((int64_t)1 << end_bit) < K) ++end_bit;
+        KTRY(hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const int32_t*)keys, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
+        KTRY(buf.alloc((char**)&sort_tmp, sort_bytes));
+        return NOMAD_OK;
+    }
+    // labels [n] in 0..K-1 (on the device); dC [K * d] in and out
+    int run(hipStream_t st, const float* dX, int32_t d, const int32_t* labels, float* dC) {
+        KTRY(hipMemsetAsync(counts, 0, sizeof(uint32_t) * (size_t)K, st));
+        KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
+        hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, kCountSpan)), dim3(256), 0, st, labels, n, K, counts, bad);
+        KTRY(hipMemcpyAsync(hcounts.data(), counts, sizeof(uint32_t) * (size_t)K, hipMemcpyDeviceToHost, st));
+        KTRY(hipStreamSynchronize(st));
+        for (int32_t j = 0; j < K; ++j) hstart[j + 1] = hstart[j] + hcounts[j];
+        KTRY(hipMemcpyAsync(lstart, hstart.data(), sizeof(uint32_t) * ((size_t)K + 1), hipMemcpyHostToDevice, st));
+        KTRY(hipcub::DeviceRadixSort::SortPairs(sort_tmp, sort_bytes, labels, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
+        hipLaunchKernelGGL(k_kmeans_update, dim3(blocks_of((int64_t)K * d, 256)), dim3(256), 0, st, dX, d, (const int32_t*)ids, (const uint32_t*)lstart, K, dC);
+        return NOMAD_OK;
+    }
+};
+
 }  // namespace
 
 #pragma GCC visibility push(default)
@@ -205,17 +245,15 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
         dX = x; dC = c; dLab = l;
     }
     // work space
-    uint32_t *qstart = nullptr, *cstart = nullptr, *lstart = nullptr, *counts = nullptr, *max_pts = nullptr, *max_norm = nullptr, *n_flagged = nullptr;
-    int32_t *new_lab = nullptr, *cand = nullptr, *flagged = nullptr, *ids_in = nullptr, *ids = nullptr, *keys = nullptr;
+    uint32_t *qstart = nullptr, *cstart = nullptr, *max_pts = nullptr, *max_norm = nullptr, *n_flagged = nullptr;
+    int32_t *new_lab = nullptr, *cand = nullptr, *flagged = nullptr;
     float *cnorm = nullptr, *tau = nullptr, *centre = nullptr, *c_used = nullptr;
     unsigned long long* changed = nullptr;
     double* inertia = nullptr;
-    int* bad = nullptr;
     KnnBlock *blocks = nullptr, *slabs = nullptr;
-    KTRY(buf.alloc(&qstart, 2)); KTRY(buf.alloc(&cstart, 2)); KTRY(buf.alloc(&lstart, (size_t)K + 1)); KTRY(buf.alloc(&counts, (size_t)K));
-    KTRY(buf.alloc(&max_pts, 1)); KTRY(buf.alloc(&max_norm, 1)); KTRY(buf.alloc(&n_flagged, 1)); KTRY(buf.alloc(&bad, 1));
+    KTRY(buf.alloc(&qstart, 2)); KTRY(buf.alloc(&cstart, 2));
+    KTRY(buf.alloc(&max_pts, 1)); KTRY(buf.alloc(&max_norm, 1)); KTRY(buf.alloc(&n_flagged, 1));
     KTRY(buf.alloc(&new_lab, (size_t)n)); KTRY(buf.alloc(&cand, (size_t)n * list_len)); KTRY(buf.alloc(&flagged, (size_t)n));
-    KTRY(buf.alloc(&ids_in, (size_t)n)); KTRY(buf.alloc(&ids, (size_t)n)); KTRY(buf.alloc(&keys, (size_t)n));
     KTRY(buf.alloc(&cnorm, (size_t)K)); KTRY(buf.alloc(&tau, (size_t)n)); KTRY(buf.alloc(&centre, (size_t)d)); KTRY(buf.alloc(&c_used, (size_t)K * d));
     KTRY(buf.alloc(&changed, 1)); KTRY(buf.alloc(&inertia, 1));
     const uint32_t hq[2] = {0u, (uint32_t)n}, hc[2] = {0u, (uint32_t)K};
@@ -235,14 +273,11 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
     hipLaunchKernelGGL(k_knn_centroid_sums, dim3((uint32_t)hslabs.size()), dim3(256), 0, st, dX, d, (const int32_t*)nullptr, qstart, slabs, centre);
     hipLaunchKernelGGL(k_knn_centroid_finish, dim3(blocks_of(d, 256)), dim3(256), 0, st, centre, qstart, 1, d);
     hipLaunchKernelGGL(k_knn_norms, dim3(blocks_of(n, kNormRows)), dim3(256), 0, st, dX, n, d, (const int32_t*)nullptr, centre, (float*)nullptr, max_pts);
-    hipLaunchKernelGGL(k_iota, dim3(blocks_of(n, 256)), dim3(256), 0, st, ids_in, n);
-    // radix sort work space (points sorted by label, stable: ascending inside a cluster)
-    int end_bit = 1;
-    while (((int64_t)1 << end_bit) < K) ++end_bit;
-    size_t sort_bytes = 0;
-    KTRY(hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const int32_t*)dLab, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
-    void* sort_tmp = nullptr;
-    KTRY(buf.alloc((char**)&sort_tmp, sort_bytes));
+    MeanStep m_step;
+    {
+        int rc = m_step.init(buf, st, n, K);
+        if (rc) return rc;
+    }
 
     KnnSets P{};
     P.XQ = dX; P.XC = dC; P.qmembers = nullptr; P.cmembers = nullptr; P.qstart = qstart; P.cstart = cstart;
@@ -252,7 +287,6 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
     P.key2 = key2;
     int32_t it = 0;
     bool have_labels = false;
-    std::vector<uint32_t> hcounts(K), hstart((size_t)K + 1, 0);
     while (it < max_iters) {
         // E step: the nearest centroid of every point, exactly
         KTRY(hipMemcpyAsync(max_norm, max_pts, sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
@@ -274,15 +308,10 @@ extern "C" int nomad_kmeans_lloyd(const float* X, int64_t n, int32_t d, int32_t 
         KTRY(hipMemcpyAsync(dLab, new_lab, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, st));
         have_labels = true;
         // M step
-        KTRY(hipMemsetAsync(counts, 0, sizeof(uint32_t) * (size_t)K, st));
-        KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
-        hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, kCountSpan)), dim3(256), 0, st, (const int32_t*)dLab, n, K, counts, bad);
-        KTRY(hipMemcpyAsync(hcounts.data(), counts, sizeof(uint32_t) * (size_t)K, hipMemcpyDeviceToHost, st));
-        KTRY(hipStreamSynchronize(st));
-        for (int32_t j = 0; j < K; ++j) hstart[j + 1] = hstart[j] + hcounts[j];
-        KTRY(hipMemcpyAsync(lstart, hstart.data(), sizeof(uint32_t) * ((size_t)K + 1), hipMemcpyHostToDevice, st));
-        KTRY(hipcub::DeviceRadixSort::SortPairs(sort_tmp, sort_bytes, (const int32_t*)dLab, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
-        hipLaunchKernelGGL(k_kmeans_update, dim3(blocks_of((int64_t)K * d, 256)), dim3(256), 0, st, dX, d, (const int32_t*)ids, (const uint32_t*)lstart, K, dC);
+        {
+            int rc = m_step.run(st, dX, d, (const int32_t*)dLab, dC);
+            if (rc) return rc;
+        }
     }
     // inertia of the labels against the centroids they were computed from
     double hinertia = 0.0;
@@ -347,31 +376,18 @@ extern "C" int nomad_kmeans_lsh_init(const float* X, int64_t n, int32_t d, int32
         KTRY(buf.alloc(&bk, (size_t)n));
         dB = bk;
     }
-    uint32_t *counts = nullptr, *lstart = nullptr;
-    int32_t *ids_in = nullptr, *ids = nullptr, *keys = nullptr;
-    int* bad = nullptr;
-    KTRY(buf.alloc(&counts, (size_t)K)); KTRY(buf.alloc(&lstart, (size_t)K + 1)); KTRY(buf.alloc(&bad, 1));
-    KTRY(buf.alloc(&ids_in, (size_t)n)); KTRY(buf.alloc(&ids, (size_t)n)); KTRY(buf.alloc(&keys, (size_t)n));
+    MeanStep m_step;
+    {
+        int rc = m_step.init(buf, st, n, K);
+        if (rc) return rc;
+    }
     hipLaunchKernelGGL(k_lsh_buckets, dim3(blocks_of(n, 256)), dim3(256), 0, st, dX, n, d, dP, dA, n_planes, K, dB);
     hipLaunchKernelGGL(k_lsh_fallback, dim3(blocks_of((int64_t)K * d, 256)), dim3(256), 0, st, dX, n, d, K, dC);
     // bucket means: the M step of Lloyd's iteration on the buckets
-    KTRY(hipMemsetAsync(counts, 0, sizeof(uint32_t) * (size_t)K, st));
-    KTRY(hipMemsetAsync(bad, 0, sizeof(int), st));
-    hipLaunchKernelGGL(k_knn_count, dim3(blocks_of(n, kCountSpan)), dim3(256), 0, st, (const int32_t*)dB, n, K, counts, bad);
-    std::vector<uint32_t> hcounts(K), hstart((size_t)K + 1, 0);
-    KTRY(hipMemcpyAsync(hcounts.data(), counts, sizeof(uint32_t) * (size_t)K, hipMemcpyDeviceToHost, st));
-    KTRY(hipStreamSynchronize(st));
-    for (int32_t j = 0; j < K; ++j) hstart[j + 1] = hstart[j] + hcounts[j];
-    KTRY(hipMemcpyAsync(lstart, hstart.data(), sizeof(uint32_t) * ((size_t)K + 1), hipMemcpyHostToDevice, st));
-    hipLaunchKernelGGL(k_iota, dim3(blocks_of(n, 256)), dim3(256), 0, st, ids_in, n);
-    int end_bit = 1;
-    while (((int64_t)1 << end_bit) < K) ++end_bit;
-    size_t sort_bytes = 0;
-    KTRY(hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const int32_t*)dB, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
-    void* sort_tmp = nullptr;
-    KTRY(buf.alloc((char**)&sort_tmp, sort_bytes));
-    KTRY(hipcub::DeviceRadixSort::SortPairs(sort_tmp, sort_bytes, (const int32_t*)dB, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
-    hipLaunchKernelGGL(k_kmeans_update, dim3(blocks_of((int64_t)K * d, 256)), dim3(256), 0, st, dX, d, (const int32_t*)ids, (const uint32_t*)lstart, K, dC);
+    {
+        int rc = m_step.run(st, dX, d, (const int32_t*)dB, dC);
+        if (rc) return rc;
+    }
     KTRY(hipGetLastError());
     if (mem == NOMAD_HOST) {
         KTRY(hipMemcpyAsync(centroids_out, dC, sizeof(float) * (size_t)K * d, hipMemcpyDeviceToHost, st));
