@@ -32,7 +32,7 @@ template <int D4>
 hipError_t launch_filter_d(hipStream_t st, uint32_t n_blocks, const KnnSets& P, const KnnBlock* blocks, int32_t list_len, int32_t* cand,
                            float* tau) {
     switch (knn_filter_list_class(list_len)) {
-        case 4: return launch_filter_dl<D4, 4>(st, n_blocks, P, blocks, list_len, cand, tau);
+        case 2: return launch_filter_dl<D4, 2>(st, n_blocks, P, blocks, list_len, cand, tau);
         case 8: return launch_filter_dl<D4, 8>(st, n_blocks, P, blocks, list_len, cand, tau);
         case 12: return launch_filter_dl<D4, 12>(st, n_blocks, P, blocks, list_len, cand, tau);
         default: return launch_filter_dl<D4, 20>(st, n_blocks, P, blocks, list_len, cand, tau);

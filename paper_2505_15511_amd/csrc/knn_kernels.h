@@ -383,6 +383,19 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
             ck[v] = tnorm[buf * kTile + i] - 2.f * acc[v];
             if (cp[v] < 0 || cp[v] == self || qpt < 0) ck[v] = __builtin_inff();
         }
+        if (L == 2) {
+            // One neighbour wanted: a lane keeps its best two, and the tile's four candidates go in one after the other
+            // without asking whether any lane has a hit (two comparisons and six selections each).
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const bool lt0 = ck[v] < lk[0], lt1 = ck[v] < lk[1];
+                lk[1] = lt0 ? lk[0] : (lt1 ? ck[v] : lk[1]);
+                lp[1] = lt0 ? lp[0] : (lt1 ? cp[v] : lp[1]);
+                lk[0] = lt0 ? ck[v] : lk[0];
+                lp[0] = lt0 ? cp[v] : lp[0];
+            }
+            return;
+        }
         // Insertion passes run for the whole wavefront, so they are spent on the lane's best remaining candidate: some lane
         // has a hit in most tiles, a lane with two in one tile is rare, and the second pass is skipped when there is none.
 #pragma nounroll   // a real loop: unrolled, every early exit would copy the whole list into the registers of the next tile
@@ -518,6 +531,9 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
         const float jq_thr = __shfl(thr, jb + g, 64);
         if (jq_pt >= 0) {
             const int64_t p = (int64_t)q0g + jq_pos;
+            // fewer entries than K' (the best-two lists of a one-neighbour search): the lists' last keys alone bound what was
+            // turned away; the slots beyond the entries keep their "no candidate" filling
+            if (kMerge < list_len && sub == 0) tau_out[p] = jq_thr;
 #pragma unroll
             for (int u = 0; u < kPerLane; ++u) {
                 if (sub + 16 * u >= kMerge) continue;
@@ -538,7 +554,7 @@ __host__ __device__ inline size_t knn_filter_lds_bytes(int d4, int L) {
            (knn_filter_split(d4) == 2 ? (size_t)knn_filter_waves(d4) * 64 * 16 : 0) + (d4 >= 192 ? (size_t)16 * d4 : 0);
 }
 // entries per lane's list for K' = list_len candidates per query: half of K', so that the four lists of a query hold 2 K'
-__host__ inline int knn_filter_list_class(int list_len) { return list_len <= 9 ? 4 : list_len <= 16 ? 8 : list_len <= 24 ? 12 : 20; }
+__host__ inline int knn_filter_list_class(int list_len) { return list_len <= 9 ? 2 : list_len <= 16 ? 8 : list_len <= 24 ? 12 : 20; }
 
 // the oracle's distance: difference, product and running sum each rounded once, in float64, t = 0..d-1 in order
 __device__ __forceinline__ double exact_distance(const float* __restrict__ x, const float* __restrict__ y, int32_t d) {
