@@ -338,7 +338,8 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
                 *(float2*)(dst + col + 2) = hi;
             }
         }
-        if (sthr == 0) { tile_pt[buf * kTile + srow] = S.pt; tnorm[buf * kTile + srow] = S.pt >= 0 ? S.nrm : 0.f; }
+        // a row that stands for no candidate gets an infinite norm: its key is infinite whatever the (zero) product
+        if (sthr == 0) { tile_pt[buf * kTile + srow] = S.pt; tnorm[buf * kTile + srow] = S.pt >= 0 ? S.nrm : __builtin_inff(); }
     };
     // multiply the tile in LDS buffer `buf` with this wavefront's queries, push what beats the lists' last keys
     auto consume = [&](int buf) {
@@ -381,7 +382,7 @@ __global__ void __launch_bounds__(64 * knn_filter_waves(D4), knn_filter_waves_pe
             const int i = 4 * (lane >> 4) + v;
             cp[v] = tile_pt[buf * kTile + i];
             ck[v] = tnorm[buf * kTile + i] - 2.f * acc[v];
-            if (cp[v] < 0 || cp[v] == self || qpt < 0) ck[v] = __builtin_inff();
+            if (cp[v] == self) ck[v] = __builtin_inff();   // (lanes without a query collect keys nobody reads)
         }
         if (L == 2) {
             // One neighbour wanted: a lane keeps its best two, and the tile's four candidates go in one after the other
