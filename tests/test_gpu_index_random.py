@@ -64,3 +64,24 @@ def test_random_index_case(seed):
     q = rng.choice(n, min(n, 60), replace=False).astype(np.int32) if seed % 2 else None
     if q is not None or n <= 1200:
         assert neighbourhood_preservation(X, Y, kq, q)[0] == mo.neighbourhood_preservation(X, Y, kq, q)[0]
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_random_pca_case(seed):
+    from oracle import pca_oracle as po
+    from paper_2505_15511_amd import pca_init
+    rng = np.random.default_rng(9000 + seed)
+    n = int(rng.integers(50, 5000))
+    d = int(rng.choice([2, 3, 5, 8, 17, 32, 64, 100, 129, 260, 400, 768]))
+    scales = np.sort(rng.uniform(0.2, 6.0, size=d))[::-1]
+    Q, _ = np.linalg.qr(rng.normal(size=(d, d)))
+    X = ((rng.normal(size=(n, d)) * scales) @ Q.T + rng.normal(size=d) * 10.0).astype(np.float32)
+    _, lam3, _ = po.principal_axes(X, min(3, d))
+    gaps = [(lam3[0] - lam3[1]) / lam3[0]] + ([(lam3[1] - lam3[2]) / lam3[0]] if d > 2 else [])
+    std0 = float(rng.choice([0.0, 0.01]))
+    ref, lam = po.pca_init(X, std0)
+    theta, st = pca_init(X, std0, return_stats=True)
+    print(f"seed {seed}: n={n} d={d} gaps {min(gaps):.3f} residual {st['residual']:.1e} after {st['iterations']}", flush=True)
+    assert np.allclose(st["eigenvalues"], lam, rtol=1e-9)
+    if min(gaps) > 0.01:                                     # the axes are well defined: the scores must agree
+        assert np.abs(theta - ref).max() <= 1e-5 * np.abs(ref).max()
