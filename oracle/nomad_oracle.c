@@ -18,7 +18,11 @@
  *
  * parity status: pinned through tests/test_oracle_*.py, which run the same closed forms,
  * finite differences, brute-force comparisons and Philox known answers on this library as
- * on the Python oracle.
+ * on the Python oracle.  The two entry points that only large runs use are pinned there too:
+ * the row-by-row mode of oracle_loss_grad (target_slot) against the rows of the full gradient
+ * (test_single_gradient_rows_equal_the_rows_of_the_full_gradient), and oracle_train against
+ * the Python oracle's epoch applied T times, bit for bit
+ * (test_training_run_is_the_epoch_applied_T_times).
  */
 #include <math.h>
 #include <stdint.h>

@@ -518,3 +518,77 @@ def test_minibatch_epochs_agree_between_the_two_implementations():
     a = IMPLS["py"](**kw, batches_per_epoch=5).epoch(theta, 1)
     b = IMPLS["c"](**kw, batches_per_epoch=5).epoch(theta, 1)
     assert np.array_equal(a[0], b[0]) and np.abs(a[1] - b[1]).max() < 1e-12 and abs(a[2] - b[2]) < 1e-12
+
+
+# ---------------------------------------------------------------- single gradient rows, whole training runs
+def _problem_with_idle_points(seed, sampled_far_field=False):
+    """Grouped, weighted random problem on 48 connected points plus six points without any edge: three of them
+    in a cluster of an active group (they move only as sampled negatives) and three in a cluster that is a group
+    of its own (no head samples from it: under the exact far field they never move at all)."""
+    n_live, n = 48, 54
+    kw = _random_problem(n_live, seed, groups=True, weights=True, s=3, M=4.0, n_clusters=5)
+    kw["n"] = n
+    kw["row_ptr"] = np.concatenate([np.asarray(kw["row_ptr"]), np.full(n - n_live, kw["row_ptr"][-1])])
+    kw["cluster_of"] = np.concatenate([np.asarray(kw["cluster_of"]), [0, 0, 0, 5, 5, 5]])
+    kw["n_clusters"] = 6
+    kw["cluster_group"] = np.concatenate([np.asarray(kw["cluster_group"]), [7]])
+    kw["sampled_far_field"] = sampled_far_field
+    return kw
+
+
+@pytest.mark.parametrize("sampled_far_field", [False, True])
+def test_single_gradient_rows_equal_the_rows_of_the_full_gradient(sampled_far_field):
+    """The C oracle's row-by-row mode (only the edges that touch a wanted point are evaluated) is the reference at
+    sizes where the full pass is out of reach; here it is held against the full gradient, whose definition the
+    finite-difference and brute-force pins above fix."""
+    for seed in (3, 4):
+        kw = _problem_with_idle_points(seed, sampled_far_field)
+        O = IMPLS["c"](**kw)
+        n = kw["n"]
+        theta = _grid_theta(n, seed + 60)
+        for t in (0, 5):
+            _, g = O.loss_and_grad(theta, t)
+            neg = O.negatives(t)
+            sampled = np.zeros(n, bool)
+            sampled[neg.reshape(-1)] = True
+            # the idle points of the active cluster are hit as negatives and by nothing else
+            assert sampled[48:51].any() and np.abs(g[48:51]).max() > 0
+            if not sampled_far_field:
+                assert not sampled[51:].any() and np.all(g[51:] == 0.0)     # a group no head belongs to
+            for pts in (np.arange(n), np.array([50, 3, 49, 17, 53, 48, 0, 51]), np.array([52]), np.array([11])):
+                rows = O.grad_at(theta, t, pts)
+                assert rows.shape == (len(pts), 2)
+                assert np.abs(rows - g[pts]).max() < 1e-13
+        # and against the literal Python oracle, rows picked from its full gradient
+        _, g_py = IMPLS["py"](**kw).loss_and_grad(theta, 5)
+        pts = np.array([49, 2, 30, 52])
+        assert np.abs(O.grad_at(theta, 5, pts) - g_py[pts]).max() < 1e-13
+
+
+@pytest.mark.parametrize("variant", ["plain", "grouped", "batches", "pooled"])
+def test_training_run_is_the_epoch_applied_T_times(variant):
+    """oracle_train (the reference of every full-training check) = epochs t = 0..T-1 of the literal Python oracle
+    chained through float32 positions, bit for bit; its loss curve is the loss at the start of every epoch."""
+    n, T = 36, 5
+    kw = _random_problem(n, 71, groups=(variant in ("grouped", "batches")), weights=True, s=3, M=4.0)
+    kw.update(n_epochs=T, lr0=0.4)
+    if variant == "batches":
+        kw["batches_per_epoch"] = 3
+    if variant == "pooled":
+        kw.update(pool_size=8, pool_block=16)
+    theta0 = _grid_theta(n, 72).astype(np.float32)
+    O, Opy = IMPLS["c"](**kw), IMPLS["py"](**kw)
+    th_c, curve = O.train(theta0, 0, T)
+    th, starts = theta0.copy(), []
+    for t in range(T):
+        starts.append(th.copy())
+        th, _, _ = Opy.epoch(th, t)
+    assert th_c.dtype == np.float32 and np.array_equal(th_c, th)
+    assert not np.array_equal(th_c, theta0)
+    if variant != "batches":       # with sub-steps the curve adds terms evaluated at different positions
+        for t in range(T):
+            assert abs(curve[t] - Opy.loss_and_grad(starts[t], t, want_grad=False)[0]) < 1e-13
+    # a run split in two continues where it stopped (epoch indices, not call counts, key the samples and the step)
+    half, _ = O.train(theta0, 0, 2)
+    rest, _ = O.train(half, 2, T)
+    assert np.array_equal(rest, th_c)
