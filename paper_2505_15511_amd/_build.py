@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import os
 import subprocess
+import tempfile
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
@@ -15,20 +16,28 @@ HEADERS = [os.path.join(_PKG, "csrc", "nomad_kernels.h"), os.path.join(_PKG, "cs
            os.path.join(_ROOT, "include", "nomad.h")]
 
 
-def hipcc_command(out: str = LIB_PATH) -> list:
-    return ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
-            "-munsafe-fp-atomics",
+def compile_flags() -> list:
+    return ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-munsafe-fp-atomics",
             # keep the compiler from forming packed-fp32 instructions
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-            "-I" + os.path.join(_ROOT, "include"), "-I" + os.path.join(_PKG, "csrc"), "-o", out] + SOURCES
+            "-I" + os.path.join(_ROOT, "include"), "-I" + os.path.join(_PKG, "csrc")]
 
 
 def build_library(verbose: bool = False) -> str:
-    proc = subprocess.run(hipcc_command(), capture_output=True, text=True)
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
-    if verbose:
-        print(proc.stderr)
+    """Every source to an object file (side by side: they are independent), then one link."""
+    with tempfile.TemporaryDirectory(prefix="nomad_build_") as tmp:
+        objects = [os.path.join(tmp, os.path.basename(src) + ".o") for src in SOURCES]
+        procs = [subprocess.Popen(["hipcc"] + compile_flags() + ["-c", src, "-o", obj], stdout=subprocess.PIPE,
+                                  stderr=subprocess.STDOUT, text=True) for src, obj in zip(SOURCES, objects)]
+        logs = [p.communicate()[0] for p in procs]
+        if any(p.returncode != 0 for p in procs):
+            raise RuntimeError("hipcc failed:\n" + "\n".join(logs))
+        link = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objects,
+                              capture_output=True, text=True)
+        if link.returncode != 0:
+            raise RuntimeError("link failed:\n" + link.stdout + link.stderr)
+        if verbose:
+            print("\n".join(logs) + link.stderr)
     return LIB_PATH
 
 

@@ -533,11 +533,39 @@ extern "C" int nomad_neighbourhood_preservation(const float* X, int64_t n, int32
     return NOMAD_OK;
 }
 
-extern "C" int nomad_random_triplet_accuracy(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low, int64_t n_triplets,
-                                             uint64_t seed, int64_t* agree_out, int mem, int32_t device, void* stream) {
-    if (!X || !Y || !agree_out || (mem != NOMAD_HOST && mem != NOMAD_DEVICE)) return NOMAD_E_INVALID_ARG;
+namespace {
+
+// One launch covers at most kTripletsPerLaunch triplets (65,536 workgroups), so that any count up to the documented
+// 2^40 stays inside the grid limits; the launches add into the same counter.
+constexpr int64_t kTripletsPerLaunch = (int64_t)1 << 24;
+
+int check_triplet_arguments(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low, int64_t n_triplets,
+                            const int64_t* agree_out, int32_t device) {
+    if (!X || !Y || !agree_out) return NOMAD_E_INVALID_ARG;
     if (n < 3 || d < 1 || d_low < 1 || n_triplets < 0 || device < 0) return NOMAD_E_INVALID_ARG;
     if (n >= ((int64_t)1 << 31) - 256 || n_triplets > ((int64_t)1 << 40)) return NOMAD_E_TOO_LARGE;
+    return NOMAD_OK;
+}
+
+// enqueue the count of the triplets 0 .. n_triplets-1 into *agree (device memory, cleared first by a kernel)
+int enqueue_triplets(hipStream_t st, const float* dX, int32_t d, const float* dY, int32_t d_low, int64_t n, int64_t n_triplets,
+                     uint64_t seed, unsigned long long* agree) {
+    hipLaunchKernelGGL(k_store_u64, dim3(1), dim3(64), 0, st, agree, 0ull);
+    for (int64_t t0 = 0; t0 < n_triplets; t0 += kTripletsPerLaunch) {
+        const int64_t t1 = std::min(n_triplets, t0 + kTripletsPerLaunch);
+        hipLaunchKernelGGL(k_triplets, dim3(blocks_of(t1 - t0, 256)), dim3(256), 0, st, dX, d, dY, d_low, (uint32_t)n, t0, t1,
+                           (uint32_t)seed, (uint32_t)(seed >> 32), agree);
+    }
+    KTRY(hipGetLastError());
+    return NOMAD_OK;
+}
+
+}  // namespace
+
+extern "C" int nomad_random_triplet_accuracy(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low, int64_t n_triplets,
+                                             uint64_t seed, int64_t* agree_out, int mem, int32_t device, void* stream) {
+    if (mem != NOMAD_HOST && mem != NOMAD_DEVICE) return NOMAD_E_INVALID_ARG;
+    if (int rc = check_triplet_arguments(X, n, d, Y, d_low, n_triplets, agree_out, device)) return rc;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) return NOMAD_E_HIP;
     KTRY(hipSetDevice(device));
@@ -555,14 +583,11 @@ extern "C" int nomad_random_triplet_accuracy(const float* X, int64_t n, int32_t 
     unsigned long long* agree = nullptr;
     unsigned long long hagree = 0;
     KTRY(buf.alloc(&agree, 1));
-    KTRY(hipMemsetAsync(agree, 0, sizeof(unsigned long long), st));
-    if (n_triplets > 0)
-        hipLaunchKernelGGL(k_triplets, dim3(blocks_of(n_triplets, 256)), dim3(256), 0, st, dX, d, dY, d_low, (uint32_t)n, n_triplets,
-                           (uint32_t)seed, (uint32_t)(seed >> 32), agree);
+    if (int rc = enqueue_triplets(st, dX, d, dY, d_low, n, n_triplets, seed, agree)) return rc;
     KTRY(hipMemcpyAsync(&hagree, agree, sizeof(hagree), hipMemcpyDeviceToHost, st));
-    KTRY(hipGetLastError());
     KTRY(hipStreamSynchronize(st));
     *agree_out = (int64_t)hagree;
     return NOMAD_OK;
 }
+
 #pragma GCC visibility pop

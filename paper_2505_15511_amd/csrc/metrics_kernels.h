@@ -117,12 +117,13 @@ __device__ __forceinline__ void anchor_distances(const float* __restrict__ a, co
 // Triplet number t (one per thread): anchor i and two other points j, k, all distinct and uniform, from the words of
 // Philox(counter = (lo32 t, hi32 t, stream, 0), key = seed) by multiply-high range reduction over n, n - 1 and n - 2
 // values, stepping over the points already taken.  It agrees when [D_X(i,j) < D_X(i,k)] == [D_Y(i,j) < D_Y(i,k)].
+// A launch covers the triplets t_begin .. t_end-1 and adds its count to *agree.
 __global__ void __launch_bounds__(256) k_triplets(const float* __restrict__ X, int32_t d, const float* __restrict__ Y, int32_t d_low,
-                                                  uint32_t n, int64_t n_triplets, uint32_t key0, uint32_t key1,
+                                                  uint32_t n, int64_t t_begin, int64_t t_end, uint32_t key0, uint32_t key1,
                                                   unsigned long long* __restrict__ agree) {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t t = t_begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     bool same = false;
-    if (t < n_triplets) {
+    if (t < t_end) {
         uint32_t w[4];
         philox4x32_10((uint32_t)t, (uint32_t)((uint64_t)t >> 32), kTripletStream, 0u, key0, key1, w);
         const uint32_t i = __umulhi(w[0], n);
@@ -139,6 +140,11 @@ __global__ void __launch_bounds__(256) k_triplets(const float* __restrict__ X, i
     }
     const unsigned long long m = __ballot(same);
     if ((threadIdx.x & 63) == 0 && m) atomicAdd(agree, (unsigned long long)__popcll(m));
+}
+
+// *p = v (one lane): clears a counter without a memset node, so that a caller may record the call into a HIP graph
+__global__ void k_store_u64(unsigned long long* __restrict__ p, unsigned long long v) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *p = v;
 }
 
 }  // namespace nomad_metrics
