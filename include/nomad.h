@@ -318,6 +318,22 @@ int nomad_random_triplet_accuracy(const float* X, int64_t n, int32_t d, const fl
                                   uint64_t seed, int64_t* agree_out, int mem, int32_t device, void* stream);
 
 /*
+ * nomad_random_triplet_accuracy for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same definition and result; differences:
+ *   - X and Y must already be device memory of `device` (there is no `mem` argument: staging host data would need an
+ *     allocation); agree_out is a host int64;
+ *   - the agreement counter lives in a 256-byte work space that is part of the library's code object (one copy per
+ *     device, held until the process ends) instead of a buffer allocated for the call.  The call performs no
+ *     hipMalloc / hipFree; it clears the counter with a kernel, counts, copies the result out and waits for `stream`;
+ *   - limits: n < 2^31 - 256 and n_triplets <= 2^40 (NOMAD_E_TOO_LARGE beyond), device ordinal < 64
+ *     (NOMAD_E_INVALID_ARG beyond);
+ *   - all calls on one device share that device's work space: calls that overlap in time on one device (two host
+ *     threads, two streams) race on the counter and must be serialised by the caller.
+ */
+int nomad_random_triplet_accuracy_noalloc(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low, int64_t n_triplets,
+                                          uint64_t seed, int64_t* agree_out, int32_t device, void* stream);
+
+/*
  * PCA initialisation of the projection (Section 3.5: the optimisation starts from a PCA of the data).
  *
  *   X          [n*d] fp32 row-major, n >= 2, 2 <= d <= NOMAD_KNN_MAX_DIM

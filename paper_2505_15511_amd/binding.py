@@ -25,7 +25,7 @@ EXPORTS = ["nomad_create", "nomad_destroy", "nomad_set_graph", "nomad_set_embedd
            "nomad_get_embedding", "nomad_get_gradient", "nomad_get_negatives", "nomad_get_means",
            "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error",
            "nomad_copy_probe", "nomad_knn_in_clusters", "nomad_kmeans_lloyd", "nomad_neighbourhood_preservation",
-           "nomad_random_triplet_accuracy", "nomad_pca_init", "nomad_kmeans_lsh_init"]
+           "nomad_random_triplet_accuracy", "nomad_random_triplet_accuracy_noalloc", "nomad_pca_init", "nomad_kmeans_lsh_init"]
 
 
 class NomadConfig(C.Structure):
@@ -79,6 +79,7 @@ def load_library():
     lib.nomad_kmeans_lloyd.argtypes = [vp, i64, i32, i32, vp, i32, vp, C.POINTER(i32), C.POINTER(C.c_double), C.c_int, i32, vp]
     lib.nomad_neighbourhood_preservation.argtypes = [vp, i64, i32, vp, i32, i32, vp, i64, C.POINTER(i64), C.c_int, i32, vp]
     lib.nomad_random_triplet_accuracy.argtypes = [vp, i64, i32, vp, i32, i64, C.c_uint64, C.POINTER(i64), C.c_int, i32, vp]
+    lib.nomad_random_triplet_accuracy_noalloc.argtypes = [vp, i64, i32, vp, i32, i64, C.c_uint64, C.POINTER(i64), i32, vp]
     lib.nomad_pca_init.argtypes = [vp, i64, i32, C.c_float, vp, C.POINTER(C.c_double), C.c_int, i32, vp]
     lib.nomad_kmeans_lsh_init.argtypes = [vp, i64, i32, i32, vp, vp, i32, vp, vp, C.c_int, i32, vp]
     lib.nomad_last_error.argtypes = [vp]
@@ -220,6 +221,19 @@ def random_triplet_accuracy(X, Y, n_triplets, seed, device=0, stream=None):
     rc = lib.nomad_random_triplet_accuracy(px, n, d, py, d_low, int(n_triplets), int(seed), C.byref(agree), mem, int(device), st)
     if rc:
         raise NomadError(rc, "nomad_random_triplet_accuracy")
+    return int(agree.value), (agree.value / int(n_triplets) if n_triplets else float("nan"))
+
+
+def random_triplet_accuracy_noalloc(X, Y, n_triplets, seed, device=0, stream=None):
+    """nomad_random_triplet_accuracy_noalloc: the same count with no device allocation; X, Y must be device tensors."""
+    lib = load_library()
+    n, d, d_low, px, py, mem, st, keep = _two_spaces(X, Y, stream, device)
+    if mem != NOMAD_DEVICE:
+        raise ValueError("the allocation-free call takes device tensors")
+    agree = C.c_int64(0)
+    rc = lib.nomad_random_triplet_accuracy_noalloc(px, n, d, py, d_low, int(n_triplets), int(seed), C.byref(agree), int(device), st)
+    if rc:
+        raise NomadError(rc, "nomad_random_triplet_accuracy_noalloc")
     return int(agree.value), (agree.value / int(n_triplets) if n_triplets else float("nan"))
 
 

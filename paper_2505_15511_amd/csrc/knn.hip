@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <vector>
 
 #include "host_util.h"
@@ -560,6 +561,29 @@ int enqueue_triplets(hipStream_t st, const float* dX, int32_t d, const float* dY
     return NOMAD_OK;
 }
 
+// ---- work space of nomad_random_triplet_accuracy_noalloc: lives in the code object, one copy per device
+constexpr int kScratchWords = 32;   // 256 bytes; word 0 is the agreement counter
+static __device__ __align__(256) unsigned long long scratch[kScratchWords];
+
+constexpr int kMaxScratchDevices = 64;
+unsigned long long* scratch_address[kMaxScratchDevices];   // device address of `scratch` on every device, once asked for
+std::mutex scratch_mutex;
+
+// Device address of this device's copy of `scratch` (the device must be current).  The array's name is only a
+// host-side handle: kernels and copies take the address hipGetSymbolAddress returns.
+int scratch_on_device(int32_t device, unsigned long long** out) {
+    if (device >= kMaxScratchDevices) return NOMAD_E_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_address[device]) {
+        void* p = nullptr;
+        KTRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return NOMAD_E_HIP;
+        scratch_address[device] = (unsigned long long*)p;
+    }
+    *out = scratch_address[device];
+    return NOMAD_OK;
+}
+
 }  // namespace
 
 extern "C" int nomad_random_triplet_accuracy(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low, int64_t n_triplets,
@@ -590,4 +614,21 @@ extern "C" int nomad_random_triplet_accuracy(const float* X, int64_t n, int32_t 
     return NOMAD_OK;
 }
 
+extern "C" int nomad_random_triplet_accuracy_noalloc(const float* X, int64_t n, int32_t d, const float* Y, int32_t d_low,
+                                                     int64_t n_triplets, uint64_t seed, int64_t* agree_out, int32_t device,
+                                                     void* stream) {
+    if (int rc = check_triplet_arguments(X, n, d, Y, d_low, n_triplets, agree_out, device)) return rc;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) return NOMAD_E_HIP;
+    KTRY(hipSetDevice(device));
+    hipStream_t st = (hipStream_t)stream;
+    unsigned long long* counter = nullptr;
+    if (int rc = scratch_on_device(device, &counter)) return rc;
+    unsigned long long hagree = 0;
+    if (int rc = enqueue_triplets(st, X, d, Y, d_low, n, n_triplets, seed, counter)) return rc;
+    KTRY(hipMemcpyAsync(&hagree, counter, sizeof(hagree), hipMemcpyDeviceToHost, st));
+    KTRY(hipStreamSynchronize(st));
+    *agree_out = (int64_t)hagree;
+    return NOMAD_OK;
+}
 #pragma GCC visibility pop

@@ -108,6 +108,12 @@ def test_stand_alone_entry_points_check_arguments_before_any_device_work(lib):
     # the documented ranges end where the launches would no longer fit: beyond them an error code, no launch
     assert lib.nomad_random_triplet_accuracy(px, 8, 4, px, 4, 2 ** 40 + 1, 0, C.byref(hits), H, 0, None) == -4
     assert lib.nomad_random_triplet_accuracy(px, 2 ** 31 - 256, 4, px, 4, 10, 0, C.byref(hits), H, 0, None) == -4
+    assert lib.nomad_random_triplet_accuracy_noalloc(px, 8, 4, px, 4, 2 ** 40 + 1, 0, C.byref(hits), 0, None) == -4
+    assert lib.nomad_random_triplet_accuracy_noalloc(px, 2 ** 31 - 256, 4, px, 4, 10, 0, C.byref(hits), 0, None) == -4
+    assert lib.nomad_random_triplet_accuracy_noalloc(px, 2, 4, px, 4, 10, 0, C.byref(hits), 0, None) == -1
+    assert lib.nomad_random_triplet_accuracy_noalloc(None, 8, 4, px, 4, 10, 0, C.byref(hits), 0, None) == -1
+    assert lib.nomad_random_triplet_accuracy_noalloc(px, 8, 4, px, 4, 10, 0, None, 0, None) == -1
+    assert lib.nomad_random_triplet_accuracy_noalloc(px, 8, 4, px, 4, 10, 0, C.byref(hits), -1, None) == -1
     assert lib.nomad_pca_init(px, 8, 1, 0.0, px, st, H, 0, None) == -1
     assert lib.nomad_pca_init(px, 1, 4, 0.0, px, st, H, 0, None) == -1
     assert lib.nomad_pca_init(px, 8, 4, float("nan"), px, st, H, 0, None) == -1
