@@ -41,6 +41,7 @@ def _load():
         _lib.oracle_cluster_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.oracle_epoch.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_void_p, C.c_void_p]
         _lib.oracle_train.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_double, C.c_void_p]
+        _lib.oracle_mean_field_at.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         _lib.oracle_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     return _lib
 
@@ -134,6 +135,16 @@ class COracle:
         rc = self.lib.oracle_loss_grad(C.byref(self.P), _ptr(th), t, None, _ptr(g), _ptr(slot), len(pts), None, None, None)
         assert rc == 0, rc
         return g
+
+    def mean_field_at(self, theta, heads):
+        """A [m], B [m, 2] of the listed heads only, each from the loop over all cells."""
+        th = np.ascontiguousarray(theta, dtype=np.float32)
+        hd = np.ascontiguousarray(heads, dtype=np.int64)
+        A = np.zeros(len(hd), dtype=np.float64)
+        B = np.zeros((len(hd), 2), dtype=np.float64)
+        rc = self.lib.oracle_mean_field_at(C.byref(self.P), _ptr(th), _ptr(hd), len(hd), _ptr(A), _ptr(B))
+        assert rc == 0, rc
+        return A, B
 
     def epoch(self, theta, t):
         th = np.array(theta, dtype=np.float32, copy=True, order="C")

@@ -22,7 +22,8 @@
  * the row-by-row mode of oracle_loss_grad (target_slot) against the rows of the full gradient
  * (test_single_gradient_rows_equal_the_rows_of_the_full_gradient), and oracle_train against
  * the Python oracle's epoch applied T times, bit for bit
- * (test_training_run_is_the_epoch_applied_T_times).
+ * (test_training_run_is_the_epoch_applied_T_times); oracle_mean_field_at against the Python
+ * oracle's mean_field (test_mean_field_sums_of_single_heads).
  */
 #include <math.h>
 #include <stdint.h>
@@ -385,6 +386,25 @@ int oracle_loss_grad(const oracle_problem* P, const float* theta, int32_t t, dou
     free(counts); free(mu);
     free_tables(&T);
     return bad ? -2 : 0;
+}
+
+/* Mean-field sums of single heads: A [n_heads], B [n_heads*2] for the listed points, each from the plain loop over
+ * all cells (Eq. 5 without |M|, and the factor of its derivative), with the cell means of theta.  The way to check
+ * these sums at sizes where the sums of every head are out of reach. */
+int oracle_mean_field_at(const oracle_problem* P, const float* theta, const int64_t* heads, int64_t n_heads, double* A,
+                         double* B) {
+    const int32_t R = P->n_clusters;
+    int64_t* counts = (int64_t*)malloc(sizeof(int64_t) * (size_t)R);
+    double* mu = (double*)malloc(sizeof(double) * 2 * (size_t)R);
+    int rc = oracle_cluster_stats(P, theta, counts, mu);
+    for (int64_t h = 0; h < n_heads && rc == 0; ++h) {
+        const int64_t i = heads[h];
+        if (i < 0 || i >= P->n) { rc = -1; break; }
+        mean_field_sums(P, counts, mu, (double)theta[2 * i], (double)theta[2 * i + 1], group_of_point(P, i), &A[h], &B[2 * h],
+                        &B[2 * h + 1]);
+    }
+    free(counts); free(mu);
+    return rc;
 }
 
 /* One epoch in place.  B = batches_per_epoch sequential sub-steps: sub-step b takes the heads

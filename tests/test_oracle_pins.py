@@ -592,3 +592,31 @@ def test_training_run_is_the_epoch_applied_T_times(variant):
     half, _ = O.train(theta0, 0, 2)
     rest, _ = O.train(half, 2, T)
     assert np.array_equal(rest, th_c)
+
+
+def test_mean_field_sums_of_single_heads():
+    """The per-head evaluator of Eq. 5's sums (used at sizes where every head's sums are out of reach) against the
+    literal Python oracle's sums over all heads, and against the sum written out for one head."""
+    kw = _problem_with_idle_points(9)
+    n = kw["n"]
+    theta = _grid_theta(n, 91)
+    A_py, B_py = IMPLS["py"](**kw).mean_field(theta)
+    O = IMPLS["c"](**kw)
+    heads = np.array([53, 0, 17, 17, 48, 30])
+    A, B = O.mean_field_at(theta, heads)
+    assert np.abs(A - A_py[heads]).max() < 1e-15 and np.abs(B - B_py[heads]).max() < 1e-15
+    assert A.min() > 0
+    # head 17 by hand: cells of other groups, weighted by their share of the points, seen through their means
+    th = theta.astype(np.float64)
+    grp, cl = np.asarray(kw["cluster_group"]), np.asarray(kw["cluster_of"])
+    a = 0.0
+    for r in range(kw["n_clusters"]):
+        if grp[r] == grp[cl[17]]:
+            continue
+        mu = th[cl == r].mean(0)
+        a += (cl == r).sum() / n / (1.0 + ((th[17] - mu) ** 2).sum())
+    assert abs(A[2] - a) < 1e-15
+    # nothing is approximated without groups, and the sampled far field has no such sums
+    kw1 = dict(kw, cluster_group=None)
+    assert np.all(IMPLS["c"](**kw1).mean_field_at(theta, heads)[0] == 0)
+    assert np.all(IMPLS["c"](**dict(kw, sampled_far_field=True)).mean_field_at(theta, heads)[0] == 0)
