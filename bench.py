@@ -92,6 +92,44 @@ def copy_probe_gbs(torch, gib=4, steps=10):
     return dict(probe="copy", bytes_read=nbytes, bytes_written=nbytes, ms=ms, gbs_read_plus_write=2 * nbytes / ms / 1e6)
 
 
+def _timed_probe(torch, launch, steps):
+    """Average milliseconds of `launch()` over `steps` calls after one warm-up, by events on torch's current stream
+    (the stream the probes are launched on)."""
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    issued = launch()
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(steps):
+        launch()
+    ev1.record()
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / steps, issued
+
+
+def gather_probe_glines(torch, table_mb=80, requests=1 << 30, steps=3):
+    """Random 8-byte gathers over a table of `table_mb` MB (80 MB = the embedding at 10 M points): requests per
+    second in units of 1e9.  Beyond the L2 size every request costs one 128-byte line, so this is also the line rate."""
+    from paper_2505_15511_amd import binding
+    table = torch.zeros(table_mb << 17, dtype=torch.float64, device="cuda")
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ms, issued = _timed_probe(torch, lambda: binding.gather_probe(table, requests, sink), steps)
+    return dict(probe="gather8", table_mb=table_mb, requests=issued, ms=ms, g_requests_per_s=issued / ms / 1e6)
+
+
+def scatter_probe_rate(torch, kind, table_mb=80, requests=1 << 28, chains=1221, steps=3):
+    from paper_2505_15511_amd import binding
+    kinds = {"atomic_f32x2": binding.PROBE_ATOMIC_F32X2, "atomic_u64": binding.PROBE_ATOMIC_U64,
+             "append12": binding.PROBE_APPEND12, "append12_grouped": binding.PROBE_APPEND12_GROUPED}
+    if kind.startswith("append"):
+        table = torch.zeros(int(requests * 12 * 1.3 + 256 * chains * 768) // 8 + 1, dtype=torch.float64, device="cuda")
+    else:
+        table = torch.zeros(table_mb << 17, dtype=torch.float64, device="cuda")
+    ms, issued = _timed_probe(torch, lambda: binding.scatter_probe(kinds[kind], table, requests, chains), steps)
+    out = dict(probe=kind, requests=issued, ms=ms, g_requests_per_s=issued / ms / 1e6)
+    out.update(dict(chains_per_workgroup=chains) if kind.startswith("append") else dict(table_mb=table_mb))
+    return out
+
+
 def knn_index_run(args, torch, workloads):
     """nomad_knn_in_clusters on an equal-weight Gaussian mixture, clusters = components, data resident on the device.
     Reports point pairs per second of the whole call and the float32 matrix-core rate of its contraction."""
@@ -303,8 +341,12 @@ def main():
     ap.add_argument("--index-clusters", type=int, default=256)
     ap.add_argument("--index-k", type=int, default=15)
     ap.add_argument("--batches", type=int, default=1, help="sub-steps per epoch (minibatch epochs); the benchmark uses 1")
-    ap.add_argument("--probe", choices=["copy"], default=None,
-                    help="run only the streaming-copy probe (counter calibration / practical HBM ceiling)")
+    ap.add_argument("--probe", choices=["copy", "gather", "atomic_f32x2", "atomic_u64", "append12", "append12_grouped", "limits"], default=None,
+                    help="run only one memory-system probe: streaming copy (counter calibration / practical HBM ceiling), "
+                         "random 8-byte gathers or atomics over a table of --probe-mb MB, or 12-byte record appends to "
+                         "--probe-chains chains per workgroup; limits: the whole table (gathers over 1 MB .. 2 GB, atomics, appends)")
+    ap.add_argument("--probe-mb", type=int, default=80)
+    ap.add_argument("--probe-chains", type=int, default=1221)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build covers one GPU's share of the path; run with --gpus 1", file=sys.stderr)
@@ -320,6 +362,20 @@ def main():
     dev = "cuda"
     if args.probe == "copy":
         print(json.dumps(copy_probe_gbs(torch, steps=args.steps)))
+        return
+    if args.probe == "limits":
+        rows = [copy_probe_gbs(torch, steps=5)]
+        rows += [gather_probe_glines(torch, table_mb=mb, steps=3) for mb in (1, 4, 16, 64, 80, 160, 512, 2048)]
+        rows += [scatter_probe_rate(torch, k, table_mb=80, steps=2) for k in ("atomic_f32x2", "atomic_u64")]
+        rows += [scatter_probe_rate(torch, "append12", chains=c, steps=3) for c in (64, 611, 1221, 7324)]
+        rows += [scatter_probe_rate(torch, "append12_grouped", chains=c, steps=3) for c in (1221, 7324)]
+        print(json.dumps({"memory_system_limits": rows}))
+        return
+    if args.probe == "gather":
+        print(json.dumps(gather_probe_glines(torch, table_mb=args.probe_mb, steps=min(args.steps, 5))))
+        return
+    if args.probe:
+        print(json.dumps(scatter_probe_rate(torch, args.probe, table_mb=args.probe_mb, chains=args.probe_chains, steps=min(args.steps, 5))))
         return
     if args.index == "knn":
         return knn_index_run(args, torch, workloads)
@@ -416,6 +472,12 @@ def main():
         "roofline": roofline,
     }
     out["copy_probe_gbs"] = round(copy_probe_gbs(torch, gib=2, steps=5)["gbs_read_plus_write"], 1)
+    # the rate at which this machine serves independent 8-byte gathers from a table the size of the embedding at
+    # 10 M points: E * s such gathers per epoch bound the i.i.d. sampler's edge pass from below (E s / rate)
+    gp = gather_probe_glines(torch, table_mb=80, steps=3)
+    out["gather_probe_glines"] = round(gp["g_requests_per_s"], 2)
+    out["gather_probe"] = {"table_mb": 80, "requests": gp["requests"], "ms": round(gp["ms"], 3),
+                           "floor_ms_for_this_workload": round(E * s / gp["g_requests_per_s"] / 1e6, 2) if pool is None and s else None}
 
     if not args.no_cpu_baseline:
         from oracle import c_oracle

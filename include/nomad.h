@@ -214,6 +214,33 @@ int nomad_profile_read(nomad_ctx* ctx, int kind, double* total_ms, int64_t* laun
 int nomad_copy_probe(void* dst, const void* src, uint64_t bytes, void* stream);
 
 /*
+ * Gather probe: enqueue one kernel in which every lane loads 8-byte slots at uniformly random positions of `table`
+ * (device memory, 8-byte aligned, table_bytes >= 8 and < 32 GiB), eight requests in flight per lane, about
+ * n_requests in all (rounded up to a whole number of rounds of 2^24 requests, at most 4096 rounds; *issued_out
+ * receives the exact count).  What it measures: the rate at which the memory system serves independent small
+ * gathers from a table of that size -- the pattern of the negatives' embedding rows in the epoch kernel.  `sink`
+ * points to 4 bytes of device memory (written only if the loaded values add up to one particular number, which
+ * keeps the loads alive).  Follows no passage of the paper; returns without waiting.
+ */
+int nomad_gather_probe(const void* table, uint64_t table_bytes, uint64_t n_requests, uint64_t* issued_out, void* sink, void* stream);
+
+/*
+ * Scatter probes, same conventions: kind NOMAD_PROBE_ATOMIC_F32X2 (two fp32 atomic adds to a random 8-byte slot per
+ * request), NOMAD_PROBE_ATOMIC_U64 (one 64-bit integer atomic add per request), NOMAD_PROBE_APPEND12 (256 persistent
+ * workgroups of 1,024 lanes, each lane appending 12-byte records to a random one of its workgroup's `chains` private
+ * regions of the table: one partial-line write per lane) and NOMAD_PROBE_APPEND12_GROUPED (the same with eight
+ * adjacent lanes writing 96 contiguous bytes).  The append kinds need table_bytes >= about 1.25 x 12 x n_requests
+ * plus 768 bytes per (workgroup, chain) (NOMAD_E_INVALID_ARG otherwise); `chains` (1..16384) is ignored by the
+ * atomic kinds.  The table's contents are overwritten.
+ */
+#define NOMAD_PROBE_ATOMIC_F32X2 1
+#define NOMAD_PROBE_ATOMIC_U64 2
+#define NOMAD_PROBE_APPEND12 3
+#define NOMAD_PROBE_APPEND12_GROUPED 4
+int nomad_scatter_probe(int kind, void* table, uint64_t table_bytes, uint64_t n_requests, uint32_t chains, uint64_t* issued_out,
+                        void* stream);
+
+/*
  * ---- the upstream index: exact nearest neighbours inside clusters (Section 3.2) ----
  *
  * The paper builds its kNN graph from a K-Means partition: the candidates for a point's neighbours are the points of

@@ -9,7 +9,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 LIB_PATH = os.environ.get("NOMAD_LIBRARY_PATH") or os.path.join(_PKG, "libnomad.so")
 SOURCES = [os.path.join(_PKG, "csrc", "nomad.hip"), os.path.join(_PKG, "csrc", "knn.hip"),
-           os.path.join(_PKG, "csrc", "pca.hip")]
+           os.path.join(_PKG, "csrc", "pca.hip"), os.path.join(_PKG, "csrc", "probes.hip")]
 HEADERS = [os.path.join(_PKG, "csrc", "nomad_kernels.h"), os.path.join(_PKG, "csrc", "knn_kernels.h"),
            os.path.join(_PKG, "csrc", "metrics_kernels.h"), os.path.join(_PKG, "csrc", "philox.h"),
            os.path.join(_PKG, "csrc", "pca_kernels.h"), os.path.join(_PKG, "csrc", "host_util.h"),

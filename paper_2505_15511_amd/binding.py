@@ -24,7 +24,7 @@ ERRORS = {-1: "NOMAD_E_INVALID_ARG", -2: "NOMAD_E_BAD_GRAPH", -3: "NOMAD_E_ORDER
 EXPORTS = ["nomad_create", "nomad_destroy", "nomad_set_graph", "nomad_set_embedding", "nomad_epoch", "nomad_loss",
            "nomad_get_embedding", "nomad_get_gradient", "nomad_get_negatives", "nomad_get_means",
            "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error",
-           "nomad_copy_probe", "nomad_knn_in_clusters", "nomad_kmeans_lloyd", "nomad_neighbourhood_preservation",
+           "nomad_copy_probe", "nomad_gather_probe", "nomad_scatter_probe", "nomad_knn_in_clusters", "nomad_kmeans_lloyd", "nomad_neighbourhood_preservation",
            "nomad_random_triplet_accuracy", "nomad_random_triplet_accuracy_noalloc", "nomad_pca_init", "nomad_kmeans_lsh_init"]
 
 
@@ -75,6 +75,8 @@ def load_library():
     lib.nomad_profile.argtypes = [vp, C.c_int]
     lib.nomad_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.nomad_copy_probe.argtypes = [vp, vp, C.c_uint64, vp]
+    lib.nomad_gather_probe.argtypes = [vp, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint64), vp, vp]
+    lib.nomad_scatter_probe.argtypes = [C.c_int, vp, C.c_uint64, C.c_uint64, C.c_uint32, C.POINTER(C.c_uint64), vp]
     lib.nomad_knn_in_clusters.argtypes = [vp, i64, i32, vp, i32, i32, vp, C.c_int, i32, vp, vp]
     lib.nomad_kmeans_lloyd.argtypes = [vp, i64, i32, i32, vp, i32, vp, C.POINTER(i32), C.POINTER(C.c_double), C.c_int, i32, vp]
     lib.nomad_neighbourhood_preservation.argtypes = [vp, i64, i32, vp, i32, i32, vp, i64, C.POINTER(i64), C.c_int, i32, vp]
@@ -120,6 +122,37 @@ def copy_probe(dst, src, stream=None):
     rc = lib.nomad_copy_probe(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes, C.c_void_p(stream or None))
     if rc:
         raise NomadError(rc, "nomad_copy_probe")
+
+
+PROBE_ATOMIC_F32X2, PROBE_ATOMIC_U64, PROBE_APPEND12, PROBE_APPEND12_GROUPED = 1, 2, 3, 4
+
+
+def gather_probe(table, n_requests, sink, stream=None):
+    """Enqueue nomad_gather_probe on a device tensor `table`; returns the number of requests issued."""
+    import torch
+    lib = load_library()
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    issued = C.c_uint64(0)
+    rc = lib.nomad_gather_probe(C.c_void_p(table.data_ptr()), table.numel() * table.element_size(), int(n_requests), C.byref(issued),
+                                C.c_void_p(sink.data_ptr()), C.c_void_p(stream or None))
+    if rc:
+        raise NomadError(rc, "nomad_gather_probe")
+    return int(issued.value)
+
+
+def scatter_probe(kind, table, n_requests, chains=1, stream=None):
+    """Enqueue nomad_scatter_probe (atomics or appends) on a device tensor `table`; returns the requests issued."""
+    import torch
+    lib = load_library()
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    issued = C.c_uint64(0)
+    rc = lib.nomad_scatter_probe(int(kind), C.c_void_p(table.data_ptr()), table.numel() * table.element_size(), int(n_requests),
+                                 int(chains), C.byref(issued), C.c_void_p(stream or None))
+    if rc:
+        raise NomadError(rc, "nomad_scatter_probe")
+    return int(issued.value)
 
 
 def knn_in_clusters(X, cluster_of, n_clusters, k, device=0, stream=None, return_stats=False):

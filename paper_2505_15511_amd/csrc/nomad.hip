@@ -879,12 +879,5 @@ int nomad_profile_read(nomad_ctx* c, int kind, double* total_ms, int64_t* launch
     return NOMAD_OK;
 }
 
-int nomad_copy_probe(void* dst, const void* src, uint64_t bytes, void* stream) {
-    if (!dst || !src || (bytes & 15u) || (((uintptr_t)dst | (uintptr_t)src) & 15u)) return NOMAD_E_INVALID_ARG;
-    if (bytes == 0) return NOMAD_OK;
-    hipLaunchKernelGGL(k_copy_probe, dim3(65536), dim3(kBlock), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst, (size_t)(bytes / 16));
-    return hipGetLastError() == hipSuccess ? NOMAD_OK : NOMAD_E_HIP;
-}
-
 }  // extern "C"
 #pragma GCC visibility pop

@@ -1497,14 +1497,6 @@ __global__ void __launch_bounds__(kBlock) k_zero_u64(unsigned long long* __restr
     if (i < n) p[i] = 0ull;
 }
 
-// ------------------------------------------------------------------ bandwidth probe
-// Plain streaming copy (16 bytes per lane, grid-stride): the practical HBM ceiling of the machine
-// and the kernel of known traffic that profiler byte counters are calibrated against.
-__global__ void __launch_bounds__(kBlock) k_copy_probe(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t count) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) dst[i] = src[i];
-}
-
 // ------------------------------------------------------------------ test hook: negatives of an edge range
 __global__ void __launch_bounds__(kBlock) k_negatives(const EdgeArgs P, int64_t e_begin, int64_t e_end, int32_t* __restrict__ out) {
     const int64_t e = e_begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
