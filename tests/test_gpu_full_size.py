@@ -24,6 +24,19 @@ def grad_err(g, ref):
     return np.abs(np.asarray(g, dtype=np.float64) - ref).max() / np.abs(ref).max()
 
 
+def grad_err_per_component(g, ref):
+    """max over points and components of |g - ref| / max(|ref|, 1e-3 max|ref|): unlike the global figure above it
+    cannot hide an error confined to points with small forces.  A component near force balance is the difference
+    of O(100) float32 terms of size max|ref| / 10, so its float32 floor is about 1e-7 max|ref|, i.e. 1e-4 of the
+    denominator's floor: the bound asserted on it is 1e-3."""
+    ref = np.asarray(ref, dtype=np.float64)
+    floor = 1e-3 * np.abs(ref).max()
+    return (np.abs(np.asarray(g, dtype=np.float64) - ref) / np.maximum(np.abs(ref), floor)).max()
+
+
+COMPONENT_TOL = 1e-3
+
+
 def device_nomad(w, mode=SCATTER_DETERMINISTIC):
     dev = "cuda"
     nm = Nomad(w.n, w.n_clusters, w.n_neg, w.noise_count, w.n_epochs, w.lr0, w.seed, mode,
@@ -101,20 +114,21 @@ def test_config4_one_epoch_and_mid_run_against_the_oracle():
         th1, g_ref, _ = O.epoch(d["theta0"], 0)
         note(f"  oracle epoch {time.time() - t0:.1f} s")
         nm.epoch(0)
-        err = grad_err(nm.get_gradient(), g_ref)
+        g0 = nm.get_gradient()
+        err, err_c = grad_err(g0, g_ref), grad_err_per_component(g0, g_ref)
         L_ref, _ = O.loss_and_grad(th1, 1, want_grad=False)
         L = nm.loss(1)
-        note(f"  epoch 0: grad err {err:.2e}, loss {L:.8f} vs {L_ref:.8f}")
-        assert err < GRAD_TOL and abs(L - L_ref) < LOSS_TOL * L_ref
+        note(f"  epoch 0: grad err {err:.2e} (per component, floor 1e-3: {err_c:.2e}), loss {L:.8f} vs {L_ref:.8f}")
+        assert err < GRAD_TOL and err_c < COMPONENT_TOL and abs(L - L_ref) < LOSS_TOL * L_ref
         for t in range(1, 12):
             nm.epoch(t)
         theta = nm.get_embedding()
         nm.epoch(12)
         g = nm.get_gradient()
         _, g_ref = O.loss_and_grad(theta, 12)
-        err = grad_err(g, g_ref)
-        note(f"  epoch 12: grad err {err:.2e}")
-        assert err < GRAD_TOL
+        err, err_c = grad_err(g, g_ref), grad_err_per_component(g, g_ref)
+        note(f"  epoch 12: grad err {err:.2e} (per component, floor 1e-3: {err_c:.2e})")
+        assert err < GRAD_TOL and err_c < COMPONENT_TOL
     # the atomic path on the same inputs
     with device_nomad(w, SCATTER_ATOMIC) as nm:
         nm.set_embedding(theta)
@@ -147,8 +161,34 @@ def test_config5_sampled_gradient_rows(scale):
     g_ref = O.grad_at(theta, 3, pts)
     note(f"  oracle rows {time.time() - t0:.1f} s")
     err = np.abs(g[pts].astype(np.float64) - g_ref).max() / np.abs(g_ref).max()
-    note(f"  grad err on {len(pts)} sampled rows {err:.2e} (max |g| {np.abs(g_ref).max():.3e})")
-    assert err < GRAD_TOL
+    err_c = grad_err_per_component(g[pts], g_ref)
+    note(f"  grad err on {len(pts)} sampled rows {err:.2e} (per component, floor 1e-3: {err_c:.2e}; max |g| {np.abs(g_ref).max():.3e})")
+    assert err < GRAD_TOL and err_c < COMPONENT_TOL
+
+
+def test_config5_mean_field_sums_of_sampled_heads_at_full_size():
+    """Eq. 5's sums A_i, B_i at 60 M points and 16,384 cells: the library's values for about 400 sampled heads (after
+    three epochs, so that the cells have spread) against the oracle's loop over all cells for each of them; the cell
+    means against the oracle's on every cell."""
+    note("config 5 full size: mean-field sums of sampled heads")
+    w = workloads.make_config(5, device="cuda")
+    O = c_oracle.COracle(**w.numpy())
+    rng = np.random.default_rng(55)
+    heads = np.unique(np.concatenate([rng.choice(w.n, 400, replace=False), [0, w.n - 1]]))
+    with device_nomad(w) as nm:
+        for t in range(3):
+            nm.epoch(t)
+        theta = nm.get_embedding()
+        A, B = nm.get_mean_field()
+        mu, counts = nm.get_means()
+    counts_ref, _, mu_ref = O.cluster_stats(theta)
+    assert np.array_equal(counts, counts_ref) and np.abs(mu - mu_ref).max() < 1e-6 * max(1.0, np.abs(mu_ref).max())
+    t0 = time.time()
+    A_ref, B_ref = O.mean_field_at(theta, heads)
+    errA = np.abs(A[heads] - A_ref).max() / np.abs(A_ref).max()
+    errB = np.abs(B[heads] - B_ref).max() / np.abs(B_ref).max()
+    note(f"  oracle {time.time() - t0:.1f} s; A err {errA:.2e} (max {A_ref.max():.3e}), B err {errB:.2e} (max {np.abs(B_ref).max():.3e})")
+    assert errA < 2e-6 and errB < 2e-6
 
 
 # ------------------------------------------------------------------ the opt-in pooled sampler at full size

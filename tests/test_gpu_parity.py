@@ -20,6 +20,18 @@ def grad_err(g, ref):
     return np.abs(np.asarray(g, dtype=np.float64) - ref).max() / np.abs(ref).max()
 
 
+def grad_err_per_component(g, ref):
+    """max over points and components of |g - ref| / max(|ref|, 1e-3 max|ref|): an error confined to points with small
+    forces (tails of hubs, heads without edges, negatives that stood for a cell mean) shows here and not in
+    grad_err.  Components near force balance are differences of float32 terms a hundred times their size, hence
+    the looser bound."""
+    ref = np.asarray(ref, dtype=np.float64)
+    return (np.abs(np.asarray(g, dtype=np.float64) - ref) / np.maximum(np.abs(ref), 1e-3 * np.abs(ref).max())).max()
+
+
+COMPONENT_TOL = 1e-3
+
+
 def note(msg):
     print(msg, flush=True)
 
@@ -139,11 +151,11 @@ def test_gradient_and_loss_after_one_epoch(case, mode):
     with make_nomad(d, mode) as nm:
         nm.epoch(0)
         g = nm.get_gradient()
-        err = grad_err(g, g_ref)
+        err, err_c = grad_err(g, g_ref), grad_err_per_component(g, g_ref)
         L = nm.loss(1)
         th = nm.get_embedding()
-    note(f"  grad err {err:.2e}  loss {L:.8f} vs {L_ref:.8f}")
-    assert err < GRAD_TOL
+    note(f"  grad err {err:.2e} (per component, floor 1e-3: {err_c:.2e})  loss {L:.8f} vs {L_ref:.8f}")
+    assert err < GRAD_TOL and err_c < COMPONENT_TOL
     assert abs(L - L_ref) < LOSS_TOL * abs(L_ref)
     assert np.abs(th - th1).max() < 1e-5 * max(1.0, np.abs(th1).max())
 
@@ -240,8 +252,8 @@ def test_deterministic_variants_on_skewed_degrees(env, monkeypatch):
             g = nm.get_gradient()
             nm.epoch(1)
             out.append((g, nm.get_embedding()))
-    note(f"  {env}: grad err {grad_err(out[0][0], g_ref):.2e}")
-    assert grad_err(out[0][0], g_ref) < GRAD_TOL
+    note(f"  {env}: grad err {grad_err(out[0][0], g_ref):.2e} (per component, floor 1e-3: {grad_err_per_component(out[0][0], g_ref):.2e})")
+    assert grad_err(out[0][0], g_ref) < GRAD_TOL and grad_err_per_component(out[0][0], g_ref) < COMPONENT_TOL
     assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
 
 
