@@ -53,6 +53,9 @@ typedef struct {
                                   /* approximated for the head enters through the cell mean and receives no force     */
     int32_t mean_gradient;        /* opt-in: the gradient also flows through mu_r = (1/n_r) sum_{l in r} theta_l: every */
                                   /* member of cell r receives (1/n_r) d(n L)/d mu_r (full mode, exact far field only)  */
+    int32_t pool_mode;            /* pooled sampler: 0 = 16-bit picks from the pool of a block of consecutive positions; */
+                                  /* 1 = distinct picks from the pool of an interleaved block (see edge_negatives)       */
+    int32_t pool_line;            /* pool_mode 1: consecutive points per pool line, a power of two                       */
 } oracle_problem;
 
 /* ---- Philox4x32-10 (published algorithm: Salmon, Moraes, Dror, Shaw, SC'11) ---- */
@@ -132,12 +135,50 @@ static inline int32_t group_of_point(const oracle_problem* P, int64_t i) {
  * ((k >> 1) & 3) of Philox(counter (lo32 e, hi32 e, t, k >> 3)): eight slots per Philox call.  Every
  * negative is still uniform over the points; negatives of different edges of a block are no longer
  * independent.
+ * pooled sampler with distinct picks (pool_mode 1; single population): the positions are cut into segments of
+ * 64; there are NB = ceil(NS / Q) blocks for NS segments and Q = pool_block / 64 segments per block; segment sigma
+ * belongs to block beta = sigma mod NB and position e has rank 64 (sigma div NB) + (e mod 64) in its block, so a
+ * block is Q segments spread evenly over the edge list.  The pool of a block is L = pool_size / pool_line lines
+ * of pool_line cyclically consecutive points; line gamma starts at the point picked by word (gamma & 3) of
+ * Philox(counter (beta, 0xFFFFFFFF, t, gamma >> 2)); entry u is point (u div L) of line (u mod L).  An edge takes
+ * one word W = word ((rank >> 10) & 3) of Philox(counter (beta, 0xFFFFFFFE, t, (rank & 1023) + 1024 (rank >> 12)));
+ * with lg = log2(pool_size), u_0 = top lg bits of W and the odd stride c = 2 (bits 1..lg-1 of W) + 1, slot k takes
+ * entry (u_0 + k c) mod pool_size.  The s <= L picks lie in s different lines, whose starts are independent
+ * uniform draws: the negatives of one edge are i.i.d. uniform over the points, as Section 3.1 defines them;
+ * negatives of different edges of a block are dependent.
  * sampled far field: the i.i.d. sampler with every head's population = all n points. */
 static void edge_negatives(const oracle_problem* P, const oracle_tables* T, int64_t e, int64_t i, int32_t t, int32_t* m) {
     int32_t g = group_of_point(P, i);
     int64_t base = T->gstart[g];
     uint64_t nloc = (uint64_t)(T->gstart[g + 1] - base);
     uint32_t key[2] = {(uint32_t)P->seed, (uint32_t)(P->seed >> 32)};
+    if (P->pool_size > 0 && P->pool_mode == 1) {
+        const int64_t E = P->row_ptr[P->n];
+        const int64_t NS = (E + 63) / 64, Q = P->pool_block / 64;
+        int64_t NB = (NS + Q - 1) / Q;
+        if (NB < 1) NB = 1;
+        const int64_t sigma = e >> 6;
+        const uint64_t beta = (uint64_t)(sigma % NB);
+        const uint64_t rank = (uint64_t)(64 * (sigma / NB) + (e & 63));
+        uint32_t ctr[4] = {(uint32_t)beta, 0xFFFFFFFEu, (uint32_t)t, (uint32_t)((rank & 1023) + 1024 * (rank >> 12))};
+        uint32_t w[4];
+        oracle_philox4x32_10(ctr, key, w);
+        const uint32_t W = w[(rank >> 10) & 3];
+        int lg = 0;
+        while ((1 << (lg + 1)) <= P->pool_size) ++lg;
+        const uint32_t PS = (uint32_t)P->pool_size, L = PS / (uint32_t)P->pool_line;
+        const uint32_t u0 = W >> (32 - lg), c = 2u * ((W >> 1) & (PS / 2 - 1)) + 1u;
+        for (int32_t k = 0; k < P->n_neg; ++k) {
+            const uint32_t u = (u0 + (uint32_t)k * c) % PS;
+            const uint32_t gamma = u % L, o = u / L;
+            uint32_t pctr[4] = {(uint32_t)beta, 0xFFFFFFFFu, (uint32_t)t, gamma >> 2};
+            uint32_t pw[4];
+            oracle_philox4x32_10(pctr, key, pw);
+            const uint64_t start = ((uint64_t)pw[gamma & 3] * nloc) >> 32;
+            m[k] = T->members[base + (int64_t)((start + o) % nloc)];
+        }
+        return;
+    }
     if (P->pool_size > 0) {
         uint64_t beta = (uint64_t)e / (uint64_t)P->pool_block;
         for (int32_t k = 0; k < P->n_neg; ++k) {

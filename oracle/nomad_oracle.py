@@ -30,6 +30,10 @@ Readings where the paper is silent (each one is listed in the design notes):
   - opt-in pooled sampler (a variant, not the paper's i.i.d. noise samples): blocks of
     pool_block consecutive CSR positions share a pool of pool_size uniformly drawn points and
     16 bits of the per-edge Philox words pick a pool entry per slot (see negatives());
+  - opt-in pooled sampler with distinct picks (pool_mode = 1; the other pooled variant, see negatives_distinct()):
+    the s negatives of one edge sit in s different, independently drawn pool lines, so they are exactly i.i.d.
+    uniform over the points as Section 3.1 defines the noise samples of an edge; only negatives of different
+    edges of a block are dependent;
   - the cells approximated for head i are those whose group differs from the group of
     i's own cluster; negatives are drawn from the points of i's own group (ascending
     index order) and weighted by omega_i = |M| * (n_loc(i)/n) / s;
@@ -114,6 +118,9 @@ class Problem:
     pool_size: int = 0                        # pooled sampler: points per pool (0 = i.i.d. per-edge sampler)
     pool_block: int = 0                       # pooled sampler: consecutive CSR positions that share a pool
     batches_per_epoch: int = 1                # B: sequential sub-steps of an epoch over consecutive head ranges
+    pool_mode: int = 0                        # pooled sampler: 0 = 16-bit picks, consecutive blocks; 1 = distinct picks,
+                                              # interleaved blocks (negatives_distinct)
+    pool_line: int = 1                        # pool_mode 1: consecutive points per pool line (a power of two)
     sampled_far_field: bool = False           # opt-in: Eq. 5's sum over approximated cells estimated from the samples
     mean_gradient: bool = False               # opt-in: the gradient also flows through the cell means mu_r(theta)
 
@@ -129,6 +136,15 @@ class Problem:
             self.noise_count = float(self.n_neg)
         assert (self.pool_size == 0) == (self.pool_block == 0), "pool_size and pool_block go together"
         assert self.pool_size == 0 or self.cluster_group is None, "the pooled sampler needs a single population"
+        assert self.pool_mode in (0, 1) and (self.pool_mode == 0 or self.pool_size > 0), "pool_mode 1 needs a pool"
+        if self.pool_mode == 1:
+            P_, l_ = self.pool_size, self.pool_line
+            assert P_ >= 2 and P_ & (P_ - 1) == 0 and P_ <= 4096, "distinct picks: the pool size is a power of two, 2..4096"
+            assert l_ >= 1 and l_ & (l_ - 1) == 0 and P_ % l_ == 0 and self.n_neg <= P_ // l_, "lines: a power of two, s <= lines"
+            assert self.pool_block % 64 == 0, "distinct picks: blocks are whole segments of 64 positions"
+            assert self.batches_per_epoch == 1, "distinct picks: one step per epoch"
+        else:
+            assert self.pool_line == 1, "pool lines belong to pool_mode 1"
         assert not (self.sampled_far_field and self.pool_size), "sampled far field and pooled sampler do not combine"
         assert not (self.sampled_far_field and self.mean_gradient), "gradient through the means needs the exact far field"
         assert not (self.mean_gradient and self.batches_per_epoch > 1), "sub-steps hold the means of the epoch start constant"
@@ -143,6 +159,7 @@ class Problem:
                  n_clusters=w["n_clusters"], n_neg=w["n_neg"], noise_count=w["noise_count"], seed=w["seed"],
                  n_epochs=w["n_epochs"], lr0=w["lr0"], weights=w.get("weights"),
                  cluster_group=w.get("cluster_group"), pool_size=w.get("pool_size", 0), pool_block=w.get("pool_block", 0),
+                 pool_mode=w.get("pool_mode", 0), pool_line=w.get("pool_line", 1),
                  batches_per_epoch=w.get("batches_per_epoch", 1), sampled_far_field=w.get("sampled_far_field", False),
                  mean_gradient=w.get("mean_gradient", False))
         d.update(over)
@@ -234,6 +251,68 @@ def pool_of_block(P: Problem, beta: int, t: int) -> np.ndarray:
     return pool
 
 
+# Second and third counter words of the two Philox streams of a pool block (the per-edge stream of the i.i.d.
+# sampler has hi32(e) = 0 in that place).
+_POOL_ENTRY_STREAM = 0xFFFFFFFF
+_POOL_PICK_STREAM = 0xFFFFFFFE
+
+
+def distinct_pool_layout(P: Problem):
+    """Pooled sampler with distinct picks: how the CSR positions are dealt to pool blocks.  The positions are cut
+    into segments of 64; with Q = pool_block / 64 segments per block there are NB = ceil(NS / Q) blocks for NS
+    segments, and segment sigma belongs to block sigma mod NB: a block is made of Q segments spread evenly over the
+    whole edge list, so the edges that share a pool come from Q different neighbourhoods of the graph.
+    Returns (NB, block(e), rank(e)): rank(e) = 64 (sigma div NB) + (e mod 64) numbers a block's positions."""
+    E = P.n_edges
+    NS = (E + 63) // 64
+    Q = P.pool_block // 64
+    NB = max(1, (NS + Q - 1) // Q)
+    return NB, (lambda e: (e >> 6) % NB), (lambda e: 64 * ((e >> 6) // NB) + (e & 63))
+
+
+def distinct_pool_entry(P: Problem, beta: int, t: int, u: int) -> int:
+    """Point behind entry u of the pool of block beta in epoch t.  The pool is L = pool_size / pool_line lines of
+    pool_line consecutive points (cyclically: the point after n-1 is 0); entry u is point number u div L of line
+    u mod L; line gamma starts at a_gamma = floor(x n / 2^32), x = word gamma & 3 of
+    Philox(counter (beta, 0xFFFFFFFF, t, gamma >> 2)).  Every entry is uniform over the points (a uniform start
+    shifted by a constant, modulo n), entries of different lines are independent."""
+    L = P.pool_size // P.pool_line
+    gamma, o = u % L, u // L
+    k0, k1 = P.seed & _MASK32, (P.seed >> 32) & _MASK32
+    x = philox4x32_10((beta & _MASK32, _POOL_ENTRY_STREAM, t, gamma >> 2), (k0, k1))[gamma & 3]
+    return (((x * P.n) >> 32) + o) % P.n
+
+
+def distinct_picks(P: Problem, beta: int, rank: int, t: int):
+    """The s pool entries of the position with rank `rank` in block beta.  One 32-bit word W per edge: word
+    (rank >> 10) & 3 of Philox(counter (beta, 0xFFFFFFFE, t, (rank & 1023) + 1024 (rank >> 12))), so that one call
+    serves four positions 1024 apart.  With lg = log2(pool_size): first entry u_0 = the top lg bits of W, stride
+    c = 2 (bits 1 .. lg-1 of W) + 1 (odd), slot k takes entry (u_0 + k c) mod pool_size.  An odd stride visits
+    s <= L different residues modulo the number of lines L (a power of two), so the s picks lie in s different
+    lines."""
+    k0, k1 = P.seed & _MASK32, (P.seed >> 32) & _MASK32
+    call = (rank & 1023) + 1024 * (rank >> 12)
+    W = philox4x32_10((beta & _MASK32, _POOL_PICK_STREAM, t, call), (k0, k1))[(rank >> 10) & 3]
+    lg = P.pool_size.bit_length() - 1
+    u0 = W >> (32 - lg)
+    c = 2 * ((W >> 1) & (P.pool_size // 2 - 1)) + 1
+    return [(u0 + k * c) % P.pool_size for k in range(P.n_neg)]
+
+
+def negatives_distinct(P: Problem, t: int, e_begin: int, e_end: int) -> np.ndarray:
+    """Pooled sampler with distinct picks (pool_mode = 1): m[e, k] = the point behind pool entry distinct_picks()[k] of
+    the pool of e's block.  The s negatives of an edge come from s different lines whose starts are independent
+    uniform draws, hence they are i.i.d. uniform over the points: the noise samples of one edge are exactly those
+    of Section 3.1; negatives of different edges of a block share lines and are dependent."""
+    _, block, rank = distinct_pool_layout(P)
+    out = np.zeros((e_end - e_begin, P.n_neg), dtype=np.int64)
+    for e in range(e_begin, e_end):
+        beta = block(e)
+        for k, u in enumerate(distinct_picks(P, beta, rank(e), t)):
+            out[e - e_begin, k] = distinct_pool_entry(P, beta, t, u)
+    return out
+
+
 def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None) -> np.ndarray:
     """Sampled negative indices m[e, slot] for the CSR edges e_begin..e_end-1 of epoch t.
 
@@ -250,6 +329,8 @@ def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None)
     out = np.zeros((e_end - e_begin, s), dtype=np.int64)
     if s == 0 or e_end == e_begin:
         return out
+    if P.pool_mode == 1:
+        return negatives_distinct(P, t, e_begin, e_end)
     e = np.arange(e_begin, e_end, dtype=np.uint64)
     k0, k1 = P.seed & _MASK32, (P.seed >> 32) & _MASK32
     if P.pool_size > 0:
