@@ -28,7 +28,8 @@ class _Problem(C.Structure):
                 ("n_neg", C.c_int32), ("noise_count", C.c_double), ("seed", C.c_uint64),
                 ("pool_size", C.c_int32), ("pool_block", C.c_int32), ("batches_per_epoch", C.c_int32),
                 ("head_begin", C.c_int64), ("head_end", C.c_int64), ("sampled_far_field", C.c_int32),
-                ("mean_gradient", C.c_int32), ("pool_mode", C.c_int32), ("pool_line", C.c_int32)]
+                ("mean_gradient", C.c_int32), ("pool_mode", C.c_int32), ("pool_line", C.c_int32),
+                ("pool_segment", C.c_int32)]
 
 
 def _load():
@@ -55,7 +56,8 @@ class COracle:
 
     def __init__(self, *, n, row_ptr, col_idx, cluster_of, n_clusters, n_neg, noise_count, seed=0, n_epochs=1,
                  lr0=1.0, weights=None, cluster_group=None, pool_size=0, pool_block=0, batches_per_epoch=1,
-                 sampled_far_field=False, mean_gradient=False, pool_mode=0, pool_line=1, **_ignored):
+                 sampled_far_field=False, mean_gradient=False, pool_mode=0, pool_line=1, pool_segment=64,
+                 **_ignored):
         self.lib = _load()
         self.n = int(n)
         self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
@@ -75,13 +77,15 @@ class COracle:
         self.P = _Problem(self.n, _ptr(self.row_ptr), _ptr(self.col_idx), _ptr(self.weights), _ptr(self.cluster_of),
                           self.n_clusters, _ptr(self.cluster_group), self.n_neg, self.noise_count, self.seed,
                           self.pool_size, self.pool_block, int(batches_per_epoch), 0, -1, int(bool(sampled_far_field)),
-                          int(bool(mean_gradient)), int(pool_mode), int(pool_line))
-        self.pool_mode, self.pool_line = int(pool_mode), int(pool_line)
+                          int(bool(mean_gradient)), int(pool_mode), int(pool_line), int(pool_segment))
+        self.pool_mode, self.pool_line, self.pool_segment = int(pool_mode), int(pool_line), int(pool_segment)
         if self.pool_mode == 1:
             Pz, ln = self.pool_size, self.pool_line
             assert 2 <= Pz <= 4096 and Pz & (Pz - 1) == 0, "distinct picks: the pool size is a power of two, 2..4096"
             assert ln >= 1 and ln & (ln - 1) == 0 and Pz % ln == 0 and self.n_neg <= Pz // ln, "lines: a power of two, s <= lines"
-            assert self.pool_block % 64 == 0 and int(batches_per_epoch) == 1, "whole segments of 64 positions; one step per epoch"
+            sg = self.pool_segment
+            assert sg >= 64 and sg & (sg - 1) == 0 and self.pool_block % sg == 0, "blocks are whole segments; segments a power of two >= 64"
+            assert int(batches_per_epoch) == 1, "distinct picks: one step per epoch"
         else:
             assert self.pool_mode == 0 and self.pool_line == 1
         assert not (mean_gradient and (sampled_far_field or int(batches_per_epoch) > 1)), \

@@ -56,6 +56,8 @@ typedef struct {
     int32_t pool_mode;            /* pooled sampler: 0 = 16-bit picks from the pool of a block of consecutive positions; */
                                   /* 1 = distinct picks from the pool of an interleaved block (see edge_negatives)       */
     int32_t pool_line;            /* pool_mode 1: consecutive points per pool line, a power of two                       */
+    int32_t pool_segment;         /* pool_mode 1: consecutive positions dealt to a block together: a power of two >= 64   */
+                                  /* that divides pool_block                                                             */
 } oracle_problem;
 
 /* ---- Philox4x32-10 (published algorithm: Salmon, Moraes, Dror, Shaw, SC'11) ---- */
@@ -136,9 +138,9 @@ static inline int32_t group_of_point(const oracle_problem* P, int64_t i) {
  * negative is still uniform over the points; negatives of different edges of a block are no longer
  * independent.
  * pooled sampler with distinct picks (pool_mode 1; single population): the positions are cut into segments of
- * 64; there are NB = ceil(NS / Q) blocks for NS segments and Q = pool_block / 64 segments per block; segment sigma
- * belongs to block beta = sigma mod NB and position e has rank 64 (sigma div NB) + (e mod 64) in its block, so a
- * block is Q segments spread evenly over the edge list.  The pool of a block is L = pool_size / pool_line lines
+ * g = pool_segment; there are NB = ceil(NS / Q) blocks for NS segments and Q = pool_block / g segments per block;
+ * segment sigma belongs to block beta = sigma mod NB and position e has rank g (sigma div NB) + (e mod g) in its
+ * block, so a block is Q segments spread evenly over the edge list (g = pool_block: consecutive blocks).  The pool of a block is L = pool_size / pool_line lines
  * of pool_line cyclically consecutive points; line gamma starts at the point picked by word (gamma & 3) of
  * Philox(counter (beta, 0xFFFFFFFF, t, gamma >> 2)); entry u is point (u div L) of line (u mod L).  An edge takes
  * one word W = word ((rank >> 10) & 3) of Philox(counter (beta, 0xFFFFFFFE, t, (rank & 1023) + 1024 (rank >> 12)));
@@ -154,12 +156,13 @@ static void edge_negatives(const oracle_problem* P, const oracle_tables* T, int6
     uint32_t key[2] = {(uint32_t)P->seed, (uint32_t)(P->seed >> 32)};
     if (P->pool_size > 0 && P->pool_mode == 1) {
         const int64_t E = P->row_ptr[P->n];
-        const int64_t NS = (E + 63) / 64, Q = P->pool_block / 64;
+        const int64_t seg = P->pool_segment;
+        const int64_t NS = (E + seg - 1) / seg, Q = P->pool_block / seg;
         int64_t NB = (NS + Q - 1) / Q;
         if (NB < 1) NB = 1;
-        const int64_t sigma = e >> 6;
+        const int64_t sigma = e / seg;
         const uint64_t beta = (uint64_t)(sigma % NB);
-        const uint64_t rank = (uint64_t)(64 * (sigma / NB) + (e & 63));
+        const uint64_t rank = (uint64_t)(seg * (sigma / NB) + (e % seg));
         uint32_t ctr[4] = {(uint32_t)beta, 0xFFFFFFFEu, (uint32_t)t, (uint32_t)((rank & 1023) + 1024 * (rank >> 12))};
         uint32_t w[4];
         oracle_philox4x32_10(ctr, key, w);

@@ -121,6 +121,8 @@ class Problem:
     pool_mode: int = 0                        # pooled sampler: 0 = 16-bit picks, consecutive blocks; 1 = distinct picks,
                                               # interleaved blocks (negatives_distinct)
     pool_line: int = 1                        # pool_mode 1: consecutive points per pool line (a power of two)
+    pool_segment: int = 64                    # pool_mode 1: consecutive CSR positions dealt to a block together (a power
+                                              # of two >= 64 that divides pool_block; = pool_block: consecutive blocks)
     sampled_far_field: bool = False           # opt-in: Eq. 5's sum over approximated cells estimated from the samples
     mean_gradient: bool = False               # opt-in: the gradient also flows through the cell means mu_r(theta)
 
@@ -141,7 +143,8 @@ class Problem:
             P_, l_ = self.pool_size, self.pool_line
             assert P_ >= 2 and P_ & (P_ - 1) == 0 and P_ <= 4096, "distinct picks: the pool size is a power of two, 2..4096"
             assert l_ >= 1 and l_ & (l_ - 1) == 0 and P_ % l_ == 0 and self.n_neg <= P_ // l_, "lines: a power of two, s <= lines"
-            assert self.pool_block % 64 == 0, "distinct picks: blocks are whole segments of 64 positions"
+            g_ = self.pool_segment
+            assert g_ >= 64 and g_ & (g_ - 1) == 0 and self.pool_block % g_ == 0, "blocks are whole segments; segments a power of two >= 64"
             assert self.batches_per_epoch == 1, "distinct picks: one step per epoch"
         else:
             assert self.pool_line == 1, "pool lines belong to pool_mode 1"
@@ -159,7 +162,7 @@ class Problem:
                  n_clusters=w["n_clusters"], n_neg=w["n_neg"], noise_count=w["noise_count"], seed=w["seed"],
                  n_epochs=w["n_epochs"], lr0=w["lr0"], weights=w.get("weights"),
                  cluster_group=w.get("cluster_group"), pool_size=w.get("pool_size", 0), pool_block=w.get("pool_block", 0),
-                 pool_mode=w.get("pool_mode", 0), pool_line=w.get("pool_line", 1),
+                 pool_mode=w.get("pool_mode", 0), pool_line=w.get("pool_line", 1), pool_segment=w.get("pool_segment", 64),
                  batches_per_epoch=w.get("batches_per_epoch", 1), sampled_far_field=w.get("sampled_far_field", False),
                  mean_gradient=w.get("mean_gradient", False))
         d.update(over)
@@ -259,15 +262,16 @@ _POOL_PICK_STREAM = 0xFFFFFFFE
 
 def distinct_pool_layout(P: Problem):
     """Pooled sampler with distinct picks: how the CSR positions are dealt to pool blocks.  The positions are cut
-    into segments of 64; with Q = pool_block / 64 segments per block there are NB = ceil(NS / Q) blocks for NS
-    segments, and segment sigma belongs to block sigma mod NB: a block is made of Q segments spread evenly over the
-    whole edge list, so the edges that share a pool come from Q different neighbourhoods of the graph.
-    Returns (NB, block(e), rank(e)): rank(e) = 64 (sigma div NB) + (e mod 64) numbers a block's positions."""
-    E = P.n_edges
-    NS = (E + 63) // 64
-    Q = P.pool_block // 64
+    into segments of g = pool_segment; with Q = pool_block / g segments per block there are NB = ceil(NS / Q) blocks
+    for NS segments, and segment sigma belongs to block sigma mod NB: a block is made of Q segments spread evenly
+    over the whole edge list, so the edges that share a pool come from Q different neighbourhoods of the graph
+    (g = pool_block: one segment per block, i.e. blocks of consecutive positions).
+    Returns (NB, block(e), rank(e)): rank(e) = g (sigma div NB) + (e mod g) numbers a block's positions."""
+    E, g = P.n_edges, P.pool_segment
+    NS = (E + g - 1) // g
+    Q = P.pool_block // g
     NB = max(1, (NS + Q - 1) // Q)
-    return NB, (lambda e: (e >> 6) % NB), (lambda e: 64 * ((e >> 6) // NB) + (e & 63))
+    return NB, (lambda e: (e // g) % NB), (lambda e: g * ((e // g) // NB) + (e % g))
 
 
 def distinct_pool_entry(P: Problem, beta: int, t: int, u: int) -> int:

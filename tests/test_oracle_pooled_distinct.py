@@ -15,16 +15,16 @@ from tests.oracle_impls import IMPLS
 BOTH = pytest.mark.parametrize("impl", ["py", "c"])
 
 
-def _problem(n, seed, s, P, G, line, deg=6.0):
+def _problem(n, seed, s, P, G, line, deg=6.0, segment=64):
     row_ptr, col = random_symmetric_graph(n, deg, seed)
     return dict(n=n, row_ptr=row_ptr, col_idx=col, cluster_of=np.zeros(n, int), n_clusters=1, n_neg=s, noise_count=float(s),
-                seed=(seed << 33) | 5, pool_size=P, pool_block=G, pool_mode=1, pool_line=line)
+                seed=(seed << 33) | 5, pool_size=P, pool_block=G, pool_mode=1, pool_line=line, pool_segment=segment)
 
 
 def test_both_implementations_draw_the_same_negatives():
-    for (n, s, P, G, line) in ((300, 5, 64, 128, 4), (1000, 3, 16, 64, 1), (777, 7, 256, 1024, 16), (50, 4, 8, 192, 2),
-                               (5000, 5, 2048, 4096, 16), (40, 2, 4, 8192, 2)):
-        kw = _problem(n, 3, s, P, G, line)
+    for (n, s, P, G, line, seg) in ((300, 5, 64, 128, 4, 64), (1000, 3, 16, 64, 1, 64), (777, 7, 256, 1024, 16, 256), (50, 4, 8, 192, 2, 64),
+                                    (5000, 5, 2048, 4096, 16, 1024), (40, 2, 4, 8192, 2, 128), (3000, 5, 64, 2048, 8, 2048)):
+        kw = _problem(n, 3, s, P, G, line, segment=seg)
         a, b = IMPLS["py"](**kw), IMPLS["c"](**kw)
         for t in (0, 6):
             ma = a.negatives(t, 0, min(len(kw["col_idx"]), 3000))
@@ -48,6 +48,10 @@ def test_picks_of_an_edge_lie_in_different_lines_and_blocks_are_interleaved():
     assert block(0) == block(63) == block(64 * NB) and block(64) == 1 and rank(64 * NB + 3) == 64 + 3
     ranks = sorted(rank(e) for e in range(E) if block(e) == 2)
     assert ranks == list(range(len(ranks))) and len(ranks) <= 256
+    # one segment per block: blocks of consecutive positions
+    Pc = po.Problem(**dict(kw, pool_segment=256))
+    NBc, blockc, rankc = po.distinct_pool_layout(Pc)
+    assert NBc == -(-E // 256) and all(blockc(e) == e // 256 and rankc(e) == e % 256 for e in range(0, E, 101))
     # the entries of a line are cyclically consecutive points; entries of the pool are what the negatives consist of
     pool = [po.distinct_pool_entry(P, 2, 1, u) for u in range(64)]
     for g in range(L):
