@@ -74,7 +74,27 @@ typedef struct {
                                /* NOMAD_FAR_FIELD_SAMPLED (opt-in estimate of it, see below)            */
     int32_t mean_gradient;     /* 0: the cell means are constants of an epoch (no gradient flows through */
                                /* them); 1: opt-in, see below                                            */
+    int32_t pool_mode;         /* pooled sampler: NOMAD_POOL_PICKS16 (0) or NOMAD_POOL_DISTINCT (1), see below; */
+                               /* 0 when pool_size is 0                                                  */
+    int32_t pool_line;         /* NOMAD_POOL_DISTINCT: consecutive points per pool line, a power of two   */
+                               /* (1 = every pool entry drawn on its own); 0 is read as 1                 */
+    int32_t pool_segment;      /* NOMAD_POOL_DISTINCT: consecutive CSR positions dealt to a block together, a */
+                               /* power of two >= 64 that divides pool_block; 0 is read as 64; not used by */
+                               /* NOMAD_POOL_PICKS16                                                      */
+    int32_t edge_weights;      /* NOMAD_WEIGHTS_GIVEN (0): p(j|i) from nomad_set_graph's weights;          */
+                               /* NOMAD_WEIGHTS_INVERSE_RANK (1): from the position of j in i's row, Eq. 7 */
 } nomad_config;
+
+/*
+ * Edge weights from ranks (edge_weights = NOMAD_WEIGHTS_INVERSE_RANK; nomad_set_graph's `weights` must then be
+ * NULL).  Eq. 7 models p(j|i) by the rank of j among i's nearest neighbours.  With the row of head i listing its
+ * k_i neighbours in ascending distance (which is what nomad_knn_in_clusters returns), the edge at position rho =
+ * 1..k_i of the row gets p(j|i) = exp(1/rho) / sum_{rho' = 1..k_i} exp(1/rho'): ranks counted from 1 and the
+ * normaliser taken over the row's own k_i terms, so that every row is a distribution (as printed, Eq. 7 has a
+ * 1/0 at rank 0 and k + 1 terms in the normaliser).  Computed on the device in float64, stored as float32.
+ */
+#define NOMAD_WEIGHTS_GIVEN 0
+#define NOMAD_WEIGHTS_INVERSE_RANK 1
 
 /*
  * Gradient through the means (opt-in; needs far_field = NOMAD_FAR_FIELD_EXACT and batches_per_epoch = 1; has no
@@ -114,6 +134,29 @@ typedef struct {
  * applies when pool_block is a multiple of 1024; other values run the general kernels.
  */
 #define NOMAD_MAX_POOL 4096
+#define NOMAD_POOL_PICKS16 0
+#define NOMAD_POOL_DISTINCT 1
+
+/*
+ * Pooled sampler with distinct picks (pool_mode = NOMAD_POOL_DISTINCT; opt-in like the variant above, same
+ * restrictions, plus batches_per_epoch = 1).  Section 3.1 defines the noise samples of ONE edge as i.i.d. draws from
+ * the noise distribution; this variant keeps exactly that and gives up only independence between different edges:
+ *   - blocks: the CSR positions are cut into segments of g = pool_segment positions; with Q = pool_block / g segments
+ *     per block and NS segments there are NB = ceil(NS / Q) blocks; segment sigma belongs to block beta = sigma mod NB
+ *     and position e has rank g (sigma div NB) + (e mod g) in its block.  A block is thus Q segments spread evenly
+ *     over the edge list (g = pool_block: blocks of consecutive positions);
+ *   - pool of block beta in epoch t: L = pool_size / pool_line lines of pool_line cyclically consecutive points
+ *     (after point n-1 comes point 0); line gamma starts at floor(x n / 2^32), x = word (gamma & 3) of
+ *     Philox(counter (beta, 0xFFFFFFFF, t, gamma >> 2), key seed); entry u is point number (u div L) of line (u mod L);
+ *   - picks: an edge takes one word W = word ((rank >> 10) & 3) of Philox(counter (beta, 0xFFFFFFFE, t,
+ *     (rank & 1023) + 1024 (rank >> 12))); with lg = log2(pool_size): u_0 = the top lg bits of W, c = 2 (bits
+ *     1..lg-1 of W) + 1, and slot k takes entry (u_0 + k c) mod pool_size.
+ * pool_size is a power of two (2..NOMAD_MAX_POOL) and s <= L: the odd stride c then puts the s picks of an edge into s
+ * different lines, whose starts are independent uniform draws, so the s negatives are independent and uniform over
+ * the points.  Negatives of different edges of a block share lines and are dependent; spreading a block over the
+ * edge list (small g) makes the edges that share a pool come from unrelated neighbourhoods.  The fast kernel
+ * applies when pool_block is 1024, 2048, 4096 or 8192 and its tables fit LDS; other shapes run the general kernels.
+ */
 
 /* Create a context.  Allocates nothing on the device yet.  *out is set only on success. */
 int nomad_create(const nomad_config* cfg, nomad_ctx** out);
@@ -184,6 +227,44 @@ int nomad_get_mean_field(nomad_ctx* ctx, float* A, float* B, int mem);
 
 /* Number of directed edges E of the current graph (0 before nomad_set_graph). */
 int64_t nomad_num_edges(const nomad_ctx* ctx);
+
+/*
+ * Which gradient-scatter path nomad_set_graph chose for this context (0 before it):
+ *   NOMAD_PATH_ATOMIC_FP32   scatter_mode = NOMAD_SCATTER_ATOMIC: fp32 global atomics, order not reproducible
+ *   NOMAD_PATH_BINNED        deterministic: forces binned by destination tile in the edge pass, summed per tile in LDS
+ *   NOMAD_PATH_BINNED_POOLED deterministic, pooled sampler: the same with the pool's rows and force sums in LDS
+ *   NOMAD_PATH_FIXED_ATOMICS deterministic fallback: 64-bit fixed-point global atomics (several times slower); taken
+ *                            when the per-tile tables do not fit LDS (s > 8, more than 67 M points) or the record pool
+ *                            could not be allocated -- nomad_set_graph then still returns NOMAD_OK and
+ *                            nomad_last_error says why
+ * Results of the three deterministic paths agree to rounding (each is reproducible run to run).
+ */
+#define NOMAD_PATH_ATOMIC_FP32 1
+#define NOMAD_PATH_BINNED 2
+#define NOMAD_PATH_BINNED_POOLED 3
+#define NOMAD_PATH_FIXED_ATOMICS 4
+int nomad_scatter_path(const nomad_ctx* ctx);
+
+/* Device memory the context holds, in bytes (graph, embedding, work space; 0 before nomad_set_graph). */
+int64_t nomad_device_bytes(const nomad_ctx* ctx);
+
+/*
+ * Launch-shape knobs for experiments and tests; results do not depend on them beyond rounding order (every setting
+ * is reproducible run to run).  Call between nomad_create and nomad_set_graph (NOMAD_E_ORDER afterwards).
+ *   NOMAD_TUNE_EDGE_BLOCK      lanes per workgroup of the binned edge pass: 1024 (default) or 512
+ *   NOMAD_TUNE_WORKGROUPS_PER_CU persistent workgroups per compute unit, 1..8 (default 1; 2 with 512 lanes)
+ *   NOMAD_TUNE_SCATTER_PATH    0 (default: the fastest path that fits) or NOMAD_PATH_FIXED_ATOMICS to force the fallback
+ *   NOMAD_TUNE_POOL_KERNEL     1 (default) or 0: run the pooled samplers on the general kernels
+ *   NOMAD_TUNE_RECORD_PHASES   0 (default: chosen from the record volume) or 1..64: the edge pass of an epoch runs in
+ *                              this many phases over ranges of CSR positions, each followed by the accumulation of its
+ *                              records, so that the record pool holds one phase at a time
+ */
+#define NOMAD_TUNE_EDGE_BLOCK 1
+#define NOMAD_TUNE_WORKGROUPS_PER_CU 2
+#define NOMAD_TUNE_SCATTER_PATH 3
+#define NOMAD_TUNE_POOL_KERNEL 4
+#define NOMAD_TUNE_RECORD_PHASES 5
+int nomad_tune(nomad_ctx* ctx, int knob, int value);
 
 /* ---- kernel timing (HIP events on the context's stream, around each launch) ---- */
 
@@ -381,7 +462,8 @@ int nomad_random_triplet_accuracy_noalloc(const float* X, int64_t n, int32_t d, 
 int nomad_pca_init(const float* X, int64_t n, int32_t d, float std0, float* theta_out, double* stats, int mem, int32_t device,
                    void* stream);
 
-/* Text of the last error of this context ("" if none).  Valid until the next call on it. */
+/* Text of the last error of this context ("" if none), or, after a successful nomad_set_graph that had to take a
+ * slower path, the reason (see nomad_scatter_path).  Valid until the next call on it. */
 const char* nomad_last_error(const nomad_ctx* ctx);
 
 #ifdef __cplusplus

@@ -23,7 +23,7 @@ ERRORS = {-1: "NOMAD_E_INVALID_ARG", -2: "NOMAD_E_BAD_GRAPH", -3: "NOMAD_E_ORDER
 
 EXPORTS = ["nomad_create", "nomad_destroy", "nomad_set_graph", "nomad_set_embedding", "nomad_epoch", "nomad_loss",
            "nomad_get_embedding", "nomad_get_gradient", "nomad_get_negatives", "nomad_get_means",
-           "nomad_get_mean_field", "nomad_num_edges", "nomad_profile", "nomad_profile_read", "nomad_last_error",
+           "nomad_get_mean_field", "nomad_num_edges", "nomad_scatter_path", "nomad_device_bytes", "nomad_tune", "nomad_profile", "nomad_profile_read", "nomad_last_error",
            "nomad_copy_probe", "nomad_gather_probe", "nomad_scatter_probe", "nomad_knn_in_clusters", "nomad_kmeans_lloyd", "nomad_neighbourhood_preservation",
            "nomad_random_triplet_accuracy", "nomad_random_triplet_accuracy_noalloc", "nomad_pca_init", "nomad_kmeans_lsh_init"]
 
@@ -33,7 +33,14 @@ class NomadConfig(C.Structure):
                 ("noise_count", C.c_float), ("n_epochs", C.c_int32), ("lr0", C.c_float), ("seed", C.c_uint64),
                 ("scatter_mode", C.c_int32), ("batches_per_epoch", C.c_int32), ("device", C.c_int32),
                 ("stream", C.c_void_p), ("pool_size", C.c_int32), ("pool_block", C.c_int32), ("far_field", C.c_int32),
-                ("mean_gradient", C.c_int32)]
+                ("mean_gradient", C.c_int32), ("pool_mode", C.c_int32), ("pool_line", C.c_int32), ("pool_segment", C.c_int32),
+                ("edge_weights", C.c_int32)]
+
+
+PATH_ATOMIC_FP32, PATH_BINNED, PATH_BINNED_POOLED, PATH_FIXED_ATOMICS = 1, 2, 3, 4
+PATH_NAMES = {0: "none", 1: "atomic_fp32", 2: "binned", 3: "binned_pooled", 4: "fixed_point_atomics"}
+TUNE = {"edge_block": 1, "workgroups_per_cu": 2, "scatter_path": 3, "pool_kernel": 4, "record_phases": 5}
+POOL_PICKS16, POOL_DISTINCT = 0, 1
 
 
 class NomadError(RuntimeError):
@@ -72,6 +79,10 @@ def load_library():
     lib.nomad_get_mean_field.argtypes = [vp, vp, vp, C.c_int]
     lib.nomad_num_edges.argtypes = [vp]
     lib.nomad_num_edges.restype = i64
+    lib.nomad_scatter_path.argtypes = [vp]
+    lib.nomad_device_bytes.argtypes = [vp]
+    lib.nomad_device_bytes.restype = i64
+    lib.nomad_tune.argtypes = [vp, C.c_int, C.c_int]
     lib.nomad_profile.argtypes = [vp, C.c_int]
     lib.nomad_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.nomad_copy_probe.argtypes = [vp, vp, C.c_uint64, vp]
@@ -329,7 +340,9 @@ class Nomad:
 
     def __init__(self, n_points, n_clusters, n_neg, noise_count=0.0, n_epochs=1, lr0=1.0, seed=0,
                  scatter_mode=SCATTER_DETERMINISTIC, device=0, stream=None, pool_size=0, pool_block=0, batches_per_epoch=1,
-                 sampled_far_field=False, mean_gradient=False):
+                 sampled_far_field=False, mean_gradient=False, pool_mode=0, pool_line=0, pool_segment=0, inverse_rank_weights=False,
+                 tune=None):
+        """tune: {knob name: value} passed to nomad_tune before the graph is set (see TUNE)."""
         self.lib = load_library()
         if stream is None:
             import torch
@@ -337,7 +350,8 @@ class Nomad:
         self.cfg = NomadConfig(C.sizeof(NomadConfig), int(n_points), int(n_clusters), int(n_neg), float(noise_count),
                                int(n_epochs), float(lr0), int(seed), int(scatter_mode), int(batches_per_epoch), int(device),
                                C.c_void_p(int(stream) if stream else None), int(pool_size), int(pool_block),
-                               FAR_FIELD_SAMPLED if sampled_far_field else FAR_FIELD_EXACT, int(bool(mean_gradient)))
+                               FAR_FIELD_SAMPLED if sampled_far_field else FAR_FIELD_EXACT, int(bool(mean_gradient)),
+                               int(pool_mode), int(pool_line), int(pool_segment), int(bool(inverse_rank_weights)))
         self.n, self.R, self.s = int(n_points), int(n_clusters), int(n_neg)
         self.device = int(device)
         self.ctx = C.c_void_p()
@@ -345,6 +359,8 @@ class Nomad:
         if rc:
             self.ctx = C.c_void_p()
             raise NomadError(rc, "nomad_create")
+        for knob, value in (tune or {}).items():
+            self._check(self.lib.nomad_tune(self.ctx, TUNE[knob], int(value)))
 
     @classmethod
     def from_workload(cls, w, scatter_mode=SCATTER_DETERMINISTIC, device=0, **over):
@@ -353,7 +369,8 @@ class Nomad:
                   pool_size=getattr(w, "pool_size", 0), pool_block=getattr(w, "pool_block", 0),
                   batches_per_epoch=getattr(w, "batches_per_epoch", 1),
                   sampled_far_field=getattr(w, "sampled_far_field", False),
-                  mean_gradient=getattr(w, "mean_gradient", False))
+                  mean_gradient=getattr(w, "mean_gradient", False), pool_mode=getattr(w, "pool_mode", 0),
+                  pool_line=getattr(w, "pool_line", 0), pool_segment=getattr(w, "pool_segment", 0))
         kw.update(over)
         nm = cls(**kw)
         nm.set_graph(w.row_ptr, w.col_idx, w.weights, w.cluster_of, w.cluster_group)
@@ -438,6 +455,17 @@ class Nomad:
         self._check(self.lib.nomad_get_mean_field(self.ctx, A.ctypes.data_as(C.c_void_p), B.ctypes.data_as(C.c_void_p),
                                                   NOMAD_HOST))
         return A, B
+
+    def scatter_path(self):
+        """nomad_scatter_path: one of the PATH_* constants."""
+        return int(self.lib.nomad_scatter_path(self.ctx))
+
+    def device_bytes(self):
+        return int(self.lib.nomad_device_bytes(self.ctx))
+
+    def note(self):
+        """Text nomad_last_error holds (after set_graph: why a slower path is in use, if one is)."""
+        return self.lib.nomad_last_error(self.ctx).decode()
 
     def num_edges(self):
         return int(self.lib.nomad_num_edges(self.ctx))

@@ -10,6 +10,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "nomad.h"
@@ -68,6 +69,13 @@ struct nomad_ctx {
     double *loss_partial = nullptr, *loss_out = nullptr;
     uint32_t edge_grid = 0;
     int* flags = nullptr;
+    // launch-shape knobs (nomad_tune) and what set_graph made of them
+    int tune_edge_block = 0, tune_wg_per_cu = 0, tune_path = 0, tune_pool_kernel = 1, tune_phases = 0;
+    int path = 0;                   // NOMAD_PATH_* in use
+    bool distinct_kernel = false;   // the pooled edge pass is the one for distinct picks
+    uint32_t pool_blocks = 1;       // distinct picks: number of blocks
+    std::unordered_map<const void*, size_t> allocations;   // device memory held, by pointer
+    int64_t device_bytes = 0;
     // timing
     bool profiling = false;
     KernelTimer timers[NOMAD_K_COUNT];
@@ -100,30 +108,39 @@ int fail(nomad_ctx* c, int code, const char* fmt, ...) {
 template <typename T>
 int dev_alloc(nomad_ctx* c, T** p, size_t count) {
     *p = nullptr;
-    HIP_TRY(c, hipMalloc((void**)p, std::max<size_t>(count, 1) * sizeof(T)));
+    const size_t bytes = std::max<size_t>(count, 1) * sizeof(T);
+    HIP_TRY(c, hipMalloc((void**)p, bytes));
+    c->allocations[*p] = bytes;
+    c->device_bytes += (int64_t)bytes;
     return NOMAD_OK;
 }
 
 template <typename T>
-void dev_free(T*& p) {
-    if (p) (void)hipFree(p);
+void dev_free(nomad_ctx* c, T*& p) {
+    if (p) {
+        auto it = c->allocations.find(p);
+        if (it != c->allocations.end()) { c->device_bytes -= (int64_t)it->second; c->allocations.erase(it); }
+        (void)hipFree(p);
+    }
     p = nullptr;
 }
 
 void free_graph(nomad_ctx* c) {
-    dev_free(c->row_ptr); dev_free(c->col); dev_free(c->cluster_of); dev_free(c->group_of_cluster);
-    dev_free(c->pe); dev_free(c->counts); dev_free(c->gbase); dev_free(c->gcount); dev_free(c->chunk_start);
-    dev_free(c->gomega); dev_free(c->hinfo); dev_free(c->gmembers); dev_free(c->cmembers); dev_free(c->chunks); dev_free(c->mean_partial);
-    dev_free(c->theta); dev_free(c->g); dev_free(c->ghead); dev_free(c->mu); dev_free(c->B); dev_free(c->cinfo);
-    dev_free(c->cell_slot); dev_free(c->group_slots);
-    dev_free(c->A); dev_free(c->gfix); dev_free(c->loss_partial); dev_free(c->loss_out);
-    dev_free(c->cS); dev_free(c->chead); dev_free(c->Gfix); dev_free(c->gmean);
+    dev_free(c, c->row_ptr); dev_free(c, c->col); dev_free(c, c->cluster_of); dev_free(c, c->group_of_cluster);
+    dev_free(c, c->pe); dev_free(c, c->counts); dev_free(c, c->gbase); dev_free(c, c->gcount); dev_free(c, c->chunk_start);
+    dev_free(c, c->gomega); dev_free(c, c->hinfo); dev_free(c, c->gmembers); dev_free(c, c->cmembers); dev_free(c, c->chunks); dev_free(c, c->mean_partial);
+    dev_free(c, c->theta); dev_free(c, c->g); dev_free(c, c->ghead); dev_free(c, c->mu); dev_free(c, c->B); dev_free(c, c->cinfo);
+    dev_free(c, c->cell_slot); dev_free(c, c->group_slots);
+    dev_free(c, c->A); dev_free(c, c->gfix); dev_free(c, c->loss_partial); dev_free(c, c->loss_out);
+    dev_free(c, c->cS); dev_free(c, c->chead); dev_free(c, c->Gfix); dev_free(c, c->gmean);
     c->through_means = false;
-    dev_free(c->flags);
-    dev_free(c->pool); dev_free(c->chunk_prev); dev_free(c->chain_head); dev_free(c->chain_fill); dev_free(c->wg_pool_begin);
-    dev_free(c->head); dev_free(c->overflow);
+    dev_free(c, c->flags);
+    dev_free(c, c->pool); dev_free(c, c->chunk_prev); dev_free(c, c->chain_head); dev_free(c, c->chain_fill); dev_free(c, c->wg_pool_begin);
+    dev_free(c, c->head); dev_free(c, c->overflow);
     c->binned = false;
     c->pool_rounds = 0;
+    c->distinct_kernel = false;
+    c->path = 0;
     c->has_graph = c->has_theta = c->has_grad = false;
     c->E = 0;
 }
@@ -178,6 +195,9 @@ void destroy_event_pool(nomad_ctx* c) {
     c->event_pool.clear();
 }
 
+inline bool is_power_of_two(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+inline uint32_t log2_of(int64_t v) { uint32_t b = 0; while (((int64_t)1 << (b + 1)) <= v) ++b; return b; }
+
 EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
     EdgeArgs a{};
     a.row_ptr = c->row_ptr; a.col = c->col; a.pe = c->pe; a.theta = c->theta;
@@ -188,6 +208,9 @@ EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
     a.noise_count = c->noise_count; a.omega0 = c->omega0;
     a.key0 = (uint32_t)c->cfg.seed; a.key1 = (uint32_t)(c->cfg.seed >> 32); a.epoch = t;
     a.pool_size = (uint32_t)c->cfg.pool_size; a.pool_block = (uint32_t)c->cfg.pool_block;
+    a.pool_mode = (uint32_t)c->cfg.pool_mode;
+    a.pool_line_bits = log2_of(c->cfg.pool_line); a.pool_segment_bits = log2_of(c->cfg.pool_segment);
+    a.pool_blocks = c->pool_blocks;
     a.s = c->cfg.n_neg; a.n = c->n; a.row_begin = 0; a.row_end = c->n;
     a.g = c->g; a.ghead = c->ghead; a.gfix = c->gfix; a.loss_partial = c->loss_partial;
     a.cS = nullptr;   // set by nomad_epoch when the gradient flows through the means
@@ -222,6 +245,8 @@ BinArgs bin_args(nomad_ctx* c) {
 constexpr size_t kMaxLdsBytes = 160 * 1024 - 256;   // per workgroup on gfx950, less the kernels' static LDS
 
 size_t edge_pass_lds_bytes(const nomad_ctx* c) {
+    if (c->pool_rounds && c->distinct_kernel)
+        return distinct_lds_bytes(c->n_bins, (uint32_t)c->cfg.pool_size, (uint32_t)(c->cfg.pool_size / c->cfg.pool_line), c->pool_rounds);
     return c->pool_rounds ? pooled_lds_bytes(c->n_bins, c->cfg.pool_block, (uint32_t)c->cfg.pool_size)
                           : binned_lds_bytes(c->n_bins, c->cfg.n_neg, c->bin_block);
 }
@@ -232,7 +257,11 @@ using EdgePassKernel = void (*)(const EdgeArgs, const BinArgs);
 template <int S, typename Fn>
 void with_edge_pass_kernel_s(const nomad_ctx* c, Fn fn) {
     EdgePassKernel k = k_edges_binned<S, 1024>;
-    if (c->pool_rounds == 1) k = k_edges_pooled<S, 1, 1024>;
+    if (c->distinct_kernel && c->pool_rounds == 1) k = k_edges_pooled_distinct<S, 1>;
+    else if (c->distinct_kernel && c->pool_rounds == 2) k = k_edges_pooled_distinct<S, 2>;
+    else if (c->distinct_kernel && c->pool_rounds == 4) k = k_edges_pooled_distinct<S, 4>;
+    else if (c->distinct_kernel && c->pool_rounds == 8) k = k_edges_pooled_distinct<S, 8>;
+    else if (c->pool_rounds == 1) k = k_edges_pooled<S, 1, 1024>;
     else if (c->pool_rounds == 2) k = k_edges_pooled<S, 2, 1024>;
     else if (c->pool_rounds == 4) k = k_edges_pooled<S, 4, 1024>;
     else if (c->pool_rounds == 8) k = k_edges_pooled<S, 8, 1024>;
@@ -351,6 +380,16 @@ int nomad_create(const nomad_config* cfg, nomad_ctx** out) {
     if ((cfg->far_field != NOMAD_FAR_FIELD_EXACT && cfg->far_field != NOMAD_FAR_FIELD_SAMPLED) ||
         (cfg->far_field == NOMAD_FAR_FIELD_SAMPLED && cfg->pool_size > 0))
         return NOMAD_E_INVALID_ARG;
+    if (cfg->pool_mode != NOMAD_POOL_PICKS16 && cfg->pool_mode != NOMAD_POOL_DISTINCT) return NOMAD_E_INVALID_ARG;
+    if (cfg->pool_mode == NOMAD_POOL_PICKS16 && (cfg->pool_line > 1 || cfg->pool_line < 0 || cfg->pool_segment < 0)) return NOMAD_E_INVALID_ARG;
+    if (cfg->pool_mode == NOMAD_POOL_DISTINCT) {
+        const int line = cfg->pool_line ? cfg->pool_line : 1, seg = cfg->pool_segment ? cfg->pool_segment : 64;
+        if (cfg->pool_size < 2 || !is_power_of_two(cfg->pool_size) || !is_power_of_two(line) || line > cfg->pool_size ||
+            cfg->n_neg > cfg->pool_size / line || seg < 64 || !is_power_of_two(seg) || cfg->pool_block % seg != 0 ||
+            cfg->batches_per_epoch != 1)
+            return NOMAD_E_INVALID_ARG;
+    }
+    if (cfg->edge_weights != NOMAD_WEIGHTS_GIVEN && cfg->edge_weights != NOMAD_WEIGHTS_INVERSE_RANK) return NOMAD_E_INVALID_ARG;
     if ((cfg->mean_gradient != 0 && cfg->mean_gradient != 1) ||
         (cfg->mean_gradient && (cfg->far_field == NOMAD_FAR_FIELD_SAMPLED || cfg->batches_per_epoch > 1)))
         return NOMAD_E_INVALID_ARG;
@@ -360,6 +399,8 @@ int nomad_create(const nomad_config* cfg, nomad_ctx** out) {
     nomad_ctx* c = new (std::nothrow) nomad_ctx();
     if (!c) return NOMAD_E_OOM;
     c->cfg = *cfg;
+    if (c->cfg.pool_line == 0) c->cfg.pool_line = 1;
+    if (c->cfg.pool_segment == 0) c->cfg.pool_segment = 64;
     c->stream = (hipStream_t)cfg->stream;
     c->n = cfg->n_points;
     c->R = cfg->n_clusters;
@@ -392,6 +433,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
     const int32_t R = c->R;
     hipStream_t st = c->stream;
     int rc;
+    std::string fallback_note;
 #define TRY(x) do { rc = (x); if (rc != NOMAD_OK) { free_graph(c); return rc; } } while (0)
 #define HTRY(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { free_graph(c); return fail(c, e_ == hipErrorOutOfMemory ? NOMAD_E_OOM : NOMAD_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); } } while (0)
 
@@ -420,11 +462,14 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
     TRY(dev_alloc(c, &c->cluster_of, (size_t)n));
     HTRY(hipMemcpy(c->cluster_of, cluster_of, sizeof(int32_t) * (size_t)n, in_kind(mem)));
     float* wdev = nullptr;
+    const bool by_rank = c->cfg.edge_weights == NOMAD_WEIGHTS_INVERSE_RANK;
+    if (by_rank && weights) { free_graph(c); return fail(c, NOMAD_E_INVALID_ARG, "edge_weights = NOMAD_WEIGHTS_INVERSE_RANK takes no weights array"); }
+    if (by_rank) TRY(dev_alloc(c, &c->pe, (size_t)E));
     if (weights) {
         TRY(dev_alloc(c, &c->pe, (size_t)E));
         TRY(dev_alloc(c, &wdev, (size_t)E));
         hipError_t e_ = E ? hipMemcpy(wdev, weights, sizeof(float) * (size_t)E, in_kind(mem)) : hipSuccess;
-        if (e_ != hipSuccess) { dev_free(wdev); free_graph(c); return fail(c, NOMAD_E_HIP, "copy of weights: %s", hipGetErrorString(e_)); }
+        if (e_ != hipSuccess) { dev_free(c, wdev); free_graph(c); return fail(c, NOMAD_E_HIP, "copy of weights: %s", hipGetErrorString(e_)); }
     }
     std::vector<int32_t> hgroup;
     c->grouped = false;
@@ -432,16 +477,16 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         hgroup.resize(R);
         hipError_t e_ = hipMemcpy(hgroup.data(), cluster_group, sizeof(int32_t) * (size_t)R,
                                   mem == NOMAD_DEVICE ? hipMemcpyDeviceToHost : hipMemcpyHostToHost);
-        if (e_ != hipSuccess) { dev_free(wdev); free_graph(c); return fail(c, NOMAD_E_HIP, "copy of cluster_group: %s", hipGetErrorString(e_)); }
+        if (e_ != hipSuccess) { dev_free(c, wdev); free_graph(c); return fail(c, NOMAD_E_HIP, "copy of cluster_group: %s", hipGetErrorString(e_)); }
         for (int32_t r = 0; r < R; ++r)
-            if (hgroup[r] < 0 || hgroup[r] >= R) { dev_free(wdev); free_graph(c); return fail(c, NOMAD_E_BAD_GRAPH, "cluster_group[%d] = %d is outside 0..|R|-1", r, hgroup[r]); }
+            if (hgroup[r] < 0 || hgroup[r] >= R) { dev_free(c, wdev); free_graph(c); return fail(c, NOMAD_E_BAD_GRAPH, "cluster_group[%d] = %d is outside 0..|R|-1", r, hgroup[r]); }
         for (int32_t r = 1; r < R; ++r)
             if (hgroup[r] != hgroup[0]) c->grouped = true;   // one label everywhere == nothing approximated
-        if (c->grouped && c->cfg.pool_size > 0) { dev_free(wdev); free_graph(c); return fail(c, NOMAD_E_INVALID_ARG, "the pooled sampler needs a single sampling population (cluster_group = NULL)"); }
+        if (c->grouped && c->cfg.pool_size > 0) { dev_free(c, wdev); free_graph(c); return fail(c, NOMAD_E_INVALID_ARG, "the pooled sampler needs a single sampling population (cluster_group = NULL)"); }
         if (c->grouped) {
             rc = dev_alloc(c, &c->group_of_cluster, (size_t)R);
             if (rc == NOMAD_OK && hipMemcpy(c->group_of_cluster, hgroup.data(), sizeof(int32_t) * (size_t)R, hipMemcpyHostToDevice) != hipSuccess) rc = fail(c, NOMAD_E_HIP, "upload of cluster_group failed");
-            if (rc != NOMAD_OK) { dev_free(wdev); free_graph(c); return rc; }
+            if (rc != NOMAD_OK) { dev_free(c, wdev); free_graph(c); return rc; }
         }
     }
 
@@ -453,7 +498,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
     if (rc == NOMAD_OK) rc = dev_alloc(c, &first, (size_t)R);
     if (rc == NOMAD_OK) rc = dev_alloc(c, &gfirst, (size_t)R);
     if (rc == NOMAD_OK) rc = dev_alloc(c, &boundaries, 2);
-    auto cleanup_tmp = [&]() { dev_free(wdev); dev_free(first); dev_free(gfirst); dev_free(boundaries); };
+    auto cleanup_tmp = [&]() { dev_free(c, wdev); dev_free(c, first); dev_free(c, gfirst); dev_free(c, boundaries); };
     if (rc != NOMAD_OK) { cleanup_tmp(); free_graph(c); return rc; }
 #define HTRY2(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { cleanup_tmp(); free_graph(c); return fail(c, e_ == hipErrorOutOfMemory ? NOMAD_E_OOM : NOMAD_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); } } while (0)
     HTRY2(hipMemsetAsync(c->flags, 0, sizeof(int) * kFlagCount, st));
@@ -466,7 +511,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
     HTRY2(hipMemcpyAsync(hflags, c->flags, sizeof(hflags), hipMemcpyDeviceToHost, st));
     HTRY2(hipStreamSynchronize(st));
     if (hflags[kFlagRowPtr]) { cleanup_tmp(); free_graph(c); return fail(c, NOMAD_E_BAD_GRAPH, "row_ptr must start at 0 and be non-decreasing"); }
-    hipLaunchKernelGGL(k_check_rows, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->row_ptr, c->col, wdev, c->pe, n, c->flags);
+    hipLaunchKernelGGL(k_check_rows, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->row_ptr, c->col, wdev, c->pe, n, by_rank ? 1 : 0, c->flags);
     hipLaunchKernelGGL(k_cluster_census, dim3(blocks_for(n)), dim3(kBlock), 0, st, c->cluster_of,
                        c->grouped ? c->group_of_cluster : nullptr, n, R, c->counts, first, gfirst, boundaries, c->flags);
     HTRY2(hipMemcpyAsync(hflags, c->flags, sizeof(hflags), hipMemcpyDeviceToHost, st));
@@ -475,7 +520,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                      : hflags[kFlagWeight] ? "weights must be finite, >= 0, with a positive sum on every non-empty row"
                      : hflags[kFlagCluster] ? "cluster_of entry outside 0..|R|-1" : nullptr;
     if (what) { cleanup_tmp(); free_graph(c); return fail(c, NOMAD_E_BAD_GRAPH, "%s", what); }
-    dev_free(wdev);
+    dev_free(c, wdev);
 
     // ---- partition tables (host arithmetic on |R|-sized arrays only)
     std::vector<uint32_t> hcounts(R), hfirst(R), hgfirst(R);
@@ -585,6 +630,12 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         HTRY(hipMemcpy(c->group_slots, gslots.data(), sizeof(int2) * (size_t)R, hipMemcpyHostToDevice));
     }
 
+    c->pool_blocks = 1;
+    if (c->cfg.pool_mode == NOMAD_POOL_DISTINCT) {   // blocks of the pooled sampler with distinct picks: NB = ceil(NS / Q)
+        const int64_t seg = c->cfg.pool_segment, NS = (E + seg - 1) / seg, Qs = c->cfg.pool_block / seg;
+        c->pool_blocks = (uint32_t)std::max<int64_t>(1, (NS + Qs - 1) / Qs);
+    }
+
     // ---- state buffers
     c->edge_grid = (blocks_for(n, kBlock / c->lpr) + 7u) & ~7u;
     TRY(dev_alloc(c, &c->theta, (size_t)n));
@@ -603,30 +654,40 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         const uint32_t n_bins = (uint32_t)((n + ((int64_t)1 << tile_bits) - 1) >> tile_bits);
         // One persistent workgroup of 1024 lanes per compute unit: the more records a round sorts, the longer the
         // contiguous run each tile receives.  (Two workgroups of 512 per compute unit measured 17 % slower at
-        // 10 M points; NOMAD_BIN_BLOCK=512 selects them for experiments when their LDS fits.)
+        // 10 M points; nomad_tune(NOMAD_TUNE_EDGE_BLOCK, 512) selects them for experiments when their LDS fits.)
         int bin_block = 0, wg_per_cu = 1;
         if (n_bins <= (uint32_t)kMaxBinsPerThread * 1024 && binned_lds_bytes(n_bins, s, 1024) <= kMaxLdsBytes) bin_block = 1024;
-        if (const char* knob = getenv("NOMAD_BIN_BLOCK"))
-            if (atoi(knob) == 512 && n_bins <= (uint32_t)kMaxBinsPerThread * 512 &&
-                2 * (binned_lds_bytes(n_bins, s, 512) + 256) <= 160 * 1024) { bin_block = 512; wg_per_cu = 2; }
-        if (const char* knob = getenv("NOMAD_WG_PER_CU"))   // tuning knob: persistent workgroups per compute unit
-            wg_per_cu = std::max(1, std::min(8, atoi(knob)));
-        // Pooled sampler: its own edge pass (pool in LDS) when the block is 1, 2, 4 or 8 rounds of 1024 positions, one
+        if (c->tune_edge_block == 512 && n_bins <= (uint32_t)kMaxBinsPerThread * 512 &&
+            2 * (binned_lds_bytes(n_bins, s, 512) + 256) <= 160 * 1024) { bin_block = 512; wg_per_cu = 2; }
+        if (c->tune_wg_per_cu) wg_per_cu = c->tune_wg_per_cu;
+        // Pooled samplers: their own edge pass (pool in LDS) when the block is 1, 2, 4 or 8 rounds of 1024 positions, one
         // workgroup per compute unit.  (Two workgroups of 512 lanes per compute unit, which lets one block's
         // bookkeeping overlap the other's rounds, measured 4 % slower: the rounds are bound by vector-ALU issue.)
         int pool_rounds = 0;
-        if (c->cfg.pool_size > 0 && c->cfg.pool_block % 1024 == 0 && !getenv("NOMAD_NO_POOL_KERNEL")) {
+        bool distinct = false;
+        if (c->cfg.pool_size > 0 && c->cfg.pool_block % 1024 == 0 && c->tune_pool_kernel) {
             const int r = c->cfg.pool_block / 1024;
-            if ((r == 1 || r == 2 || r == 4 || r == 8) &&
-                pooled_lds_bytes(n_bins, c->cfg.pool_block, (uint32_t)c->cfg.pool_size) <= kMaxLdsBytes)
-                pool_rounds = r;
+            if (r == 1 || r == 2 || r == 4 || r == 8) {
+                if (c->cfg.pool_mode == NOMAD_POOL_DISTINCT) {
+                    // 32-bit byte offsets into col / head (4 E) and theta (8 n)
+                    if (distinct_lds_bytes(n_bins, (uint32_t)c->cfg.pool_size, (uint32_t)(c->cfg.pool_size / c->cfg.pool_line), r) <= kMaxLdsBytes &&
+                        E < ((int64_t)1 << 30) && n < ((int64_t)1 << 29)) { pool_rounds = r; distinct = true; }
+                } else if (pooled_lds_bytes(n_bins, c->cfg.pool_block, (uint32_t)c->cfg.pool_size) <= kMaxLdsBytes) {
+                    pool_rounds = r;
+                }
+            }
         }
         if (pool_rounds) { bin_block = 1024; wg_per_cu = 1; }
-        if (s <= 8 && E > 0 && bin_block && !getenv("NOMAD_NO_BINNING")) {
+        std::string why;   // why the fallback path is in use, if it is
+        if (c->tune_path == NOMAD_PATH_FIXED_ATOMICS) why = "the fixed-point atomics path was asked for (nomad_tune)";
+        else if (s > 8) why = "more than 8 negatives per edge: the binned edge pass is built for s <= 8";
+        else if (!bin_block) why = "the per-tile tables of the binned edge pass do not fit LDS at this number of points";
+        if (E > 0 && why.empty()) {
             hipDeviceProp_t prop;
             HTRY(hipGetDeviceProperties(&prop, c->cfg.device));
             c->bin_block = bin_block;
             c->pool_rounds = pool_rounds;
+            c->distinct_kernel = distinct;
             c->n_wg = std::max(1, prop.multiProcessorCount) * wg_per_cu;
             c->n_bins = n_bins;
             c->tile_bits = tile_bits;
@@ -634,7 +695,10 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
             unsigned long long want = 0;
             bool ok = dev_alloc(c, &c->wg_pool_begin, (size_t)c->n_wg + 1) == NOMAD_OK && dev_alloc(c, &total_dev, 1) == NOMAD_OK;
             if (ok) {
-                if (c->pool_rounds)
+                if (c->pool_rounds && distinct)
+                    hipLaunchKernelGGL(k_wg_pools_distinct, dim3(1), dim3(64), 0, st, c->pool_blocks, c->n_wg, (int64_t)c->cfg.pool_block,
+                                       (uint32_t)c->cfg.pool_size, n_bins, c->wg_pool_begin, total_dev);
+                else if (c->pool_rounds)
                     hipLaunchKernelGGL(k_wg_pools_pooled, dim3(1), dim3(64), 0, st, E, c->n_wg, (int64_t)c->cfg.pool_block,
                                        (uint32_t)c->cfg.pool_size, n_bins, c->wg_pool_begin, total_dev);
                 else
@@ -642,7 +706,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 ok = hipMemcpyAsync(&want, total_dev, sizeof(want), hipMemcpyDeviceToHost, st) == hipSuccess &&
                      hipStreamSynchronize(st) == hipSuccess;
             }
-            dev_free(total_dev);
+            dev_free(c, total_dev);
             if (ok && want < (1ull << 31)) {
                 c->max_chunks = (uint32_t)want;
                 const size_t chains = (size_t)c->n_wg * n_bins;
@@ -661,12 +725,18 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 ok = false;
             }
             if (!ok) {
+                char buf[256];
+                snprintf(buf, sizeof(buf), "the record pool of the binned edge pass (%.1f GB) could not be set up (%s)",
+                         (double)want * kChunk * 12 / 1e9, c->err.empty() ? "size out of range" : c->err.c_str());
+                why = buf;
                 (void)hipGetLastError();
-                dev_free(c->pool); dev_free(c->chunk_prev); dev_free(c->chain_head); dev_free(c->chain_fill); dev_free(c->wg_pool_begin);
-                dev_free(c->head); dev_free(c->overflow);
-                c->err.clear();
+                dev_free(c, c->pool); dev_free(c, c->chunk_prev); dev_free(c, c->chain_head); dev_free(c, c->chain_fill); dev_free(c, c->wg_pool_begin);
+                dev_free(c, c->head); dev_free(c, c->overflow);
+                c->pool_rounds = 0;
+                c->distinct_kernel = false;
             }
         }
+        if (!c->binned && E > 0) fallback_note = "deterministic scatter on the fixed-point atomics path: " + why;
         if (!c->binned) {
             TRY(dev_alloc(c, &c->gfix, (size_t)n * 2));
             hipLaunchKernelGGL(k_zero_u64, dim3(blocks_for(n * 2)), dim3(kBlock), 0, st, c->gfix, n * 2);
@@ -679,8 +749,37 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
 #undef HTRY
 #undef HTRY2
     c->has_graph = true;
-    c->err.clear();
+    c->path = c->cfg.scatter_mode == NOMAD_SCATTER_ATOMIC ? NOMAD_PATH_ATOMIC_FP32
+              : !c->binned ? NOMAD_PATH_FIXED_ATOMICS : c->pool_rounds ? NOMAD_PATH_BINNED_POOLED : NOMAD_PATH_BINNED;
+    c->err = fallback_note;   // empty unless a slower path had to be taken
     return NOMAD_OK;
+}
+
+int nomad_scatter_path(const nomad_ctx* c) { return c ? c->path : 0; }
+
+int64_t nomad_device_bytes(const nomad_ctx* c) { return c ? c->device_bytes : 0; }
+
+int nomad_tune(nomad_ctx* c, int knob, int value) {
+    if (!c) return NOMAD_E_INVALID_ARG;
+    if (c->has_graph) return fail(c, NOMAD_E_ORDER, "nomad_tune has to come before nomad_set_graph");
+    switch (knob) {
+        case NOMAD_TUNE_EDGE_BLOCK:
+            if (value != 1024 && value != 512) break;
+            c->tune_edge_block = value; return NOMAD_OK;
+        case NOMAD_TUNE_WORKGROUPS_PER_CU:
+            if (value < 1 || value > 8) break;
+            c->tune_wg_per_cu = value; return NOMAD_OK;
+        case NOMAD_TUNE_SCATTER_PATH:
+            if (value != 0 && value != NOMAD_PATH_FIXED_ATOMICS) break;
+            c->tune_path = value; return NOMAD_OK;
+        case NOMAD_TUNE_POOL_KERNEL:
+            if (value != 0 && value != 1) break;
+            c->tune_pool_kernel = value; return NOMAD_OK;
+        case NOMAD_TUNE_RECORD_PHASES:
+            if (value < 0 || value > 64) break;
+            c->tune_phases = value; return NOMAD_OK;
+    }
+    return fail(c, NOMAD_E_INVALID_ARG, "nomad_tune: unknown knob %d or value %d out of range", knob, value);
 }
 
 int nomad_set_embedding(nomad_ctx* c, const float* theta, int mem) {
@@ -804,7 +903,7 @@ int nomad_get_negatives(nomad_ctx* c, int32_t t, int64_t e_begin, int64_t e_end,
     hipLaunchKernelGGL(k_negatives, dim3(blocks_for(cnt)), dim3(kBlock), 0, c->stream, a, e_begin, e_end, dst);
     hipError_t e_ = hipStreamSynchronize(c->stream);
     if (e_ == hipSuccess && tmp) e_ = hipMemcpy(out, tmp, sizeof(int32_t) * (size_t)cnt * s, hipMemcpyDeviceToHost);
-    dev_free(tmp);
+    dev_free(c, tmp);
     if (e_ != hipSuccess) return fail(c, NOMAD_E_HIP, "negatives: %s", hipGetErrorString(e_));
     return NOMAD_OK;
 }

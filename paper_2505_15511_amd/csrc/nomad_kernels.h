@@ -76,12 +76,25 @@ __global__ void k_check_row_ptr(const int32_t* __restrict__ row_ptr, int64_t n, 
     if (i < n && row_ptr[i + 1] < row_ptr[i]) flags[kFlagRowPtr] = 1;
 }
 
-// one thread per row: columns in range, no self loops; normalised weights p(j|i)
+// one thread per row: columns in range, no self loops; normalised weights p(j|i), from the caller's weights w or,
+// with by_rank, from the position of the edge in its row: the inverse-rank model of Eq. 7 read with ranks 1..k_i and
+// the row's own k_i-term normaliser, exp(1/rho) / sum_{rho'} exp(1/rho')
 __global__ void k_check_rows(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
-                             const float* __restrict__ w, float* __restrict__ pe, int64_t n, int* flags) {
+                             const float* __restrict__ w, float* __restrict__ pe, int64_t n, int by_rank, int* flags) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int32_t a = row_ptr[i], b = row_ptr[i + 1];
+    if (by_rank) {
+        double z = 0.0;
+        for (int32_t e = a; e < b; ++e) {
+            const int32_t j = col[e];
+            if (j < 0 || j >= n) flags[kFlagCol] = 1;
+            else if (j == i) flags[kFlagSelfLoop] = 1;
+            z += exp(1.0 / (double)(e - a + 1));
+        }
+        for (int32_t e = a; e < b; ++e) pe[e] = (float)(exp(1.0 / (double)(e - a + 1)) / z);
+        return;
+    }
     double sum = 0.0;
     for (int32_t e = a; e < b; ++e) {
         const int32_t j = col[e];
@@ -335,6 +348,10 @@ struct EdgeArgs {
     float omega0;                  // single-group omega
     uint32_t key0, key1, epoch;
     uint32_t pool_size, pool_block;   // pooled sampler (0, 0 = i.i.d. negatives per edge)
+    uint32_t pool_mode;               // 0: 16-bit picks, consecutive blocks; 1: distinct picks, interleaved blocks
+    uint32_t pool_line_bits;          // distinct picks: log2 of the points per pool line
+    uint32_t pool_segment_bits;       // distinct picks: log2 of the positions dealt to a block together
+    uint32_t pool_blocks;             // distinct picks: number of blocks NB
     int32_t s;
     int64_t n;
     int64_t row_begin, row_end;    // heads this launch covers (a sub-step of a minibatch epoch; else 0, n)
@@ -456,9 +473,49 @@ __device__ __forceinline__ int32_t pool_point(const EdgeArgs& P, const Populatio
     return draw_index(w[u & 3u], pop);
 }
 
+// ---- pooled sampler with distinct picks (see nomad.h).  One population: all n points.
+constexpr uint32_t kPoolEntryStream = 0xFFFFFFFFu, kPoolPickStream = 0xFFFFFFFEu;
+
+// entry of slot k given the edge's word W: (u_0 + k c) mod pool_size, u_0 = top log2(pool_size) bits of W,
+// c = 2 (bits 1 .. log2(pool_size) - 1 of W) + 1
+__device__ __forceinline__ uint32_t distinct_pick(uint32_t W, int k, uint32_t pool_size) {
+    const uint32_t u0 = W >> (__clz(pool_size) + 1);     // 32 - log2(pool_size)
+    const uint32_t c = (W & (pool_size - 2u)) | 1u;      // = 2 ((W >> 1) & (pool_size / 2 - 1)) + 1
+    return (u0 + (uint32_t)k * c) & (pool_size - 1u);
+}
+
+// point behind entry u of block beta's pool: point number (u div L) of line (u mod L)
+__device__ __forceinline__ int32_t distinct_pool_point(const EdgeArgs& P, uint32_t beta, uint32_t u) {
+    const uint32_t lg = 31u - (uint32_t)__clz(P.pool_size), lg_lines = lg - P.pool_line_bits;
+    const uint32_t gamma = u & ((1u << lg_lines) - 1u), o = u >> lg_lines;
+    uint32_t w[4];
+    philox4x32_10(beta, kPoolEntryStream, P.epoch, gamma >> 2, P.key0, P.key1, w);
+    uint32_t pt = __umulhi(w[gamma & 3u], (uint32_t)P.n) + o;
+    if (pt >= (uint32_t)P.n) pt -= (uint32_t)P.n;
+    return (int32_t)pt;
+}
+
+// block and rank of CSR position e
+__device__ __forceinline__ void distinct_block_of(const EdgeArgs& P, uint32_t e, uint32_t& beta, uint32_t& rank) {
+    const uint32_t sigma = e >> P.pool_segment_bits;
+    beta = sigma % P.pool_blocks;
+    rank = ((sigma / P.pool_blocks) << P.pool_segment_bits) + (e & ((1u << P.pool_segment_bits) - 1u));
+}
+
+__device__ __forceinline__ uint32_t distinct_edge_word(const EdgeArgs& P, uint32_t beta, uint32_t rank) {
+    uint32_t w[4];
+    philox4x32_10(beta, kPoolPickStream, P.epoch, (rank & 1023u) + 1024u * (rank >> 12), P.key0, P.key1, w);
+    return w[(rank >> 10) & 3u];
+}
+
 // Negative of slot k of CSR position e in epoch P.epoch (general form, any s).
 __device__ __forceinline__ int32_t negative_of_slot(const EdgeArgs& P, const Population& pop, int32_t e, int k) {
     uint32_t w[4];
+    if (P.pool_mode == 1) {
+        uint32_t beta, rank;
+        distinct_block_of(P, (uint32_t)e, beta, rank);
+        return distinct_pool_point(P, beta, distinct_pick(distinct_edge_word(P, beta, rank), k, P.pool_size));
+    }
     if (P.pool_size == 0) {
         philox4x32_10((uint32_t)e, 0u, P.epoch, (uint32_t)(k >> 2), P.key0, P.key1, w);
         return draw_index(w[k & 3], pop);
@@ -479,6 +536,12 @@ __device__ __forceinline__ void draw_negatives(const EdgeArgs& P, const Populati
             for (int l = 0; l < 4; ++l)
                 if (4 * b + l < S) m[4 * b + l] = draw_index(w[l], pop);
         }
+    } else if (P.pool_mode == 1) {
+        uint32_t beta, rank;
+        distinct_block_of(P, (uint32_t)e, beta, rank);
+        const uint32_t W = distinct_edge_word(P, beta, rank);
+#pragma unroll
+        for (int k = 0; k < S; ++k) m[k] = distinct_pool_point(P, beta, distinct_pick(W, k, P.pool_size));
     } else {
         uint32_t w[4];
         philox4x32_10((uint32_t)e, 0u, P.epoch, 0u, P.key0, P.key1, w);   // S <= 8 here: one call
@@ -1253,6 +1316,280 @@ __global__ void __launch_bounds__(BS) k_edges_pooled(const EdgeArgs P, const Bin
         Q.chain_head[(size_t)b * W + w] = ch < pool_end ? ch : kNoChunk;
         Q.chain_fill[(size_t)b * W + w] = fill[b];
     }
+}
+
+// ------------------------------------------------------------------ K3 + K4, pooled sampler with distinct picks
+// Same plan as k_edges_pooled (pool rows and their force sums in LDS, unsorted records ranked per tile, chains
+// extended once per block) for the sampler whose picks of one edge lie in different pool lines (nomad.h).  What
+// differs: a block's positions are Q segments spread over the edge list (position of rank r * 1024 + lane: segment
+// rank >> seg_bits of the block, offset rank & (segment - 1)); one Philox call serves a lane's picks of four rounds
+// (word r & 3 of call number lane + 1024 (r >> 2)); a pool line is pool_line consecutive points, read by adjacent
+// lanes (one or two 128-byte lines per pool line instead of one per entry), and its entries' records leave as one
+// contiguous run; positions, indices and byte offsets are 32-bit (needs 8 n < 2^32, checked by the host).
+__host__ __device__ inline size_t distinct_lds_bytes(uint32_t n_bins, uint32_t pool_size, uint32_t lines, int rounds) {
+    return (size_t)pool_size * 28 + ((size_t)lines + (size_t)4 * n_bins + 3 * (size_t)(32 * rounds)) * sizeof(uint32_t);
+}
+
+struct DistinctFetch {   // what a lane has in flight for its edge of the next round
+    bool has;
+    uint32_t e, i, j, ea, eb;
+    float pe;
+    float2 ti, tj;
+};
+
+template <typename T>
+__device__ __forceinline__ T load_at(const T* base, uint32_t index) {   // 64-bit base + 32-bit byte offset
+    return *(const T*)((const char*)base + (size_t)(index * (uint32_t)sizeof(T)));
+}
+
+template <int S, int ROUNDS>
+__global__ void __launch_bounds__(1024) k_edges_pooled_distinct(const EdgeArgs P, const BinArgs Q) {
+    constexpr int SS = S > 0 ? S : 1;
+    constexpr int BS = 1024;
+    constexpr int NP = kMaxPoolPerLane;
+    constexpr int kSide = 32 * ROUNDS;                                 // partial head sums a block can produce
+    extern __shared__ unsigned long long lds_pool[];
+    const uint32_t PS = P.pool_size, B = Q.n_bins, n = (uint32_t)P.n, E = (uint32_t)Q.E, NB = P.pool_blocks;
+    const uint32_t line_bits = P.pool_line_bits, seg_bits = P.pool_segment_bits;
+    const uint32_t L = PS >> line_bits, lg_lines = 31u - (uint32_t)__clz(L);
+    const int tb = Q.tile_bits;
+    unsigned long long* pool_acc = lds_pool;                         // [2 PS] fixed-point force sums
+    float2* pool_th = (float2*)(pool_acc + 2 * (size_t)PS);          // [PS] embedding rows of the pool
+    uint32_t* pool_pt = (uint32_t*)(pool_th + PS);                   // [PS] the points
+    uint32_t* line_start = pool_pt + PS;                             // [L] first point of every line of the NEXT block
+    uint32_t* cnt = line_start + L;                                  // [B] records of this block per tile
+    uint32_t* fill = cnt + B;                                        // [B] records in the open chunk (kChunk: none open / full)
+    uint32_t* chunk = fill + B;                                      // [B] open chunk of this (workgroup, tile)
+    uint32_t* base = chunk + B;                                      // [B] first chunk allocated for this block
+    uint32_t* side_pt = base + B;                                    // [kSide] partial head sums: the head
+    float* side_x = (float*)(side_pt + kSide);
+    float* side_y = side_x + kSide;
+    __shared__ uint32_t pool_cursor, side_n;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t W = gridDim.x, w = blockIdx.x;
+    const uint32_t pool_end = min(Q.wg_pool_begin[w + 1], Q.max_chunks);
+    for (uint32_t b = tid; b < B; b += BS) { cnt[b] = 0; fill[b] = kChunk; chunk[b] = kNoChunk; base[b] = 0; }
+    for (uint32_t u = tid; u < 2 * PS; u += BS) pool_acc[u] = 0ull;
+    if (tid == 0) { pool_cursor = Q.wg_pool_begin[w]; side_n = 0; }
+
+    // ---- the pool of a block: line starts (one Philox call per four lines), then every lane fetches up to NP entries;
+    // lane index idx = tid + 1024 k stands for point number idx % pool_line of line idx / pool_line, i.e. entry
+    // (idx % pool_line) L + idx / pool_line: adjacent lanes read adjacent points
+    auto draw_lines = [&](uint32_t blk) {
+        if (4u * tid < L && blk < NB) {
+            uint32_t wd[4];
+            philox4x32_10(blk, kPoolEntryStream, P.epoch, tid, P.key0, P.key1, wd);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (4u * tid + k < L) line_start[4u * tid + k] = __umulhi(wd[k], n);
+        }
+    };
+    uint32_t next_pt[NP];
+    float2 next_th[NP];
+    auto fetch_pool = [&](uint32_t blk) {
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            next_pt[k] = 0u;
+            next_th[k] = make_float2(0.f, 0.f);
+            const uint32_t idx = tid + (uint32_t)k * BS;
+            if (idx < PS && blk < NB) {
+                uint32_t pt = line_start[idx >> line_bits] + (idx & ((1u << line_bits) - 1u));
+                if (pt >= n) pt -= n;
+                next_pt[k] = pt;
+                next_th[k] = load_at(P.theta, pt);
+            }
+        }
+    };
+    auto entry_of = [&](uint32_t idx) { return ((idx & ((1u << line_bits) - 1u)) << lg_lines) + (idx >> line_bits); };
+    auto stage_pool = [&]() {
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            const uint32_t idx = tid + (uint32_t)k * BS;
+            if (idx < PS) { const uint32_t u = entry_of(idx); pool_pt[u] = next_pt[k]; pool_th[u] = next_th[k]; }
+        }
+    };
+    // ---- positions: rank r * 1024 + tid of block blk
+    auto position = [&](uint32_t blk, int r, bool& has) {
+        const uint32_t rank = (uint32_t)r * BS + tid;
+        const uint32_t e = ((blk + (rank >> seg_bits) * NB) << seg_bits) + (rank & ((1u << seg_bits) - 1u));
+        has = blk < NB && e < E;
+        return e;
+    };
+    auto issue = [&](bool has, uint32_t e, uint32_t i, uint32_t j, DistinctFetch& f) {
+        f.has = has; f.e = e; f.i = i; f.j = j; f.ea = 0; f.eb = 0; f.pe = 0.f;
+        f.ti = make_float2(0.f, 0.f);
+        f.tj = make_float2(0.f, 0.f);
+        if (!has) return;
+        f.ea = (uint32_t)load_at(P.row_ptr, i);
+        f.eb = (uint32_t)load_at(P.row_ptr + 1, i);
+        f.ti = load_at(P.theta, i);
+        f.tj = load_at(P.theta, j);
+        if (P.pe) f.pe = load_at(P.pe, e);
+    };
+    draw_lines(w);
+    lds_barrier();
+    fetch_pool(w);
+    stage_pool();
+    DistinctFetch f;
+    uint32_t i_next = 0, j_next = 0;
+    {
+        bool h0, h1;
+        const uint32_t e0 = position(w, 0, h0);
+        const uint32_t e1 = position(w + W * (1 / ROUNDS), 1 % ROUNDS, h1);
+        uint32_t i0 = 0, j0 = 0;
+        if (h0) { i0 = (uint32_t)load_at(Q.head, e0); j0 = (uint32_t)load_at(P.col, e0); }
+        if (h1) { i_next = (uint32_t)load_at(Q.head, e1); j_next = (uint32_t)load_at(P.col, e1); }
+        issue(h0, e0, i0, j0, f);
+    }
+    auto emit = [&](bool valid, uint32_t pt, uint32_t rank, float x, float y) {
+        if (!valid) return;
+        const uint32_t b = pt >> tb;
+        const uint32_t pos = fill[b] + rank;
+        uint32_t ch, off;
+        if (pos < (uint32_t)kChunk) { ch = chunk[b]; off = pos; }
+        else { ch = base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
+        if (ch < pool_end) {   // kNoChunk is above any valid id
+            uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
+            dst[0] = pt & ((1u << tb) - 1u);
+            dst[1] = __float_as_uint(x);
+            dst[2] = __float_as_uint(y);
+        }
+    };
+    HeadCtx h;
+    h.omega = P.omega0;
+    h.MA = h.MBx = h.MBy = 0.f;
+    for (uint32_t blk = w; blk < NB; blk += W) {
+        lds_barrier();   // the block's pool is in LDS, the tile tables are those left by the block before
+        bool tv[ROUNDS];
+        uint32_t tpt[ROUNDS], trk[ROUNDS];
+        float tfx[ROUNDS], tfy[ROUNDS];
+        uint32_t wd[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            if ((r & 3) == 0) philox4x32_10(blk, kPoolPickStream, P.epoch, tid + 1024u * (uint32_t)(r >> 2), P.key0, P.key1, wd);
+            const bool has = f.has;
+            const uint32_t e = f.e, i = f.i, ea = f.ea, eb = f.eb;
+            float hx = 0.f, hy = 0.f;
+            tv[r] = has; tpt[r] = 0u; trk[r] = 0u; tfx[r] = 0.f; tfy[r] = 0.f;
+            if (has) {
+                uint32_t slot[SS];
+                float2 tm[SS];
+#pragma unroll
+                for (int k = 0; k < S; ++k) slot[k] = distinct_pick(wd[r & 3], k, PS);
+#pragma unroll
+                for (int k = 0; k < S; ++k) tm[k] = pool_th[slot[k]];
+                h.ti = f.ti;
+                EdgeOut<SS> o;
+                edge_math<S, false>(h, P.pe ? f.pe : __builtin_amdgcn_rcpf((float)(eb - ea)), f.tj, tm, o);
+                hx = o.hx;
+                hy = o.hy;
+#pragma unroll
+                for (int k = 0; k < S; ++k) {
+                    atomicAdd(&pool_acc[2 * slot[k]], to_fixed(o.rx[k]));
+                    atomicAdd(&pool_acc[2 * slot[k] + 1], to_fixed(o.ry[k]));
+                }
+                tpt[r] = f.j; tfx[r] = -o.a * o.dx; tfy[r] = -o.a * o.dy;
+                trk[r] = atomicAdd(&cnt[tpt[r] >> tb], 1u);
+            }
+            {   // the loads of the next round go out before this round's head sums are reduced
+                bool h1, h2;
+                const uint32_t e1 = position(blk + W * ((r + 1) / ROUNDS), (r + 1) % ROUNDS, h1);   // one round ahead
+                const uint32_t e2 = position(blk + W * ((r + 2) / ROUNDS), (r + 2) % ROUNDS, h2);   // two rounds ahead
+                const uint32_t i1 = i_next, j1 = j_next;
+                if (h2) { i_next = (uint32_t)load_at(Q.head, e2); j_next = (uint32_t)load_at(P.col, e2); }
+                issue(h1, e1, i1, j1, f);
+            }
+            if (reduce_head_sums(Q, has, (int32_t)i, (int32_t)ea, (int32_t)eb, (int64_t)e, (int64_t)E, hx, hy)) {
+                const uint32_t k = atomicAdd(&side_n, 1u);
+                side_pt[k] = i; side_x[k] = hx; side_y[k] = hy;
+            }
+        }
+        draw_lines(blk + W);
+        lds_barrier();   // every force of the block is in pool_acc, the side list and the next block's lines are complete
+        // ---- one record per pool entry that received a force, one per partial head sum
+        bool pv[NP];
+        uint32_t ppt[NP], prk[NP];
+        float pfx[NP], pfy[NP];
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            const uint32_t idx = tid + (uint32_t)k * BS;
+            pv[k] = false; ppt[k] = 0u; prk[k] = 0u; pfx[k] = 0.f; pfy[k] = 0.f;
+            if (idx < PS) {
+                const uint32_t u = entry_of(idx);
+                const long long ax = (long long)pool_acc[2 * u], ay = (long long)pool_acc[2 * u + 1];
+                pv[k] = (ax | ay) != 0;
+                if (pv[k]) {
+                    pool_acc[2 * u] = 0ull;
+                    pool_acc[2 * u + 1] = 0ull;
+                    ppt[k] = pool_pt[u];
+                    pfx[k] = (float)((double)ax * kFixInv);
+                    pfy[k] = (float)((double)ay * kFixInv);
+                    prk[k] = atomicAdd(&cnt[ppt[k] >> tb], 1u);
+                }
+            }
+        }
+        const bool sv = tid < side_n;
+        uint32_t spt = 0u, srk = 0u;
+        float sx = 0.f, sy = 0.f;
+        if (sv) { spt = side_pt[tid]; sx = side_x[tid]; sy = side_y[tid]; srk = atomicAdd(&cnt[spt >> tb], 1u); }
+        fetch_pool(blk + W);
+        lds_barrier();   // the counts are complete
+        // ---- tiles whose open chunk cannot take this block's records get new chunks, linked to the chain
+        for (uint32_t b = tid; b < B; b += BS) {
+            const uint32_t c = cnt[b], fl = fill[b];
+            if (c != 0 && fl + c > (uint32_t)kChunk) {
+                const uint32_t k = (fl + c - 1) / kChunk;
+                const uint32_t nb = atomicAdd(&pool_cursor, k);
+                base[b] = nb;
+                if (nb + k > pool_end) *Q.overflow = 1;
+                uint32_t prev = chunk[b];
+                for (uint32_t y = 0; y < k && nb + y < pool_end; ++y) { Q.chunk_prev[nb + y] = prev; prev = nb + y; }
+            }
+        }
+        lds_barrier();
+        // ---- every lane writes its own records
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) emit(tv[r], tpt[r], trk[r], tfx[r], tfy[r]);
+#pragma unroll
+        for (int k = 0; k < NP; ++k) emit(pv[k], ppt[k], prk[k], pfx[k], pfy[k]);
+        emit(sv, spt, srk, sx, sy);
+        lds_barrier();   // the tables have been read
+        // ---- chain state after this block, counts back to zero; the next block's pool into LDS
+        for (uint32_t b = tid; b < B; b += BS) {
+            const uint32_t c = cnt[b];
+            if (c != 0) {
+                const uint32_t fl = fill[b];
+                if (fl + c > (uint32_t)kChunk) {
+                    const uint32_t k = (fl + c - 1) / kChunk;
+                    chunk[b] = base[b] + k - 1;
+                    fill[b] = fl + c - k * kChunk;
+                } else {
+                    fill[b] = fl + c;
+                }
+                cnt[b] = 0;
+            }
+        }
+        if (tid == 0) side_n = 0;
+        stage_pool();
+    }
+    lds_barrier();
+    for (uint32_t b = tid; b < B; b += BS) {
+        const uint32_t ch = chunk[b];
+        Q.chain_head[(size_t)b * W + w] = ch < pool_end ? ch : kNoChunk;
+        Q.chain_fill[(size_t)b * W + w] = fill[b];
+    }
+}
+
+// chunk-id range of each workgroup for the kernel above: blocks w, w + W, ...; records per block: one tail per
+// position, two partial head sums per wavefront and round, one per pool entry
+__global__ void k_wg_pools_distinct(uint32_t n_blocks, int W, int64_t block_edges, uint32_t pool_size, uint32_t n_bins,
+                                    uint32_t* __restrict__ wg_pool_begin, unsigned long long* __restrict__ total) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    const uint64_t per_block = (uint64_t)block_edges + pooled_side_records(block_edges) + pool_size;
+    const uint64_t blocks = ((uint64_t)n_blocks + W - 1) / W;
+    const uint64_t per_wg = blocks * per_block / kChunk + n_bins + 1;
+    for (int w = 0; w <= W; ++w) wg_pool_begin[w] = (uint32_t)min(per_wg * (uint64_t)w, (uint64_t)0xFFFFFFFFull);
+    *total = per_wg * (uint64_t)W;
 }
 
 // private chunk-id range of each workgroup: enough for every record its slabs can emit (s+1 per

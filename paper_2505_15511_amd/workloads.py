@@ -50,6 +50,9 @@ class Workload:
     k: int = 15
     pool_size: int = 0             # opt-in pooled sampler: points per pool (0 = i.i.d. negatives per edge)
     pool_block: int = 0            # opt-in pooled sampler: consecutive CSR positions sharing a pool
+    pool_mode: int = 0             # pooled sampler: 0 = 16-bit picks, 1 = distinct picks (exactly i.i.d. inside an edge)
+    pool_line: int = 1             # distinct picks: consecutive points per pool line
+    pool_segment: int = 64         # distinct picks: consecutive CSR positions dealt to a block together
     batches_per_epoch: int = 1     # sequential sub-steps of an epoch over consecutive head ranges
     sampled_far_field: bool = False   # opt-in: the sum over approximated cells estimated from the samples
     mean_gradient: bool = False       # opt-in: the gradient also flows through the cell means
@@ -66,6 +69,7 @@ class Workload:
             cluster_of=h(self.cluster_of), n_clusters=self.n_clusters, cluster_group=h(self.cluster_group),
             theta0=h(self.theta0), n_neg=self.n_neg, noise_count=self.noise_count,
             n_epochs=self.n_epochs, lr0=self.lr0, seed=self.seed, pool_size=self.pool_size, pool_block=self.pool_block,
+            pool_mode=self.pool_mode, pool_line=self.pool_line, pool_segment=self.pool_segment,
             batches_per_epoch=self.batches_per_epoch, sampled_far_field=self.sampled_far_field,
             mean_gradient=self.mean_gradient,
         )

@@ -40,10 +40,12 @@ def test_only_the_abi_is_exported():
 
 def test_config_struct_layout_matches_header():
     # uint32 | int64 | int32 int32 | float int32 | float (pad) | uint64 | int32 int32 | int32 (pad) | void* | int32 int32 | int32 int32
-    assert C.sizeof(binding.NomadConfig) == 88
+    assert C.sizeof(binding.NomadConfig) == 104
     assert binding.NomadConfig.seed.offset == 40 and binding.NomadConfig.stream.offset == 64
     assert binding.NomadConfig.pool_size.offset == 72 and binding.NomadConfig.pool_block.offset == 76
     assert binding.NomadConfig.far_field.offset == 80 and binding.NomadConfig.mean_gradient.offset == 84
+    assert binding.NomadConfig.pool_mode.offset == 88 and binding.NomadConfig.pool_line.offset == 92
+    assert binding.NomadConfig.pool_segment.offset == 96 and binding.NomadConfig.edge_weights.offset == 100
 
 
 def test_argument_errors_before_any_device_work(lib):
@@ -69,6 +71,22 @@ def test_argument_errors_before_any_device_work(lib):
     cfg.far_field, cfg.batches_per_epoch = 0, 2                       # ... and one step per epoch
     assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1
     cfg.mean_gradient, cfg.batches_per_epoch = 0, 1
+    # the pooled sampler with distinct picks: power-of-two pool, s <= lines, whole segments, one step per epoch
+    for size, block, line, seg, batches, ok in ((64, 1024, 4, 64, 1, True), (48, 1024, 1, 64, 1, False), (64, 1024, 32, 64, 1, False),
+                                                (64, 1024, 4, 96, 1, False), (64, 1000, 4, 64, 1, False), (64, 1024, 4, 2048, 1, False),
+                                                (64, 1024, 4, 64, 2, False), (64, 1024, 0, 0, 1, True), (1, 1024, 1, 64, 1, False)):
+        cfg.pool_size, cfg.pool_block, cfg.pool_mode, cfg.pool_line, cfg.pool_segment, cfg.batches_per_epoch = size, block, 1, line, seg, batches
+        rc = lib.nomad_create(C.byref(cfg), C.byref(ctx))
+        assert (rc == -1) == (not ok), (size, block, line, seg, batches, rc)      # accepted: 0, or -6 where no GPU is present
+        if rc == 0:
+            lib.nomad_destroy(ctx)
+            ctx = C.c_void_p()
+    cfg.pool_size, cfg.pool_block, cfg.pool_mode, cfg.pool_line, cfg.pool_segment, cfg.batches_per_epoch = 0, 0, 0, 0, 0, 1
+    cfg.pool_line = 4                                                 # lines belong to the distinct picks
+    assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1
+    cfg.pool_line, cfg.edge_weights = 0, 2
+    assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -1
+    cfg.edge_weights = 0
     cfg.n_points = 2 ** 31
     assert lib.nomad_create(C.byref(cfg), C.byref(ctx)) == -4
     assert not ctx.value
@@ -78,6 +96,7 @@ def test_argument_errors_before_any_device_work(lib):
     assert lib.nomad_set_graph(None, None, None, None, None, None, 0) == -1
     assert lib.nomad_num_edges(None) == 0
     assert lib.nomad_last_error(None) == b"null context"
+    assert lib.nomad_tune(None, 1, 512) == -1 and lib.nomad_scatter_path(None) == 0 and lib.nomad_device_bytes(None) == 0
 
 
 def test_stand_alone_entry_points_check_arguments_before_any_device_work(lib):
@@ -127,7 +146,7 @@ def test_header_is_plain_c(tmp_path):
     if not shutil.which("gcc"):
         pytest.skip("no C compiler")
     src = tmp_path / "use_header.c"
-    src.write_text('#include "nomad.h"\nint main(void) { return sizeof(nomad_config) == 88 ? 0 : 1; }\n')
+    src.write_text('#include "nomad.h"\nint main(void) { return sizeof(nomad_config) == 104 ? 0 : 1; }\n')
     exe = tmp_path / "use_header"
     inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I" + inc, str(src), "-o", str(exe)], check=True)

@@ -7,7 +7,8 @@ import pytest
 import torch
 
 from oracle import c_oracle
-from paper_2505_15511_amd import Nomad, NomadError, SCATTER_ATOMIC, SCATTER_DETERMINISTIC, workloads
+from paper_2505_15511_amd import (Nomad, NomadError, PATH_ATOMIC_FP32, PATH_BINNED, PATH_BINNED_POOLED, PATH_FIXED_ATOMICS,
+                                  SCATTER_ATOMIC, SCATTER_DETERMINISTIC, workloads)
 
 pytestmark = pytest.mark.gpu
 
@@ -64,12 +65,13 @@ def small_random(seed, n=3000, R=12, groups=True, weights=True, contiguous=False
                 cluster_group=grp, theta0=theta0, n_neg=s, noise_count=M, n_epochs=T, lr0=0.5, seed=seed * 31 + 7)
 
 
-def make_nomad(d, mode):
+def make_nomad(d, mode, tune=None):
     nm = Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
                pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0),
                batches_per_epoch=d.get("batches_per_epoch", 1), sampled_far_field=d.get("sampled_far_field", False),
-               mean_gradient=d.get("mean_gradient", False))
-    nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
+               mean_gradient=d.get("mean_gradient", False), pool_mode=d.get("pool_mode", 0), pool_line=d.get("pool_line", 0),
+               pool_segment=d.get("pool_segment", 0), inverse_rank_weights=d.get("inverse_rank_weights", False), tune=tune)
+    nm.set_graph(d["row_ptr"], d["col_idx"], None if d.get("inverse_rank_weights") else d["weights"], d["cluster_of"], d["cluster_group"])
     nm.set_embedding(d["theta0"])
     return nm
 
@@ -235,19 +237,20 @@ def skewed_degree_graph(seed, n=6000, hubs=3):
                 seed=seed + 99)
 
 
-@pytest.mark.parametrize("env", [{}, {"NOMAD_BIN_BLOCK": "512"}, {"NOMAD_WG_PER_CU": "3"}, {"NOMAD_NO_BINNING": "1"}],
-                         ids=["1024-lane", "512-lane", "3-per-cu", "fixed-point-atomics"])
-def test_deterministic_variants_on_skewed_degrees(env, monkeypatch):
+@pytest.mark.parametrize("tune,path", [({}, PATH_BINNED), ({"edge_block": 512}, PATH_BINNED), ({"workgroups_per_cu": 3}, PATH_BINNED),
+                                       ({"scatter_path": PATH_FIXED_ATOMICS}, PATH_FIXED_ATOMICS), ({"record_phases": 3}, PATH_BINNED)],
+                         ids=["1024-lane", "512-lane", "3-per-cu", "fixed-point-atomics", "3-phases"])
+def test_deterministic_variants_on_skewed_degrees(tune, path):
     """Every launch shape of the deterministic path gives the oracle's gradient, and the same embedding bit for bit
-    when run twice, on rows of very different lengths."""
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
+    when run twice, on rows of very different lengths; the library says which path it runs."""
+    env = tune
     d = skewed_degree_graph(4)
     O = c_oracle.COracle(**d)
     th1, g_ref, _ = O.epoch(d["theta0"], 0)
     out = []
     for _ in range(2):
-        with make_nomad(d, SCATTER_DETERMINISTIC) as nm:
+        with make_nomad(d, SCATTER_DETERMINISTIC, tune=tune) as nm:
+            assert nm.scatter_path() == path and (nm.note() == "") == (path == PATH_BINNED) and nm.device_bytes() > 0
             nm.epoch(0)
             g = nm.get_gradient()
             nm.epoch(1)
@@ -281,6 +284,83 @@ def test_pooled_sampler_negatives_gradient_and_loss(pool, mode):
         note(f"  pooled {pool} {case} mode={mode}: grad err {err:.2e}  loss {L:.8f} vs {L_ref:.8f}")
         assert err < GRAD_TOL
         assert abs(L - L_ref) < LOSS_TOL * abs(L_ref)
+
+
+# pool size, block, points per line, segment: the fast kernel at 1, 2, 4 and 8 rounds, lines of 1 to 64 points, blocks of
+# consecutive positions (segment = block) and spread blocks, and shapes only the general kernels take
+DISTINCT = [pytest.param((2048, 4096, 16, 256), id="P2048-G4096-line16-seg256"), pytest.param((4096, 8192, 16, 64), id="P4096-G8192-line16-seg64"),
+            pytest.param((1024, 1024, 1, 1024), id="P1024-G1024-line1-consecutive"), pytest.param((512, 2048, 64, 1024), id="P512-G2048-line64-seg1024"),
+            pytest.param((64, 8192, 4, 8192), id="P64-G8192-line4-consecutive"), pytest.param((16, 192, 2, 64), id="P16-G192-general-kernels"),
+            pytest.param((256, 4096, 8, 2048), id="P256-G4096-line8-seg2048")]
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("pool", DISTINCT)
+def test_pooled_sampler_with_distinct_picks_negatives_gradient_and_loss(pool, mode):
+    for case in ("config3@0.05", "skewed", "tiny"):
+        d = dict(workload(3, 0.05).numpy()) if case == "config3@0.05" else skewed_degree_graph(6) if case == "skewed" else \
+            small_random(9, n=300, groups=False, weights=True, s=5, M=5.0)
+        d["pool_size"], d["pool_block"], d["pool_line"], d["pool_segment"] = pool
+        d["pool_mode"] = 1
+        O = c_oracle.COracle(**d)
+        E = len(d["col_idx"])
+        th1, g_ref, _ = O.epoch(d["theta0"], 0)
+        L_ref, _ = O.loss_and_grad(th1, 1, want_grad=False)
+        with make_nomad(d, mode) as nm:
+            if mode == SCATTER_DETERMINISTIC:
+                assert nm.scatter_path() == (PATH_BINNED_POOLED if pool[1] % 1024 == 0 else PATH_BINNED)
+            assert np.array_equal(nm.get_negatives(0), O.negatives(0))
+            assert np.array_equal(nm.get_negatives(3, E // 7, E // 7 + min(E // 2, 8000)), O.negatives(3, E // 7, E // 7 + min(E // 2, 8000)))
+            nm.epoch(0)
+            g = nm.get_gradient()
+            err, err_c = grad_err(g, g_ref), grad_err_per_component(g, g_ref)
+            L = nm.loss(1)
+            th = nm.get_embedding()
+            th2_ref, g2_ref, _ = O.epoch(th, 1)            # a second epoch from the library's own embedding
+            nm.epoch(1)
+            err2 = grad_err(nm.get_gradient(), g2_ref)
+        note(f"  distinct picks {pool} {case} mode={mode}: grad err {err:.2e} / {err2:.2e} (per component {err_c:.2e})  loss {L:.8f} vs {L_ref:.8f}")
+        assert err < GRAD_TOL and err2 < GRAD_TOL and err_c < COMPONENT_TOL
+        assert abs(L - L_ref) < LOSS_TOL * abs(L_ref)
+        assert np.abs(th - th1).max() < 1e-5 * max(1.0, np.abs(th1).max())
+
+
+def test_pooled_sampler_with_distinct_picks_is_bit_reproducible_and_the_general_kernels_agree():
+    d = dict(workload(3, 0.05).numpy(), pool_size=2048, pool_block=4096, pool_mode=1, pool_line=16, pool_segment=256)
+    runs = []
+    for tune in (None, None, {"pool_kernel": 0}):
+        with make_nomad(d, SCATTER_DETERMINISTIC, tune=tune) as nm:
+            assert nm.scatter_path() == (PATH_BINNED if tune else PATH_BINNED_POOLED)
+            for t in range(4):
+                nm.epoch(t)
+            runs.append((nm.get_gradient(), nm.get_embedding()))
+    assert np.array_equal(runs[0][0], runs[1][0]) and np.array_equal(runs[0][1], runs[1][1])
+    assert np.abs(runs[0][0] - runs[2][0]).max() < 2e-5 * np.abs(runs[0][0]).max()       # another kernel, another summation order
+    with pytest.raises(NomadError) as ei:                                                   # one sampling population only
+        make_nomad(dict(small_random(6), pool_size=64, pool_block=256, pool_mode=1, pool_line=4, pool_segment=64), SCATTER_DETERMINISTIC)
+    assert ei.value.code == -1
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_inverse_rank_weights_computed_by_the_library(mode):
+    """edge_weights = NOMAD_WEIGHTS_INVERSE_RANK: p(j|i) from the position of j in i's row (Eq. 7 read with ranks from 1 and
+    the row's own normaliser), on rows of different lengths; the oracle receives the same model as explicit weights."""
+    from oracle import nomad_oracle as po
+    d = dict(small_random(21, n=2500, groups=True, weights=False, s=3))
+    deg = np.diff(d["row_ptr"])
+    d["weights"] = np.concatenate([po.inverse_rank_weights(int(k)) for k in deg if k > 0]).astype(np.float32)
+    assert deg.min() != deg.max()
+    O = c_oracle.COracle(**d)
+    _, g_ref, _ = O.epoch(d["theta0"], 0)
+    L_ref = O.loss_and_grad(d["theta0"], 0, want_grad=False)[0]
+    with make_nomad(dict(d, inverse_rank_weights=True), mode) as nm:
+        assert abs(nm.loss(0) - L_ref) < LOSS_TOL * abs(L_ref)
+        nm.epoch(0)
+        assert grad_err(nm.get_gradient(), g_ref) < GRAD_TOL
+    nm = Nomad(d["n"], d["n_clusters"], 3, 4.0, 5, 0.5, 1, mode, inverse_rank_weights=True)
+    with pytest.raises(NomadError, match="INVALID_ARG"):                                    # weights and the rank model exclude each other
+        nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
+    nm.close()
 
 
 def test_pooled_sampler_is_bit_reproducible_and_needs_one_population():
