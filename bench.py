@@ -320,7 +320,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--groups", type=int, default=None, help="deal the clusters into this many groups")
     ap.add_argument("--pool", default=None, metavar="P,G",
-                    help="opt-in pooled sampler: pool size and block length (e.g. 2048,4096); not the benchmark's sampler")
+                    help="opt-in pooled sampler: pool size and block length (e.g. 2048,4096), or P,G,line,segment for the "
+                         "sampler with distinct picks (e.g. 4096,8192,16,256); not the benchmark's sampler")
     ap.add_argument("--graph", choices=["symmetrised", "paper"], default="symmetrised",
                     help="paper: the directed kNN graph with inverse-rank weights of Section 3.1 / Eq. 7 (planted configs); "
                          "the benchmark uses the symmetrised unit-weight graph")
@@ -340,6 +341,7 @@ def main():
     ap.add_argument("--index-d", type=int, default=128)
     ap.add_argument("--index-clusters", type=int, default=256)
     ap.add_argument("--index-k", type=int, default=15)
+    ap.add_argument("--phases", type=int, default=0, help="record phases of the deterministic edge pass (0: the library's choice)")
     ap.add_argument("--batches", type=int, default=1, help="sub-steps per epoch (minibatch epochs); the benchmark uses 1")
     ap.add_argument("--probe", choices=["copy", "gather", "atomic_f32x2", "atomic_u64", "append12", "append12_grouped", "limits"], default=None,
                     help="run only one memory-system probe: streaming copy (counter calibration / practical HBM ceiling), "
@@ -354,7 +356,7 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2505_15511_amd import Nomad, SCATTER_ATOMIC, SCATTER_DETERMINISTIC, workloads
+    from paper_2505_15511_amd import Nomad, SCATTER_ATOMIC, SCATTER_DETERMINISTIC, binding, workloads
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -395,7 +397,9 @@ def main():
     pool = None
     if args.pool:
         pool = tuple(int(x) for x in args.pool.split(","))
-        w.pool_size, w.pool_block = pool
+        w.pool_size, w.pool_block = pool[:2]
+        if len(pool) == 4:                      # points per pool line, segment: the sampler with distinct picks
+            w.pool_mode, w.pool_line, w.pool_segment = 1, pool[2], pool[3]
     n, E, s, R = w.n, w.n_edges, w.n_neg, w.n_clusters
     steps, warmup = args.steps, args.warmup
     if warmup + steps > w.n_epochs:
@@ -406,7 +410,9 @@ def main():
     if args.hip_graph:
         return hip_graph_run(args, torch, Nomad, w, mode, warmup, steps)
     nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode, pool_size=w.pool_size, pool_block=w.pool_block,
-               batches_per_epoch=args.batches, sampled_far_field=w.sampled_far_field, mean_gradient=w.mean_gradient)
+               batches_per_epoch=args.batches, sampled_far_field=w.sampled_far_field, mean_gradient=w.mean_gradient,
+               pool_mode=w.pool_mode, pool_line=w.pool_line, pool_segment=w.pool_segment,
+               inverse_rank_weights=w.inverse_rank_weights, tune={"record_phases": args.phases} if args.phases else None)
     t0 = time.time()
     nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None if w.weights is None else w.weights.to(dev), w.cluster_of.to(dev),
                  None if w.cluster_group is None else w.cluster_group.to(dev))
@@ -427,12 +433,14 @@ def main():
     prof = nm.profile_read()
     nm.profile(False)
     loss = nm.loss(warmup + steps)
+    path_name, state_gb = binding.PATH_NAMES[nm.scatter_path()], nm.device_bytes() / 1e9
     ms_per_step = 1e3 * elapsed / steps
     grouped = w.cluster_group is not None
+    weighted = w.weights is not None or w.inverse_rank_weights
     kernels = {}
     for name, (ms, cnt) in prof.items():
         if cnt:
-            ab = algorithmic_bytes(name, n, E, s, R, grouped, w.weights is not None, mode == SCATTER_DETERMINISTIC, pool)
+            ab = algorithmic_bytes(name, n, E, s, R, grouped, weighted, mode == SCATTER_DETERMINISTIC, pool)
             kernels[name] = dict(ms=ms / cnt, launches=cnt, algorithmic_gb=ab / 1e9, gbs=ab / (ms / cnt) / 1e6)
     dom = max(kernels, key=lambda k: kernels[k]["ms"])
     if dom in ("mean_field", "mean_gradient"):
@@ -447,7 +455,7 @@ def main():
     if args.scale == 1.0 and args.groups is None and pool is None and args.batches == 1 and args.graph == "symmetrised" \
             and not w.sampled_far_field and not w.mean_gradient:
         roofline["traffic"] = measured_traffic(dom, args.config, args.mode)
-    epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, w.weights is not None, mode == SCATTER_DETERMINISTIC, pool) for k in kernels
+    epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, weighted, mode == SCATTER_DETERMINISTIC, pool) for k in kernels
                       if k not in ("mean_field", "mean_gradient"))
     out = {
         "metric": "positive+negative edge updates/sec per epoch at 1 GPU",
@@ -459,7 +467,9 @@ def main():
                                f"|M|={w.noise_count:g}, {'grouped (mean-field)' if grouped else 'no approximated cells'}",
                    "scatter_mode": args.mode,
                    "batches_per_epoch": args.batches,
-                   "sampler": "iid per edge" if pool is None else f"pooled, {pool[0]} points per block of {pool[1]} edges (opt-in variant)",
+                   "sampler": "iid per edge" if pool is None else f"pooled, {pool[0]} points per block of {pool[1]} edges (opt-in variant)"
+                              + (f", distinct picks, lines of {pool[2]} points, segments of {pool[3]} positions" if len(pool) == 4 else ""),
+                   "scatter_path": None,
                    "far_field": "Eq. 5 summed over the approximated cells" if not w.sampled_far_field else
                                 "estimated from the samples (opt-in variant)",
                    "means": "constants of the epoch" if not w.mean_gradient else "differentiated (opt-in variant)"},
@@ -469,8 +479,10 @@ def main():
         "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
         "loss_after": loss,
         "setup_s": round(setup_s, 3), "generate_s": round(gen_s, 3),
+        "library_state_gb": round(state_gb, 2),
         "roofline": roofline,
     }
+    out["config"]["scatter_path"] = path_name
     out["copy_probe_gbs"] = round(copy_probe_gbs(torch, gib=2, steps=5)["gbs_read_plus_write"], 1)
     # the rate at which this machine serves independent 8-byte gathers from a table the size of the embedding at
     # 10 M points: E * s such gathers per epoch bound the i.i.d. sampler's edge pass from below (E s / rate)

@@ -57,12 +57,16 @@ class COracle:
     def __init__(self, *, n, row_ptr, col_idx, cluster_of, n_clusters, n_neg, noise_count, seed=0, n_epochs=1,
                  lr0=1.0, weights=None, cluster_group=None, pool_size=0, pool_block=0, batches_per_epoch=1,
                  sampled_far_field=False, mean_gradient=False, pool_mode=0, pool_line=1, pool_segment=64,
-                 **_ignored):
+                 inverse_rank_weights=False, **_ignored):
         self.lib = _load()
         self.n = int(n)
         self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
         self.col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
         self.cluster_of = np.ascontiguousarray(cluster_of, dtype=np.int32)
+        if inverse_rank_weights:                 # p(j|i) from the position of j in i's row (Eq. 7): the Python oracle's table
+            from .nomad_oracle import rank_model_weights
+            assert weights is None, "either explicit weights or the rank model"
+            weights = rank_model_weights(self.row_ptr)
         self.weights = None if weights is None else np.ascontiguousarray(weights, dtype=np.float32)
         self.cluster_group = None if cluster_group is None else np.ascontiguousarray(cluster_group, dtype=np.int32)
         self.n_clusters = int(n_clusters)

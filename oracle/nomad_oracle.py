@@ -123,6 +123,7 @@ class Problem:
     pool_line: int = 1                        # pool_mode 1: consecutive points per pool line (a power of two)
     pool_segment: int = 64                    # pool_mode 1: consecutive CSR positions dealt to a block together (a power
                                               # of two >= 64 that divides pool_block; = pool_block: consecutive blocks)
+    inverse_rank_weights: bool = False        # p(j|i) from the position of j in i's row (Eq. 7) instead of `weights`
     sampled_far_field: bool = False           # opt-in: Eq. 5's sum over approximated cells estimated from the samples
     mean_gradient: bool = False               # opt-in: the gradient also flows through the cell means mu_r(theta)
 
@@ -130,6 +131,9 @@ class Problem:
         self.row_ptr = np.asarray(self.row_ptr, dtype=np.int64)
         self.col_idx = np.asarray(self.col_idx, dtype=np.int64)
         self.cluster_of = np.asarray(self.cluster_of, dtype=np.int64)
+        if self.inverse_rank_weights:
+            assert self.weights is None, "either explicit weights or the rank model"
+            self.weights = rank_model_weights(self.row_ptr)
         if self.weights is not None:
             self.weights = np.asarray(self.weights, dtype=np.float32)
         if self.cluster_group is not None:
@@ -163,6 +167,7 @@ class Problem:
                  n_epochs=w["n_epochs"], lr0=w["lr0"], weights=w.get("weights"),
                  cluster_group=w.get("cluster_group"), pool_size=w.get("pool_size", 0), pool_block=w.get("pool_block", 0),
                  pool_mode=w.get("pool_mode", 0), pool_line=w.get("pool_line", 1), pool_segment=w.get("pool_segment", 64),
+                 inverse_rank_weights=w.get("inverse_rank_weights", False),
                  batches_per_epoch=w.get("batches_per_epoch", 1), sampled_far_field=w.get("sampled_far_field", False),
                  mean_gradient=w.get("mean_gradient", False))
         d.update(over)
@@ -496,6 +501,18 @@ def inverse_rank_weights(k: int) -> np.ndarray:
     normaliser so that it is a distribution: p(rho) = exp(1/rho) / sum_{rho'=1..k} exp(1/rho')."""
     w = np.exp(1.0 / np.arange(1, k + 1, dtype=np.float64))
     return w / w.sum()
+
+
+def rank_model_weights(row_ptr) -> np.ndarray:
+    """Per-edge weights of a graph whose rows list a head's neighbours in ascending distance: the edge at position
+    rho = 1..k_i of row i gets inverse_rank_weights(k_i)[rho - 1] (Eq. 7 with the row's own length k_i)."""
+    row_ptr = np.asarray(row_ptr, dtype=np.int64)
+    out = np.zeros(int(row_ptr[-1]), dtype=np.float64)
+    for i in range(len(row_ptr) - 1):
+        a, b = int(row_ptr[i]), int(row_ptr[i + 1])
+        if b > a:
+            out[a:b] = inverse_rank_weights(b - a)
+    return out
 
 
 def neighbourhood_preservation(nbrs_a: np.ndarray, nbrs_b: np.ndarray) -> float:

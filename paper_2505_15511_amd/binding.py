@@ -370,7 +370,8 @@ class Nomad:
                   batches_per_epoch=getattr(w, "batches_per_epoch", 1),
                   sampled_far_field=getattr(w, "sampled_far_field", False),
                   mean_gradient=getattr(w, "mean_gradient", False), pool_mode=getattr(w, "pool_mode", 0),
-                  pool_line=getattr(w, "pool_line", 0), pool_segment=getattr(w, "pool_segment", 0))
+                  pool_line=getattr(w, "pool_line", 0), pool_segment=getattr(w, "pool_segment", 0),
+                  inverse_rank_weights=getattr(w, "inverse_rank_weights", False))
         kw.update(over)
         nm = cls(**kw)
         nm.set_graph(w.row_ptr, w.col_idx, w.weights, w.cluster_of, w.cluster_group)

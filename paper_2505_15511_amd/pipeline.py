@@ -16,8 +16,9 @@ from .binding import (SCATTER_DETERMINISTIC, Nomad, kmeans_lloyd, kmeans_lsh_ini
 
 def neighbour_lists_to_csr(nbrs: torch.Tensor, graph: str = "directed"):
     """CSR of the kNN graph from neighbour lists [n, k] in rank order (-1 = no such neighbour).
-    "directed": the paper's digraph, row i = i's out-neighbours weighted by the inverse-rank model (Eq. 7);
-    "symmetric": union with the transposed edges, unit weights.  Returns (row_ptr, col_idx, weights or None)."""
+    "directed": the paper's digraph, row i = i's out-neighbours in rank order (the library derives p(j|i) from the
+    ranks, Eq. 7, when asked to: inverse_rank_weights); "symmetric": union with the transposed edges, unit weights.
+    Returns (row_ptr, col_idx, None)."""
     n, k = nbrs.shape
     valid = nbrs >= 0
     if graph == "symmetric":
@@ -30,8 +31,7 @@ def neighbour_lists_to_csr(nbrs: torch.Tensor, graph: str = "directed"):
     elif graph == "directed":
         counts = valid.sum(dim=1)
         col = nbrs[valid].to(torch.int32).contiguous()
-        wk = torch.from_numpy(workloads.inverse_rank_weights(k).astype(np.float32)).to(nbrs.device)
-        w = wk[None, :].expand(n, k)[valid].contiguous()          # the library normalises every row
+        w = None                                                   # rows stay in rank order: the library weighs them (Eq. 7)
     else:
         raise ValueError("graph must be 'directed' or 'symmetric'")
     row_ptr = torch.zeros(n + 1, dtype=torch.int64, device=nbrs.device)
@@ -85,7 +85,8 @@ def project(X: torch.Tensor, n_clusters: int, k: int = 15, n_epochs: int = 200, 
         theta0 = workloads.init_embedding(n, seed, std0, device=X.device)
     else:
         raise ValueError("init must be 'pca' or 'random'")
-    with Nomad(n, R, n_neg, noise_count, n_epochs, lr0, seed, SCATTER_DETERMINISTIC, device, **nomad_options) as nm:
+    with Nomad(n, R, n_neg, noise_count, n_epochs, lr0, seed, SCATTER_DETERMINISTIC, device,
+               inverse_rank_weights=(graph == "directed"), **nomad_options) as nm:
         timed("set_graph", lambda: (nm.set_graph(row_ptr, col, w, labels, None), nm.set_embedding(theta0)))
 
         def run():

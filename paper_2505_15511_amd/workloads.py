@@ -53,6 +53,7 @@ class Workload:
     pool_mode: int = 0             # pooled sampler: 0 = 16-bit picks, 1 = distinct picks (exactly i.i.d. inside an edge)
     pool_line: int = 1             # distinct picks: consecutive points per pool line
     pool_segment: int = 64         # distinct picks: consecutive CSR positions dealt to a block together
+    inverse_rank_weights: bool = False   # rows are in rank order and p(j|i) follows the inverse-rank model of Eq. 7
     batches_per_epoch: int = 1     # sequential sub-steps of an epoch over consecutive head ranges
     sampled_far_field: bool = False   # opt-in: the sum over approximated cells estimated from the samples
     mean_gradient: bool = False       # opt-in: the gradient also flows through the cell means
@@ -70,6 +71,7 @@ class Workload:
             theta0=h(self.theta0), n_neg=self.n_neg, noise_count=self.noise_count,
             n_epochs=self.n_epochs, lr0=self.lr0, seed=self.seed, pool_size=self.pool_size, pool_block=self.pool_block,
             pool_mode=self.pool_mode, pool_line=self.pool_line, pool_segment=self.pool_segment,
+            inverse_rank_weights=self.inverse_rank_weights,
             batches_per_epoch=self.batches_per_epoch, sampled_far_field=self.sampled_far_field,
             mean_gradient=self.mean_gradient,
         )
@@ -224,22 +226,14 @@ def planted_knn_graph(n: int, n_clusters: int, k: int, cross_frac: float, seed: 
                 out_nbrs=nbrs32, sizes=sizes_np)
 
 
-def inverse_rank_weights(k: int) -> np.ndarray:
-    """p(j|i) of the inverse-rank edge model (Eq. 7) for the neighbour of rank rho = 1..k: e^(1/rho) over the sum of
-    the k terms.  float64 [k]; an input of the path, not part of its arithmetic."""
-    w = np.exp(1.0 / np.arange(1, k + 1, dtype=np.float64))
-    return w / w.sum()
-
-
 def directed_rank_csr(out_nbrs: torch.Tensor):
     """The kNN digraph as Section 3.1 has it: row i holds i's k out-neighbours in rank order (no transposed
-    edges added), weighted by the inverse-rank model.  Returns (row_ptr int32 [n+1], col_idx int32 [n k],
-    weights float32 [n k])."""
+    edges added).  Its edge probabilities follow from the ranks (Eq. 7): computing them is the library's part (and
+    the oracle's), not the generator's.  Returns (row_ptr int32 [n+1], col_idx int32 [n k])."""
     n, k = out_nbrs.shape
     dev = out_nbrs.device
     row_ptr = (torch.arange(n + 1, dtype=torch.int64, device=dev) * k).to(torch.int32)
-    wk = torch.from_numpy(inverse_rank_weights(k).astype(np.float32)).to(dev)
-    return row_ptr, out_nbrs.reshape(-1).to(torch.int32).contiguous(), wk.repeat(n).contiguous()
+    return row_ptr, out_nbrs.reshape(-1).to(torch.int32).contiguous()
 
 
 def init_embedding(n: int, seed: int, std: float = 0.01, device="cpu") -> torch.Tensor:
@@ -291,11 +285,11 @@ def make_config(cfg: int, *, scale: float = 1.0, device="cpu", n_groups: Optiona
         group = torch.arange(R, dtype=torch.int32, device=device)
     if n_groups is not None:
         group = torch.from_numpy(balanced_groups(pg["sizes"], n_groups)).to(device)
-    weights = None
     if paper_graph:
-        pg["row_ptr"], pg["col_idx"], weights = directed_rank_csr(pg["out_nbrs"])
+        pg["row_ptr"], pg["col_idx"] = directed_rank_csr(pg["out_nbrs"])
         name += "+directed-rank"
-    return Workload(name=name, n=n, row_ptr=pg["row_ptr"], col_idx=pg["col_idx"], cluster_of=pg["cluster_of"], weights=weights,
+    return Workload(name=name, n=n, row_ptr=pg["row_ptr"], col_idx=pg["col_idx"], cluster_of=pg["cluster_of"], weights=None,
+                    inverse_rank_weights=paper_graph,
                     n_clusters=R, theta0=init_embedding(n, 2000 + cfg, device=device), n_neg=c["s"],
                     noise_count=c["M"], n_epochs=c["T"], lr0=1.0, seed=3000 + cfg, cluster_group=group,
                     out_nbrs=pg["out_nbrs"], k=c["k"])

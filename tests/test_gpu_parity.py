@@ -484,7 +484,7 @@ def test_directed_graph_without_reverse_edges(mode):
 def test_paper_graph_directed_with_inverse_rank_weights(mode):
     """Section 3.1's own input: the directed kNN graph (no transposed edges), p(j|i) from the inverse-rank model, Eq. 7."""
     d = workload(3, 0.03, paper_graph=True).numpy()
-    assert d["weights"] is not None and len(d["col_idx"]) == d["n"] * 15
+    assert d["weights"] is None and d["inverse_rank_weights"] and len(d["col_idx"]) == d["n"] * 15
     O = c_oracle.COracle(**d)
     _, g_ref, _ = O.epoch(d["theta0"], 0)
     with make_nomad(d, mode) as nm:

@@ -444,19 +444,32 @@ def test_inverse_rank_model_is_a_distribution():
     assert np.all(np.diff(p15) < 0)
 
 
-def test_paper_graph_workload_matches_the_inverse_rank_model():
-    """The directed workload: k out-edges per point in rank order, weights = the oracle's Eq. 7 model, rows sum to one."""
+def test_paper_graph_workload_and_the_rank_model_of_the_oracle():
+    """The directed workload: k out-edges per point in rank order and a flag instead of weights; both oracles then weigh
+    position rho of a row of length k_i by the model of Eq. 7 for k_i neighbours, rows of any length."""
     from paper_2505_15511_amd import workloads
     w = workloads.make_config(3, scale=0.003, paper_graph=True)
     d = w.numpy()
     k = w.k
+    assert d["weights"] is None and d["inverse_rank_weights"]
     assert np.array_equal(d["row_ptr"], np.arange(w.n + 1) * k)
     assert np.array_equal(d["col_idx"].reshape(w.n, k), w.out_nbrs.numpy())
-    assert np.allclose(d["weights"].reshape(w.n, k), po.inverse_rank_weights(k)[None, :], rtol=1e-7, atol=0)
-    assert np.allclose(d["weights"].reshape(w.n, k).sum(1), 1.0, atol=1e-6)
     assert not np.any(d["col_idx"].reshape(w.n, k) == np.arange(w.n)[:, None])
     sym = workloads.make_config(3, scale=0.003).numpy()
     assert len(sym["col_idx"]) > len(d["col_idx"])          # the benchmark graph adds the transposed edges
+    P = po.Problem.from_workload(d)
+    assert np.allclose(P.weights.reshape(w.n, k), po.inverse_rank_weights(k)[None, :], rtol=1e-7, atol=0)
+    # ragged rows: lengths 3, 0, 1, 2
+    rp = np.array([0, 3, 3, 4, 6])
+    wr = po.rank_model_weights(rp)
+    z3 = math.exp(1.0) + math.exp(0.5) + math.exp(1 / 3)
+    assert np.allclose(wr, [math.e / z3, math.exp(0.5) / z3, math.exp(1 / 3) / z3, 1.0, math.e / (math.e + math.exp(0.5)), math.exp(0.5) / (math.e + math.exp(0.5))], atol=1e-15)
+    kw = dict(n=4, row_ptr=rp, col_idx=[1, 2, 3, 0, 0, 1], cluster_of=[0, 0, 0, 0], n_clusters=1, n_neg=2, noise_count=2.0, seed=3)
+    theta = _grid_theta(4, 5)
+    for impl in ("py", "c"):
+        a = IMPLS[impl](**kw, inverse_rank_weights=True).loss_and_grad(theta, 0)
+        b = IMPLS[impl](**kw, weights=wr.astype(np.float32)).loss_and_grad(theta, 0)
+        assert a[0] == b[0] and np.array_equal(a[1], b[1])
 
 
 def test_neighbourhood_preservation_metric():
