@@ -441,7 +441,9 @@ def main():
     for name, (ms, cnt) in prof.items():
         if cnt:
             ab = algorithmic_bytes(name, n, E, s, R, grouped, weighted, mode == SCATTER_DETERMINISTIC, pool)
-            kernels[name] = dict(ms=ms / cnt, launches=cnt, algorithmic_gb=ab / 1e9, gbs=ab / (ms / cnt) / 1e6)
+            # per epoch: with record phases an epoch's edge pass is several launches, each over its share of the edges
+            kernels[name] = dict(ms=ms / steps, launches=cnt, launches_per_epoch=cnt / steps, algorithmic_gb=ab / 1e9,
+                                 gbs=ab / (ms / steps) / 1e6)
     dom = max(kernels, key=lambda k: kernels[k]["ms"])
     if dom in ("mean_field", "mean_gradient"):
         # n * |R| kernel evaluations (Eq. 5 and its derivative factor): plain-ALU bound, not HBM bound
@@ -477,6 +479,7 @@ def main():
         "epoch_model_gb": epoch_bytes / 1e9,
         "epoch_hbm_frac_model": epoch_bytes / (elapsed / steps) / 1e9 / HBM_PEAK_GBS,
         "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
+        "launches_per_epoch": {k: v["launches_per_epoch"] for k, v in kernels.items()},
         "loss_after": loss,
         "setup_s": round(setup_s, 3), "generate_s": round(gen_s, 3),
         "library_state_gb": round(state_gb, 2),

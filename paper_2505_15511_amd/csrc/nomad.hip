@@ -72,6 +72,8 @@ struct nomad_ctx {
     // launch-shape knobs (nomad_tune) and what set_graph made of them
     int tune_edge_block = 0, tune_wg_per_cu = 0, tune_path = 0, tune_pool_kernel = 1, tune_phases = 0;
     int path = 0;                   // NOMAD_PATH_* in use
+    int phases = 1;                 // record phases of the binned edge pass
+    unsigned long long* carry = nullptr;   // [2 n] fixed-point sums carried from phase to phase (phases > 1)
     bool distinct_kernel = false;   // the pooled edge pass is the one for distinct picks
     uint32_t pool_blocks = 1;       // distinct picks: number of blocks
     std::unordered_map<const void*, size_t> allocations;   // device memory held, by pointer
@@ -136,7 +138,8 @@ void free_graph(nomad_ctx* c) {
     c->through_means = false;
     dev_free(c, c->flags);
     dev_free(c, c->pool); dev_free(c, c->chunk_prev); dev_free(c, c->chain_head); dev_free(c, c->chain_fill); dev_free(c, c->wg_pool_begin);
-    dev_free(c, c->head); dev_free(c, c->overflow);
+    dev_free(c, c->head); dev_free(c, c->overflow); dev_free(c, c->carry);
+    c->phases = 1;
     c->binned = false;
     c->pool_rounds = 0;
     c->distinct_kernel = false;
@@ -701,8 +704,21 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 else if (c->pool_rounds)
                     hipLaunchKernelGGL(k_wg_pools_pooled, dim3(1), dim3(64), 0, st, E, c->n_wg, (int64_t)c->cfg.pool_block,
                                        (uint32_t)c->cfg.pool_size, n_bins, c->wg_pool_begin, total_dev);
-                else
-                    hipLaunchKernelGGL(k_wg_pools, dim3(1), dim3(64), 0, st, E, c->n_wg, s + 1, c->bin_block, n_bins, c->wg_pool_begin, total_dev);
+                else {
+                    // Record phases: the edge pass of a step runs over `phases` ranges of positions, each followed by the
+                    // tile pass, so the pool holds the records of one range.  Default: as many (a power of two, at
+                    // most 64) as keep one range's records under 8 GB (each further phase costs about half a per cent
+                    // of an epoch: the tile pass walks shorter chains and carries its sums through memory).
+                    int phases = c->tune_phases;
+                    if (phases == 0) {
+                        phases = 1;
+                        while (phases < 64 && (double)E * (s + 1) * 12.0 / phases > 8e9) phases *= 2;
+                    }
+                    c->phases = (int)std::max<int64_t>(1, std::min<int64_t>(phases, (E + c->bin_block - 1) / c->bin_block));
+                    const int64_t per_phase = (E + c->phases - 1) / c->phases + c->bin_block;   // ranges are cut at multiples of the block
+                    hipLaunchKernelGGL(k_wg_pools, dim3(1), dim3(64), 0, st, std::min<int64_t>(E, per_phase), c->n_wg, s + 1, c->bin_block, n_bins,
+                                       c->wg_pool_begin, total_dev);
+                }
                 ok = hipMemcpyAsync(&want, total_dev, sizeof(want), hipMemcpyDeviceToHost, st) == hipSuccess &&
                      hipStreamSynchronize(st) == hipSuccess;
             }
@@ -713,7 +729,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 ok = dev_alloc(c, &c->pool, (size_t)c->max_chunks * kChunk * 3) == NOMAD_OK &&
                      dev_alloc(c, &c->chunk_prev, c->max_chunks) == NOMAD_OK && dev_alloc(c, &c->chain_head, chains) == NOMAD_OK &&
                      dev_alloc(c, &c->chain_fill, chains) == NOMAD_OK && dev_alloc(c, &c->head, (size_t)E) == NOMAD_OK &&
-                     dev_alloc(c, &c->overflow, 1) == NOMAD_OK;
+                     dev_alloc(c, &c->overflow, 1) == NOMAD_OK && (c->phases == 1 || dev_alloc(c, &c->carry, (size_t)n * 2) == NOMAD_OK);
                 if (ok) ok = prepare_binned(c) == NOMAD_OK;
                 if (ok) {
                     HTRY(hipMemsetAsync(c->overflow, 0, sizeof(int), st));
@@ -731,7 +747,8 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 why = buf;
                 (void)hipGetLastError();
                 dev_free(c, c->pool); dev_free(c, c->chunk_prev); dev_free(c, c->chain_head); dev_free(c, c->chain_fill); dev_free(c, c->wg_pool_begin);
-                dev_free(c, c->head); dev_free(c, c->overflow);
+                dev_free(c, c->head); dev_free(c, c->overflow); dev_free(c, c->carry);
+                c->phases = 1;
                 c->pool_rounds = 0;
                 c->distinct_kernel = false;
             }
@@ -816,13 +833,22 @@ int nomad_epoch(nomad_ctx* c, int32_t t) {
         a.row_end = r1;
         if (c->through_means) a.cS = c->cS;
         if (c->cfg.scatter_mode == NOMAD_SCATTER_DETERMINISTIC && c->binned) {
-            { Timed tm(c, NOMAD_K_EDGES);
-              launch_edges_binned(c, a, e0, e1); }
-            run_mean_gradient(c, r0, r1);
-            { Timed tm(c, NOMAD_K_TILES);   // accumulates the records of every tile and takes the SGD step for its points
-              hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 << c->tile_bits,
-                                 c->stream, bin_args(c), (uint32_t)c->n_wg, c->g, n, c->theta, eta,
-                                 c->through_means ? c->cluster_of : nullptr, c->through_means ? c->gmean : nullptr); }
+            // the positions of this step in `phases` ranges cut at multiples of the workgroup size; every range's
+            // records are accumulated before the next range reuses the pool, the last accumulation takes the step
+            const int phases = c->pool_rounds ? 1 : (int)std::max<int64_t>(1, std::min<int64_t>(c->phases, (e1 - e0 + c->bin_block - 1) / c->bin_block));
+            for (int ph = 0; ph < phases; ++ph) {
+                const int64_t blocks = (e1 - e0 + c->bin_block - 1) / c->bin_block;
+                const int64_t p0 = e0 + blocks * ph / phases * c->bin_block, p1 = ph + 1 == phases ? e1 : e0 + blocks * (ph + 1) / phases * c->bin_block;
+                { Timed tm(c, NOMAD_K_EDGES);
+                  launch_edges_binned(c, a, p0, p1); }
+                const bool last = ph + 1 == phases;
+                if (last) run_mean_gradient(c, r0, r1);
+                const int kind = phases == 1 ? kPhaseOnly : ph == 0 ? kPhaseFirst : last ? kPhaseLast : kPhaseMiddle;
+                Timed tm(c, NOMAD_K_TILES);   // accumulates the records of every tile; the last one takes the SGD step for its points
+                hipLaunchKernelGGL(k_tile_accumulate, dim3(c->n_bins), dim3(kBinBlock), sizeof(unsigned long long) * 2 << c->tile_bits,
+                                   c->stream, bin_args(c), (uint32_t)c->n_wg, c->g, n, c->theta, eta,
+                                   c->through_means ? c->cluster_of : nullptr, c->through_means ? c->gmean : nullptr, c->carry, kind);
+            }
             continue;
         }
         if (c->cfg.scatter_mode == NOMAD_SCATTER_ATOMIC) {

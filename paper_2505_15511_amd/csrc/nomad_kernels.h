@@ -729,7 +729,8 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
 //                    records were appended or read in.  It then adds the head sums and writes g.
 constexpr int kMaxTileBits = 13;        // 8192 points: 128 KB of accumulators
 constexpr int kMinTileBits = 8;
-constexpr int kChunk = 1024;            // records per chunk (12 KB)
+constexpr int kChunk = 256;             // records per chunk (3 KB): every (workgroup, tile) chain ends in a partly filled
+                                        // chunk, so the pool carries workgroups x tiles x kChunk records of slack
 constexpr int kBinBlock = 1024;          // threads of the tile pass and of the large edge-pass workgroup
 constexpr int kMaxBinsPerThread = 8;    // tiles one thread owns in the per-round scan
 constexpr uint32_t kNoChunk = 0xFFFFFFFFu;
@@ -1722,47 +1723,87 @@ __global__ void __launch_bounds__(kBlock) k_add_mean_gradient(float2* __restrict
 
 // With `theta` given it also takes the SGD step of Section 3.4 for its points, theta <- theta - eta g (the
 // edge pass that read theta has finished by then).
+// An epoch's edge pass may run in phases over ranges of CSR positions, each followed by this kernel, so that the
+// record pool holds one phase at a time: `carry` ([2 n] fixed-point sums) takes the tile's sums of every phase but the
+// last (kPhaseFirst stores them, kPhaseMiddle adds them), and the last phase (kPhaseLast) adds what was carried before
+// it goes on as the single-phase form (kPhaseOnly) does.  Integer sums: the result does not depend on the phases.
+enum TilePhase { kPhaseOnly = 0, kPhaseFirst = 1, kPhaseMiddle = 2, kPhaseLast = 3 };
+
 __global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const BinArgs Q, uint32_t n_wg, float2* __restrict__ g, int64_t n,
                                                               float2* __restrict__ theta, float eta,
-                                                              const int32_t* __restrict__ cluster_of, const float2* __restrict__ gmean) {
+                                                              const int32_t* __restrict__ cluster_of, const float2* __restrict__ gmean,
+                                                              unsigned long long* __restrict__ carry, int phase) {
     extern __shared__ unsigned long long acc[];   // [2 << tile_bits]
     constexpr int kPerLane = kChunk / 64;         // records one lane takes from a full chunk
-    constexpr int kBatch = 8;                     // loads in flight per lane
     const uint32_t b = blockIdx.x;
     const int tile = 1 << Q.tile_bits;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int l = threadIdx.x; l < 2 * tile; l += kBinBlock) acc[l] = 0ull;
     __syncthreads();
-    for (uint32_t w = wave; w < n_wg; w += kBinBlock / 64) {
-        uint32_t ch = Q.chain_head[(size_t)b * n_wg + w];
-        uint32_t cnt = Q.chain_fill[(size_t)b * n_wg + w];
-        while (ch != kNoChunk) {
-            const uint32_t prev = Q.chunk_prev[ch];
-            const uint32_t* src = Q.pool + (size_t)ch * kChunk * 3;
+    // A wavefront walks the chains of kChains workgroups side by side: the loads of a step (next chunk ids and up to
+    // kPerLane records per lane and chain) all go out before any is used, so the latency of following a chain is
+    // paid once per step for all of them.  Chunk ids and fills are wave-uniform.
+    constexpr int kChains = 4;
+    for (uint32_t w0 = (uint32_t)wave * kChains; w0 < n_wg; w0 += (kBinBlock / 64) * kChains) {
+        uint32_t ch[kChains], cnt[kChains];
 #pragma unroll
-            for (int r0 = 0; r0 < kPerLane; r0 += kBatch) {
-                uint32_t rec[kBatch][3];
+        for (int k = 0; k < kChains; ++k) {
+            const bool live = w0 + k < n_wg;
+            ch[k] = live ? Q.chain_head[(size_t)b * n_wg + w0 + k] : kNoChunk;
+            cnt[k] = live ? Q.chain_fill[(size_t)b * n_wg + w0 + k] : 0u;
+            ch[k] = __builtin_amdgcn_readfirstlane(ch[k]);
+            cnt[k] = __builtin_amdgcn_readfirstlane(cnt[k]);
+        }
+        bool any = true;
+        while (any) {
+            uint32_t prev[kChains];
+            uint32_t rec[kChains][kPerLane][3];
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const uint32_t r = (uint32_t)(r0 + u) * 64u + lane;
-                    if (r < cnt) { rec[u][0] = src[3 * r]; rec[u][1] = src[3 * r + 1]; rec[u][2] = src[3 * r + 2]; }
-                }
+            for (int k = 0; k < kChains; ++k) {
+                prev[k] = kNoChunk;
+                if (ch[k] != kNoChunk) {
+                    prev[k] = Q.chunk_prev[ch[k]];
+                    const uint32_t* src = Q.pool + (size_t)ch[k] * kChunk * 3;
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const uint32_t r = (uint32_t)(r0 + u) * 64u + lane;
-                    if (r < cnt) {
-                        const uint32_t ml = rec[u][0] & (uint32_t)(tile - 1);
-                        atomicAdd(&acc[2 * ml], to_fixed(__uint_as_float(rec[u][1])));
-                        atomicAdd(&acc[2 * ml + 1], to_fixed(__uint_as_float(rec[u][2])));
+                    for (int u = 0; u < kPerLane; ++u) {
+                        const uint32_t r = (uint32_t)u * 64u + lane;
+                        if (r < cnt[k]) { rec[k][u][0] = src[3 * r]; rec[k][u][1] = src[3 * r + 1]; rec[k][u][2] = src[3 * r + 2]; }
                     }
                 }
             }
-            ch = prev;
-            cnt = kChunk;
+            any = false;
+#pragma unroll
+            for (int k = 0; k < kChains; ++k) {
+                if (ch[k] != kNoChunk) {
+#pragma unroll
+                    for (int u = 0; u < kPerLane; ++u) {
+                        const uint32_t r = (uint32_t)u * 64u + lane;
+                        if (r < cnt[k]) {
+                            const uint32_t ml = rec[k][u][0] & (uint32_t)(tile - 1);
+                            atomicAdd(&acc[2 * ml], to_fixed(__uint_as_float(rec[k][u][1])));
+                            atomicAdd(&acc[2 * ml + 1], to_fixed(__uint_as_float(rec[k][u][2])));
+                        }
+                    }
+                    ch[k] = __builtin_amdgcn_readfirstlane(prev[k]);
+                    cnt[k] = kChunk;
+                    any = any || ch[k] != kNoChunk;
+                }
+            }
         }
     }
     __syncthreads();
     const int64_t p0 = (int64_t)b << Q.tile_bits;
+    if (phase == kPhaseFirst || phase == kPhaseMiddle) {   // not the last phase of the step: carry the sums on
+        for (int l = threadIdx.x; l < 2 * tile && 2 * p0 + l < 2 * n; l += kBinBlock) {
+            const unsigned long long before = phase == kPhaseMiddle ? carry[2 * p0 + l] : 0ull;
+            carry[2 * p0 + l] = before + acc[l];
+        }
+        return;
+    }
+    if (phase == kPhaseLast) {
+        for (int l = threadIdx.x; l < 2 * tile && 2 * p0 + l < 2 * n; l += kBinBlock) acc[l] += carry[2 * p0 + l];
+        __syncthreads();
+    }
     for (int l = threadIdx.x; l < tile && p0 + l < n; l += kBinBlock) {
         const float2 hd = Q.ghead[p0 + l];
         Q.ghead[p0 + l] = make_float2(0.f, 0.f);   // consumed: rows that hand their head sum on as records rely on this
