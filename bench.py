@@ -59,16 +59,17 @@ def algorithmic_bytes(kernel, n, E, s, R, grouped, weighted, deterministic, pool
     raise KeyError(kernel)
 
 
-def measured_traffic(kernel, config, mode):
-    """HBM bytes per launch from the committed rocprofv3 counter summary (profiles/hbm_bytes_per_launch.txt:
-    lines `<config> <mode> <kernel> <bytes>`), or None if that kernel and workload have not been profiled."""
+def measured_traffic(kernel, config, mode, launches_per_epoch=1.0):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (profiles/hbm_bytes_per_launch.txt: lines
+    `<config> <mode> <kernel> <bytes of that kernel's launches of one epoch>`), or None if that kernel and workload
+    have not been profiled.  The counters do not depend on how many launches an epoch's edge pass is cut into."""
     path = os.path.join(ROOT, "profiles", "hbm_bytes_per_launch.txt")
     try:
         with open(path) as fh:
             for line in fh:
                 f = line.split()
                 if len(f) >= 4 and not line.startswith("#") and f[0] == f"config{config}" and f[1] == mode and f[2] == kernel:
-                    return float(f[3])
+                    return float(f[3]) / launches_per_epoch
     except OSError:
         pass
     return None
@@ -272,6 +273,85 @@ def pipeline_run(args, torch, workloads):
         "triplet_accuracy": {"pca_start": start_accuracy, "final": accuracy}}))
 
 
+def pool_of(w):
+    """(pool size, block[, line, segment]) of a workload's pooled sampler, or None."""
+    if not w.pool_size:
+        return None
+    return (w.pool_size, w.pool_block, w.pool_line, w.pool_segment) if w.pool_mode == 1 else (w.pool_size, w.pool_block)
+
+
+def timed_epochs(torch, w, mode, steps, warmup, batches=1, phases=0):
+    """`warmup` untimed and `steps` timed epochs of workload w (graph and embedding resident on the device before the
+    clock starts), with the library's per-launch HIP events on its stream.  Returns the timings, the per-kernel
+    figures per epoch and the roofline entry of the kernel that takes most of the epoch."""
+    from paper_2505_15511_amd import Nomad, SCATTER_DETERMINISTIC, binding
+    dev = "cuda"
+    n, E, s, R = w.n, w.n_edges, w.n_neg, w.n_clusters
+    pool = pool_of(w)
+    nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode, pool_size=w.pool_size, pool_block=w.pool_block,
+               batches_per_epoch=batches, sampled_far_field=w.sampled_far_field, mean_gradient=w.mean_gradient,
+               pool_mode=w.pool_mode, pool_line=w.pool_line, pool_segment=w.pool_segment,
+               inverse_rank_weights=w.inverse_rank_weights, tune={"record_phases": phases} if phases else None)
+    t0 = time.time()
+    nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None if w.weights is None else w.weights.to(dev), w.cluster_of.to(dev),
+                 None if w.cluster_group is None else w.cluster_group.to(dev))
+    nm.set_embedding(w.theta0.to(dev))
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+    for t in range(warmup):
+        nm.epoch(t)
+    torch.cuda.synchronize()
+    nm.profile(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(warmup, warmup + steps):
+        nm.epoch(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = nm.profile_read()
+    nm.profile(False)
+    loss = nm.loss(warmup + steps)
+    path_name, state_gb, note = binding.PATH_NAMES[nm.scatter_path()], nm.device_bytes() / 1e9, nm.note()
+    nm.close()
+    grouped = w.cluster_group is not None
+    weighted = w.weights is not None or w.inverse_rank_weights
+    det = mode == SCATTER_DETERMINISTIC
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        if cnt:
+            ab = algorithmic_bytes(name, n, E, s, R, grouped, weighted, det, pool)
+            # per epoch: with record phases an epoch's edge pass is several launches, each over its share of the edges
+            kernels[name] = dict(ms=ms / steps, launches=cnt, launches_per_epoch=cnt / steps, algorithmic_gb=ab / 1e9,
+                                 gbs=ab / (ms / steps) / 1e6)
+    dom = max(kernels, key=lambda k: kernels[k]["ms"])
+    if dom in ("mean_field", "mean_gradient"):
+        # n * |R| kernel evaluations (Eq. 5 and its derivative factor): plain-ALU bound, not HBM bound
+        flops = MEAN_FIELD_FLOPS * float(n) * float(R)
+        roofline = dict(bound="alu", kernel=dom, achieved=flops / (kernels[dom]["ms"] * 1e-3) / 1e12,
+                        peak=FP32_VALU_PEAK_TFLOPS, unit="TFLOP/s", traffic=None)
+    else:
+        # per launch: an epoch's edge pass is `launches_per_epoch` launches (record phases), each over its share of the edges
+        lpe = kernels[dom]["launches_per_epoch"]
+        roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s", traffic=None,
+                        launches_per_epoch=lpe, algorithmic_gb_per_launch=round(kernels[dom]["algorithmic_gb"] / lpe, 3),
+                        ms_per_launch=round(kernels[dom]["ms"] / lpe, 4))
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, weighted, det, pool) for k in kernels
+                      if k not in ("mean_field", "mean_gradient"))
+    return dict(ms_per_step=1e3 * elapsed / steps, elapsed=elapsed, kernels=kernels, roofline=roofline, loss=loss, path=path_name,
+                state_gb=state_gb, note=note, setup_s=setup_s, grouped=grouped, epoch_bytes=epoch_bytes)
+
+
+def summary_of(w, m, steps):
+    """The short form of a measurement for the lists of variants and configurations."""
+    E, s = w.n_edges, w.n_neg
+    t = m["elapsed"] / steps
+    return {"workload": w.name, "n": w.n, "edges": E, "ms_per_step": round(1e3 * t, 4), "edges_per_s": E / t, "updates_per_s": E * (1 + s) / t,
+            "kernels_ms": {k: round(v["ms"], 4) for k, v in m["kernels"].items()}, "scatter_path": m["path"],
+            "library_state_gb": round(m["state_gb"], 2),
+            "roofline": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in m["roofline"].items()}, "frac": round(m["roofline"]["frac"], 4)}
+
+
 def hip_graph_run(args, torch, Nomad, w, mode, warmup, steps):
     """The timed epochs recorded once into a HIP graph (nomad_epoch only enqueues kernels on the caller's stream) and
     replayed: one graph launch for 2 x steps kernels."""
@@ -318,6 +398,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the configuration (testing only)")
     ap.add_argument("--mode", choices=["det", "atomic"], default="det")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="the default run only: skip the variants and the other configurations")
     ap.add_argument("--groups", type=int, default=None, help="deal the clusters into this many groups")
     ap.add_argument("--pool", default=None, metavar="P,G",
                     help="opt-in pooled sampler: pool size and block length (e.g. 2048,4096), or P,G,line,segment for the "
@@ -409,56 +490,16 @@ def main():
     w.mean_gradient = args.mean_gradient
     if args.hip_graph:
         return hip_graph_run(args, torch, Nomad, w, mode, warmup, steps)
-    nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode, pool_size=w.pool_size, pool_block=w.pool_block,
-               batches_per_epoch=args.batches, sampled_far_field=w.sampled_far_field, mean_gradient=w.mean_gradient,
-               pool_mode=w.pool_mode, pool_line=w.pool_line, pool_segment=w.pool_segment,
-               inverse_rank_weights=w.inverse_rank_weights, tune={"record_phases": args.phases} if args.phases else None)
-    t0 = time.time()
-    nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None if w.weights is None else w.weights.to(dev), w.cluster_of.to(dev),
-                 None if w.cluster_group is None else w.cluster_group.to(dev))
-    nm.set_embedding(w.theta0.to(dev))
-    torch.cuda.synchronize()
-    setup_s = time.time() - t0
-
-    for t in range(warmup):
-        nm.epoch(t)
-    torch.cuda.synchronize()
-    nm.profile(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(warmup, warmup + steps):
-        nm.epoch(t)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    prof = nm.profile_read()
-    nm.profile(False)
-    loss = nm.loss(warmup + steps)
-    path_name, state_gb = binding.PATH_NAMES[nm.scatter_path()], nm.device_bytes() / 1e9
-    ms_per_step = 1e3 * elapsed / steps
-    grouped = w.cluster_group is not None
-    weighted = w.weights is not None or w.inverse_rank_weights
-    kernels = {}
-    for name, (ms, cnt) in prof.items():
-        if cnt:
-            ab = algorithmic_bytes(name, n, E, s, R, grouped, weighted, mode == SCATTER_DETERMINISTIC, pool)
-            # per epoch: with record phases an epoch's edge pass is several launches, each over its share of the edges
-            kernels[name] = dict(ms=ms / steps, launches=cnt, launches_per_epoch=cnt / steps, algorithmic_gb=ab / 1e9,
-                                 gbs=ab / (ms / steps) / 1e6)
-    dom = max(kernels, key=lambda k: kernels[k]["ms"])
-    if dom in ("mean_field", "mean_gradient"):
-        # n * |R| kernel evaluations (Eq. 5 and its derivative factor): plain-ALU bound, not HBM bound
-        evals = float(n) * float(R)
-        flops = MEAN_FIELD_FLOPS * evals
-        roofline = dict(bound="alu", kernel=dom, achieved=flops / (kernels[dom]["ms"] * 1e-3) / 1e12,
-                        peak=FP32_VALU_PEAK_TFLOPS, unit="TFLOP/s", traffic=None)
-    else:
-        roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s", traffic=None)
-    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    default_run = (args.config == 4 and args.scale == 1.0 and args.mode == "det" and pool is None and args.groups is None and
+                   args.batches == 1 and args.graph == "symmetrised" and not w.sampled_far_field and not w.mean_gradient and
+                   args.phases == 0)
+    m = timed_epochs(torch, w, mode, steps, warmup, batches=args.batches, phases=args.phases)
+    kernels, roofline, loss, elapsed, epoch_bytes = m["kernels"], m["roofline"], m["loss"], m["elapsed"], m["epoch_bytes"]
+    ms_per_step, path_name, state_gb, setup_s, grouped = m["ms_per_step"], m["path"], m["state_gb"], m["setup_s"], m["grouped"]
+    dom = roofline["kernel"]
     if args.scale == 1.0 and args.groups is None and pool is None and args.batches == 1 and args.graph == "symmetrised" \
             and not w.sampled_far_field and not w.mean_gradient:
-        roofline["traffic"] = measured_traffic(dom, args.config, args.mode)
-    epoch_bytes = sum(algorithmic_bytes(k, n, E, s, R, grouped, weighted, mode == SCATTER_DETERMINISTIC, pool) for k in kernels
-                      if k not in ("mean_field", "mean_gradient"))
+        roofline["traffic"] = measured_traffic(dom, args.config, args.mode, roofline.get("launches_per_epoch", 1.0))
     out = {
         "metric": "positive+negative edge updates/sec per epoch at 1 GPU",
         "value": E * (1 + s) / (elapsed / steps),
@@ -520,7 +561,32 @@ def main():
             cpu = dict(value=reps * E * (1 + s) / dt, unit="updates/s", cores=O.threads, kind="oracle",
                        sample=f"{reps} full epoch(s) of loss+gradient of {w.name} ({E} edges each) in {dt:.2f} s")
         out["cpu_baseline"] = cpu
-    nm.close()
+    if default_run and not args.no_extras:
+        # Beside the headline (which stays the i.i.d. sampler): the pooled sampler with distinct picks on the same workload,
+        # priced with its own algorithmic bytes, and the other configurations (deterministic) plus configuration 4 on the
+        # atomic path, five timed epochs each.
+        w.pool_size, w.pool_block, w.pool_mode, w.pool_line, w.pool_segment = 2048, 8192, 1, 16, 256
+        mv = timed_epochs(torch, w, SCATTER_DETERMINISTIC, 10, 3)
+        out["variants"] = {"pooled_exact": dict(summary_of(w, mv, 10), sampler="pooled, distinct picks: 2048 points in lines of 16 per block of "
+                                                "8192 positions dealt in segments of 256; the negatives of one edge are i.i.d. uniform, "
+                                                "negatives of different edges of a block are not independent (opt-in variant)")}
+        w.pool_size, w.pool_block, w.pool_mode, w.pool_line, w.pool_segment = 0, 0, 0, 1, 64
+        ma = timed_epochs(torch, w, SCATTER_ATOMIC, 5, 2)
+        out["all_configs"] = {"4_atomic": summary_of(w, ma, 5)}
+        del w
+        torch.cuda.empty_cache()
+        for cfg in (1, 2, 3, 5):
+            wc = workloads.make_config(cfg, device=dev if cfg >= 3 else "cpu")
+            torch.cuda.synchronize()
+            mc = timed_epochs(torch, wc, SCATTER_DETERMINISTIC, 5, 2)
+            out["all_configs"][str(cfg)] = summary_of(wc, mc, 5)
+            if mc["roofline"]["bound"] == "hbm":
+                out["all_configs"][str(cfg)]["roofline"]["traffic"] = measured_traffic(mc["roofline"]["kernel"], cfg, "det",
+                                                                                      mc["roofline"].get("launches_per_epoch", 1.0))
+            del wc, mc
+            torch.cuda.empty_cache()
+        out["all_configs"]["4"] = {"ms_per_step": round(ms_per_step, 4), "edges_per_s": out["edges_per_sec"], "updates_per_s": out["value"],
+                                   "frac": round(roofline["frac"], 4)}
     print(json.dumps(out))
 
 

@@ -260,6 +260,31 @@ def test_deterministic_variants_on_skewed_degrees(tune, path):
     assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
 
 
+def test_record_phases_change_the_pool_size_and_nothing_else():
+    """The edge pass of a step in 1, 3, 8 or 64 phases (sums carried from phase to phase in 64-bit fixed point): gradient
+    and embedding are the same bit for bit, the library holds less memory, and the knob is refused once the graph is set."""
+    d = dict(workload(3, 0.05).numpy())
+    runs = []
+    for phases in (1, 3, 8, 64):
+        for sub_steps in (1, 3):
+            with make_nomad(dict(d, batches_per_epoch=sub_steps), SCATTER_DETERMINISTIC, tune={"record_phases": phases}) as nm:
+                assert nm.scatter_path() == PATH_BINNED
+                for t in range(3):
+                    nm.epoch(t)
+                runs.append((phases, sub_steps, nm.get_gradient(), nm.get_embedding(), nm.device_bytes()))
+                with pytest.raises(NomadError, match="ORDER"):
+                    nm._check(nm.lib.nomad_tune(nm.ctx, 5, 2))
+    for sub_steps in (1, 3):
+        same = [r for r in runs if r[1] == sub_steps]
+        for r in same[1:]:
+            assert np.array_equal(r[2], same[0][2]) and np.array_equal(r[3], same[0][3]), (r[0], sub_steps)
+        assert same[2][4] < same[0][4]                    # eight phases hold a smaller pool than one
+    _, g_ref, _ = c_oracle.COracle(**d).epoch(runs[0][3] * 0 + d["theta0"], 0)   # and they are the oracle's numbers
+    with make_nomad(d, SCATTER_DETERMINISTIC, tune={"record_phases": 8}) as nm:
+        nm.epoch(0)
+        assert grad_err(nm.get_gradient(), g_ref) < GRAD_TOL
+
+
 # ------------------------------------------------------------------ the opt-in pooled sampler
 POOLS = [pytest.param((48, 100), id="P48-G100-general-kernels"), pytest.param((2048, 4096), id="P2048-G4096"),
          pytest.param((1000, 1024), id="P1000-G1024"), pytest.param((4096, 2048), id="P4096-G2048"),
