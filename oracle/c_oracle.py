@@ -83,7 +83,7 @@ class COracle:
                           self.pool_size, self.pool_block, int(batches_per_epoch), 0, -1, int(bool(sampled_far_field)),
                           int(bool(mean_gradient)), int(pool_mode), int(pool_line), int(pool_segment))
         self.pool_mode, self.pool_line, self.pool_segment = int(pool_mode), int(pool_line), int(pool_segment)
-        if self.pool_mode == 1:
+        if self.pool_mode in (1, 2):
             Pz, ln = self.pool_size, self.pool_line
             assert 2 <= Pz <= 4096 and Pz & (Pz - 1) == 0, "distinct picks: the pool size is a power of two, 2..4096"
             assert ln >= 1 and ln & (ln - 1) == 0 and Pz % ln == 0 and self.n_neg <= Pz // ln, "lines: a power of two, s <= lines"

@@ -54,7 +54,8 @@ typedef struct {
     int32_t mean_gradient;        /* opt-in: the gradient also flows through mu_r = (1/n_r) sum_{l in r} theta_l: every */
                                   /* member of cell r receives (1/n_r) d(n L)/d mu_r (full mode, exact far field only)  */
     int32_t pool_mode;            /* pooled sampler: 0 = 16-bit picks from the pool of a block of consecutive positions; */
-                                  /* 1 = distinct picks from the pool of an interleaved block (see edge_negatives)       */
+                                  /* 1 = distinct picks from the pool of an interleaved block (see edge_negatives);      */
+                                  /* 2 = the same with the pools' lines dealt from a permutation (stratified_line_start) */
     int32_t pool_line;            /* pool_mode 1: consecutive points per pool line, a power of two                       */
     int32_t pool_segment;         /* pool_mode 1: consecutive positions dealt to a block together: a power of two >= 64   */
                                   /* that divides pool_block                                                             */
@@ -149,12 +150,40 @@ static inline int32_t group_of_point(const oracle_problem* P, int64_t i) {
  * uniform draws: the negatives of one edge are i.i.d. uniform over the points, as Section 3.1 defines them;
  * negatives of different edges of a block are dependent.
  * sampled far field: the i.i.d. sampler with every head's population = all n points. */
+/* Stratified pools (pool_mode 2): the lines of an epoch's pools are dealt from a keyed permutation of the NL = ceil(n / l)
+ * lines of l = pool_line consecutive points, so that every line serves the same number of pools (to within one).
+ * Keys per epoch from Philox(counter (0, 0xFFFFFFFD, t, 0)) = (w0, w1, w2, w3) and (counter (1, ...)) = (w4, .., w7):
+ * multipliers A = (w0|1, w2|1, w4|1), increments C = (w1, w3, w5), cyclic shift r = floor(w6 n / 2^32).  The permutation
+ * works on b = max(1, ceil(log2 NL)) bits: three rounds of x <- (A_k x + C_k) mod 2^b; x <- x xor (x >> max(1, b / 2)),
+ * repeated until x < NL.  Line gamma of block beta starts at (l pi((beta L + gamma) mod NL) + r) mod n. */
+static uint64_t stratified_line_start(const oracle_problem* P, uint64_t n, uint64_t beta, int32_t t, uint32_t gamma, uint32_t L) {
+    uint32_t key[2] = {(uint32_t)P->seed, (uint32_t)(P->seed >> 32)};
+    uint32_t c0[4] = {0u, 0xFFFFFFFDu, (uint32_t)t, 0u}, c1[4] = {1u, 0xFFFFFFFDu, (uint32_t)t, 0u}, w[8];
+    oracle_philox4x32_10(c0, key, w);
+    oracle_philox4x32_10(c1, key, w + 4);
+    const uint64_t A[3] = {w[0] | 1u, w[2] | 1u, w[4] | 1u}, C[3] = {w[1], w[3], w[5]};
+    const uint64_t r = ((uint64_t)w[6] * n) >> 32;
+    const uint64_t line = (uint64_t)P->pool_line, NL = (n + line - 1) / line;
+    int b = 1;
+    while (((uint64_t)1 << b) < NL) ++b;
+    const uint64_t mask = ((uint64_t)1 << b) - 1;
+    const int sh = b / 2 > 1 ? b / 2 : 1;
+    uint64_t x = (beta * L + gamma) % NL;
+    do {
+        for (int k = 0; k < 3; ++k) {
+            x = (A[k] * x + C[k]) & mask;
+            x ^= x >> sh;
+        }
+    } while (x >= NL);
+    return (line * x + r) % n;
+}
+
 static void edge_negatives(const oracle_problem* P, const oracle_tables* T, int64_t e, int64_t i, int32_t t, int32_t* m) {
     int32_t g = group_of_point(P, i);
     int64_t base = T->gstart[g];
     uint64_t nloc = (uint64_t)(T->gstart[g + 1] - base);
     uint32_t key[2] = {(uint32_t)P->seed, (uint32_t)(P->seed >> 32)};
-    if (P->pool_size > 0 && P->pool_mode == 1) {
+    if (P->pool_size > 0 && (P->pool_mode == 1 || P->pool_mode == 2)) {
         const int64_t E = P->row_ptr[P->n];
         const int64_t seg = P->pool_segment;
         const int64_t NS = (E + seg - 1) / seg, Q = P->pool_block / seg;
@@ -174,10 +203,15 @@ static void edge_negatives(const oracle_problem* P, const oracle_tables* T, int6
         for (int32_t k = 0; k < P->n_neg; ++k) {
             const uint32_t u = (u0 + (uint32_t)k * c) % PS;
             const uint32_t gamma = u % L, o = u / L;
-            uint32_t pctr[4] = {(uint32_t)beta, 0xFFFFFFFFu, (uint32_t)t, gamma >> 2};
-            uint32_t pw[4];
-            oracle_philox4x32_10(pctr, key, pw);
-            const uint64_t start = ((uint64_t)pw[gamma & 3] * nloc) >> 32;
+            uint64_t start;
+            if (P->pool_mode == 2) {
+                start = stratified_line_start(P, nloc, beta, t, gamma, L);
+            } else {
+                uint32_t pctr[4] = {(uint32_t)beta, 0xFFFFFFFFu, (uint32_t)t, gamma >> 2};
+                uint32_t pw[4];
+                oracle_philox4x32_10(pctr, key, pw);
+                start = ((uint64_t)pw[gamma & 3] * nloc) >> 32;
+            }
             m[k] = T->members[base + (int64_t)((start + o) % nloc)];
         }
         return;

@@ -119,7 +119,8 @@ class Problem:
     pool_block: int = 0                       # pooled sampler: consecutive CSR positions that share a pool
     batches_per_epoch: int = 1                # B: sequential sub-steps of an epoch over consecutive head ranges
     pool_mode: int = 0                        # pooled sampler: 0 = 16-bit picks, consecutive blocks; 1 = distinct picks,
-                                              # interleaved blocks (negatives_distinct)
+                                              # interleaved blocks (negatives_distinct); 2 = the same with the pools' lines
+                                              # dealt from a permutation (stratified_line_start)
     pool_line: int = 1                        # pool_mode 1: consecutive points per pool line (a power of two)
     pool_segment: int = 64                    # pool_mode 1: consecutive CSR positions dealt to a block together (a power
                                               # of two >= 64 that divides pool_block; = pool_block: consecutive blocks)
@@ -142,8 +143,8 @@ class Problem:
             self.noise_count = float(self.n_neg)
         assert (self.pool_size == 0) == (self.pool_block == 0), "pool_size and pool_block go together"
         assert self.pool_size == 0 or self.cluster_group is None, "the pooled sampler needs a single population"
-        assert self.pool_mode in (0, 1) and (self.pool_mode == 0 or self.pool_size > 0), "pool_mode 1 needs a pool"
-        if self.pool_mode == 1:
+        assert self.pool_mode in (0, 1, 2) and (self.pool_mode == 0 or self.pool_size > 0), "pool_mode 1 and 2 need a pool"
+        if self.pool_mode in (1, 2):
             P_, l_ = self.pool_size, self.pool_line
             assert P_ >= 2 and P_ & (P_ - 1) == 0 and P_ <= 4096, "distinct picks: the pool size is a power of two, 2..4096"
             assert l_ >= 1 and l_ & (l_ - 1) == 0 and P_ % l_ == 0 and self.n_neg <= P_ // l_, "lines: a power of two, s <= lines"
@@ -287,9 +288,50 @@ def distinct_pool_entry(P: Problem, beta: int, t: int, u: int) -> int:
     shifted by a constant, modulo n), entries of different lines are independent."""
     L = P.pool_size // P.pool_line
     gamma, o = u % L, u // L
+    if P.pool_mode == 2:
+        return (stratified_line_start(P, beta, t, gamma) + o) % P.n
     k0, k1 = P.seed & _MASK32, (P.seed >> 32) & _MASK32
     x = philox4x32_10((beta & _MASK32, _POOL_ENTRY_STREAM, t, gamma >> 2), (k0, k1))[gamma & 3]
     return (((x * P.n) >> 32) + o) % P.n
+
+
+_POOL_KEY_STREAM = 0xFFFFFFFD
+
+
+def stratified_keys(P: Problem, t: int):
+    """Per-epoch constants of the stratified pools (pool_mode = 2): three odd multipliers A_k, three increments C_k and
+    a shift r_t uniform over the points, from two Philox calls with counters (0, 0xFFFFFFFD, t, 0) and (1, 0xFFFFFFFD, t, 0)."""
+    k0, k1 = P.seed & _MASK32, (P.seed >> 32) & _MASK32
+    w = philox4x32_10((0, _POOL_KEY_STREAM, t, 0), (k0, k1)) + philox4x32_10((1, _POOL_KEY_STREAM, t, 0), (k0, k1))
+    return (w[0] | 1, w[2] | 1, w[4] | 1), (w[1], w[3], w[5]), (w[6] * P.n) >> 32
+
+
+def stratified_line_permutation(x: int, n_lines: int, A, C) -> int:
+    """A keyed bijection of 0 .. n_lines-1: on b = max(1, ceil(log2 n_lines)) bits, three rounds of
+    x <- (A_k x + C_k) mod 2^b; x <- x xor (x >> max(1, b // 2)) (each a bijection of the b-bit numbers), repeated
+    until the value is below n_lines (cycle walking keeps it a bijection of the smaller range)."""
+    b = max(1, (n_lines - 1).bit_length())
+    mask, sh = (1 << b) - 1, max(1, b // 2)
+    while True:
+        for k in range(3):
+            x = (A[k] * x + C[k]) & mask
+            x ^= x >> sh
+        if x < n_lines:
+            return x
+
+
+def stratified_line_start(P: Problem, beta: int, t: int, gamma: int) -> int:
+    """First point of line gamma of block beta's pool in epoch t (pool_mode = 2).  The n points form NL = ceil(n / l)
+    lines of l = pool_line consecutive points; the lines an epoch's pools consist of are dealt from a permutation:
+    block beta's line gamma is line number pi_t((beta L + gamma) mod NL), shifted cyclically by r_t:
+    start = (l pi_t(.) + r_t) mod n.  Every line of points is then used by the same number of pools of an epoch
+    (to within one), instead of a Poisson-distributed number: what a point receives as a negative over an epoch
+    fluctuates as little as with independent draws per edge.  Every start is still uniform over the points (r_t is);
+    the lines of one pool are distinct, i.e. drawn without replacement."""
+    L = P.pool_size // P.pool_line
+    NL = (P.n + P.pool_line - 1) // P.pool_line
+    A, C, r = stratified_keys(P, t)
+    return (P.pool_line * stratified_line_permutation((beta * L + gamma) % NL, NL, A, C) + r) % P.n
 
 
 def distinct_picks(P: Problem, beta: int, rank: int, t: int):
@@ -338,7 +380,7 @@ def negatives(P: Problem, t: int, e_begin: int = 0, e_end: Optional[int] = None)
     out = np.zeros((e_end - e_begin, s), dtype=np.int64)
     if s == 0 or e_end == e_begin:
         return out
-    if P.pool_mode == 1:
+    if P.pool_mode in (1, 2):
         return negatives_distinct(P, t, e_begin, e_end)
     e = np.arange(e_begin, e_end, dtype=np.uint64)
     k0, k1 = P.seed & _MASK32, (P.seed >> 32) & _MASK32

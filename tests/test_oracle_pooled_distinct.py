@@ -183,3 +183,99 @@ def test_loss_gradient_and_epoch_with_distinct_picks(impl):
         assert np.abs(fd - g).max() < 1e-7 * max(1.0, np.abs(g).max())
     nxt, g3, _ = O.epoch(theta, 2)
     assert np.array_equal(nxt, (theta.astype(np.float64) - 0.3 * (1 - 2 / 6) * g).astype(np.float32)) and np.array_equal(g3, g)
+
+
+# ---------------------------------------------------------------- stratified pools (pool_mode = 2)
+def _stratified(n, seed, s, P, G, line, segment=64, deg=6.0):
+    return dict(_problem(n, seed, s, P, G, line, deg=deg, segment=segment), pool_mode=2)
+
+
+def test_line_permutation_is_a_bijection_for_every_size_and_key():
+    rng = np.random.default_rng(1)
+    for NL in (1, 2, 3, 5, 8, 13, 64, 100, 257, 1000, 4097):
+        for _ in range(4):
+            A = tuple(int(x) | 1 for x in rng.integers(0, 2 ** 32, 3))
+            C = tuple(int(x) for x in rng.integers(0, 2 ** 32, 3))
+            out = [po.stratified_line_permutation(x, NL, A, C) for x in range(NL)]
+            assert sorted(out) == list(range(NL))
+    # keys: two Philox calls; the multipliers are odd, the shift lies in the points' range, another epoch gives other keys
+    P = po.Problem(**_stratified(300, 3, 3, 16, 64, 2))
+    A, C, r = po.stratified_keys(P, 4)
+    w = po.philox4x32_10((0, 0xFFFFFFFD, 4, 0), (P.seed & 0xFFFFFFFF, P.seed >> 32)) + po.philox4x32_10((1, 0xFFFFFFFD, 4, 0), (P.seed & 0xFFFFFFFF, P.seed >> 32))
+    assert A == (w[0] | 1, w[2] | 1, w[4] | 1) and C == (w[1], w[3], w[5]) and r == (w[6] * 300) >> 32 and 0 <= r < 300
+    assert po.stratified_keys(P, 5) != po.stratified_keys(P, 4)
+
+
+def test_every_line_of_points_serves_the_same_number_of_pools():
+    """What the variant is for: over the pools of one epoch every line of points is used floor or ceil(NB L / NL) times, so
+    every point is a pool member equally often (independent draws would give a Poisson-distributed number)."""
+    for (n, P_, G, line) in ((640, 64, 128, 4), (1000, 16, 64, 1), (784, 256, 1024, 16)):
+        kw = _stratified(n, 4, 3, P_, G, line)
+        P = po.Problem(**kw)
+        NB, _, _ = po.distinct_pool_layout(P)
+        L, NL = P_ // line, n // line
+        for t in (0, 3):
+            members = np.zeros(n, int)
+            for beta in range(NB):
+                pool = [po.distinct_pool_entry(P, beta, t, u) for u in range(P_)]
+                assert len(set(pool)) == P_                                       # the lines of one pool are distinct (n is a multiple of the line)
+                for g in range(L):
+                    assert [(pool[o * L + g] - pool[g]) % n for o in range(line)] == list(range(line))
+                np.add.at(members, pool, 1)
+            lo, hi = (NB * L) // NL, -(-(NB * L) // NL)
+            assert members.min() >= lo and members.max() <= hi and members.sum() == NB * P_
+        iid = po.Problem(**dict(kw, pool_mode=1))
+        spread = np.zeros(n, int)
+        for beta in range(NB):
+            np.add.at(spread, [po.distinct_pool_entry(iid, beta, 0, u) for u in range(P_)], 1)
+        assert spread.max() - spread.min() > hi - lo + 1                          # independent draws are not that even
+
+
+def test_stratified_negatives_are_uniform_over_the_points_and_both_implementations_agree():
+    for (n, s, P_, G, line, seg) in ((300, 5, 64, 128, 4, 64), (1000, 3, 16, 64, 1, 64), (777, 7, 256, 1024, 16, 256), (50, 4, 8, 192, 2, 64),
+                                     (5000, 5, 2048, 4096, 16, 1024)):
+        kw = _stratified(n, 3, s, P_, G, line, segment=seg)
+        a, b = IMPLS["py"](**kw), IMPLS["c"](**kw)
+        hi = min(len(kw["col_idx"]), 2500)
+        for t in (0, 6):
+            assert np.array_equal(a.negatives(t, 0, hi), b.negatives(t, 0, hi))
+    n = 24
+    O = IMPLS["c"](**_stratified(n, 6, 3, 16, 64, 1, deg=5.0))    # lines of one point: no pair of points is ruled out but (a, a)
+    single = np.zeros(n)
+    pairs = np.zeros((n, n))
+    for t in range(6000):
+        m = O.negatives(t)[::5]
+        np.add.at(single, m[:, 1], 1)
+        np.add.at(pairs, (m[:, 0], m[:, 2]), 1)
+    chi1 = ((single - single.sum() / n) ** 2 / (single.sum() / n)).sum()
+    assert chi1 < (n - 1) + 24 * math.sqrt(2 * (n - 1))                       # every negative is uniform (the shift r_t is)
+    # two negatives of an edge lie in different lines: never the same point, every other pair about equally often
+    assert np.trace(pairs) == 0
+    off = pairs[~np.eye(n, dtype=bool)]
+    assert off.min() > 0.6 * off.mean() and off.max() < 1.5 * off.mean()
+
+
+def test_expected_loss_with_stratified_pools_is_eq_2_with_noise_samples_drawn_without_replacement():
+    """Lines of one point: the s negatives of an edge are s different points, (close to) uniform over such tuples, so the
+    expectation of the sampled loss is Eq. 2's with the noise samples of an edge drawn without replacement, enumerated here
+    on 7 points; the difference to independent draws is of order s^2 / n and vanishes at real sizes."""
+    n, M = 7, 2
+    row_ptr = np.arange(0, 2 * n + 1, 2)
+    col = np.stack([(np.arange(n) - 1) % n, (np.arange(n) + 1) % n], 1).reshape(-1)
+    rng = np.random.default_rng(5)
+    theta = (np.round(rng.normal(size=(n, 2)) * 0.8 * 1024) / 1024).astype(np.float32)
+    th = theta.astype(np.float64)
+    q = 1.0 / (1.0 + ((th[:, None, :] - th[None, :, :]) ** 2).sum(-1))
+    exact = 0.0
+    for i in range(n):
+        for e in range(row_ptr[i], row_ptr[i + 1]):
+            j = col[e]
+            exact += sum(-math.log(q[i, j] / (q[i, j] + q[i, a] + q[i, b])) for a in range(n) for b in range(n) if a != b) / (n * (n - 1)) / 2
+    exact /= n
+    kw = dict(n=n, row_ptr=row_ptr, col_idx=col, cluster_of=np.zeros(n, int), n_clusters=1, n_neg=M, noise_count=float(M), seed=99,
+              pool_size=4, pool_block=64, pool_mode=2, pool_line=1)
+    T = 20000
+    O = IMPLS["c"](**kw)
+    draws = np.array([O.loss_and_grad(theta, t, want_grad=False)[0] for t in range(T)])
+    se = draws.std() / math.sqrt(T)
+    assert abs(draws.mean() - exact) < 5 * se + 2e-3 * exact       # the keyed permutations are not all permutations: a small allowance
