@@ -277,7 +277,7 @@ def pool_of(w):
     """(pool size, block[, line, segment]) of a workload's pooled sampler, or None."""
     if not w.pool_size:
         return None
-    return (w.pool_size, w.pool_block, w.pool_line, w.pool_segment) if w.pool_mode == 1 else (w.pool_size, w.pool_block)
+    return (w.pool_size, w.pool_block, w.pool_line, w.pool_segment, w.pool_mode) if w.pool_mode else (w.pool_size, w.pool_block)
 
 
 def timed_epochs(torch, w, mode, steps, warmup, batches=1, phases=0):
@@ -402,7 +402,7 @@ def main():
     ap.add_argument("--groups", type=int, default=None, help="deal the clusters into this many groups")
     ap.add_argument("--pool", default=None, metavar="P,G",
                     help="opt-in pooled sampler: pool size and block length (e.g. 2048,4096), or P,G,line,segment for the "
-                         "sampler with distinct picks (e.g. 4096,8192,16,256); not the benchmark's sampler")
+                         "sampler with distinct picks (e.g. 4096,8192,16,256; a fifth value 2 selects stratified pools); not the benchmark's sampler")
     ap.add_argument("--graph", choices=["symmetrised", "paper"], default="symmetrised",
                     help="paper: the directed kNN graph with inverse-rank weights of Section 3.1 / Eq. 7 (planted configs); "
                          "the benchmark uses the symmetrised unit-weight graph")
@@ -479,8 +479,8 @@ def main():
     if args.pool:
         pool = tuple(int(x) for x in args.pool.split(","))
         w.pool_size, w.pool_block = pool[:2]
-        if len(pool) == 4:                      # points per pool line, segment: the sampler with distinct picks
-            w.pool_mode, w.pool_line, w.pool_segment = 1, pool[2], pool[3]
+        if len(pool) >= 4:                      # points per pool line, segment[, mode]: the sampler with distinct picks
+            w.pool_mode, w.pool_line, w.pool_segment = (pool[4] if len(pool) == 5 else 1), pool[2], pool[3]
     n, E, s, R = w.n, w.n_edges, w.n_neg, w.n_clusters
     steps, warmup = args.steps, args.warmup
     if warmup + steps > w.n_epochs:
@@ -511,7 +511,8 @@ def main():
                    "scatter_mode": args.mode,
                    "batches_per_epoch": args.batches,
                    "sampler": "iid per edge" if pool is None else f"pooled, {pool[0]} points per block of {pool[1]} edges (opt-in variant)"
-                              + (f", distinct picks, lines of {pool[2]} points, segments of {pool[3]} positions" if len(pool) == 4 else ""),
+                              + (f", distinct picks, lines of {pool[2]} points, segments of {pool[3]} positions" if len(pool) >= 4 else "")
+                              + (", stratified pools" if len(pool) == 5 and pool[4] == 2 else ""),
                    "scatter_path": None,
                    "far_field": "Eq. 5 summed over the approximated cells" if not w.sampled_far_field else
                                 "estimated from the samples (opt-in variant)",
@@ -565,11 +566,17 @@ def main():
         # Beside the headline (which stays the i.i.d. sampler): the pooled sampler with distinct picks on the same workload,
         # priced with its own algorithmic bytes, and the other configurations (deterministic) plus configuration 4 on the
         # atomic path, five timed epochs each.
-        w.pool_size, w.pool_block, w.pool_mode, w.pool_line, w.pool_segment = 2048, 8192, 1, 16, 256
-        mv = timed_epochs(torch, w, SCATTER_DETERMINISTIC, 10, 3)
-        out["variants"] = {"pooled_exact": dict(summary_of(w, mv, 10), sampler="pooled, distinct picks: 2048 points in lines of 16 per block of "
-                                                "8192 positions dealt in segments of 256; the negatives of one edge are i.i.d. uniform, "
-                                                "negatives of different edges of a block are not independent (opt-in variant)")}
+        out["variants"] = {}
+        for key, pmode, text in (("pooled_exact", 1, "the negatives of one edge are i.i.d. uniform, negatives of different edges of a block are "
+                                                       "not independent"),
+                                 ("pooled_stratified", 2, "as pooled_exact with the pools' lines dealt from a permutation of the lines of points: "
+                                                          "every point is a pool member equally often; the negatives of one edge are drawn "
+                                                          "without replacement at line granularity")):
+            psize = 2048 if pmode == 1 else 4096
+            w.pool_size, w.pool_block, w.pool_mode, w.pool_line, w.pool_segment = psize, 8192, pmode, 16, 256
+            mv = timed_epochs(torch, w, SCATTER_DETERMINISTIC, 10, 3)
+            out["variants"][key] = dict(summary_of(w, mv, 10), sampler=f"pooled, distinct picks: {psize} points in lines of 16 per block of 8192 "
+                                        "positions dealt in segments of 256; " + text + " (opt-in variant)")
         w.pool_size, w.pool_block, w.pool_mode, w.pool_line, w.pool_segment = 0, 0, 0, 1, 64
         ma = timed_epochs(torch, w, SCATTER_ATOMIC, 5, 2)
         out["all_configs"] = {"4_atomic": summary_of(w, ma, 5)}

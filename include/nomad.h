@@ -74,11 +74,11 @@ typedef struct {
                                /* NOMAD_FAR_FIELD_SAMPLED (opt-in estimate of it, see below)            */
     int32_t mean_gradient;     /* 0: the cell means are constants of an epoch (no gradient flows through */
                                /* them); 1: opt-in, see below                                            */
-    int32_t pool_mode;         /* pooled sampler: NOMAD_POOL_PICKS16 (0) or NOMAD_POOL_DISTINCT (1), see below; */
+    int32_t pool_mode;         /* pooled sampler: NOMAD_POOL_PICKS16 (0), NOMAD_POOL_DISTINCT (1) or NOMAD_POOL_STRATIFIED (2), see below; */
                                /* 0 when pool_size is 0                                                  */
-    int32_t pool_line;         /* NOMAD_POOL_DISTINCT: consecutive points per pool line, a power of two   */
+    int32_t pool_line;         /* NOMAD_POOL_DISTINCT / _STRATIFIED: consecutive points per pool line, a power of two */
                                /* (1 = every pool entry drawn on its own); 0 is read as 1                 */
-    int32_t pool_segment;      /* NOMAD_POOL_DISTINCT: consecutive CSR positions dealt to a block together, a */
+    int32_t pool_segment;      /* NOMAD_POOL_DISTINCT / _STRATIFIED: consecutive CSR positions dealt to a block together, a */
                                /* power of two >= 64 that divides pool_block; 0 is read as 64; not used by */
                                /* NOMAD_POOL_PICKS16                                                      */
     int32_t edge_weights;      /* NOMAD_WEIGHTS_GIVEN (0): p(j|i) from nomad_set_graph's weights;          */
@@ -136,6 +136,7 @@ typedef struct {
 #define NOMAD_MAX_POOL 4096
 #define NOMAD_POOL_PICKS16 0
 #define NOMAD_POOL_DISTINCT 1
+#define NOMAD_POOL_STRATIFIED 2
 
 /*
  * Pooled sampler with distinct picks (pool_mode = NOMAD_POOL_DISTINCT; opt-in like the variant above, same
@@ -156,6 +157,18 @@ typedef struct {
  * the points.  Negatives of different edges of a block share lines and are dependent; spreading a block over the
  * edge list (small g) makes the edges that share a pool come from unrelated neighbourhoods.  The fast kernel
  * applies when pool_block is 1024, 2048, 4096 or 8192 and its tables fit LDS; other shapes run the general kernels.
+ *
+ * Stratified pools (pool_mode = NOMAD_POOL_STRATIFIED): as NOMAD_POOL_DISTINCT, except for where the lines of a pool start.
+ * With independent draws the number of pools a point belongs to in one epoch is Poisson-distributed, and what a point
+ * receives as a negative comes in bursts: on data with real neighbourhood structure that costs quality.  Here the
+ * lines of an epoch's pools are dealt from a keyed permutation pi_t of the NL = ceil(n / pool_line) lines of
+ * consecutive points: line gamma of block beta starts at (pool_line pi_t((beta L + gamma) mod NL) + r_t) mod n, so every
+ * line of points serves the same number of pools (to within one).  Keys per epoch from two Philox calls, counters
+ * (0, 0xFFFFFFFD, t, 0) -> (w0..w3) and (1, 0xFFFFFFFD, t, 0) -> (w4..w7): multipliers A = (w0|1, w2|1, w4|1), increments
+ * C = (w1, w3, w5), shift r_t = floor(w6 n / 2^32).  pi_t works on b = max(1, ceil(log2 NL)) bits: three rounds of
+ * x <- (A_k x + C_k) mod 2^b, x <- x xor (x >> max(1, b / 2)), repeated until x < NL.  Every negative is still uniform
+ * over the points (r_t is uniform); the lines of one pool are distinct, i.e. the negatives of one edge are drawn
+ * without replacement at the granularity of lines instead of independently (a difference of order s^2 pool_line / n).
  */
 
 /* Create a context.  Allocates nothing on the device yet.  *out is set only on success. */

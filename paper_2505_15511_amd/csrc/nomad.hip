@@ -74,6 +74,7 @@ struct nomad_ctx {
     int path = 0;                   // NOMAD_PATH_* in use
     int phases = 1;                 // record phases of the binned edge pass
     unsigned long long* carry = nullptr;   // [2 n] fixed-point sums carried from phase to phase (phases > 1)
+    uint32_t* pool_keys = nullptr;  // stratified pools: the keys of the epoch whose kernels run next on the stream
     bool distinct_kernel = false;   // the pooled edge pass is the one for distinct picks
     uint32_t pool_blocks = 1;       // distinct picks: number of blocks
     std::unordered_map<const void*, size_t> allocations;   // device memory held, by pointer
@@ -138,7 +139,7 @@ void free_graph(nomad_ctx* c) {
     c->through_means = false;
     dev_free(c, c->flags);
     dev_free(c, c->pool); dev_free(c, c->chunk_prev); dev_free(c, c->chain_head); dev_free(c, c->chain_fill); dev_free(c, c->wg_pool_begin);
-    dev_free(c, c->head); dev_free(c, c->overflow); dev_free(c, c->carry);
+    dev_free(c, c->head); dev_free(c, c->overflow); dev_free(c, c->carry); dev_free(c, c->pool_keys);
     c->phases = 1;
     c->binned = false;
     c->pool_rounds = 0;
@@ -214,6 +215,9 @@ EdgeArgs edge_args(nomad_ctx* c, uint32_t t) {
     a.pool_mode = (uint32_t)c->cfg.pool_mode;
     a.pool_line_bits = log2_of(c->cfg.pool_line); a.pool_segment_bits = log2_of(c->cfg.pool_segment);
     a.pool_blocks = c->pool_blocks;
+    a.pool_keys = c->pool_keys;
+    if (c->cfg.pool_mode == NOMAD_POOL_STRATIFIED)   // the keys of epoch t, ahead of the kernels that read them on the same stream
+        hipLaunchKernelGGL(k_pool_keys, dim3(1), dim3(64), 0, c->stream, a.key0, a.key1, t, (uint32_t)c->n, c->pool_keys);
     a.s = c->cfg.n_neg; a.n = c->n; a.row_begin = 0; a.row_end = c->n;
     a.g = c->g; a.ghead = c->ghead; a.gfix = c->gfix; a.loss_partial = c->loss_partial;
     a.cS = nullptr;   // set by nomad_epoch when the gradient flows through the means
@@ -383,9 +387,10 @@ int nomad_create(const nomad_config* cfg, nomad_ctx** out) {
     if ((cfg->far_field != NOMAD_FAR_FIELD_EXACT && cfg->far_field != NOMAD_FAR_FIELD_SAMPLED) ||
         (cfg->far_field == NOMAD_FAR_FIELD_SAMPLED && cfg->pool_size > 0))
         return NOMAD_E_INVALID_ARG;
-    if (cfg->pool_mode != NOMAD_POOL_PICKS16 && cfg->pool_mode != NOMAD_POOL_DISTINCT) return NOMAD_E_INVALID_ARG;
+    if (cfg->pool_mode != NOMAD_POOL_PICKS16 && cfg->pool_mode != NOMAD_POOL_DISTINCT && cfg->pool_mode != NOMAD_POOL_STRATIFIED)
+        return NOMAD_E_INVALID_ARG;
     if (cfg->pool_mode == NOMAD_POOL_PICKS16 && (cfg->pool_line > 1 || cfg->pool_line < 0 || cfg->pool_segment < 0)) return NOMAD_E_INVALID_ARG;
-    if (cfg->pool_mode == NOMAD_POOL_DISTINCT) {
+    if (cfg->pool_mode == NOMAD_POOL_DISTINCT || cfg->pool_mode == NOMAD_POOL_STRATIFIED) {
         const int line = cfg->pool_line ? cfg->pool_line : 1, seg = cfg->pool_segment ? cfg->pool_segment : 64;
         if (cfg->pool_size < 2 || !is_power_of_two(cfg->pool_size) || !is_power_of_two(line) || line > cfg->pool_size ||
             cfg->n_neg > cfg->pool_size / line || seg < 64 || !is_power_of_two(seg) || cfg->pool_block % seg != 0 ||
@@ -634,7 +639,8 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
     }
 
     c->pool_blocks = 1;
-    if (c->cfg.pool_mode == NOMAD_POOL_DISTINCT) {   // blocks of the pooled sampler with distinct picks: NB = ceil(NS / Q)
+    if (c->cfg.pool_mode != NOMAD_POOL_PICKS16) {   // blocks of the pooled sampler with distinct picks: NB = ceil(NS / Q)
+        if (c->cfg.pool_mode == NOMAD_POOL_STRATIFIED) TRY(dev_alloc(c, &c->pool_keys, 8));
         const int64_t seg = c->cfg.pool_segment, NS = (E + seg - 1) / seg, Qs = c->cfg.pool_block / seg;
         c->pool_blocks = (uint32_t)std::max<int64_t>(1, (NS + Qs - 1) / Qs);
     }
@@ -671,7 +677,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         if (c->cfg.pool_size > 0 && c->cfg.pool_block % 1024 == 0 && c->tune_pool_kernel) {
             const int r = c->cfg.pool_block / 1024;
             if (r == 1 || r == 2 || r == 4 || r == 8) {
-                if (c->cfg.pool_mode == NOMAD_POOL_DISTINCT) {
+                if (c->cfg.pool_mode != NOMAD_POOL_PICKS16) {
                     // 32-bit byte offsets into col / head (4 E) and theta (8 n)
                     if (distinct_lds_bytes(n_bins, (uint32_t)c->cfg.pool_size, (uint32_t)(c->cfg.pool_size / c->cfg.pool_line), r) <= kMaxLdsBytes &&
                         E < ((int64_t)1 << 30) && n < ((int64_t)1 << 29)) { pool_rounds = r; distinct = true; }

@@ -352,6 +352,7 @@ struct EdgeArgs {
     uint32_t pool_line_bits;          // distinct picks: log2 of the points per pool line
     uint32_t pool_segment_bits;       // distinct picks: log2 of the positions dealt to a block together
     uint32_t pool_blocks;             // distinct picks: number of blocks NB
+    const uint32_t* pool_keys;        // stratified pools: this epoch's (A0, A1, A2, C0, C1, C2, r, 0), written by k_pool_keys
     int32_t s;
     int64_t n;
     int64_t row_begin, row_end;    // heads this launch covers (a sub-step of a minibatch epoch; else 0, n)
@@ -484,13 +485,54 @@ __device__ __forceinline__ uint32_t distinct_pick(uint32_t W, int k, uint32_t po
     return (u0 + (uint32_t)k * c) & (pool_size - 1u);
 }
 
+// ---- stratified pools (pool_mode 2, see nomad.h): the lines of an epoch's pools are dealt from a keyed permutation
+constexpr uint32_t kPoolKeyStream = 0xFFFFFFFDu;
+
+// this epoch's keys: multipliers (odd), increments, cyclic shift of the lines
+__global__ void k_pool_keys(uint32_t key0, uint32_t key1, uint32_t epoch, uint32_t n, uint32_t* __restrict__ keys) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    uint32_t a[4], b[4];
+    philox4x32_10(0u, kPoolKeyStream, epoch, 0u, key0, key1, a);
+    philox4x32_10(1u, kPoolKeyStream, epoch, 0u, key0, key1, b);
+    keys[0] = a[0] | 1u; keys[1] = a[2] | 1u; keys[2] = b[0] | 1u;
+    keys[3] = a[1]; keys[4] = a[3]; keys[5] = b[1];
+    keys[6] = __umulhi(b[2], n);
+    keys[7] = 0u;
+}
+
+// the keyed bijection of 0 .. n_lines-1: three rounds of x <- (A_k x + C_k) mod 2^b, x <- x xor (x >> max(1, b / 2)) on
+// b = max(1, ceil(log2 n_lines)) bits, repeated until the value lies below n_lines
+__device__ __forceinline__ uint32_t line_permutation(uint32_t x, uint32_t n_lines, const uint32_t* __restrict__ keys) {
+    const uint32_t b = n_lines > 2u ? 32u - (uint32_t)__clz(n_lines - 1u) : 1u;
+    const uint32_t mask = b >= 32u ? 0xFFFFFFFFu : (1u << b) - 1u, sh = b / 2u > 1u ? b / 2u : 1u;
+    const uint32_t A0 = keys[0], A1 = keys[1], A2 = keys[2], C0 = keys[3], C1 = keys[4], C2 = keys[5];
+    do {
+        x = (A0 * x + C0) & mask; x ^= x >> sh;
+        x = (A1 * x + C1) & mask; x ^= x >> sh;
+        x = (A2 * x + C2) & mask; x ^= x >> sh;
+    } while (x >= n_lines);
+    return x;
+}
+
+// first point of the line with running number `index` (= beta L + gamma) of this epoch
+__device__ __forceinline__ uint32_t stratified_line_start(const EdgeArgs& P, uint64_t index) {
+    const uint32_t n = (uint32_t)P.n, n_lines = (n + (1u << P.pool_line_bits) - 1u) >> P.pool_line_bits;
+    const uint32_t x = line_permutation((uint32_t)(index % n_lines), n_lines, P.pool_keys);
+    return (uint32_t)((((uint64_t)x << P.pool_line_bits) + P.pool_keys[6]) % n);
+}
+
 // point behind entry u of block beta's pool: point number (u div L) of line (u mod L)
 __device__ __forceinline__ int32_t distinct_pool_point(const EdgeArgs& P, uint32_t beta, uint32_t u) {
     const uint32_t lg = 31u - (uint32_t)__clz(P.pool_size), lg_lines = lg - P.pool_line_bits;
     const uint32_t gamma = u & ((1u << lg_lines) - 1u), o = u >> lg_lines;
-    uint32_t w[4];
-    philox4x32_10(beta, kPoolEntryStream, P.epoch, gamma >> 2, P.key0, P.key1, w);
-    uint32_t pt = __umulhi(w[gamma & 3u], (uint32_t)P.n) + o;
+    uint32_t pt;
+    if (P.pool_mode == 2) {
+        pt = stratified_line_start(P, ((uint64_t)beta << lg_lines) + gamma) + o;
+    } else {
+        uint32_t w[4];
+        philox4x32_10(beta, kPoolEntryStream, P.epoch, gamma >> 2, P.key0, P.key1, w);
+        pt = __umulhi(w[gamma & 3u], (uint32_t)P.n) + o;
+    }
     if (pt >= (uint32_t)P.n) pt -= (uint32_t)P.n;
     return (int32_t)pt;
 }
@@ -511,7 +553,7 @@ __device__ __forceinline__ uint32_t distinct_edge_word(const EdgeArgs& P, uint32
 // Negative of slot k of CSR position e in epoch P.epoch (general form, any s).
 __device__ __forceinline__ int32_t negative_of_slot(const EdgeArgs& P, const Population& pop, int32_t e, int k) {
     uint32_t w[4];
-    if (P.pool_mode == 1) {
+    if (P.pool_mode != 0) {
         uint32_t beta, rank;
         distinct_block_of(P, (uint32_t)e, beta, rank);
         return distinct_pool_point(P, beta, distinct_pick(distinct_edge_word(P, beta, rank), k, P.pool_size));
@@ -536,7 +578,7 @@ __device__ __forceinline__ void draw_negatives(const EdgeArgs& P, const Populati
             for (int l = 0; l < 4; ++l)
                 if (4 * b + l < S) m[4 * b + l] = draw_index(w[l], pop);
         }
-    } else if (P.pool_mode == 1) {
+    } else if (P.pool_mode != 0) {
         uint32_t beta, rank;
         distinct_block_of(P, (uint32_t)e, beta, rank);
         const uint32_t W = distinct_edge_word(P, beta, rank);
@@ -1377,7 +1419,10 @@ __global__ void __launch_bounds__(1024) k_edges_pooled_distinct(const EdgeArgs P
     // lane index idx = tid + 1024 k stands for point number idx % pool_line of line idx / pool_line, i.e. entry
     // (idx % pool_line) L + idx / pool_line: adjacent lanes read adjacent points
     auto draw_lines = [&](uint32_t blk) {
-        if (4u * tid < L && blk < NB) {
+        if (P.pool_mode == 2) {   // stratified pools: the block's lines, dealt from this epoch's permutation of the lines
+            if (blk < NB)         // (up to 4096 lines when a line is a single point: more than one per lane)
+                for (uint32_t g = tid; g < L; g += BS) line_start[g] = stratified_line_start(P, (uint64_t)blk * L + g);
+        } else if (4u * tid < L && blk < NB) {
             uint32_t wd[4];
             philox4x32_10(blk, kPoolEntryStream, P.epoch, tid, P.key0, P.key1, wd);
 #pragma unroll

@@ -319,14 +319,25 @@ DISTINCT = [pytest.param((2048, 4096, 16, 256), id="P2048-G4096-line16-seg256"),
             pytest.param((256, 4096, 8, 2048), id="P256-G4096-line8-seg2048")]
 
 
+# the same sampler with stratified pools (pool_mode 2): the last field
+STRATIFIED = [pytest.param((2048, 8192, 16, 256, 2), id="stratified-P2048-G8192-line16-seg256"),
+              pytest.param((1024, 1024, 1, 64, 2), id="stratified-P1024-G1024-line1-seg64"),
+              pytest.param((4096, 4096, 64, 4096, 2), id="stratified-P4096-G4096-line64-consecutive"),
+              pytest.param((4096, 2048, 1, 256, 2), id="stratified-P4096-G2048-line1-seg256"),      # more lines than lanes
+              pytest.param((2048, 8192, 1, 256, 2), id="stratified-P2048-G8192-line1-seg256"),
+              pytest.param((32, 320, 4, 64, 2), id="stratified-P32-G320-general-kernels")]
+
+
 @pytest.mark.parametrize("mode", MODES)
-@pytest.mark.parametrize("pool", DISTINCT)
+@pytest.mark.parametrize("pool", DISTINCT + STRATIFIED)
 def test_pooled_sampler_with_distinct_picks_negatives_gradient_and_loss(pool, mode):
+    pool_mode = pool[4] if len(pool) == 5 else 1
+    pool = pool[:4]
     for case in ("config3@0.05", "skewed", "tiny"):
         d = dict(workload(3, 0.05).numpy()) if case == "config3@0.05" else skewed_degree_graph(6) if case == "skewed" else \
             small_random(9, n=300, groups=False, weights=True, s=5, M=5.0)
         d["pool_size"], d["pool_block"], d["pool_line"], d["pool_segment"] = pool
-        d["pool_mode"] = 1
+        d["pool_mode"] = pool_mode
         O = c_oracle.COracle(**d)
         E = len(d["col_idx"])
         th1, g_ref, _ = O.epoch(d["theta0"], 0)
