@@ -59,17 +59,17 @@ def algorithmic_bytes(kernel, n, E, s, R, grouped, weighted, deterministic, pool
     raise KeyError(kernel)
 
 
-def measured_traffic(kernel, config, mode, launches_per_epoch=1.0):
-    """HBM bytes per launch from the committed rocprofv3 counter summary (profiles/hbm_bytes_per_launch.txt: lines
-    `<config> <mode> <kernel> <bytes of that kernel's launches of one epoch>`), or None if that kernel and workload
+def measured_traffic(kernel, config, mode, launches_per_epoch=1.0, sampler="iid"):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (profiles/hbm_bytes_per_epoch.txt: lines
+    `<config> <mode> <sampler> <kernel> <bytes of that kernel's launches of one epoch>`), or None if that kernel and workload
     have not been profiled.  The counters do not depend on how many launches an epoch's edge pass is cut into."""
-    path = os.path.join(ROOT, "profiles", "hbm_bytes_per_launch.txt")
+    path = os.path.join(ROOT, "profiles", "hbm_bytes_per_epoch.txt")
     try:
         with open(path) as fh:
             for line in fh:
                 f = line.split()
-                if len(f) >= 4 and not line.startswith("#") and f[0] == f"config{config}" and f[1] == mode and f[2] == kernel:
-                    return float(f[3]) / launches_per_epoch
+                if len(f) >= 5 and not line.startswith("#") and f[:4] == [f"config{config}", mode, sampler, kernel]:
+                    return float(f[4]) / launches_per_epoch
     except OSError:
         pass
     return None
@@ -575,10 +575,12 @@ def main():
             psize = 2048 if pmode == 1 else 4096
             w.pool_size, w.pool_block, w.pool_mode, w.pool_line, w.pool_segment = psize, 8192, pmode, 16, 256
             mv = timed_epochs(torch, w, SCATTER_DETERMINISTIC, 10, 3)
+            mv["roofline"]["traffic"] = measured_traffic(mv["roofline"]["kernel"], 4, "det", 1.0, key)
             out["variants"][key] = dict(summary_of(w, mv, 10), sampler=f"pooled, distinct picks: {psize} points in lines of 16 per block of 8192 "
                                         "positions dealt in segments of 256; " + text + " (opt-in variant)")
         w.pool_size, w.pool_block, w.pool_mode, w.pool_line, w.pool_segment = 0, 0, 0, 1, 64
         ma = timed_epochs(torch, w, SCATTER_ATOMIC, 5, 2)
+        ma["roofline"]["traffic"] = measured_traffic(ma["roofline"]["kernel"], 4, "atomic")
         out["all_configs"] = {"4_atomic": summary_of(w, ma, 5)}
         del w
         torch.cuda.empty_cache()
