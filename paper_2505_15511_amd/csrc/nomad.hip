@@ -713,12 +713,16 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 else {
                     // Record phases: the edge pass of a step runs over `phases` ranges of positions, each followed by the
                     // tile pass, so the pool holds the records of one range.  Default: as many (a power of two, at
-                    // most 64) as keep one range's records under 8 GB (each further phase costs about half a per cent
-                    // of an epoch: the tile pass walks shorter chains and carries its sums through memory).
+                    // most 64) as keep one range's records under 8 GB, and under 4 GB for a step with more than 32 GB
+                    // of records, where the pool would otherwise outweigh the graph (each further phase costs about
+                    // half a per cent of an epoch: the tile pass walks shorter chains and carries its sums through
+                    // memory).
                     int phases = c->tune_phases;
                     if (phases == 0) {
+                        const double step_bytes = (double)E * (s + 1) * 12.0;
+                        const double per_phase = step_bytes > 32e9 ? 4e9 : 8e9;
                         phases = 1;
-                        while (phases < 64 && (double)E * (s + 1) * 12.0 / phases > 8e9) phases *= 2;
+                        while (phases < 64 && step_bytes / phases > per_phase) phases *= 2;
                     }
                     c->phases = (int)std::max<int64_t>(1, std::min<int64_t>(phases, (E + c->bin_block - 1) / c->bin_block));
                     const int64_t per_phase = (E + c->phases - 1) / c->phases + c->bin_block;   // ranges are cut at multiples of the block

@@ -771,7 +771,7 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
 //                    records were appended or read in.  It then adds the head sums and writes g.
 constexpr int kMaxTileBits = 13;        // 8192 points: 128 KB of accumulators
 constexpr int kMinTileBits = 8;
-constexpr int kChunk = 256;             // records per chunk (3 KB): every (workgroup, tile) chain ends in a partly filled
+constexpr int kChunk = 128;             // records per chunk (1.5 KB): every (workgroup, tile) chain ends in a partly filled
                                         // chunk, so the pool carries workgroups x tiles x kChunk records of slack
 constexpr int kBinBlock = 1024;          // threads of the tile pass and of the large edge-pass workgroup
 constexpr int kMaxBinsPerThread = 8;    // tiles one thread owns in the per-round scan
@@ -1788,7 +1788,7 @@ __global__ void __launch_bounds__(kBinBlock) k_tile_accumulate(const BinArgs Q, 
     // A wavefront walks the chains of kChains workgroups side by side: the loads of a step (next chunk ids and up to
     // kPerLane records per lane and chain) all go out before any is used, so the latency of following a chain is
     // paid once per step for all of them.  Chunk ids and fills are wave-uniform.
-    constexpr int kChains = 4;
+    constexpr int kChains = 8;
     for (uint32_t w0 = (uint32_t)wave * kChains; w0 < n_wg; w0 += (kBinBlock / 64) * kChains) {
         uint32_t ch[kChains], cnt[kChains];
 #pragma unroll
