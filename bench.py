@@ -60,19 +60,31 @@ def algorithmic_bytes(kernel, n, E, s, R, grouped, weighted, deterministic, pool
 
 
 def measured_traffic(kernel, config, mode, launches_per_epoch=1.0, sampler="iid"):
-    """HBM bytes per launch from the committed rocprofv3 counter summary (profiles/hbm_bytes_per_epoch.txt: lines
-    `<config> <mode> <sampler> <kernel> <bytes of that kernel's launches of one epoch>`), or None if that kernel and workload
-    have not been profiled.  The counters do not depend on how many launches an epoch's edge pass is cut into."""
+    """(HBM bytes per launch, the kernel's milliseconds per epoch when the counters were read) from the committed rocprofv3
+    counter summary (profiles/hbm_bytes_per_epoch.txt: lines `<config> <mode> <sampler> <kernel> <bytes of that kernel's
+    launches of one epoch> <its ms per epoch in the kernel trace of the same build>`), or (None, None) if that kernel and
+    workload have not been profiled.  The counters do not depend on how many launches an epoch's edge pass is cut into."""
     path = os.path.join(ROOT, "profiles", "hbm_bytes_per_epoch.txt")
     try:
         with open(path) as fh:
             for line in fh:
                 f = line.split()
                 if len(f) >= 5 and not line.startswith("#") and f[:4] == [f"config{config}", mode, sampler, kernel]:
-                    return float(f[4]) / launches_per_epoch
+                    return float(f[4]) / launches_per_epoch, (float(f[5]) if len(f) >= 6 else None)
     except OSError:
         pass
-    return None
+    return None, None
+
+
+def attach_traffic(roofline, ms_per_epoch, config, mode, sampler="iid"):
+    """roofline.traffic from the committed counters.  They are not read in this run: `traffic_current` says whether the
+    kernel still takes the time it took when they were (within 15 %; small kernels: within 20 us), i.e. whether the
+    summary under profiles/ still describes the kernel that was just timed."""
+    traffic, ms_then = measured_traffic(roofline["kernel"], config, mode, roofline.get("launches_per_epoch", 1.0), sampler)
+    roofline["traffic"] = traffic
+    if traffic is not None and ms_then is not None:
+        roofline["traffic_counted_at_ms_per_epoch"] = ms_then
+        roofline["traffic_current"] = bool(abs(ms_per_epoch - ms_then) <= max(0.15 * ms_then, 0.02))
 
 
 def copy_probe_gbs(torch, gib=4, steps=10):
@@ -499,7 +511,7 @@ def main():
     dom = roofline["kernel"]
     if args.scale == 1.0 and args.groups is None and pool is None and args.batches == 1 and args.graph == "symmetrised" \
             and not w.sampled_far_field and not w.mean_gradient:
-        roofline["traffic"] = measured_traffic(dom, args.config, args.mode, roofline.get("launches_per_epoch", 1.0))
+        attach_traffic(roofline, kernels[dom]["ms"], args.config, args.mode)
     out = {
         "metric": "positive+negative edge updates/sec per epoch at 1 GPU",
         "value": E * (1 + s) / (elapsed / steps),
@@ -575,12 +587,12 @@ def main():
             psize = 2048 if pmode == 1 else 4096
             w.pool_size, w.pool_block, w.pool_mode, w.pool_line, w.pool_segment = psize, 8192, pmode, 16, 256
             mv = timed_epochs(torch, w, SCATTER_DETERMINISTIC, 10, 3)
-            mv["roofline"]["traffic"] = measured_traffic(mv["roofline"]["kernel"], 4, "det", 1.0, key)
+            attach_traffic(mv["roofline"], mv["kernels"][mv["roofline"]["kernel"]]["ms"], 4, "det", key)
             out["variants"][key] = dict(summary_of(w, mv, 10), sampler=f"pooled, distinct picks: {psize} points in lines of 16 per block of 8192 "
                                         "positions dealt in segments of 256; " + text + " (opt-in variant)")
         w.pool_size, w.pool_block, w.pool_mode, w.pool_line, w.pool_segment = 0, 0, 0, 1, 64
         ma = timed_epochs(torch, w, SCATTER_ATOMIC, 5, 2)
-        ma["roofline"]["traffic"] = measured_traffic(ma["roofline"]["kernel"], 4, "atomic")
+        attach_traffic(ma["roofline"], ma["kernels"][ma["roofline"]["kernel"]]["ms"], 4, "atomic")
         out["all_configs"] = {"4_atomic": summary_of(w, ma, 5)}
         del w
         torch.cuda.empty_cache()
@@ -588,10 +600,9 @@ def main():
             wc = workloads.make_config(cfg, device=dev if cfg >= 3 else "cpu")
             torch.cuda.synchronize()
             mc = timed_epochs(torch, wc, SCATTER_DETERMINISTIC, 5, 2)
-            out["all_configs"][str(cfg)] = summary_of(wc, mc, 5)
             if mc["roofline"]["bound"] == "hbm":
-                out["all_configs"][str(cfg)]["roofline"]["traffic"] = measured_traffic(mc["roofline"]["kernel"], cfg, "det",
-                                                                                      mc["roofline"].get("launches_per_epoch", 1.0))
+                attach_traffic(mc["roofline"], mc["kernels"][mc["roofline"]["kernel"]]["ms"], cfg, "det")
+            out["all_configs"][str(cfg)] = summary_of(wc, mc, 5)
             del wc, mc
             torch.cuda.empty_cache()
         out["all_configs"]["4"] = {"ms_per_step": round(ms_per_step, 4), "edges_per_s": out["edges_per_sec"], "updates_per_s": out["value"],
