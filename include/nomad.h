@@ -271,12 +271,16 @@ int64_t nomad_device_bytes(const nomad_ctx* ctx);
  *   NOMAD_TUNE_RECORD_PHASES   0 (default: chosen from the record volume) or 1..64: the edge pass of an epoch runs in
  *                              this many phases over ranges of CSR positions, each followed by the accumulation of its
  *                              records, so that the record pool holds one phase at a time
+ *   NOMAD_TUNE_RECORD_SORT     0 (default: sorted unless there are more tiles than a round has records), 1: a round's
+ *                              records are counting-sorted by tile in LDS and written by consecutive lanes, 2: every
+ *                              lane writes its own records
  */
 #define NOMAD_TUNE_EDGE_BLOCK 1
 #define NOMAD_TUNE_WORKGROUPS_PER_CU 2
 #define NOMAD_TUNE_SCATTER_PATH 3
 #define NOMAD_TUNE_POOL_KERNEL 4
 #define NOMAD_TUNE_RECORD_PHASES 5
+#define NOMAD_TUNE_RECORD_SORT 6
 int nomad_tune(nomad_ctx* ctx, int knob, int value);
 
 /* ---- kernel timing (HIP events on the context's stream, around each launch) ---- */

@@ -60,6 +60,7 @@ struct nomad_ctx {
     bool binned = false;
     int n_wg = 0, bin_block = 1024;
     int pool_rounds = 0;            // > 0: the pooled edge pass runs, pool_block = bin_block * pool_rounds
+    bool sorted_records = true;     // the binned edge pass counting-sorts a round's records by tile before writing them
     std::vector<int64_t> batch_row, batch_edge;   // [B + 1] first head / first CSR position of every sub-step
     uint32_t n_bins = 0, max_chunks = 0;
     int tile_bits = kMaxTileBits;
@@ -70,7 +71,7 @@ struct nomad_ctx {
     uint32_t edge_grid = 0;
     int* flags = nullptr;
     // launch-shape knobs (nomad_tune) and what set_graph made of them
-    int tune_edge_block = 0, tune_wg_per_cu = 0, tune_path = 0, tune_pool_kernel = 1, tune_phases = 0;
+    int tune_edge_block = 0, tune_wg_per_cu = 0, tune_path = 0, tune_pool_kernel = 1, tune_phases = 0, tune_record_sort = 0;
     int path = 0;                   // NOMAD_PATH_* in use
     int phases = 1;                 // record phases of the binned edge pass
     unsigned long long* carry = nullptr;   // [2 n] fixed-point sums carried from phase to phase (phases > 1)
@@ -255,7 +256,7 @@ size_t edge_pass_lds_bytes(const nomad_ctx* c) {
     if (c->pool_rounds && c->distinct_kernel)
         return distinct_lds_bytes(c->n_bins, (uint32_t)c->cfg.pool_size, (uint32_t)(c->cfg.pool_size / c->cfg.pool_line), c->pool_rounds);
     return c->pool_rounds ? pooled_lds_bytes(c->n_bins, c->cfg.pool_block, (uint32_t)c->cfg.pool_size)
-                          : binned_lds_bytes(c->n_bins, c->cfg.n_neg, c->bin_block);
+                          : binned_lds_bytes(c->n_bins, c->cfg.n_neg, c->bin_block, c->sorted_records);
 }
 
 // Calls `fn(kernel)` with the edge-pass kernel that matches the context: number of negatives, sampler, launch shape.
@@ -272,7 +273,8 @@ void with_edge_pass_kernel_s(const nomad_ctx* c, Fn fn) {
     else if (c->pool_rounds == 2) k = k_edges_pooled<S, 2, 1024>;
     else if (c->pool_rounds == 4) k = k_edges_pooled<S, 4, 1024>;
     else if (c->pool_rounds == 8) k = k_edges_pooled<S, 8, 1024>;
-    else if (c->bin_block == 512) k = k_edges_binned<S, 512>;
+    else if (c->bin_block == 512) k = c->sorted_records ? k_edges_binned<S, 512, true> : k_edges_binned<S, 512, false>;
+    else if (!c->sorted_records) k = k_edges_binned<S, 1024, false>;
     fn(k);
 }
 
@@ -664,10 +666,14 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         // One persistent workgroup of 1024 lanes per compute unit: the more records a round sorts, the longer the
         // contiguous run each tile receives.  (Two workgroups of 512 per compute unit measured 17 % slower at
         // 10 M points; nomad_tune(NOMAD_TUNE_EDGE_BLOCK, 512) selects them for experiments when their LDS fits.)
+        // A round's records are counting-sorted by tile in LDS before they are written, unless there are more tiles than
+        // a round has records (60 M points, s = 2): then no tile receives a run worth sorting for, and every lane
+        // writes its own records (two barriers and the scan over the tiles less per round).
+        bool sorted = c->tune_record_sort != 2 && (c->tune_record_sort == 1 || (size_t)n_bins <= binned_records_per_round(s, 1024));
         int bin_block = 0, wg_per_cu = 1;
-        if (n_bins <= (uint32_t)kMaxBinsPerThread * 1024 && binned_lds_bytes(n_bins, s, 1024) <= kMaxLdsBytes) bin_block = 1024;
-        if (c->tune_edge_block == 512 && n_bins <= (uint32_t)kMaxBinsPerThread * 512 &&
-            2 * (binned_lds_bytes(n_bins, s, 512) + 256) <= 160 * 1024) { bin_block = 512; wg_per_cu = 2; }
+        if ((!sorted || n_bins <= (uint32_t)kMaxBinsPerThread * 1024) && binned_lds_bytes(n_bins, s, 1024, sorted) <= kMaxLdsBytes) bin_block = 1024;
+        if (c->tune_edge_block == 512 && (!sorted || n_bins <= (uint32_t)kMaxBinsPerThread * 512) &&
+            2 * (binned_lds_bytes(n_bins, s, 512, sorted) + 256) <= 160 * 1024) { bin_block = 512; wg_per_cu = 2; }
         if (c->tune_wg_per_cu) wg_per_cu = c->tune_wg_per_cu;
         // Pooled samplers: their own edge pass (pool in LDS) when the block is 1, 2, 4 or 8 rounds of 1024 positions, one
         // workgroup per compute unit.  (Two workgroups of 512 lanes per compute unit, which lets one block's
@@ -686,7 +692,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                 }
             }
         }
-        if (pool_rounds) { bin_block = 1024; wg_per_cu = 1; }
+        if (pool_rounds) { bin_block = 1024; wg_per_cu = 1; sorted = true; }
         std::string why;   // why the fallback path is in use, if it is
         if (c->tune_path == NOMAD_PATH_FIXED_ATOMICS) why = "the fixed-point atomics path was asked for (nomad_tune)";
         else if (s > 8) why = "more than 8 negatives per edge: the binned edge pass is built for s <= 8";
@@ -695,6 +701,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
             hipDeviceProp_t prop;
             HTRY(hipGetDeviceProperties(&prop, c->cfg.device));
             c->bin_block = bin_block;
+            c->sorted_records = sorted;
             c->pool_rounds = pool_rounds;
             c->distinct_kernel = distinct;
             c->n_wg = std::max(1, prop.multiProcessorCount) * wg_per_cu;
@@ -805,6 +812,9 @@ int nomad_tune(nomad_ctx* c, int knob, int value) {
         case NOMAD_TUNE_RECORD_PHASES:
             if (value < 0 || value > 64) break;
             c->tune_phases = value; return NOMAD_OK;
+        case NOMAD_TUNE_RECORD_SORT:
+            if (value < 0 || value > 2) break;
+            c->tune_record_sort = value; return NOMAD_OK;
     }
     return fail(c, NOMAD_E_INVALID_ARG, "nomad_tune: unknown knob %d or value %d out of range", knob, value);
 }

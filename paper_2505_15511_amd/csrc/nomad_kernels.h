@@ -796,8 +796,8 @@ struct BinArgs {
 // LDS of k_edges_binned: per tile (record count / first sorted slot, fill of the open chunk, open
 // chunk, first chunk allocated this round) and the round's records, sorted by tile.
 __host__ __device__ inline size_t binned_records_per_round(int s, int block) { return (size_t)block * (s + 1) + 2 * (block / 64); }
-__host__ __device__ inline size_t binned_lds_bytes(uint32_t n_bins, int s, int block) {
-    return ((size_t)4 * n_bins + 1 + 3 * binned_records_per_round(s, block)) * sizeof(uint32_t);
+__host__ __device__ inline size_t binned_lds_bytes(uint32_t n_bins, int s, int block, bool sorted = true) {
+    return ((size_t)4 * n_bins + 1 + (sorted ? 3 * binned_records_per_round(s, block) : 0)) * sizeof(uint32_t);
 }
 
 // Workgroup barrier that orders LDS accesses only.  The edge pass never reads back, inside the
@@ -947,6 +947,64 @@ __device__ __forceinline__ void sort_and_flush(const BinLds& L, const BinArgs& Q
     lds_barrier();
 }
 
+// The same round without the counting sort, for graphs whose rounds reach few of many tiles (more tiles than a round
+// has records, and negatives drawn near the head): a record's place in its chain is the chain's fill plus the rank
+// it took from the tile's counter, so once the chains have been extended every lane writes its own records.  The
+// records of one tile still land side by side; what is given up is that consecutive lanes write them, what is saved
+// are the scan over all tiles, the staging in LDS and two of the round's six barriers.  All lanes must call.
+template <int NR, int BS>
+__device__ __forceinline__ void direct_flush(const BinLds& L, const BinArgs& Q, uint32_t pool_end, uint32_t* pool_cursor,
+                                             const bool (&valid)[NR], const uint32_t (&pt)[NR], const uint32_t (&rank)[NR],
+                                             const float (&fx)[NR], const float (&fy)[NR]) {
+    const uint32_t B = L.B;
+    const int tb = L.tile_bits;
+    lds_barrier();   // the round's counts are complete
+    for (uint32_t b = threadIdx.x; b < B; b += BS) {
+        const uint32_t c = L.start[b], fl = L.fill[b];
+        if (c != 0 && fl + c > (uint32_t)kChunk) {
+            const uint32_t k = (fl + c - 1) / kChunk;
+            const uint32_t nb = atomicAdd(pool_cursor, k);
+            L.base[b] = nb;
+            if (nb + k > pool_end) *Q.overflow = 1;
+            uint32_t prev = L.chunk[b];
+            for (uint32_t y = 0; y < k && nb + y < pool_end; ++y) { Q.chunk_prev[nb + y] = prev; prev = nb + y; }
+        }
+    }
+    lds_barrier();
+#pragma unroll
+    for (int k = 0; k < NR; ++k) {
+        if (valid[k]) {
+            const uint32_t b = pt[k] >> tb;
+            const uint32_t pos = L.fill[b] + rank[k];
+            uint32_t ch, off;
+            if (pos < (uint32_t)kChunk) { ch = L.chunk[b]; off = pos; }
+            else { ch = L.base[b] + (pos - kChunk) / kChunk; off = (pos - kChunk) % kChunk; }
+            if (ch < pool_end) {   // kNoChunk is above any valid id
+                uint32_t* dst = Q.pool + ((size_t)ch * kChunk + off) * 3;
+                dst[0] = pt[k] & ((1u << tb) - 1u);
+                dst[1] = __float_as_uint(fx[k]);
+                dst[2] = __float_as_uint(fy[k]);
+            }
+        }
+    }
+    lds_barrier();   // the tables have been read
+    for (uint32_t b = threadIdx.x; b < B; b += BS) {
+        const uint32_t c = L.start[b];
+        if (c != 0) {
+            const uint32_t fl = L.fill[b];
+            if (fl + c > (uint32_t)kChunk) {
+                const uint32_t k = (fl + c - 1) / kChunk;
+                L.chunk[b] = L.base[b] + k - 1;
+                L.fill[b] = fl + c - k * kChunk;
+            } else {
+                L.fill[b] = fl + c;
+            }
+            L.start[b] = 0;
+        }
+    }
+    lds_barrier();
+}
+
 // the last chunk of every chain and how full it is (end of the edge pass)
 template <int BS>
 __device__ __forceinline__ void publish_chains(const BinLds& L, const BinArgs& Q, uint32_t pool_end) {
@@ -1033,14 +1091,14 @@ __device__ __forceinline__ void resolve_far_negatives(const EdgeArgs& P, EdgeFet
     }
 }
 
-template <int S, int BS>
+template <int S, int BS, bool SORT = true>
 __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const BinArgs Q) {
     constexpr int SS = S > 0 ? S : 1;
     constexpr int kWaves = BS / 64;
     constexpr int NREC = BS * (S + 1) + 2 * kWaves;
     constexpr int NR = S + 2;   // per lane: the tail, the negatives, and possibly a partial head sum
     extern __shared__ uint32_t lds_bins[];
-    const BinLds L = carve_bin_lds(lds_bins, Q.n_bins, NREC, Q.tile_bits);
+    const BinLds L = carve_bin_lds(lds_bins, Q.n_bins, SORT ? NREC : 0, Q.tile_bits);
     __shared__ uint32_t wave_total[kWaves];
     __shared__ uint32_t pool_cursor;
     const int tid = threadIdx.x;
@@ -1108,7 +1166,8 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
 #pragma unroll
         for (int k = 0; k < NR; ++k)
             if (valid[k]) rank[k] = take_rank(L, dst_pt[k]);
-        sort_and_flush<NR, BS, (NREC + BS - 1) / BS>(L, Q, pool_end, &pool_cursor, wave_total, valid, dst_pt, rank, fx, fy);
+        if (SORT) sort_and_flush<NR, BS, (NREC + BS - 1) / BS>(L, Q, pool_end, &pool_cursor, wave_total, valid, dst_pt, rank, fx, fy);
+        else direct_flush<NR, BS>(L, Q, pool_end, &pool_cursor, valid, dst_pt, rank, fx, fy);
     }
     publish_chains<BS>(L, Q, pool_end);
 }

@@ -238,8 +238,10 @@ def skewed_degree_graph(seed, n=6000, hubs=3):
 
 
 @pytest.mark.parametrize("tune,path", [({}, PATH_BINNED), ({"edge_block": 512}, PATH_BINNED), ({"workgroups_per_cu": 3}, PATH_BINNED),
-                                       ({"scatter_path": PATH_FIXED_ATOMICS}, PATH_FIXED_ATOMICS), ({"record_phases": 3}, PATH_BINNED)],
-                         ids=["1024-lane", "512-lane", "3-per-cu", "fixed-point-atomics", "3-phases"])
+                                       ({"scatter_path": PATH_FIXED_ATOMICS}, PATH_FIXED_ATOMICS), ({"record_phases": 3}, PATH_BINNED),
+                                       ({"record_sort": 2}, PATH_BINNED), ({"record_sort": 2, "edge_block": 512, "record_phases": 3}, PATH_BINNED)],
+                         ids=["1024-lane", "512-lane", "3-per-cu", "fixed-point-atomics", "3-phases", "unsorted-records",
+                              "unsorted-512-lane-3-phases"])
 def test_deterministic_variants_on_skewed_degrees(tune, path):
     """Every launch shape of the deterministic path gives the oracle's gradient, and the same embedding bit for bit
     when run twice, on rows of very different lengths; the library says which path it runs."""
@@ -258,6 +260,29 @@ def test_deterministic_variants_on_skewed_degrees(tune, path):
     note(f"  {env}: grad err {grad_err(out[0][0], g_ref):.2e} (per component, floor 1e-3: {grad_err_per_component(out[0][0], g_ref):.2e})")
     assert grad_err(out[0][0], g_ref) < GRAD_TOL and grad_err_per_component(out[0][0], g_ref) < COMPONENT_TOL
     assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
+
+
+@pytest.mark.parametrize("case", ["skewed", "config5@0.001", "config3@0.05"])
+def test_sorted_and_unsorted_records_give_the_same_bits(case):
+    """A round's records written after a counting sort by tile, or by the lanes that made them: the tile sums are integer
+    sums of the same records, so gradient and embedding agree bit for bit (and with the library's own choice)."""
+    d = skewed_degree_graph(5) if case == "skewed" else dict(workload(int(case[6]), float(case.split("@")[1])).numpy())
+    runs = []
+    for tune in ({}, {"record_sort": 1}, {"record_sort": 2}):
+        with make_nomad(d, SCATTER_DETERMINISTIC, tune=tune) as nm:
+            assert nm.scatter_path() == PATH_BINNED
+            for t in range(3):
+                nm.epoch(t)
+            runs.append((nm.get_gradient(), nm.get_embedding()))
+    for g, th in runs[1:]:
+        assert np.array_equal(g, runs[0][0]) and np.array_equal(th, runs[0][1])
+    O = c_oracle.COracle(**d)
+    _, g_ref, _ = O.epoch(d["theta0"], 0)
+    with make_nomad(d, SCATTER_DETERMINISTIC, tune={"record_sort": 2}) as nm:
+        nm.epoch(0)
+        g = nm.get_gradient()
+    note(f"  {case}, unsorted records: grad err {grad_err(g, g_ref):.2e} (per component: {grad_err_per_component(g, g_ref):.2e})")
+    assert grad_err(g, g_ref) < GRAD_TOL and grad_err_per_component(g, g_ref) < COMPONENT_TOL
 
 
 def test_record_phases_change_the_pool_size_and_nothing_else():
