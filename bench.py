@@ -292,7 +292,7 @@ def pool_of(w):
     return (w.pool_size, w.pool_block, w.pool_line, w.pool_segment, w.pool_mode) if w.pool_mode else (w.pool_size, w.pool_block)
 
 
-def timed_epochs(torch, w, mode, steps, warmup, batches=1, phases=0, record_sort=0):
+def timed_epochs(torch, w, mode, steps, warmup, batches=1, phases=0, tune=None):
     """`warmup` untimed and `steps` timed epochs of workload w (graph and embedding resident on the device before the
     clock starts), with the library's per-launch HIP events on its stream.  Returns the timings, the per-kernel
     figures per epoch and the roofline entry of the kernel that takes most of the epoch."""
@@ -303,7 +303,7 @@ def timed_epochs(torch, w, mode, steps, warmup, batches=1, phases=0, record_sort
     nm = Nomad(n, R, s, w.noise_count, w.n_epochs, w.lr0, w.seed, mode, pool_size=w.pool_size, pool_block=w.pool_block,
                batches_per_epoch=batches, sampled_far_field=w.sampled_far_field, mean_gradient=w.mean_gradient,
                pool_mode=w.pool_mode, pool_line=w.pool_line, pool_segment=w.pool_segment,
-               inverse_rank_weights=w.inverse_rank_weights, tune=dict(({"record_phases": phases} if phases else {}), **({"record_sort": record_sort} if record_sort else {})) or None)
+               inverse_rank_weights=w.inverse_rank_weights, tune=dict(({"record_phases": phases} if phases else {}), **(tune or {})) or None)
     t0 = time.time()
     nm.set_graph(w.row_ptr.to(dev), w.col_idx.to(dev), None if w.weights is None else w.weights.to(dev), w.cluster_of.to(dev),
                  None if w.cluster_group is None else w.cluster_group.to(dev))
@@ -435,9 +435,9 @@ def main():
     ap.add_argument("--index-clusters", type=int, default=256)
     ap.add_argument("--index-k", type=int, default=15)
     ap.add_argument("--phases", type=int, default=0, help="record phases of the deterministic edge pass (0: the library's choice)")
-    ap.add_argument("--record-sort", type=int, default=0, choices=[0, 1, 2],
-                    help="binned edge pass: 1 = a round's records are sorted by tile before they are written, 2 = every lane writes "
-                         "its own, 0 = the library's choice")
+    ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
+                    help="a launch-shape knob of nomad_tune by its name in binding.TUNE (edge_block, workgroups_per_cu, record_sort, "
+                         "flush_rounds, ...); may be given several times")
     ap.add_argument("--batches", type=int, default=1, help="sub-steps per epoch (minibatch epochs); the benchmark uses 1")
     ap.add_argument("--probe", choices=["copy", "gather", "atomic_f32x2", "atomic_u64", "append12", "append12_grouped", "limits"], default=None,
                     help="run only one memory-system probe: streaming copy (counter calibration / practical HBM ceiling), "
@@ -507,8 +507,9 @@ def main():
         return hip_graph_run(args, torch, Nomad, w, mode, warmup, steps)
     default_run = (args.config == 4 and args.scale == 1.0 and args.mode == "det" and pool is None and args.groups is None and
                    args.batches == 1 and args.graph == "symmetrised" and not w.sampled_far_field and not w.mean_gradient and
-                   args.phases == 0)
-    m = timed_epochs(torch, w, mode, steps, warmup, batches=args.batches, phases=args.phases, record_sort=args.record_sort)
+                   args.phases == 0 and not args.tune)
+    m = timed_epochs(torch, w, mode, steps, warmup, batches=args.batches, phases=args.phases,
+                     tune={kv.split('=')[0]: int(kv.split('=')[1]) for kv in args.tune})
     kernels, roofline, loss, elapsed, epoch_bytes = m["kernels"], m["roofline"], m["loss"], m["elapsed"], m["epoch_bytes"]
     ms_per_step, path_name, state_gb, setup_s, grouped = m["ms_per_step"], m["path"], m["state_gb"], m["setup_s"], m["grouped"]
     dom = roofline["kernel"]

@@ -274,6 +274,8 @@ int64_t nomad_device_bytes(const nomad_ctx* ctx);
  *   NOMAD_TUNE_RECORD_SORT     0 (default: sorted unless there are more tiles than a round has records), 1: a round's
  *                              records are counting-sorted by tile in LDS and written by consecutive lanes, 2: every
  *                              lane writes its own records
+ *   NOMAD_TUNE_FLUSH_ROUNDS    0 (default: 2), 1 or 2: rounds of 1024 positions the unsorted form takes between two
+ *                              flushes of its records (1024-lane workgroups only)
  */
 #define NOMAD_TUNE_EDGE_BLOCK 1
 #define NOMAD_TUNE_WORKGROUPS_PER_CU 2
@@ -281,6 +283,7 @@ int64_t nomad_device_bytes(const nomad_ctx* ctx);
 #define NOMAD_TUNE_POOL_KERNEL 4
 #define NOMAD_TUNE_RECORD_PHASES 5
 #define NOMAD_TUNE_RECORD_SORT 6
+#define NOMAD_TUNE_FLUSH_ROUNDS 7
 int nomad_tune(nomad_ctx* ctx, int knob, int value);
 
 /* ---- kernel timing (HIP events on the context's stream, around each launch) ---- */

@@ -39,7 +39,7 @@ class NomadConfig(C.Structure):
 
 PATH_ATOMIC_FP32, PATH_BINNED, PATH_BINNED_POOLED, PATH_FIXED_ATOMICS = 1, 2, 3, 4
 PATH_NAMES = {0: "none", 1: "atomic_fp32", 2: "binned", 3: "binned_pooled", 4: "fixed_point_atomics"}
-TUNE = {"edge_block": 1, "workgroups_per_cu": 2, "scatter_path": 3, "pool_kernel": 4, "record_phases": 5, "record_sort": 6}
+TUNE = {"edge_block": 1, "workgroups_per_cu": 2, "scatter_path": 3, "pool_kernel": 4, "record_phases": 5, "record_sort": 6, "flush_rounds": 7}
 POOL_PICKS16, POOL_DISTINCT, POOL_STRATIFIED = 0, 1, 2
 
 

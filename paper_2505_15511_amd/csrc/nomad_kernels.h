@@ -1091,12 +1091,13 @@ __device__ __forceinline__ void resolve_far_negatives(const EdgeArgs& P, EdgeFet
     }
 }
 
-template <int S, int BS, bool SORT = true>
+template <int S, int BS, bool SORT = true, int ROUNDS = 1>
 __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const BinArgs Q) {
+    static_assert(!SORT || ROUNDS == 1, "the sorted form stages one round's records in LDS");
     constexpr int SS = S > 0 ? S : 1;
     constexpr int kWaves = BS / 64;
     constexpr int NREC = BS * (S + 1) + 2 * kWaves;
-    constexpr int NR = S + 2;   // per lane: the tail, the negatives, and possibly a partial head sum
+    constexpr int NR = S + 2;   // per lane and round: the tail, the negatives, and possibly a partial head sum
     extern __shared__ uint32_t lds_bins[];
     const BinLds L = carve_bin_lds(lds_bins, Q.n_bins, SORT ? NREC : 0, Q.tile_bits);
     __shared__ uint32_t wave_total[kWaves];
@@ -1124,50 +1125,57 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
         if (e1 < Q.e_end) { i_next = Q.head[e1]; j_next = P.col[e1]; }
         issue_edge<S, true>(P, e0 < Q.e_end, (int32_t)e0, i0, j0, f);
     }
-    for (int64_t slab = w; slab < n_slabs; slab += W) {
-        // one edge per lane; records: slot 0 the tail (force -a d_ij), slots 1..S the negatives
-        const int64_t e64 = Q.e_begin + slab * BS + tid;
-        const int64_t e_end = min(Q.e_begin + (slab + 1) * BS, Q.e_end);
-        const bool has = f.has;
-        const int32_t i = f.i, ea = f.ea, eb = f.eb;
-        bool valid[NR];
-        uint32_t dst_pt[NR], rank[NR];
-        float fx[NR], fy[NR];
+    // The unsorted form takes ROUNDS rounds between two flushes (no barrier in between: a record only takes its rank
+    // from the tile's counter when it is made); slabs past the end are empty rounds.
+    for (int64_t slab0 = w; slab0 < n_slabs; slab0 += (int64_t)W * ROUNDS) {
+        bool valid[NR * ROUNDS];
+        uint32_t dst_pt[NR * ROUNDS], rank[NR * ROUNDS];
+        float fx[NR * ROUNDS], fy[NR * ROUNDS];
 #pragma unroll
-        for (int k = 0; k < NR; ++k) { valid[k] = k <= S && has; dst_pt[k] = 0u; rank[k] = 0u; fx[k] = 0.f; fy[k] = 0.f; }
-        float hx = 0.f, hy = 0.f;
-        if (has) {
-            if (P.far) resolve_far_negatives<S>(P, f);
-            EdgeOut<SS> o;
-            edge_math<S, false>(f.h, f.pe, f.tj, f.tm, o);
-            hx = o.hx;
-            hy = o.hy;
-            if (P.cS) P.cS[f.e] = o.c;
-            dst_pt[0] = (uint32_t)f.j; fx[0] = -o.a * o.dx; fy[0] = -o.a * o.dy;
+        for (int r = 0; r < ROUNDS; ++r) {
+            // one edge per lane; records: slot 0 the tail (force -a d_ij), slots 1..S the negatives
+            const int64_t slab = slab0 + (int64_t)r * W;
+            const int64_t e64 = Q.e_begin + slab * BS + tid;
+            const int64_t e_end = min(Q.e_begin + (slab + 1) * BS, Q.e_end);
+            const bool has = f.has;
+            const int32_t i = f.i, ea = f.ea, eb = f.eb;
+            const int base = r * NR;
 #pragma unroll
-            for (int k = 0; k < S; ++k) {
-                valid[k + 1] = f.m[k] >= 0;
-                dst_pt[k + 1] = f.m[k] >= 0 ? (uint32_t)f.m[k] : 0u;
-                fx[k + 1] = o.rx[k];
-                fy[k + 1] = o.ry[k];
+            for (int k = 0; k < NR; ++k) { valid[base + k] = k <= S && has; dst_pt[base + k] = 0u; rank[base + k] = 0u; fx[base + k] = 0.f; fy[base + k] = 0.f; }
+            float hx = 0.f, hy = 0.f;
+            if (has) {
+                if (P.far) resolve_far_negatives<S>(P, f);
+                EdgeOut<SS> o;
+                edge_math<S, false>(f.h, f.pe, f.tj, f.tm, o);
+                hx = o.hx;
+                hy = o.hy;
+                if (P.cS) P.cS[f.e] = o.c;
+                dst_pt[base] = (uint32_t)f.j; fx[base] = -o.a * o.dx; fy[base] = -o.a * o.dy;
+#pragma unroll
+                for (int k = 0; k < S; ++k) {
+                    valid[base + k + 1] = f.m[k] >= 0;
+                    dst_pt[base + k + 1] = f.m[k] >= 0 ? (uint32_t)f.m[k] : 0u;
+                    fx[base + k + 1] = o.rx[k];
+                    fy[base + k + 1] = o.ry[k];
+                }
             }
-        }
-        // the loads of the next round go out before this round is sorted and written
-        {
-            const int64_t e1 = e64 + stride, e2 = e1 + stride;
-            const int32_t i1 = i_next, j1 = j_next;
-            if (e2 < Q.e_end) { i_next = Q.head[e2]; j_next = P.col[e2]; }
-            issue_edge<S, true>(P, e1 < Q.e_end, (int32_t)e1, i1, j1, f);
-        }
-        valid[S + 1] = reduce_head_sums(Q, has, i, ea, eb, e64, e_end, hx, hy);
-        dst_pt[S + 1] = valid[S + 1] ? (uint32_t)i : 0u;
-        fx[S + 1] = hx;
-        fy[S + 1] = hy;
+            // the loads of the next round go out before this round is sorted and written
+            {
+                const int64_t e1 = e64 + stride, e2 = e1 + stride;
+                const int32_t i1 = i_next, j1 = j_next;
+                if (e2 < Q.e_end) { i_next = Q.head[e2]; j_next = P.col[e2]; }
+                issue_edge<S, true>(P, e1 < Q.e_end, (int32_t)e1, i1, j1, f);
+            }
+            valid[base + S + 1] = reduce_head_sums(Q, has, i, ea, eb, e64, e_end, hx, hy);
+            dst_pt[base + S + 1] = valid[base + S + 1] ? (uint32_t)i : 0u;
+            fx[base + S + 1] = hx;
+            fy[base + S + 1] = hy;
 #pragma unroll
-        for (int k = 0; k < NR; ++k)
-            if (valid[k]) rank[k] = take_rank(L, dst_pt[k]);
-        if (SORT) sort_and_flush<NR, BS, (NREC + BS - 1) / BS>(L, Q, pool_end, &pool_cursor, wave_total, valid, dst_pt, rank, fx, fy);
-        else direct_flush<NR, BS>(L, Q, pool_end, &pool_cursor, valid, dst_pt, rank, fx, fy);
+            for (int k = 0; k < NR; ++k)
+                if (valid[base + k]) rank[base + k] = take_rank(L, dst_pt[base + k]);
+        }
+        if (SORT) sort_and_flush<NR * ROUNDS, BS, (NREC + BS - 1) / BS>(L, Q, pool_end, &pool_cursor, wave_total, valid, dst_pt, rank, fx, fy);
+        else direct_flush<NR * ROUNDS, BS>(L, Q, pool_end, &pool_cursor, valid, dst_pt, rank, fx, fy);
     }
     publish_chains<BS>(L, Q, pool_end);
 }

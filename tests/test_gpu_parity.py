@@ -268,7 +268,7 @@ def test_sorted_and_unsorted_records_give_the_same_bits(case):
     sums of the same records, so gradient and embedding agree bit for bit (and with the library's own choice)."""
     d = skewed_degree_graph(5) if case == "skewed" else dict(workload(int(case[6]), float(case.split("@")[1])).numpy())
     runs = []
-    for tune in ({}, {"record_sort": 1}, {"record_sort": 2}):
+    for tune in ({}, {"record_sort": 1}, {"record_sort": 2}, {"record_sort": 2, "flush_rounds": 1}):
         with make_nomad(d, SCATTER_DETERMINISTIC, tune=tune) as nm:
             assert nm.scatter_path() == PATH_BINNED
             for t in range(3):
