@@ -1,7 +1,6 @@
 // libnomad: the upstream index (K-Means, in-cluster exact nearest neighbours) and the quality measures behind the C ABI of
 // include/nomad.h (host side).
 #include <hip/hip_runtime.h>
-#include <hipcub/hipcub.hpp>
 
 #include <algorithm>
 #include <cmath>
@@ -88,24 +87,27 @@ int nearest_in_groups(hipStream_t st, const KnnSets& P, const KnnBlock* blocks, 
 struct MeanStep {
     int64_t n = 0;
     int32_t K = 0;
-    int end_bit = 1;
-    size_t sort_bytes = 0;
-    uint32_t *counts = nullptr, *lstart = nullptr;
-    int32_t *ids_in = nullptr, *ids = nullptr, *keys = nullptr;
+    int passes = 1;                 // radix passes of 8 bits that cover the labels 0..K-1
+    uint32_t n_blocks = 0;          // workgroups of a sort pass
+    uint32_t *counts = nullptr, *lstart = nullptr, *hist = nullptr, *tile_total = nullptr;
+    uint32_t n_tiles = 0;           // tiles of the scan over the 256 n_blocks digit counters
+    int32_t *keys[2] = {nullptr, nullptr}, *ids[2] = {nullptr, nullptr};   // a pass reads one pair of arrays and writes the other
     int* bad = nullptr;
-    void* sort_tmp = nullptr;
     std::vector<uint32_t> hcounts, hstart;
 
-    int init(Buffers& buf, hipStream_t st, int64_t n_, int32_t K_) {
+    int init(Buffers& buf, hipStream_t, int64_t n_, int32_t K_) {
         n = n_; K = K_;
         hcounts.assign((size_t)K, 0u);
         hstart.assign((size_t)K + 1, 0u);
+        int bits = 1;
+        while (((int64_t)1 << bits) < K) ++bits;
+        passes = (bits + 7) / 8;
+        n_blocks = blocks_of(n, kSortSpan);
         KTRY(buf.alloc(&counts, (size_t)K)); KTRY(buf.alloc(&lstart, (size_t)K + 1)); KTRY(buf.alloc(&bad, 1));
-        KTRY(buf.alloc(&ids_in, (size_t)n)); KTRY(buf.alloc(&ids, (size_t)n)); KTRY(buf.alloc(&keys, (size_t)n));
-        hipLaunchKernelGGL(k_iota, dim3(blocks_of(n, 256)), dim3(256), 0, st, ids_in, n);
-        while (((int64_t)1 << end_bit) < K) ++end_bit;
-        KTRY(hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const int32_t*)keys, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
-        KTRY(buf.alloc((char**)&sort_tmp, sort_bytes));
+        n_tiles = (uint32_t)(((size_t)256 * n_blocks + kScanTile - 1) / kScanTile);
+        KTRY(buf.alloc(&hist, (size_t)256 * n_blocks));
+        KTRY(buf.alloc(&tile_total, (size_t)n_tiles));
+        for (int x = 0; x < (passes > 1 ? 2 : 1); ++x) { KTRY(buf.alloc(&keys[x], (size_t)n)); KTRY(buf.alloc(&ids[x], (size_t)n)); }
         return NOMAD_OK;
     }
     // labels [n] in 0..K-1 (on the device); dC [K * d] in and out
@@ -117,8 +119,20 @@ struct MeanStep {
         KTRY(hipStreamSynchronize(st));
         for (int32_t j = 0; j < K; ++j) hstart[j + 1] = hstart[j] + hcounts[j];
         KTRY(hipMemcpyAsync(lstart, hstart.data(), sizeof(uint32_t) * ((size_t)K + 1), hipMemcpyHostToDevice, st));
-        KTRY(hipcub::DeviceRadixSort::SortPairs(sort_tmp, sort_bytes, labels, keys, (const int32_t*)ids_in, ids, (int)n, 0, end_bit, st));
-        hipLaunchKernelGGL(k_kmeans_update, dim3(blocks_of((int64_t)K * d, 256)), dim3(256), 0, st, dX, d, (const int32_t*)ids, (const uint32_t*)lstart, K, dC);
+        const int32_t* kin = labels;
+        const int32_t* vin = nullptr;   // first pass: the point at position i is i
+        int out = 0;
+        for (int p = 0; p < passes; ++p) {
+            hipLaunchKernelGGL(k_sort_count, dim3(n_blocks), dim3(256), 0, st, kin, n, 8 * p, n_blocks, hist);
+            hipLaunchKernelGGL(k_sort_scan_tiles, dim3(n_tiles), dim3(256), 0, st, hist, (uint64_t)256 * n_blocks, tile_total);
+            hipLaunchKernelGGL(k_sort_scan, dim3(1), dim3(1024), 0, st, tile_total, (uint64_t)n_tiles);
+            hipLaunchKernelGGL(k_sort_scatter, dim3(n_blocks), dim3(256), 0, st, kin, vin, n, 8 * p, n_blocks, (const uint32_t*)hist,
+                               (const uint32_t*)tile_total, keys[out], ids[out]);
+            kin = keys[out]; vin = ids[out];
+            out ^= 1;
+        }
+        hipLaunchKernelGGL(k_kmeans_update, dim3(blocks_of((int64_t)K * d, 256)), dim3(256), 0, st, dX, d, vin, (const uint32_t*)lstart, K, dC);
+        KTRY(hipGetLastError());
         return NOMAD_OK;
     }
 };

@@ -745,6 +745,123 @@ __global__ void __launch_bounds__(256) k_iota(int32_t* __restrict__ v, int64_t n
     if (i < n) v[i] = (int32_t)i;
 }
 
+// ---- stable sort of the points by label (the M step adds a cluster's rows in ascending point order)
+// Least-significant-digit radix passes of 8 bits over (label, point) pairs.  A workgroup of 256 lanes owns kSortSpan
+// consecutive positions of a pass's input: it counts its digits (k_sort_count), an exclusive scan over the counts in
+// (digit, workgroup) order gives every workgroup the first output slot of each of its digits (two levels), and the
+// scatter (k_sort_scatter) ranks the pairs of a chunk of 256 in input order: inside a wavefront by the lanes below
+// with the same digit (eight ballots), across wavefronts by their counts taken in wavefront order, across chunks by a
+// running slot per digit.  Equal digits keep their input order in every pass, so equal labels end up in ascending
+// point order.
+constexpr int kSortSpan = 2048;
+
+__global__ void __launch_bounds__(256) k_sort_count(const int32_t* __restrict__ keys, int64_t n, int shift, uint32_t n_blocks,
+                                                    uint32_t* __restrict__ hist) {   // hist [256][n_blocks]
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0u;
+    __syncthreads();
+    const int64_t i0 = (int64_t)blockIdx.x * kSortSpan;
+    for (int u = 0; u < kSortSpan / 256; ++u) {
+        const int64_t i = i0 + u * 256 + threadIdx.x;
+        if (i < n) atomicAdd(&h[((uint32_t)keys[i] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    hist[(size_t)threadIdx.x * n_blocks + blockIdx.x] = h[threadIdx.x];
+}
+
+// Exclusive scan of the m counters in two levels: every workgroup scans a tile of kScanTile consecutive counters in
+// place and reports the tile's total (k_sort_scan_tiles); one workgroup scans the totals (k_sort_scan); the scatter adds
+// a counter's tile offset when it reads it.
+constexpr int kScanTile = 2048;
+
+__global__ void __launch_bounds__(256) k_sort_scan_tiles(uint32_t* __restrict__ hist, uint64_t m, uint32_t* __restrict__ tile_total) {
+    __shared__ uint32_t wave_sum[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t x0 = (uint64_t)blockIdx.x * kScanTile + (uint64_t)threadIdx.x * 8;
+    uint32_t v[8];
+    uint32_t own = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { v[u] = x0 + u < m ? hist[x0 + u] : 0u; own += v[u]; }
+    uint32_t incl = own;
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+        const uint32_t up = __shfl_up(incl, dlt, 64);
+        if (lane >= dlt) incl += up;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    uint32_t run = incl - own;
+    for (int w = 0; w < wave; ++w) run += wave_sum[w];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        if (x0 + u < m) hist[x0 + u] = run;
+        run += v[u];
+    }
+    if (threadIdx.x == 255) tile_total[blockIdx.x] = run;
+}
+
+// exclusive scan of m counters in place; one workgroup, every lane a contiguous share
+__global__ void __launch_bounds__(1024) k_sort_scan(uint32_t* __restrict__ hist, uint64_t m) {
+    __shared__ uint32_t part[1024];
+    const uint64_t per = (m + 1023) / 1024;
+    const uint64_t a = min(m, (uint64_t)threadIdx.x * per), b = min(m, a + per);
+    uint32_t own = 0;
+    for (uint64_t x = a; x < b; ++x) own += hist[x];
+    part[threadIdx.x] = own;
+    __syncthreads();
+    for (int dlt = 1; dlt < 1024; dlt <<= 1) {
+        const uint32_t v = (int)threadIdx.x >= dlt ? part[threadIdx.x - dlt] : 0u;
+        __syncthreads();
+        part[threadIdx.x] += v;
+        __syncthreads();
+    }
+    uint32_t run = part[threadIdx.x] - own;
+    for (uint64_t x = a; x < b; ++x) { const uint32_t c = hist[x]; hist[x] = run; run += c; }
+}
+
+// vals_in == nullptr: the value of position i is i (first pass)
+__global__ void __launch_bounds__(256) k_sort_scatter(const int32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int64_t n,
+                                                      int shift, uint32_t n_blocks, const uint32_t* __restrict__ first_slot,
+                                                      const uint32_t* __restrict__ tile_offset, int32_t* __restrict__ keys_out,
+                                                      int32_t* __restrict__ vals_out) {
+    __shared__ uint32_t running[256];       // next output slot of every digit for this workgroup
+    __shared__ uint32_t wave_cnt[4][256];   // pairs of the chunk with each digit, per wavefront
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    {
+        const size_t x = (size_t)threadIdx.x * n_blocks + blockIdx.x;   // the counters in (digit, workgroup) order
+        running[threadIdx.x] = first_slot[x] + tile_offset[x / kScanTile];
+    }
+    const int64_t i0 = (int64_t)blockIdx.x * kSortSpan;
+    for (int u = 0; u < kSortSpan / 256; ++u) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) wave_cnt[w][threadIdx.x] = 0u;
+        __syncthreads();
+        const int64_t i = i0 + u * 256 + threadIdx.x;
+        const bool has = i < n;
+        const int32_t key = has ? keys_in[i] : 0;
+        const int32_t val = has ? (vals_in ? vals_in[i] : (int32_t)i) : 0;
+        const uint32_t dgt = ((uint32_t)key >> shift) & 255u;
+        unsigned long long same = __ballot(has);   // lanes of this wavefront that hold a pair with this lane's digit
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const bool set = (dgt >> bit) & 1u;
+            const unsigned long long m = __ballot(set);
+            same &= set ? m : ~m;
+        }
+        const uint32_t below = (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
+        if (has && below == 0u) wave_cnt[wave][dgt] = (uint32_t)__popcll(same);
+        __syncthreads();
+        if (has) {
+            uint32_t pos = running[dgt] + below;
+            for (int w = 0; w < wave; ++w) pos += wave_cnt[w][dgt];
+            keys_out[pos] = key;
+            vals_out[pos] = val;
+        }
+        __syncthreads();
+        running[threadIdx.x] += wave_cnt[0][threadIdx.x] + wave_cnt[1][threadIdx.x] + wave_cnt[2][threadIdx.x] + wave_cnt[3][threadIdx.x];
+    }
+}
+
 // how many points changed their cluster
 __global__ void __launch_bounds__(256) k_kmeans_changed(const int32_t* __restrict__ a, const int32_t* __restrict__ b, int64_t n,
                                                         unsigned long long* __restrict__ changed) {

@@ -129,3 +129,53 @@ def test_hash_start_with_median_anchors_matches_the_oracle_exactly(n, d, K, b):
     Cg_ref, bg_ref = km.lsh_init(G, pl, km.lsh_median_anchors(G, pl), min(8, len(G)))
     Cg, bg = kmeans_lsh_init(G, min(8, len(G)), pl, None, return_buckets=True)
     assert np.array_equal(bg.astype(np.int64), bg_ref) and np.array_equal(Cg, Cg_ref)
+
+
+def order_sensitive_points(n, d, K, seed):
+    """Points whose cluster is fixed by column 0 (centroid j sits at 4096 j, the other columns of every centroid are 0), with
+    columns 1.. built so that a cluster's float64 sum depends on the order of its additions: in every cluster and column an
+    even number of members carry +-2^30 in cancelling pairs and the rest values near 2^-30, which a running sum that stands
+    at a multiple of 2^30 absorbs and one that stands at zero keeps."""
+    rng = np.random.default_rng(seed)
+    member_of = rng.integers(0, K, n)
+    X = np.zeros((n, d), dtype=np.float32)
+    X[:, 0] = 4096.0 * member_of
+    X[:, 1:] = (rng.uniform(-1, 1, (n, d - 1)) * 2.0 ** -30).astype(np.float32)
+    for j in range(K):
+        idx = np.flatnonzero(member_of == j)
+        for col in range(1, d):
+            q = len(idx) // 4
+            pick = rng.choice(idx, 2 * q, replace=False)
+            X[pick[:q], col] = 2.0 ** 30
+            X[pick[q:], col] = -(2.0 ** 30)
+    C0 = np.zeros((K, d), dtype=np.float32)
+    C0[:, 0] = 4096.0 * np.arange(K)
+    return X, C0, member_of
+
+
+@pytest.mark.parametrize("n,d,K", [(20000, 6, 40), (20000, 4, 300), (60000, 3, 3000)])
+def test_m_step_adds_in_ascending_point_order(n, d, K):
+    """Centroids equal to the oracle's bit for bit on rows whose sums depend on the order of the additions: the points of
+    every cluster were added in ascending point order (one radix pass of the sort for K <= 256, two beyond)."""
+    note(f"kmeans M-step order n={n} d={d} K={K}")
+    X, C0, member_of = order_sensitive_points(n, d, K, K)
+    lab_ref, _ = km.assign(X, C0)
+    assert np.array_equal(lab_ref, member_of)
+    C_ref = km.update(X, lab_ref, C0)
+    # the test has teeth: the same rows added in descending order give other numbers in most clusters
+    C_rev = km.update(X[::-1], lab_ref[::-1], C0)
+    assert (C_rev[:, 1:] != C_ref[:, 1:]).mean() > 0.5
+    C, lab, it, _ = kmeans_lloyd(X, C0, 1)
+    assert it == 1 and np.array_equal(lab.astype(np.int64), lab_ref)
+    assert np.array_equal(C, C_ref)
+
+
+def test_more_clusters_than_two_radix_digits():
+    """Labels beyond 65,535: three radix passes of the M step's sort.  The nearest centroid of every point is known by
+    construction (distance 0 in column 0 against at least 4096^2), so the E step of the oracle is not needed at this size."""
+    n, d, K = 140000, 2, 66000
+    X, C0, member_of = order_sensitive_points(n, d, K, 9)
+    C_ref = km.update(X, member_of, C0)
+    C, lab, it, _ = kmeans_lloyd(X, C0, 1)
+    assert it == 1 and member_of.max() > 65535 and np.array_equal(lab.astype(np.int64), member_of)
+    assert np.array_equal(C, C_ref)
