@@ -121,9 +121,22 @@ __global__ void k_cluster_census(const int32_t* __restrict__ cluster_of, const i
     if (i >= n) return;
     const int32_t c = cluster_of[i];
     if (c < 0 || c >= R) { flags[kFlagCluster] = 1; return; }
-    atomicAdd(&counts[c], 1u);
-    atomicMin(&first[c], (uint32_t)i);
-    if (group_of_cluster) atomicMin(&gfirst[group_of_cluster[c]], (uint32_t)i);
+    // Points are usually numbered cluster by cluster: when the lanes of a wavefront that are still here all hold the same
+    // cluster, its first lane reports for all of them (one atomic instead of 64 on one address).
+    const unsigned long long here = __ballot(1);
+    const int leader = __ffsll((long long)here) - 1;
+    const int32_t c0 = __shfl(c, leader, 64);
+    if (__ballot(c != c0) == 0ull) {
+        if ((int)(threadIdx.x & 63) == leader) {
+            atomicAdd(&counts[c], (uint32_t)__popcll(here));
+            atomicMin(&first[c], (uint32_t)i);   // the lowest lane holds the lowest index
+            if (group_of_cluster) atomicMin(&gfirst[group_of_cluster[c]], (uint32_t)i);
+        }
+    } else {
+        atomicAdd(&counts[c], 1u);
+        atomicMin(&first[c], (uint32_t)i);
+        if (group_of_cluster) atomicMin(&gfirst[group_of_cluster[c]], (uint32_t)i);
+    }
     if (i > 0) {
         const int32_t p = cluster_of[i - 1];
         if (p >= 0 && p < R) {
