@@ -262,11 +262,15 @@ def test_deterministic_variants_on_skewed_degrees(tune, path):
     assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
 
 
-@pytest.mark.parametrize("case", ["skewed", "config5@0.001", "config3@0.05"])
+@pytest.mark.parametrize("case", ["skewed", "config5@0.001", "config3@0.05", "config5@0.001-3-sub-steps", "config3@0.05-pooled-general-kernels"])
 def test_sorted_and_unsorted_records_give_the_same_bits(case):
     """A round's records written after a counting sort by tile, or by the lanes that made them: the tile sums are integer
     sums of the same records, so gradient and embedding agree bit for bit (and with the library's own choice)."""
-    d = skewed_degree_graph(5) if case == "skewed" else dict(workload(int(case[6]), float(case.split("@")[1])).numpy())
+    d = skewed_degree_graph(5) if case == "skewed" else dict(workload(int(case[6]), float(case.split("@")[1].split("-")[0])).numpy())
+    if case.endswith("sub-steps"):
+        d["batches_per_epoch"] = 3
+    if case.endswith("general-kernels"):
+        d["pool_size"], d["pool_block"] = 48, 100      # a block that is no multiple of 1024: the general kernels draw from the pools
     runs = []
     for tune in ({}, {"record_sort": 1}, {"record_sort": 2}, {"record_sort": 2, "flush_rounds": 1}):
         with make_nomad(d, SCATTER_DETERMINISTIC, tune=tune) as nm:
