@@ -13,6 +13,7 @@ SOURCES = [os.path.join(_PKG, "csrc", "nomad.hip"), os.path.join(_PKG, "csrc", "
 HEADERS = [os.path.join(_PKG, "csrc", "nomad_kernels.h"), os.path.join(_PKG, "csrc", "knn_kernels.h"),
            os.path.join(_PKG, "csrc", "metrics_kernels.h"), os.path.join(_PKG, "csrc", "philox.h"),
            os.path.join(_PKG, "csrc", "pca_kernels.h"), os.path.join(_PKG, "csrc", "host_util.h"),
+           os.path.join(_PKG, "csrc", "edge_plan.h"),
            os.path.join(_ROOT, "include", "nomad.h")]
 
 

@@ -251,9 +251,6 @@ BinArgs bin_args(nomad_ctx* c) {
     return q;
 }
 
-constexpr size_t kMaxLdsBytes = 160 * 1024 - 256;   // per workgroup on gfx950, less the kernels' static LDS
-constexpr int kDefaultFlushRounds = 2;              // unsorted binned edge pass: rounds between two flushes (5 % faster than one
-                                                    // at 60 M points; four spill registers and are slower)
 
 size_t edge_pass_lds_bytes(const nomad_ctx* c) {
     if (c->pool_rounds && c->distinct_kernel)
@@ -664,39 +661,17 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
         // Binned scatter of the tail and negative forces: needs a compile-time s and per-tile tables
         // that fit LDS; if its record pool cannot be allocated, fixed-point global atomics remain
         // as the fallback.
-        int tile_bits = kMinTileBits;   // about a thousand tiles when n allows, never above 8192 points a tile
-        while (tile_bits < kMaxTileBits && (n >> tile_bits) > 1024) ++tile_bits;
-        const uint32_t n_bins = (uint32_t)((n + ((int64_t)1 << tile_bits) - 1) >> tile_bits);
-        // One persistent workgroup of 1024 lanes per compute unit: the more records a round sorts, the longer the
-        // contiguous run each tile receives.  (Two workgroups of 512 per compute unit measured 17 % slower at
-        // 10 M points; nomad_tune(NOMAD_TUNE_EDGE_BLOCK, 512) selects them for experiments when their LDS fits.)
-        // A round's records are counting-sorted by tile in LDS before they are written, unless there are more tiles than
-        // a round has records (60 M points, s = 2): then no tile receives a run worth sorting for, and every lane
-        // writes its own records (two barriers and the scan over the tiles less per round).
-        bool sorted = c->tune_record_sort != 2 && (c->tune_record_sort == 1 || (size_t)n_bins <= binned_records_per_round(s, 1024));
-        int bin_block = 0, wg_per_cu = 1;
-        if ((!sorted || n_bins <= (uint32_t)kMaxBinsPerThread * 1024) && binned_lds_bytes(n_bins, s, 1024, sorted) <= kMaxLdsBytes) bin_block = 1024;
-        if (c->tune_edge_block == 512 && (!sorted || n_bins <= (uint32_t)kMaxBinsPerThread * 512) &&
-            2 * (binned_lds_bytes(n_bins, s, 512, sorted) + 256) <= 160 * 1024) { bin_block = 512; wg_per_cu = 2; }
-        if (c->tune_wg_per_cu) wg_per_cu = c->tune_wg_per_cu;
-        // Pooled samplers: their own edge pass (pool in LDS) when the block is 1, 2, 4 or 8 rounds of 1024 positions, one
-        // workgroup per compute unit.  (Two workgroups of 512 lanes per compute unit, which lets one block's
-        // bookkeeping overlap the other's rounds, measured 4 % slower: the rounds are bound by vector-ALU issue.)
-        int pool_rounds = 0;
-        bool distinct = false;
-        if (c->cfg.pool_size > 0 && c->cfg.pool_block % 1024 == 0 && c->tune_pool_kernel) {
-            const int r = c->cfg.pool_block / 1024;
-            if (r == 1 || r == 2 || r == 4 || r == 8) {
-                if (c->cfg.pool_mode != NOMAD_POOL_PICKS16) {
-                    // 32-bit byte offsets into col / head (4 E) and theta (8 n)
-                    if (distinct_lds_bytes(n_bins, (uint32_t)c->cfg.pool_size, (uint32_t)(c->cfg.pool_size / c->cfg.pool_line), r) <= kMaxLdsBytes &&
-                        E < ((int64_t)1 << 30) && n < ((int64_t)1 << 29)) { pool_rounds = r; distinct = true; }
-                } else if (pooled_lds_bytes(n_bins, c->cfg.pool_block, (uint32_t)c->cfg.pool_size) <= kMaxLdsBytes) {
-                    pool_rounds = r;
-                }
-            }
-        }
-        if (pool_rounds) { bin_block = 1024; wg_per_cu = 1; sorted = true; }
+        EdgePlanRequest want_plan;
+        want_plan.n = n; want_plan.E = E; want_plan.s = s;
+        want_plan.pool_size = c->cfg.pool_size; want_plan.pool_block = c->cfg.pool_block; want_plan.pool_line = std::max(1, c->cfg.pool_line);
+        want_plan.pool_distinct = c->cfg.pool_mode != NOMAD_POOL_PICKS16;
+        want_plan.tune_edge_block = c->tune_edge_block; want_plan.tune_wg_per_cu = c->tune_wg_per_cu;
+        want_plan.tune_pool_kernel = c->tune_pool_kernel; want_plan.tune_record_sort = c->tune_record_sort;
+        want_plan.tune_flush_rounds = c->tune_flush_rounds;
+        const EdgePlan plan = plan_edge_pass(want_plan);   // tile size, kernel, launch shape (edge_plan.h)
+        const int tile_bits = plan.tile_bits, bin_block = plan.bin_block, wg_per_cu = plan.wg_per_cu, pool_rounds = plan.pool_rounds;
+        const uint32_t n_bins = plan.n_bins;
+        const bool sorted = plan.sorted, distinct = plan.distinct_kernel;
         std::string why;   // why the fallback path is in use, if it is
         if (c->tune_path == NOMAD_PATH_FIXED_ATOMICS) why = "the fixed-point atomics path was asked for (nomad_tune)";
         else if (s > 8) why = "more than 8 negatives per edge: the binned edge pass is built for s <= 8";
@@ -706,7 +681,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
             HTRY(hipGetDeviceProperties(&prop, c->cfg.device));
             c->bin_block = bin_block;
             c->sorted_records = sorted;
-            c->flush_rounds = (!sorted && bin_block == 1024) ? (c->tune_flush_rounds ? c->tune_flush_rounds : kDefaultFlushRounds) : 1;
+            c->flush_rounds = plan.flush_rounds;
             c->pool_rounds = pool_rounds;
             c->distinct_kernel = distinct;
             c->n_wg = std::max(1, prop.multiProcessorCount) * wg_per_cu;
@@ -723,20 +698,7 @@ int nomad_set_graph(nomad_ctx* c, const int32_t* row_ptr, const int32_t* col_idx
                     hipLaunchKernelGGL(k_wg_pools_pooled, dim3(1), dim3(64), 0, st, E, c->n_wg, (int64_t)c->cfg.pool_block,
                                        (uint32_t)c->cfg.pool_size, n_bins, c->wg_pool_begin, total_dev);
                 else {
-                    // Record phases: the edge pass of a step runs over `phases` ranges of positions, each followed by the
-                    // tile pass, so the pool holds the records of one range.  Default: as many (a power of two, at
-                    // most 64) as keep one range's records under 8 GB, and under 4 GB for a step with more than 32 GB
-                    // of records, where the pool would otherwise outweigh the graph (each further phase costs about
-                    // half a per cent of an epoch: the tile pass walks shorter chains and carries its sums through
-                    // memory).
-                    int phases = c->tune_phases;
-                    if (phases == 0) {
-                        const double step_bytes = (double)E * (s + 1) * 12.0;
-                        const double per_phase = step_bytes > 32e9 ? 4e9 : 8e9;
-                        phases = 1;
-                        while (phases < 64 && step_bytes / phases > per_phase) phases *= 2;
-                    }
-                    c->phases = (int)std::max<int64_t>(1, std::min<int64_t>(phases, (E + c->bin_block - 1) / c->bin_block));
+                    c->phases = plan_record_phases(E, s, c->bin_block, c->tune_phases);   // edge_plan.h
                     const int64_t per_phase = (E + c->phases - 1) / c->phases + c->bin_block;   // ranges are cut at multiples of the block
                     hipLaunchKernelGGL(k_wg_pools, dim3(1), dim3(64), 0, st, std::min<int64_t>(E, per_phase), c->n_wg, s + 1, c->bin_block, n_bins,
                                        c->wg_pool_begin, total_dev);

@@ -15,6 +15,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "edge_plan.h"
 #include "philox.h"
 
 namespace nomad {
@@ -782,12 +783,7 @@ __global__ void __launch_bounds__(kBlock) k_edges(const EdgeArgs P) {
 //                    adds the records into 2 x 64-bit fixed-point accumulators per point in LDS.
 //                    Integer addition is associative, so the result does not depend on the order
 //                    records were appended or read in.  It then adds the head sums and writes g.
-constexpr int kMaxTileBits = 13;        // 8192 points: 128 KB of accumulators
-constexpr int kMinTileBits = 8;
-constexpr int kChunk = 128;             // records per chunk (1.5 KB): every (workgroup, tile) chain ends in a partly filled
-                                        // chunk, so the pool carries workgroups x tiles x kChunk records of slack
-constexpr int kBinBlock = 1024;          // threads of the tile pass and of the large edge-pass workgroup
-constexpr int kMaxBinsPerThread = 8;    // tiles one thread owns in the per-round scan
+// (tile and chunk sizes and the LDS budgets: edge_plan.h)
 constexpr uint32_t kNoChunk = 0xFFFFFFFFu;
 
 struct BinArgs {
@@ -806,12 +802,6 @@ struct BinArgs {
     int* overflow;                // set if a workgroup's chunk range were ever exceeded (it cannot be)
 };
 
-// LDS of k_edges_binned: per tile (record count / first sorted slot, fill of the open chunk, open
-// chunk, first chunk allocated this round) and the round's records, sorted by tile.
-__host__ __device__ inline size_t binned_records_per_round(int s, int block) { return (size_t)block * (s + 1) + 2 * (block / 64); }
-__host__ __device__ inline size_t binned_lds_bytes(uint32_t n_bins, int s, int block, bool sorted = true) {
-    return ((size_t)4 * n_bins + 1 + (sorted ? 3 * binned_records_per_round(s, block) : 0)) * sizeof(uint32_t);
-}
 
 // Workgroup barrier that orders LDS accesses only.  The edge pass never reads back, inside the
 // kernel, anything it wrote to global memory, so its barriers need not wait for outstanding global
@@ -1204,11 +1194,6 @@ __global__ void __launch_bounds__(BS) k_edges_binned(const EdgeArgs P, const Bin
 // ranks, so their writes still coalesce; a pool entry's record is alone in its tile whichever way it is written.
 constexpr int kMaxPoolPerLane = 4;   // pool entries one lane fetches and hands on: pool_size <= 4 * workgroup size
 
-// partial head sums a block can produce: two per wavefront and round
-__host__ __device__ inline size_t pooled_side_records(int64_t block_edges) { return (size_t)(block_edges / 32); }
-__host__ __device__ inline size_t pooled_lds_bytes(uint32_t n_bins, int64_t block_edges, uint32_t pool_size) {
-    return (size_t)pool_size * 28 + ((size_t)4 * n_bins + 3 * pooled_side_records(block_edges)) * sizeof(uint32_t);
-}
 
 // What a lane of the pooled edge pass has in flight for its next edge (no groups there: one population, no mean field).
 struct PoolFetch {
@@ -1449,9 +1434,6 @@ __global__ void __launch_bounds__(BS) k_edges_pooled(const EdgeArgs P, const Bin
 // (word r & 3 of call number lane + 1024 (r >> 2)); a pool line is pool_line consecutive points, read by adjacent
 // lanes (one or two 128-byte lines per pool line instead of one per entry), and its entries' records leave as one
 // contiguous run; positions, indices and byte offsets are 32-bit (needs 8 n < 2^32, checked by the host).
-__host__ __device__ inline size_t distinct_lds_bytes(uint32_t n_bins, uint32_t pool_size, uint32_t lines, int rounds) {
-    return (size_t)pool_size * 28 + ((size_t)lines + (size_t)4 * n_bins + 3 * (size_t)(32 * rounds)) * sizeof(uint32_t);
-}
 
 struct DistinctFetch {   // what a lane has in flight for its edge of the next round
     bool has;
