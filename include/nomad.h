@@ -76,7 +76,7 @@ typedef struct {
                                /* them); 1: opt-in, see below                                            */
     int32_t pool_mode;         /* pooled sampler: NOMAD_POOL_PICKS16 (0), NOMAD_POOL_DISTINCT (1) or NOMAD_POOL_STRATIFIED (2), see below; */
                                /* 0 when pool_size is 0                                                  */
-    int32_t pool_line;         /* NOMAD_POOL_DISTINCT / _STRATIFIED: consecutive points per pool line, a power of two */
+    int32_t pool_line;         /* NOMAD_POOL_DISTINCT / _STRATIFIED: consecutive points per pool line, a power of two, at most n_points */
                                /* (1 = every pool entry drawn on its own); 0 is read as 1                 */
     int32_t pool_segment;      /* NOMAD_POOL_DISTINCT / _STRATIFIED: consecutive CSR positions dealt to a block together, a */
                                /* power of two >= 64 that divides pool_block; 0 is read as 64; not used by */
@@ -152,7 +152,7 @@ typedef struct {
  *   - picks: an edge takes one word W = word ((rank >> 10) & 3) of Philox(counter (beta, 0xFFFFFFFE, t,
  *     (rank & 1023) + 1024 (rank >> 12))); with lg = log2(pool_size): u_0 = the top lg bits of W, c = 2 (bits
  *     1..lg-1 of W) + 1, and slot k takes entry (u_0 + k c) mod pool_size.
- * pool_size is a power of two (2..NOMAD_MAX_POOL) and s <= L: the odd stride c then puts the s picks of an edge into s
+ * pool_size is a power of two (2..NOMAD_MAX_POOL), pool_line <= n and s <= L: the odd stride c then puts the s picks of an edge into s
  * different lines, whose starts are independent uniform draws, so the s negatives are independent and uniform over
  * the points.  Negatives of different edges of a block share lines and are dependent; spreading a block over the
  * edge list (small g) makes the edges that share a pool come from unrelated neighbourhoods.  The fast kernel

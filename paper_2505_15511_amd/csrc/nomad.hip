@@ -395,9 +395,10 @@ int nomad_create(const nomad_config* cfg, nomad_ctx** out) {
     if (cfg->pool_mode == NOMAD_POOL_PICKS16 && (cfg->pool_line > 1 || cfg->pool_line < 0 || cfg->pool_segment < 0)) return NOMAD_E_INVALID_ARG;
     if (cfg->pool_mode == NOMAD_POOL_DISTINCT || cfg->pool_mode == NOMAD_POOL_STRATIFIED) {
         const int line = cfg->pool_line ? cfg->pool_line : 1, seg = cfg->pool_segment ? cfg->pool_segment : 64;
+        // (a line is at most the whole point set: its points are start, start + 1, ... taken modulo n with one subtraction)
         if (cfg->pool_size < 2 || !is_power_of_two(cfg->pool_size) || !is_power_of_two(line) || line > cfg->pool_size ||
-            cfg->n_neg > cfg->pool_size / line || seg < 64 || !is_power_of_two(seg) || cfg->pool_block % seg != 0 ||
-            cfg->batches_per_epoch != 1)
+            line > cfg->n_points || cfg->n_neg > cfg->pool_size / line || seg < 64 || !is_power_of_two(seg) ||
+            cfg->pool_block % seg != 0 || cfg->batches_per_epoch != 1)
             return NOMAD_E_INVALID_ARG;
     }
     if (cfg->edge_weights != NOMAD_WEIGHTS_GIVEN && cfg->edge_weights != NOMAD_WEIGHTS_INVERSE_RANK) return NOMAD_E_INVALID_ARG;

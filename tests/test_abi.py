@@ -74,7 +74,8 @@ def test_argument_errors_before_any_device_work(lib):
     # the pooled sampler with distinct picks: power-of-two pool, s <= lines, whole segments, one step per epoch
     for size, block, line, seg, batches, ok in ((64, 1024, 4, 64, 1, True), (48, 1024, 1, 64, 1, False), (64, 1024, 32, 64, 1, False),
                                                 (64, 1024, 4, 96, 1, False), (64, 1000, 4, 64, 1, False), (64, 1024, 4, 2048, 1, False),
-                                                (64, 1024, 4, 64, 2, False), (64, 1024, 0, 0, 1, True), (1, 1024, 1, 64, 1, False)):
+                                                (64, 1024, 4, 64, 2, False), (64, 1024, 0, 0, 1, True), (1, 1024, 1, 64, 1, False),
+                                                (128, 1024, 8, 64, 1, True), (128, 1024, 16, 64, 1, False)):   # a line longer than the 10 points
         cfg.pool_size, cfg.pool_block, cfg.pool_mode, cfg.pool_line, cfg.pool_segment, cfg.batches_per_epoch = size, block, 1, line, seg, batches
         rc = lib.nomad_create(C.byref(cfg), C.byref(ctx))
         assert (rc == -1) == (not ok), (size, block, line, seg, batches, rc)      # accepted: 0, or -6 where no GPU is present

@@ -76,3 +76,68 @@ def test_random_case_against_the_oracle(seed, mode):
     tol = 2e-4 if (mode == SCATTER_ATOMIC and d.get("pool_size", 0) == 1) else GRAD_TOL
     assert np.abs(g - g_ref).max() <= tol * scale
     assert np.abs(th - th_ref).max() <= 1e-5 * max(1.0, np.abs(th_ref).max())
+
+
+def random_variant(seed):
+    """A random case with what the family above does not draw: the pooled samplers with distinct picks and with stratified
+    pools (any valid pool, line and segment), the library-computed inverse-rank weights, and the launch-shape knobs of the
+    deterministic edge pass (sorted or unsorted records, rounds per flush, record phases, 512-lane workgroups)."""
+    d = random_case(seed + 1000)
+    rng = np.random.default_rng(seed + 77_000)
+    d["batches_per_epoch"] = 1 if rng.random() < 0.7 else d["batches_per_epoch"]
+    s = d["n_neg"]
+    for k in ("pool_size", "pool_block", "sampled_far_field", "mean_gradient"):
+        d.pop(k, None)
+    if s > 0 and d["cluster_group"] is None and d["batches_per_epoch"] == 1 and rng.random() < 0.6:
+        line = int(rng.choice([v for v in (1, 2, 16, 64) if v <= d["n"]]))    # a line is at most the whole point set
+        lines = int(2 ** rng.integers(int(np.ceil(np.log2(max(s, 2)))), 8))          # at least s lines: picks in different lines
+        seg = int(rng.choice([64, 256, 1024]))
+        d["pool_mode"] = int(rng.choice([1, 2]))
+        d["pool_line"], d["pool_segment"] = line, seg
+        d["pool_size"] = line * lines
+        d["pool_block"] = seg * int(rng.choice([1, 2, 3, 8, 16]))
+        if d["pool_size"] > 4096:
+            d["pool_size"], d["pool_line"] = 4096, max(1, 4096 // lines)
+        assert d["pool_line"] <= d["n"] and s <= d["pool_size"] // d["pool_line"]
+    if d["weights"] is None and rng.random() < 0.3:
+        d["inverse_rank_weights"] = True
+    tune = {}
+    if rng.random() < 0.5:
+        tune["record_sort"] = int(rng.choice([1, 2]))
+    if rng.random() < 0.3:
+        tune["flush_rounds"] = int(rng.choice([1, 2]))
+    if rng.random() < 0.4:
+        tune["record_phases"] = int(rng.choice([2, 3, 7]))
+    if rng.random() < 0.2:
+        tune["edge_block"] = 512
+    if rng.random() < 0.2:
+        tune["pool_kernel"] = 0
+    return d, tune
+
+
+@pytest.mark.parametrize("mode", [pytest.param(SCATTER_DETERMINISTIC, id="det"), pytest.param(SCATTER_ATOMIC, id="atomic")])
+@pytest.mark.parametrize("seed", range(int(os.environ.get("NOMAD_RANDOM_VARIANTS_FROM", 0)), int(os.environ.get("NOMAD_RANDOM_VARIANTS_TO", 80))))
+def test_random_variant_against_the_oracle(seed, mode):
+    d, tune = random_variant(seed)
+    O = c_oracle.COracle(**d)
+    th_ref, g_ref, _ = O.epoch(d["theta0"], 1)
+    with Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
+               pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0), batches_per_epoch=d["batches_per_epoch"],
+               pool_mode=d.get("pool_mode", 0), pool_line=d.get("pool_line", 0), pool_segment=d.get("pool_segment", 0),
+               inverse_rank_weights=d.get("inverse_rank_weights", False), tune=tune if mode == SCATTER_DETERMINISTIC else None) as nm:
+        nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
+        nm.set_embedding(d["theta0"])
+        if d["n_neg"] and len(d["col_idx"]):
+            assert np.array_equal(nm.get_negatives(1), O.negatives(1))
+        nm.epoch(1)
+        g, th = nm.get_gradient(), nm.get_embedding()
+    _, g_full = c_oracle.COracle(**{**d, "batches_per_epoch": 1}).loss_and_grad(d["theta0"], 1)
+    # As above, with the floor at 3e-2: where a gradient vanishes by exact cancellation (two points, the negative is the
+    # tail) what is left is the float32 rounding of forces as large as p(j|i) = 1, up to two units in the last place of 1
+    # (2.4e-7), which the bar of 1e-5 admits against a scale of 3e-2.
+    scale = max(np.abs(g_full).max(), np.abs(g_ref).max(), 3e-2)
+    print(f"  seed {seed}: n={d['n']} E={len(d['col_idx'])} s={d['n_neg']} B={d['batches_per_epoch']} pool={d.get('pool_size', 0)}/"
+          f"{d.get('pool_block', 0)} mode={d.get('pool_mode', 0)} line={d.get('pool_line', 0)} seg={d.get('pool_segment', 0)} "
+          f"rank-weights={d.get('inverse_rank_weights', False)} tune={tune} grad err {np.abs(g - g_ref).max() / scale:.2e}", flush=True)
+    assert np.abs(g - g_ref).max() <= GRAD_TOL * scale
+    assert np.abs(th - th_ref).max() <= 1e-5 * max(1.0, np.abs(th_ref).max())
