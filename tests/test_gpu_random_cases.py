@@ -141,3 +141,69 @@ def test_random_variant_against_the_oracle(seed, mode):
           f"rank-weights={d.get('inverse_rank_weights', False)} tune={tune} grad err {np.abs(g - g_ref).max() / scale:.2e}", flush=True)
     assert np.abs(g - g_ref).max() <= GRAD_TOL * scale
     assert np.abs(th - th_ref).max() <= 1e-5 * max(1.0, np.abs(th_ref).max())
+
+
+def random_large_case(seed):
+    """Graphs that span many tiles and every workgroup of the edge pass: planted clusters of 20,000 to 300,000 points, any
+    s up to 8, optional groups (exact or sampled far field), optional pooled sampler of any mode with blocks the fast kernels
+    take, and the launch-shape knobs."""
+    from paper_2505_15511_amd import workloads
+    rng = np.random.default_rng(seed + 500_000)
+    n = int(rng.choice([20_000, 70_000, 150_000, 300_000]))
+    R = int(rng.choice([3, 40, 300]))
+    k = int(rng.choice([3, 8, 15]))
+    g = workloads.planted_knn_graph(n, R, k, float(rng.choice([0.0, 0.02, 0.3])), seed + 9)
+    s = int(rng.choice([0, 1, 2, 5, 8]))
+    d = dict(n=n, row_ptr=g["row_ptr"].numpy(), col_idx=g["col_idx"].numpy(), weights=None, cluster_of=g["cluster_of"].numpy(),
+             n_clusters=R, cluster_group=None, theta0=(rng.normal(size=(n, 2)) * rng.choice([0.01, 1.0, 10.0])).astype(np.float32),
+             n_neg=s, noise_count=float(rng.choice([2.5, 5.0])), n_epochs=5, lr0=0.3, seed=int(seed) * 104_729 + 3, batches_per_epoch=1)
+    kind = rng.choice(["plain", "grouped", "pooled"]) if s > 0 else "plain"
+    if kind == "grouped":
+        d["cluster_group"] = workloads.balanced_groups(g["sizes"], int(rng.choice([2, 3, min(R, 8)]))).astype(np.int32)
+        if rng.random() < 0.5:
+            d["sampled_far_field"] = True
+    if kind == "pooled":
+        d["pool_mode"] = int(rng.choice([0, 1, 2]))
+        d["pool_block"] = int(rng.choice([1024, 2048, 4096, 8192]))
+        if d["pool_mode"] == 0:
+            d["pool_size"] = int(rng.choice([64, 1000, 2048, 4096]))
+        else:
+            d["pool_line"] = int(rng.choice([1, 4, 16, 64]))
+            d["pool_size"] = int(rng.choice([v for v in (512, 2048, 4096) if v // d["pool_line"] >= s]))
+            d["pool_segment"] = int(rng.choice([v for v in (64, 256, 1024) if d["pool_block"] % v == 0]))
+    if kind == "plain" and rng.random() < 0.3:
+        d["batches_per_epoch"] = 3
+    tune = {}
+    if rng.random() < 0.5:
+        tune["record_sort"] = int(rng.choice([1, 2]))
+    if rng.random() < 0.4:
+        tune["record_phases"] = int(rng.choice([2, 5]))
+    if rng.random() < 0.2:
+        tune["flush_rounds"] = 1
+    return d, tune
+
+
+@pytest.mark.parametrize("mode", [pytest.param(SCATTER_DETERMINISTIC, id="det"), pytest.param(SCATTER_ATOMIC, id="atomic")])
+@pytest.mark.parametrize("seed", range(int(os.environ.get("NOMAD_RANDOM_LARGE_FROM", 0)), int(os.environ.get("NOMAD_RANDOM_LARGE_TO", 16))))
+def test_random_large_case_against_the_oracle(seed, mode):
+    d, tune = random_large_case(seed)
+    O = c_oracle.COracle(**d)
+    th_ref, g_ref, _ = O.epoch(d["theta0"], 2)
+    with Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
+               pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0), batches_per_epoch=d["batches_per_epoch"],
+               pool_mode=d.get("pool_mode", 0), pool_line=d.get("pool_line", 0), pool_segment=d.get("pool_segment", 0),
+               sampled_far_field=d.get("sampled_far_field", False), tune=tune if mode == SCATTER_DETERMINISTIC else None) as nm:
+        nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
+        nm.set_embedding(d["theta0"])
+        if d["n_neg"]:
+            e0 = int(np.random.default_rng(seed).integers(0, max(1, len(d["col_idx"]) - 20_000)))
+            assert np.array_equal(nm.get_negatives(2, e0, e0 + 20_000), O.negatives(2, e0, e0 + 20_000))
+        nm.epoch(2)
+        g, th = nm.get_gradient(), nm.get_embedding()
+        path = nm.scatter_path()
+    scale = max(np.abs(g_ref).max(), 3e-2)
+    print(f"  seed {seed}: n={d['n']} E={len(d['col_idx'])} s={d['n_neg']} B={d['batches_per_epoch']} groups={d['cluster_group'] is not None} "
+          f"far={d.get('sampled_far_field', False)} pool={d.get('pool_size', 0)}/{d.get('pool_block', 0)} mode={d.get('pool_mode', 0)} "
+          f"line={d.get('pool_line', 0)} seg={d.get('pool_segment', 0)} tune={tune} path={path} grad err {np.abs(g - g_ref).max() / scale:.2e}", flush=True)
+    assert np.abs(g - g_ref).max() <= GRAD_TOL * scale
+    assert np.abs(th - th_ref).max() <= 1e-5 * max(1.0, np.abs(th_ref).max())
