@@ -180,6 +180,11 @@ def random_large_case(seed):
         tune["record_phases"] = int(rng.choice([2, 5]))
     if rng.random() < 0.2:
         tune["flush_rounds"] = 1
+    extra = np.random.default_rng(seed + 900_000)      # drawn apart, so that the cases above stay what they were
+    if extra.random() < 0.3:
+        d["weights"] = extra.uniform(0.1, 3.0, len(d["col_idx"])).astype(np.float32)
+    if kind == "grouped" and not d.get("sampled_far_field") and extra.random() < 0.4:
+        d["mean_gradient"] = True
     return d, tune
 
 
@@ -192,7 +197,8 @@ def test_random_large_case_against_the_oracle(seed, mode):
     with Nomad(d["n"], d["n_clusters"], d["n_neg"], d["noise_count"], d["n_epochs"], d["lr0"], d["seed"], mode,
                pool_size=d.get("pool_size", 0), pool_block=d.get("pool_block", 0), batches_per_epoch=d["batches_per_epoch"],
                pool_mode=d.get("pool_mode", 0), pool_line=d.get("pool_line", 0), pool_segment=d.get("pool_segment", 0),
-               sampled_far_field=d.get("sampled_far_field", False), tune=tune if mode == SCATTER_DETERMINISTIC else None) as nm:
+               sampled_far_field=d.get("sampled_far_field", False), mean_gradient=d.get("mean_gradient", False),
+               tune=tune if mode == SCATTER_DETERMINISTIC else None) as nm:
         nm.set_graph(d["row_ptr"], d["col_idx"], d["weights"], d["cluster_of"], d["cluster_group"])
         nm.set_embedding(d["theta0"])
         if d["n_neg"]:
@@ -203,7 +209,8 @@ def test_random_large_case_against_the_oracle(seed, mode):
         path = nm.scatter_path()
     scale = max(np.abs(g_ref).max(), 3e-2)
     print(f"  seed {seed}: n={d['n']} E={len(d['col_idx'])} s={d['n_neg']} B={d['batches_per_epoch']} groups={d['cluster_group'] is not None} "
-          f"far={d.get('sampled_far_field', False)} pool={d.get('pool_size', 0)}/{d.get('pool_block', 0)} mode={d.get('pool_mode', 0)} "
+          f"far={d.get('sampled_far_field', False)} mean-gradient={d.get('mean_gradient', False)} weights={d['weights'] is not None} "
+          f"pool={d.get('pool_size', 0)}/{d.get('pool_block', 0)} mode={d.get('pool_mode', 0)} "
           f"line={d.get('pool_line', 0)} seg={d.get('pool_segment', 0)} tune={tune} path={path} grad err {np.abs(g - g_ref).max() / scale:.2e}", flush=True)
     assert np.abs(g - g_ref).max() <= GRAD_TOL * scale
     assert np.abs(th - th_ref).max() <= 1e-5 * max(1.0, np.abs(th_ref).max())
