@@ -75,7 +75,7 @@ def test_random_case_against_the_oracle(seed, mode):
     # ordinary in-degrees; the fixed-point deterministic mode keeps the bar there as well.
     tol = 2e-4 if (mode == SCATTER_ATOMIC and d.get("pool_size", 0) == 1) else GRAD_TOL
     assert np.abs(g - g_ref).max() <= tol * scale
-    assert np.abs(th - th_ref).max() <= 1e-5 * max(1.0, np.abs(th_ref).max())
+    assert np.abs(th - th_ref).max() <= tol * max(1.0, np.abs(th_ref).max())      # the step carries the gradient's error
 
 
 def random_variant(seed):
